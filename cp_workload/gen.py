@@ -1,0 +1,420 @@
+"""Seeded synthetic workloads: token ids, sensitivity masks, request offsets,
+donor prompts for pool prefill, free lists and table sizes.
+
+This module only *draws inputs*.  It holds none of the method's arithmetic (no
+hashing, no table, no span logic, no rotation) and serves the CPU oracle and
+the GPU library alike.  Everything is host-side numpy; KV values come from
+``cp_workload.kvgen``.
+
+The five named workloads follow the five benchmark configurations (tiny,
+Llama-3-8B shape, fragmentation stress, RoPE-shift reuse, Llama-3-70B shape).
+They stand in for the paper's RAG-style prompts (Sec. 3.2: a long shared
+system/template part, retrieved passages reused across requests, a short
+unique user part, sensitive tokens a small fraction arranged in short runs);
+no dataset item is reproduced.  ``scale`` shrinks a workload for tests while
+keeping its structure.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+VOCAB = 32000
+
+
+@dataclass(frozen=True)
+class KVShape:
+    n_layers: int
+    n_kv_heads: int
+    head_dim: int
+
+    @property
+    def row_bytes(self) -> int:  # one (token, layer, K|V) row, bf16
+        return self.n_kv_heads * self.head_dim * 2
+
+    @property
+    def tok_bytes(self) -> int:  # all rows of one token
+        return self.n_layers * 2 * self.row_bytes
+
+
+@dataclass
+class Workload:
+    name: str
+    seed: int
+    shape: KVShape
+    # request batch (the lookup side), R requests packed back to back
+    tok: np.ndarray  # uint32[N]
+    mask: np.ndarray  # uint8[N], 1 = sensitive
+    off: np.ndarray  # uint32[R+1]
+    # donor prompts (pool prefill), inserted in order, possibly in several batches
+    donor_tok: np.ndarray
+    donor_mask: np.ndarray
+    donor_off: np.ndarray
+    donor_batches: list  # list of (first_donor, last_donor_exclusive)
+    pool_slots: int
+    free_slots: np.ndarray  # uint32 permutation of the pool's slots: hand-out order
+    table_capacity: int
+    rope_theta: float | None = None  # None: no key re-rotation in this workload
+    rope_style: int = 0
+    notes: dict = field(default_factory=dict)
+
+    @property
+    def n_tokens(self) -> int:
+        return int(self.off[-1])
+
+    @property
+    def n_requests(self) -> int:
+        return len(self.off) - 1
+
+
+# --------------------------------------------------------------------------
+# small helpers
+
+
+def _tokens(rng, n):
+    return rng.integers(0, VOCAB, size=int(n), dtype=np.uint32)
+
+
+def _geom(rng, mean):
+    """Geometric length >= 1 with the given mean."""
+    if mean <= 1.0:
+        return 1
+    return int(rng.geometric(1.0 / mean))
+
+
+def _mask_process(rng, n, run_mean, cover, start_sensitive=False):
+    """Alternating non-sensitive gaps / sensitive runs, both geometric, so that a
+    fraction ``cover`` of the tokens is sensitive in expectation."""
+    m = np.zeros(int(n), np.uint8)
+    if cover <= 0.0 or n == 0:
+        return m
+    gap_mean = run_mean * (1.0 - cover) / cover
+    i = 0
+    sens = start_sensitive
+    while i < n:
+        ln = _geom(rng, run_mean if sens else gap_mean)
+        if sens:
+            m[i : i + ln] = 1
+        i += ln
+        sens = not sens
+    return m
+
+
+def _pack(parts_tok, parts_mask):
+    off = np.zeros(len(parts_tok) + 1, np.uint32)
+    off[1:] = np.cumsum([len(p) for p in parts_tok])
+    if len(parts_tok) == 0:
+        return np.zeros(0, np.uint32), np.zeros(0, np.uint8), off
+    return (
+        np.concatenate(parts_tok).astype(np.uint32),
+        np.concatenate(parts_mask).astype(np.uint8),
+        off,
+    )
+
+
+def _batches(donor_off, max_tokens):
+    """Split donors into consecutive batches of at most ``max_tokens`` tokens."""
+    out, first, n = [], 0, len(donor_off) - 1
+    for d in range(n):
+        if d > first and int(donor_off[d + 1]) - int(donor_off[first]) > max_tokens:
+            out.append((first, d))
+            first = d
+    if n > first:
+        out.append((first, n))
+    return out
+
+
+# --------------------------------------------------------------------------
+# workload 1: tiny
+
+
+def make_tiny(seed=0xC0FFEE01, T=512, n_donors=8, pool_slots=4096, shape=KVShape(2, 2, 64)):
+    rng = np.random.default_rng(seed)
+    tok = _tokens(rng, T)
+    mask = _mask_process(rng, T, run_mean=6.0, cover=0.20)
+    # the request's non-sensitive segments
+    segs, i = [], 0
+    while i < T:
+        if mask[i]:
+            i += 1
+            continue
+        j = i
+        while j < T and not mask[j]:
+            j += 1
+        segs.append(tok[i:j].copy())
+        i = j
+    d_tok, d_mask = [], []
+    for d in range(n_donors):
+        pt, pm = [], []
+        n = 0
+        order = rng.permutation(len(segs))
+        for si in order:
+            seg = segs[si]
+            sep = _geom(rng, 6.0)
+            pt.append(_tokens(rng, sep))
+            pm.append(np.ones(sep, np.uint8))
+            if rng.random() < 0.5:
+                u = rng.random()
+                if u < 0.25 and len(seg) > 1:  # a proper prefix, then different text
+                    k = int(rng.integers(1, len(seg)))
+                    piece = np.concatenate([seg[:k], _tokens(rng, len(seg) - k)])
+                elif u < 0.5:  # the whole segment and more
+                    piece = np.concatenate([seg, _tokens(rng, _geom(rng, 8.0))])
+                else:
+                    piece = seg.copy()
+            else:
+                piece = _tokens(rng, len(seg))
+            if d == 0 and si == order[0]:
+                # negative case: the segment preceded by one extra non-sensitive token
+                piece = np.concatenate([_tokens(rng, 1), seg])
+            pt.append(piece)
+            pm.append(np.zeros(len(piece), np.uint8))
+            n += sep + len(piece)
+            if n >= T:
+                break
+        t = np.concatenate(pt)[:T]
+        m = np.concatenate(pm)[:T]
+        if len(t) < T:
+            pad = T - len(t)
+            t = np.concatenate([t, _tokens(rng, pad)])
+            m = np.concatenate([m, np.ones(pad, np.uint8)])
+        d_tok.append(t)
+        d_mask.append(m)
+    dt, dm, doff = _pack(d_tok, d_mask)
+    return Workload(
+        name="tiny", seed=seed, shape=shape,
+        tok=tok, mask=mask, off=np.array([0, T], np.uint32),
+        donor_tok=dt, donor_mask=dm, donor_off=doff, donor_batches=[(0, n_donors)],
+        pool_slots=pool_slots, free_slots=rng.permutation(pool_slots).astype(np.uint32),
+        table_capacity=2 * pool_slots,
+    )
+
+
+# --------------------------------------------------------------------------
+# workloads 2 and 5: shared system prefix + documents from a corpus + user text
+
+
+def make_docs(name, seed, shape, R, T, prefix_len, n_docs, doc_len, docs_per_request, run_mean, cover,
+              pool_slots, table_capacity=None, donor_batch_tokens=1 << 17):
+    rng = np.random.default_rng(seed)
+    prefix = _tokens(rng, prefix_len)
+    docs, dmasks = [], []
+    for _ in range(n_docs):
+        ln = int(rng.integers(doc_len[0], doc_len[1] + 1))
+        docs.append(_tokens(rng, ln))
+        dmasks.append(_mask_process(rng, ln, run_mean, cover))  # the mask travels with the document
+    r_tok, r_mask, picks = [], [], []
+    for _ in range(R):
+        chosen = rng.choice(n_docs, size=min(docs_per_request, n_docs), replace=False)
+        pt, pm, n = [prefix], [np.zeros(prefix_len, np.uint8)], prefix_len
+        used = []
+        for d in chosen:
+            room = T - n
+            if room <= 0:
+                break
+            ln = min(len(docs[d]), room)
+            pt.append(docs[d][:ln])
+            pm.append(dmasks[d][:ln])
+            n += ln
+            used.append(int(d))
+        if n < T:  # the user's own text: never in the pool
+            pt.append(_tokens(rng, T - n))
+            pm.append(_mask_process(rng, T - n, run_mean, cover))
+        r_tok.append(np.concatenate(pt)[:T])
+        r_mask.append(np.concatenate(pm)[:T])
+        picks.append(used)
+    tok, mask, off = _pack(r_tok, r_mask)
+    d_tok = [np.concatenate([prefix, docs[d]]) for d in range(n_docs)]
+    d_mask = [np.concatenate([np.zeros(prefix_len, np.uint8), dmasks[d]]) for d in range(n_docs)]
+    dt, dm, doff = _pack(d_tok, d_mask)
+    if table_capacity is None:
+        table_capacity = 2 * pool_slots
+    return Workload(
+        name=name, seed=seed, shape=shape, tok=tok, mask=mask, off=off,
+        donor_tok=dt, donor_mask=dm, donor_off=doff, donor_batches=_batches(doff, donor_batch_tokens),
+        pool_slots=pool_slots, free_slots=rng.permutation(pool_slots).astype(np.uint32),
+        table_capacity=table_capacity, notes={"picks": picks},
+    )
+
+
+def make_llama8b(seed=0xC0FFEE02, scale=1.0, shape=KVShape(32, 8, 128)):
+    s = scale
+    return make_docs("llama3-8b", seed, shape, R=max(2, round(16 * s)), T=max(64, round(4096 * s)),
+                     prefix_len=max(8, round(1024 * s)), n_docs=max(4, round(64 * s)),
+                     doc_len=(max(4, round(512 * s)), max(8, round(1024 * s))), docs_per_request=3,
+                     run_mean=8.0, cover=0.15, pool_slots=max(256, round(262144 * s)))
+
+
+def make_llama70b(seed=0xC0FFEE05, scale=1.0, shape=KVShape(80, 8, 128)):
+    s = scale
+    return make_docs("llama3-70b", seed, shape, R=max(2, round(4 * min(1.0, s * 4))), T=max(64, round(32768 * s)),
+                     prefix_len=max(8, round(4096 * s)), n_docs=max(4, round(256 * s)),
+                     doc_len=(max(4, round(1024 * s)), max(8, round(2048 * s))), docs_per_request=16,
+                     run_mean=12.0, cover=0.10, pool_slots=max(256, round(393216 * s)),
+                     donor_batch_tokens=max(1024, round(65536 * min(1.0, s * 4))))
+
+
+# --------------------------------------------------------------------------
+# workload 3: fragmentation stress
+
+
+def make_frag(seed=0xC0FFEE03, scale=1.0, shape=KVShape(32, 8, 128), load=0.85, miss_frac=0.05):
+    rng = np.random.default_rng(seed)
+    R, T = max(2, round(64 * scale)), max(64, round(2048 * scale))
+    pool_slots = max(256, round(131072 * scale))
+    # Span corpus: runs of 1..16 tokens, each stored as a whole run (a sensitive
+    # token before it).  Two runs that begin with the same tokens share keys, so
+    # count distinct run prefixes (token tuples, no hashing) until the pool is
+    # exactly full.
+    seen = set()
+    spans = []
+    while len(seen) < pool_slots:
+        ln = int(rng.integers(1, 17))
+        sp = _tokens(rng, ln)
+        t = tuple(int(x) for x in sp)
+        new = [t[: k + 1] for k in range(ln) if t[: k + 1] not in seen]
+        if len(seen) + len(new) > pool_slots:  # cut the last run so the count lands exactly
+            keep = pool_slots - len(seen)
+            # prefixes are added shortest first, so keeping the first `keep` new ones keeps a prefix
+            new = new[:keep]
+            sp = sp[: len(new[-1])]
+        seen.update(new)
+        spans.append(sp)
+    # donors: [sensitive separator][span][sensitive separator][span]..., ~T tokens each
+    d_tok, d_mask, cur_t, cur_m, n = [], [], [], [], 0
+    for sp in spans:
+        sep = int(rng.integers(1, 9))
+        cur_t += [_tokens(rng, sep), sp]
+        cur_m += [np.ones(sep, np.uint8), np.zeros(len(sp), np.uint8)]
+        n += sep + len(sp)
+        if n >= T:
+            d_tok.append(np.concatenate(cur_t))
+            d_mask.append(np.concatenate(cur_m))
+            cur_t, cur_m, n = [], [], 0
+    if cur_t:
+        d_tok.append(np.concatenate(cur_t))
+        d_mask.append(np.concatenate(cur_m))
+    dt, dm, doff = _pack(d_tok, d_mask)
+    # requests: reusable spans (uniform 1..16) between sensitive runs (uniform 1..8).
+    # With those lengths alone 4.5/13 = 34.6 % of the tokens would be sensitive; a
+    # fraction q of the reusable spans is turned sensitive as well so that the
+    # coverage is 40 % while reusable spans keep their length distribution.
+    q = (0.40 * 13.0 - 4.5) / 8.5
+    r_tok, r_mask = [], []
+    for _ in range(R):
+        pt, pm, n = [], [], 0
+        while n < T:
+            sep = int(rng.integers(1, 9))
+            pt.append(_tokens(rng, sep))
+            pm.append(np.ones(sep, np.uint8))
+            if rng.random() < miss_frac:
+                sp = _tokens(rng, int(rng.integers(1, 17)))
+            else:
+                sp = spans[int(rng.integers(0, len(spans)))]
+            pt.append(sp)
+            pm.append(np.full(len(sp), 1 if rng.random() < q else 0, np.uint8))
+            n += sep + len(sp)
+        r_tok.append(np.concatenate(pt)[:T])
+        r_mask.append(np.concatenate(pm)[:T])
+    tok, mask, off = _pack(r_tok, r_mask)
+    capacity = int(np.ceil(pool_slots / load))
+    return Workload(
+        name="frag", seed=seed, shape=shape, tok=tok, mask=mask, off=off,
+        donor_tok=dt, donor_mask=dm, donor_off=doff, donor_batches=_batches(doff, 1 << 16),
+        pool_slots=pool_slots, free_slots=rng.permutation(pool_slots).astype(np.uint32),
+        table_capacity=capacity, notes={"n_spans_corpus": len(spans)},
+    )
+
+
+# --------------------------------------------------------------------------
+# workload 4: reuse at shifted positions (key re-rotation)
+
+
+def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=500000.0, max_shift=512):
+    """Every reusable piece (system prefix, documents) sits in the donors at a
+    nominal position and in each request at that position plus a shift drawn
+    uniformly from [-max_shift, max_shift].  Fillers between pieces are the
+    user's own text and end in a sensitive token, so each piece starts a run in
+    donor and request alike."""
+    rng = np.random.default_rng(seed)
+    s = scale
+    ms = max(2, round(max_shift * s))
+    prefix_len = max(8, round(1024 * s))
+    doc_len = (max(4, round(512 * s)), max(8, round(1024 * s)))
+    n_docs, k_docs = max(6, round(64 * s)), 3
+    pool_slots = max(256, round(262144 * s))
+    run_mean, cover = 8.0, 0.25
+    spacing = doc_len[1] + 2 * ms
+    nominal = [ms] + [2 * ms + prefix_len + ms + k * spacing for k in range(k_docs)]  # piece 0 = the prefix
+    # 8 * 512 + 1024 + 3 * 1024 = 8192 at full scale
+    R, T = max(2, round(16 * s)), max(round(8192 * s), nominal[-1] + ms + doc_len[1])
+    prefix = _tokens(rng, prefix_len)
+    docs, dmasks, group = [], [], []
+    for d in range(n_docs):
+        ln = int(rng.integers(doc_len[0], doc_len[1] + 1))
+        docs.append(_tokens(rng, ln))
+        dmasks.append(_mask_process(rng, ln, run_mean, cover))
+        group.append(d % k_docs)  # a document is always used in the same place of the prompt
+
+    def filler(n, strict):
+        """n tokens of private text ending in a sensitive token (n may be 0).  ``strict``: all of it is
+        sensitive (the donors' own user text is never shared, Sec. 4.3.3 policy 3)."""
+        if n == 0:
+            return np.zeros(0, np.uint32), np.zeros(0, np.uint8)
+        m = np.ones(n, np.uint8) if strict else _mask_process(rng, n, run_mean, cover)
+        m[-1] = 1
+        return _tokens(rng, n), m
+
+    def compose(pieces, starts, total):
+        pt, pm, cur = [], [], 0
+        for (t, m), st in zip(pieces, starts):
+            assert st >= cur, "pieces overlap"
+            ft, fm = filler(st - cur, strict=total is None)
+            pt += [ft, t]
+            pm += [fm, m]
+            cur = st + len(t)
+        if total is not None and cur < total:
+            ft, fm = filler(total - cur, strict=False)
+            pt.append(ft)
+            pm.append(fm)
+        return np.concatenate(pt), np.concatenate(pm)
+
+    zeros = np.zeros(prefix_len, np.uint8)
+    d_tok, d_mask = [], []
+    for d in range(n_docs):  # donor d: prefix and document d at their nominal places
+        t, m = compose([(prefix, zeros), (docs[d], dmasks[d])], [nominal[0], nominal[1 + group[d]]], None)
+        d_tok.append(t)
+        d_mask.append(m)
+    r_tok, r_mask, shifts = [], [], []
+    by_group = [[d for d in range(n_docs) if group[d] == g] for g in range(k_docs)]
+    for _ in range(R):
+        sh = rng.integers(-ms, ms + 1, size=1 + k_docs)
+        chosen = [int(rng.choice(by_group[g])) for g in range(k_docs)]
+        pieces = [(prefix, zeros)] + [(docs[d], dmasks[d]) for d in chosen]
+        starts = [nominal[k] + int(sh[k]) for k in range(1 + k_docs)]
+        t, m = compose(pieces, starts, T)
+        r_tok.append(t[:T])
+        r_mask.append(m[:T])
+        shifts.append([int(x) for x in sh])
+    tok, mask, off = _pack(r_tok, r_mask)
+    dt, dm, doff = _pack(d_tok, d_mask)
+    return Workload(
+        name="rope", seed=seed, shape=shape, tok=tok, mask=mask, off=off,
+        donor_tok=dt, donor_mask=dm, donor_off=doff, donor_batches=_batches(doff, 1 << 17),
+        pool_slots=pool_slots, free_slots=rng.permutation(pool_slots).astype(np.uint32),
+        table_capacity=2 * pool_slots, rope_theta=theta, rope_style=0, notes={"shifts": shifts, "max_shift": ms},
+    )
+
+
+WORKLOADS = {
+    "tiny": lambda scale=1.0, **kw: make_tiny(**kw),
+    "llama3-8b": make_llama8b,
+    "frag": make_frag,
+    "rope": make_rope,
+    "llama3-70b": make_llama70b,
+}
+
+
+def make(name, **kw) -> Workload:
+    return WORKLOADS[name](**kw)

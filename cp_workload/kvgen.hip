@@ -1,0 +1,108 @@
+// Device side of the synthetic KV value generator: fill and verify kernels.
+//
+// Input generation and test tooling only.  The definition of a value is stated
+// in kvgen.py; this file repeats it for the GPU so that tens of GiB of pool and
+// request buffers can be filled and checked in place.  None of the method's
+// arithmetic is here and the GPU library does not include this file.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr uint64_t kC1 = 0x9E3779B97F4A7C15ull;
+constexpr uint64_t kC2 = 0xD1B54A32D192ED03ull;
+constexpr uint64_t kM = 0xD6E8FEB86659FD93ull;
+constexpr uint64_t kUidNone = 0xFFFFFFFFFFFFFFFFull;
+constexpr uint32_t kPoison16 = 0xC0DEu;
+constexpr uint32_t kScaleBits = 0x3BDDB47Bu;  // float nearest to 1 / 147.8
+
+struct GenLayout {
+  uint32_t n_layers, row_elems;
+  uint64_t tok_stride, layer_stride, kv_stride;
+};
+
+__device__ __forceinline__ uint32_t elem_bits(uint32_t w) {
+  int s = (int)((w & 0xFF) + ((w >> 8) & 0xFF) + ((w >> 16) & 0xFF) + (w >> 24));
+  float x = (float)(s - 510) * __uint_as_float(kScaleBits);
+  uint32_t u = __float_as_uint(x);
+  u = u + 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// Two bf16 values (elements 2*pair and 2*pair+1) packed low/high in 32 bits.
+__device__ __forceinline__ uint32_t pair_bits(uint64_t seed, uint64_t row_id, uint32_t pair) {
+  uint64_t z = seed + row_id * kC1 + (uint64_t)pair * kC2;
+  z ^= z >> 32;
+  z *= kM;
+  z ^= z >> 32;
+  z *= kM;
+  z ^= z >> 32;
+  return elem_bits((uint32_t)z) | (elem_bits((uint32_t)(z >> 32)) << 16);
+}
+
+// One block per row, rows taken grid-stride.  Thread handles pairs tid, tid+B, ..
+__global__ void fill_kernel(uint8_t *base, GenLayout lay, const uint64_t *uid, uint64_t uid_base,
+                            uint32_t n_tok, uint64_t seed) {
+  const uint64_t n_rows = (uint64_t)n_tok * lay.n_layers * 2;
+  const uint32_t n_pairs = lay.row_elems / 2;
+  for (uint64_t r = blockIdx.x; r < n_rows; r += gridDim.x) {
+    uint32_t kv = (uint32_t)(r & 1);
+    uint64_t tl = r >> 1;
+    uint32_t l = (uint32_t)(tl % lay.n_layers);
+    uint32_t t = (uint32_t)(tl / lay.n_layers);
+    uint64_t u = uid ? uid[t] : uid_base + t;
+    uint32_t *row = (uint32_t *)(base + t * lay.tok_stride + l * lay.layer_stride + kv * lay.kv_stride);
+    uint64_t row_id = (u * lay.n_layers + l) * 2 + kv;
+    for (uint32_t p = threadIdx.x; p < n_pairs; p += blockDim.x)
+      row[p] = (u == kUidNone) ? (kPoison16 | (kPoison16 << 16)) : pair_bits(seed, row_id, p);
+  }
+}
+
+__global__ void verify_kernel(const uint8_t *base, GenLayout lay, const uint64_t *uid,
+                              const uint8_t *skip_k, uint32_t n_tok, uint64_t seed,
+                              unsigned long long *n_bad) {
+  const uint64_t n_rows = (uint64_t)n_tok * lay.n_layers * 2;
+  const uint32_t n_pairs = lay.row_elems / 2;
+  uint32_t bad = 0;
+  for (uint64_t r = blockIdx.x; r < n_rows; r += gridDim.x) {
+    uint32_t kv = (uint32_t)(r & 1);
+    uint64_t tl = r >> 1;
+    uint32_t l = (uint32_t)(tl % lay.n_layers);
+    uint32_t t = (uint32_t)(tl / lay.n_layers);
+    if (kv == 0 && skip_k && skip_k[t]) continue;
+    uint64_t u = uid[t];
+    const uint32_t *row =
+        (const uint32_t *)(base + t * lay.tok_stride + l * lay.layer_stride + kv * lay.kv_stride);
+    uint64_t row_id = (u * lay.n_layers + l) * 2 + kv;
+    for (uint32_t p = threadIdx.x; p < n_pairs; p += blockDim.x) {
+      uint32_t want = (u == kUidNone) ? (kPoison16 | (kPoison16 << 16)) : pair_bits(seed, row_id, p);
+      uint32_t got = row[p];
+      bad += ((got & 0xFFFFu) != (want & 0xFFFFu)) + ((got >> 16) != (want >> 16));
+    }
+  }
+  if (bad) atomicAdd(n_bad, (unsigned long long)bad);
+}
+
+uint32_t grid_for(uint64_t n_rows) {
+  uint64_t g = n_rows < 65536 ? n_rows : 65536;
+  return (uint32_t)(g ? g : 1);
+}
+
+}  // namespace
+
+extern "C" int kvgen_fill(hipStream_t stream, void *base, GenLayout lay, const uint64_t *uid,
+                          uint64_t uid_base, uint32_t n_tok, uint64_t seed) {
+  if (n_tok == 0) return 0;
+  uint64_t n_rows = (uint64_t)n_tok * lay.n_layers * 2;
+  fill_kernel<<<grid_for(n_rows), 256, 0, stream>>>((uint8_t *)base, lay, uid, uid_base, n_tok, seed);
+  return (int)hipGetLastError();
+}
+
+extern "C" int kvgen_verify(hipStream_t stream, const void *base, GenLayout lay, const uint64_t *uid,
+                            const uint8_t *skip_k, uint32_t n_tok, uint64_t seed, uint64_t *n_bad) {
+  if (n_tok == 0) return 0;
+  uint64_t n_rows = (uint64_t)n_tok * lay.n_layers * 2;
+  verify_kernel<<<grid_for(n_rows), 256, 0, stream>>>((const uint8_t *)base, lay, uid, skip_k, n_tok, seed,
+                                                      (unsigned long long *)n_bad);
+  return (int)hipGetLastError();
+}

@@ -1,0 +1,187 @@
+"""ctypes front end of the CPU oracle (``cp_oracle.cpp``).
+
+TEST INFRASTRUCTURE ONLY.  Only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the product package never does.
+Arrays are numpy arrays in host memory; every function returns new arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcp_oracle.so")
+
+HASH_NONE = 0xFFFFFFFFFFFFFFFF
+SLOT_NONE = 0xFFFFFFFF
+FLAG_SPANS_OVERFLOW = 1
+FLAG_POOL_FULL = 2
+BASE = 0x100000001B3
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with g++ -O2 into ``libcp_oracle.so`` beside its source."""
+    src = os.path.join(_HERE, "cp_oracle.cpp")
+    if force or not os.path.exists(_LIB_PATH):
+        subprocess.run(
+            ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB_PATH, src],
+            check=True,
+        )
+    return _LIB_PATH
+
+
+class Layout(C.Structure):
+    """Mirror of ``cpo_layout`` (strides in bytes)."""
+
+    _fields_ = [
+        ("n_layers", C.c_uint32),
+        ("n_kv_heads", C.c_uint32),
+        ("head_dim", C.c_uint32),
+        ("tok_stride", C.c_uint64),
+        ("layer_stride", C.c_uint64),
+        ("kv_stride", C.c_uint64),
+    ]
+
+    @property
+    def row_bytes(self) -> int:
+        return self.n_kv_heads * self.head_dim * 2
+
+
+class Rope(C.Structure):
+    _fields_ = [("theta", C.c_double), ("style", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            build()
+        L = C.CDLL(_LIB_PATH)
+        vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32
+        L.cpo_index_new.restype = vp
+        L.cpo_index_free.argtypes = [vp]
+        L.cpo_index_size.restype = u64
+        L.cpo_index_size.argtypes = [vp]
+        L.cpo_hash_segments.argtypes = [vp, vp, vp, u32, u64, vp]
+        L.cpo_probe.argtypes = [vp, vp, u32, vp]
+        L.cpo_build_spans.restype = u32
+        L.cpo_build_spans.argtypes = [vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
+        L.cpo_gather_kv.argtypes = [vp, Layout, vp, Layout, vp, vp, vp, vp, u32, vp]
+        L.cpo_insert_kv.restype = u32
+        L.cpo_insert_kv.argtypes = [vp, vp, vp, u32, vp, u32, vp, Layout, vp, Layout, vp, vp, vp, vp, vp]
+        L.cpo_bf16_to_double.restype = C.c_double
+        L.cpo_bf16_to_double.argtypes = [C.c_uint16]
+        L.cpo_double_to_bf16.restype = C.c_uint16
+        L.cpo_double_to_bf16.argtypes = [C.c_double]
+        L.cpo_rope_head.argtypes = [vp, vp, u32, i32, C.c_double, u32]
+        L.cpo_rope_head_f64.argtypes = [vp, vp, u32, C.c_double, C.c_double, u32]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _arr(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+class Index:
+    """The pool index (key -> slot)."""
+
+    def __init__(self):
+        self._h = C.c_void_p(lib().cpo_index_new())
+
+    def __len__(self):
+        return int(lib().cpo_index_size(self._h))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.cpo_index_free(self._h)
+            self._h = None
+
+
+def hash_segments(tok, mask, off, base=BASE):
+    tok, mask, off = _arr(tok, np.uint32), _arr(mask, np.uint8), _arr(off, np.uint32)
+    out = np.empty(tok.shape[0], dtype=np.uint64)
+    lib().cpo_hash_segments(_p(tok), _p(mask), _p(off), len(off) - 1, base, _p(out))
+    return out
+
+
+def probe(index: Index, hashes):
+    hashes = _arr(hashes, np.uint64)
+    out = np.empty(hashes.shape[0], dtype=np.uint32)
+    lib().cpo_probe(index._h, _p(hashes), hashes.shape[0], _p(out))
+    return out
+
+
+def build_spans(slot, off, slot_pos=None, max_spans=None):
+    """Returns (src, dst, len, delta, n_spans_found, flags); arrays hold min(n, max_spans)."""
+    slot, off = _arr(slot, np.uint32), _arr(off, np.uint32)
+    if slot_pos is not None:
+        slot_pos = _arr(slot_pos, np.int32)
+    if max_spans is None:
+        max_spans = max(1, slot.shape[0])
+    src = np.zeros(max_spans, np.uint32)
+    dst = np.zeros(max_spans, np.uint32)
+    ln = np.zeros(max_spans, np.uint32)
+    delta = np.zeros(max_spans, np.int32)
+    flags = np.zeros(1, np.uint32)
+    n = lib().cpo_build_spans(_p(slot), _p(off), len(off) - 1, _p(slot_pos), max_spans, _p(src), _p(dst),
+                              _p(ln), _p(delta), _p(flags))
+    k = min(n, max_spans)
+    return src[:k], dst[:k], ln[:k], delta[:k], int(n), int(flags[0])
+
+
+def gather_kv(pool, pool_l: Layout, dst, dst_l: Layout, src, dstpos, ln, delta=None, rope: Rope | None = None):
+    """Copies in place into ``dst`` (a writable uint8/uint16 numpy buffer)."""
+    src, dstpos, ln = _arr(src, np.uint32), _arr(dstpos, np.uint32), _arr(ln, np.uint32)
+    if delta is not None:
+        delta = _arr(delta, np.int32)
+    lib().cpo_gather_kv(_p(pool), pool_l, _p(dst), dst_l, _p(src), _p(dstpos), _p(ln), _p(delta), len(src),
+                        C.byref(rope) if rope is not None else None)
+
+
+def insert_kv(index: Index, hashes, off, free_slots, src, src_l: Layout, pool, pool_l: Layout, slot_pos,
+              tok=None, slot_tok=None):
+    """Returns (slot_out, n_inserted, flags).  ``pool``, ``slot_pos`` (and ``slot_tok``) are updated in place."""
+    hashes, off, free_slots = _arr(hashes, np.uint64), _arr(off, np.uint32), _arr(free_slots, np.uint32)
+    assert slot_pos.dtype == np.int32 and slot_pos.flags.c_contiguous
+    if tok is not None:
+        tok = _arr(tok, np.uint32)
+        assert slot_tok is not None and slot_tok.dtype == np.uint32
+    slot_out = np.empty(hashes.shape[0], np.uint32)
+    flags = np.zeros(1, np.uint32)
+    n = lib().cpo_insert_kv(index._h, _p(hashes), _p(off), len(off) - 1, _p(free_slots), len(free_slots), _p(src),
+                            src_l, _p(pool), pool_l, _p(slot_pos), _p(slot_out), _p(flags), _p(tok), _p(slot_tok))
+    return slot_out, int(n), int(flags[0])
+
+
+def bf16_to_double(bits: int) -> float:
+    return float(lib().cpo_bf16_to_double(int(bits)))
+
+
+def double_to_bf16(x: float) -> int:
+    return int(lib().cpo_double_to_bf16(float(x)))
+
+
+def rope_head(x_bits, delta: int, theta: float, style: int = 0):
+    x_bits = _arr(x_bits, np.uint16)
+    out = np.empty_like(x_bits)
+    lib().cpo_rope_head(_p(x_bits), _p(out), x_bits.shape[0], int(delta), float(theta), int(style))
+    return out
+
+
+def rope_head_f64(x, delta: float, theta: float, style: int = 0):
+    x = _arr(x, np.float64)
+    out = np.empty_like(x)
+    lib().cpo_rope_head_f64(_p(x), _p(out), x.shape[0], float(delta), float(theta), int(style))
+    return out

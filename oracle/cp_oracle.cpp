@@ -1,0 +1,224 @@
+// CPU oracle for the token-granular KV sharing path of CachePrune.
+//
+// TEST INFRASTRUCTURE ONLY: see cp_oracle.h.  Plain sequential code, one loop
+// per definition, no blocking, no threads, no tuning.  It shares nothing with
+// the GPU library.
+#include "cp_oracle.h"
+
+#include <cfenv>
+#include <cmath>
+#include <cstring>
+#include <unordered_map>
+#include <vector>
+
+struct cpo_index {
+  std::unordered_map<uint64_t, uint32_t> map;
+};
+
+extern "C" cpo_index *cpo_index_new(void) { return new cpo_index(); }
+extern "C" void cpo_index_free(cpo_index *ix) { delete ix; }
+extern "C" uint64_t cpo_index_size(const cpo_index *ix) { return ix->map.size(); }
+
+// Sec. 4.2.1: sensitive tokens are separators; Sec. 4.2.2: polynomial rolling
+// hash.  Horner form of  sum (t_m + 1) * base^(k-m)  with unsigned wrap-around
+// (= arithmetic mod 2^64).
+extern "C" void cpo_hash_segments(const uint32_t *tok, const uint8_t *mask, const uint32_t *off,
+                                  uint32_t R, uint64_t base, uint64_t *hash_out) {
+  for (uint32_t r = 0; r < R; ++r) {
+    uint64_t c = 0;
+    for (uint32_t i = off[r]; i < off[r + 1]; ++i) {
+      if (mask[i]) {
+        hash_out[i] = CPO_HASH_NONE;
+        c = 0;
+      } else {
+        c = c * base + (uint64_t)tok[i] + 1u;
+        hash_out[i] = (c == CPO_HASH_NONE) ? CPO_HASH_NONE - 1 : c;
+      }
+    }
+  }
+}
+
+// Sec. 4.3.5 "Storage format and indexing": segments are found through a hash
+// index.  Here: one key per pooled token, looked up in an ordinary map.
+extern "C" void cpo_probe(const cpo_index *ix, const uint64_t *hash, uint32_t N,
+                          uint32_t *slot_out) {
+  for (uint32_t i = 0; i < N; ++i) {
+    slot_out[i] = CPO_SLOT_NONE;
+    if (hash[i] == CPO_HASH_NONE) continue;
+    auto it = ix->map.find(hash[i]);
+    if (it != ix->map.end()) slot_out[i] = it->second;
+  }
+}
+
+// Sec. 4.3.1: the retriever's metadata are token spans.  Sequential run-length
+// encoding of the slot array.
+extern "C" uint32_t cpo_build_spans(const uint32_t *slot, const uint32_t *off, uint32_t R,
+                                    const int32_t *slot_pos, uint32_t max_spans,
+                                    uint32_t *span_src, uint32_t *span_dst, uint32_t *span_len,
+                                    int32_t *span_delta, uint32_t *flags) {
+  uint32_t n = 0; // spans opened so far
+  for (uint32_t r = 0; r < R; ++r) {
+    bool open = false;
+    uint32_t cur_src = 0, cur_dst = 0, cur_len = 0;
+    int32_t cur_delta = 0;
+    auto close = [&]() {
+      if (!open) return;
+      if (n < max_spans) {
+        span_src[n] = cur_src;
+        span_dst[n] = cur_dst;
+        span_len[n] = cur_len;
+        if (span_delta) span_delta[n] = cur_delta;
+      }
+      ++n;
+      open = false;
+    };
+    for (uint32_t i = off[r]; i < off[r + 1]; ++i) {
+      if (slot[i] == CPO_SLOT_NONE) {
+        close();
+        continue;
+      }
+      int32_t p = (int32_t)(i - off[r]);
+      int32_t d = slot_pos ? p - slot_pos[slot[i]] : 0;
+      if (open && slot[i] == cur_src + cur_len && d == cur_delta) {
+        ++cur_len; // position i follows position i-1 because the span is open
+      } else {
+        close();
+        open = true;
+        cur_src = slot[i];
+        cur_dst = i;
+        cur_len = 1;
+        cur_delta = d;
+      }
+    }
+    close();
+  }
+  if (n > max_spans && flags) *flags |= CPO_FLAG_SPANS_OVERFLOW;
+  return n;
+}
+
+extern "C" double cpo_bf16_to_double(uint16_t bits) {
+  uint32_t u = (uint32_t)bits << 16; // bf16 is the upper half of an IEEE float
+  float f;
+  std::memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+// One rounding, to nearest, ties to even, from double to the bf16 grid
+// (8 significant bits, float's exponent range).
+extern "C" uint16_t cpo_double_to_bf16(double x) {
+  float f;
+  if (std::isnan(x)) {
+    f = std::nanf("");
+  } else if (std::isinf(x) || x == 0.0) {
+    f = (float)x;
+  } else {
+    int e;
+    std::frexp(x, &e);                 // |x| = m * 2^e, m in [0.5, 1)
+    int q = e - 8;                     // spacing of bf16 values around x is 2^q
+    if (q < -133) q = -133;            // subnormal range: fixed spacing 2^-133
+    int old = std::fegetround();
+    std::fesetround(FE_TONEAREST);     // nearbyint: ties to even
+    double n = std::nearbyint(std::ldexp(x, -q));
+    std::fesetround(old);
+    double y = std::ldexp(n, q);
+    if (std::fabs(y) >= std::ldexp(1.0, 128)) y = std::copysign(INFINITY, x);
+    f = (float)y;                      // exact: y is on the bf16 grid
+  }
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  return (uint16_t)(u >> 16);
+}
+
+// Rotary embedding: the pair (a, b) at frequency index j turns by the angle
+// delta * theta^(-2j/head_dim).
+extern "C" void cpo_rope_head_f64(const double *in, double *out, uint32_t head_dim, double delta,
+                                  double theta, uint32_t style) {
+  uint32_t half = head_dim / 2;
+  for (uint32_t j = 0; j < half; ++j) {
+    double inv_freq = std::pow(theta, -2.0 * (double)j / (double)head_dim);
+    double phi = delta * inv_freq;
+    double c = std::cos(phi), s = std::sin(phi);
+    uint32_t ia = style == 0 ? j : 2 * j;
+    uint32_t ib = style == 0 ? j + half : 2 * j + 1;
+    double a = in[ia], b = in[ib];
+    out[ia] = a * c - b * s;
+    out[ib] = b * c + a * s;
+  }
+}
+
+extern "C" void cpo_rope_head(const uint16_t *in, uint16_t *out, uint32_t head_dim,
+                              int32_t delta, double theta, uint32_t style) {
+  std::vector<double> x(head_dim), y(head_dim);
+  for (uint32_t e = 0; e < head_dim; ++e) x[e] = cpo_bf16_to_double(in[e]);
+  cpo_rope_head_f64(x.data(), y.data(), head_dim, (double)delta, theta, style);
+  for (uint32_t e = 0; e < head_dim; ++e) out[e] = cpo_double_to_bf16(y[e]);
+}
+
+static inline const uint8_t *row_ptr(const void *base, const cpo_layout &l, uint64_t t,
+                                     uint32_t layer, uint32_t kv) {
+  return (const uint8_t *)base + t * l.tok_stride + layer * l.layer_stride + kv * l.kv_stride;
+}
+
+// Sec. 4.1 / 4.3.1: matched segments are placed into the request; everything
+// else is left alone.
+extern "C" void cpo_gather_kv(const void *pool, cpo_layout pool_l, void *dst, cpo_layout dst_l,
+                              const uint32_t *span_src, const uint32_t *span_dst,
+                              const uint32_t *span_len, const int32_t *span_delta,
+                              uint32_t n_spans, const cpo_rope *rope) {
+  const uint32_t H = pool_l.n_kv_heads, D = pool_l.head_dim;
+  const size_t row_bytes = (size_t)H * D * 2;
+  for (uint32_t s = 0; s < n_spans; ++s) {
+    int32_t delta = (span_delta && rope) ? span_delta[s] : 0;
+    for (uint32_t k = 0; k < span_len[s]; ++k) {
+      for (uint32_t l = 0; l < pool_l.n_layers; ++l) {
+        for (uint32_t kv = 0; kv < 2; ++kv) {
+          const uint8_t *from = row_ptr(pool, pool_l, (uint64_t)span_src[s] + k, l, kv);
+          uint8_t *to = (uint8_t *)row_ptr(dst, dst_l, (uint64_t)span_dst[s] + k, l, kv);
+          if (kv == 0 && delta != 0) {
+            for (uint32_t h = 0; h < H; ++h)
+              cpo_rope_head((const uint16_t *)from + (size_t)h * D, (uint16_t *)to + (size_t)h * D,
+                            D, delta, rope->theta, rope->style);
+          } else {
+            std::memcpy(to, from, row_bytes);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Sec. 4.1 "Workflow" (post-inference storing) and Sec. 4.3.5 (one copy of a
+// duplicate): first occurrence in packed order owns the key.
+extern "C" uint32_t cpo_insert_kv(cpo_index *ix, const uint64_t *hash, const uint32_t *off,
+                                  uint32_t R, const uint32_t *free_slots, uint32_t n_free,
+                                  const void *src, cpo_layout src_l, void *pool, cpo_layout pool_l,
+                                  int32_t *slot_pos, uint32_t *slot_out, uint32_t *flags,
+                                  const uint32_t *tok, uint32_t *slot_tok) {
+  const size_t row_bytes = (size_t)pool_l.n_kv_heads * pool_l.head_dim * 2;
+  uint32_t n_new = 0;
+  for (uint32_t r = 0; r < R; ++r) {
+    for (uint32_t i = off[r]; i < off[r + 1]; ++i) {
+      slot_out[i] = CPO_SLOT_NONE;
+      if (hash[i] == CPO_HASH_NONE) continue;
+      auto it = ix->map.find(hash[i]);
+      if (it != ix->map.end()) {
+        slot_out[i] = it->second;
+        continue;
+      }
+      if (n_new == n_free) {
+        if (flags) *flags |= CPO_FLAG_POOL_FULL;
+        continue;
+      }
+      uint32_t s = free_slots[n_new++];
+      ix->map.emplace(hash[i], s);
+      slot_pos[s] = (int32_t)(i - off[r]);
+      slot_out[i] = s;
+      if (tok && slot_tok) slot_tok[s] = tok[i];
+      for (uint32_t l = 0; l < pool_l.n_layers; ++l)
+        for (uint32_t kv = 0; kv < 2; ++kv)
+          std::memcpy((uint8_t *)row_ptr(pool, pool_l, s, l, kv), row_ptr(src, src_l, i, l, kv),
+                      row_bytes);
+    }
+  }
+  return n_new;
+}

@@ -1,0 +1,125 @@
+/*
+ * CPU oracle for the token-granular KV sharing path of CachePrune.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, sequential, deliberately slow
+ * reference that the tests, the smoke check and the benchmark's CPU-baseline
+ * leg call to decide whether the GPU library is right.  It shares no source,
+ * header, table or helper with the GPU library and must never be used as a
+ * product code path or as a fallback.
+ *
+ * All pointers are HOST pointers.  Nothing here is thread-safe.
+ *
+ * What each function follows (paper = CachePrune):
+ *   - Sensitive tokens (mask = 1) are separators that cut a prompt into
+ *     segments; only tokens with mask = 0 may be shared (Sec. 3.3 definition
+ *     of selective sharing, Sec. 4.2.1 first paragraph).
+ *   - Segments are identified by a polynomial rolling hash (Sec. 4.2.2,
+ *     "Choice of rolling hash algorithm").  This build takes the hash modulo
+ *     2^64 with a fixed base and hashes every run from its first token
+ *     (a "chain" hash), one key per token.
+ *   - The pool keeps one copy of a duplicated segment (Sec. 4.3.5 "Lifecycle
+ *     management"): insertion is insert-if-absent, first occurrence wins.
+ *   - Matched segments are linked into the request, unmatched positions are
+ *     left for the engine (Sec. 4.1 "KV Retriever", Sec. 4.3.1 "Operational
+ *     details").  Here "linking" is a copy of the token's K and V rows of
+ *     every layer into the request's buffers.
+ *   - Key re-rotation by a position delta (RoPE) is not in the paper; it is
+ *     the textbook rotary embedding, evaluated in double precision.
+ */
+#ifndef CP_ORACLE_H
+#define CP_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CPO_HASH_NONE 0xFFFFFFFFFFFFFFFFull /* hash of a sensitive token      */
+#define CPO_SLOT_NONE 0xFFFFFFFFu           /* "no pool slot"                 */
+
+#define CPO_FLAG_SPANS_OVERFLOW 1u /* more spans than max_spans; extra dropped */
+#define CPO_FLAG_POOL_FULL 2u      /* free list exhausted; later tokens dropped */
+
+/* Byte address of the row of (token or slot t, layer l, kv in {0 = K, 1 = V}):
+ *   base + t * tok_stride + l * layer_stride + kv * kv_stride
+ * A row is n_kv_heads * head_dim bf16 values, contiguous. */
+typedef struct {
+  uint32_t n_layers, n_kv_heads, head_dim;
+  uint64_t tok_stride, layer_stride, kv_stride; /* bytes */
+} cpo_layout;
+
+/* Rotary embedding parameters.  style 0: element j pairs with j + head_dim/2;
+ * style 1: element 2j pairs with 2j + 1. */
+typedef struct {
+  double theta;
+  uint32_t style;
+} cpo_rope;
+
+/* The pool index: an associative container key -> slot.  Opaque. */
+typedef struct cpo_index cpo_index;
+cpo_index *cpo_index_new(void);
+void cpo_index_free(cpo_index *);
+uint64_t cpo_index_size(const cpo_index *);
+
+/* Chain hash of every token.  R requests are packed back to back, request r
+ * holds tokens off[r] .. off[r+1]-1.  For a sensitive token hash_out = NONE
+ * and the chain restarts; the chain also restarts at every request start.
+ * For the k-th token (k = 0, 1, ..) of a run t_0 .. t_k:
+ *   hash = sum_{m=0..k} (t_m + 1) * base^(k-m)   (mod 2^64),
+ * and a result equal to NONE is replaced by NONE - 1. */
+void cpo_hash_segments(const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t R,
+                       uint64_t base, uint64_t *hash_out);
+
+/* slot_out[i] = slot stored under hash[i], or SLOT_NONE (also for hash NONE). */
+void cpo_probe(const cpo_index *, const uint64_t *hash, uint32_t N, uint32_t *slot_out);
+
+/* Run-length pass.  A span is a maximal run of consecutive positions of one
+ * request whose slots are valid and consecutive and (if slot_pos is given)
+ * share one position delta = (position inside the request) - slot_pos[slot].
+ * Spans come out in (request, position) order; dst is the packed token index.
+ * Returns the number of spans found; only the first max_spans are stored and
+ * SPANS_OVERFLOW is or-ed into *flags if there were more.  slot_pos and
+ * span_delta may be NULL (delta = 0). */
+uint32_t cpo_build_spans(const uint32_t *slot, const uint32_t *off, uint32_t R,
+                         const int32_t *slot_pos, uint32_t max_spans, uint32_t *span_src,
+                         uint32_t *span_dst, uint32_t *span_len, int32_t *span_delta,
+                         uint32_t *flags);
+
+/* For every span, k < len, layer, K and V: copy the row of pool slot src+k to
+ * the row of request token dst+k.  If span_delta and rope are non-NULL, K rows
+ * of spans with delta != 0 are rotated by delta positions (double precision,
+ * one rounding to bf16, round-to-nearest-even); V rows and delta = 0 are byte
+ * copies.  Rows not covered by a span are not touched. */
+void cpo_gather_kv(const void *pool, cpo_layout pool_l, void *dst, cpo_layout dst_l,
+                   const uint32_t *span_src, const uint32_t *span_dst, const uint32_t *span_len,
+                   const int32_t *span_delta, uint32_t n_spans, const cpo_rope *rope);
+
+/* Insert-if-absent, in packed order.  A token with a valid hash whose key is
+ * absent takes the next slot of free_slots, records slot_pos[slot] = position
+ * inside its request, and has all its rows copied from src to the pool.  When
+ * the free list is used up POOL_FULL is flagged and the token is dropped
+ * (slot_out = NONE).  slot_out[i] = slot now holding the key, NONE for
+ * sensitive tokens.  tok / slot_tok (both nullable) record which token id was
+ * stored in each slot, for audits.  Returns the number of newly stored tokens. */
+uint32_t cpo_insert_kv(cpo_index *, const uint64_t *hash, const uint32_t *off, uint32_t R,
+                       const uint32_t *free_slots, uint32_t n_free, const void *src,
+                       cpo_layout src_l, void *pool, cpo_layout pool_l, int32_t *slot_pos,
+                       uint32_t *slot_out, uint32_t *flags, const uint32_t *tok,
+                       uint32_t *slot_tok);
+
+/* Building blocks exposed so that tests can pin them one by one. */
+double cpo_bf16_to_double(uint16_t bits);
+uint16_t cpo_double_to_bf16(double x); /* round-to-nearest-even, one rounding */
+/* Rotate one head (head_dim bf16 values) by delta positions. */
+void cpo_rope_head(const uint16_t *in, uint16_t *out, uint32_t head_dim, int32_t delta,
+                   double theta, uint32_t style);
+/* Same rotation without any rounding: double in, double out. */
+void cpo_rope_head_f64(const double *in, double *out, uint32_t head_dim, double delta,
+                       double theta, uint32_t style);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
