@@ -61,12 +61,38 @@ def row(seed: int, uid: int, layer: int, kv: int, n_layers: int, row_elems: int)
 
 
 def rows_for_tokens(seed, uids, n_layers, row_elems):
-    """uint16[len(uids), n_layers, 2, row_elems] on the host (small inputs only)."""
-    out = np.empty((len(uids), n_layers, 2, row_elems), np.uint16)
-    for t, uid in enumerate(uids):
-        for l in range(n_layers):
-            for kv in range(2):
-                out[t, l, kv] = row(seed, int(uid), l, kv, n_layers, row_elems)
+    """uint16[len(uids), n_layers, 2, row_elems] on the host (same definition as ``row``,
+    vectorised over rows; meant for up to a few hundred MB)."""
+    uids = np.asarray(list(uids) if not isinstance(uids, np.ndarray) else uids, dtype=np.uint64)
+    n = len(uids)
+    out = np.empty((n, n_layers, 2, row_elems), np.uint16)
+    if n == 0:
+        return out
+    flat = out.reshape(n * n_layers * 2, row_elems)
+    lkv = np.arange(n_layers * 2, dtype=np.uint64)  # layer * 2 + kv
+    pair = np.arange(row_elems // 2, dtype=np.uint64)
+    step = max(1, (1 << 22) // max(1, row_elems))  # rows per chunk
+    with np.errstate(over="ignore"):
+        row_id = ((uids[:, None] * np.uint64(n_layers * 2)) + lkv[None, :]).reshape(-1)
+        for r0 in range(0, len(row_id), step):
+            rid = row_id[r0 : r0 + step]
+            z = np.uint64(seed) + rid[:, None] * np.uint64(C1) + pair[None, :] * np.uint64(C2)
+            z ^= z >> np.uint64(32)
+            z *= np.uint64(M)
+            z ^= z >> np.uint64(32)
+            z *= np.uint64(M)
+            z ^= z >> np.uint64(32)
+            words = np.empty((len(rid), row_elems), np.uint32)
+            words[:, 0::2] = (z & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+            words[:, 1::2] = (z >> np.uint64(32)).astype(np.uint32)
+            s = (words & 0xFF) + ((words >> 8) & 0xFF) + ((words >> 16) & 0xFF) + (words >> 24)
+            x = (s.astype(np.int32) - 510).astype(np.float32) * SCALE
+            u = x.view(np.uint32)
+            u = u + np.uint32(0x7FFF) + ((u >> 16) & 1)
+            flat[r0 : r0 + step] = (u >> 16).astype(np.uint16)
+    poison = uids == np.uint64(UID_NONE)
+    if poison.any():
+        out[poison] = POISON16
     return out
 
 

@@ -1,0 +1,183 @@
+/*
+ * libcacheprune — token-granular, privacy-aware KV-cache sharing on AMD MI355X
+ * (gfx950).  C ABI of the data-parallel hot path of CachePrune:
+ *
+ *   lookup :  cp_hash_segments -> cp_probe -> cp_build_spans -> cp_gather_kv
+ *   insert :  cp_hash_segments -> cp_insert_kv
+ *
+ * Conventions for every call
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; none synchronises.  Work of successive
+ *     calls on one stream runs in order.
+ *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned
+ *     by the caller.  The library allocates and frees nothing and keeps no state
+ *     besides the last HIP error code.
+ *   - `scratch` is caller-provided device memory of at least
+ *     cp_scratch_bytes(N, max_spans) bytes, 256-byte aligned, whose contents are
+ *     meaningless between calls; calls that share a scratch buffer must be on
+ *     one stream.
+ *   - R requests are packed back to back: request r holds the tokens
+ *     off[r] .. off[r+1]-1, off[0] = 0, off[R] = N, off non-decreasing.
+ *   - Return value: CP_OK or a negative CP_ERR_* code.  Argument errors are
+ *     detected on the host before anything is enqueued.  Capacity conditions
+ *     found on the device do not fail the call; they set bits in the caller's
+ *     device word `status_flags` (or-ed in, never cleared by the library).
+ *   - Limits: N < 2^31 tokens per call, pool slots < 2^31, table capacity
+ *     < 2^32 entries, bf16 KV only.
+ */
+#ifndef CACHEPRUNE_H
+#define CACHEPRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CP_HASH_NONE 0xFFFFFFFFFFFFFFFFull /* hash of a sensitive token; also "empty" table key */
+#define CP_SLOT_NONE 0xFFFFFFFFu           /* "no pool slot" */
+
+#define CP_OK 0
+#define CP_ERR_INVALID_ARG (-1) /* null / misaligned pointer, inconsistent sizes          */
+#define CP_ERR_UNSUPPORTED (-2) /* shape or size outside the limits above                  */
+#define CP_ERR_HIP (-3)         /* a launch failed; see cp_last_hip_error()                */
+#define CP_ERR_SCRATCH (-4)     /* scratch_bytes smaller than cp_scratch_bytes() demands   */
+
+#define CP_FLAG_SPANS_OVERFLOW 1u /* more than max_spans spans: only the first max_spans kept  */
+#define CP_FLAG_POOL_FULL 2u      /* free list used up: later new tokens were not stored       */
+#define CP_FLAG_TABLE_FULL 4u     /* no free table entry: affected tokens were not stored      */
+#define CP_FLAG_BAD_INDEX 8u      /* a span / free-list entry points outside pool or buffer: skipped */
+
+#define CP_TABLE_BUCKET 16u /* table entries per bucket; capacity is a multiple of it */
+
+/* Open-addressing hash table  chain hash -> pool slot  (the pool index of
+ * Sec. 4.3.5 "Storage format and indexing", one key per pooled token).
+ * `capacity` entries, a multiple of CP_TABLE_BUCKET, any such value (not only
+ * powers of two).  cp_table_init makes it empty.  Only the mapping is part of
+ * the contract; the arrangement of entries is not. */
+typedef struct {
+  uint64_t *keys;    /* [capacity], 128-byte aligned */
+  uint32_t *vals;    /* [capacity], 64-byte aligned  */
+  uint64_t capacity; /* entries */
+} cp_table;
+
+/* Where the KV rows of a token (or pool slot) live.  Row (t, layer, kv) with
+ * kv = 0 for K and 1 for V starts at byte
+ *     base + t * tok_stride + layer * layer_stride + kv * kv_stride
+ * and holds n_kv_heads * head_dim bf16 values contiguously.  Base and strides
+ * are multiples of 16 bytes and so is the row size. */
+typedef struct {
+  uint32_t n_layers, n_kv_heads, head_dim;
+  uint64_t tok_stride, layer_stride, kv_stride; /* bytes */
+} cp_kv_layout;
+
+/* Rotary position embedding used when a cached key is reused at another
+ * position (not part of the paper; the textbook rotation).  style 0 pairs
+ * element j with j + head_dim/2, style 1 pairs 2j with 2j + 1. */
+typedef struct {
+  double theta;
+  uint32_t style;
+} cp_rope;
+
+/* Smallest valid table capacity that keeps n_keys keys at or below load_factor. */
+uint64_t cp_table_capacity_for(uint64_t n_keys, double load_factor);
+
+/* Device bytes of scratch that any call below needs for N tokens / max_spans spans. */
+size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans);
+
+/* hipError_t of the last failed launch of this thread's calls (0 = none). */
+int32_t cp_last_hip_error(void);
+
+/* Launch-shape knobs of the row mover behind cp_gather_kv / cp_insert_kv (host
+ * state, process wide; results never depend on them).
+ *   key 0: rows of one token per work item (0 = all 2 * n_layers rows)
+ *   key 1: resident workgroups per compute unit
+ *   key 2: bit 0 non-temporal loads, bit 1 non-temporal stores */
+int32_t cp_tune(int32_t key, uint32_t value);
+
+/* Empty the table: every key CP_HASH_NONE, every value CP_SLOT_NONE. */
+int32_t cp_table_init(void *stream, cp_table table);
+
+/* Segmented chain hash (Sec. 4.2.1: sensitive tokens are separators that cut a
+ * prompt into segments; Sec. 4.2.2: polynomial rolling hash, here modulo 2^64).
+ * For the k-th token of a run of non-sensitive tokens t_0 .. t_k inside one
+ * request:  hash = sum_{m<=k} (t_m + 1) * base^(k-m)  mod 2^64, with the value
+ * CP_HASH_NONE replaced by CP_HASH_NONE - 1.  Sensitive tokens (mask != 0) get
+ * CP_HASH_NONE; runs restart after them and at every request start.
+ *   tok [N] uint32, mask [N] uint8, off [R+1] uint32  ->  hash_out [N] uint64. */
+int32_t cp_hash_segments(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off,
+                         uint32_t N, uint32_t R, uint64_t base, uint64_t *hash_out, void *scratch,
+                         size_t scratch_bytes);
+
+/* Table lookup (the hash lookup the retriever performs, Sec. 4.2.2 / 4.3.1):
+ * slot_out[i] = slot stored under hash[i], or CP_SLOT_NONE if the key is absent
+ * or hash[i] is CP_HASH_NONE.  A sensitive token is therefore never served. */
+int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out);
+
+/* Run-length pass: turn per-token slots into copy descriptors (the "token
+ * spans" of the retriever's metadata, Sec. 4.3.1).  A span is a maximal run of
+ * consecutive positions of one request whose slots are valid and consecutive
+ * and, if slot_pos is given, share one position delta
+ *     delta = (position inside the request) - slot_pos[slot].
+ * Spans are written in (request, position) order: span_src = first pool slot,
+ * span_dst = packed index of the first token, span_len, span_delta.
+ * *n_spans (device) = min(number of spans, max_spans); if there were more,
+ * CP_FLAG_SPANS_OVERFLOW is set and the first max_spans are kept.
+ * slot_pos and span_delta may be NULL (then delta is 0 / not written).
+ * span_off, if not NULL, receives [max_spans + 1] exclusive prefix sums of
+ * span_len (span_off[k] = tokens covered by spans 0..k-1, entries up to
+ * *n_spans are valid); passing it on to cp_gather_kv saves that call a pass. */
+int32_t cp_build_spans(void *stream, const uint32_t *slot, const uint32_t *off, uint32_t N, uint32_t R,
+                       const int32_t *slot_pos, uint32_t max_spans, uint32_t *span_src,
+                       uint32_t *span_dst, uint32_t *span_len, int32_t *span_delta,
+                       uint32_t *span_off, uint32_t *n_spans, uint32_t *status_flags, void *scratch,
+                       size_t scratch_bytes);
+
+/* Token-granular gather ("links them to the sequence", Sec. 4.1 KV Retriever;
+ * here a copy out of the pool into the request's per-layer K/V buffers).
+ * For every span s < *n_spans, k < span_len[s], every layer, K and V:
+ *     row(dst, span_dst[s] + k)  <-  row(pool, span_src[s] + k).
+ * Rows of tokens not covered by a span are not written (Sec. 4.3.1: unmatched
+ * positions are left for the engine).  If rope and span_delta are both
+ * non-NULL, K rows of spans with delta != 0 are rotated by delta positions
+ * (evaluated in double precision, rounded once to bf16); V rows and spans with
+ * delta == 0 are copied bit for bit.  `rope` is a HOST pointer, read before
+ * the call returns.  span_off may be NULL (computed internally) or the array
+ * cp_build_spans produced (then scratch may be NULL).  Spans must not overlap
+ * in dst.  pool_l and dst_l must agree on n_layers, n_kv_heads and head_dim;
+ * rotation needs head_dim a power of two in [16, 512].  The pool holds
+ * n_pool_slots slots and dst n_dst_tokens tokens: a token of a span that falls
+ * outside either is skipped and CP_FLAG_BAD_INDEX is set. */
+int32_t cp_gather_kv(void *stream, const void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, void *dst,
+                     cp_kv_layout dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
+                     const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
+                     const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
+                     const cp_rope *rope, uint32_t *status_flags, void *scratch, size_t scratch_bytes);
+
+/* Insert-if-absent with the matching scatter (post-inference storing, Sec. 4.1
+ * "Workflow"; one copy of a duplicate, Sec. 4.3.5 "Lifecycle management").
+ * Every token with hash != CP_HASH_NONE whose key is not in the table gets a
+ * table entry and a pool slot; its rows are copied  row(src, i) -> row(pool,
+ * slot)  and slot_pos[slot] = position inside its request.  Determinism: if a
+ * key occurs several times in one call the occurrence with the lowest packed
+ * index stores it, keys already present are left alone, and new slots are
+ * free_slots[0], free_slots[1], .. in packed order of the storing tokens — the
+ * result does not depend on scheduling.  When the n_free slots are used up the
+ * remaining new tokens are dropped and CP_FLAG_POOL_FULL is set.  Free-list
+ * entries >= n_pool_slots are never used (CP_FLAG_BAD_INDEX).  If the table has
+ * no free entry left CP_FLAG_TABLE_FULL is set and which of the affected tokens
+ * were dropped is unspecified: size the table for the keys it must hold.
+ *   slot_out [N]: slot holding each token's key after the call, CP_SLOT_NONE
+ *                 for sensitive or dropped tokens.
+ *   *n_inserted (device): number of tokens stored by this call. */
+int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
+                     uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
+                     cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
+                     int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
+                     void *scratch, size_t scratch_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

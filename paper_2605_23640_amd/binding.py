@@ -1,0 +1,217 @@
+"""Thin ctypes binding of libcacheprune.so: the same entry points as
+``include/cacheprune.h``, taking torch CUDA(ROCm) tensors for device memory.
+
+Argument marshalling only — every step of the path runs in the library's HIP
+kernels.  There is no CPU fallback: if the library is not built or no GPU is
+present, the calls raise.
+
+Integer tensors use torch's signed dtypes of the same width (int32 for uint32,
+int64 for uint64); the bit patterns are what the C ABI defines.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcacheprune.so")
+
+HASH_NONE = 0xFFFFFFFFFFFFFFFF
+SLOT_NONE = 0xFFFFFFFF
+BASE = 0x100000001B3  # polynomial base of the chain hash
+TABLE_BUCKET = 16
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH = 0, -1, -2, -3, -4
+FLAG_SPANS_OVERFLOW, FLAG_POOL_FULL, FLAG_TABLE_FULL, FLAG_BAD_INDEX = 1, 2, 4, 8
+
+EXPORTS = [
+    "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_tune", "cp_table_init",
+    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv",
+]
+
+
+class CpError(RuntimeError):
+    def __init__(self, fn, code):
+        names = {-1: "CP_ERR_INVALID_ARG", -2: "CP_ERR_UNSUPPORTED", -3: "CP_ERR_HIP", -4: "CP_ERR_SCRATCH"}
+        extra = f" (hipError {lib().cp_last_hip_error()})" if code == ERR_HIP else ""
+        super().__init__(f"{fn} failed: {names.get(code, code)}{extra}")
+        self.code = code
+
+
+class TableStruct(C.Structure):
+    _fields_ = [("keys", C.c_void_p), ("vals", C.c_void_p), ("capacity", C.c_uint64)]
+
+
+class KVLayout(C.Structure):
+    """``cp_kv_layout``: row (t, layer, kv) at base + t*tok_stride + layer*layer_stride + kv*kv_stride."""
+
+    _fields_ = [("n_layers", C.c_uint32), ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32),
+                ("tok_stride", C.c_uint64), ("layer_stride", C.c_uint64), ("kv_stride", C.c_uint64)]
+
+    @property
+    def row_bytes(self):
+        return self.n_kv_heads * self.head_dim * 2
+
+    @staticmethod
+    def token_major(n_layers, n_kv_heads, head_dim):
+        """[slot][layer][K|V][head][dim]: all rows of a token contiguous."""
+        rb = n_kv_heads * head_dim * 2
+        return KVLayout(n_layers, n_kv_heads, head_dim, n_layers * 2 * rb, 2 * rb, rb)
+
+    @staticmethod
+    def layer_major(n_layers, n_kv_heads, head_dim, n_tokens):
+        """[layer][K|V][token][head][dim]: per-layer K and V buffers."""
+        rb = n_kv_heads * head_dim * 2
+        return KVLayout(n_layers, n_kv_heads, head_dim, rb, 2 * n_tokens * rb, n_tokens * rb)
+
+
+class Rope(C.Structure):
+    _fields_ = [("theta", C.c_double), ("style", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libcacheprune.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with __graft_entry__.build() "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, u32, u64, i32, sz = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int32, C.c_size_t
+        L.cp_table_capacity_for.restype = u64
+        L.cp_table_capacity_for.argtypes = [u64, C.c_double]
+        L.cp_scratch_bytes.restype = sz
+        L.cp_scratch_bytes.argtypes = [u32, u32]
+        L.cp_last_hip_error.restype = i32
+        L.cp_tune.restype = i32
+        L.cp_tune.argtypes = [i32, u32]
+        L.cp_table_init.restype = i32
+        L.cp_table_init.argtypes = [vp, TableStruct]
+        L.cp_hash_segments.restype = i32
+        L.cp_hash_segments.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, sz]
+        L.cp_probe.restype = i32
+        L.cp_probe.argtypes = [vp, TableStruct, vp, u32, vp]
+        L.cp_build_spans.restype = i32
+        L.cp_build_spans.argtypes = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
+        L.cp_gather_kv.restype = i32
+        L.cp_gather_kv.argtypes = [vp, vp, KVLayout, u32, vp, KVLayout, u32, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, sz]
+        L.cp_insert_kv.restype = i32
+        L.cp_insert_kv.argtypes = [vp, TableStruct, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout, u32, vp, vp,
+                                   vp, vp, vp, sz]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise CpError(fn, rc)
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("libcacheprune takes device tensors only")
+
+
+def cp_table_capacity_for(n_keys, load_factor=0.5):
+    return int(lib().cp_table_capacity_for(int(n_keys), float(load_factor)))
+
+
+def cp_scratch_bytes(N, max_spans=0):
+    return int(lib().cp_scratch_bytes(int(N), int(max_spans)))
+
+
+def cp_tune(key, value):
+    _check("cp_tune", lib().cp_tune(int(key), int(value)))
+
+
+def new_scratch(N, max_spans, device="cuda"):
+    return torch.empty(cp_scratch_bytes(N, max_spans), dtype=torch.uint8, device=device)
+
+
+class Table:
+    """Device arrays of a ``cp_table`` (torch owns the memory)."""
+
+    def __init__(self, capacity, device="cuda", stream=None):
+        if capacity % TABLE_BUCKET:
+            raise ValueError("capacity must be a multiple of 16")
+        self.capacity = int(capacity)
+        self.keys = torch.empty(self.capacity, dtype=torch.int64, device=device)
+        self.vals = torch.empty(self.capacity, dtype=torch.int32, device=device)
+        cp_table_init(self, stream)
+
+    @property
+    def struct(self):
+        return TableStruct(self.keys.data_ptr(), self.vals.data_ptr(), self.capacity)
+
+
+def cp_table_init(table: Table, stream=None):
+    _check("cp_table_init", lib().cp_table_init(_stream(stream), table.struct))
+
+
+def cp_hash_segments(tok, mask, off, hash_out, scratch, base=BASE, stream=None):
+    """tok int32[N], mask uint8[N], off int32[R+1] -> hash_out int64[N]."""
+    _need_cuda(tok, mask, off, hash_out, scratch)
+    N, R = tok.numel(), off.numel() - 1
+    assert mask.numel() == N and hash_out.numel() == N
+    _check("cp_hash_segments", lib().cp_hash_segments(_stream(stream), _ptr(tok), _ptr(mask), _ptr(off), N, R, base,
+                                                      _ptr(hash_out), _ptr(scratch), scratch.numel()))
+    return hash_out
+
+
+def cp_probe(table: Table, hashes, slot_out, stream=None):
+    _need_cuda(hashes, slot_out)
+    N = hashes.numel()
+    assert slot_out.numel() == N
+    _check("cp_probe", lib().cp_probe(_stream(stream), table.struct, _ptr(hashes), N, _ptr(slot_out)))
+    return slot_out
+
+
+def cp_build_spans(slot, off, slot_pos, max_spans, span_src, span_dst, span_len, span_delta, span_off, n_spans,
+                   status_flags, scratch, stream=None):
+    _need_cuda(slot, off, slot_pos, span_src, span_dst, span_len, span_delta, span_off, n_spans, status_flags, scratch)
+    N, R = slot.numel(), off.numel() - 1
+    assert span_src.numel() >= max_spans and span_dst.numel() >= max_spans and span_len.numel() >= max_spans
+    assert span_delta is None or span_delta.numel() >= max_spans
+    assert span_off is None or span_off.numel() >= max_spans + 1
+    _check("cp_build_spans", lib().cp_build_spans(
+        _stream(stream), _ptr(slot), _ptr(off), N, R, _ptr(slot_pos), max_spans, _ptr(span_src), _ptr(span_dst),
+        _ptr(span_len), _ptr(span_delta), _ptr(span_off), _ptr(n_spans), _ptr(status_flags), _ptr(scratch),
+        scratch.numel()))
+
+
+def cp_gather_kv(pool, pool_l: KVLayout, n_pool_slots, dst, dst_l: KVLayout, n_dst_tokens, span_src, span_dst,
+                 span_len, span_delta, span_off, n_spans, max_spans, rope: Rope | None, status_flags, scratch,
+                 stream=None):
+    _need_cuda(pool, dst, span_src, span_dst, span_len, span_delta, span_off, n_spans, status_flags, scratch)
+    _check("cp_gather_kv", lib().cp_gather_kv(
+        _stream(stream), _ptr(pool), pool_l, n_pool_slots, _ptr(dst), dst_l, n_dst_tokens, _ptr(span_src),
+        _ptr(span_dst), _ptr(span_len), _ptr(span_delta), _ptr(span_off), _ptr(n_spans), max_spans,
+        C.byref(rope) if rope is not None else None, _ptr(status_flags), _ptr(scratch),
+        scratch.numel() if scratch is not None else 0))
+
+
+def cp_insert_kv(table: Table, hashes, off, free_slots, n_free, src, src_l: KVLayout, pool, pool_l: KVLayout,
+                 n_pool_slots, slot_pos, slot_out, n_inserted, status_flags, scratch, stream=None):
+    _need_cuda(hashes, off, free_slots, src, pool, slot_pos, slot_out, n_inserted, status_flags, scratch)
+    N, R = hashes.numel(), off.numel() - 1
+    assert slot_out.numel() == N and (free_slots is None or free_slots.numel() >= n_free)
+    _check("cp_insert_kv", lib().cp_insert_kv(
+        _stream(stream), table.struct, _ptr(hashes), _ptr(off), N, R, _ptr(free_slots), n_free, _ptr(src), src_l,
+        _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags),
+        _ptr(scratch), scratch.numel()))

@@ -1,0 +1,274 @@
+// The pool index as an open-addressing table on the GPU (Sec. 4.3.5 "Storage
+// format and indexing": cached segments are found through a hash index; here
+// one key per pooled token), its lookup (cp_probe) and the table side of
+// insertion (cp_insert_kv; Sec. 4.3.5 "Lifecycle management": one copy of a
+// duplicate).
+//
+// Layout: buckets of 16 entries.  The 16 keys of a bucket are one 128-byte
+// line, fetched by a group of 16 lanes with one coalesced load; wavefront
+// ballots find the matching or the first empty entry.  A key lives in the
+// first bucket, walking from its home bucket with wrap-around, that had a free
+// entry when it arrived.  Entries are never removed, so a bucket that was full
+// stays full and a walk may stop at the first bucket that shows a free entry.
+//
+// Values: a pool slot (< 2^31), CP_SLOT_NONE for an entry whose token could not
+// be stored (treated as absent), or, only while cp_insert_kv runs, the marker
+// kPending | i naming the lowest packed token index i that wants the entry.
+#include "cp_device.h"
+#include "cp_internal.h"
+
+namespace cp {
+namespace {
+
+constexpr uint32_t kBucket = CP_TABLE_BUCKET;
+constexpr uint32_t kPending = 0x80000000u;
+constexpr int kProbeThreads = 256;
+
+__device__ __forceinline__ uint32_t home_bucket(uint64_t h, uint32_t n_buckets) {
+  h ^= h >> 32;
+  h *= 0xD6E8FEB86659FD93ull;
+  h ^= h >> 32;
+  h *= 0xD6E8FEB86659FD93ull;
+  h ^= h >> 32;
+  return __umulhi((uint32_t)h, n_buckets);  // uniform over [0, n_buckets) for any n_buckets
+}
+
+// 16-bit slice of a wavefront ballot belonging to this lane's group of 16.
+__device__ __forceinline__ uint32_t group_bits(unsigned long long ballot) {
+  return (uint32_t)(ballot >> (threadIdx.x & 48)) & 0xFFFFu;
+}
+
+__global__ __launch_bounds__(kProbeThreads) void table_init_kernel(cp_table t) {
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < t.capacity) {
+    t.keys[i] = CP_HASH_NONE;
+    t.vals[i] = CP_SLOT_NONE;
+  }
+}
+
+// One group of 16 lanes per token.
+__global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                              uint32_t N, uint32_t *__restrict__ slot_out) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  const uint32_t n_buckets = (uint32_t)(t.capacity / kBucket);
+  uint64_t h = q < N ? hash[q] : CP_HASH_NONE;
+  bool active = h != CP_HASH_NONE;
+  uint32_t b = home_bucket(h, n_buckets), walked = 0, result = CP_SLOT_NONE;
+  while (__any(active)) {  // wavefront-uniform loop; groups drop out one by one
+    uint64_t k = CP_HASH_NONE;
+    if (active) k = t.keys[(uint64_t)b * kBucket + sub];
+    uint32_t hit = group_bits(__ballot(active && k == h));
+    uint32_t empty = group_bits(__ballot(active && k == CP_HASH_NONE));
+    if (active) {
+      if (hit) {
+        result = t.vals[(uint64_t)b * kBucket + (__ffs(hit) - 1)];
+        active = false;
+      } else if (empty || ++walked == n_buckets) {
+        active = false;
+      } else {
+        b = b + 1 == n_buckets ? 0 : b + 1;
+      }
+    }
+  }
+  if (q < N && sub == 0) slot_out[q] = result >= kPending ? CP_SLOT_NONE : result;
+}
+
+// Insert, step 1: find or claim the table entry of every token's key and leave
+// in vals[] the smallest packed index that asked for a not-yet-stored key.
+__global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                                     uint32_t N, uint32_t *__restrict__ entry_of,
+                                                                     uint32_t *status_flags) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  const uint32_t n_buckets = (uint32_t)(t.capacity / kBucket);
+  uint64_t h = q < N ? hash[q] : CP_HASH_NONE;
+  bool active = h != CP_HASH_NONE;
+  uint32_t b = home_bucket(h, n_buckets), walked = 0, entry = CP_SLOT_NONE;
+  while (__any(active)) {
+    unsigned long long *kp = (unsigned long long *)&t.keys[(uint64_t)b * kBucket + sub];
+    uint64_t k = CP_HASH_NONE;
+    // other workgroups fill entries while this kernel runs: read at device scope, past the per-CU cache
+    if (active) k = __hip_atomic_load(kp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t hit = group_bits(__ballot(active && k == h));
+    uint32_t empty = group_bits(__ballot(active && k == CP_HASH_NONE));
+    // the lane that saw the first free entry tries to take it
+    bool try_claim = active && !hit && empty && sub == (uint32_t)(__ffs(empty) - 1);
+    uint64_t old = 0;
+    if (try_claim) old = atomicCAS(kp, (unsigned long long)CP_HASH_NONE, (unsigned long long)h);
+    // success also if another group stored this very key there in the meantime
+    uint32_t claimed = group_bits(__ballot(try_claim && (old == CP_HASH_NONE || old == h)));
+    if (active) {
+      if (hit) {
+        entry = b * kBucket + (__ffs(hit) - 1);
+        active = false;
+      } else if (empty) {
+        if (claimed) {
+          entry = b * kBucket + (__ffs(empty) - 1);
+          active = false;
+        }  // else: someone else took that entry; look at the same bucket again
+      } else if (++walked == n_buckets) {
+        active = false;  // every bucket is full
+      } else {
+        b = b + 1 == n_buckets ? 0 : b + 1;
+      }
+    }
+  }
+  if (q < N && sub == 0) {
+    entry_of[q] = entry;
+    if (entry != CP_SLOT_NONE) {
+      atomicMin(&t.vals[entry], kPending | q);  // no effect on a stored slot (< kPending)
+    } else if (h != CP_HASH_NONE) {
+      atomicOr(status_flags, CP_FLAG_TABLE_FULL);
+    }
+  }
+}
+
+// Insert, step 2: ordered count of the storing tokens (the owners of new keys).
+struct OwnerRankOp {
+  using T = uint32_t;
+  const uint32_t *entry_of;
+  const uint32_t *vals;
+  uint32_t *rank;      // [N]  rank of token i among the owners, valid for owners only
+  uint32_t *owners;    // [min(N, n_free)]  owner token of rank w
+  uint32_t *n_inserted;
+  uint32_t *status_flags;
+  uint32_t N, n_free;
+
+  static __device__ __forceinline__ T identity() { return 0; }
+  static __device__ __forceinline__ T combine(T a, T b) { return a + b; }
+  __device__ __forceinline__ uint32_t count() const { return N; }
+  __device__ __forceinline__ T load(uint32_t i) const {
+    uint32_t e = entry_of[i];
+    return (e != CP_SLOT_NONE && vals[e] == (kPending | i)) ? 1u : 0u;
+  }
+  __device__ __forceinline__ void store(uint32_t i, T excl, T incl) const {
+    if (incl != excl) {
+      rank[i] = excl;
+      if (excl < n_free) owners[excl] = i;
+    }
+  }
+  __device__ __forceinline__ void finish(T total) const {
+    *n_inserted = total < n_free ? total : n_free;
+    if (total > n_free) atomicOr(status_flags, CP_FLAG_POOL_FULL);
+  }
+};
+
+// Insert, step 3: every token learns the slot that holds its key after the call.
+__global__ __launch_bounds__(256) void insert_resolve_kernel(const uint32_t *__restrict__ entry_of,
+                                                             const uint32_t *__restrict__ vals,
+                                                             const uint32_t *__restrict__ rank,
+                                                             const uint32_t *__restrict__ free_slots, uint32_t n_free,
+                                                             uint32_t n_pool_slots, uint32_t N,
+                                                             uint32_t *__restrict__ slot_out) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  uint32_t e = entry_of[i], s = CP_SLOT_NONE;
+  if (e != CP_SLOT_NONE) {
+    uint32_t v = vals[e];
+    if (v < kPending) {
+      s = v;  // stored by an earlier call
+    } else if (v != CP_SLOT_NONE) {
+      uint32_t owner = v & ~kPending;
+      uint32_t r = owner < N ? rank[owner] : n_free;  // a marker of this call always names a token < N
+      if (r < n_free) s = free_slots[r];
+      if (s >= n_pool_slots) s = CP_SLOT_NONE;  // a free-list entry outside the pool is never used
+    }
+  }
+  slot_out[i] = s;
+}
+
+// Insert, step 4: owners replace the marker by their slot (or by "absent" when
+// the free list ran out) and record the position their token had in its request.
+__global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__restrict__ entry_of, uint32_t *vals,
+                                                            const uint32_t *__restrict__ rank,
+                                                            const uint32_t *__restrict__ free_slots, uint32_t n_free,
+                                                            uint32_t n_pool_slots, const uint32_t *__restrict__ off,
+                                                            uint32_t R, uint32_t N, int32_t *__restrict__ slot_pos) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  uint32_t e = entry_of[i];
+  if (e == CP_SLOT_NONE || vals[e] != (kPending | i)) return;  // only the owner touches its entry
+  uint32_t r = rank[i], s = CP_SLOT_NONE;
+  if (r < n_free) {
+    s = free_slots[r];
+    if (s < n_pool_slots) slot_pos[s] = (int32_t)(i - off[request_of(off, R, i)]);
+    else s = CP_SLOT_NONE;  // a free-list entry outside the pool is never used
+  }
+  vals[e] = s;
+}
+
+}  // namespace
+}  // namespace cp
+
+extern "C" uint64_t cp_table_capacity_for(uint64_t n_keys, double load_factor) {
+  if (!(load_factor > 0.0) || load_factor > 1.0) load_factor = 0.5;
+  double want = (double)n_keys / load_factor;
+  uint64_t c = (uint64_t)want;
+  if ((double)c < want) ++c;
+  if (c < n_keys + 1) c = n_keys + 1;  // at least one entry stays free
+  return (c + CP_TABLE_BUCKET - 1) / CP_TABLE_BUCKET * CP_TABLE_BUCKET;
+}
+
+static int32_t table_ok(const cp_table &t) {
+  if (!t.keys || !t.vals || t.capacity == 0) return CP_ERR_INVALID_ARG;
+  if (t.capacity % CP_TABLE_BUCKET || !cp::aligned(t.keys, 128) || !cp::aligned(t.vals, 64)) return CP_ERR_INVALID_ARG;
+  if (t.capacity >= 0x100000000ull) return CP_ERR_UNSUPPORTED;
+  return CP_OK;
+}
+
+extern "C" int32_t cp_table_init(void *stream, cp_table table) {
+  using namespace cp;
+  if (int32_t rc = table_ok(table)) return rc;
+  table_init_kernel<<<div_up(table.capacity, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(table);
+  return check_launch();
+}
+
+extern "C" int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out) {
+  using namespace cp;
+  if (N == 0) return CP_OK;
+  if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (int32_t rc = table_ok(table)) return rc;
+  if (!hash || !slot_out || !aligned(hash, 8) || !aligned(slot_out, 4)) return CP_ERR_INVALID_ARG;
+  probe_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(table, hash, N,
+                                                                                                          slot_out);
+  return check_launch();
+}
+
+extern "C" int32_t cp_insert_kv(void *stream_, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
+                                uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
+                                cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
+                                int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
+                                void *scratch, size_t scratch_bytes) {
+  using namespace cp;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (N >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (int32_t rc = table_ok(table)) return rc;
+  if (!n_inserted || !status_flags || !scratch || !aligned(scratch, 256)) return CP_ERR_INVALID_ARG;
+  if (N && (!hash || !off || R == 0 || !slot_out || !slot_pos || !src || !pool)) return CP_ERR_INVALID_ARG;
+  if (n_free && !free_slots) return CP_ERR_INVALID_ARG;
+  if (!aligned(hash, 8) || !aligned(src, 16) || !aligned(pool, 16)) return CP_ERR_INVALID_ARG;
+  if (!layout_ok(src_l) || !layout_ok(pool_l) || !layouts_match(src_l, pool_l)) return CP_ERR_UNSUPPORTED;
+  if (scratch_bytes < cp_scratch_bytes(N, 0)) return CP_ERR_SCRATCH;
+  Scratch sc(scratch, scratch_bytes);
+  uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
+  uint32_t *entry_of = sc.take<uint32_t>(N);
+  uint32_t *rank = sc.take<uint32_t>(N);
+  uint32_t *owners = sc.take<uint32_t>(N);
+  if (!agg || !entry_of || !rank || !owners) return CP_ERR_SCRATCH;
+  const uint32_t blocks = div_up(N, 256);
+  if (N)
+    insert_claim_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
+        table, hash, N, entry_of, status_flags);
+  OwnerRankOp op{entry_of, table.vals, rank, owners, n_inserted, status_flags, N, n_free};
+  if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, agg)) return rc;
+  if (N == 0) return CP_OK;
+  insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, N,
+                                                    slot_out);
+  insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, off, R,
+                                                   N, slot_pos);
+  if (int32_t rc = check_launch()) return rc;
+  uint32_t max_items = N < n_free ? N : n_free;
+  return launch_scatter(stream, src, src_l, N, pool, pool_l, n_pool_slots, owners, free_slots, n_inserted, max_items,
+                        status_flags);
+}

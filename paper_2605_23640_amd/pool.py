@@ -1,0 +1,109 @@
+"""A token-granular KV pool on one GPU: device memory (torch) plus the call
+sequences of the two paths through libcacheprune.
+
+    lookup :  cp_hash_segments -> cp_probe -> cp_build_spans -> cp_gather_kv
+    insert :  cp_hash_segments -> cp_insert_kv
+
+Nothing here computes: tensors are allocated and handed to the C ABI.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class LookupResult:
+    hash: torch.Tensor  # int64[N]
+    slot: torch.Tensor  # int32[N]
+    span_src: torch.Tensor  # int32[max_spans]
+    span_dst: torch.Tensor
+    span_len: torch.Tensor
+    span_delta: torch.Tensor
+    span_off: torch.Tensor  # int32[max_spans + 1]
+    n_spans: torch.Tensor  # int32[1], device
+
+
+class LookupBuffers:
+    """Reusable per-batch device arrays for the lookup path (N tokens, up to max_spans spans)."""
+
+    def __init__(self, N, max_spans=None, device="cuda"):
+        self.N = N
+        self.max_spans = N if max_spans is None else max_spans
+        i32, i64 = torch.int32, torch.int64
+        self.hash = torch.empty(N, dtype=i64, device=device)
+        self.slot = torch.empty(N, dtype=i32, device=device)
+        m = max(1, self.max_spans)
+        self.span_src = torch.empty(m, dtype=i32, device=device)
+        self.span_dst = torch.empty(m, dtype=i32, device=device)
+        self.span_len = torch.empty(m, dtype=i32, device=device)
+        self.span_delta = torch.empty(m, dtype=i32, device=device)
+        self.span_off = torch.empty(m + 1, dtype=i32, device=device)
+        self.n_spans = torch.zeros(1, dtype=i32, device=device)
+        self.scratch = B.new_scratch(max(N, 1), self.max_spans, device)
+
+
+class KVPool:
+    """Pool of ``n_slots`` token slots (token-major rows), its hash table, the
+    cached position of every slot and the free list (hand-out order)."""
+
+    def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
+                 device="cuda", pool_tensor=None):
+        self.device = device
+        self.n_slots = int(n_slots)
+        self.layout = B.KVLayout.token_major(n_layers, n_kv_heads, head_dim)
+        self.shape = (n_layers, n_kv_heads, head_dim)
+        if pool_tensor is None:
+            pool_tensor = torch.empty(self.n_slots * self.layout.tok_stride, dtype=torch.uint8, device=device)
+        self.pool = pool_tensor
+        self.table = B.Table((int(table_capacity) + B.TABLE_BUCKET - 1) // B.TABLE_BUCKET * B.TABLE_BUCKET, device)
+        self.slot_pos = torch.zeros(self.n_slots, dtype=torch.int32, device=device)
+        self.free_slots = free_slots.to(device=device, dtype=torch.int32).contiguous()
+        self.n_used = 0  # free-list entries handed out so far (host copy)
+        self.flags = torch.zeros(1, dtype=torch.int32, device=device)
+        self.n_inserted = torch.zeros(1, dtype=torch.int32, device=device)
+        self.rope = rope  # binding.Rope or None
+
+    def request_layout(self, n_tokens):
+        L, H, D = self.shape
+        return B.KVLayout.layer_major(L, H, D, n_tokens)
+
+    def hash(self, tok, mask, off, out, scratch, stream=None):
+        return B.cp_hash_segments(tok, mask, off, out, scratch, stream=stream)
+
+    def lookup(self, tok, mask, off, dst, buf: LookupBuffers, gather=True, stream=None) -> LookupResult:
+        """Serve a request batch: after the call the rows of every matched token of
+        ``dst`` (layer-major, N tokens) hold the pooled KV.  No host synchronisation."""
+        N = tok.numel()
+        B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
+        B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
+        B.cp_build_spans(buf.slot, off, self.slot_pos if self.rope is not None else None, buf.max_spans, buf.span_src,
+                         buf.span_dst, buf.span_len, buf.span_delta, buf.span_off, buf.n_spans, self.flags,
+                         buf.scratch, stream=stream)
+        if gather:
+            B.cp_gather_kv(self.pool, self.layout, self.n_slots, dst, self.request_layout(N), N, buf.span_src,
+                           buf.span_dst, buf.span_len, buf.span_delta if self.rope is not None else None,
+                           buf.span_off, buf.n_spans, buf.max_spans, self.rope, self.flags, buf.scratch,
+                           stream=stream)
+        return LookupResult(buf.hash, buf.slot, buf.span_src, buf.span_dst, buf.span_len, buf.span_delta,
+                            buf.span_off, buf.n_spans)
+
+    def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None):
+        """Store the non-sensitive tokens of a batch that the pool does not hold yet,
+        taking their KV rows from ``src`` (layer-major, N tokens).  With ``sync`` the
+        host free-list cursor is advanced (one device-to-host read)."""
+        N = tok.numel()
+        if not hashes_ready:
+            B.cp_hash_segments(tok, mask, off, hash_buf, scratch, stream=stream)
+        n_free = self.free_slots.numel() - self.n_used
+        B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src, self.request_layout(N),
+                       self.pool, self.layout, self.n_slots, self.slot_pos, slot_out, self.n_inserted, self.flags,
+                       scratch, stream=stream)
+        if sync:
+            n = int(self.n_inserted.item())
+            self.n_used += n
+            return n
+        return None

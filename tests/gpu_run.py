@@ -1,0 +1,141 @@
+"""Runs a synthetic workload through libcacheprune on cuda:0 (test helper).
+
+Mirrors ``oracle/harness.py`` step for step, but every step is a call through
+the C ABI binding; KV inputs are written on the device by the generator's fill
+kernel with the same (seed, uid) as the host generator."""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+import paper_2605_23640_amd as cp
+from cp_workload import kvgen
+
+DEV = "cuda:0"
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int32) if a.dtype == np.uint32 else
+                            np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def host_u32(t):
+    return t.detach().cpu().numpy().view(np.uint32)
+
+
+def host_u64(t):
+    return t.detach().cpu().numpy().view(np.uint64)
+
+
+def gen_layout(l: cp.binding.KVLayout) -> kvgen.GenLayout:
+    return kvgen.GenLayout(l.n_layers, l.n_kv_heads * l.head_dim, l.tok_stride, l.layer_stride, l.kv_stride)
+
+
+def poison_tensor(n_bytes):
+    t = torch.empty(n_bytes // 2, dtype=torch.int16, device=DEV)
+    t.fill_(int(np.array([kvgen.POISON16], np.uint16).view(np.int16)[0]))
+    return t.view(torch.uint8)
+
+
+def stream_ptr():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+@dataclass
+class GpuState:
+    wl: object
+    pool: cp.KVPool
+    donor_hash: np.ndarray
+    donor_slot: np.ndarray
+    n_inserted: list
+    flags: int
+
+
+def make_pool(wl, free_slots=None, n_free=None) -> cp.KVPool:
+    sh = wl.shape
+    rope = cp.binding.Rope(wl.rope_theta, wl.rope_style) if wl.rope_theta is not None else None
+    fs = wl.free_slots if free_slots is None else free_slots
+    if n_free is not None:
+        fs = fs[:n_free]
+    pool = cp.KVPool(sh.n_layers, sh.n_kv_heads, sh.head_dim, wl.pool_slots, wl.table_capacity,
+                     torch.from_numpy(fs.view(np.int32)), rope=rope, device=DEV,
+                     pool_tensor=poison_tensor(wl.pool_slots * sh.tok_bytes))
+    pool.slot_pos.fill_(np.iinfo(np.int32).min)
+    return pool
+
+
+def prefill(wl, pool: cp.KVPool = None) -> GpuState:
+    """Insert the donor prompts batch by batch; donor token with packed index u has uid u."""
+    sh = wl.shape
+    pool = pool or make_pool(wl)
+    donor_hash = np.empty(len(wl.donor_tok), np.uint64)
+    donor_slot = np.empty(len(wl.donor_tok), np.uint32)
+    counts = []
+    for first, last in wl.donor_batches:
+        t0, t1 = int(wl.donor_off[first]), int(wl.donor_off[last])
+        n = t1 - t0
+        src = torch.empty(max(1, n) * sh.tok_bytes, dtype=torch.uint8, device=DEV)
+        lay = pool.request_layout(n)
+        kvgen.fill(stream_ptr(), C.c_void_p(src.data_ptr()), gen_layout(lay), n, wl.seed, uid_base=t0)
+        tok, mask = dev_i32(wl.donor_tok[t0:t1]), torch.from_numpy(wl.donor_mask[t0:t1].copy()).to(DEV)
+        off = dev_i32((wl.donor_off[first:last + 1] - wl.donor_off[first]).astype(np.uint32))
+        hbuf = torch.empty(n, dtype=torch.int64, device=DEV)
+        sout = torch.empty(n, dtype=torch.int32, device=DEV)
+        scratch = cp.binding.new_scratch(max(1, n), 0, DEV)
+        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch))
+        donor_hash[t0:t1] = host_u64(hbuf)
+        donor_slot[t0:t1] = host_u32(sout)
+        del src
+    return GpuState(wl, pool, donor_hash, donor_slot, counts, int(pool.flags.item()))
+
+
+@dataclass
+class GpuLookup:
+    hash: np.ndarray
+    slot: np.ndarray
+    span_src: np.ndarray
+    span_dst: np.ndarray
+    span_len: np.ndarray
+    span_delta: np.ndarray
+    span_off: np.ndarray
+    n_spans: int
+    flags: int
+    dst: torch.Tensor  # uint8 device tensor, layer-major [L][2][N][row_bytes]
+
+
+def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=True) -> GpuLookup:
+    wl, sh = st.wl, st.wl.shape
+    tok = wl.tok if tok is None else tok
+    mask = wl.mask if mask is None else mask
+    off = wl.off if off is None else off
+    N = len(tok)
+    buf = cp.LookupBuffers(N, max_spans, DEV)
+    dst = poison_tensor(max(1, N) * sh.tok_bytes)
+    st.pool.flags.zero_()
+    st.pool.lookup(dev_i32(tok), torch.from_numpy(np.ascontiguousarray(mask)).to(DEV), dev_i32(off), dst, buf,
+                   gather=gather)
+    torch.cuda.synchronize()
+    n = int(buf.n_spans.item())
+    return GpuLookup(host_u64(buf.hash), host_u32(buf.slot), host_u32(buf.span_src)[:n], host_u32(buf.span_dst)[:n],
+                     host_u32(buf.span_len)[:n], buf.span_delta.cpu().numpy()[:n], host_u32(buf.span_off)[:n + 1], n,
+                     int(st.pool.flags.item()), dst)
+
+
+def dst_as_rows(dst, sh, N):
+    """Device dst buffer -> host uint16[L][2][N][row_elems]."""
+    return dst.view(torch.int16).cpu().numpy().view(np.uint16).reshape(sh.n_layers, 2, N, sh.row_bytes // 2)
+
+
+def verify_rows(buf, layout, uids, seed, skip_k=None):
+    """Count elements of a device buffer that differ from the generator's rows for the given uids
+    (UID_NONE = poison expected)."""
+    n = len(uids)
+    u = torch.from_numpy(np.ascontiguousarray(uids, dtype=np.uint64).view(np.int64)).to(DEV)
+    sk = None if skip_k is None else torch.from_numpy(np.ascontiguousarray(skip_k, dtype=np.uint8)).to(DEV)
+    bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    kvgen.verify(stream_ptr(), C.c_void_p(buf.data_ptr()), gen_layout(layout), C.c_void_p(u.data_ptr()), n, seed,
+                 C.c_void_p(bad.data_ptr()), None if sk is None else C.c_void_p(sk.data_ptr()))
+    return int(bad.item())

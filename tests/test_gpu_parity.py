@@ -1,0 +1,222 @@
+"""Parity of libcacheprune (HIP, through the C ABI) against the CPU oracle on the
+same seeded inputs: hashes, slots, spans, inserted slots and copied rows bit for
+bit; re-rotated keys within one bf16 step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from cp_workload import gen, kvgen
+from oracle import harness as OH
+
+pytestmark = pytest.mark.gpu
+
+NONE = O.SLOT_NONE
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a ROCm device; there is no fallback path")
+    from tests import gpu_run
+
+    return gpu_run
+
+
+def bf16_ordinal(bits):
+    """Map bf16 bit patterns to integers that are consecutive for adjacent values."""
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+
+def compare_all(G, wl, max_ulp_sample=None):
+    """Run prefill + lookup on both sides and compare everything."""
+    fl = []
+    ost = OH.prefill(wl, flags_out=fl)
+    olk = OH.lookup(ost)
+    gst = G.prefill(wl)
+    glk = G.lookup(gst)
+    N = wl.n_tokens
+    assert np.array_equal(gst.donor_hash, ost.donor_hash)
+    assert np.array_equal(gst.donor_slot, ost.donor_slot)
+    assert sum(gst.n_inserted) == ost.n_used and gst.flags == fl[0]
+    assert np.array_equal(G.host_u32(gst.pool.slot_pos.view(torch.int32))[ost.slot_uid != kvgen.UID_NONE].view(np.int32),
+                          ost.slot_pos[ost.slot_uid != kvgen.UID_NONE])
+    # the pool itself: every stored slot holds its donor token's rows, every other slot is untouched
+    assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0
+    assert np.array_equal(glk.hash, olk.hash)
+    assert np.array_equal(glk.slot, olk.slot)
+    assert glk.n_spans == olk.n_spans and glk.flags == olk.flags
+    for f in ("span_src", "span_dst", "span_len"):
+        assert np.array_equal(getattr(glk, f), getattr(olk, f)), f
+    if wl.rope_theta is not None:
+        assert np.array_equal(glk.span_delta, olk.span_delta)
+    assert np.array_equal(glk.span_off, np.concatenate([[0], np.cumsum(olk.span_len)]).astype(np.uint32))
+    got = G.dst_as_rows(glk.dst, wl.shape, N)
+    if wl.rope_theta is None:
+        assert np.array_equal(got, olk.dst)
+    else:
+        assert np.array_equal(got[:, 1], olk.dst[:, 1])  # V rows: bit exact
+        d = np.abs(bf16_ordinal(got[:, 0]) - bf16_ordinal(olk.dst[:, 0]))
+        hist = np.bincount(np.minimum(d, 2).ravel(), minlength=3)
+        print("bf16 ordinal distance of re-rotated keys {0,1,>1}:", hist.tolist())
+        assert hist[2] == 0  # within one bf16 step of the double-precision result, every element
+        assert hist[1] <= 1e-3 * hist.sum()
+    return ost, olk, gst, glk
+
+
+def test_tiny_config(G):
+    wl = gen.make("tiny")
+    ost, olk, gst, glk = compare_all(G, wl)
+    assert glk.n_spans > 100 and (glk.slot != NONE).mean() > 0.5
+
+
+def test_llama8b_shape_small(G):
+    # true row shape (32 layers x 8 heads x 128), a few thousand tokens: several scan tiles + ragged tail
+    wl = gen.make_docs("llama3-8b-small", 0xC0FFEE02, gen.KVShape(32, 8, 128), R=3, T=1371, prefix_len=300, n_docs=6,
+                       doc_len=(150, 300), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096)
+    compare_all(G, wl)
+
+
+def test_llama70b_shape_small(G):
+    wl = gen.make_docs("llama3-70b-small", 0xC0FFEE05, gen.KVShape(80, 8, 128), R=2, T=700, prefix_len=200, n_docs=5,
+                       doc_len=(60, 120), docs_per_request=4, run_mean=12.0, cover=0.10, pool_slots=1024,
+                       donor_batch_tokens=700)
+    assert len(wl.donor_batches) > 1
+    compare_all(G, wl)
+
+
+def test_frag_small_high_load(G):
+    wl = gen.make_frag(scale=1 / 32, shape=gen.KVShape(4, 8, 128))
+    assert abs(wl.pool_slots / wl.table_capacity - 0.85) < 0.01
+    ost, olk, gst, glk = compare_all(G, wl)
+    assert gst.pool.n_used == wl.pool_slots  # the pool is exactly full
+
+
+@pytest.mark.parametrize("style", [0, 1])
+def test_rope_small(G, style):
+    wl = gen.make_rope(scale=1 / 16, shape=gen.KVShape(3, 8, 128))
+    wl.rope_style = style
+    ost, olk, gst, glk = compare_all(G, wl)
+    assert (glk.span_delta != 0).mean() > 0.8
+
+
+def test_rope_small_head_dim_64_and_large_shifts(G):
+    wl = gen.make_rope(scale=1 / 16, shape=gen.KVShape(1, 2, 64), max_shift=2048 * 16)
+    ost, olk, gst, glk = compare_all(G, wl)
+    assert np.abs(glk.span_delta).max() > 1000
+
+
+def test_contiguous_slots_give_long_spans(G):
+    wl = gen.make_docs("contig", 7, gen.KVShape(4, 2, 64), R=4, T=1500, prefix_len=400, n_docs=5, doc_len=(200, 400),
+                       docs_per_request=3, run_mean=8.0, cover=0.10, pool_slots=4096)
+    wl.free_slots = np.arange(wl.pool_slots, dtype=np.uint32)  # slots handed out in order
+    ost, olk, gst, glk = compare_all(G, wl)
+    assert glk.span_len.max() >= 100 and glk.n_spans < (glk.slot != NONE).sum() / 4
+
+
+def test_edge_cases_lookup(G):
+    wl = gen.make("tiny")
+    ost = OH.prefill(wl)
+    gst = G.prefill(wl)
+    cases = {
+        "empty batch": (np.zeros(0, np.uint32), np.zeros(0, np.uint8), np.array([0], np.uint32)),
+        "empty requests": (wl.tok[:5], wl.mask[:5], np.array([0, 0, 5, 5], np.uint32)),
+        "single token": (wl.donor_tok[6:7], np.zeros(1, np.uint8), np.array([0, 1], np.uint32)),
+        "all sensitive": (wl.tok[:100], np.ones(100, np.uint8), np.array([0, 50, 100], np.uint32)),
+        "one-token requests": (wl.tok[:64], wl.mask[:64], np.arange(65, dtype=np.uint32)),
+        "donor replay": (wl.donor_tok[:1500], wl.donor_mask[:1500], np.array([0, 512, 1024, 1500], np.uint32)),
+    }
+    for name, (tok, mask, off) in cases.items():
+        o = OH.lookup(ost, tok=tok, mask=mask, off=off)
+        g = G.lookup(gst, tok=tok, mask=mask, off=off)
+        assert np.array_equal(g.hash, o.hash) and np.array_equal(g.slot, o.slot), name
+        assert g.n_spans == o.n_spans and np.array_equal(g.span_src, o.span_src), name
+        assert np.array_equal(g.span_dst, o.span_dst) and np.array_equal(g.span_len, o.span_len), name
+        if len(tok):
+            assert np.array_equal(G.dst_as_rows(g.dst, wl.shape, len(tok)), o.dst), name
+    # span capacity: only the first max_spans spans are kept, gathered, and the overflow is flagged
+    o = OH.lookup(ost, max_spans=37)
+    g = G.lookup(gst, max_spans=37)
+    assert o.flags == g.flags == O.FLAG_SPANS_OVERFLOW and g.n_spans == 37 and o.n_spans > 37
+    assert np.array_equal(g.span_src, o.span_src) and np.array_equal(g.span_len, o.span_len)
+    assert np.array_equal(G.dst_as_rows(g.dst, wl.shape, wl.n_tokens), o.dst)
+
+
+def test_pool_full_and_repeat_insert(G):
+    wl = gen.make("tiny")
+    n_free = 700  # fewer slots than the donors need
+    fl = []
+    wl2 = gen.make("tiny")
+    wl2.free_slots = wl.free_slots[:n_free]
+    ost = OH.prefill(wl2, flags_out=fl)
+    gst = G.prefill(wl, G.make_pool(wl, n_free=n_free))
+    assert fl[0] == O.FLAG_POOL_FULL == gst.flags and ost.n_used == n_free == sum(gst.n_inserted)
+    assert np.array_equal(gst.donor_slot, ost.donor_slot)
+    assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0
+    o, g = OH.lookup(ost), G.lookup(gst)
+    assert np.array_equal(g.slot, o.slot) and np.array_equal(G.dst_as_rows(g.dst, wl.shape, wl.n_tokens), o.dst)
+    # inserting everything again stores nothing and reports the same slots
+    gst2 = G.prefill(wl, gst.pool)
+    assert sum(gst2.n_inserted) == 0 and np.array_equal(gst2.donor_slot, ost.donor_slot)
+
+
+def test_insert_is_deterministic(G):
+    wl = gen.make_frag(scale=1 / 64, shape=gen.KVShape(1, 1, 8))
+    ref = OH.prefill(wl).donor_slot
+    for _ in range(10):
+        assert np.array_equal(G.prefill(wl).donor_slot, ref)
+
+
+def test_layer_major_pool_gather(G):
+    """The gather takes any strides: same spans out of a layer-major pool."""
+    import ctypes as C
+
+    import paper_2605_23640_amd as cp
+
+    rng = np.random.default_rng(3)
+    L, H, D, S, N = 3, 2, 64, 300, 200
+    rb = H * D * 2
+    pool = rng.integers(0, 65536, (L, 2, S, H * D)).astype(np.uint16)
+    src = np.array([10, 250, 40], np.uint32)
+    dst = np.array([0, 50, 199], np.uint32)
+    ln = np.array([30, 50, 1], np.uint32)
+    want = np.full((L, 2, N, H * D), kvgen.POISON16, np.uint16)
+    O.gather_kv(pool, O.Layout(L, H, D, rb, 2 * S * rb, S * rb), want, O.Layout(L, H, D, rb, 2 * N * rb, N * rb), src,
+                dst, ln)
+    dpool = torch.from_numpy(pool.view(np.int16)).to(G.DEV)
+    out = G.poison_tensor(N * L * 2 * rb)
+    flags = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    n_sp = torch.tensor([3], dtype=torch.int32, device=G.DEV)
+    scratch = cp.binding.new_scratch(N, 8, G.DEV)
+    cp.cp_gather_kv(dpool, cp.binding.KVLayout.layer_major(L, H, D, S), S, out, cp.binding.KVLayout.layer_major(L, H, D, N),
+                    N, G.dev_i32(src), G.dev_i32(dst), G.dev_i32(ln), None, None, n_sp, 8, None, flags, scratch)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.dst_as_rows(out, gen.KVShape(L, H, D), N), want) and int(flags.item()) == 0
+    # a span that points outside the pool is skipped and flagged, nothing else is disturbed
+    out2 = G.poison_tensor(N * L * 2 * rb)
+    bad_src = np.array([10, 290, 40], np.uint32)  # 290 + 50 > 300 slots
+    cp.cp_gather_kv(dpool, cp.binding.KVLayout.layer_major(L, H, D, S), S, out2,
+                    cp.binding.KVLayout.layer_major(L, H, D, N), N, G.dev_i32(bad_src), G.dev_i32(dst), G.dev_i32(ln),
+                    None, None, n_sp, 8, None, flags, scratch)
+    torch.cuda.synchronize()
+    assert int(flags.item()) == cp.binding.FLAG_BAD_INDEX
+    got = G.dst_as_rows(out2, gen.KVShape(L, H, D), N)
+    assert np.array_equal(got[:, :, :50], want[:, :, :50]) and np.array_equal(got[:, :, 199], want[:, :, 199])
+    assert np.array_equal(got[:, :, 50:60], pool[:, :, 290:300]) and (got[:, :, 60:100] == kvgen.POISON16).all()
+
+
+def test_argument_errors_are_reported_not_launched(G):
+    import paper_2605_23640_amd as cp
+
+    t = torch.zeros(64, dtype=torch.int32, device=G.DEV)
+    h = torch.zeros(64, dtype=torch.int64, device=G.DEV)
+    small = torch.zeros(256, dtype=torch.uint8, device=G.DEV)
+    with pytest.raises(cp.binding.CpError) as e:
+        cp.cp_hash_segments(t, t.view(torch.uint8)[:64], t[:2], h, small[:16])
+    assert e.value.code == cp.binding.ERR_SCRATCH
+    tab = cp.binding.Table(64, G.DEV)
+    tab.capacity = 40  # not a multiple of the bucket size
+    with pytest.raises(cp.binding.CpError) as e:
+        cp.cp_probe(tab, h, t)
+    assert e.value.code == cp.binding.ERR_INVALID_ARG

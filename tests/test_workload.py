@@ -1,0 +1,51 @@
+"""Input generators: determinism, stated structure of the five workloads, and
+agreement of the two host forms of the KV value generator."""
+import numpy as np
+
+from cp_workload import gen, kvgen
+
+
+def test_kvgen_vectorised_equals_rowwise_and_looks_normal():
+    uids = np.array([0, 1, 7, 123456789, kvgen.UID_NONE], np.uint64)
+    rows = kvgen.rows_for_tokens(42, uids, 3, 64)
+    for t, u in enumerate(uids):
+        for l in range(3):
+            for kv in range(2):
+                assert np.array_equal(rows[t, l, kv], kvgen.row(42, int(u), l, kv, 3, 64))
+    assert (rows[4] == kvgen.POISON16).all()
+    big = kvgen.rows_for_tokens(1, np.arange(64), 4, 256)
+    x = (big.astype(np.uint32) << 16).view(np.float32)
+    assert abs(x.mean()) < 0.02 and abs(x.std() - 1.0) < 0.02 and np.abs(x).max() < 3.6
+    assert len(np.unique(big)) > 500  # values differ across tokens, layers, K/V and elements
+    assert not np.array_equal(big[0, 0, 0], big[0, 0, 1]) and not np.array_equal(big[0, 0, 0], big[1, 0, 0])
+
+
+def test_workloads_are_deterministic_and_well_formed():
+    for name, kw in [("tiny", {}), ("llama3-8b", {"scale": 1 / 16}), ("frag", {"scale": 1 / 32}),
+                     ("rope", {"scale": 1 / 16}), ("llama3-70b", {"scale": 1 / 32})]:
+        a, b = gen.make(name, **kw), gen.make(name, **kw)
+        for f in ("tok", "mask", "off", "donor_tok", "donor_mask", "donor_off", "free_slots"):
+            assert np.array_equal(getattr(a, f), getattr(b, f)), (name, f)
+        assert a.off[0] == 0 and a.off[-1] == len(a.tok) == len(a.mask) and (np.diff(a.off.astype(np.int64)) >= 0).all()
+        assert a.donor_off[-1] == len(a.donor_tok) and a.tok.max() < gen.VOCAB
+        assert sorted(a.free_slots.tolist()) == list(range(a.pool_slots))  # a permutation of the slots
+        assert a.donor_batches[0][0] == 0 and a.donor_batches[-1][1] == len(a.donor_off) - 1
+        assert all(x[1] == y[0] for x, y in zip(a.donor_batches, a.donor_batches[1:]))
+
+
+def test_full_size_shapes_match_the_stated_configurations():
+    t = gen.make("tiny")
+    assert (t.n_requests, t.n_tokens, t.pool_slots, t.shape.tok_bytes) == (1, 512, 4096, 1024)
+    assert len(t.donor_off) - 1 == 8 and 0.12 < t.mask.mean() < 0.28
+    a = gen.make("llama3-8b")
+    assert (a.n_requests, a.n_tokens, a.pool_slots, a.shape.tok_bytes) == (16, 65536, 262144, 128 * 1024)
+    assert (a.mask[:1024] == 0).all() and 0.09 < a.mask.mean() < 0.15  # 15 % of the non-system tokens
+    f = gen.make("frag")
+    assert (f.n_requests, f.n_tokens, f.pool_slots) == (64, 131072, 131072)
+    assert abs(f.mask.mean() - 0.40) < 0.02 and abs(f.pool_slots / f.table_capacity - 0.85) < 1e-3
+    r = gen.make("rope")
+    assert (r.n_requests, r.n_tokens, r.rope_theta) == (16, 131072, 500000.0)
+    assert all(abs(s) <= 512 for sh in r.notes["shifts"] for s in sh)
+    b = gen.make("llama3-70b")
+    assert (b.n_requests, b.n_tokens, b.pool_slots, b.shape.tok_bytes) == (4, 131072, 393216, 320 * 1024)
+    assert b.pool_slots * b.shape.tok_bytes == 120 * 2**30 and 0.06 < b.mask.mean() < 0.11
