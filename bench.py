@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the CachePrune KV sharing path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama3-8b]
+
+One *step* is one pass of the whole hot path over one request batch of the
+workload, all inputs resident in HBM:
+
+    lookup : cp_hash_segments -> cp_probe -> cp_build_spans -> cp_gather_kv
+    insert : cp_insert_kv of the same batch (hashes from the lookup), taking the
+             KV rows of the tokens the pool does not hold yet from the request
+             buffers
+    reset  : the table's key/value arrays are copied back from a snapshot
+             (device to device, a few MiB) so that every step meets the same
+             pool state; this copy is inside the timed region.
+
+Prints ONE JSON line.  `value` is the KV bytes moved per second by the whole
+step (gather and insert, read + write); `roofline` prices the gather kernel
+alone against the HBM peak; `cpu_baseline` is the CPU oracle timed on this
+host on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
+# HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/), per workload; None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(wl, n_requests, G, torch, np):
+    """The CPU oracle, as it stands, on the first ``n_requests`` requests of the workload."""
+    import oracle as O
+    from cp_workload import gen
+    from oracle import harness as OH
+
+    sw = gen.subsample(wl, n_requests, pool_slots=1 << 15)
+    sh = sw.shape
+    n_d = len(sw.donor_tok)
+    re = sh.row_bytes // 2
+    # donor KV: written by the generator's device kernel, then copied to the host
+    dev = torch.empty(n_d * sh.tok_bytes, dtype=torch.uint8, device=G.DEV)
+    lay = G.cp.binding.KVLayout.layer_major(sh.n_layers, sh.n_kv_heads, sh.head_dim, n_d)
+    from cp_workload import kvgen
+    kvgen.fill(G.stream_ptr(), C.c_void_p(dev.data_ptr()), G.gen_layout(lay), n_d, sw.seed, uid_base=0)
+    torch.cuda.synchronize()
+    host_src = dev.view(torch.int16).cpu().numpy().view(np.uint16).reshape(sh.n_layers, 2, n_d, re)
+    del dev
+    pool = np.empty((sw.pool_slots, sh.n_layers, 2, re), np.uint16)  # untouched pages stay virtual
+    st = OH.prefill(sw, src_provider=lambda t0, n: np.ascontiguousarray(host_src[:, :, t0:t0 + n]), pool=pool)
+    del host_src
+    lk = OH.lookup(st)  # hash, probe, spans, gather: timed inside
+    N = sw.n_tokens
+    slot_pos = st.slot_pos
+    t = time.perf_counter()
+    slot_out, n_new, _ = O.insert_kv(st.index, lk.hash, sw.off, sw.free_slots[st.n_used:], lk.dst, OH.buf_layout(sh, N),
+                                     st.pool, OH.pool_layout(sh), slot_pos)
+    t_ins = time.perf_counter() - t
+    matched = int((lk.slot != O.SLOT_NONE).sum())
+    t_total = sum(lk.times.values()) + t_ins
+    moved = 2.0 * sh.tok_bytes * (matched + n_new)
+    return {
+        "value": moved / t_total / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {n_requests} of {wl.n_requests} requests ({N} tokens, {matched} reused, {n_new} stored), "
+                  f"same step (lookup + insert), pool of {sw.pool_slots} slots with the donors those requests use",
+        "reused_tokens_per_s": matched / t_total,
+        "seconds": {**{k: round(v, 4) for k, v in lk.times.items()}, "insert": round(t_ins, 4)},
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3-8b", choices=["tiny", "llama3-8b", "frag", "rope", "llama3-70b"])
+    ap.add_argument("--cpu-requests", type=int, default=4, help="requests in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--rows-per-item", type=int, default=None)
+    ap.add_argument("--blocks-per-cu", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    if not torch.cuda.is_available():
+        raise RuntimeError("bench.py needs a GPU: the HIP path has no fallback")
+    import paper_2605_23640_amd as cp
+    from cp_workload import gen
+    from paper_2605_23640_amd import harness as G
+
+    if args.rows_per_item is not None:
+        cp.cp_tune(0, args.rows_per_item)
+    if args.blocks_per_cu is not None:
+        cp.cp_tune(1, args.blocks_per_cu)
+    if args.nontemporal is not None:
+        cp.cp_tune(2, args.nontemporal)
+
+    t0 = time.time()
+    wl = gen.make(args.workload)
+    sh = wl.shape
+    N = wl.n_tokens
+    log(f"[bench] workload {wl.name}: {wl.n_requests} requests, {N} tokens, {sh.tok_bytes // 1024} KiB/token, "
+        f"pool {wl.pool_slots} slots = {wl.pool_slots * sh.tok_bytes / 2**30:.1f} GiB")
+    gst = G.prefill(wl)
+    pool = gst.pool
+    log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
+
+    tok, mask, off = G.dev_i32(wl.tok), torch.from_numpy(wl.mask.copy()).to(G.DEV), G.dev_i32(wl.off)
+    buf = cp.LookupBuffers(N, N, G.DEV)
+    dst = G.poison_tensor(N * sh.tok_bytes)
+    slot_out = torch.empty(N, dtype=torch.int32, device=G.DEV)
+    ins_scratch = cp.binding.new_scratch(N, 0, G.DEV)
+    keys0, vals0 = pool.table.keys.clone(), pool.table.vals.clone()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    ev_ins = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+
+    def step(k=None):
+        pool.lookup(tok, mask, off, dst, buf, gather_events=None if k is None else ev[k])
+        if k is not None:
+            ev_ins[k][0].record()
+        pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False)
+        if k is not None:
+            ev_ins[k][1].record()
+        pool.table.keys.copy_(keys0, non_blocking=True)
+        pool.table.vals.copy_(vals0, non_blocking=True)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        step(k)
+    torch.cuda.synchronize()
+    t_total = time.perf_counter() - t_start
+
+    n_spans = int(buf.n_spans.item())
+    matched = int(buf.span_off[n_spans].item())
+    inserted = int(pool.n_inserted.item())
+    flags = int(pool.flags.item())
+    gather_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    insert_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_ins]))
+    ms_per_step = t_total / args.steps * 1e3
+    gather_bytes = 2.0 * sh.tok_bytes * matched  # algorithmic: every reused row read once and written once
+    step_bytes = 2.0 * sh.tok_bytes * (matched + inserted)
+    gather_gbps = gather_bytes / (gather_ms * 1e-3) / 1e9
+
+    # plain device-to-device copy of the same volume, for context
+    a = torch.empty(int(gather_bytes // 2), dtype=torch.uint8, device=G.DEV)
+    b = torch.empty_like(a)
+    for _ in range(2):
+        b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2.0 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+
+    out = {
+        "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
+        "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64 hashes, bf16 rows moved bit-exact",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: {wl.n_requests} requests x {N // wl.n_requests} tokens, "
+                        f"{sh.n_layers} layers x {sh.n_kv_heads} KV heads x {sh.head_dim} bf16 "
+                        f"({sh.tok_bytes // 1024} KiB/token), pool {wl.pool_slots} slots "
+                        f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) token-major, slots in random order",
+            "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
+            "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
+            "stored_tokens_per_step": inserted, "status_flags": flags,
+        },
+        "reused_tokens_per_s": matched / (ms_per_step * 1e-3),
+        "gather_GBps": gather_gbps,
+        "gather_pct_of_hbm_peak": 100.0 * gather_gbps / HBM_PEAK_GBPS,
+        "gather_ms": gather_ms, "insert_ms": insert_ms,
+        "front_and_reset_ms": ms_per_step - gather_ms - insert_ms,
+        "d2d_copy_GBps_same_volume": copy_gbps,
+        "roofline": {
+            "kernel": "move_rows_kernel (cp_gather_kv)", "bound": "hbm", "achieved": gather_gbps,
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
+            "traffic": MEASURED_TRAFFIC.get(wl.name),
+        },
+    }
+    if args.cpu_requests > 0:
+        del dst
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -407,6 +407,33 @@ def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=50000
     )
 
 
+def subsample(wl: Workload, n_requests: int, pool_slots: int | None = None) -> Workload:
+    """A bounded sample of a workload: its first ``n_requests`` requests and, when the
+    workload records which documents each request uses, only the donor prompts of those
+    documents.  The pool may be shrunk (same bytes per token, fewer slots); donors stay in
+    their original order and form one insert batch."""
+    n_requests = min(n_requests, wl.n_requests)
+    e = int(wl.off[n_requests])
+    picks = wl.notes.get("picks")
+    n_donors = len(wl.donor_off) - 1
+    keep = sorted({d for p in picks[:n_requests] for d in p}) if picks is not None else list(range(n_donors))
+    dt = [wl.donor_tok[wl.donor_off[d]:wl.donor_off[d + 1]] for d in keep]
+    dm = [wl.donor_mask[wl.donor_off[d]:wl.donor_off[d + 1]] for d in keep]
+    dtok, dmask, doff = _pack(dt, dm)
+    slots = wl.pool_slots if pool_slots is None else pool_slots
+    assert slots >= len(dtok), "sample pool too small for its donors"
+    rng = np.random.default_rng(wl.seed ^ 0x5A5A)
+    free = wl.free_slots if slots == wl.pool_slots else rng.permutation(slots).astype(np.uint32)
+    return Workload(
+        name=f"{wl.name}[first {n_requests} requests]", seed=wl.seed, shape=wl.shape,
+        tok=wl.tok[:e].copy(), mask=wl.mask[:e].copy(), off=wl.off[:n_requests + 1].copy(),
+        donor_tok=dtok, donor_mask=dmask, donor_off=doff, donor_batches=[(0, len(keep))],
+        pool_slots=slots, free_slots=free,
+        table_capacity=wl.table_capacity if slots == wl.pool_slots else 2 * slots,
+        rope_theta=wl.rope_theta, rope_style=wl.rope_style, notes={"donors_kept": keep},
+    )
+
+
 WORKLOADS = {
     "tiny": lambda scale=1.0, **kw: make_tiny(**kw),
     "llama3-8b": make_llama8b,

@@ -74,9 +74,12 @@ class KVPool:
     def hash(self, tok, mask, off, out, scratch, stream=None):
         return B.cp_hash_segments(tok, mask, off, out, scratch, stream=stream)
 
-    def lookup(self, tok, mask, off, dst, buf: LookupBuffers, gather=True, stream=None) -> LookupResult:
+    def lookup(self, tok, mask, off, dst, buf: LookupBuffers, gather=True, stream=None,
+               gather_events=None) -> LookupResult:
         """Serve a request batch: after the call the rows of every matched token of
-        ``dst`` (layer-major, N tokens) hold the pooled KV.  No host synchronisation."""
+        ``dst`` (layer-major, N tokens) hold the pooled KV.  No host synchronisation.
+        ``gather_events`` = (start, end) torch events recorded on the stream around
+        the gather call alone (for timing)."""
         N = tok.numel()
         B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
         B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
@@ -84,10 +87,14 @@ class KVPool:
                          buf.span_dst, buf.span_len, buf.span_delta, buf.span_off, buf.n_spans, self.flags,
                          buf.scratch, stream=stream)
         if gather:
+            if gather_events is not None:
+                gather_events[0].record(stream)
             B.cp_gather_kv(self.pool, self.layout, self.n_slots, dst, self.request_layout(N), N, buf.span_src,
                            buf.span_dst, buf.span_len, buf.span_delta if self.rope is not None else None,
                            buf.span_off, buf.n_spans, buf.max_spans, self.rope, self.flags, buf.scratch,
                            stream=stream)
+            if gather_events is not None:
+                gather_events[1].record(stream)
         return LookupResult(buf.hash, buf.slot, buf.span_src, buf.span_dst, buf.span_len, buf.span_delta,
                             buf.span_off, buf.n_spans)
 

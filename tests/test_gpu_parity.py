@@ -18,7 +18,7 @@ NONE = O.SLOT_NONE
 def G():
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a ROCm device; there is no fallback path")
-    from tests import gpu_run
+    from paper_2605_23640_amd import harness as gpu_run
 
     return gpu_run
 
