@@ -89,9 +89,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3-8b", choices=["tiny", "llama3-8b", "frag", "rope", "llama3-70b"])
     ap.add_argument("--cpu-requests", type=int, default=4, help="requests in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--rows-per-item", type=int, default=None)
-    ap.add_argument("--blocks-per-cu", type=int, default=None)
-    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
+    ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
+    ap.add_argument("--nontemporal", type=int, default=None, help="cp_tune key 2")
+    ap.add_argument("--unroll", type=int, default=None, help="cp_tune key 3")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the side measurements (gather without read sharing, plain copy): used under the profiler")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain fill and one plain read kernel of known size (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -106,12 +111,9 @@ def main():
     from cp_workload import gen
     from paper_2605_23640_amd import harness as G
 
-    if args.rows_per_item is not None:
-        cp.cp_tune(0, args.rows_per_item)
-    if args.blocks_per_cu is not None:
-        cp.cp_tune(1, args.blocks_per_cu)
-    if args.nontemporal is not None:
-        cp.cp_tune(2, args.nontemporal)
+    for key, val in enumerate([args.multicast, args.blocks_per_cu, args.nontemporal, args.unroll]):
+        if val is not None:
+            cp.cp_tune(key, val)
 
     t0 = time.time()
     wl = gen.make(args.workload)
@@ -124,16 +126,19 @@ def main():
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
 
     tok, mask, off = G.dev_i32(wl.tok), torch.from_numpy(wl.mask.copy()).to(G.DEV), G.dev_i32(wl.off)
-    buf = cp.LookupBuffers(N, N, G.DEV)
+    buf = cp.LookupBuffers(N, N, G.DEV, n_pool_slots=pool.n_slots)
     dst = G.poison_tensor(N * sh.tok_bytes)
     slot_out = torch.empty(N, dtype=torch.int32, device=G.DEV)
     ins_scratch = cp.binding.new_scratch(N, 0, G.DEV)
     keys0, vals0 = pool.table.keys.clone(), pool.table.vals.clone()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    ev_ins = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    K = args.steps
+    hev = cp.binding.HipEvents(2 * K + 2)  # pairs around the gather's mover kernel, on the launch stream
+    ev_ins = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
 
     def step(k=None):
-        pool.lookup(tok, mask, off, dst, buf, gather_events=None if k is None else ev[k])
+        if k is not None:
+            cp.binding.cp_gather_events(hev.ev[2 * k], hev.ev[2 * k + 1])
+        pool.lookup(tok, mask, off, dst, buf)
         if k is not None:
             ev_ins[k][0].record()
         pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False)
@@ -146,43 +151,69 @@ def main():
         step()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(K):
         step(k)
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t_start
+    cp.binding.cp_gather_events(None, None)
 
     n_spans = int(buf.n_spans.item())
     matched = int(buf.span_off[n_spans].item())
     inserted = int(pool.n_inserted.item())
     flags = int(pool.flags.item())
-    gather_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    slots = G.host_u32(buf.slot)
+    unique_src = int(len(np.unique(slots[slots != 0xFFFFFFFF])))
+    gather_ms = float(np.mean([hev.elapsed_ms(2 * k, 2 * k + 1) for k in range(K)]))
     insert_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_ins]))
-    ms_per_step = t_total / args.steps * 1e3
+    ms_per_step = t_total / K * 1e3
     gather_bytes = 2.0 * sh.tok_bytes * matched  # algorithmic: every reused row read once and written once
     step_bytes = 2.0 * sh.tok_bytes * (matched + inserted)
     gather_gbps = gather_bytes / (gather_ms * 1e-3) / 1e9
 
+    def gather_alone(reps=5):
+        """cp_gather_kv alone on the spans of the last step; returns ms of its mover kernel."""
+        ms = []
+        for r in range(reps + 1):
+            cp.binding.cp_gather_events(hev.ev[2 * K], hev.ev[2 * K + 1])
+            cp.cp_gather_kv(pool.pool, pool.layout, pool.n_slots, dst, pool.request_layout(N), N, buf.span_src,
+                            buf.span_dst, buf.span_len, buf.span_delta if pool.rope is not None else None,
+                            buf.span_off, buf.n_spans, buf.max_spans, pool.rope, pool.flags, buf.scratch)
+            torch.cuda.synchronize()
+            if r:
+                ms.append(hev.elapsed_ms(2 * K, 2 * K + 1))
+        cp.binding.cp_gather_events(None, None)
+        return float(np.mean(ms))
+
+    # the same gather with every token reading its own copy of the source rows (no sharing of reads)
+    own_read_ms = None
+    if not args.no_extras:
+        cp.cp_tune(0, 0)
+        own_read_ms = gather_alone()
+        cp.cp_tune(0, 1 if args.multicast is None else args.multicast)
+
     # plain device-to-device copy of the same volume, for context
-    a = torch.empty(int(gather_bytes // 2), dtype=torch.uint8, device=G.DEV)
-    b = torch.empty_like(a)
-    for _ in range(2):
-        b.copy_(a)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        b.copy_(a)
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2.0 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del a, b
+    copy_gbps = None
+    if not args.no_extras:
+        a = torch.empty(int(gather_bytes // 2), dtype=torch.uint8, device=G.DEV)
+        b = torch.empty_like(a)
+        for _ in range(2):
+            b.copy_(a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 5 * 2.0 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del a, b
 
     out = {
         "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
         "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u64 hashes, bf16 rows moved bit-exact",
+        "dtype": "u64 hashes, bf16 rows moved bit-exact" + (", f64 key rotation" if pool.rope is not None else ""),
         "data": "synthetic",
         "config": {
             "workload": f"{wl.name}: {wl.n_requests} requests x {N // wl.n_requests} tokens, "
@@ -191,20 +222,36 @@ def main():
                         f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) token-major, slots in random order",
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
-            "stored_tokens_per_step": inserted, "status_flags": flags,
+            "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,
         },
         "reused_tokens_per_s": matched / (ms_per_step * 1e-3),
         "gather_GBps": gather_gbps,
         "gather_pct_of_hbm_peak": 100.0 * gather_gbps / HBM_PEAK_GBPS,
         "gather_ms": gather_ms, "insert_ms": insert_ms,
         "front_and_reset_ms": ms_per_step - gather_ms - insert_ms,
+        # bytes that must cross HBM when every distinct source row is read once: written + distinct read
+        "gather_min_hbm_GBps": sh.tok_bytes * (matched + unique_src) / (gather_ms * 1e-3) / 1e9,
+        "gather_GBps_without_read_sharing": None if own_read_ms is None else gather_bytes / (own_read_ms * 1e-3) / 1e9,
         "d2d_copy_GBps_same_volume": copy_gbps,
         "roofline": {
-            "kernel": "move_rows_kernel (cp_gather_kv)", "bound": "hbm", "achieved": gather_gbps,
+            "kernel": "gather_rows_kernel (cp_gather_kv)", "bound": "hbm", "achieved": gather_gbps,
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
             "traffic": MEASURED_TRAFFIC.get(wl.name),
         },
     }
+    hev.close()
+    if args.calibrate:
+        # kernels of known traffic for scaling the profiler's byte counters: the generator's fill
+        # writes, and its verify reads, every byte of the request buffers exactly once
+        from cp_workload import kvgen
+        lay = pool.request_layout(N)
+        kvgen.fill(G.stream_ptr(), C.c_void_p(dst.data_ptr()), G.gen_layout(lay), N, wl.seed, uid_base=0)
+        bad = G.verify_rows(dst, lay, np.arange(N, dtype=np.uint64), wl.seed)
+        torch.cuda.synchronize()
+        out["calibration"] = {"fill_kernel_bytes_written": N * sh.tok_bytes, "verify_kernel_bytes_read": N * sh.tok_bytes,
+                              "verify_mismatches": bad, "gather_bytes_written": sh.tok_bytes * matched,
+                              "gather_bytes_read_algorithmic": sh.tok_bytes * matched,
+                              "gather_bytes_read_distinct": sh.tok_bytes * unique_src}
     if args.cpu_requests > 0:
         del dst
         torch.cuda.empty_cache()

@@ -13,7 +13,7 @@
  *     by the caller.  The library allocates and frees nothing and keeps no state
  *     besides the last HIP error code.
  *   - `scratch` is caller-provided device memory of at least
- *     cp_scratch_bytes(N, max_spans) bytes, 256-byte aligned, whose contents are
+ *     cp_scratch_bytes(N, max_spans, n_pool_slots) bytes, 256-byte aligned, whose contents are
  *     meaningless between calls; calls that share a scratch buffer must be on
  *     one stream.
  *   - R requests are packed back to back: request r holds the tokens
@@ -83,18 +83,36 @@ typedef struct {
 /* Smallest valid table capacity that keeps n_keys keys at or below load_factor. */
 uint64_t cp_table_capacity_for(uint64_t n_keys, double load_factor);
 
-/* Device bytes of scratch that any call below needs for N tokens / max_spans spans. */
-size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans);
+/* Device bytes of scratch that any call below needs for N tokens (the larger of
+ * the batch size and the number of destination tokens), max_spans spans and a
+ * pool of n_pool_slots slots. */
+size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots);
 
 /* hipError_t of the last failed launch of this thread's calls (0 = none). */
 int32_t cp_last_hip_error(void);
 
 /* Launch-shape knobs of the row mover behind cp_gather_kv / cp_insert_kv (host
  * state, process wide; results never depend on them).
- *   key 0: rows of one token per work item (0 = all 2 * n_layers rows)
+ *   key 0: 1 (default) = tokens of one call that read the same pool slot share one
+ *          read of it ("read once, write many"); 0 = every token reads for itself
  *   key 1: resident workgroups per compute unit
- *   key 2: bit 0 non-temporal loads, bit 1 non-temporal stores */
+ *   key 2: bit 0 non-temporal loads, bit 1 non-temporal stores
+ *   key 3: 16-byte loads a lane issues before its first store (4 or 8) */
 int32_t cp_tune(int32_t key, uint32_t value);
+
+/* Timing hook for benchmarks: two hipEvent_t (host handles passed as void*, the
+ * caller creates and destroys them) that every following cp_gather_kv records
+ * on its stream right before and right after its row-mover kernel, so that the
+ * kernel can be timed apart from the small set-up kernels of the call.
+ * NULL, NULL switches the hook off.  Host state, process wide. */
+int32_t cp_gather_events(void *start_event, void *stop_event);
+
+/* hipEvent helpers for callers without their own HIP binding: create a timing
+ * event (NULL on failure), milliseconds between two recorded events (negative
+ * on failure, e.g. not yet complete), destroy. */
+void *cp_event_create(void);
+float cp_event_elapsed_ms(void *start_event, void *stop_event);
+void cp_event_destroy(void *event);
 
 /* Empty the table: every key CP_HASH_NONE, every value CP_SLOT_NONE. */
 int32_t cp_table_init(void *stream, cp_table table);
@@ -144,8 +162,7 @@ int32_t cp_build_spans(void *stream, const uint32_t *slot, const uint32_t *off, 
  * (evaluated in double precision, rounded once to bf16); V rows and spans with
  * delta == 0 are copied bit for bit.  `rope` is a HOST pointer, read before
  * the call returns.  span_off may be NULL (computed internally) or the array
- * cp_build_spans produced (then scratch may be NULL).  Spans must not overlap
- * in dst.  pool_l and dst_l must agree on n_layers, n_kv_heads and head_dim;
+ * cp_build_spans produced.  Spans must not overlap in dst.  pool_l and dst_l must agree on n_layers, n_kv_heads and head_dim;
  * rotation needs head_dim a power of two in [16, 512].  The pool holds
  * n_pool_slots slots and dst n_dst_tokens tokens: a token of a span that falls
  * outside either is skipped and CP_FLAG_BAD_INDEX is set. */

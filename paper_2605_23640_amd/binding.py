@@ -28,7 +28,8 @@ FLAG_SPANS_OVERFLOW, FLAG_POOL_FULL, FLAG_TABLE_FULL, FLAG_BAD_INDEX = 1, 2, 4, 
 
 EXPORTS = [
     "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_tune", "cp_table_init",
-    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv",
+    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv", "cp_gather_events",
+    "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
 ]
 
 
@@ -86,10 +87,12 @@ def lib():
         L.cp_table_capacity_for.restype = u64
         L.cp_table_capacity_for.argtypes = [u64, C.c_double]
         L.cp_scratch_bytes.restype = sz
-        L.cp_scratch_bytes.argtypes = [u32, u32]
+        L.cp_scratch_bytes.argtypes = [u32, u32, u32]
         L.cp_last_hip_error.restype = i32
         L.cp_tune.restype = i32
         L.cp_tune.argtypes = [i32, u32]
+        L.cp_gather_events.restype = i32
+        L.cp_gather_events.argtypes = [vp, vp]
         L.cp_table_init.restype = i32
         L.cp_table_init.argtypes = [vp, TableStruct]
         L.cp_hash_segments.restype = i32
@@ -132,16 +135,49 @@ def cp_table_capacity_for(n_keys, load_factor=0.5):
     return int(lib().cp_table_capacity_for(int(n_keys), float(load_factor)))
 
 
-def cp_scratch_bytes(N, max_spans=0):
-    return int(lib().cp_scratch_bytes(int(N), int(max_spans)))
+def cp_scratch_bytes(N, max_spans=0, n_pool_slots=0):
+    return int(lib().cp_scratch_bytes(int(N), int(max_spans), int(n_pool_slots)))
 
 
 def cp_tune(key, value):
     _check("cp_tune", lib().cp_tune(int(key), int(value)))
 
 
-def new_scratch(N, max_spans, device="cuda"):
-    return torch.empty(cp_scratch_bytes(N, max_spans), dtype=torch.uint8, device=device)
+def cp_gather_events(start_event, stop_event):
+    """hipEvent_t handles (ints / c_void_p, or None) recorded around the gather's row-mover kernel."""
+    _check("cp_gather_events", lib().cp_gather_events(start_event, stop_event))
+
+
+class HipEvents:
+    """n timing hipEvents made by the library's own HIP runtime (cp_event_*)."""
+
+    def __init__(self, n):
+        L = lib()
+        L.cp_event_create.restype = C.c_void_p
+        L.cp_event_elapsed_ms.restype = C.c_float
+        L.cp_event_elapsed_ms.argtypes = [C.c_void_p, C.c_void_p]
+        L.cp_event_destroy.argtypes = [C.c_void_p]
+        self.ev = []
+        for _ in range(n):
+            e = L.cp_event_create()
+            if not e:
+                raise RuntimeError("cp_event_create failed")
+            self.ev.append(C.c_void_p(e))
+
+    def elapsed_ms(self, a, b):
+        ms = float(lib().cp_event_elapsed_ms(self.ev[a], self.ev[b]))
+        if ms < 0:
+            raise RuntimeError(f"cp_event_elapsed_ms failed (hipError {lib().cp_last_hip_error()})")
+        return ms
+
+    def close(self):
+        for e in self.ev:
+            lib().cp_event_destroy(e)
+        self.ev = []
+
+
+def new_scratch(N, max_spans, device="cuda", n_pool_slots=0):
+    return torch.empty(cp_scratch_bytes(N, max_spans, n_pool_slots), dtype=torch.uint8, device=device)
 
 
 class Table:

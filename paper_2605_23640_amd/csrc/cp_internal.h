@@ -11,9 +11,12 @@ namespace cp {
 
 // Tunables (set through cp_tune; defaults chosen from measurements on MI355X).
 struct Tuning {
-  uint32_t move_rows_per_item = 0;   // rows of one token a workgroup moves per work item; 0 = all rows
-  uint32_t move_blocks_per_cu = 8;   // resident workgroups per compute unit for the row mover
-  uint32_t move_nontemporal = 3;     // bit 0: non-temporal loads, bit 1: non-temporal stores
+  uint32_t move_multicast = 1;       // 1: tokens that read the same pool slot are served by one read
+  uint32_t move_blocks_per_cu = 2;   // resident workgroups per compute unit for the row mover
+  uint32_t move_nontemporal = 2;     // bit 0: non-temporal loads, bit 1: non-temporal stores
+  uint32_t move_unroll = 8;          // 16-byte loads a lane issues before its first store (4 or 8)
+  hipEvent_t gather_start = nullptr; // if set (cp_gather_events): recorded right before / after the
+  hipEvent_t gather_stop = nullptr;  // gather's row-mover launch, on the call's stream
 };
 Tuning &tuning();
 
@@ -36,14 +39,24 @@ struct Scratch {
 bool layout_ok(const cp_kv_layout &l);
 bool layouts_match(const cp_kv_layout &a, const cp_kv_layout &b);
 
+// One token's worth of work for the row mover: copy all rows of `from` (a pool
+// slot when gathering, a request token when scattering) to `to`.  `next` links
+// the items that share a source into a chain (0xFFFFFFFF ends it); an item
+// whose `from` is 0xFFFFFFFF is skipped.
+struct alignas(16) MoveItem {
+  uint32_t from, to;
+  int32_t delta;
+  uint32_t next;
+};
+
 // Row mover used by the insert path: for w < *n_items (device count, at most
-// max_items) copy all rows of token item_tok[w] of `src` to slot item_slot[w] of
-// `pool`.  Items naming a token >= n_src_tokens or a slot >= n_pool_slots are
-// skipped and flagged.
+// max_items) copy all rows of token items[w].from of `src` to slot items[w].to
+// of `pool`.  `counter` is a device word that is 0 when the kernel starts.
+// Items naming a token >= n_src_tokens or a slot >= n_pool_slots are skipped
+// and flagged.
 int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &src_l, uint32_t n_src_tokens,
-                       void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, const uint32_t *item_tok,
-                       const uint32_t *item_slot, const uint32_t *n_items, uint32_t max_items,
-                       uint32_t *status_flags);
+                       void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, const MoveItem *items,
+                       const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags);
 
 // Exclusive prefix sums of span_len[0 .. *n_spans) into span_off[0 .. *n_spans],
 // agg = div_up(max_spans, 1024) + 1 words of scratch.

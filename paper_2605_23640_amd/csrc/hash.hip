@@ -49,7 +49,7 @@ extern "C" int32_t cp_hash_segments(void *stream, const uint32_t *tok, const uin
   if (!tok || !mask || !off || !hash_out || !scratch || R == 0) return CP_ERR_INVALID_ARG;
   if (!aligned(tok, 4) || !aligned(off, 4) || !aligned(hash_out, 8) || !aligned(scratch, 16))
     return CP_ERR_INVALID_ARG;
-  if (scratch_bytes < cp_scratch_bytes(N, 0)) return CP_ERR_SCRATCH;
+  if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   HashOp op{tok, mask, off, hash_out, base, N, R};
   return run_scan<HashOp>((hipStream_t)stream, op, N, (HashOp::T *)scratch);
 }

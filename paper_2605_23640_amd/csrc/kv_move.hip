@@ -4,21 +4,30 @@
 // Retriever, Sec. 4.3.1) becomes a copy of every matched token's K and V rows;
 // positions that no span covers are never written.
 //
-// This is the HBM-bound part of the path: each matched token moves
-// 2 * n_layers * row_bytes bytes in and the same amount out, nothing is reused,
-// so the kernel is a pure stream of 16-byte loads and stores:
-//   - a work item is (token, chunk of that token's rows); workgroups take items
-//     grid-stride so a fixed, chip-filling grid serves any device-resident count;
+// This is the HBM-bound part of the path: every matched token needs
+// 2 * n_layers * row_bytes bytes written, and the same amount read unless
+// several requests of the batch reuse the same pool slot (a shared system
+// prompt, a retrieved passage used twice).  Design:
+//   - spans are first expanded into one 16-byte descriptor per token
+//     (source slot, destination token, position delta, link), so the mover
+//     never searches;
+//   - tokens that read the same pool slot are linked into a chain while being
+//     expanded (one atomic exchange per token on a per-slot head word); the
+//     token that ends up as head of a chain moves the rows for the whole chain:
+//     each 16-byte piece is loaded once and stored to every destination
+//     ("read once, write many").  The order inside a chain depends on timing,
+//     the bytes written do not;
+//   - work items (chains) are handed to workgroups through an atomic counter,
+//     so long chains and single tokens balance; every workgroup leaves the loop
+//     as soon as the counter passes the item count;
 //   - inside an item the 256 lanes walk the (row, 16-byte column) space in
-//     row-major order, so every wavefront touches whole contiguous 1 KiB pieces;
-//   - several loads are issued before the first store to keep bytes in flight;
-//   - loads and stores can be non-temporal: nothing is read twice and the
-//     destination is not read back by this kernel.
+//     row-major order, so every wavefront touches whole contiguous 1 KiB pieces,
+//     several loads are issued before the first store, and both directions can
+//     be non-temporal (nothing is read back by this kernel).
 // Key re-rotation (textbook RoPE, not in the paper) is done in double precision
-// on the way through registers: the cos/sin of (delta * inv_freq[j]) are
-// computed once per work item into LDS, the partner element of a pair comes from
-// the neighbouring lane (half-split style) or from the same 16 bytes
-// (interleaved style).
+// on the way through registers: cos/sin of delta * inv_freq[j] are computed once
+// per destination into LDS, the partner element of a pair comes from the
+// neighbouring lane (half-split style) or from the same 16 bytes (interleaved).
 #include "cp_device.h"
 #include "cp_internal.h"
 
@@ -51,47 +60,10 @@ bool layouts_match(const cp_kv_layout &a, const cp_kv_layout &b) {
 namespace {
 
 constexpr int kMoveThreads = 256;
-constexpr int kMoveUnroll = 4;
-constexpr uint32_t kMaxHalfDim = 256;  // head_dim <= 512 when rotating
-
-struct MoveItem {
-  uint32_t from, to;
-  int32_t delta;
-};
-
-// Work items of the gather: token w of the concatenation of all spans.
-struct SpanItems {
-  const uint32_t *span_src, *span_dst, *span_off;
-  const int32_t *span_delta;  // nullable
-  const uint32_t *n_spans;
-  uint32_t max_spans;
-  __device__ __forceinline__ uint32_t n() const {
-    uint32_t k = *n_spans;
-    return k < max_spans ? k : max_spans;
-  }
-  __device__ __forceinline__ uint32_t count() const { return span_off[n()]; }
-  __device__ __forceinline__ MoveItem get(uint32_t w) const {
-    uint32_t lo = 0, hi = n();  // invariant: span_off[lo] <= w < span_off[hi]
-    while (hi - lo > 1) {
-      uint32_t mid = (lo + hi) >> 1;
-      if (span_off[mid] <= w) lo = mid; else hi = mid;
-    }
-    uint32_t k = w - span_off[lo];
-    return MoveItem{span_src[lo] + k, span_dst[lo] + k, span_delta ? span_delta[lo] : 0};
-  }
-};
-
-// Work items of the scatter: w-th newly stored token.
-struct ListItems {
-  const uint32_t *item_from, *item_to;
-  const uint32_t *n_items;
-  uint32_t max_items;
-  __device__ __forceinline__ uint32_t count() const {
-    uint32_t k = *n_items;
-    return k < max_items ? k : max_items;
-  }
-  __device__ __forceinline__ MoveItem get(uint32_t w) const { return MoveItem{item_from[w], item_to[w], 0}; }
-};
+constexpr uint32_t kMaxHalfDim = 256;    // head_dim <= 512 when rotating
+constexpr uint32_t kMaxFanout = 16;      // destinations served per pass over the source rows
+constexpr uint32_t kTrigDoubles = 2048;  // LDS doubles for cos (and as many for sin): fan-out * head_dim/2 <= this
+constexpr uint32_t kNone = 0xFFFFFFFFu;
 
 struct RopeArg {
   uint32_t style, head_dim;
@@ -177,114 +149,232 @@ __device__ __forceinline__ u32x4 rotate_vec(u32x4 own, u32x4 par, uint32_t col_i
   return out;
 }
 
-template <class Items, class RA, bool ROPE, bool NTL, bool NTS>
-__global__ __launch_bounds__(kMoveThreads) void move_rows_kernel(Items items, const uint8_t *__restrict__ from,
-                                                                 cp_kv_layout fl, uint32_t n_from,
-                                                                 uint8_t *__restrict__ to, cp_kv_layout tl,
-                                                                 uint32_t n_to, uint32_t rows_per_item,
-                                                                 uint32_t *status_flags, RA rope) {
-  __shared__ double s_cos[ROPE ? kMaxHalfDim : 1], s_sin[ROPE ? kMaxHalfDim : 1];
+// ---- gather front end: clear the per-slot chain heads, expand spans, link chains -------------
+
+__global__ __launch_bounds__(256) void gather_init_kernel(uint32_t *__restrict__ head, uint32_t n_head,
+                                                          uint32_t *__restrict__ counter) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_head) head[i] = kNone;
+  if (i == 0) *counter = 0;
+}
+
+// One thread per token of the concatenated spans.
+__global__ __launch_bounds__(256) void gather_expand_kernel(
+    const uint32_t *__restrict__ span_src, const uint32_t *__restrict__ span_dst,
+    const uint32_t *__restrict__ span_off, const int32_t *__restrict__ span_delta, const uint32_t *__restrict__ n_spans,
+    uint32_t max_spans, uint32_t n_pool_slots, uint32_t n_dst_tokens, MoveItem *__restrict__ items,
+    uint32_t *__restrict__ head /* nullable: no grouping */, uint32_t *__restrict__ n_items,
+    uint32_t *__restrict__ status_flags) {
+  uint32_t n = *n_spans;
+  if (n > max_spans) n = max_spans;
+  uint32_t total = span_off[n];
+  if (total > n_dst_tokens) total = n_dst_tokens;  // spans that do not overlap cannot cover more
+  const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+  if (w == 0) *n_items = total;
+  if (w >= total) return;
+  uint32_t lo = 0, hi = n;  // invariant: span_off[lo] <= w < span_off[hi]
+  while (hi - lo > 1) {
+    uint32_t mid = (lo + hi) >> 1;
+    if (span_off[mid] <= w) lo = mid; else hi = mid;
+  }
+  const uint32_t k = w - span_off[lo];
+  MoveItem it{span_src[lo] + k, span_dst[lo] + k, span_delta ? span_delta[lo] : 0, kNone};
+  if (it.from >= n_pool_slots || it.to >= n_dst_tokens) {
+    atomicOr(status_flags, CP_FLAG_BAD_INDEX);
+    it.from = it.to = kNone;  // the mover skips it
+  } else if (head) {
+    it.next = atomicExch(&head[it.from], w);  // push onto the chain of tokens that read this slot
+  }
+  items[w] = it;
+}
+
+// ---- the mover ---------------------------------------------------------------------------------
+
+template <class RA, bool ROPE, bool NTL, bool NTS, int U>
+__device__ __forceinline__ void move_rows_body(
+    const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
+    const uint32_t *__restrict__ head /* nullable: every item is its own chain */, uint32_t *counter,
+    const uint8_t *__restrict__ from, const cp_kv_layout &fl, uint32_t n_from, uint8_t *__restrict__ to,
+    const cp_kv_layout &tl, uint32_t n_to, uint32_t fanout, uint32_t *status_flags, const RA &rope) {
+  __shared__ uint32_t s_next_w;     // next work item of this workgroup
+  __shared__ uint32_t s_k, s_more;  // destinations in this pass; chain node to continue with
+  __shared__ uint32_t s_to[kMaxFanout];
+  __shared__ int32_t s_delta[kMaxFanout];
+  __shared__ double s_cos[ROPE ? kTrigDoubles : 1], s_sin[ROPE ? kTrigDoubles : 1];
+
+  uint32_t n_items = *n_items_ptr;
+  if (n_items > max_items) n_items = max_items;
   const uint32_t n_rows = fl.n_layers * 2;
   const uint32_t vpr = fl.n_kv_heads * fl.head_dim / 8;  // 16-byte vectors per row
-  const uint32_t chunks = (n_rows + rows_per_item - 1) / rows_per_item;
-  const uint64_t n_items = (uint64_t)items.count() * chunks;
-  // lane t starts at vector t of the item and advances by 256 vectors per step
+  // lane t starts at vector t of the token and advances by 256 vectors per step
   const uint32_t r_step = kMoveThreads / vpr, c_step = kMoveThreads % vpr;
   const uint32_t r_init = threadIdx.x / vpr, c_init = threadIdx.x % vpr;
   const uint32_t vph = fl.head_dim / 8;  // vectors per head
   const uint32_t half = fl.head_dim / 2;
+  const uint32_t steps = (n_rows * vpr + kMoveThreads - 1) / kMoveThreads;  // same for every lane
 
-  for (uint64_t it = blockIdx.x; it < n_items; it += gridDim.x) {
-    const uint32_t w = (uint32_t)(it / chunks), ch = (uint32_t)(it - (uint64_t)w * chunks);
-    const MoveItem d = items.get(w);
-    if (d.from >= n_from || d.to >= n_to) {  // same for the whole workgroup
-      if (threadIdx.x == 0) atomicOr(status_flags, CP_FLAG_BAD_INDEX);
-      continue;
-    }
-    const uint32_t row0 = ch * rows_per_item;
-    const uint32_t nr = min(rows_per_item, n_rows - row0);
-    const uint8_t *fbase = from + (uint64_t)d.from * fl.tok_stride;
-    uint8_t *tbase = to + (uint64_t)d.to * tl.tok_stride;
-    const bool rot = ROPE && d.delta != 0;
-    if (ROPE) {
-      __syncthreads();  // the previous item's readers are done with the tables
-      if (rot && threadIdx.x < half) {
-        double sn, cs;
-        sincos((double)d.delta * rope.inv_freq[threadIdx.x], &sn, &cs);
-        s_cos[threadIdx.x] = cs;
-        s_sin[threadIdx.x] = sn;
-      }
-      __syncthreads();
-    }
-    const uint32_t steps = (nr * vpr + kMoveThreads - 1) / kMoveThreads;  // same for every lane
-    uint32_t r = r_init, c = c_init;
-    for (uint32_t j = 0; j < steps; j += kMoveUnroll) {
-      u32x4 v[kMoveUnroll];
-      uint8_t *dp[kMoveUnroll];
-      uint32_t cc[kMoveUnroll];
-      bool ok[kMoveUnroll], is_k[kMoveUnroll];
-#pragma unroll
-      for (int u = 0; u < kMoveUnroll; ++u) {
-        ok[u] = r < nr;  // r only grows, so the valid steps of a lane are a prefix
-        const uint32_t row = row0 + r;
-        const uint64_t l = row >> 1, kv = row & 1;
-        is_k[u] = kv == 0;
-        cc[u] = c;
-        dp[u] = tbase + l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
-        v[u] = u32x4{0, 0, 0, 0};
-        if (ok[u]) v[u] = load16<NTL>(fbase + l * fl.layer_stride + kv * fl.kv_stride + (uint64_t)c * 16);
-        c += c_step;
-        r += r_step;
-        if (c >= vpr) {
-          c -= vpr;
-          r += 1;
-        }
-      }
-      if (rot) {
-#pragma unroll
-        for (int u = 0; u < kMoveUnroll; ++u) {
-          const uint32_t cih = cc[u] % vph;
-          u32x4 par = v[u];
-          if (rope.style == 0) {  // partner vector sits half a head away: vph/2 lanes (all lanes take part)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) par[q] = __shfl_xor(v[u][q], (int)(vph / 2), kWave);
+  if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);
+  __syncthreads();
+  while (true) {
+    const uint32_t w = s_next_w;  // same value in every lane
+    if (w >= n_items) break;      // the counter only grows: every workgroup gets here
+    MoveItem cur = items[w];
+    const bool leader = cur.from != kNone && (head == nullptr || head[cur.from] == w);
+    __syncthreads();  // everyone has read s_next_w
+    if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);  // fetched while this item is being moved
+    if (leader && cur.from < n_from) {
+      const uint8_t *fbase = from + (uint64_t)cur.from * fl.tok_stride;
+      uint32_t node = w;
+      do {  // passes of at most `fanout` destinations over the same source rows
+        if (threadIdx.x == 0) {
+          uint32_t k = 0, nd = node;
+          MoveItem it = nd == w ? cur : items[nd];
+          while (true) {
+            if (it.to < n_to) {
+              s_to[k] = it.to;
+              s_delta[k] = it.delta;
+              ++k;
+            }
+            nd = it.next;
+            if (nd == kNone || nd >= n_items || k == fanout) break;
+            it = items[nd];
           }
-          if (ok[u] && is_k[u]) v[u] = rotate_vec(v[u], par, cih, rope.style, half, s_cos, s_sin);
+          s_k = k;
+          s_more = (nd != kNone && nd < n_items) ? nd : kNone;
         }
-      }
+        __syncthreads();
+        const uint32_t K = s_k;
+        if (ROPE) {
+          for (uint32_t i = threadIdx.x; i < K * half; i += kMoveThreads) {
+            const uint32_t k = i / half, j = i - k * half;
+            const int32_t dl = s_delta[k];
+            if (dl != 0) {
+              double sn, cs;
+              sincos((double)dl * rope.inv_freq[j], &sn, &cs);
+              s_cos[i] = cs;
+              s_sin[i] = sn;
+            }
+          }
+          __syncthreads();
+        }
+        uint32_t r = r_init, c = c_init;
+        for (uint32_t j = 0; j < steps; j += U) {
+          u32x4 v[U], par[U];
+          uint64_t doff[U];
+          uint32_t cc[U];
+          bool ok[U], is_k[U];
 #pragma unroll
-      for (int u = 0; u < kMoveUnroll; ++u)
-        if (ok[u]) store16<NTS>(dp[u], v[u]);
+          for (int u = 0; u < U; ++u) {
+            ok[u] = r < n_rows;  // r only grows, so the valid steps of a lane are a prefix
+            const uint64_t l = r >> 1, kv = r & 1;
+            is_k[u] = kv == 0;
+            cc[u] = c;
+            doff[u] = l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
+            v[u] = u32x4{0, 0, 0, 0};
+            if (ok[u]) v[u] = load16<NTL>(fbase + l * fl.layer_stride + kv * fl.kv_stride + (uint64_t)c * 16);
+            par[u] = v[u];
+            c += c_step;
+            r += r_step;
+            if (c >= vpr) {
+              c -= vpr;
+              r += 1;
+            }
+          }
+          if (ROPE && rope.style == 0) {
+            // partner vector sits half a head away: vph/2 lanes further (all lanes take part)
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) par[u][q] = __shfl_xor(v[u][q], (int)(vph / 2), kWave);
+          }
+          for (uint32_t k = 0; k < K; ++k) {
+            uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
+            const bool rot = ROPE && s_delta[k] != 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              if (!ok[u]) continue;
+              u32x4 x = v[u];
+              if (rot && is_k[u])
+                x = rotate_vec(v[u], par[u], cc[u] % vph, rope.style, half, s_cos + k * half, s_sin + k * half);
+              store16<NTS>(tbase + doff[u], x);
+            }
+          }
+        }
+        node = s_more;
+        __syncthreads();  // lists and tables are free for the next pass / item
+      } while (node != kNone);
+    } else {
+      if (cur.from != kNone && cur.from >= n_from && threadIdx.x == 0) atomicOr(status_flags, CP_FLAG_BAD_INDEX);
+      __syncthreads();  // s_next_w is written
     }
   }
 }
 
-template <class Items, class RA, bool ROPE>
-int32_t launch_move(hipStream_t stream, const Items &items, uint32_t max_tokens, const void *from,
-                    const cp_kv_layout &fl, uint32_t n_from, void *to, const cp_kv_layout &tl, uint32_t n_to,
-                    uint32_t *status_flags, const RA &rope) {
-  if (max_tokens == 0) return CP_OK;
+// The two users of the mover get kernels of their own name, so that profiles tell them apart.
+template <class RA, bool ROPE, bool NTL, bool NTS, int U>
+__global__ __launch_bounds__(kMoveThreads) void gather_rows_kernel(
+    const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
+    const uint32_t *__restrict__ head, uint32_t *counter, const uint8_t *__restrict__ pool, cp_kv_layout pool_l,
+    uint32_t n_pool_slots, uint8_t *__restrict__ dst, cp_kv_layout dst_l, uint32_t n_dst_tokens, uint32_t fanout,
+    uint32_t *status_flags, RA rope) {
+  move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, head, counter, pool, pool_l, n_pool_slots, dst,
+                                        dst_l, n_dst_tokens, fanout, status_flags, rope);
+}
+
+template <class RA, bool ROPE, bool NTL, bool NTS, int U>
+__global__ __launch_bounds__(kMoveThreads) void scatter_rows_kernel(
+    const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
+    const uint32_t *__restrict__ head, uint32_t *counter, const uint8_t *__restrict__ src, cp_kv_layout src_l,
+    uint32_t n_src_tokens, uint8_t *__restrict__ pool, cp_kv_layout pool_l, uint32_t n_pool_slots, uint32_t fanout,
+    uint32_t *status_flags, RA rope) {
+  move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, head, counter, src, src_l, n_src_tokens, pool,
+                                        pool_l, n_pool_slots, fanout, status_flags, rope);
+}
+
+uint32_t cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    cus = v;
+  }
+  return (uint32_t)cus;
+}
+
+template <class RA, bool ROPE, bool GATHER>
+int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n_items, uint32_t max_items,
+                    const uint32_t *head, uint32_t *counter, const void *from, const cp_kv_layout &fl, uint32_t n_from,
+                    void *to, const cp_kv_layout &tl, uint32_t n_to, uint32_t *status_flags, const RA &rope) {
+  if (max_items == 0) return CP_OK;
   const Tuning &tn = tuning();
-  const uint32_t n_rows = fl.n_layers * 2;
-  uint32_t rpi = tn.move_rows_per_item ? tn.move_rows_per_item : n_rows;
-  if (rpi > n_rows) rpi = n_rows;
-  const uint64_t max_items = (uint64_t)max_tokens * ((n_rows + rpi - 1) / rpi);
-  int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-    cus = 256;
-  uint64_t grid = (uint64_t)cus * (tn.move_blocks_per_cu ? tn.move_blocks_per_cu : 8);
+  uint64_t grid = (uint64_t)cu_count() * (tn.move_blocks_per_cu ? tn.move_blocks_per_cu : 8);
   if (grid > max_items) grid = max_items;
+  uint32_t fanout = kMaxFanout;
+  if (ROPE) {
+    uint32_t cap = kTrigDoubles / (fl.head_dim / 2);
+    if (fanout > cap) fanout = cap;
+  }
   const uint8_t *f = (const uint8_t *)from;
   uint8_t *t = (uint8_t *)to;
-#define CP_LAUNCH(NTL, NTS)                                                                                      \
-  move_rows_kernel<Items, RA, ROPE, NTL, NTS><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(items, f, fl, n_from, t, tl, \
-                                                                                        n_to, rpi, status_flags, rope)
-  switch (tn.move_nontemporal & 3u) {
-    case 0: CP_LAUNCH(false, false); break;
-    case 1: CP_LAUNCH(true, false); break;
-    case 2: CP_LAUNCH(false, true); break;
-    default: CP_LAUNCH(true, true); break;
+#define CP_LAUNCH(NTL, NTS, UN)                                                                             \
+  if (GATHER)                                                                                               \
+    gather_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                \
+        items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope);  \
+  else                                                                                                      \
+    scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(               \
+        items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope)
+  const bool deep = !ROPE && tn.move_unroll >= 8;  // rotation keeps the short form: it needs the registers
+  switch ((tn.move_nontemporal & 3u) | (deep ? 4u : 0u)) {
+    case 0: CP_LAUNCH(false, false, 4); break;
+    case 1: CP_LAUNCH(true, false, 4); break;
+    case 2: CP_LAUNCH(false, true, 4); break;
+    case 3: CP_LAUNCH(true, true, 4); break;
+    case 4: CP_LAUNCH(false, false, 8); break;
+    case 5: CP_LAUNCH(true, false, 8); break;
+    case 6: CP_LAUNCH(false, true, 8); break;
+    default: CP_LAUNCH(true, true, 8); break;
   }
 #undef CP_LAUNCH
   return check_launch();
@@ -293,13 +383,11 @@ int32_t launch_move(hipStream_t stream, const Items &items, uint32_t max_tokens,
 }  // namespace
 
 int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &src_l, uint32_t n_src_tokens,
-                       void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, const uint32_t *item_tok,
-                       const uint32_t *item_slot, const uint32_t *n_items, uint32_t max_items,
-                       uint32_t *status_flags) {
-  ListItems items{item_tok, item_slot, n_items, max_items};
+                       void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, const MoveItem *items,
+                       const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags) {
   NoRope none{};
-  return launch_move<ListItems, NoRope, false>(stream, items, max_items, src, src_l, n_src_tokens, pool, pool_l, n_pool_slots,
-                                       status_flags, none);
+  return launch_move<NoRope, false, false>(stream, items, n_items, max_items, nullptr, counter, src, src_l, n_src_tokens, pool,
+                                    pool_l, n_pool_slots, status_flags, none);
 }
 
 }  // namespace cp
@@ -311,10 +399,10 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
                                 const cp_rope *rope, uint32_t *status_flags, void *scratch, size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
-  if (max_spans == 0 || n_dst_tokens == 0) return CP_OK;
+  if (max_spans == 0 || n_dst_tokens == 0 || n_pool_slots == 0) return CP_OK;
   if (n_dst_tokens >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (!pool || !dst || !span_src || !span_dst || !span_len || !n_spans || !status_flags) return CP_ERR_INVALID_ARG;
-  if (!aligned(pool, 16) || !aligned(dst, 16)) return CP_ERR_INVALID_ARG;
+  if (!scratch || !aligned(scratch, 256) || !aligned(pool, 16) || !aligned(dst, 16)) return CP_ERR_INVALID_ARG;
   if (!layout_ok(pool_l) || !layout_ok(dst_l) || !layouts_match(pool_l, dst_l)) return CP_ERR_UNSUPPORTED;
   const bool use_rope = rope != nullptr && span_delta != nullptr;
   RopeArg ra{};
@@ -327,31 +415,78 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
     ra.head_dim = D;
     for (uint32_t j = 0; j < D / 2; ++j) ra.inv_freq[j] = std::pow(rope->theta, -2.0 * (double)j / (double)D);
   }
+  if (scratch_bytes < cp_scratch_bytes(n_dst_tokens, max_spans, n_pool_slots)) return CP_ERR_SCRATCH;
+  Scratch sc(scratch, scratch_bytes);
+  uint32_t *agg = sc.take<uint32_t>(div_up(max_spans, kScanTile) + 1);
+  uint32_t *offs = sc.take<uint32_t>((size_t)max_spans + 1);
+  uint32_t *counters = sc.take<uint32_t>(2);  // [0] work counter, [1] item count
+  MoveItem *items = sc.take<MoveItem>(n_dst_tokens);
+  const bool group = tuning().move_multicast != 0;
+  uint32_t *head = group ? sc.take<uint32_t>(n_pool_slots) : nullptr;
+  if (!agg || !offs || !counters || !items || (group && !head)) return CP_ERR_SCRATCH;
   if (!span_off) {
-    if (!scratch || !aligned(scratch, 256)) return CP_ERR_INVALID_ARG;
-    if (scratch_bytes < cp_scratch_bytes(0, max_spans)) return CP_ERR_SCRATCH;
-    Scratch sc(scratch, scratch_bytes);
-    uint32_t *agg = sc.take<uint32_t>(div_up(max_spans, kScanTile) + 1);
-    uint32_t *offs = sc.take<uint32_t>((size_t)max_spans + 1);
-    if (!agg || !offs) return CP_ERR_SCRATCH;
     if (int32_t rc = launch_span_offsets(stream, span_len, n_spans, max_spans, offs, agg)) return rc;
     span_off = offs;
   }
-  SpanItems items{span_src, span_dst, span_off, use_rope ? span_delta : nullptr, n_spans, max_spans};
+  gather_init_kernel<<<group ? div_up(n_pool_slots, 256) : 1, 256, 0, stream>>>(head, group ? n_pool_slots : 0,
+                                                                                counters);
   // spans do not overlap in dst, so they cover at most n_dst_tokens tokens
-  if (use_rope)
-    return launch_move<SpanItems, RopeArg, true>(stream, items, n_dst_tokens, pool, pool_l, n_pool_slots, dst, dst_l,
-                                                 n_dst_tokens, status_flags, ra);
-  NoRope none{};
-  return launch_move<SpanItems, NoRope, false>(stream, items, n_dst_tokens, pool, pool_l, n_pool_slots, dst, dst_l,
-                                               n_dst_tokens, status_flags, none);
+  gather_expand_kernel<<<div_up(n_dst_tokens, 256), 256, 0, stream>>>(
+      span_src, span_dst, span_off, use_rope ? span_delta : nullptr, n_spans, max_spans, n_pool_slots, n_dst_tokens,
+      items, head, counters + 1, status_flags);
+  if (int32_t rc = check_launch()) return rc;
+  const Tuning &tn = tuning();
+  if (tn.gather_start && hipEventRecord(tn.gather_start, stream) != hipSuccess) return CP_ERR_HIP;
+  int32_t rc;
+  if (use_rope) {
+    rc = launch_move<RopeArg, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                    n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, ra);
+  } else {
+    NoRope none{};
+    rc = launch_move<NoRope, false, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                    n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, none);
+  }
+  if (tn.gather_stop && hipEventRecord(tn.gather_stop, stream) != hipSuccess) return CP_ERR_HIP;
+  return rc;
 }
 
-extern "C" size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans) {
+extern "C" int32_t cp_gather_events(void *start_event, void *stop_event) {
+  cp::tuning().gather_start = (hipEvent_t)start_event;
+  cp::tuning().gather_stop = (hipEvent_t)stop_event;
+  return CP_OK;
+}
+
+extern "C" void *cp_event_create(void) {
+  hipEvent_t e = nullptr;
+  hipError_t rc = hipEventCreate(&e);
+  if (rc != hipSuccess) {
+    cp::last_hip_error() = (int32_t)rc;
+    return nullptr;
+  }
+  return (void *)e;
+}
+
+extern "C" float cp_event_elapsed_ms(void *start_event, void *stop_event) {
+  float ms = -1.0f;
+  hipError_t rc = hipEventElapsedTime(&ms, (hipEvent_t)start_event, (hipEvent_t)stop_event);
+  if (rc != hipSuccess) {
+    cp::last_hip_error() = (int32_t)rc;
+    return -1.0f;
+  }
+  return ms;
+}
+
+extern "C" void cp_event_destroy(void *event) {
+  if (event) (void)hipEventDestroy((hipEvent_t)event);
+}
+
+extern "C" size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots) {
   using namespace cp;
   uint64_t n = N > max_spans ? N : max_spans;
-  // tile totals (16 bytes each) + three per-token words + span offsets, each piece padded to 256 bytes
-  return (size_t)(((uint64_t)div_up(n, kScanTile) + 2) * 16 + 3ull * 4 * N + 4ull * ((uint64_t)max_spans + 1) + 8 * 256);
+  // tile totals (16 bytes each), three per-token words (insert) and one 16-byte descriptor per
+  // token (gather, insert), span offsets, one chain head per pool slot; pieces padded to 256 bytes
+  return (size_t)(((uint64_t)div_up(n, kScanTile) + 2) * 16 + (3ull * 4 + 16) * N + 4ull * ((uint64_t)max_spans + 1) +
+                  4ull * n_pool_slots + 12 * 256);
 }
 
 extern "C" int32_t cp_last_hip_error(void) { return cp::last_hip_error(); }
@@ -359,9 +494,10 @@ extern "C" int32_t cp_last_hip_error(void) { return cp::last_hip_error(); }
 extern "C" int32_t cp_tune(int32_t key, uint32_t value) {
   cp::Tuning &t = cp::tuning();
   switch (key) {
-    case 0: t.move_rows_per_item = value; return CP_OK;
+    case 0: t.move_multicast = value; return CP_OK;
     case 1: t.move_blocks_per_cu = value; return CP_OK;
     case 2: t.move_nontemporal = value; return CP_OK;
+    case 3: t.move_unroll = value; return CP_OK;
     default: return CP_ERR_INVALID_ARG;
   }
 }

@@ -106,7 +106,7 @@ extern "C" int32_t cp_build_spans(void *stream_, const uint32_t *slot, const uin
   if (!n_spans || !status_flags || !scratch || !aligned(scratch, 256)) return CP_ERR_INVALID_ARG;
   if (N && (!slot || !off || R == 0)) return CP_ERR_INVALID_ARG;
   if (max_spans && (!span_src || !span_dst || !span_len)) return CP_ERR_INVALID_ARG;
-  if (scratch_bytes < cp_scratch_bytes(N, max_spans)) return CP_ERR_SCRATCH;
+  if (scratch_bytes < cp_scratch_bytes(N, max_spans, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
   uint32_t tiles = div_up(N > max_spans ? N : max_spans, kScanTile) + 1;
   SpanOp::T *agg = sc.take<SpanOp::T>(tiles);

@@ -130,7 +130,6 @@ struct OwnerRankOp {
   const uint32_t *entry_of;
   const uint32_t *vals;
   uint32_t *rank;      // [N]  rank of token i among the owners, valid for owners only
-  uint32_t *owners;    // [min(N, n_free)]  owner token of rank w
   uint32_t *n_inserted;
   uint32_t *status_flags;
   uint32_t N, n_free;
@@ -145,7 +144,6 @@ struct OwnerRankOp {
   __device__ __forceinline__ void store(uint32_t i, T excl, T incl) const {
     if (incl != excl) {
       rank[i] = excl;
-      if (excl < n_free) owners[excl] = i;
     }
   }
   __device__ __forceinline__ void finish(T total) const {
@@ -184,8 +182,11 @@ __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__re
                                                             const uint32_t *__restrict__ rank,
                                                             const uint32_t *__restrict__ free_slots, uint32_t n_free,
                                                             uint32_t n_pool_slots, const uint32_t *__restrict__ off,
-                                                            uint32_t R, uint32_t N, int32_t *__restrict__ slot_pos) {
+                                                            uint32_t R, uint32_t N, int32_t *__restrict__ slot_pos,
+                                                            MoveItem *__restrict__ items,
+                                                            uint32_t *__restrict__ move_counter) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) *move_counter = 0;  // work counter of the scatter that follows
   if (i >= N) return;
   uint32_t e = entry_of[i];
   if (e == CP_SLOT_NONE || vals[e] != (kPending | i)) return;  // only the owner touches its entry
@@ -196,6 +197,8 @@ __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__re
     else s = CP_SLOT_NONE;  // a free-list entry outside the pool is never used
   }
   vals[e] = s;
+  // work list of the scatter: token i -> slot s (an unusable entry is marked and skipped)
+  if (r < n_free) items[r] = MoveItem{s == CP_SLOT_NONE ? CP_SLOT_NONE : i, s, 0, CP_SLOT_NONE};
 }
 
 }  // namespace
@@ -249,26 +252,27 @@ extern "C" int32_t cp_insert_kv(void *stream_, cp_table table, const uint64_t *h
   if (n_free && !free_slots) return CP_ERR_INVALID_ARG;
   if (!aligned(hash, 8) || !aligned(src, 16) || !aligned(pool, 16)) return CP_ERR_INVALID_ARG;
   if (!layout_ok(src_l) || !layout_ok(pool_l) || !layouts_match(src_l, pool_l)) return CP_ERR_UNSUPPORTED;
-  if (scratch_bytes < cp_scratch_bytes(N, 0)) return CP_ERR_SCRATCH;
+  if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
   uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
   uint32_t *entry_of = sc.take<uint32_t>(N);
   uint32_t *rank = sc.take<uint32_t>(N);
-  uint32_t *owners = sc.take<uint32_t>(N);
-  if (!agg || !entry_of || !rank || !owners) return CP_ERR_SCRATCH;
+  uint32_t *counter = sc.take<uint32_t>(1);
+  MoveItem *items = sc.take<MoveItem>(N);
+  if (!agg || !entry_of || !rank || !counter || !items) return CP_ERR_SCRATCH;
   const uint32_t blocks = div_up(N, 256);
   if (N)
     insert_claim_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
         table, hash, N, entry_of, status_flags);
-  OwnerRankOp op{entry_of, table.vals, rank, owners, n_inserted, status_flags, N, n_free};
+  OwnerRankOp op{entry_of, table.vals, rank, n_inserted, status_flags, N, n_free};
   if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, agg)) return rc;
   if (N == 0) return CP_OK;
   insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, N,
                                                     slot_out);
   insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, off, R,
-                                                   N, slot_pos);
+                                                   N, slot_pos, items, counter);
   if (int32_t rc = check_launch()) return rc;
   uint32_t max_items = N < n_free ? N : n_free;
-  return launch_scatter(stream, src, src_l, N, pool, pool_l, n_pool_slots, owners, free_slots, n_inserted, max_items,
+  return launch_scatter(stream, src, src_l, N, pool, pool_l, n_pool_slots, items, n_inserted, max_items, counter,
                         status_flags);
 }

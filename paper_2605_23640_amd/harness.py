@@ -112,7 +112,7 @@ def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=T
     mask = wl.mask if mask is None else mask
     off = wl.off if off is None else off
     N = len(tok)
-    buf = cp.LookupBuffers(N, max_spans, DEV)
+    buf = cp.LookupBuffers(N, max_spans, DEV, n_pool_slots=st.pool.n_slots)
     dst = poison_tensor(max(1, N) * sh.tok_bytes)
     st.pool.flags.zero_()
     st.pool.lookup(dev_i32(tok), torch.from_numpy(np.ascontiguousarray(mask)).to(DEV), dev_i32(off), dst, buf,

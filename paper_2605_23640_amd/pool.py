@@ -30,7 +30,7 @@ class LookupResult:
 class LookupBuffers:
     """Reusable per-batch device arrays for the lookup path (N tokens, up to max_spans spans)."""
 
-    def __init__(self, N, max_spans=None, device="cuda"):
+    def __init__(self, N, max_spans=None, device="cuda", n_pool_slots=0):
         self.N = N
         self.max_spans = N if max_spans is None else max_spans
         i32, i64 = torch.int32, torch.int64
@@ -43,7 +43,7 @@ class LookupBuffers:
         self.span_delta = torch.empty(m, dtype=i32, device=device)
         self.span_off = torch.empty(m + 1, dtype=i32, device=device)
         self.n_spans = torch.zeros(1, dtype=i32, device=device)
-        self.scratch = B.new_scratch(max(N, 1), self.max_spans, device)
+        self.scratch = B.new_scratch(max(N, 1), self.max_spans, device, n_pool_slots)
 
 
 class KVPool:

@@ -1,0 +1,109 @@
+"""Parity at the full sizes of the benchmark configurations (Llama-3-8B shape,
+fragmentation stress, RoPE-shift reuse, Llama-3-70B shape), in the launch
+configuration bench.py times.
+
+Hashes, slots, spans, deltas and inserted slots are compared in full against
+the CPU oracle (they do not depend on the KV shape, so the oracle runs them on
+a one-layer stand-in pool).  KV bytes are checked everywhere on the device by
+the generator's verify kernel: the oracle says which donor token owns each
+slot and which slot serves each request token, the generator says what that
+donor token's rows are, and every row of the pool and of the request buffers
+must hold exactly that (or the untouched fill pattern).  Re-rotated keys are
+compared on a seeded sample of tokens against the oracle's double-precision
+rotation, one by one."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from cp_workload import gen, kvgen
+from oracle import harness as OH
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a ROCm device; there is no fallback path")
+    from paper_2605_23640_amd import harness
+
+    return harness
+
+
+def bf16_ordinal(bits):
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+
+def oracle_bookkeeping(wl):
+    """Oracle prefill + lookup with a tiny stand-in KV shape (index, slots, spans only)."""
+    import copy
+
+    w = copy.copy(wl)
+    w.shape = gen.KVShape(1, 1, 8)
+    st = OH.prefill(w, src_provider=lambda t0, n: np.zeros((1, 2, n, 8), np.uint16))
+    lk = OH.lookup(st, gather=False)
+    return st, lk
+
+
+@pytest.mark.parametrize("name", ["llama3-8b", "frag", "rope", "llama3-70b"])
+def test_full_size(G, name):
+    wl = gen.make(name)
+    sh, N = wl.shape, wl.n_tokens
+    print(f"\n[{name}] {wl.n_requests} requests x {N // wl.n_requests} tokens, pool "
+          f"{wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB, request buffers {N * sh.tok_bytes / 2**30:.0f} GiB", flush=True)
+    ost, olk = oracle_bookkeeping(wl)
+    gst = G.prefill(wl)
+    print(f"[{name}] prefilled {sum(gst.n_inserted)} tokens", flush=True)
+    assert np.array_equal(gst.donor_hash, ost.donor_hash)
+    assert np.array_equal(gst.donor_slot, ost.donor_slot)
+    assert sum(gst.n_inserted) == ost.n_used and gst.flags == 0
+    stored = ost.slot_uid != kvgen.UID_NONE
+    assert np.array_equal(gst.pool.slot_pos.cpu().numpy()[stored], ost.slot_pos[stored])
+    assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0  # the whole pool
+    glk = G.lookup(gst)
+    print(f"[{name}] lookup: {glk.n_spans} spans, {(glk.slot != O.SLOT_NONE).sum()} tokens served", flush=True)
+    assert np.array_equal(glk.hash, olk.hash) and np.array_equal(glk.slot, olk.slot)
+    assert glk.n_spans == olk.n_spans and glk.flags == 0
+    for f in ("span_src", "span_dst", "span_len"):
+        assert np.array_equal(getattr(glk, f), getattr(olk, f)), f
+    served = olk.slot != O.SLOT_NONE
+    assert (olk.slot[wl.mask == 1] == O.SLOT_NONE).all()  # no sensitive token is served
+    # expected owner (donor token) of every request row; unmatched rows must still hold the fill pattern
+    uid = np.full(N, kvgen.UID_NONE, np.uint64)
+    uid[served] = ost.slot_uid[olk.slot[served]]
+    lay = gst.pool.request_layout(N)
+    if wl.rope_theta is None:
+        assert G.verify_rows(glk.dst, lay, uid, wl.seed) == 0  # every row of the request buffers
+    else:
+        assert np.array_equal(glk.span_delta, olk.span_delta)
+        delta = np.zeros(N, np.int32)
+        for d, l, dl in zip(olk.span_dst, olk.span_len, olk.span_delta):
+            delta[d:d + l] = dl
+        rotated = served & (delta != 0)
+        # V rows everywhere and K rows of unshifted tokens: exact generator bytes
+        assert G.verify_rows(glk.dst, lay, uid, wl.seed, skip_k=rotated.astype(np.uint8)) == 0
+        # K rows of a seeded sample of shifted tokens against the oracle's rotation
+        rng = np.random.default_rng(wl.seed)
+        idx = np.sort(rng.choice(np.flatnonzero(rotated), size=192, replace=False))
+        re = sh.row_bytes // 2
+        view = glk.dst.view(torch.int16).view(sh.n_layers, 2, N, re)
+        got = view[:, 0, torch.from_numpy(idx).to(G.DEV), :].cpu().numpy().view(np.uint16)  # [L][sample][re]
+        src = kvgen.rows_for_tokens(wl.seed, uid[idx], sh.n_layers, re)[:, :, 0, :]  # [sample][L][re]
+        hist = np.zeros(3, np.int64)
+        D = sh.head_dim
+        for s, i in enumerate(idx):
+            for l in range(sh.n_layers):
+                for h in range(sh.n_kv_heads):
+                    want = O.rope_head(src[s, l, h * D:(h + 1) * D], int(delta[i]), wl.rope_theta, wl.rope_style)
+                    d = np.abs(bf16_ordinal(got[l, s, h * D:(h + 1) * D]) - bf16_ordinal(want))
+                    hist += np.bincount(np.minimum(d, 2), minlength=3)
+        print(f"[{name}] bf16 distance of {hist.sum()} sampled re-rotated key elements {{0,1,>1}}: {hist.tolist()}",
+              flush=True)
+        assert hist[2] == 0 and hist[1] <= 1e-3 * hist.sum()
+    del gst, glk
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -188,7 +188,7 @@ def test_layer_major_pool_gather(G):
     out = G.poison_tensor(N * L * 2 * rb)
     flags = torch.zeros(1, dtype=torch.int32, device=G.DEV)
     n_sp = torch.tensor([3], dtype=torch.int32, device=G.DEV)
-    scratch = cp.binding.new_scratch(N, 8, G.DEV)
+    scratch = cp.binding.new_scratch(N, 8, G.DEV, S)
     cp.cp_gather_kv(dpool, cp.binding.KVLayout.layer_major(L, H, D, S), S, out, cp.binding.KVLayout.layer_major(L, H, D, N),
                     N, G.dev_i32(src), G.dev_i32(dst), G.dev_i32(ln), None, None, n_sp, 8, None, flags, scratch)
     torch.cuda.synchronize()
@@ -220,3 +220,26 @@ def test_argument_errors_are_reported_not_launched(G):
     with pytest.raises(cp.binding.CpError) as e:
         cp.cp_probe(tab, h, t)
     assert e.value.code == cp.binding.ERR_INVALID_ARG
+
+
+def test_verify_kernel_counts_real_differences(G):
+    """The device-side checker used at full size: agrees with the host generator and reports what differs."""
+    import ctypes as C
+
+    import paper_2605_23640_amd as cp
+
+    L, H, D, n = 3, 2, 64, 37
+    lay = cp.binding.KVLayout.layer_major(L, H, D, n)
+    buf = torch.empty(n * L * 2 * H * D * 2, dtype=torch.uint8, device=G.DEV)
+    kvgen.fill(G.stream_ptr(), C.c_void_p(buf.data_ptr()), G.gen_layout(lay), n, 99, uid_base=1000)
+    host = kvgen.rows_for_tokens(99, np.arange(1000, 1000 + n), L, H * D).transpose(1, 2, 0, 3)
+    assert np.array_equal(G.dst_as_rows(buf, gen.KVShape(L, H, D), n), host)  # device fill == host definition
+    uids = np.arange(1000, 1000 + n, dtype=np.uint64)
+    assert G.verify_rows(buf, lay, uids, 99) == 0
+    wrong = uids.copy()
+    wrong[5] += 1  # one token expected to be another one: (nearly) all its elements differ
+    bad = G.verify_rows(buf, lay, wrong, 99)
+    assert 0.9 * L * 2 * H * D < bad <= L * 2 * H * D
+    assert G.verify_rows(buf, lay, uids, 98) > 0.9 * n * L * 2 * H * D  # another seed: everything differs
+    buf.view(torch.int16)[7] += 1  # a single flipped element is seen
+    assert G.verify_rows(buf, lay, uids, 99) == 1
