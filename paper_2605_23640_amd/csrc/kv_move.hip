@@ -65,14 +65,36 @@ constexpr uint32_t kMaxFanout = 16;      // destinations served per pass over th
 constexpr uint32_t kTrigDoubles = 2048;  // LDS doubles for cos (and as many for sin): fan-out * head_dim/2 <= this
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 
+// cos/sin of (delta * inv_freq[j]) for any 32-bit delta come from five small
+// tables, one per 7-bit digit of |delta|: entry [level][m][j] holds cos and sin of
+// (m << 7*level) * inv_freq[j].  The angles of the digits add up to the exact
+// product, so four complex multiplications give the wanted pair, and the mover
+// needs no trigonometric code of its own.
+constexpr uint32_t kTrigLevels = 5, kTrigDigit = 128;
+
+struct InvFreq {
+  double v[kMaxHalfDim];  // theta^(-2j/head_dim), evaluated on the host
+};
 struct RopeArg {
   uint32_t style, head_dim;
-  double inv_freq[kMaxHalfDim];  // theta^(-2j/head_dim), evaluated on the host
+  const double2 *tables;  // [kTrigLevels][kTrigDigit][head_dim / 2]
 };
-struct NoRope {  // stand-in for kernels that never rotate: keeps their argument block small
+struct NoRope {  // stand-in for kernels that never rotate
   uint32_t style, head_dim;
-  double inv_freq[1];
+  const double2 *tables;
 };
+
+__global__ __launch_bounds__(256) void rope_tables_kernel(InvFreq inv, uint32_t half, double2 *__restrict__ tables) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= kTrigLevels * kTrigDigit * half) return;
+  const uint32_t j = i % half, m = (i / half) % kTrigDigit, level = i / (half * kTrigDigit);
+  const double mult = (double)((uint64_t)m << (7 * level));  // exact
+  const double f = inv.v[j];
+  const double p = mult * f, e = fma(mult, f, -p);  // mult * f = p + e exactly
+  double sn, cs;
+  sincos(p, &sn, &cs);
+  tables[i] = make_double2(cs - e * sn, sn + e * cs);  // first-order correction for the rounded-off part e
+}
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -87,64 +109,89 @@ __device__ __forceinline__ void store16(uint8_t *p, u32x4 v) {
   else *(u32x4 *)p = v;
 }
 
-__device__ __forceinline__ double bf16_to_f64(uint32_t b) { return (double)__uint_as_float(b << 16); }
+// The two bf16 values packed in a dword, as doubles (exact).
+__device__ __forceinline__ double bf16_lo_to_f64(uint32_t w) { return (double)__uint_as_float(w << 16); }
+__device__ __forceinline__ double bf16_hi_to_f64(uint32_t w) { return (double)__uint_as_float(w & 0xFFFF0000u); }
 
-// double -> bf16 bits, one rounding to nearest, ties to even.
-__device__ __forceinline__ uint32_t f64_to_bf16(double x) {
-  const uint64_t u = (uint64_t)__double_as_longlong(x);
-  const uint32_t hi = (uint32_t)(u >> 32), lo = (uint32_t)u;
-  // keep sign(1) exponent(11) mantissa(7): round the bit pattern at bit 13 of the high word
-  uint32_t t = hi + 0xFFFu + (((hi >> 13) & 1u) | (lo != 0u));
-  uint32_t top = t >> 13;
-  int32_t e = (int32_t)((top >> 7) & 0x7FFu) - 896;  // re-bias 1023 -> 127
-  if (e >= 1 && e <= 254) return ((top >> 18) << 15) | ((uint32_t)e << 7) | (top & 0x7Fu);
-  // zero, bf16-subnormal, overflow, inf, nan: go through float with a sticky bit (round to odd)
-  if (x != x) return 0x7FC0u;
-  float f = (float)x;
-  uint32_t b = __float_as_uint(f);
-  double back = (double)f;
-  if (back != x) {
-    if (fabs(back) > fabs(x)) b -= 1u;  // undo a rounding away from zero
-    b |= 1u;
-  }
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return b >> 16;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// A double rounded to float and then to bf16 is rounded twice; the result differs from one direct
+// rounding only if the float happens to sit exactly half way between two bf16 values although the
+// double did not.  Such a float (low half 0x8000, inexact) is nudged one float step back towards
+// the double, after which the second rounding goes the right way.
+__device__ __forceinline__ float toward(float f, double x) {
+  uint32_t u = __float_as_uint(f);
+  const double back = (double)f;
+  if (back != x && x == x) u += fabs(back) > fabs(x) ? 0xFFFFFFFFu : 1u;  // sign-magnitude: -1 shrinks, +1 grows
+  return __uint_as_float(u);
 }
 
-// Rotate the 8 bf16 values of one 16-byte vector.  `own` holds this lane's
-// values, `par` the partner values (half-split) — unused for interleaved.
-// cs points at cos[0..half), sn at sin[0..half) in LDS.
-__device__ __forceinline__ u32x4 rotate_vec(u32x4 own, u32x4 par, uint32_t col_in_head, uint32_t style, uint32_t half,
-                                            const double *cs, const double *sn) {
-  u32x4 out;
+// Two doubles -> two bf16 packed in a dword (x0 low), each with the effect of a single rounding to
+// nearest, ties to even.  The float -> bf16 step is the hardware's packed conversion.
+__device__ __forceinline__ uint32_t f64x2_to_bf16x2(double x0, double x1) {
+  float f0 = (float)x0, f1 = (float)x1;
+  const bool tie0 = (__float_as_uint(f0) & 0xFFFFu) == 0x8000u, tie1 = (__float_as_uint(f1) & 0xFFFFu) == 0x8000u;
+  if (__builtin_expect(tie0 || tie1, 0)) {
+    if (tie0) f0 = toward(f0, x0);
+    if (tie1) f1 = toward(f1, x1);
+  }
+  const bf16x2 r = __builtin_convertvector(f32x2{f0, f1}, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// The cos/sin values one lane needs.  A lane always works on the same 16-byte
+// column of a head (the lane stride, 256 vectors, is a multiple of the vectors
+// per head), so these are loaded once per destination and kept in registers.
+// Half-split style: 8 frequencies, s already carries the lane's sign
+// (first half of the head: y = a*c - b*s, second half: y = a*c + b*s, b being
+// the partner element).  Interleaved style: 4 frequencies in c[0..3], s[0..3].
+struct Trig8 {
+  double c[8], s[8];
+};
+
+__device__ __forceinline__ Trig8 load_trig(uint32_t style, uint32_t half, uint32_t col_in_head, const double *cs,
+                                           const double *sn) {
+  Trig8 t;
   if (style == 0) {
     const uint32_t vec_per_half = half / 8;
     const bool second = col_in_head >= vec_per_half;
     const uint32_t j0 = (second ? col_in_head - vec_per_half : col_in_head) * 8;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      uint32_t r = 0;
-#pragma unroll
-      for (int hlf = 0; hlf < 2; ++hlf) {
-        uint32_t j = j0 + 2 * w + hlf;
-        double a = bf16_to_f64((own[w] >> (16 * hlf)) & 0xFFFFu);
-        double b = bf16_to_f64((par[w] >> (16 * hlf)) & 0xFFFFu);
-        double c = cs[j], s = sn[j];
-        // first half:  a*c - b*s   (b is the second-half partner)
-        // second half: a*c + b*s   (b is the first-half partner)
-        double y = second ? fma(a, c, b * s) : fma(a, c, -(b * s));
-        r |= f64_to_bf16(y) << (16 * hlf);
-      }
-      out[w] = r;
+    for (int e = 0; e < 8; ++e) {
+      t.c[e] = cs[j0 + e];
+      t.s[e] = second ? -sn[j0 + e] : sn[j0 + e];
     }
   } else {
     const uint32_t j0 = col_in_head * 4;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      double a = bf16_to_f64(own[w] & 0xFFFFu), b = bf16_to_f64(own[w] >> 16);
-      double c = cs[j0 + w], s = sn[j0 + w];
-      out[w] = f64_to_bf16(fma(a, c, -(b * s))) | (f64_to_bf16(fma(b, c, a * s)) << 16);
+    for (int e = 0; e < 4; ++e) {
+      t.c[e] = cs[j0 + e];
+      t.s[e] = sn[j0 + e];
+      t.c[e + 4] = t.s[e + 4] = 0.0;
     }
+  }
+  return t;
+}
+
+// Rotate the 8 bf16 values of one 16-byte vector.  `own` holds this lane's
+// values, `par` the partner vector from half a head away (half-split only).
+__device__ __forceinline__ u32x4 rotate_vec(u32x4 own, u32x4 par, uint32_t style, const Trig8 &t) {
+  u32x4 out;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    double y0, y1;  // the rotated values of elements 2w and 2w+1 of the vector
+    if (style == 0) {
+      const double a0 = bf16_lo_to_f64(own[w]), a1 = bf16_hi_to_f64(own[w]);
+      const double b0 = bf16_lo_to_f64(par[w]), b1 = bf16_hi_to_f64(par[w]);
+      y0 = fma(a0, t.c[2 * w], -(b0 * t.s[2 * w]));
+      y1 = fma(a1, t.c[2 * w + 1], -(b1 * t.s[2 * w + 1]));
+    } else {
+      const double a = bf16_lo_to_f64(own[w]), b = bf16_hi_to_f64(own[w]);
+      y0 = fma(a, t.c[w], -(b * t.s[w]));
+      y1 = fma(b, t.c[w], a * t.s[w]);
+    }
+    out[w] = f64x2_to_bf16x2(y0, y1);
   }
   return out;
 }
@@ -204,24 +251,34 @@ __device__ __forceinline__ void move_rows_body(
 
   uint32_t n_items = *n_items_ptr;
   if (n_items > max_items) n_items = max_items;
-  const uint32_t n_rows = fl.n_layers * 2;
-  const uint32_t vpr = fl.n_kv_heads * fl.head_dim / 8;  // 16-byte vectors per row
-  // lane t starts at vector t of the token and advances by 256 vectors per step
+  // A rotating gather hands out two work units per item: the K rows (arithmetic on every element)
+  // and the V rows (plain copies).  Workgroups of both kinds share a compute unit, so the copies'
+  // memory traffic overlaps the rotations' arithmetic.  Otherwise a unit is all rows of the item.
+  const uint32_t parts = ROPE ? 2u : 1u;
+  const uint32_t n_units = n_items * parts;
+  const uint32_t n_rows = ROPE ? fl.n_layers : fl.n_layers * 2;  // rows of one unit
+  const uint32_t vpr = fl.n_kv_heads * fl.head_dim / 8;          // 16-byte vectors per row
+  // lane t starts at vector t of the unit and advances by 256 vectors per step
   const uint32_t r_step = kMoveThreads / vpr, c_step = kMoveThreads % vpr;
   const uint32_t r_init = threadIdx.x / vpr, c_init = threadIdx.x % vpr;
   const uint32_t vph = fl.head_dim / 8;  // vectors per head
+  // column of this lane inside its head: the same at every step, because the lane stride (256
+  // vectors) and the row length are both multiples of the vectors per head
+  const uint32_t cih = threadIdx.x % vph;
   const uint32_t half = fl.head_dim / 2;
   const uint32_t steps = (n_rows * vpr + kMoveThreads - 1) / kMoveThreads;  // same for every lane
 
   if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);
   __syncthreads();
   while (true) {
-    const uint32_t w = s_next_w;  // same value in every lane
-    if (w >= n_items) break;      // the counter only grows: every workgroup gets here
+    const uint32_t unit = s_next_w;  // same value in every lane
+    if (unit >= n_units) break;      // the counter only grows: every workgroup gets here
+    const uint32_t w = unit / parts, part = unit % parts;  // part: 0 = K rows, 1 = V rows (rotating gather)
+    const bool rotating = ROPE && part == 0;
     MoveItem cur = items[w];
     const bool leader = cur.from != kNone && (head == nullptr || head[cur.from] == w);
     __syncthreads();  // everyone has read s_next_w
-    if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);  // fetched while this item is being moved
+    if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);  // fetched while this unit is being moved
     if (leader && cur.from < n_from) {
       const uint8_t *fbase = from + (uint64_t)cur.from * fl.tok_stride;
       uint32_t node = w;
@@ -244,35 +301,40 @@ __device__ __forceinline__ void move_rows_body(
         }
         __syncthreads();
         const uint32_t K = s_k;
-        if (ROPE) {
+        if (rotating) {
           for (uint32_t i = threadIdx.x; i < K * half; i += kMoveThreads) {
             const uint32_t k = i / half, j = i - k * half;
             const int32_t dl = s_delta[k];
             if (dl != 0) {
-              double sn, cs;
-              sincos((double)dl * rope.inv_freq[j], &sn, &cs);
+              uint32_t a = dl < 0 ? 0u - (uint32_t)dl : (uint32_t)dl;  // |delta|, digit by digit
+              double2 t = rope.tables[(a & (kTrigDigit - 1)) * half + j];
+              double cs = t.x, sn = t.y;
+#pragma unroll
+              for (uint32_t level = 1; level < kTrigLevels; ++level) {
+                a >>= 7;
+                t = rope.tables[(level * kTrigDigit + (a & (kTrigDigit - 1))) * half + j];
+                const double c2 = cs * t.x - sn * t.y;  // angles add: multiply the unit vectors
+                sn = sn * t.x + cs * t.y;
+                cs = c2;
+              }
               s_cos[i] = cs;
-              s_sin[i] = sn;
+              s_sin[i] = dl < 0 ? -sn : sn;
             }
           }
           __syncthreads();
         }
         uint32_t r = r_init, c = c_init;
         for (uint32_t j = 0; j < steps; j += U) {
-          u32x4 v[U], par[U];
+          u32x4 v[U];
           uint64_t doff[U];
-          uint32_t cc[U];
-          bool ok[U], is_k[U];
+          bool ok[U];
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             ok[u] = r < n_rows;  // r only grows, so the valid steps of a lane are a prefix
-            const uint64_t l = r >> 1, kv = r & 1;
-            is_k[u] = kv == 0;
-            cc[u] = c;
+            const uint64_t l = ROPE ? r : r >> 1, kv = ROPE ? part : r & 1;
             doff[u] = l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
             v[u] = u32x4{0, 0, 0, 0};
             if (ok[u]) v[u] = load16<NTL>(fbase + l * fl.layer_stride + kv * fl.kv_stride + (uint64_t)c * 16);
-            par[u] = v[u];
             c += c_step;
             r += r_step;
             if (c >= vpr) {
@@ -280,28 +342,39 @@ __device__ __forceinline__ void move_rows_body(
               r += 1;
             }
           }
-          if (ROPE && rope.style == 0) {
-            // partner vector sits half a head away: vph/2 lanes further (all lanes take part)
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-              for (int q = 0; q < 4; ++q) par[u][q] = __shfl_xor(v[u][q], (int)(vph / 2), kWave);
-          }
-          for (uint32_t k = 0; k < K; ++k) {
-            uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
-            const bool rot = ROPE && s_delta[k] != 0;
+          if (rotating) {
+            // vector-outer, destination-inner: the double-precision copies of one vector's elements
+            // are the only ones alive while its destinations are served
 #pragma unroll
             for (int u = 0; u < U; ++u) {
               if (!ok[u]) continue;
-              u32x4 x = v[u];
-              if (rot && is_k[u])
-                x = rotate_vec(v[u], par[u], cc[u] % vph, rope.style, half, s_cos + k * half, s_sin + k * half);
-              store16<NTS>(tbase + doff[u], x);
+              u32x4 par = v[u];
+              if (rope.style == 0) {
+                // the partner vector sits half a head away, vph/2 lanes further; a lane and its
+                // partner are in the same row, so both are here
+#pragma unroll
+                for (int q = 0; q < 4; ++q) par[q] = __shfl_xor(v[u][q], (int)(vph / 2), kWave);
+              }
+              for (uint32_t k = 0; k < K; ++k) {
+                uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
+                u32x4 x = v[u];
+                if (s_delta[k] != 0)
+                  x = rotate_vec(v[u], par, rope.style,
+                                 load_trig(rope.style, half, cih, s_cos + k * half, s_sin + k * half));
+                store16<NTS>(tbase + doff[u], x);
+              }
+            }
+          } else {
+            for (uint32_t k = 0; k < K; ++k) {
+              uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
+#pragma unroll
+              for (int u = 0; u < U; ++u)
+                if (ok[u]) store16<NTS>(tbase + doff[u], v[u]);
             }
           }
         }
         node = s_more;
-        __syncthreads();  // lists and tables are free for the next pass / item
+        __syncthreads();  // lists and tables are free for the next pass / unit
       } while (node != kNone);
     } else {
       if (cur.from != kNone && cur.from >= n_from && threadIdx.x == 0) atomicOr(status_flags, CP_FLAG_BAD_INDEX);
@@ -311,8 +384,10 @@ __device__ __forceinline__ void move_rows_body(
 }
 
 // The two users of the mover get kernels of their own name, so that profiles tell them apart.
+// (at least 4 wavefronts per SIMD: caps the rotating form at 128 registers so that memory latency
+// hides behind the other wavefronts' arithmetic)
 template <class RA, bool ROPE, bool NTL, bool NTS, int U>
-__global__ __launch_bounds__(kMoveThreads) void gather_rows_kernel(
+__global__ __launch_bounds__(kMoveThreads, 4) void gather_rows_kernel(
     const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
     const uint32_t *__restrict__ head, uint32_t *counter, const uint8_t *__restrict__ pool, cp_kv_layout pool_l,
     uint32_t n_pool_slots, uint8_t *__restrict__ dst, cp_kv_layout dst_l, uint32_t n_dst_tokens, uint32_t fanout,
@@ -349,8 +424,10 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
                     void *to, const cp_kv_layout &tl, uint32_t n_to, uint32_t *status_flags, const RA &rope) {
   if (max_items == 0) return CP_OK;
   const Tuning &tn = tuning();
-  uint64_t grid = (uint64_t)cu_count() * (tn.move_blocks_per_cu ? tn.move_blocks_per_cu : 8);
-  if (grid > max_items) grid = max_items;
+  uint32_t bpc = ROPE ? tn.move_blocks_per_cu_rope : tn.move_blocks_per_cu;
+  uint64_t grid = (uint64_t)cu_count() * (bpc ? bpc : 2);
+  const uint64_t max_units = (uint64_t)max_items * (ROPE ? 2 : 1);
+  if (grid > max_units) grid = max_units;
   uint32_t fanout = kMaxFanout;
   if (ROPE) {
     uint32_t cap = kTrigDoubles / (fl.head_dim / 2);
@@ -358,23 +435,32 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   }
   const uint8_t *f = (const uint8_t *)from;
   uint8_t *t = (uint8_t *)to;
-#define CP_LAUNCH(NTL, NTS, UN)                                                                             \
-  if (GATHER)                                                                                               \
-    gather_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                \
-        items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope);  \
-  else                                                                                                      \
-    scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(               \
+#define CP_LAUNCH(NTL, NTS, UN)                                                                              \
+  if constexpr (GATHER)                                                                                      \
+    gather_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                 \
+        items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope);   \
+  else                                                                                                       \
+    scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                \
         items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope)
-  const bool deep = !ROPE && tn.move_unroll >= 8;  // rotation keeps the short form: it needs the registers
-  switch ((tn.move_nontemporal & 3u) | (deep ? 4u : 0u)) {
-    case 0: CP_LAUNCH(false, false, 4); break;
-    case 1: CP_LAUNCH(true, false, 4); break;
-    case 2: CP_LAUNCH(false, true, 4); break;
-    case 3: CP_LAUNCH(true, true, 4); break;
-    case 4: CP_LAUNCH(false, false, 8); break;
-    case 5: CP_LAUNCH(true, false, 8); break;
-    case 6: CP_LAUNCH(false, true, 8); break;
-    default: CP_LAUNCH(true, true, 8); break;
+  const uint32_t nt = tn.move_nontemporal & 3u;
+  if constexpr (ROPE) {  // rotation keeps the short form: it needs the registers
+    switch (nt) {
+      case 0: CP_LAUNCH(false, false, 4); break;
+      case 1: CP_LAUNCH(true, false, 4); break;
+      case 2: CP_LAUNCH(false, true, 4); break;
+      default: CP_LAUNCH(true, true, 4); break;
+    }
+  } else {
+    switch (nt | (tn.move_unroll >= 8 ? 4u : 0u)) {
+      case 0: CP_LAUNCH(false, false, 4); break;
+      case 1: CP_LAUNCH(true, false, 4); break;
+      case 2: CP_LAUNCH(false, true, 4); break;
+      case 3: CP_LAUNCH(true, true, 4); break;
+      case 4: CP_LAUNCH(false, false, 8); break;
+      case 5: CP_LAUNCH(true, false, 8); break;
+      case 6: CP_LAUNCH(false, true, 8); break;
+      default: CP_LAUNCH(true, true, 8); break;
+    }
   }
 #undef CP_LAUNCH
   return check_launch();
@@ -413,7 +499,6 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
     if (rope->style > 1 || !(rope->theta > 0.0)) return CP_ERR_INVALID_ARG;
     ra.style = rope->style;
     ra.head_dim = D;
-    for (uint32_t j = 0; j < D / 2; ++j) ra.inv_freq[j] = std::pow(rope->theta, -2.0 * (double)j / (double)D);
   }
   if (scratch_bytes < cp_scratch_bytes(n_dst_tokens, max_spans, n_pool_slots)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
@@ -423,7 +508,15 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
   MoveItem *items = sc.take<MoveItem>(n_dst_tokens);
   const bool group = tuning().move_multicast != 0;
   uint32_t *head = group ? sc.take<uint32_t>(n_pool_slots) : nullptr;
-  if (!agg || !offs || !counters || !items || (group && !head)) return CP_ERR_SCRATCH;
+  double2 *tables = use_rope ? sc.take<double2>((size_t)kTrigLevels * kTrigDigit * (pool_l.head_dim / 2)) : nullptr;
+  if (!agg || !offs || !counters || !items || (group && !head) || (use_rope && !tables)) return CP_ERR_SCRATCH;
+  if (use_rope) {
+    InvFreq inv{};
+    const uint32_t D = pool_l.head_dim;
+    for (uint32_t j = 0; j < D / 2; ++j) inv.v[j] = std::pow(rope->theta, -2.0 * (double)j / (double)D);
+    rope_tables_kernel<<<div_up((uint64_t)kTrigLevels * kTrigDigit * (D / 2), 256), 256, 0, stream>>>(inv, D / 2, tables);
+    ra.tables = tables;
+  }
   if (!span_off) {
     if (int32_t rc = launch_span_offsets(stream, span_len, n_spans, max_spans, offs, agg)) return rc;
     span_off = offs;
@@ -484,9 +577,10 @@ extern "C" size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans, uint32_t n_po
   using namespace cp;
   uint64_t n = N > max_spans ? N : max_spans;
   // tile totals (16 bytes each), three per-token words (insert) and one 16-byte descriptor per
-  // token (gather, insert), span offsets, one chain head per pool slot; pieces padded to 256 bytes
+  // token (gather, insert), span offsets, one chain head per pool slot, the cos/sin digit tables;
+  // pieces padded to 256 bytes
   return (size_t)(((uint64_t)div_up(n, kScanTile) + 2) * 16 + (3ull * 4 + 16) * N + 4ull * ((uint64_t)max_spans + 1) +
-                  4ull * n_pool_slots + 12 * 256);
+                  4ull * n_pool_slots + (size_t)kTrigLevels * kTrigDigit * kMaxHalfDim * sizeof(double2) + 12 * 256);
 }
 
 extern "C" int32_t cp_last_hip_error(void) { return cp::last_hip_error(); }
@@ -498,6 +592,7 @@ extern "C" int32_t cp_tune(int32_t key, uint32_t value) {
     case 1: t.move_blocks_per_cu = value; return CP_OK;
     case 2: t.move_nontemporal = value; return CP_OK;
     case 3: t.move_unroll = value; return CP_OK;
+    case 4: t.move_blocks_per_cu_rope = value; return CP_OK;
     default: return CP_ERR_INVALID_ARG;
   }
 }
