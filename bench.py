@@ -49,7 +49,7 @@ def cpu_baseline(wl, n_requests, G, torch, np):
     from cp_workload import gen
     from oracle import harness as OH
 
-    sw = gen.subsample(wl, n_requests, pool_slots=1 << 15)
+    sw = gen.subsample(wl, n_requests, pool_slots=1 << 17)
     sh = sw.shape
     n_d = len(sw.donor_tok)
     re = sh.row_bytes // 2
@@ -89,7 +89,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3-8b", choices=["tiny", "llama3-8b", "frag", "rope", "llama3-70b"])
-    ap.add_argument("--cpu-requests", type=int, default=4, help="requests in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
     ap.add_argument("--nontemporal", type=int, default=None, help="cp_tune key 2")
