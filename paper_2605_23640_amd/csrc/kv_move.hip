@@ -75,12 +75,13 @@ constexpr uint32_t kTrigLevels = 5, kTrigDigit = 128;
 struct InvFreq {
   double v[kMaxHalfDim];  // theta^(-2j/head_dim), evaluated on the host
 };
+template <uint32_t STYLE>  // the pairing style is a compile-time property of the kernel
 struct RopeArg {
-  uint32_t style, head_dim;
+  static constexpr uint32_t style = STYLE;
   const double2 *tables;  // [kTrigLevels][kTrigDigit][head_dim / 2]
 };
 struct NoRope {  // stand-in for kernels that never rotate
-  uint32_t style, head_dim;
+  static constexpr uint32_t style = 0;
   const double2 *tables;
 };
 
@@ -140,60 +141,93 @@ __device__ __forceinline__ uint32_t f64x2_to_bf16x2(double x0, double x1) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-// The cos/sin values one lane needs.  A lane always works on the same 16-byte
-// column of a head (the lane stride, 256 vectors, is a multiple of the vectors
-// per head), so these are loaded once per destination and kept in registers.
-// Half-split style: 8 frequencies, s already carries the lane's sign
-// (first half of the head: y = a*c - b*s, second half: y = a*c + b*s, b being
-// the partner element).  Interleaved style: 4 frequencies in c[0..3], s[0..3].
-struct Trig8 {
-  double c[8], s[8];
+// Rotation of one 16-byte vector (8 bf16 values) of a K row.
+//
+// A lane always works on the same 16-byte column of a head (the lane stride, 256 vectors, and the
+// row length are multiples of the vectors per head), so which frequencies it needs is fixed.
+//
+// Half-split style (element j pairs with j + head_dim/2): the lane `vph/2` further holds the partner
+// vector.  The two lanes split the eight pairs between them — the first-half lane does pairs 0..3,
+// the second-half lane pairs 4..7 — and each computes BOTH outputs of its pairs, so every input is
+// widened to double once and every lane needs only four cos/sin pairs.  Two dwords go each way
+// before (the partner's inputs for my pairs) and after (the partner's half of the results).
+//
+// Interleaved style (2j pairs with 2j+1): both elements of a pair are in the lane's own vector;
+// four pairs, four cos/sin pairs, no exchange.
+struct Trig4 {
+  double c[4], s[4];
 };
 
-__device__ __forceinline__ Trig8 load_trig(uint32_t style, uint32_t half, uint32_t col_in_head, const double *cs,
-                                           const double *sn) {
-  Trig8 t;
-  if (style == 0) {
+// Index of the first of the four frequencies this lane works on.
+template <uint32_t STYLE>
+__device__ __forceinline__ uint32_t first_freq(uint32_t half, uint32_t col_in_head) {
+  if (STYLE == 0) {
     const uint32_t vec_per_half = half / 8;
     const bool second = col_in_head >= vec_per_half;
-    const uint32_t j0 = (second ? col_in_head - vec_per_half : col_in_head) * 8;
+    return (second ? col_in_head - vec_per_half : col_in_head) * 8 + (second ? 4u : 0u);
+  }
+  return col_in_head * 4;
+}
+
+__device__ __forceinline__ Trig4 load_trig(uint32_t j0, const double *cs, const double *sn) {
+  Trig4 t;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      t.c[e] = cs[j0 + e];
-      t.s[e] = second ? -sn[j0 + e] : sn[j0 + e];
-    }
-  } else {
-    const uint32_t j0 = col_in_head * 4;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      t.c[e] = cs[j0 + e];
-      t.s[e] = sn[j0 + e];
-      t.c[e + 4] = t.s[e + 4] = 0.0;
-    }
+  for (int e = 0; e < 4; ++e) {
+    t.c[e] = cs[j0 + e];
+    t.s[e] = sn[j0 + e];
   }
   return t;
 }
 
-// Rotate the 8 bf16 values of one 16-byte vector.  `own` holds this lane's
-// values, `par` the partner vector from half a head away (half-split only).
-__device__ __forceinline__ u32x4 rotate_vec(u32x4 own, u32x4 par, uint32_t style, const Trig8 &t) {
-  u32x4 out;
+// The inputs of this lane's four pairs as doubles: x1 from the first half of the head (or the even
+// elements), x2 from the second half (or the odd elements).
+struct Pairs4 {
+  double x1[4], x2[4];
+};
+
+template <uint32_t STYLE>
+__device__ __forceinline__ Pairs4 widen_pairs(u32x4 own, bool second, int partner_xor) {
+  Pairs4 p;
+  if (STYLE == 0) {
+    // my pairs use dwords 0..1 (first-half lane) or 2..3 (second-half lane) of both vectors;
+    // the partner needs the other two dwords of mine
+    const uint32_t mine0 = second ? own[2] : own[0], mine1 = second ? own[3] : own[1];
+    const uint32_t give0 = second ? own[0] : own[2], give1 = second ? own[1] : own[3];
+    const uint32_t got0 = __shfl_xor(give0, partner_xor, kWave), got1 = __shfl_xor(give1, partner_xor, kWave);
+    const uint32_t f0 = second ? got0 : mine0, f1 = second ? got1 : mine1;  // first-half elements
+    const uint32_t g0 = second ? mine0 : got0, g1 = second ? mine1 : got1;  // second-half elements
+    p.x1[0] = bf16_lo_to_f64(f0), p.x1[1] = bf16_hi_to_f64(f0), p.x1[2] = bf16_lo_to_f64(f1), p.x1[3] = bf16_hi_to_f64(f1);
+    p.x2[0] = bf16_lo_to_f64(g0), p.x2[1] = bf16_hi_to_f64(g0), p.x2[2] = bf16_lo_to_f64(g1), p.x2[3] = bf16_hi_to_f64(g1);
+  } else {
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    double y0, y1;  // the rotated values of elements 2w and 2w+1 of the vector
-    if (style == 0) {
-      const double a0 = bf16_lo_to_f64(own[w]), a1 = bf16_hi_to_f64(own[w]);
-      const double b0 = bf16_lo_to_f64(par[w]), b1 = bf16_hi_to_f64(par[w]);
-      y0 = fma(a0, t.c[2 * w], -(b0 * t.s[2 * w]));
-      y1 = fma(a1, t.c[2 * w + 1], -(b1 * t.s[2 * w + 1]));
-    } else {
-      const double a = bf16_lo_to_f64(own[w]), b = bf16_hi_to_f64(own[w]);
-      y0 = fma(a, t.c[w], -(b * t.s[w]));
-      y1 = fma(b, t.c[w], a * t.s[w]);
+    for (int w = 0; w < 4; ++w) {
+      p.x1[w] = bf16_lo_to_f64(own[w]);
+      p.x2[w] = bf16_hi_to_f64(own[w]);
     }
-    out[w] = f64x2_to_bf16x2(y0, y1);
   }
-  return out;
+  return p;
+}
+
+template <uint32_t STYLE>
+__device__ __forceinline__ u32x4 rotate_pairs(const Pairs4 &p, const Trig4 &t, bool second, int partner_xor) {
+  double y1[4], y2[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    y1[e] = fma(p.x1[e], t.c[e], -(p.x2[e] * t.s[e]));
+    y2[e] = fma(p.x2[e], t.c[e], p.x1[e] * t.s[e]);
+  }
+  if (STYLE == 0) {
+    // y1 belongs to the first-half lane's vector, y2 to the second-half lane's
+    const uint32_t a0 = f64x2_to_bf16x2(y1[0], y1[1]), a1 = f64x2_to_bf16x2(y1[2], y1[3]);
+    const uint32_t b0 = f64x2_to_bf16x2(y2[0], y2[1]), b1 = f64x2_to_bf16x2(y2[2], y2[3]);
+    const uint32_t keep0 = second ? b0 : a0, keep1 = second ? b1 : a1;
+    const uint32_t got0 = __shfl_xor(second ? a0 : b0, partner_xor, kWave);
+    const uint32_t got1 = __shfl_xor(second ? a1 : b1, partner_xor, kWave);
+    // first-half lane: its own pairs 0..3 then the partner's 4..7; second-half lane the other way round
+    return second ? u32x4{got0, got1, keep0, keep1} : u32x4{keep0, keep1, got0, got1};
+  }
+  return u32x4{f64x2_to_bf16x2(y1[0], y2[0]), f64x2_to_bf16x2(y1[1], y2[1]), f64x2_to_bf16x2(y1[2], y2[2]),
+               f64x2_to_bf16x2(y1[3], y2[3])};
 }
 
 // ---- gather front end: clear the per-slot chain heads, expand spans, link chains -------------
@@ -265,6 +299,8 @@ __device__ __forceinline__ void move_rows_body(
   // column of this lane inside its head: the same at every step, because the lane stride (256
   // vectors) and the row length are both multiples of the vectors per head
   const uint32_t cih = threadIdx.x % vph;
+  const bool second = cih >= vph / 2;                          // lane holds second-half elements of its head
+  const uint32_t j_first = first_freq<RA::style>(fl.head_dim / 2, cih);  // its four frequencies start here
   const uint32_t half = fl.head_dim / 2;
   const uint32_t steps = (n_rows * vpr + kMoveThreads - 1) / kMoveThreads;  // same for every lane
 
@@ -348,19 +384,14 @@ __device__ __forceinline__ void move_rows_body(
 #pragma unroll
             for (int u = 0; u < U; ++u) {
               if (!ok[u]) continue;
-              u32x4 par = v[u];
-              if (rope.style == 0) {
-                // the partner vector sits half a head away, vph/2 lanes further; a lane and its
-                // partner are in the same row, so both are here
-#pragma unroll
-                for (int q = 0; q < 4; ++q) par[q] = __shfl_xor(v[u][q], (int)(vph / 2), kWave);
-              }
+              // a lane and its partner are in the same row, so both are here for the exchanges
+              const Pairs4 pairs = widen_pairs<RA::style>(v[u], second, (int)(vph / 2));
               for (uint32_t k = 0; k < K; ++k) {
                 uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
                 u32x4 x = v[u];
                 if (s_delta[k] != 0)
-                  x = rotate_vec(v[u], par, rope.style,
-                                 load_trig(rope.style, half, cih, s_cos + k * half, s_sin + k * half));
+                  x = rotate_pairs<RA::style>(pairs, load_trig(j_first, s_cos + k * half, s_sin + k * half), second,
+                                              (int)(vph / 2));
                 store16<NTS>(tbase + doff[u], x);
               }
             }
@@ -491,14 +522,11 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
   if (!scratch || !aligned(scratch, 256) || !aligned(pool, 16) || !aligned(dst, 16)) return CP_ERR_INVALID_ARG;
   if (!layout_ok(pool_l) || !layout_ok(dst_l) || !layouts_match(pool_l, dst_l)) return CP_ERR_UNSUPPORTED;
   const bool use_rope = rope != nullptr && span_delta != nullptr;
-  RopeArg ra{};
   if (use_rope) {
     const uint32_t D = pool_l.head_dim;
     // pairs must not straddle 16-byte vectors or wavefronts: power-of-two head_dim in [16, 512]
     if (D < 16 || D > 2 * kMaxHalfDim || (D & (D - 1))) return CP_ERR_UNSUPPORTED;
     if (rope->style > 1 || !(rope->theta > 0.0)) return CP_ERR_INVALID_ARG;
-    ra.style = rope->style;
-    ra.head_dim = D;
   }
   if (scratch_bytes < cp_scratch_bytes(n_dst_tokens, max_spans, n_pool_slots)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
@@ -515,7 +543,6 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
     const uint32_t D = pool_l.head_dim;
     for (uint32_t j = 0; j < D / 2; ++j) inv.v[j] = std::pow(rope->theta, -2.0 * (double)j / (double)D);
     rope_tables_kernel<<<div_up((uint64_t)kTrigLevels * kTrigDigit * (D / 2), 256), 256, 0, stream>>>(inv, D / 2, tables);
-    ra.tables = tables;
   }
   if (!span_off) {
     if (int32_t rc = launch_span_offsets(stream, span_len, n_spans, max_spans, offs, agg)) return rc;
@@ -531,9 +558,12 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
   const Tuning &tn = tuning();
   if (tn.gather_start && hipEventRecord(tn.gather_start, stream) != hipSuccess) return CP_ERR_HIP;
   int32_t rc;
-  if (use_rope) {
-    rc = launch_move<RopeArg, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                    n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, ra);
+  if (use_rope && rope->style == 0) {
+    rc = launch_move<RopeArg<0>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                             n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<0>{tables});
+  } else if (use_rope) {
+    rc = launch_move<RopeArg<1>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                             n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<1>{tables});
   } else {
     NoRope none{};
     rc = launch_move<NoRope, false, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
