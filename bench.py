@@ -35,8 +35,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command, scaled by what the same counters read for kernels of known size
-# (profiles/gather_rows_kernel_llama3-8b.txt); None for workloads not profiled that way.
-MEASURED_TRAFFIC = {"llama3-8b": 9038385933}
+# (profiles/gather_rows_kernel_<workload>.txt); None for workloads not profiled that way.
+MEASURED_TRAFFIC = {"llama3-8b": 9038385933, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522}
 
 
 def log(*a):
