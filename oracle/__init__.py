@@ -75,6 +75,14 @@ def lib():
         L.cpo_gather_kv.argtypes = [vp, Layout, vp, Layout, vp, vp, vp, vp, u32, vp]
         L.cpo_insert_kv.restype = u32
         L.cpo_insert_kv.argtypes = [vp, vp, vp, u32, vp, u32, vp, Layout, vp, Layout, vp, vp, vp, vp, vp]
+        L.cpo_anchor_set_new.restype = vp
+        L.cpo_anchor_set_free.argtypes = [vp]
+        L.cpo_anchor_set_size.restype = u64
+        L.cpo_anchor_set_size.argtypes = [vp]
+        L.cpo_run_offsets.argtypes = [vp, vp, u32, vp]
+        L.cpo_insert_anchors.argtypes = [vp, vp, vp, u32, u32]
+        L.cpo_hash_floating.argtypes = [vp, vp, vp, u32, u64, u32, vp]
+        L.cpo_probe2.argtypes = [vp, vp, vp, u32, vp]
         L.cpo_bf16_to_double.restype = C.c_double
         L.cpo_bf16_to_double.argtypes = [C.c_uint16]
         L.cpo_double_to_bf16.restype = C.c_uint16
@@ -107,6 +115,47 @@ class Index:
         if getattr(self, "_h", None) and _lib is not None:
             _lib.cpo_index_free(self._h)
             self._h = None
+
+
+class AnchorSet:
+    """The stored runs' prefix hashes (floating-anchor lookup)."""
+
+    def __init__(self):
+        self._h = C.c_void_p(lib().cpo_anchor_set_new())
+
+    def __len__(self):
+        return int(lib().cpo_anchor_set_size(self._h))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.cpo_anchor_set_free(self._h)
+            self._h = None
+
+
+def run_offsets(mask, off):
+    mask, off = _arr(mask, np.uint8), _arr(off, np.uint32)
+    out = np.empty(mask.shape[0], np.uint32)
+    lib().cpo_run_offsets(_p(mask), _p(off), len(off) - 1, _p(out))
+    return out
+
+
+def insert_anchors(anchors: AnchorSet, hashes, run_off, W):
+    hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
+    lib().cpo_insert_anchors(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], int(W))
+
+
+def hash_floating(anchors: AnchorSet, hashes, run_off, W, base=BASE):
+    hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
+    out = np.empty(hashes.shape[0], np.uint64)
+    lib().cpo_hash_floating(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], base, int(W), _p(out))
+    return out
+
+
+def probe2(index: Index, hash_a, hash_b):
+    hash_a, hash_b = _arr(hash_a, np.uint64), _arr(hash_b, np.uint64)
+    out = np.empty(hash_a.shape[0], np.uint32)
+    lib().cpo_probe2(index._h, _p(hash_a), _p(hash_b), hash_a.shape[0], _p(out))
+    return out
 
 
 def hash_segments(tok, mask, off, base=BASE):

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstring>
 #include <unordered_map>
+#include <unordered_set>
 #include <vector>
 
 struct cpo_index {
@@ -221,4 +222,91 @@ extern "C" uint32_t cpo_insert_kv(cpo_index *ix, const uint64_t *hash, const uin
     }
   }
   return n_new;
+}
+
+// ---- floating anchors (Sec. 4.2.2 Step 1 and Step 2) -------------------------------------------
+
+struct cpo_anchor_set {
+  std::unordered_set<uint64_t> set;
+};
+
+extern "C" cpo_anchor_set *cpo_anchor_set_new(void) { return new cpo_anchor_set(); }
+extern "C" void cpo_anchor_set_free(cpo_anchor_set *a) { delete a; }
+extern "C" uint64_t cpo_anchor_set_size(const cpo_anchor_set *a) { return a->set.size(); }
+
+extern "C" void cpo_run_offsets(const uint8_t *mask, const uint32_t *off, uint32_t R,
+                                uint32_t *run_off_out) {
+  for (uint32_t r = 0; r < R; ++r) {
+    uint32_t n = 0;  // non-sensitive tokens seen since the run started
+    for (uint32_t i = off[r]; i < off[r + 1]; ++i) {
+      if (mask[i]) {
+        run_off_out[i] = 0xFFFFFFFFu;
+        n = 0;
+      } else {
+        run_off_out[i] = n++;
+      }
+    }
+  }
+}
+
+extern "C" void cpo_insert_anchors(cpo_anchor_set *as, const uint64_t *hash, const uint32_t *run_off,
+                                   uint32_t N, uint32_t W) {
+  for (uint32_t i = 0; i < N; ++i)
+    if (hash[i] != CPO_HASH_NONE && run_off[i] == W - 1) as->set.insert(hash[i]);
+}
+
+extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const uint64_t *hash,
+                                  const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
+                                  uint64_t *hash_float_out) {
+  // precomputed powers of the base
+  std::vector<uint64_t> pw((size_t)N + 1);
+  pw[0] = 1;
+  for (uint32_t k = 1; k <= N; ++k) pw[k] = pw[k - 1] * base;
+  // hash of tokens a..i of one run, from the run's chain hashes: h[i] - h[a-1] * base^(i-a+1)
+  auto sub = [&](uint32_t a, uint32_t i) {
+    uint64_t before = run_off[a] == 0 ? 0 : hash[a - 1];
+    return hash[i] - before * pw[i - a + 1];
+  };
+  // Step 1: slide the window; window ending at i starts at a = i - W + 1
+  std::vector<uint8_t> anchor_at(N, 0);
+  for (uint32_t i = 0; i < N; ++i) {
+    if (hash[i] == CPO_HASH_NONE || run_off[i] + 1 < W) continue;  // window would leave the run
+    uint32_t a = i - (W - 1);
+    if (run_off[a] == 0) continue;  // at the run start the plain chain hash already is this key
+    if (as->set.count(sub(a, i))) anchor_at[a] = 1;
+  }
+  // Step 2: key of every token from its latest anchor
+  bool have = false;
+  uint32_t a = 0;
+  for (uint32_t i = 0; i < N; ++i) {
+    hash_float_out[i] = CPO_HASH_NONE;
+    if (hash[i] == CPO_HASH_NONE) {
+      have = false;
+      continue;
+    }
+    if (run_off[i] == 0) have = false;  // a new run
+    if (anchor_at[i]) {
+      have = true;
+      a = i;
+    }
+    if (have) {
+      uint64_t h = sub(a, i);
+      hash_float_out[i] = (h == CPO_HASH_NONE) ? CPO_HASH_NONE - 1 : h;
+    }
+  }
+}
+
+extern "C" void cpo_probe2(const cpo_index *ix, const uint64_t *hash_a, const uint64_t *hash_b,
+                           uint32_t N, uint32_t *slot_out) {
+  for (uint32_t i = 0; i < N; ++i) {
+    slot_out[i] = CPO_SLOT_NONE;
+    for (const uint64_t *h : {hash_a, hash_b}) {
+      if (h[i] == CPO_HASH_NONE) continue;
+      auto it = ix->map.find(h[i]);
+      if (it != ix->map.end()) {
+        slot_out[i] = it->second;
+        break;
+      }
+    }
+  }
 }

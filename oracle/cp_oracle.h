@@ -109,6 +109,36 @@ uint32_t cpo_insert_kv(cpo_index *, const uint64_t *hash, const uint32_t *off, u
                        uint32_t *slot_out, uint32_t *flags, const uint32_t *tok,
                        uint32_t *slot_tok);
 
+/* ---- Floating anchors (Sec. 4.2.2, Step 1 "prefix filtering" and Step 2's O(1) substring hash) ----
+ * The pool also keeps, for every stored run of at least W tokens, the rolling hash of its first W
+ * tokens.  A lookup slides a W-token window over each run of the request; where the window's hash is
+ * one of the stored prefix hashes, a stored run may start there ("anchor"), and the tokens from
+ * there on get a second key: the hash of the request's tokens from the anchor through the token,
+ * computed in O(1) from the run's chain hashes and a power of the base.  A token is served under
+ * its run-start key if that hits, else under the key of the latest anchor at or before it. */
+typedef struct cpo_anchor_set cpo_anchor_set; /* set of prefix hashes. Opaque. */
+cpo_anchor_set *cpo_anchor_set_new(void);
+void cpo_anchor_set_free(cpo_anchor_set *);
+uint64_t cpo_anchor_set_size(const cpo_anchor_set *);
+
+/* run_off_out[i] = number of non-sensitive tokens between the start of token i's run and i
+ * (0 for the first token of a run), 0xFFFFFFFF for sensitive tokens. */
+void cpo_run_offsets(const uint8_t *mask, const uint32_t *off, uint32_t R, uint32_t *run_off_out);
+
+/* Store the prefix hash of every run that has at least W tokens: the chain hash of its W-th token. */
+void cpo_insert_anchors(cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off, uint32_t N,
+                        uint32_t W);
+
+/* hash_float_out[i] = hash of the tokens from the latest anchor a <= i of i's run through i, where
+ * an anchor is a position a > run start such that the W tokens from a lie inside the run and their
+ * hash is in the set; CPO_HASH_NONE where there is no such anchor (and for sensitive tokens). */
+void cpo_hash_floating(const cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off,
+                       uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out);
+
+/* Lookup with two keys per token: slot under hash_a if present, else under hash_b, else NONE. */
+void cpo_probe2(const cpo_index *, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
+                uint32_t *slot_out);
+
 /* Building blocks exposed so that tests can pin them one by one. */
 double cpo_bf16_to_double(uint16_t bits);
 uint16_t cpo_double_to_bf16(double x); /* round-to-nearest-even, one rounding */
