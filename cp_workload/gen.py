@@ -196,7 +196,9 @@ def make_tiny(seed=0xC0FFEE01, T=512, n_donors=8, pool_slots=4096, shape=KVShape
 
 
 def make_docs(name, seed, shape, R, T, prefix_len, n_docs, doc_len, docs_per_request, run_mean, cover,
-              pool_slots, table_capacity=None, donor_batch_tokens=1 << 17):
+              pool_slots, table_capacity=None, donor_batch_tokens=1 << 17, lead_len=None):
+    """Requests = shared prefix [+ a unique non-sensitive lead of lead_len=(lo, hi) tokens] + documents + the
+    user's own text; donors = prefix + one document each."""
     rng = np.random.default_rng(seed)
     prefix = _tokens(rng, prefix_len)
     docs, dmasks = [], []
@@ -209,6 +211,11 @@ def make_docs(name, seed, shape, R, T, prefix_len, n_docs, doc_len, docs_per_req
         chosen = rng.choice(n_docs, size=min(docs_per_request, n_docs), replace=False)
         pt, pm, n = [prefix], [np.zeros(prefix_len, np.uint8)], prefix_len
         used = []
+        if lead_len is not None:  # text of this request alone, in the same run as the document after it
+            ln = int(rng.integers(lead_len[0], lead_len[1] + 1))
+            pt.append(_tokens(rng, ln))
+            pm.append(np.zeros(ln, np.uint8))
+            n += ln
         for d in chosen:
             room = T - n
             if room <= 0:
@@ -253,6 +260,19 @@ def make_llama70b(seed=0xC0FFEE05, scale=1.0, shape=KVShape(80, 8, 128)):
                      doc_len=(max(4, round(1024 * s)), max(8, round(2048 * s))), docs_per_request=16,
                      run_mean=12.0, cover=0.10, pool_slots=max(256, round(393216 * s)),
                      donor_batch_tokens=max(1024, round(65536 * min(1.0, s * 4))))
+
+
+def make_float(seed=0xC0FFEE06, scale=1.0, shape=KVShape(32, 8, 128)):
+    """Documents stored on their own (their runs start at the document's first token) and
+    retrieved into requests behind text that differs per request: the part of a document up to
+    its first sensitive token continues the run of whatever precedes it, so only a floating
+    anchor (Sec. 4.2.2 Step 1) finds it; later runs match by their run-start keys as well."""
+    s = scale
+    return make_docs("float", seed, shape, R=max(2, round(16 * s)), T=max(64, round(4096 * s)),
+                     prefix_len=0, n_docs=max(4, round(64 * s)),
+                     doc_len=(max(4, round(512 * s)), max(8, round(1024 * s))), docs_per_request=4,
+                     run_mean=8.0, cover=0.02, pool_slots=max(256, round(262144 * s)),
+                     lead_len=(max(1, round(16 * s)), max(2, round(256 * s))))
 
 
 # --------------------------------------------------------------------------
@@ -440,6 +460,7 @@ WORKLOADS = {
     "frag": make_frag,
     "rope": make_rope,
     "llama3-70b": make_llama70b,
+    "float": make_float,
 }
 
 

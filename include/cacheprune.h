@@ -134,6 +134,35 @@ int32_t cp_hash_segments(void *stream, const uint32_t *tok, const uint8_t *mask,
  * or hash[i] is CP_HASH_NONE.  A sensitive token is therefore never served. */
 int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out);
 
+/* ---- Floating anchors: matches that do not start at the start of a run --------------------------
+ * Sec. 4.2.2 Step 1 ("prefix filtering"): every stored segment keeps the hash of its first W tokens;
+ * a W-token window slides over the request and is compared with those prefix hashes.  Step 2: the
+ * hash of any substring follows in O(1) from prefix hashes and a power of the base.  Here:
+ *   - cp_hash_runs is cp_hash_segments that also returns run_off[i], the number of tokens between
+ *     the start of token i's run and i (0xFFFFFFFF for sensitive tokens);
+ *   - cp_insert_anchors stores, for every run of at least W tokens, the chain hash of its W-th
+ *     token (= the hash of its first W tokens) in a second table `anchors` used as a set
+ *     (CP_FLAG_TABLE_FULL if it has no room);
+ *   - cp_hash_floating marks as anchor every position a after its run's start whose W-token window
+ *     lies inside the run and hashes to a key of `anchors`, and gives every token i the key of the
+ *     request's tokens a..i for the latest anchor a <= i of its run:
+ *         hash_float_out[i] = hash[i] - hash[a-1] * base^(i-a+1)   (mod 2^64; CP_HASH_NONE -> NONE-1),
+ *     CP_HASH_NONE where there is no such anchor.  That key equals the chain hash the same tokens
+ *     get as the beginning of a stored run, so it is looked up in the ordinary table;
+ *   - cp_probe2 looks every token up under hash_a and, if that misses, under hash_b.
+ * A token is thus served under its run-start key if possible, else from its latest anchor.
+ * `base` must be odd.  W >= 1. */
+int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
+                     uint32_t R, uint64_t base, uint64_t *hash_out, uint32_t *run_off_out, void *scratch,
+                     size_t scratch_bytes);
+int32_t cp_insert_anchors(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
+                          uint32_t N, uint32_t W, uint32_t *status_flags);
+int32_t cp_hash_floating(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
+                         uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out, void *scratch,
+                         size_t scratch_bytes);
+int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
+                  uint32_t *slot_out);
+
 /* Run-length pass: turn per-token slots into copy descriptors (the "token
  * spans" of the retriever's metadata, Sec. 4.3.1).  A span is a maximal run of
  * consecutive positions of one request whose slots are valid and consecutive

@@ -46,12 +46,15 @@ class OracleState:
     donor_hash: np.ndarray | None = None
     donor_slot: np.ndarray | None = None  # slot_out of every donor token
     times: dict = field(default_factory=dict)
+    anchors: O.AnchorSet | None = None  # floating anchors: hashes of the stored runs' first W tokens
+    anchor_window: int | None = None
 
 
-def prefill(wl, src_provider=None, pool=None, flags_out=None) -> OracleState:
+def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None) -> OracleState:
     """Insert the donor prompts batch by batch.  ``src_provider(first_tok, n_tok)``
     returns the layer-major KV buffer of a donor batch (default: host generator,
-    uid = packed donor index)."""
+    uid = packed donor index).  With ``anchor_window`` = W the hash of every
+    stored run's first W tokens is also recorded as a floating anchor."""
     sh = wl.shape
     re = sh.row_bytes // 2
     if pool is None:
@@ -63,6 +66,9 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None) -> OracleState:
         slot_uid=np.full(wl.pool_slots, kvgen.UID_NONE, np.uint64),
     )
     st.donor_hash = O.hash_segments(wl.donor_tok, wl.donor_mask, wl.donor_off)
+    if anchor_window is not None:
+        st.anchors, st.anchor_window = O.AnchorSet(), int(anchor_window)
+        O.insert_anchors(st.anchors, st.donor_hash, O.run_offsets(wl.donor_mask, wl.donor_off), st.anchor_window)
     st.donor_slot = np.full(len(wl.donor_tok), O.SLOT_NONE, np.uint32)
     flags = 0
     for first, last in wl.donor_batches:
@@ -102,6 +108,8 @@ class Lookup:
     flags: int
     dst: np.ndarray | None  # uint16[L][2][N][row_elems]
     times: dict
+    hash_float: np.ndarray | None = None
+    run_off: np.ndarray | None = None
 
 
 def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_spans=None) -> Lookup:
@@ -116,8 +124,14 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
     t = time.perf_counter()
     h = O.hash_segments(tok, mask, off)
     times["hash"] = time.perf_counter() - t
+    hf = roff = None
     t = time.perf_counter()
-    slot = O.probe(st.index, h)
+    if st.anchors is None:
+        slot = O.probe(st.index, h)
+    else:
+        roff = O.run_offsets(mask, off)
+        hf = O.hash_floating(st.anchors, h, roff, st.anchor_window)
+        slot = O.probe2(st.index, h, hf)
     times["probe"] = time.perf_counter() - t
     use_rope = wl.rope_theta is not None
     t = time.perf_counter()
@@ -130,4 +144,4 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
         t = time.perf_counter()
         O.gather_kv(st.pool, pool_layout(sh), buf, buf_layout(sh, N), src, dst, ln, delta if use_rope else None, rope)
         times["gather"] = time.perf_counter() - t
-    return Lookup(h, slot, src, dst, ln, delta, n, fl, buf, times)
+    return Lookup(h, slot, src, dst, ln, delta, n, fl, buf, times, hf, roff)

@@ -30,6 +30,7 @@ EXPORTS = [
     "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_tune", "cp_table_init",
     "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv", "cp_gather_events",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
+    "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
 ]
 
 
@@ -99,6 +100,14 @@ def lib():
         L.cp_hash_segments.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, sz]
         L.cp_probe.restype = i32
         L.cp_probe.argtypes = [vp, TableStruct, vp, u32, vp]
+        L.cp_hash_runs.restype = i32
+        L.cp_hash_runs.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, vp, sz]
+        L.cp_insert_anchors.restype = i32
+        L.cp_insert_anchors.argtypes = [vp, TableStruct, vp, vp, u32, u32, vp]
+        L.cp_hash_floating.restype = i32
+        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, vp, u32, u64, u32, vp, vp, sz]
+        L.cp_probe2.restype = i32
+        L.cp_probe2.argtypes = [vp, TableStruct, vp, vp, u32, vp]
         L.cp_build_spans.restype = i32
         L.cp_build_spans.argtypes = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_gather_kv.restype = i32
@@ -208,6 +217,40 @@ def cp_hash_segments(tok, mask, off, hash_out, scratch, base=BASE, stream=None):
     _check("cp_hash_segments", lib().cp_hash_segments(_stream(stream), _ptr(tok), _ptr(mask), _ptr(off), N, R, base,
                                                       _ptr(hash_out), _ptr(scratch), scratch.numel()))
     return hash_out
+
+
+def cp_hash_runs(tok, mask, off, hash_out, run_off_out, scratch, base=BASE, stream=None):
+    """cp_hash_segments that also returns run_off int32[N] (tokens since the start of the run)."""
+    _need_cuda(tok, mask, off, hash_out, run_off_out, scratch)
+    N, R = tok.numel(), off.numel() - 1
+    assert mask.numel() == N and hash_out.numel() == N and run_off_out.numel() == N
+    _check("cp_hash_runs", lib().cp_hash_runs(_stream(stream), _ptr(tok), _ptr(mask), _ptr(off), N, R, base,
+                                              _ptr(hash_out), _ptr(run_off_out), _ptr(scratch), scratch.numel()))
+    return hash_out
+
+
+def cp_insert_anchors(anchors: Table, hashes, run_off, W, status_flags, stream=None):
+    _need_cuda(hashes, run_off, status_flags)
+    _check("cp_insert_anchors", lib().cp_insert_anchors(_stream(stream), anchors.struct, _ptr(hashes), _ptr(run_off),
+                                                        hashes.numel(), int(W), _ptr(status_flags)))
+
+
+def cp_hash_floating(anchors: Table, hashes, run_off, W, hash_float_out, scratch, base=BASE, stream=None):
+    _need_cuda(hashes, run_off, hash_float_out, scratch)
+    N = hashes.numel()
+    assert run_off.numel() == N and hash_float_out.numel() == N
+    _check("cp_hash_floating", lib().cp_hash_floating(_stream(stream), anchors.struct, _ptr(hashes), _ptr(run_off), N,
+                                                      base, int(W), _ptr(hash_float_out), _ptr(scratch),
+                                                      scratch.numel()))
+    return hash_float_out
+
+
+def cp_probe2(table: Table, hash_a, hash_b, slot_out, stream=None):
+    _need_cuda(hash_a, hash_b, slot_out)
+    N = hash_a.numel()
+    assert hash_b.numel() == N and slot_out.numel() == N
+    _check("cp_probe2", lib().cp_probe2(_stream(stream), table.struct, _ptr(hash_a), _ptr(hash_b), N, _ptr(slot_out)))
+    return slot_out
 
 
 def cp_probe(table: Table, hashes, slot_out, stream=None):

@@ -46,13 +46,11 @@ __global__ __launch_bounds__(kProbeThreads) void table_init_kernel(cp_table t) {
   }
 }
 
-// One group of 16 lanes per token.
-__global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const uint64_t *__restrict__ hash,
-                                                              uint32_t N, uint32_t *__restrict__ slot_out) {
-  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+// Value stored under key h, or CP_SLOT_NONE.  Called by all lanes of a wavefront together; the 16
+// lanes of a group pass the same h (CP_HASH_NONE = nothing to look up) and get the same answer.
+__device__ __forceinline__ uint32_t group_lookup(const cp_table &t, uint64_t h) {
   const uint32_t sub = threadIdx.x & (kBucket - 1);
   const uint32_t n_buckets = (uint32_t)(t.capacity / kBucket);
-  uint64_t h = q < N ? hash[q] : CP_HASH_NONE;
   bool active = h != CP_HASH_NONE;
   uint32_t b = home_bucket(h, n_buckets), walked = 0, result = CP_SLOT_NONE;
   while (__any(active)) {  // wavefront-uniform loop; groups drop out one by one
@@ -71,7 +69,82 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const 
       }
     }
   }
-  if (q < N && sub == 0) slot_out[q] = result >= kPending ? CP_SLOT_NONE : result;
+  return result >= kPending ? CP_SLOT_NONE : result;
+}
+
+// One group of 16 lanes per token.  hash_b (nullable): second key, tried when the first misses.
+__global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                              const uint64_t *__restrict__ hash_b, uint32_t N,
+                                                              uint32_t *__restrict__ slot_out) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  uint32_t result = group_lookup(t, q < N ? hash[q] : CP_HASH_NONE);
+  if (hash_b) {  // same for the whole grid
+    const uint64_t h2 = (q < N && result == CP_SLOT_NONE) ? hash_b[q] : CP_HASH_NONE;
+    const uint32_t r2 = group_lookup(t, h2);
+    if (result == CP_SLOT_NONE) result = r2;
+  }
+  if (q < N && (threadIdx.x & (kBucket - 1)) == 0) slot_out[q] = result;
+}
+
+// Floating-anchor lookup, step 1: does the W-token window ending at token i match a stored prefix
+// hash?  Only windows that lie inside one run and start after the run's first token are looked at.
+__global__ __launch_bounds__(kProbeThreads) void window_hit_kernel(cp_table anchors,
+                                                                   const uint64_t *__restrict__ hash,
+                                                                   const uint32_t *__restrict__ run_off, uint32_t N,
+                                                                   uint32_t W, uint64_t base_pow_w,
+                                                                   uint8_t *__restrict__ hit) {
+  const uint32_t i = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  uint64_t wh = CP_HASH_NONE;
+  if (i < N && hash[i] != CP_HASH_NONE && run_off[i] >= W && run_off[i] != 0xFFFFFFFFu) {
+    wh = hash[i] - hash[i - W] * base_pow_w;  // tokens i-W+1 .. i; token i-W is in the same run
+    if (wh == CP_HASH_NONE) wh = CP_HASH_NONE - 1;
+  }
+  const uint32_t r = group_lookup(anchors, wh);
+  if (i < N && (threadIdx.x & (kBucket - 1)) == 0) hit[i] = r != CP_SLOT_NONE;
+}
+
+// Store the prefix hash of every run of at least W tokens (the chain hash of its W-th token) in the
+// anchor table: a set, so the order of arrival does not matter.
+__global__ __launch_bounds__(kProbeThreads) void insert_anchor_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                                      const uint32_t *__restrict__ run_off,
+                                                                      uint32_t N, uint32_t W,
+                                                                      uint32_t *status_flags) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  const uint32_t n_buckets = (uint32_t)(t.capacity / kBucket);
+  uint64_t h = (q < N && run_off[q] == W - 1) ? hash[q] : CP_HASH_NONE;
+  bool active = h != CP_HASH_NONE;
+  uint32_t b = home_bucket(h, n_buckets), walked = 0, entry = CP_SLOT_NONE;
+  while (__any(active)) {
+    unsigned long long *kp = (unsigned long long *)&t.keys[(uint64_t)b * kBucket + sub];
+    uint64_t k = CP_HASH_NONE;
+    if (active) k = __hip_atomic_load(kp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t hit = group_bits(__ballot(active && k == h));
+    uint32_t empty = group_bits(__ballot(active && k == CP_HASH_NONE));
+    bool try_claim = active && !hit && empty && sub == (uint32_t)(__ffs(empty) - 1);
+    uint64_t old = 0;
+    if (try_claim) old = atomicCAS(kp, (unsigned long long)CP_HASH_NONE, (unsigned long long)h);
+    uint32_t claimed = group_bits(__ballot(try_claim && (old == CP_HASH_NONE || old == h)));
+    if (active) {
+      if (hit) {
+        entry = b * kBucket + (__ffs(hit) - 1);
+        active = false;
+      } else if (empty) {
+        if (claimed) {
+          entry = b * kBucket + (__ffs(empty) - 1);
+          active = false;
+        }
+      } else if (++walked == n_buckets) {
+        active = false;
+      } else {
+        b = b + 1 == n_buckets ? 0 : b + 1;
+      }
+    }
+  }
+  if (q < N && sub == 0 && h != CP_HASH_NONE) {
+    if (entry != CP_SLOT_NONE) t.vals[entry] = 0;  // any value other than NONE marks membership
+    else atomicOr(status_flags, CP_FLAG_TABLE_FULL);
+  }
 }
 
 // Insert, step 1: find or claim the table entry of every token's key and leave
@@ -227,16 +300,49 @@ extern "C" int32_t cp_table_init(void *stream, cp_table table) {
   return check_launch();
 }
 
-extern "C" int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out) {
+static int32_t probe_common(void *stream, const cp_table &table, const uint64_t *hash, const uint64_t *hash_b,
+                            uint32_t N, uint32_t *slot_out) {
   using namespace cp;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (int32_t rc = table_ok(table)) return rc;
-  if (!hash || !slot_out || !aligned(hash, 8) || !aligned(slot_out, 4)) return CP_ERR_INVALID_ARG;
-  probe_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(table, hash, N,
-                                                                                                          slot_out);
+  if (!hash || !slot_out || !aligned(hash, 8) || !aligned(hash_b, 8) || !aligned(slot_out, 4)) return CP_ERR_INVALID_ARG;
+  probe_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(
+      table, hash, hash_b, N, slot_out);
   return check_launch();
 }
+
+extern "C" int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out) {
+  return probe_common(stream, table, hash, nullptr, N, slot_out);
+}
+
+extern "C" int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
+                             uint32_t *slot_out) {
+  if (N && !hash_b) return CP_ERR_INVALID_ARG;
+  return probe_common(stream, table, hash_a, hash_b, N, slot_out);
+}
+
+extern "C" int32_t cp_insert_anchors(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
+                                     uint32_t N, uint32_t W, uint32_t *status_flags) {
+  using namespace cp;
+  if (N == 0) return CP_OK;
+  if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (int32_t rc = table_ok(anchors)) return rc;
+  if (W == 0 || !hash || !run_off || !status_flags || !aligned(hash, 8)) return CP_ERR_INVALID_ARG;
+  insert_anchor_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(
+      anchors, hash, run_off, N, W, status_flags);
+  return check_launch();
+}
+
+namespace cp {
+int32_t launch_window_hits(hipStream_t stream, const cp_table &anchors, const uint64_t *hash, const uint32_t *run_off,
+                           uint32_t N, uint32_t W, uint64_t base_pow_w, uint8_t *hit) {
+  if (int32_t rc = table_ok(anchors)) return rc;
+  window_hit_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(anchors, hash, run_off,
+                                                                                                N, W, base_pow_w, hit);
+  return check_launch();
+}
+}  // namespace cp
 
 extern "C" int32_t cp_insert_kv(void *stream_, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
                                 uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,

@@ -54,7 +54,7 @@ class GpuState:
     flags: int
 
 
-def make_pool(wl, free_slots=None, n_free=None) -> cp.KVPool:
+def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, anchor_capacity=None) -> cp.KVPool:
     sh = wl.shape
     rope = cp.binding.Rope(wl.rope_theta, wl.rope_style) if wl.rope_theta is not None else None
     fs = wl.free_slots if free_slots is None else free_slots
@@ -62,7 +62,8 @@ def make_pool(wl, free_slots=None, n_free=None) -> cp.KVPool:
         fs = fs[:n_free]
     pool = cp.KVPool(sh.n_layers, sh.n_kv_heads, sh.head_dim, wl.pool_slots, wl.table_capacity,
                      torch.from_numpy(fs.view(np.int32)), rope=rope, device=DEV,
-                     pool_tensor=poison_tensor(wl.pool_slots * sh.tok_bytes))
+                     pool_tensor=poison_tensor(wl.pool_slots * sh.tok_bytes), anchor_window=anchor_window,
+                     anchor_capacity=anchor_capacity)
     pool.slot_pos.fill_(np.iinfo(np.int32).min)
     return pool
 
@@ -85,7 +86,8 @@ def prefill(wl, pool: cp.KVPool = None) -> GpuState:
         hbuf = torch.empty(n, dtype=torch.int64, device=DEV)
         sout = torch.empty(n, dtype=torch.int32, device=DEV)
         scratch = cp.binding.new_scratch(max(1, n), 0, DEV)
-        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch))
+        roff = torch.empty(max(1, n), dtype=torch.int32, device=DEV) if pool.anchors is not None else None
+        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch, run_off_buf=roff))
         donor_hash[t0:t1] = host_u64(hbuf)
         donor_slot[t0:t1] = host_u32(sout)
         del src
@@ -104,6 +106,8 @@ class GpuLookup:
     n_spans: int
     flags: int
     dst: torch.Tensor  # uint8 device tensor, layer-major [L][2][N][row_bytes]
+    hash_float: np.ndarray = None  # pools with floating anchors only
+    run_off: np.ndarray = None
 
 
 def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=True) -> GpuLookup:
@@ -119,9 +123,11 @@ def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=T
                    gather=gather)
     torch.cuda.synchronize()
     n = int(buf.n_spans.item())
+    anch = st.pool.anchors is not None
     return GpuLookup(host_u64(buf.hash), host_u32(buf.slot), host_u32(buf.span_src)[:n], host_u32(buf.span_dst)[:n],
                      host_u32(buf.span_len)[:n], buf.span_delta.cpu().numpy()[:n], host_u32(buf.span_off)[:n + 1], n,
-                     int(st.pool.flags.item()), dst)
+                     int(st.pool.flags.item()), dst, host_u64(buf.hash_float) if anch else None,
+                     host_u32(buf.run_off) if anch else None)
 
 
 def dst_as_rows(dst, sh, N):

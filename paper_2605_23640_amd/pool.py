@@ -4,6 +4,11 @@ sequences of the two paths through libcacheprune.
     lookup :  cp_hash_segments -> cp_probe -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_segments -> cp_insert_kv
 
+and, for a pool with floating anchors (window W),
+
+    lookup :  cp_hash_runs -> cp_hash_floating -> cp_probe2 -> cp_build_spans -> cp_gather_kv
+    insert :  cp_hash_runs -> cp_insert_anchors -> cp_insert_kv
+
 Nothing here computes: tensors are allocated and handed to the C ABI.
 """
 from __future__ import annotations
@@ -35,6 +40,8 @@ class LookupBuffers:
         self.max_spans = N if max_spans is None else max_spans
         i32, i64 = torch.int32, torch.int64
         self.hash = torch.empty(N, dtype=i64, device=device)
+        self.hash_float = torch.empty(N, dtype=i64, device=device)  # floating-anchor keys (if the pool uses them)
+        self.run_off = torch.empty(N, dtype=i32, device=device)
         self.slot = torch.empty(N, dtype=i32, device=device)
         m = max(1, self.max_spans)
         self.span_src = torch.empty(m, dtype=i32, device=device)
@@ -51,7 +58,7 @@ class KVPool:
     cached position of every slot and the free list (hand-out order)."""
 
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
-                 device="cuda", pool_tensor=None):
+                 device="cuda", pool_tensor=None, anchor_window=None, anchor_capacity=None):
         self.device = device
         self.n_slots = int(n_slots)
         self.layout = B.KVLayout.token_major(n_layers, n_kv_heads, head_dim)
@@ -66,6 +73,12 @@ class KVPool:
         self.flags = torch.zeros(1, dtype=torch.int32, device=device)
         self.n_inserted = torch.zeros(1, dtype=torch.int32, device=device)
         self.rope = rope  # binding.Rope or None
+        # floating anchors: window length W and the set of stored runs' prefix hashes (None: run-start keys only)
+        self.anchor_window = anchor_window
+        self.anchors = None
+        if anchor_window is not None:
+            cap = anchor_capacity if anchor_capacity is not None else max(1024, self.n_slots // 4)
+            self.anchors = B.Table((int(cap) + B.TABLE_BUCKET - 1) // B.TABLE_BUCKET * B.TABLE_BUCKET, device)
 
     def request_layout(self, n_tokens):
         L, H, D = self.shape
@@ -81,8 +94,14 @@ class KVPool:
         ``gather_events`` = (start, end) torch events recorded on the stream around
         the gather call alone (for timing)."""
         N = tok.numel()
-        B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
-        B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
+        if self.anchors is None:
+            B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
+            B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
+        else:
+            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
+            B.cp_hash_floating(self.anchors, buf.hash, buf.run_off, self.anchor_window, buf.hash_float, buf.scratch,
+                               stream=stream)
+            B.cp_probe2(self.table, buf.hash, buf.hash_float, buf.slot, stream=stream)
         B.cp_build_spans(buf.slot, off, self.slot_pos if self.rope is not None else None, buf.max_spans, buf.span_src,
                          buf.span_dst, buf.span_len, buf.span_delta, buf.span_off, buf.n_spans, self.flags,
                          buf.scratch, stream=stream)
@@ -98,12 +117,20 @@ class KVPool:
         return LookupResult(buf.hash, buf.slot, buf.span_src, buf.span_dst, buf.span_len, buf.span_delta,
                             buf.span_off, buf.n_spans)
 
-    def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None):
+    def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None,
+               run_off_buf=None):
         """Store the non-sensitive tokens of a batch that the pool does not hold yet,
         taking their KV rows from ``src`` (layer-major, N tokens).  With ``sync`` the
-        host free-list cursor is advanced (one device-to-host read)."""
+        host free-list cursor is advanced (one device-to-host read).  A pool with
+        floating anchors also needs ``run_off_buf`` (int32[N]; filled here unless
+        ``hashes_ready``)."""
         N = tok.numel()
-        if not hashes_ready:
+        if self.anchors is not None:
+            assert run_off_buf is not None, "a pool with floating anchors needs run_off_buf"
+            if not hashes_ready:
+                B.cp_hash_runs(tok, mask, off, hash_buf, run_off_buf, scratch, stream=stream)
+            B.cp_insert_anchors(self.anchors, hash_buf, run_off_buf, self.anchor_window, self.flags, stream=stream)
+        elif not hashes_ready:
             B.cp_hash_segments(tok, mask, off, hash_buf, scratch, stream=stream)
         n_free = self.free_slots.numel() - self.n_used
         B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src, self.request_layout(N),

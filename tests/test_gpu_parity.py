@@ -29,13 +29,16 @@ def bf16_ordinal(bits):
     return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
 
 
-def compare_all(G, wl, max_ulp_sample=None):
+def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, anchor_capacity=None):
     """Run prefill + lookup on both sides and compare everything."""
     fl = []
-    ost = OH.prefill(wl, flags_out=fl)
+    ost = OH.prefill(wl, flags_out=fl, anchor_window=anchor_window)
     olk = OH.lookup(ost)
-    gst = G.prefill(wl)
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=anchor_window, anchor_capacity=anchor_capacity))
     glk = G.lookup(gst)
+    if anchor_window is not None:
+        assert np.array_equal(glk.run_off, olk.run_off)
+        assert np.array_equal(glk.hash_float, olk.hash_float)
     N = wl.n_tokens
     assert np.array_equal(gst.donor_hash, ost.donor_hash)
     assert np.array_equal(gst.donor_slot, ost.donor_slot)
