@@ -43,7 +43,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(wl, n_requests, G, torch, np):
+def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None):
     """The CPU oracle, as it stands, on the first ``n_requests`` requests of the workload."""
     import oracle as O
     from cp_workload import gen
@@ -62,7 +62,8 @@ def cpu_baseline(wl, n_requests, G, torch, np):
     host_src = dev.view(torch.int16).cpu().numpy().view(np.uint16).reshape(sh.n_layers, 2, n_d, re)
     del dev
     pool = np.empty((sw.pool_slots, sh.n_layers, 2, re), np.uint16)  # untouched pages stay virtual
-    st = OH.prefill(sw, src_provider=lambda t0, n: np.ascontiguousarray(host_src[:, :, t0:t0 + n]), pool=pool)
+    st = OH.prefill(sw, src_provider=lambda t0, n: np.ascontiguousarray(host_src[:, :, t0:t0 + n]), pool=pool,
+                    anchor_window=anchor_window)
     del host_src
     lk = OH.lookup(st)  # hash, probe, spans, gather: timed inside
     N = sw.n_tokens
@@ -88,7 +89,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama3-8b", choices=["tiny", "llama3-8b", "frag", "rope", "llama3-70b"])
+    ap.add_argument("--workload", default="llama3-8b", choices=["tiny", "llama3-8b", "frag", "rope", "llama3-70b", "float"])
+    ap.add_argument("--anchor-window", type=int, default=None,
+                    help="W: look stored runs up through floating anchors as well (default: run-start keys only)")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
@@ -122,7 +125,7 @@ def main():
     N = wl.n_tokens
     log(f"[bench] workload {wl.name}: {wl.n_requests} requests, {N} tokens, {sh.tok_bytes // 1024} KiB/token, "
         f"pool {wl.pool_slots} slots = {wl.pool_slots * sh.tok_bytes / 2**30:.1f} GiB")
-    gst = G.prefill(wl)
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window))
     pool = gst.pool
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
 
@@ -132,6 +135,8 @@ def main():
     slot_out = torch.empty(N, dtype=torch.int32, device=G.DEV)
     ins_scratch = cp.binding.new_scratch(N, 0, G.DEV)
     keys0, vals0 = pool.table.keys.clone(), pool.table.vals.clone()
+    if pool.anchors is not None:
+        akeys0, avals0 = pool.anchors.keys.clone(), pool.anchors.vals.clone()
     K = args.steps
     hev = cp.binding.HipEvents(2 * K + 2)  # pairs around the gather's mover kernel, on the launch stream
     ev_ins = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
@@ -142,11 +147,15 @@ def main():
         pool.lookup(tok, mask, off, dst, buf)
         if k is not None:
             ev_ins[k][0].record()
-        pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False)
+        pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False,
+                    run_off_buf=buf.run_off)
         if k is not None:
             ev_ins[k][1].record()
         pool.table.keys.copy_(keys0, non_blocking=True)
         pool.table.vals.copy_(vals0, non_blocking=True)
+        if pool.anchors is not None:
+            pool.anchors.keys.copy_(akeys0, non_blocking=True)
+            pool.anchors.vals.copy_(avals0, non_blocking=True)
 
     for _ in range(args.warmup):
         step()
@@ -222,6 +231,7 @@ def main():
                         f"({sh.tok_bytes // 1024} KiB/token), pool {wl.pool_slots} slots "
                         f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) token-major, slots in random order",
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
+            "anchor_window": args.anchor_window,
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
             "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,
         },
@@ -256,7 +266,7 @@ def main():
     if args.cpu_requests > 0:
         del dst
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np, args.anchor_window)
     print(json.dumps(out), flush=True)
 
 
