@@ -81,7 +81,12 @@ def lib():
         L.cpo_anchor_set_size.argtypes = [vp]
         L.cpo_run_offsets.argtypes = [vp, vp, u32, vp]
         L.cpo_insert_anchors.argtypes = [vp, vp, vp, u32, u32]
-        L.cpo_hash_floating.argtypes = [vp, vp, vp, u32, u64, u32, vp]
+        L.cpo_hash_floating.argtypes = [vp, vp, vp, u32, u64, u32, vp, vp]
+        L.cpo_text_new.restype = vp
+        L.cpo_text_new.argtypes = [u32]
+        L.cpo_text_free.argtypes = [vp]
+        L.cpo_text_record.argtypes = [vp, vp, vp, u32, vp]
+        L.cpo_verify.argtypes = [vp, vp, vp, vp, u32, C.c_int, vp]
         L.cpo_probe2.argtypes = [vp, vp, vp, u32, vp]
         L.cpo_bf16_to_double.restype = C.c_double
         L.cpo_bf16_to_double.argtypes = [C.c_uint16]
@@ -144,10 +149,39 @@ def insert_anchors(anchors: AnchorSet, hashes, run_off, W):
     lib().cpo_insert_anchors(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], int(W))
 
 
-def hash_floating(anchors: AnchorSet, hashes, run_off, W, base=BASE):
+def hash_floating(anchors: AnchorSet, hashes, run_off, W, base=BASE, with_offsets=False):
     hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
     out = np.empty(hashes.shape[0], np.uint64)
-    lib().cpo_hash_floating(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], base, int(W), _p(out))
+    foff = np.empty(hashes.shape[0], np.uint32) if with_offsets else None
+    lib().cpo_hash_floating(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], base, int(W), _p(out),
+                            _p(foff) if with_offsets else None)
+    return (out, foff) if with_offsets else out
+
+
+class Text:
+    """The token string every pool slot was stored for (exact verification)."""
+
+    def __init__(self, n_slots):
+        self._h = lib().cpo_text_new(int(n_slots))
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().cpo_text_free(self._h)
+            self._h = None
+
+
+def text_record(text: Text, tok, run_off, slot_out):
+    """Record a batch after insert_kv; returns slot_out with unverified tokens set to NONE."""
+    tok, run_off = _arr(tok, np.uint32), _arr(run_off, np.uint32)
+    out = np.array(slot_out, dtype=np.uint32, copy=True)
+    lib().cpo_text_record(text._h, _p(tok), _p(run_off), tok.shape[0], _p(out))
+    return out
+
+
+def verify(text: Text, tok, seg_off, cand, merge_into=None):
+    tok, seg_off, cand = _arr(tok, np.uint32), _arr(seg_off, np.uint32), _arr(cand, np.uint32)
+    out = np.empty(tok.shape[0], np.uint32) if merge_into is None else np.array(merge_into, np.uint32, copy=True)
+    lib().cpo_verify(text._h, _p(tok), _p(seg_off), _p(cand), tok.shape[0], 0 if merge_into is None else 1, _p(out))
     return out
 
 

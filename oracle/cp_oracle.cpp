@@ -257,7 +257,7 @@ extern "C" void cpo_insert_anchors(cpo_anchor_set *as, const uint64_t *hash, con
 
 extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const uint64_t *hash,
                                   const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
-                                  uint64_t *hash_float_out) {
+                                  uint64_t *hash_float_out, uint32_t *float_off_out) {
   // precomputed powers of the base
   std::vector<uint64_t> pw((size_t)N + 1);
   pw[0] = 1;
@@ -273,13 +273,16 @@ extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const uint64_t *hash
     if (hash[i] == CPO_HASH_NONE || run_off[i] + 1 < W) continue;  // window would leave the run
     uint32_t a = i - (W - 1);
     if (run_off[a] == 0) continue;  // at the run start the plain chain hash already is this key
-    if (as->set.count(sub(a, i))) anchor_at[a] = 1;
+    uint64_t wh = sub(a, i);
+    if (wh == CPO_HASH_NONE) wh = CPO_HASH_NONE - 1;  // stored hashes never take the reserved value
+    if (as->set.count(wh)) anchor_at[a] = 1;
   }
   // Step 2: key of every token from its latest anchor
   bool have = false;
   uint32_t a = 0;
   for (uint32_t i = 0; i < N; ++i) {
     hash_float_out[i] = CPO_HASH_NONE;
+    if (float_off_out) float_off_out[i] = 0xFFFFFFFFu;
     if (hash[i] == CPO_HASH_NONE) {
       have = false;
       continue;
@@ -292,7 +295,76 @@ extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const uint64_t *hash
     if (have) {
       uint64_t h = sub(a, i);
       hash_float_out[i] = (h == CPO_HASH_NONE) ? CPO_HASH_NONE - 1 : h;
+      if (float_off_out) float_off_out[i] = i - a;
     }
+  }
+}
+
+// ---- exact verification -------------------------------------------------------------------------
+
+struct cpo_text {
+  std::vector<uint32_t> archive;  // every token of every recorded batch, in arrival order
+  std::vector<uint64_t> last;     // per slot: archive index of the slot's own token
+  std::vector<uint32_t> len;      // per slot: length of the text (0 = none yet, 0xFFFFFFFF = never matches)
+};
+
+extern "C" cpo_text *cpo_text_new(uint32_t n_slots) {
+  cpo_text *t = new cpo_text;
+  t->last.assign(n_slots, 0);
+  t->len.assign(n_slots, 0);
+  return t;
+}
+extern "C" void cpo_text_free(cpo_text *t) { delete t; }
+
+// Does slot s hold exactly the `n` tokens that end at tok[i]?  Compared one token at a time.
+static bool text_equals(const cpo_text *t, uint32_t s, const uint32_t *tok, uint32_t i, uint32_t n) {
+  if (s >= t->len.size() || t->len[s] != n) return false;
+  for (uint32_t k = 0; k < n; ++k)
+    if (t->archive[t->last[s] - k] != tok[i - k]) return false;
+  return true;
+}
+
+extern "C" void cpo_text_record(cpo_text *t, const uint32_t *tok, const uint32_t *run_off, uint32_t N,
+                                uint32_t *slot_out) {
+  const uint64_t base = t->archive.size();
+  t->archive.insert(t->archive.end(), tok, tok + N);
+  bool prev_ok = false;
+  for (uint32_t i = 0; i < N; ++i) {
+    if (run_off[i] == 0xFFFFFFFFu) {  // sensitive
+      prev_ok = false;
+      continue;
+    }
+    const bool start_ok = run_off[i] == 0 || prev_ok;
+    const uint32_t s = slot_out[i], n = run_off[i] + 1;
+    bool ok = false;
+    if (s < t->len.size()) {
+      if (t->len[s] == 0) {  // a slot filled by this batch, seen at its first (storing) token
+        if (start_ok) {
+          t->last[s] = base + i;
+          t->len[s] = n;
+          ok = true;
+        } else {
+          t->len[s] = 0xFFFFFFFFu;  // stored behind a prefix that was not verified: unusable
+        }
+      } else {
+        ok = start_ok && text_equals(t, s, tok, i, n);
+      }
+    }
+    if (!ok) slot_out[i] = CPO_SLOT_NONE;
+    prev_ok = ok;
+  }
+}
+
+extern "C" void cpo_verify(const cpo_text *t, const uint32_t *tok, const uint32_t *seg_off,
+                           const uint32_t *cand, uint32_t N, int merge, uint32_t *slot_out) {
+  bool prev_ok = false;
+  for (uint32_t i = 0; i < N; ++i) {
+    bool ok = false;
+    if (seg_off[i] != 0xFFFFFFFFu && (seg_off[i] == 0 || prev_ok))
+      ok = text_equals(t, cand[i], tok, i, seg_off[i] + 1);
+    prev_ok = ok;
+    const uint32_t r = ok ? cand[i] : CPO_SLOT_NONE;
+    if (!merge || slot_out[i] == CPO_SLOT_NONE) slot_out[i] = r;
   }
 }
 

@@ -133,12 +133,35 @@ void cpo_insert_anchors(cpo_anchor_set *, const uint64_t *hash, const uint32_t *
  * an anchor is a position a > run start such that the W tokens from a lie inside the run and their
  * hash is in the set; CPO_HASH_NONE where there is no such anchor (and for sensitive tokens). */
 void cpo_hash_floating(const cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off,
-                       uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out);
+                       uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out,
+                       uint32_t *float_off_out /* nullable: i - a, 0xFFFFFFFF without an anchor */);
 
 /* Lookup with two keys per token: slot under hash_a if present, else under hash_b, else NONE. */
 void cpo_probe2(const cpo_index *, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                 uint32_t *slot_out);
 
+/* ---- Exact verification (Sec. 4.2.2, Step 2 "full verification") ----
+ * A hash match is only a candidate.  The paper confirms it with a cryptographic hash of the
+ * substring so that no collision of the rolling hash can produce a false match; what that reaches
+ * is "the stored text equals the request's text", and this oracle writes that definition out: it
+ * keeps the text every slot was stored for and compares token by token.
+ * A match is extended from the start of its segment (run start, or floating anchor) one token at a
+ * time and ends at the first token that fails: token i is accepted iff token i-1 of the segment was
+ * (or i starts it) and its candidate slot holds exactly the segment's tokens up to i. */
+typedef struct cpo_text cpo_text; /* per slot: the token string it was stored for. Opaque. */
+cpo_text *cpo_text_new(uint32_t n_slots);
+void cpo_text_free(cpo_text *);
+/* Call after cpo_insert_kv with the batch's tokens, run offsets and slot_out.  Slots seen for the
+ * first time get their text (the run from its start through the token); a token whose slot holds
+ * a different text, or that follows such a token in its run, gets slot_out = NONE, and a slot
+ * first filled by such a token never matches anything. */
+void cpo_text_record(cpo_text *, const uint32_t *tok, const uint32_t *run_off, uint32_t N,
+                     uint32_t *slot_out);
+/* seg_off[i] = offset of token i in its segment (0 = first, 0xFFFFFFFF = in none); cand[i] = the
+ * slot found under the segment's key for i.  slot_out[i] = cand[i] if accepted, else NONE; with
+ * merge != 0 only entries of slot_out that are NONE are written. */
+void cpo_verify(const cpo_text *, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
+                uint32_t N, int merge, uint32_t *slot_out);
 /* Building blocks exposed so that tests can pin them one by one. */
 double cpo_bf16_to_double(uint16_t bits);
 uint16_t cpo_double_to_bf16(double x); /* round-to-nearest-even, one rounding */
