@@ -157,11 +157,48 @@ int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t *mask, con
                      size_t scratch_bytes);
 int32_t cp_insert_anchors(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
                           uint32_t N, uint32_t W, uint32_t *status_flags);
+/* float_off_out (device u32[N], may be NULL): i - a for a token with an anchor, 0xFFFFFFFF otherwise. */
 int32_t cp_hash_floating(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
-                         uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out, void *scratch,
-                         size_t scratch_bytes);
+                         uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out, uint32_t *float_off_out,
+                         void *scratch, size_t scratch_bytes);
 int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                   uint32_t *slot_out);
+
+/* ---- Exact matches: no false match from a collision of the rolling hash -------------------------
+ * Sec. 4.2.2 Step 2 ("full verification"): a candidate found through the rolling hash is confirmed
+ * before it is used, so that a collision cannot link another text's KV.  The paper confirms with a
+ * cryptographic hash of the substring; this library confirms by comparison with what the pool
+ * recorded when it stored the tokens, which is exact.  Two caller-owned device arrays of
+ * n_pool_slots words describe the stored runs as a trie whose nodes are slots:
+ *     slot_tok[s]    = token id slot s was stored for,
+ *     slot_parent[s] = slot of the token before it in its run, CP_SLOT_NONE for a run's first token.
+ * Initialise slot_parent to CP_PARENT_POISON (a value no lookup ever equals); slot_tok needs none.
+ *
+ * cp_insert_kv_chain is cp_insert_kv that also maintains the two arrays.  tok / run_off: the batch's
+ * tokens and run offsets (cp_hash_runs).  Every token's slot is confirmed against the recorded
+ * chains before it is reported: slot_out[i] = the slot that holds exactly the tokens of i's run up to
+ * i, CP_SLOT_NONE for a sensitive token, a token that could not be stored, and a token whose key
+ * belongs to another text (or that follows such a token in its run).  A slot taken by a token of the
+ * last kind is consumed but can never match (its parent is set to CP_PARENT_POISON).
+ *
+ * cp_verify_chain confirms the candidates of one key stream of a lookup.  seg_off[i] = offset of
+ * token i in its segment: run_off for run-start keys, float_off for floating keys; 0xFFFFFFFF = in
+ * no segment.  cand[i] = slot found under that stream's key (cp_probe).  Token i is accepted iff
+ * every token from its segment's start through i is consistent: cand < n_pool_slots,
+ * slot_tok[cand[i]] == tok[i], and slot_parent[cand[i]] == cand[i-1] (CP_SLOT_NONE at offset 0); by
+ * induction cand[i] then holds exactly the segment's tokens up to i.  slot_out[i] = cand[i] if
+ * accepted, else CP_SLOT_NONE; with merge != 0 only entries of slot_out that are CP_SLOT_NONE are
+ * written (second key stream).  cand and slot_out must not be the same array. */
+#define CP_PARENT_POISON 0xFFFFFFFEu
+int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, const uint32_t *tok,
+                           const uint32_t *run_off, const uint32_t *off, uint32_t N, uint32_t R,
+                           const uint32_t *free_slots, uint32_t n_free, const void *src, cp_kv_layout src_l,
+                           void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, int32_t *slot_pos,
+                           uint32_t *slot_tok, uint32_t *slot_parent, uint32_t *slot_out, uint32_t *n_inserted,
+                           uint32_t *status_flags, void *scratch, size_t scratch_bytes);
+int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand, uint32_t N,
+                        const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots, int32_t merge,
+                        uint32_t *slot_out, void *scratch, size_t scratch_bytes);
 
 /* Run-length pass: turn per-token slots into copy descriptors (the "token
  * spans" of the retriever's metadata, Sec. 4.3.1).  A span is a maximal run of

@@ -48,13 +48,15 @@ class OracleState:
     times: dict = field(default_factory=dict)
     anchors: O.AnchorSet | None = None  # floating anchors: hashes of the stored runs' first W tokens
     anchor_window: int | None = None
+    text: O.Text | None = None  # exact verification: the token string every slot was stored for
 
 
-def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None) -> OracleState:
+def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None, verify=False) -> OracleState:
     """Insert the donor prompts batch by batch.  ``src_provider(first_tok, n_tok)``
     returns the layer-major KV buffer of a donor batch (default: host generator,
     uid = packed donor index).  With ``anchor_window`` = W the hash of every
-    stored run's first W tokens is also recorded as a floating anchor."""
+    stored run's first W tokens is also recorded as a floating anchor; with
+    ``verify`` the pool records every slot's text and reports only confirmed slots."""
     sh = wl.shape
     re = sh.row_bytes // 2
     if pool is None:
@@ -69,6 +71,8 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
     if anchor_window is not None:
         st.anchors, st.anchor_window = O.AnchorSet(), int(anchor_window)
         O.insert_anchors(st.anchors, st.donor_hash, O.run_offsets(wl.donor_mask, wl.donor_off), st.anchor_window)
+    if verify:
+        st.text = O.Text(wl.pool_slots)
     st.donor_slot = np.full(len(wl.donor_tok), O.SLOT_NONE, np.uint32)
     flags = 0
     for first, last in wl.donor_batches:
@@ -80,6 +84,9 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         slot_out, n_new, fl = O.insert_kv(
             st.index, st.donor_hash[t0:t1], off, wl.free_slots[st.n_used :], src, buf_layout(sh, n), st.pool,
             pool_layout(sh), st.slot_pos, tok=wl.donor_tok[t0:t1], slot_tok=st.slot_tok)
+        if st.text is not None:
+            raw = slot_out
+            slot_out = O.text_record(st.text, wl.donor_tok[t0:t1], O.run_offsets(wl.donor_mask[t0:t1], off), raw)
         st.donor_slot[t0:t1] = slot_out
         st.n_used += n_new
         flags |= fl
@@ -87,7 +94,7 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         new_slots = set(int(s) for s in wl.free_slots[before : st.n_used])
         seen = set()
         for i in range(n):
-            s = int(slot_out[i])
+            s = int(raw[i]) if st.text is not None else int(slot_out[i])
             if s in new_slots and s not in seen:
                 seen.add(s)
                 st.slot_uid[s] = t0 + i
@@ -126,7 +133,13 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
     times["hash"] = time.perf_counter() - t
     hf = roff = None
     t = time.perf_counter()
-    if st.anchors is None:
+    if st.text is not None:
+        roff = O.run_offsets(mask, off)
+        slot = O.verify(st.text, tok, roff, O.probe(st.index, h))
+        if st.anchors is not None:
+            hf, foff = O.hash_floating(st.anchors, h, roff, st.anchor_window, with_offsets=True)
+            slot = O.verify(st.text, tok, foff, O.probe(st.index, hf), merge_into=slot)
+    elif st.anchors is None:
         slot = O.probe(st.index, h)
     else:
         roff = O.run_offsets(mask, off)

@@ -31,7 +31,9 @@ EXPORTS = [
     "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv", "cp_gather_events",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
+    "cp_insert_kv_chain", "cp_verify_chain",
 ]
+PARENT_POISON = 0xFFFFFFFE
 
 
 class CpError(RuntimeError):
@@ -105,7 +107,12 @@ def lib():
         L.cp_insert_anchors.restype = i32
         L.cp_insert_anchors.argtypes = [vp, TableStruct, vp, vp, u32, u32, vp]
         L.cp_hash_floating.restype = i32
-        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, vp, u32, u64, u32, vp, vp, sz]
+        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, vp, u32, u64, u32, vp, vp, vp, sz]
+        L.cp_insert_kv_chain.restype = i32
+        L.cp_insert_kv_chain.argtypes = [vp, TableStruct, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
+                                         u32, vp, vp, vp, vp, vp, vp, vp, sz]
+        L.cp_verify_chain.restype = i32
+        L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, sz]
         L.cp_probe2.restype = i32
         L.cp_probe2.argtypes = [vp, TableStruct, vp, vp, u32, vp]
         L.cp_build_spans.restype = i32
@@ -235,14 +242,42 @@ def cp_insert_anchors(anchors: Table, hashes, run_off, W, status_flags, stream=N
                                                         hashes.numel(), int(W), _ptr(status_flags)))
 
 
-def cp_hash_floating(anchors: Table, hashes, run_off, W, hash_float_out, scratch, base=BASE, stream=None):
-    _need_cuda(hashes, run_off, hash_float_out, scratch)
+def cp_hash_floating(anchors: Table, hashes, run_off, W, hash_float_out, scratch, base=BASE, stream=None,
+                     float_off_out=None):
+    _need_cuda(hashes, run_off, hash_float_out, scratch, float_off_out)
     N = hashes.numel()
     assert run_off.numel() == N and hash_float_out.numel() == N
+    assert float_off_out is None or float_off_out.numel() == N
     _check("cp_hash_floating", lib().cp_hash_floating(_stream(stream), anchors.struct, _ptr(hashes), _ptr(run_off), N,
-                                                      base, int(W), _ptr(hash_float_out), _ptr(scratch),
-                                                      scratch.numel()))
+                                                      base, int(W), _ptr(hash_float_out), _ptr(float_off_out),
+                                                      _ptr(scratch), scratch.numel()))
     return hash_float_out
+
+
+def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, merge, slot_out, scratch, stream=None):
+    _need_cuda(tok, seg_off, cand, slot_tok, slot_parent, slot_out, scratch)
+    N = tok.numel()
+    assert seg_off.numel() == N and cand.numel() == N and slot_out.numel() == N
+    assert slot_tok.numel() >= n_pool_slots and slot_parent.numel() >= n_pool_slots
+    _check("cp_verify_chain", lib().cp_verify_chain(_stream(stream), _ptr(tok), _ptr(seg_off), _ptr(cand), N,
+                                                    _ptr(slot_tok), _ptr(slot_parent), n_pool_slots, 1 if merge else 0,
+                                                    _ptr(slot_out), _ptr(scratch), scratch.numel()))
+    return slot_out
+
+
+def cp_insert_kv_chain(table: Table, hashes, tok, run_off, off, free_slots, n_free, src, src_l: KVLayout, pool,
+                       pool_l: KVLayout, n_pool_slots, slot_pos, slot_tok, slot_parent, slot_out, n_inserted,
+                       status_flags, scratch, stream=None):
+    _need_cuda(hashes, tok, run_off, off, free_slots, src, pool, slot_pos, slot_tok, slot_parent, slot_out, n_inserted,
+               status_flags, scratch)
+    N, R = hashes.numel(), off.numel() - 1
+    assert tok.numel() == N and run_off.numel() == N and slot_out.numel() == N
+    assert free_slots is None or free_slots.numel() >= n_free
+    assert slot_tok.numel() >= n_pool_slots and slot_parent.numel() >= n_pool_slots
+    _check("cp_insert_kv_chain", lib().cp_insert_kv_chain(
+        _stream(stream), table.struct, _ptr(hashes), _ptr(tok), _ptr(run_off), _ptr(off), N, R, _ptr(free_slots),
+        n_free, _ptr(src), src_l, _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_tok), _ptr(slot_parent),
+        _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags), _ptr(scratch), scratch.numel()))
 
 
 def cp_probe2(table: Table, hash_a, hash_b, slot_out, stream=None):

@@ -68,6 +68,7 @@ struct FloatKeyOp {
   const uint32_t *run_off;
   const uint8_t *hit;  // hit[i]: the W-token window ending at i matches a stored prefix hash
   uint64_t *out;
+  uint32_t *float_off;  // nullable: i - a for tokens with an anchor, else 0xFFFFFFFF
   uint64_t base;
   uint32_t N, W;
 
@@ -80,15 +81,18 @@ struct FloatKeyOp {
   }
   __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
     uint64_t key = CP_HASH_NONE;
+    uint32_t fo = 0xFFFFFFFFu;
     const uint32_t ro = run_off[i];
     if (hash[i] != CP_HASH_NONE && incl != 0) {
       const uint32_t a = incl - 1;
       if (a > i - ro) {  // inside this run and after its start (a window at the run start is the plain key)
         key = hash[i] - hash[a - 1] * pow_u64(base, i - a + 1);
         if (key == CP_HASH_NONE) key = CP_HASH_NONE - 1;
+        fo = i - a;
       }
     }
     out[i] = key;
+    if (float_off) float_off[i] = fo;
   }
   __device__ __forceinline__ void finish(T) const {}
 };
@@ -127,8 +131,8 @@ extern "C" int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t
 }
 
 extern "C" int32_t cp_hash_floating(void *stream_, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
-                                    uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out, void *scratch,
-                                    size_t scratch_bytes) {
+                                    uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out,
+                                    uint32_t *float_off_out, void *scratch, size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (N == 0) return CP_OK;
@@ -145,6 +149,6 @@ extern "C" int32_t cp_hash_floating(void *stream_, cp_table anchors, const uint6
   for (uint64_t b = base, k = W; k; k >>= 1, b *= b)
     if (k & 1) pw *= b;
   if (int32_t rc = launch_window_hits(stream, anchors, hash, run_off, N, W, pw, hit)) return rc;
-  FloatKeyOp op{hash, run_off, hit, hash_float_out, base, N, W};
+  FloatKeyOp op{hash, run_off, hit, hash_float_out, float_off_out, base, N, W};
   return run_scan<FloatKeyOp>(stream, op, N, agg);
 }

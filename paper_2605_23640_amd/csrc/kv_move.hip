@@ -606,11 +606,11 @@ extern "C" void cp_event_destroy(void *event) {
 extern "C" size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots) {
   using namespace cp;
   uint64_t n = N > max_spans ? N : max_spans;
-  // tile totals (at most 32 bytes each), three per-token words (insert), one 16-byte descriptor per
-  // token (gather, insert) and one flag byte per token (floating anchors), span offsets, one chain
-  // head per pool slot, the cos/sin digit tables; pieces padded to 256 bytes
-  return (size_t)(((uint64_t)div_up(n, kScanTile) + 2) * 32 + (3ull * 4 + 16 + 1) * N + 4ull * ((uint64_t)max_spans + 1) +
-                  4ull * n_pool_slots + (size_t)kTrigLevels * kTrigDigit * kMaxHalfDim * sizeof(double2) + 12 * 256);
+  // tile totals (at most 32 bytes each), four per-token words (insert), one 16-byte descriptor per
+  // token (gather, insert) and two flag bytes per token (floating anchors, chain-recording insert),
+  // span offsets, one chain head per pool slot, the cos/sin digit tables; pieces padded to 256 bytes
+  return (size_t)(((uint64_t)div_up(n, kScanTile) + 2) * 32 + (4ull * 4 + 16 + 2) * N + 4ull * ((uint64_t)max_spans + 1) +
+                  4ull * n_pool_slots + (size_t)kTrigLevels * kTrigDigit * kMaxHalfDim * sizeof(double2) + 16 * 256);
 }
 
 extern "C" int32_t cp_last_hip_error(void) { return cp::last_hip_error(); }

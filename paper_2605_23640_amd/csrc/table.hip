@@ -231,9 +231,11 @@ __global__ __launch_bounds__(256) void insert_resolve_kernel(const uint32_t *__r
                                                              const uint32_t *__restrict__ rank,
                                                              const uint32_t *__restrict__ free_slots, uint32_t n_free,
                                                              uint32_t n_pool_slots, uint32_t N,
-                                                             uint32_t *__restrict__ slot_out) {
+                                                             uint32_t *__restrict__ slot_out,
+                                                             uint8_t *__restrict__ owner) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
+  if (owner) owner[i] = 0;  // set again by the commit step for the tokens that store
   uint32_t e = entry_of[i], s = CP_SLOT_NONE;
   if (e != CP_SLOT_NONE) {
     uint32_t v = vals[e];
@@ -249,6 +251,26 @@ __global__ __launch_bounds__(256) void insert_resolve_kernel(const uint32_t *__r
   slot_out[i] = s;
 }
 
+// What the chain-recording insert adds (all null otherwise): the batch's tokens and run offsets, the
+// slot every token resolved to, the per-slot token / parent arrays and a flag per storing token.
+struct ChainRecord {
+  const uint32_t *tok, *run_off, *cand;
+  uint32_t *slot_tok, *slot_parent;
+  uint8_t *owner;
+};
+
+// Chain-recording insert, last step: a token that took a slot but whose run was not confirmed up to
+// it (the slot found for an earlier token of the run holds another text) leaves a slot nobody may
+// match: its parent is set to a value no candidate ever equals.
+__global__ __launch_bounds__(256) void insert_poison_kernel(const uint8_t *__restrict__ owner,
+                                                            const uint32_t *__restrict__ cand,
+                                                            const uint32_t *__restrict__ slot_out, uint32_t N,
+                                                            uint32_t n_pool_slots, uint32_t *__restrict__ slot_parent) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N || !owner[i]) return;
+  if (slot_out[i] == CP_SLOT_NONE && cand[i] < n_pool_slots) slot_parent[cand[i]] = CP_PARENT_POISON;
+}
+
 // Insert, step 4: owners replace the marker by their slot (or by "absent" when
 // the free list ran out) and record the position their token had in its request.
 __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__restrict__ entry_of, uint32_t *vals,
@@ -257,7 +279,7 @@ __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__re
                                                             uint32_t n_pool_slots, const uint32_t *__restrict__ off,
                                                             uint32_t R, uint32_t N, int32_t *__restrict__ slot_pos,
                                                             MoveItem *__restrict__ items,
-                                                            uint32_t *__restrict__ move_counter) {
+                                                            uint32_t *__restrict__ move_counter, ChainRecord chain) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) *move_counter = 0;  // work counter of the scatter that follows
   if (i >= N) return;
@@ -268,6 +290,17 @@ __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__re
     s = free_slots[r];
     if (s < n_pool_slots) slot_pos[s] = (int32_t)(i - off[request_of(off, R, i)]);
     else s = CP_SLOT_NONE;  // a free-list entry outside the pool is never used
+  }
+  if (chain.slot_tok && s != CP_SLOT_NONE) {
+    // the slot's node of the trie of stored runs: its token and the slot of the token before it
+    uint32_t parent = CP_SLOT_NONE;
+    if (chain.run_off[i] != 0) {
+      parent = i ? chain.cand[i - 1] : CP_SLOT_NONE;
+      if (parent == CP_SLOT_NONE) parent = CP_PARENT_POISON;  // its predecessor has no slot: never matches
+    }
+    chain.slot_tok[s] = chain.tok[i];
+    chain.slot_parent[s] = parent;
+    chain.owner[i] = 1;
   }
   vals[e] = s;
   // work list of the scatter: token i -> slot s (an unusable entry is marked and skipped)
@@ -344,17 +377,20 @@ int32_t launch_window_hits(hipStream_t stream, const cp_table &anchors, const ui
 }
 }  // namespace cp
 
-extern "C" int32_t cp_insert_kv(void *stream_, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
-                                uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
-                                cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
-                                int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
-                                void *scratch, size_t scratch_bytes) {
+static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
+                             uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
+                             cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
+                             int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
+                             void *scratch, size_t scratch_bytes, const uint32_t *tok, const uint32_t *run_off,
+                             uint32_t *slot_tok, uint32_t *slot_parent) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
+  const bool chain = slot_tok != nullptr;
   if (N >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (int32_t rc = table_ok(table)) return rc;
   if (!n_inserted || !status_flags || !scratch || !aligned(scratch, 256)) return CP_ERR_INVALID_ARG;
   if (N && (!hash || !off || R == 0 || !slot_out || !slot_pos || !src || !pool)) return CP_ERR_INVALID_ARG;
+  if (chain && N && (!tok || !run_off || !slot_parent)) return CP_ERR_INVALID_ARG;
   if (n_free && !free_slots) return CP_ERR_INVALID_ARG;
   if (!aligned(hash, 8) || !aligned(src, 16) || !aligned(pool, 16)) return CP_ERR_INVALID_ARG;
   if (!layout_ok(src_l) || !layout_ok(pool_l) || !layouts_match(src_l, pool_l)) return CP_ERR_UNSUPPORTED;
@@ -365,7 +401,9 @@ extern "C" int32_t cp_insert_kv(void *stream_, cp_table table, const uint64_t *h
   uint32_t *rank = sc.take<uint32_t>(N);
   uint32_t *counter = sc.take<uint32_t>(1);
   MoveItem *items = sc.take<MoveItem>(N);
-  if (!agg || !entry_of || !rank || !counter || !items) return CP_ERR_SCRATCH;
+  uint32_t *cand = chain ? sc.take<uint32_t>(N) : slot_out;  // slot every token's key resolves to
+  uint8_t *owner = chain ? sc.take<uint8_t>(N) : nullptr;
+  if (!agg || !entry_of || !rank || !counter || !items || (N && !cand) || (chain && !owner)) return CP_ERR_SCRATCH;
   const uint32_t blocks = div_up(N, 256);
   if (N)
     insert_claim_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
@@ -374,11 +412,44 @@ extern "C" int32_t cp_insert_kv(void *stream_, cp_table table, const uint64_t *h
   if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, agg)) return rc;
   if (N == 0) return CP_OK;
   insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, N,
-                                                    slot_out);
+                                                    cand, owner);
+  ChainRecord rec{tok, run_off, cand, slot_tok, slot_parent, owner};
   insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, off, R,
-                                                   N, slot_pos, items, counter);
+                                                   N, slot_pos, items, counter, chain ? rec : ChainRecord{});
   if (int32_t rc = check_launch()) return rc;
+  if (chain) {
+    // confirm every token's slot against the recorded chains (new slots are consistent by construction,
+    // slots found under an existing key need not be), then take the unconfirmed new slots out of play
+    if (int32_t rc = launch_chain_verify(stream, tok, run_off, cand, N, slot_tok, slot_parent, n_pool_slots, 0,
+                                         slot_out, agg))
+      return rc;
+    insert_poison_kernel<<<blocks, 256, 0, stream>>>(owner, cand, slot_out, N, n_pool_slots, slot_parent);
+    if (int32_t rc = check_launch()) return rc;
+  }
   uint32_t max_items = N < n_free ? N : n_free;
   return launch_scatter(stream, src, src_l, N, pool, pool_l, n_pool_slots, items, n_inserted, max_items, counter,
                         status_flags);
+}
+
+extern "C" int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
+                                uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
+                                cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
+                                int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
+                                void *scratch, size_t scratch_bytes) {
+  return insert_common(stream, table, hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
+                       slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, nullptr, nullptr, nullptr,
+                       nullptr);
+}
+
+extern "C" int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, const uint32_t *tok,
+                                      const uint32_t *run_off, const uint32_t *off, uint32_t N, uint32_t R,
+                                      const uint32_t *free_slots, uint32_t n_free, const void *src, cp_kv_layout src_l,
+                                      void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, int32_t *slot_pos,
+                                      uint32_t *slot_tok, uint32_t *slot_parent, uint32_t *slot_out,
+                                      uint32_t *n_inserted, uint32_t *status_flags, void *scratch,
+                                      size_t scratch_bytes) {
+  if (!slot_tok || !slot_parent) return CP_ERR_INVALID_ARG;
+  return insert_common(stream, table, hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
+                       slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, tok, run_off, slot_tok,
+                       slot_parent);
 }

@@ -9,6 +9,12 @@ and, for a pool with floating anchors (window W),
     lookup :  cp_hash_runs -> cp_hash_floating -> cp_probe2 -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_runs -> cp_insert_anchors -> cp_insert_kv
 
+and, for a pool that confirms every match exactly (``verify=True``),
+
+    lookup :  cp_hash_runs -> cp_probe -> cp_verify_chain [-> cp_hash_floating -> cp_probe -> cp_verify_chain]
+              -> cp_build_spans -> cp_gather_kv
+    insert :  cp_hash_runs [-> cp_insert_anchors] -> cp_insert_kv_chain
+
 Nothing here computes: tensors are allocated and handed to the C ABI.
 """
 from __future__ import annotations
@@ -42,6 +48,8 @@ class LookupBuffers:
         self.hash = torch.empty(N, dtype=i64, device=device)
         self.hash_float = torch.empty(N, dtype=i64, device=device)  # floating-anchor keys (if the pool uses them)
         self.run_off = torch.empty(N, dtype=i32, device=device)
+        self.float_off = torch.empty(N, dtype=i32, device=device)
+        self.cand = torch.empty(N, dtype=i32, device=device)  # unconfirmed slots (pools that verify)
         self.slot = torch.empty(N, dtype=i32, device=device)
         m = max(1, self.max_spans)
         self.span_src = torch.empty(m, dtype=i32, device=device)
@@ -58,7 +66,7 @@ class KVPool:
     cached position of every slot and the free list (hand-out order)."""
 
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
-                 device="cuda", pool_tensor=None, anchor_window=None, anchor_capacity=None):
+                 device="cuda", pool_tensor=None, anchor_window=None, anchor_capacity=None, verify=False):
         self.device = device
         self.n_slots = int(n_slots)
         self.layout = B.KVLayout.token_major(n_layers, n_kv_heads, head_dim)
@@ -80,6 +88,13 @@ class KVPool:
             cap = anchor_capacity if anchor_capacity is not None else max(1024, self.n_slots // 4)
             self.anchors = B.Table((int(cap) + B.TABLE_BUCKET - 1) // B.TABLE_BUCKET * B.TABLE_BUCKET, device)
 
+        # exact verification: per slot, the token it was stored for and the slot of its predecessor in the run
+        self.verify = bool(verify)
+        self.slot_tok = self.slot_parent = None
+        if self.verify:
+            self.slot_tok = torch.zeros(self.n_slots, dtype=torch.int32, device=device)
+            self.slot_parent = torch.full((self.n_slots,), B.PARENT_POISON - (1 << 32), dtype=torch.int32, device=device)
+
     def request_layout(self, n_tokens):
         L, H, D = self.shape
         return B.KVLayout.layer_major(L, H, D, n_tokens)
@@ -94,7 +109,18 @@ class KVPool:
         ``gather_events`` = (start, end) torch events recorded on the stream around
         the gather call alone (for timing)."""
         N = tok.numel()
-        if self.anchors is None:
+        if self.verify:
+            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
+            B.cp_probe(self.table, buf.hash, buf.cand, stream=stream)
+            B.cp_verify_chain(tok, buf.run_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, False,
+                              buf.slot, buf.scratch, stream=stream)
+            if self.anchors is not None:
+                B.cp_hash_floating(self.anchors, buf.hash, buf.run_off, self.anchor_window, buf.hash_float,
+                                   buf.scratch, stream=stream, float_off_out=buf.float_off)
+                B.cp_probe(self.table, buf.hash_float, buf.cand, stream=stream)
+                B.cp_verify_chain(tok, buf.float_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, True,
+                                  buf.slot, buf.scratch, stream=stream)
+        elif self.anchors is None:
             B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
             B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
         else:
@@ -122,20 +148,28 @@ class KVPool:
         """Store the non-sensitive tokens of a batch that the pool does not hold yet,
         taking their KV rows from ``src`` (layer-major, N tokens).  With ``sync`` the
         host free-list cursor is advanced (one device-to-host read).  A pool with
-        floating anchors also needs ``run_off_buf`` (int32[N]; filled here unless
-        ``hashes_ready``)."""
+        floating anchors or verification also needs ``run_off_buf`` (int32[N];
+        filled here unless ``hashes_ready``)."""
         N = tok.numel()
-        if self.anchors is not None:
-            assert run_off_buf is not None, "a pool with floating anchors needs run_off_buf"
+        if self.anchors is not None or self.verify:
+            assert run_off_buf is not None, "a pool with floating anchors or verification needs run_off_buf"
             if not hashes_ready:
                 B.cp_hash_runs(tok, mask, off, hash_buf, run_off_buf, scratch, stream=stream)
-            B.cp_insert_anchors(self.anchors, hash_buf, run_off_buf, self.anchor_window, self.flags, stream=stream)
+            if self.anchors is not None:
+                B.cp_insert_anchors(self.anchors, hash_buf, run_off_buf, self.anchor_window, self.flags,
+                                    stream=stream)
         elif not hashes_ready:
             B.cp_hash_segments(tok, mask, off, hash_buf, scratch, stream=stream)
         n_free = self.free_slots.numel() - self.n_used
-        B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src, self.request_layout(N),
-                       self.pool, self.layout, self.n_slots, self.slot_pos, slot_out, self.n_inserted, self.flags,
-                       scratch, stream=stream)
+        if self.verify:
+            B.cp_insert_kv_chain(self.table, hash_buf, tok, run_off_buf, off, self.free_slots[self.n_used:], n_free,
+                                 src, self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos,
+                                 self.slot_tok, self.slot_parent, slot_out, self.n_inserted, self.flags, scratch,
+                                 stream=stream)
+        else:
+            B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src,
+                           self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos, slot_out,
+                           self.n_inserted, self.flags, scratch, stream=stream)
         if sync:
             n = int(self.n_inserted.item())
             self.n_used += n

@@ -29,12 +29,12 @@ def bf16_ordinal(bits):
     return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
 
 
-def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, anchor_capacity=None):
+def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, anchor_capacity=None, verify=False):
     """Run prefill + lookup on both sides and compare everything."""
     fl = []
-    ost = OH.prefill(wl, flags_out=fl, anchor_window=anchor_window)
+    ost = OH.prefill(wl, flags_out=fl, anchor_window=anchor_window, verify=verify)
     olk = OH.lookup(ost)
-    gst = G.prefill(wl, G.make_pool(wl, anchor_window=anchor_window, anchor_capacity=anchor_capacity))
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=anchor_window, anchor_capacity=anchor_capacity, verify=verify))
     glk = G.lookup(gst)
     if anchor_window is not None:
         assert np.array_equal(glk.run_off, olk.run_off)
