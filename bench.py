@@ -43,7 +43,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None):
+def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False):
     """The CPU oracle, as it stands, on the first ``n_requests`` requests of the workload."""
     import oracle as O
     from cp_workload import gen
@@ -63,7 +63,7 @@ def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None):
     del dev
     pool = np.empty((sw.pool_slots, sh.n_layers, 2, re), np.uint16)  # untouched pages stay virtual
     st = OH.prefill(sw, src_provider=lambda t0, n: np.ascontiguousarray(host_src[:, :, t0:t0 + n]), pool=pool,
-                    anchor_window=anchor_window)
+                    anchor_window=anchor_window, verify=verify)
     del host_src
     lk = OH.lookup(st)  # hash, probe, spans, gather: timed inside
     N = sw.n_tokens
@@ -71,6 +71,8 @@ def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None):
     t = time.perf_counter()
     slot_out, n_new, _ = O.insert_kv(st.index, lk.hash, sw.off, sw.free_slots[st.n_used:], lk.dst, OH.buf_layout(sh, N),
                                      st.pool, OH.pool_layout(sh), slot_pos)
+    if st.text is not None:
+        O.text_record(st.text, sw.tok, lk.run_off, slot_out)
     t_ins = time.perf_counter() - t
     matched = int((lk.slot != O.SLOT_NONE).sum())
     t_total = sum(lk.times.values()) + t_ins
@@ -92,6 +94,8 @@ def main():
     ap.add_argument("--workload", default="llama3-8b", choices=["tiny", "llama3-8b", "frag", "rope", "llama3-70b", "float"])
     ap.add_argument("--anchor-window", type=int, default=None,
                     help="W: look stored runs up through floating anchors as well (default: run-start keys only)")
+    ap.add_argument("--verify", action="store_true",
+                    help="confirm every match exactly against the pool's per-slot (token, parent) records")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
@@ -125,7 +129,7 @@ def main():
     N = wl.n_tokens
     log(f"[bench] workload {wl.name}: {wl.n_requests} requests, {N} tokens, {sh.tok_bytes // 1024} KiB/token, "
         f"pool {wl.pool_slots} slots = {wl.pool_slots * sh.tok_bytes / 2**30:.1f} GiB")
-    gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window))
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window, verify=args.verify))
     pool = gst.pool
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
 
@@ -231,7 +235,7 @@ def main():
                         f"({sh.tok_bytes // 1024} KiB/token), pool {wl.pool_slots} slots "
                         f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) token-major, slots in random order",
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
-            "anchor_window": args.anchor_window,
+            "anchor_window": args.anchor_window, "verify": args.verify,
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
             "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,
         },
@@ -266,7 +270,7 @@ def main():
     if args.cpu_requests > 0:
         del dst
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np, args.anchor_window)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np, args.anchor_window, args.verify)
     print(json.dumps(out), flush=True)
 
 
