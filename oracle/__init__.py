@@ -87,6 +87,14 @@ def lib():
         L.cpo_text_free.argtypes = [vp]
         L.cpo_text_record.argtypes = [vp, vp, vp, u32, vp]
         L.cpo_verify.argtypes = [vp, vp, vp, vp, u32, C.c_int, vp]
+        L.cpo_filter_matches.argtypes = [vp, vp, u32, u32, vp, u32, vp]
+        L.cpo_mark_recompute.argtypes = [vp, vp, u32, u32, vp]
+        L.cpo_fill_unmatched.argtypes = [vp, u32, vp, Layout]
+        L.cpo_touch.argtypes = [vp, u32, u32, u32, vp]
+        L.cpo_lru_threshold.restype = u32
+        L.cpo_lru_threshold.argtypes = [vp, u32, u32, u32, u32]
+        L.cpo_evict.restype = u32
+        L.cpo_evict.argtypes = [vp, vp, u32, u32, vp, vp, vp]
         L.cpo_probe2.argtypes = [vp, vp, vp, u32, vp]
         L.cpo_bf16_to_double.restype = C.c_double
         L.cpo_bf16_to_double.argtypes = [C.c_uint16]
@@ -190,6 +198,52 @@ def probe2(index: Index, hash_a, hash_b):
     out = np.empty(hash_a.shape[0], np.uint32)
     lib().cpo_probe2(index._h, _p(hash_a), _p(hash_b), hash_a.shape[0], _p(out))
     return out
+
+
+LRU_MAX_AGE = 4096  # ages of LRU_MAX_AGE - 1 epochs and more are evicted as one class
+
+
+def filter_matches(slot, off, min_len, slot_recompute=None):
+    slot, off = _arr(slot, np.uint32), _arr(off, np.uint32)
+    out = np.empty(slot.shape[0], np.uint32)
+    n_slots = 0 if slot_recompute is None else slot_recompute.shape[0]
+    lib().cpo_filter_matches(_p(slot), _p(off), len(off) - 1, int(min_len),
+                             None if slot_recompute is None else _p(slot_recompute), n_slots, _p(out))
+    return out
+
+
+def mark_recompute(slot, recompute, slot_recompute):
+    """In place on slot_recompute (uint8[n_slots])."""
+    slot, recompute = _arr(slot, np.uint32), _arr(recompute, np.uint8)
+    assert slot_recompute.dtype == np.uint8 and slot_recompute.flags.c_contiguous
+    lib().cpo_mark_recompute(_p(slot), _p(recompute), slot.shape[0], slot_recompute.shape[0], _p(slot_recompute))
+
+
+def fill_unmatched(slot, dst, dst_l: Layout):
+    slot = _arr(slot, np.uint32)
+    assert dst.flags.c_contiguous
+    lib().cpo_fill_unmatched(_p(slot), slot.shape[0], _p(dst), dst_l)
+
+
+def touch(slot, epoch, slot_stamp):
+    """In place on slot_stamp (uint32[n_slots])."""
+    slot = _arr(slot, np.uint32)
+    assert slot_stamp.dtype == np.uint32 and slot_stamp.flags.c_contiguous
+    lib().cpo_touch(_p(slot), slot.shape[0], int(epoch), slot_stamp.shape[0], _p(slot_stamp))
+
+
+def lru_threshold(slot_stamp, epoch_now, n_needed, max_age=LRU_MAX_AGE):
+    assert slot_stamp.dtype == np.uint32 and slot_stamp.flags.c_contiguous
+    return int(lib().cpo_lru_threshold(_p(slot_stamp), slot_stamp.shape[0], int(epoch_now), int(n_needed), int(max_age)))
+
+
+def evict(index: Index, slot_stamp, threshold, text: "Text | None" = None, slot_recompute=None):
+    """Frees slots in place; returns the freed slots (ascending)."""
+    assert slot_stamp.dtype == np.uint32 and slot_stamp.flags.c_contiguous
+    freed = np.empty(slot_stamp.shape[0], np.uint32)
+    n = lib().cpo_evict(index._h, _p(slot_stamp), slot_stamp.shape[0], int(threshold), _p(freed),
+                        None if text is None else text._h, None if slot_recompute is None else _p(slot_recompute))
+    return freed[:n].copy()
 
 
 def hash_segments(tok, mask, off, base=BASE):

@@ -382,3 +382,88 @@ extern "C" void cpo_probe2(const cpo_index *ix, const uint64_t *hash_a, const ui
     }
   }
 }
+
+// ---- pool policies ------------------------------------------------------------------------------
+
+// Sec. 4.2.1 "Optimization": a reusable segment must have a minimum length.  Step 3: tokens marked
+// for recomputation are not reused.  One pass per request: find each maximal stretch of matched
+// tokens, drop it when it is too short, else drop only its marked tokens.
+extern "C" void cpo_filter_matches(const uint32_t *slot_in, const uint32_t *off, uint32_t R,
+                                   uint32_t min_len, const uint8_t *slot_recompute,
+                                   uint32_t n_pool_slots, uint32_t *slot_out) {
+  for (uint32_t r = 0; r < R; ++r) {
+    uint32_t i = off[r];
+    while (i < off[r + 1]) {
+      if (slot_in[i] == CPO_SLOT_NONE) {
+        slot_out[i++] = CPO_SLOT_NONE;
+        continue;
+      }
+      uint32_t e = i;
+      while (e < off[r + 1] && slot_in[e] != CPO_SLOT_NONE) ++e;  // stretch [i, e)
+      for (uint32_t k = i; k < e; ++k) {
+        uint32_t s = slot_in[k];
+        bool keep = e - i >= min_len;
+        if (keep && slot_recompute && s < n_pool_slots && slot_recompute[s]) keep = false;
+        slot_out[k] = keep ? s : CPO_SLOT_NONE;
+      }
+      i = e;
+    }
+  }
+}
+
+extern "C" void cpo_mark_recompute(const uint32_t *slot, const uint8_t *recompute, uint32_t N,
+                                   uint32_t n_pool_slots, uint8_t *slot_recompute) {
+  for (uint32_t i = 0; i < N; ++i)
+    if (slot[i] < n_pool_slots && recompute[i]) slot_recompute[slot[i]] = 1;
+}
+
+// Sec. 4.3.1 "Operational details": tokens that are not linked are zero placeholders.
+extern "C" void cpo_fill_unmatched(const uint32_t *slot, uint32_t N, void *dst, cpo_layout dst_l) {
+  const size_t row_bytes = (size_t)dst_l.n_kv_heads * dst_l.head_dim * 2;
+  for (uint32_t i = 0; i < N; ++i) {
+    if (slot[i] != CPO_SLOT_NONE) continue;
+    for (uint32_t l = 0; l < dst_l.n_layers; ++l)
+      for (uint32_t kv = 0; kv < 2; ++kv) std::memset((uint8_t *)row_ptr(dst, dst_l, i, l, kv), 0, row_bytes);
+  }
+}
+
+// Sec. 4.3.5 "Lifecycle management": least-recently-used eviction.  Every slot remembers the
+// number (epoch) of the last batch that used it; 0 = the slot is free.
+extern "C" void cpo_touch(const uint32_t *slot, uint32_t N, uint32_t epoch, uint32_t n_pool_slots,
+                          uint32_t *slot_stamp) {
+  for (uint32_t i = 0; i < N; ++i)
+    if (slot[i] < n_pool_slots && slot_stamp[slot[i]] < epoch) slot_stamp[slot[i]] = epoch;
+}
+
+extern "C" uint32_t cpo_lru_threshold(const uint32_t *slot_stamp, uint32_t n_pool_slots,
+                                      uint32_t epoch_now, uint32_t n_needed, uint32_t max_age) {
+  if (n_needed == 0) return 0;
+  // oldest first: all slots of age >= a go together; ages of max_age - 1 and more are one class
+  for (int64_t a = (int64_t)max_age - 1; a >= 0; --a) {
+    int64_t T = (int64_t)epoch_now - a + 1;  // "last used before epoch T"
+    if (T <= 1) continue;
+    uint64_t n = 0;
+    for (uint32_t s = 0; s < n_pool_slots; ++s)
+      if (slot_stamp[s] != 0 && (int64_t)slot_stamp[s] < T) ++n;
+    if (n >= n_needed) return (uint32_t)T;
+  }
+  return epoch_now + 1;  // not enough even so: everything that is in use goes
+}
+
+extern "C" uint32_t cpo_evict(cpo_index *ix, uint32_t *slot_stamp, uint32_t n_pool_slots,
+                              uint32_t threshold, uint32_t *freed_slots, cpo_text *text,
+                              uint8_t *slot_recompute) {
+  std::vector<uint8_t> gone(n_pool_slots, 0);
+  uint32_t n = 0;
+  for (uint32_t s = 0; s < n_pool_slots; ++s) {
+    if (slot_stamp[s] == 0 || slot_stamp[s] >= threshold) continue;
+    gone[s] = 1;
+    freed_slots[n++] = s;  // ascending slot order
+    slot_stamp[s] = 0;
+    if (slot_recompute) slot_recompute[s] = 0;
+    if (text) text->len[s] = 0;
+  }
+  for (auto it = ix->map.begin(); it != ix->map.end();)
+    it = (it->second < n_pool_slots && gone[it->second]) ? ix->map.erase(it) : std::next(it);
+  return n;
+}

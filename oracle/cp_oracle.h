@@ -162,6 +162,33 @@ void cpo_text_record(cpo_text *, const uint32_t *tok, const uint32_t *run_off, u
  * merge != 0 only entries of slot_out that are NONE are written. */
 void cpo_verify(const cpo_text *, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
                 uint32_t N, int merge, uint32_t *slot_out);
+/* ---- Pool policies ----
+ * Minimum segment length (Sec. 4.2.1 "Optimization"): a stretch = a maximal run of consecutive
+ * positions of one request with slot_in != NONE; a stretch shorter than min_len is dropped whole.
+ * Recompute marks (Sec. 4.2.1 Step 3): in a kept stretch, a token whose slot is marked in
+ * slot_recompute (nullable) is dropped.  Dropped = slot_out NONE. */
+void cpo_filter_matches(const uint32_t *slot_in, const uint32_t *off, uint32_t R, uint32_t min_len,
+                        const uint8_t *slot_recompute, uint32_t n_pool_slots, uint32_t *slot_out);
+/* slot_recompute[slot[i]] = 1 for every token with a slot and recompute[i] != 0 (marks accumulate). */
+void cpo_mark_recompute(const uint32_t *slot, const uint8_t *recompute, uint32_t N,
+                        uint32_t n_pool_slots, uint8_t *slot_recompute);
+/* Zero placeholders (Sec. 4.3.1 "Operational details"): all rows of every token with slot NONE
+ * are set to zero; other rows are not touched. */
+void cpo_fill_unmatched(const uint32_t *slot, uint32_t N, void *dst, cpo_layout dst_l);
+/* Least-recently-used eviction (Sec. 4.3.5 "Lifecycle management").  slot_stamp[s] = epoch of the
+ * last batch that used slot s, 0 = free.  cpo_touch raises the stamp of every named slot to epoch.
+ * cpo_lru_threshold returns the smallest T of the form epoch_now - a + 1, a < max_age, such that at
+ * least n_needed slots were last used before T (all slots of age max_age - 1 or more count as one
+ * class); epoch_now + 1 if even that is not enough, 0 if n_needed = 0.  cpo_evict frees every slot
+ * in use with stamp < threshold: its key leaves the index, its stamp, mark and text are cleared; the
+ * freed slots are listed in ascending order; returns their number. */
+void cpo_touch(const uint32_t *slot, uint32_t N, uint32_t epoch, uint32_t n_pool_slots,
+               uint32_t *slot_stamp);
+uint32_t cpo_lru_threshold(const uint32_t *slot_stamp, uint32_t n_pool_slots, uint32_t epoch_now,
+                           uint32_t n_needed, uint32_t max_age);
+uint32_t cpo_evict(cpo_index *, uint32_t *slot_stamp, uint32_t n_pool_slots, uint32_t threshold,
+                   uint32_t *freed_slots, cpo_text *text /* nullable */,
+                   uint8_t *slot_recompute /* nullable */);
 /* Building blocks exposed so that tests can pin them one by one. */
 double cpo_bf16_to_double(uint16_t bits);
 uint16_t cpo_double_to_bf16(double x); /* round-to-nearest-even, one rounding */
