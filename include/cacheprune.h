@@ -261,6 +261,60 @@ int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const u
                      int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
                      void *scratch, size_t scratch_bytes);
 
+/* ---- Pool policies -----------------------------------------------------------------------------
+ * All arrays are device memory owned by the caller; scratch as for the other calls
+ * (cp_scratch_bytes(N, 0, n_pool_slots)).
+ *
+ * cp_filter_matches - minimum segment length (Sec. 4.2.1 "Optimization": a segment qualifies as
+ * reusable only from a minimum length) and recompute marks (Sec. 4.2.1 Step 3: marked tokens of a
+ * reused segment are recomputed, not reused).  A stretch is a maximal run of consecutive positions
+ * of one request with slot_in != CP_SLOT_NONE.  slot_out[i] = CP_SLOT_NONE for every token of a
+ * stretch shorter than min_len and, in the other stretches, for tokens whose slot is marked in
+ * slot_recompute (u8[n_pool_slots], may be NULL); slot_in[i] otherwise.  A marked token counts
+ * towards the length of its stretch.  slot_out may be slot_in.
+ *
+ * cp_mark_recompute - slot_recompute[slot[i]] = 1 for every token with a slot and
+ * recompute[i] != 0.  Called with the slot_out of an insert; marks accumulate over batches.
+ *
+ * cp_fill_unmatched - zero placeholders (Sec. 4.3.1 "Operational details": tokens that are not
+ * linked are represented as zeros for the engine to fill): all rows of every token i < N of dst
+ * with slot[i] == CP_SLOT_NONE are set to zero; no other row is written.
+ *
+ * Least-recently-used eviction (Sec. 4.3.5 "Lifecycle management"), at the granularity of batches:
+ * slot_stamp[s] (u32[n_pool_slots]) = number (epoch >= 1) of the last batch that used slot s, 0 =
+ * the slot is free.
+ *   cp_touch: slot_stamp[slot[i]] = max(itself, epoch) for every token with a slot.  Call it with
+ *     the unfiltered slots of a lookup and with the slot_out of an insert; since a match at a token
+ *     implies matches at the tokens before it in its segment, a token is then never older than the
+ *     tokens stored behind it.
+ *   cp_lru_threshold: *threshold_out (device) = the smallest T = epoch_now - a + 1, 0 <= a <
+ *     CP_LRU_MAX_AGE, such that at least n_needed slots in use have stamp < T (slots of age
+ *     CP_LRU_MAX_AGE - 1 or more count as one class; stamps above epoch_now are never chosen);
+ *     epoch_now + 1 if all slots in use together are fewer; 0 if n_needed == 0.
+ *   cp_evict: every slot in use with stamp < *threshold (device) is freed: the value of its key's
+ *     table entry becomes CP_SLOT_NONE (the key stays and is reused if the text is stored again),
+ *     its stamp becomes 0, its slot_parent CP_PARENT_POISON and its slot_recompute 0 (both arrays
+ *     may be NULL).  freed_slots (u32[n_pool_slots]) receives the freed slots in ascending order,
+ *     *n_freed (device) their number: append them to the free list.
+ *   cp_table_compact: copy the live entries (value != CP_SLOT_NONE) of src into dst, which must be
+ *     initialised and must not share memory with src; drops the keys eviction left behind.
+ *     CP_FLAG_TABLE_FULL if dst is too small. */
+#define CP_LRU_MAX_AGE 4096u
+int32_t cp_filter_matches(void *stream, const uint32_t *slot_in, const uint32_t *off, uint32_t N, uint32_t R,
+                          uint32_t min_len, const uint8_t *slot_recompute, uint32_t n_pool_slots, uint32_t *slot_out,
+                          void *scratch, size_t scratch_bytes);
+int32_t cp_mark_recompute(void *stream, const uint32_t *slot, const uint8_t *recompute, uint32_t N,
+                          uint32_t n_pool_slots, uint8_t *slot_recompute);
+int32_t cp_fill_unmatched(void *stream, const uint32_t *slot, uint32_t N, void *dst, cp_kv_layout dst_l);
+int32_t cp_touch(void *stream, const uint32_t *slot, uint32_t N, uint32_t epoch, uint32_t n_pool_slots,
+                 uint32_t *slot_stamp);
+int32_t cp_lru_threshold(void *stream, const uint32_t *slot_stamp, uint32_t n_pool_slots, uint32_t epoch_now,
+                         uint32_t n_needed, uint32_t *threshold_out, void *scratch, size_t scratch_bytes);
+int32_t cp_evict(void *stream, cp_table table, uint32_t *slot_stamp, uint32_t n_pool_slots, const uint32_t *threshold,
+                 uint32_t *freed_slots, uint32_t *n_freed, uint32_t *slot_parent, uint8_t *slot_recompute,
+                 void *scratch, size_t scratch_bytes);
+int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags);
+
 #ifdef __cplusplus
 }
 #endif

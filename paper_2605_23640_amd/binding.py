@@ -32,8 +32,11 @@ EXPORTS = [
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
     "cp_insert_kv_chain", "cp_verify_chain",
+    "cp_filter_matches", "cp_mark_recompute", "cp_fill_unmatched", "cp_touch", "cp_lru_threshold", "cp_evict",
+    "cp_table_compact",
 ]
 PARENT_POISON = 0xFFFFFFFE
+LRU_MAX_AGE = 4096
 
 
 class CpError(RuntimeError):
@@ -113,6 +116,20 @@ def lib():
                                          u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_verify_chain.restype = i32
         L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, sz]
+        L.cp_filter_matches.restype = i32
+        L.cp_filter_matches.argtypes = [vp, vp, vp, u32, u32, u32, vp, u32, vp, vp, sz]
+        L.cp_mark_recompute.restype = i32
+        L.cp_mark_recompute.argtypes = [vp, vp, vp, u32, u32, vp]
+        L.cp_fill_unmatched.restype = i32
+        L.cp_fill_unmatched.argtypes = [vp, vp, u32, vp, KVLayout]
+        L.cp_touch.restype = i32
+        L.cp_touch.argtypes = [vp, vp, u32, u32, u32, vp]
+        L.cp_lru_threshold.restype = i32
+        L.cp_lru_threshold.argtypes = [vp, vp, u32, u32, u32, vp, vp, sz]
+        L.cp_evict.restype = i32
+        L.cp_evict.argtypes = [vp, TableStruct, vp, u32, vp, vp, vp, vp, vp, vp, sz]
+        L.cp_table_compact.restype = i32
+        L.cp_table_compact.argtypes = [vp, TableStruct, TableStruct, vp]
         L.cp_probe2.restype = i32
         L.cp_probe2.argtypes = [vp, TableStruct, vp, vp, u32, vp]
         L.cp_build_spans.restype = i32
@@ -278,6 +295,58 @@ def cp_insert_kv_chain(table: Table, hashes, tok, run_off, off, free_slots, n_fr
         _stream(stream), table.struct, _ptr(hashes), _ptr(tok), _ptr(run_off), _ptr(off), N, R, _ptr(free_slots),
         n_free, _ptr(src), src_l, _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_tok), _ptr(slot_parent),
         _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags), _ptr(scratch), scratch.numel()))
+
+
+def cp_filter_matches(slot_in, off, min_len, slot_recompute, n_pool_slots, slot_out, scratch, stream=None):
+    _need_cuda(slot_in, off, slot_recompute, slot_out, scratch)
+    N, R = slot_in.numel(), off.numel() - 1
+    assert slot_out.numel() == N and (slot_recompute is None or slot_recompute.numel() >= n_pool_slots)
+    _check("cp_filter_matches", lib().cp_filter_matches(_stream(stream), _ptr(slot_in), _ptr(off), N, R, int(min_len),
+                                                        _ptr(slot_recompute), n_pool_slots, _ptr(slot_out),
+                                                        _ptr(scratch), scratch.numel()))
+    return slot_out
+
+
+def cp_mark_recompute(slot, recompute, n_pool_slots, slot_recompute, stream=None):
+    _need_cuda(slot, recompute, slot_recompute)
+    N = slot.numel()
+    assert recompute.numel() == N and slot_recompute.numel() >= n_pool_slots
+    _check("cp_mark_recompute", lib().cp_mark_recompute(_stream(stream), _ptr(slot), _ptr(recompute), N, n_pool_slots,
+                                                        _ptr(slot_recompute)))
+
+
+def cp_fill_unmatched(slot, dst, dst_l: KVLayout, stream=None):
+    _need_cuda(slot, dst)
+    _check("cp_fill_unmatched", lib().cp_fill_unmatched(_stream(stream), _ptr(slot), slot.numel(), _ptr(dst), dst_l))
+
+
+def cp_touch(slot, epoch, n_pool_slots, slot_stamp, stream=None):
+    _need_cuda(slot, slot_stamp)
+    assert slot_stamp.numel() >= n_pool_slots
+    _check("cp_touch", lib().cp_touch(_stream(stream), _ptr(slot), slot.numel(), int(epoch), n_pool_slots,
+                                      _ptr(slot_stamp)))
+
+
+def cp_lru_threshold(slot_stamp, n_pool_slots, epoch_now, n_needed, threshold_out, scratch, stream=None):
+    _need_cuda(slot_stamp, threshold_out, scratch)
+    assert slot_stamp.numel() >= n_pool_slots
+    _check("cp_lru_threshold", lib().cp_lru_threshold(_stream(stream), _ptr(slot_stamp), n_pool_slots, int(epoch_now),
+                                                      int(n_needed), _ptr(threshold_out), _ptr(scratch),
+                                                      scratch.numel()))
+
+
+def cp_evict(table: Table, slot_stamp, n_pool_slots, threshold, freed_slots, n_freed, slot_parent, slot_recompute,
+             scratch, stream=None):
+    _need_cuda(slot_stamp, threshold, freed_slots, n_freed, slot_parent, slot_recompute, scratch)
+    assert slot_stamp.numel() >= n_pool_slots and freed_slots.numel() >= n_pool_slots
+    _check("cp_evict", lib().cp_evict(_stream(stream), table.struct, _ptr(slot_stamp), n_pool_slots, _ptr(threshold),
+                                      _ptr(freed_slots), _ptr(n_freed), _ptr(slot_parent), _ptr(slot_recompute),
+                                      _ptr(scratch), scratch.numel()))
+
+
+def cp_table_compact(src: Table, dst: Table, status_flags, stream=None):
+    _need_cuda(status_flags)
+    _check("cp_table_compact", lib().cp_table_compact(_stream(stream), src.struct, dst.struct, _ptr(status_flags)))
 
 
 def cp_probe2(table: Table, hash_a, hash_b, slot_out, stream=None):

@@ -103,59 +103,12 @@ __global__ __launch_bounds__(kProbeThreads) void window_hit_kernel(cp_table anch
   if (i < N && (threadIdx.x & (kBucket - 1)) == 0) hit[i] = r != CP_SLOT_NONE;
 }
 
-// Store the prefix hash of every run of at least W tokens (the chain hash of its W-th token) in the
-// anchor table: a set, so the order of arrival does not matter.
-__global__ __launch_bounds__(kProbeThreads) void insert_anchor_kernel(cp_table t, const uint64_t *__restrict__ hash,
-                                                                      const uint32_t *__restrict__ run_off,
-                                                                      uint32_t N, uint32_t W,
-                                                                      uint32_t *status_flags) {
-  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+// Index of the entry that holds key h, taking a free entry for it if there is none yet; CP_SLOT_NONE
+// if h is CP_HASH_NONE or every bucket is full.  Called by all lanes of a wavefront together; the 16
+// lanes of a group pass the same h and get the same answer.
+__device__ __forceinline__ uint32_t group_claim(const cp_table &t, uint64_t h) {
   const uint32_t sub = threadIdx.x & (kBucket - 1);
   const uint32_t n_buckets = (uint32_t)(t.capacity / kBucket);
-  uint64_t h = (q < N && run_off[q] == W - 1) ? hash[q] : CP_HASH_NONE;
-  bool active = h != CP_HASH_NONE;
-  uint32_t b = home_bucket(h, n_buckets), walked = 0, entry = CP_SLOT_NONE;
-  while (__any(active)) {
-    unsigned long long *kp = (unsigned long long *)&t.keys[(uint64_t)b * kBucket + sub];
-    uint64_t k = CP_HASH_NONE;
-    if (active) k = __hip_atomic_load(kp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    uint32_t hit = group_bits(__ballot(active && k == h));
-    uint32_t empty = group_bits(__ballot(active && k == CP_HASH_NONE));
-    bool try_claim = active && !hit && empty && sub == (uint32_t)(__ffs(empty) - 1);
-    uint64_t old = 0;
-    if (try_claim) old = atomicCAS(kp, (unsigned long long)CP_HASH_NONE, (unsigned long long)h);
-    uint32_t claimed = group_bits(__ballot(try_claim && (old == CP_HASH_NONE || old == h)));
-    if (active) {
-      if (hit) {
-        entry = b * kBucket + (__ffs(hit) - 1);
-        active = false;
-      } else if (empty) {
-        if (claimed) {
-          entry = b * kBucket + (__ffs(empty) - 1);
-          active = false;
-        }
-      } else if (++walked == n_buckets) {
-        active = false;
-      } else {
-        b = b + 1 == n_buckets ? 0 : b + 1;
-      }
-    }
-  }
-  if (q < N && sub == 0 && h != CP_HASH_NONE) {
-    if (entry != CP_SLOT_NONE) t.vals[entry] = 0;  // any value other than NONE marks membership
-    else atomicOr(status_flags, CP_FLAG_TABLE_FULL);
-  }
-}
-
-// Insert, step 1: find or claim the table entry of every token's key and leave
-// in vals[] the smallest packed index that asked for a not-yet-stored key.
-__global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t, const uint64_t *__restrict__ hash,
-                                                                     uint32_t N, uint32_t *__restrict__ entry_of,
-                                                                     uint32_t *status_flags) {
-  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
-  const uint32_t sub = threadIdx.x & (kBucket - 1);
-  const uint32_t n_buckets = (uint32_t)(t.capacity / kBucket);
-  uint64_t h = q < N ? hash[q] : CP_HASH_NONE;
   bool active = h != CP_HASH_NONE;
   uint32_t b = home_bucket(h, n_buckets), walked = 0, entry = CP_SLOT_NONE;
   while (__any(active)) {
@@ -187,6 +140,53 @@ __global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t,
       }
     }
   }
+  return entry;
+}
+
+// Store the prefix hash of every run of at least W tokens (the chain hash of its W-th token) in the
+// anchor table: a set, so the order of arrival does not matter.
+__global__ __launch_bounds__(kProbeThreads) void insert_anchor_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                                      const uint32_t *__restrict__ run_off,
+                                                                      uint32_t N, uint32_t W,
+                                                                      uint32_t *status_flags) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  const uint64_t h = (q < N && run_off[q] == W - 1) ? hash[q] : CP_HASH_NONE;
+  const uint32_t entry = group_claim(t, h);
+  if (q < N && sub == 0 && h != CP_HASH_NONE) {
+    if (entry != CP_SLOT_NONE) t.vals[entry] = 0;  // any value other than NONE marks membership
+    else atomicOr(status_flags, CP_FLAG_TABLE_FULL);
+  }
+}
+
+// Copy of the live entries of one table into another (fresh) one: the keys of evicted slots, which
+// stay behind with the value "absent", are left out.  One group of 16 lanes per source entry.
+__global__ __launch_bounds__(kProbeThreads) void table_compact_kernel(cp_table src, cp_table dst,
+                                                                      uint32_t *status_flags) {
+  const uint64_t e = ((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket;
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  uint64_t h = CP_HASH_NONE;
+  uint32_t v = CP_SLOT_NONE;
+  if (e < src.capacity) {
+    v = src.vals[e];
+    if (v < kPending) h = src.keys[e];
+  }
+  const uint32_t entry = group_claim(dst, h);
+  if (sub == 0 && h != CP_HASH_NONE) {
+    if (entry != CP_SLOT_NONE) dst.vals[entry] = v;
+    else atomicOr(status_flags, CP_FLAG_TABLE_FULL);
+  }
+}
+
+// Insert, step 1: find or claim the table entry of every token's key and leave
+// in vals[] the smallest packed index that asked for a not-yet-stored key.
+__global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                                     uint32_t N, uint32_t *__restrict__ entry_of,
+                                                                     uint32_t *status_flags) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  const uint64_t h = q < N ? hash[q] : CP_HASH_NONE;
+  const uint32_t entry = group_claim(t, h);
   if (q < N && sub == 0) {
     entry_of[q] = entry;
     if (entry != CP_SLOT_NONE) {
@@ -452,4 +452,14 @@ extern "C" int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64
   return insert_common(stream, table, hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
                        slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, tok, run_off, slot_tok,
                        slot_parent);
+}
+
+extern "C" int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags) {
+  using namespace cp;
+  if (int32_t rc = table_ok(src)) return rc;
+  if (int32_t rc = table_ok(dst)) return rc;
+  if (!status_flags || src.keys == dst.keys || src.vals == dst.vals) return CP_ERR_INVALID_ARG;
+  table_compact_kernel<<<div_up(src.capacity * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(
+      src, dst, status_flags);
+  return check_launch();
 }

@@ -15,6 +15,10 @@ and, for a pool that confirms every match exactly (``verify=True``),
               -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_runs [-> cp_insert_anchors] -> cp_insert_kv_chain
 
+Policies hook in after the slots are known: cp_touch (LRU stamps), cp_filter_matches (minimum
+length, recompute marks) before cp_build_spans, cp_fill_unmatched after the gather;
+cp_mark_recompute / cp_touch after an insert; ``evict`` = cp_lru_threshold -> cp_evict.
+
 Nothing here computes: tensors are allocated and handed to the C ABI.
 """
 from __future__ import annotations
@@ -50,7 +54,8 @@ class LookupBuffers:
         self.run_off = torch.empty(N, dtype=i32, device=device)
         self.float_off = torch.empty(N, dtype=i32, device=device)
         self.cand = torch.empty(N, dtype=i32, device=device)  # unconfirmed slots (pools that verify)
-        self.slot = torch.empty(N, dtype=i32, device=device)
+        self.slot = torch.empty(N, dtype=i32, device=device)  # slot of every matched token
+        self.served = torch.empty(N, dtype=i32, device=device)  # ... of those that pass the pool's policies
         m = max(1, self.max_spans)
         self.span_src = torch.empty(m, dtype=i32, device=device)
         self.span_dst = torch.empty(m, dtype=i32, device=device)
@@ -66,7 +71,8 @@ class KVPool:
     cached position of every slot and the free list (hand-out order)."""
 
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
-                 device="cuda", pool_tensor=None, anchor_window=None, anchor_capacity=None, verify=False):
+                 device="cuda", pool_tensor=None, anchor_window=None, anchor_capacity=None, verify=False,
+                 min_len=1, recompute_marks=False, zero_fill=False, lru=False):
         self.device = device
         self.n_slots = int(n_slots)
         self.layout = B.KVLayout.token_major(n_layers, n_kv_heads, head_dim)
@@ -94,6 +100,35 @@ class KVPool:
         if self.verify:
             self.slot_tok = torch.zeros(self.n_slots, dtype=torch.int32, device=device)
             self.slot_parent = torch.full((self.n_slots,), B.PARENT_POISON - (1 << 32), dtype=torch.int32, device=device)
+        # policies: minimum length of a reused stretch, per-slot recompute marks, zero placeholders for tokens
+        # that are not served, least-recently-used eviction by batch number (epoch)
+        self.min_len = int(min_len)
+        self.slot_recompute = torch.zeros(self.n_slots, dtype=torch.uint8, device=device) if recompute_marks else None
+        self.zero_fill = bool(zero_fill)
+        self.slot_stamp = torch.zeros(self.n_slots, dtype=torch.int32, device=device) if lru else None
+        self.epoch = 1
+        self.threshold = torch.zeros(1, dtype=torch.int32, device=device)
+        self.n_freed = torch.zeros(1, dtype=torch.int32, device=device)
+
+    @property
+    def filters(self):
+        return self.min_len > 1 or self.slot_recompute is not None
+
+    def n_free(self):
+        return self.free_slots.numel() - self.n_used
+
+    def evict(self, n_needed, scratch, stream=None):
+        """Free at least ``n_needed`` slots, least recently used batches first (whole batches
+        at a time); the freed slots go to the end of the free list.  Reads one count back."""
+        assert self.slot_stamp is not None, "pool was created without lru=True"
+        freed = torch.empty(self.n_slots, dtype=torch.int32, device=self.device)
+        B.cp_lru_threshold(self.slot_stamp, self.n_slots, self.epoch, n_needed, self.threshold, scratch, stream=stream)
+        B.cp_evict(self.table, self.slot_stamp, self.n_slots, self.threshold, freed, self.n_freed, self.slot_parent,
+                   self.slot_recompute, scratch, stream=stream)
+        n = int(self.n_freed.item())
+        self.free_slots = torch.cat([self.free_slots[self.n_used:], freed[:n]])
+        self.n_used = 0
+        return freed[:n]
 
     def request_layout(self, n_tokens):
         L, H, D = self.shape
@@ -128,7 +163,13 @@ class KVPool:
             B.cp_hash_floating(self.anchors, buf.hash, buf.run_off, self.anchor_window, buf.hash_float, buf.scratch,
                                stream=stream)
             B.cp_probe2(self.table, buf.hash, buf.hash_float, buf.slot, stream=stream)
-        B.cp_build_spans(buf.slot, off, self.slot_pos if self.rope is not None else None, buf.max_spans, buf.span_src,
+        if self.slot_stamp is not None:
+            B.cp_touch(buf.slot, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
+        served = buf.slot  # buf.slot: every matched token; served: those that pass the policies
+        if self.filters:
+            served = B.cp_filter_matches(buf.slot, off, self.min_len, self.slot_recompute, self.n_slots, buf.served,
+                                         buf.scratch, stream=stream)
+        B.cp_build_spans(served, off, self.slot_pos if self.rope is not None else None, buf.max_spans, buf.span_src,
                          buf.span_dst, buf.span_len, buf.span_delta, buf.span_off, buf.n_spans, self.flags,
                          buf.scratch, stream=stream)
         if gather:
@@ -140,16 +181,19 @@ class KVPool:
                            stream=stream)
             if gather_events is not None:
                 gather_events[1].record(stream)
+            if self.zero_fill:
+                B.cp_fill_unmatched(served, dst, self.request_layout(N), stream=stream)
         return LookupResult(buf.hash, buf.slot, buf.span_src, buf.span_dst, buf.span_len, buf.span_delta,
                             buf.span_off, buf.n_spans)
 
     def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None,
-               run_off_buf=None):
+               run_off_buf=None, recompute=None):
         """Store the non-sensitive tokens of a batch that the pool does not hold yet,
         taking their KV rows from ``src`` (layer-major, N tokens).  With ``sync`` the
         host free-list cursor is advanced (one device-to-host read).  A pool with
         floating anchors or verification also needs ``run_off_buf`` (int32[N];
-        filled here unless ``hashes_ready``)."""
+        filled here unless ``hashes_ready``).  ``recompute`` (uint8[N]): tokens the
+        annotator marked for recomputation when their segment is reused."""
         N = tok.numel()
         if self.anchors is not None or self.verify:
             assert run_off_buf is not None, "a pool with floating anchors or verification needs run_off_buf"
@@ -170,6 +214,11 @@ class KVPool:
             B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src,
                            self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos, slot_out,
                            self.n_inserted, self.flags, scratch, stream=stream)
+        if recompute is not None:
+            assert self.slot_recompute is not None, "pool was created without recompute_marks=True"
+            B.cp_mark_recompute(slot_out, recompute, self.n_slots, self.slot_recompute, stream=stream)
+        if self.slot_stamp is not None:
+            B.cp_touch(slot_out, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         if sync:
             n = int(self.n_inserted.item())
             self.n_used += n
