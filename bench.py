@@ -43,7 +43,8 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False):
+def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False, min_len=1, recompute=0.0,
+                 zero_fill=False):
     """The CPU oracle, as it stands, on the first ``n_requests`` requests of the workload."""
     import oracle as O
     from cp_workload import gen
@@ -63,9 +64,10 @@ def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False)
     del dev
     pool = np.empty((sw.pool_slots, sh.n_layers, 2, re), np.uint16)  # untouched pages stay virtual
     st = OH.prefill(sw, src_provider=lambda t0, n: np.ascontiguousarray(host_src[:, :, t0:t0 + n]), pool=pool,
-                    anchor_window=anchor_window, verify=verify)
+                    anchor_window=anchor_window, verify=verify,
+                    recompute=None if recompute <= 0.0 else (sw.donor_u < recompute).astype(np.uint8))
     del host_src
-    lk = OH.lookup(st)  # hash, probe, spans, gather: timed inside
+    lk = OH.lookup(st, min_len=min_len, zero_fill=zero_fill)  # hash, probe, spans, gather: timed inside
     N = sw.n_tokens
     slot_pos = st.slot_pos
     t = time.perf_counter()
@@ -74,7 +76,7 @@ def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False)
     if st.text is not None:
         O.text_record(st.text, sw.tok, lk.run_off, slot_out)
     t_ins = time.perf_counter() - t
-    matched = int((lk.slot != O.SLOT_NONE).sum())
+    matched = int((lk.served != O.SLOT_NONE).sum())
     t_total = sum(lk.times.values()) + t_ins
     moved = 2.0 * sh.tok_bytes * (matched + n_new)
     return {
@@ -96,6 +98,11 @@ def main():
                     help="W: look stored runs up through floating anchors as well (default: run-start keys only)")
     ap.add_argument("--verify", action="store_true",
                     help="confirm every match exactly against the pool's per-slot (token, parent) records")
+    ap.add_argument("--min-len", type=int, default=1, help="drop matched stretches shorter than this many tokens")
+    ap.add_argument("--recompute", type=float, default=0.0,
+                    help="fraction of the stored tokens marked for recomputation (seeded, uniform): not served")
+    ap.add_argument("--zero-fill", action="store_true", help="write zero rows for every token that is not served")
+    ap.add_argument("--lru", action="store_true", help="keep last-use stamps for eviction")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
@@ -129,7 +136,13 @@ def main():
     N = wl.n_tokens
     log(f"[bench] workload {wl.name}: {wl.n_requests} requests, {N} tokens, {sh.tok_bytes // 1024} KiB/token, "
         f"pool {wl.pool_slots} slots = {wl.pool_slots * sh.tok_bytes / 2**30:.1f} GiB")
-    gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window, verify=args.verify))
+    rec = None
+    if args.recompute > 0.0:
+        assert wl.donor_u is not None, "this workload draws no recompute marks"
+        rec = (wl.donor_u < args.recompute).astype(np.uint8)
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window, verify=args.verify, min_len=args.min_len,
+                                    recompute_marks=rec is not None, zero_fill=args.zero_fill, lru=args.lru),
+                    recompute=rec)
     pool = gst.pool
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
 
@@ -175,7 +188,7 @@ def main():
     matched = int(buf.span_off[n_spans].item())
     inserted = int(pool.n_inserted.item())
     flags = int(pool.flags.item())
-    slots = G.host_u32(buf.slot)
+    slots = G.host_u32(buf.served if pool.filters else buf.slot)
     unique_src = int(len(np.unique(slots[slots != 0xFFFFFFFF])))
     gather_ms = float(np.mean([hev.elapsed_ms(2 * k, 2 * k + 1) for k in range(K)]))
     insert_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_ins]))
@@ -235,7 +248,8 @@ def main():
                         f"({sh.tok_bytes // 1024} KiB/token), pool {wl.pool_slots} slots "
                         f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) token-major, slots in random order",
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
-            "anchor_window": args.anchor_window, "verify": args.verify,
+            "anchor_window": args.anchor_window, "verify": args.verify, "min_len": args.min_len,
+            "recompute_fraction": args.recompute, "zero_fill": args.zero_fill, "lru_stamps": args.lru,
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
             "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,
         },
@@ -270,7 +284,8 @@ def main():
     if args.cpu_requests > 0:
         del dst
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np, args.anchor_window, args.verify)
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_requests, G, torch, np, args.anchor_window, args.verify,
+                                           args.min_len, args.recompute, args.zero_fill)
     print(json.dumps(out), flush=True)
 
 

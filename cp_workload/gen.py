@@ -58,6 +58,9 @@ class Workload:
     rope_theta: float | None = None  # None: no key re-rotation in this workload
     rope_style: int = 0
     notes: dict = field(default_factory=dict)
+    # one uniform number per donor token, equal wherever donors share text (it travels with the prefix and with
+    # each document): "marked for recomputation at rate rho" = donor_u < rho.  None: not drawn for this workload.
+    donor_u: np.ndarray | None = None
 
     @property
     def n_tokens(self) -> int:
@@ -237,11 +240,15 @@ def make_docs(name, seed, shape, R, T, prefix_len, n_docs, doc_len, docs_per_req
     dt, dm, doff = _pack(d_tok, d_mask)
     if table_capacity is None:
         table_capacity = 2 * pool_slots
+    urng = np.random.default_rng(seed ^ 0x5EC0)  # a stream of its own: the prompts above do not depend on it
+    prefix_u = urng.random(prefix_len, dtype=np.float32)
+    doc_u = [urng.random(len(d), dtype=np.float32) for d in docs]
+    donor_u = np.concatenate([np.concatenate([prefix_u, doc_u[d]]) for d in range(n_docs)])
     return Workload(
         name=name, seed=seed, shape=shape, tok=tok, mask=mask, off=off,
         donor_tok=dt, donor_mask=dm, donor_off=doff, donor_batches=_batches(doff, donor_batch_tokens),
         pool_slots=pool_slots, free_slots=rng.permutation(pool_slots).astype(np.uint32),
-        table_capacity=table_capacity, notes={"picks": picks},
+        table_capacity=table_capacity, notes={"picks": picks}, donor_u=donor_u,
     )
 
 
@@ -451,6 +458,8 @@ def subsample(wl: Workload, n_requests: int, pool_slots: int | None = None) -> W
         pool_slots=slots, free_slots=free,
         table_capacity=wl.table_capacity if slots == wl.pool_slots else 2 * slots,
         rope_theta=wl.rope_theta, rope_style=wl.rope_style, notes={"donors_kept": keep},
+        donor_u=None if wl.donor_u is None else
+        np.concatenate([wl.donor_u[wl.donor_off[d]:wl.donor_off[d + 1]] for d in keep]),
     )
 
 

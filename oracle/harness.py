@@ -49,9 +49,11 @@ class OracleState:
     anchors: O.AnchorSet | None = None  # floating anchors: hashes of the stored runs' first W tokens
     anchor_window: int | None = None
     text: O.Text | None = None  # exact verification: the token string every slot was stored for
+    marks: np.ndarray | None = None  # uint8 per slot: recompute marks
 
 
-def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None, verify=False) -> OracleState:
+def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None, verify=False,
+            recompute=None) -> OracleState:
     """Insert the donor prompts batch by batch.  ``src_provider(first_tok, n_tok)``
     returns the layer-major KV buffer of a donor batch (default: host generator,
     uid = packed donor index).  With ``anchor_window`` = W the hash of every
@@ -73,6 +75,8 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         O.insert_anchors(st.anchors, st.donor_hash, O.run_offsets(wl.donor_mask, wl.donor_off), st.anchor_window)
     if verify:
         st.text = O.Text(wl.pool_slots)
+    if recompute is not None:  # uint8 per donor token: the annotator's recompute marks
+        st.marks = np.zeros(wl.pool_slots, np.uint8)
     st.donor_slot = np.full(len(wl.donor_tok), O.SLOT_NONE, np.uint32)
     flags = 0
     for first, last in wl.donor_batches:
@@ -87,6 +91,8 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         if st.text is not None:
             raw = slot_out
             slot_out = O.text_record(st.text, wl.donor_tok[t0:t1], O.run_offsets(wl.donor_mask[t0:t1], off), raw)
+        if st.marks is not None:
+            O.mark_recompute(slot_out, recompute[t0:t1], st.marks)
         st.donor_slot[t0:t1] = slot_out
         st.n_used += n_new
         flags |= fl
@@ -117,9 +123,11 @@ class Lookup:
     times: dict
     hash_float: np.ndarray | None = None
     run_off: np.ndarray | None = None
+    served: np.ndarray | None = None  # slots after minimum length / recompute marks
 
 
-def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_spans=None) -> Lookup:
+def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_spans=None, min_len=1,
+           zero_fill=False) -> Lookup:
     """Hash, probe, span building and gather for the request batch (timed per step)."""
     wl, sh = st.wl, st.wl.shape
     tok = wl.tok if tok is None else tok
@@ -147,8 +155,13 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
         slot = O.probe2(st.index, h, hf)
     times["probe"] = time.perf_counter() - t
     use_rope = wl.rope_theta is not None
+    served = slot
+    if min_len > 1 or st.marks is not None:
+        t = time.perf_counter()
+        served = O.filter_matches(slot, off, min_len, st.marks)
+        times["filter"] = time.perf_counter() - t
     t = time.perf_counter()
-    src, dst, ln, delta, n, fl = O.build_spans(slot, off, st.slot_pos if use_rope else None, max_spans)
+    src, dst, ln, delta, n, fl = O.build_spans(served, off, st.slot_pos if use_rope else None, max_spans)
     times["spans"] = time.perf_counter() - t
     buf = None
     if gather:
@@ -157,4 +170,8 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
         t = time.perf_counter()
         O.gather_kv(st.pool, pool_layout(sh), buf, buf_layout(sh, N), src, dst, ln, delta if use_rope else None, rope)
         times["gather"] = time.perf_counter() - t
-    return Lookup(h, slot, src, dst, ln, delta, n, fl, buf, times, hf, roff)
+        if zero_fill:
+            t = time.perf_counter()
+            O.fill_unmatched(served, buf, buf_layout(sh, N))
+            times["fill"] = time.perf_counter() - t
+    return Lookup(h, slot, src, dst, ln, delta, n, fl, buf, times, hf, roff, served)

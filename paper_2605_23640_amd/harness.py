@@ -54,7 +54,7 @@ class GpuState:
     flags: int
 
 
-def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, anchor_capacity=None, verify=False) -> cp.KVPool:
+def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, anchor_capacity=None, verify=False, **policies) -> cp.KVPool:
     sh = wl.shape
     rope = cp.binding.Rope(wl.rope_theta, wl.rope_style) if wl.rope_theta is not None else None
     fs = wl.free_slots if free_slots is None else free_slots
@@ -63,13 +63,14 @@ def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, anchor_capac
     pool = cp.KVPool(sh.n_layers, sh.n_kv_heads, sh.head_dim, wl.pool_slots, wl.table_capacity,
                      torch.from_numpy(fs.view(np.int32)), rope=rope, device=DEV,
                      pool_tensor=poison_tensor(wl.pool_slots * sh.tok_bytes), anchor_window=anchor_window,
-                     anchor_capacity=anchor_capacity, verify=verify)
+                     anchor_capacity=anchor_capacity, verify=verify, **policies)
     pool.slot_pos.fill_(np.iinfo(np.int32).min)
     return pool
 
 
-def prefill(wl, pool: cp.KVPool = None) -> GpuState:
-    """Insert the donor prompts batch by batch; donor token with packed index u has uid u."""
+def prefill(wl, pool: cp.KVPool = None, recompute=None) -> GpuState:
+    """Insert the donor prompts batch by batch; donor token with packed index u has uid u.
+    ``recompute``: uint8 per donor token, the annotator's recompute marks."""
     sh = wl.shape
     pool = pool or make_pool(wl)
     donor_hash = np.empty(len(wl.donor_tok), np.uint64)
@@ -87,7 +88,8 @@ def prefill(wl, pool: cp.KVPool = None) -> GpuState:
         sout = torch.empty(n, dtype=torch.int32, device=DEV)
         scratch = cp.binding.new_scratch(max(1, n), 0, DEV)
         roff = torch.empty(max(1, n), dtype=torch.int32, device=DEV) if (pool.anchors is not None or pool.verify) else None
-        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch, run_off_buf=roff))
+        rec = None if recompute is None else torch.from_numpy(np.ascontiguousarray(recompute[t0:t1], np.uint8)).to(DEV)
+        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch, run_off_buf=roff, recompute=rec))
         donor_hash[t0:t1] = host_u64(hbuf)
         donor_slot[t0:t1] = host_u32(sout)
         del src
@@ -106,6 +108,7 @@ class GpuLookup:
     n_spans: int
     flags: int
     dst: torch.Tensor  # uint8 device tensor, layer-major [L][2][N][row_bytes]
+    served: np.ndarray = None  # slots after the pool's policies (= slot without policies)
     hash_float: np.ndarray = None  # pools with floating anchors only
     run_off: np.ndarray = None
 
@@ -127,7 +130,8 @@ def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=T
     runs = anch or st.pool.verify
     return GpuLookup(host_u64(buf.hash), host_u32(buf.slot), host_u32(buf.span_src)[:n], host_u32(buf.span_dst)[:n],
                      host_u32(buf.span_len)[:n], buf.span_delta.cpu().numpy()[:n], host_u32(buf.span_off)[:n + 1], n,
-                     int(st.pool.flags.item()), dst, host_u64(buf.hash_float) if anch else None,
+                     int(st.pool.flags.item()), dst, host_u32(buf.served) if st.pool.filters else host_u32(buf.slot),
+                     host_u64(buf.hash_float) if anch else None,
                      host_u32(buf.run_off) if runs else None)
 
 

@@ -10,7 +10,7 @@ import torch
 import oracle as O
 from cp_workload import gen, kvgen
 from oracle import harness as OH
-from test_gpu_parity import G  # noqa: F401  (fixture)
+from test_gpu_parity import G, compare_all  # noqa: F401  (G is a fixture)
 
 pytestmark = pytest.mark.gpu
 
@@ -249,3 +249,25 @@ def test_table_compact_after_eviction(G):
     tiny = B.Table(16, G.DEV)
     B.cp_table_compact(pool.table, tiny, pool.flags)
     assert int(pool.flags.item()) & B.FLAG_TABLE_FULL
+
+
+@pytest.mark.parametrize("min_len,rho,zero_fill", [(16, 0.0, False), (1, 0.25, True), (24, 0.25, True)])
+def test_policies_on_the_8b_shaped_workload(G, min_len, rho, zero_fill):
+    wl = gen.make_docs("llama3-8b-small", 0xC0FFEE02, gen.KVShape(32, 8, 128), R=3, T=1371, prefix_len=300, n_docs=6,
+                       doc_len=(150, 300), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096)
+    rec = (wl.donor_u < rho).astype(np.uint8) if rho else None
+    ost, olk, gst, glk = compare_all(G, wl, min_len=min_len, recompute=rec, zero_fill=zero_fill)
+    matched, served = (olk.slot != NONE).sum(), (olk.served != NONE).sum()
+    assert 0 < served < matched
+    if zero_fill:
+        rows = G.dst_as_rows(glk.dst, wl.shape, wl.n_tokens)
+        assert (rows[:, :, olk.served == NONE] == 0).all()
+
+
+def test_policies_with_rope_anchors_and_verification(G):
+    wl = gen.make("float", scale=0.25)
+    wl.shape = gen.KVShape(2, 8, 128)
+    wl.rope_theta, wl.rope_style = 500000.0, 1
+    rec = (wl.donor_u < 0.25).astype(np.uint8)
+    ost, olk, gst, glk = compare_all(G, wl, anchor_window=8, verify=True, min_len=12, recompute=rec, zero_fill=True)
+    assert (olk.served != NONE).sum() > 100 and (glk.span_delta != 0).mean() > 0.5
