@@ -107,3 +107,51 @@ def test_full_size(G, name):
     del gst, glk
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def test_full_size_float_anchors_verified_policies(G):
+    """The rows added beyond the base path at the 8B size: floating anchors (W = 16), exact
+    verification, minimum stretch length, recompute marks, zero placeholders."""
+    import copy
+
+    W, min_len, rho = 16, 32, 0.25
+    wl = gen.make("float")
+    sh, N = wl.shape, wl.n_tokens
+    rec = (wl.donor_u < rho).astype(np.uint8)
+    w = copy.copy(wl)
+    w.shape = gen.KVShape(1, 1, 8)
+    ost = OH.prefill(w, src_provider=lambda t0, n: np.zeros((1, 2, n, 8), np.uint16), anchor_window=W, verify=True,
+                     recompute=rec)
+    olk = OH.lookup(ost, gather=False, min_len=min_len)
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=W, verify=True, min_len=min_len, recompute_marks=True,
+                                    zero_fill=True), recompute=rec)
+    print(f"\n[float] prefilled {sum(gst.n_inserted)} tokens", flush=True)
+    assert np.array_equal(gst.donor_hash, ost.donor_hash) and np.array_equal(gst.donor_slot, ost.donor_slot)
+    assert sum(gst.n_inserted) == ost.n_used and gst.flags == 0
+    assert np.array_equal(gst.pool.slot_recompute.cpu().numpy(), ost.marks)
+    assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0
+    glk = G.lookup(gst)
+    for f in ("hash", "hash_float", "run_off", "slot", "served", "span_src", "span_dst", "span_len"):
+        assert np.array_equal(getattr(glk, f), getattr(olk, f)), f
+    served = olk.served != O.SLOT_NONE
+    matched = olk.slot != O.SLOT_NONE
+    floating = matched & (O.probe(ost.index, olk.hash) == O.SLOT_NONE)
+    print(f"[float] matched {matched.sum()} ({floating.sum()} through floating keys), served {served.sum()}, "
+          f"{glk.n_spans} spans", flush=True)
+    assert floating.sum() > 0.2 * N and 0.5 * matched.sum() < served.sum() < 0.8 * matched.sum()
+    # served rows hold the owner's rows; every other row is zero
+    uid = np.full(N, kvgen.UID_NONE, np.uint64)
+    uid[served] = ost.slot_uid[olk.served[served]]
+    lay = gst.pool.request_layout(N)
+    view = glk.dst.view(torch.int16).view(sh.n_layers, 2, N, sh.row_bytes // 2)
+    rest = torch.from_numpy(np.flatnonzero(~served)).to(G.DEV)
+    for l in range(sh.n_layers):
+        assert not bool(view[l][:, rest, :].any()), l
+    # the verify kernel expects the fill pattern where no owner is named: put it back over the zero rows
+    pat = int(np.array([kvgen.POISON16], np.uint16).view(np.int16)[0])
+    for l in range(sh.n_layers):
+        view[l][:, rest, :] = pat
+    assert G.verify_rows(glk.dst, lay, uid, wl.seed) == 0
+    del gst, glk, view
+    gc.collect()
+    torch.cuda.empty_cache()
