@@ -95,6 +95,10 @@ def lib():
         L.cpo_lru_threshold.argtypes = [vp, u32, u32, u32, u32]
         L.cpo_evict.restype = u32
         L.cpo_evict.argtypes = [vp, vp, u32, u32, vp, vp, vp]
+        L.cpo_sat_build.argtypes = [vp, u32, u64, vp]
+        L.cpo_sat_rect.restype = C.c_int64
+        L.cpo_sat_rect.argtypes = [vp, u32, C.c_int64, C.c_int64, C.c_int64, C.c_int64]
+        L.cpo_annotate.argtypes = [vp, u32, vp, u32, u32, vp, vp, vp, vp, vp]
         L.cpo_probe2.argtypes = [vp, vp, vp, u32, vp]
         L.cpo_bf16_to_double.restype = C.c_double
         L.cpo_bf16_to_double.argtypes = [C.c_uint16]
@@ -244,6 +248,31 @@ def evict(index: Index, slot_stamp, threshold, text: "Text | None" = None, slot_
     n = lib().cpo_evict(index._h, _p(slot_stamp), slot_stamp.shape[0], int(threshold), _p(freed),
                         None if text is None else text._h, None if slot_recompute is None else _p(slot_recompute))
     return freed[:n].copy()
+
+
+def sat_build(attn):
+    """attn: float32[n][ld] (ld >= n) -> int64[n][n] summed-area table of the fixed-point weights."""
+    attn = np.ascontiguousarray(attn, np.float32)
+    n, ld = attn.shape[0], attn.shape[1]
+    T = np.empty((n, n), np.int64)
+    lib().cpo_sat_build(_p(attn), n, ld, _p(T))
+    return T
+
+
+def sat_rect(T, x1, x2, y1, y2):
+    return int(lib().cpo_sat_rect(_p(T), T.shape[0], int(x1), int(x2), int(y1), int(y2)))
+
+
+def annotate(T, mask, min_len=1, rho_percent=25):
+    """Returns (best_l, best_r, best_score, reusable, recompute), one entry per token."""
+    mask = _arr(mask, np.uint8)
+    n = T.shape[0]
+    assert T.dtype == np.int64 and T.flags.c_contiguous and mask.shape[0] == n
+    bl, br = np.empty(n, np.uint32), np.empty(n, np.uint32)
+    bs = np.empty(n, np.int64)
+    reus, rec = np.empty(n, np.uint8), np.empty(n, np.uint8)
+    lib().cpo_annotate(_p(T), n, _p(mask), int(min_len), int(rho_percent), _p(bl), _p(br), _p(bs), _p(reus), _p(rec))
+    return bl, br, bs, reus, rec
 
 
 def hash_segments(tok, mask, off, base=BASE):

@@ -5,6 +5,7 @@
 // the GPU library.
 #include "cp_oracle.h"
 
+#include <algorithm>
 #include <cfenv>
 #include <cmath>
 #include <cstring>
@@ -466,4 +467,98 @@ extern "C" uint32_t cpo_evict(cpo_index *ix, uint32_t *slot_stamp, uint32_t n_po
   for (auto it = ix->map.begin(); it != ix->map.end();)
     it = (it->second < n_pool_slots && gone[it->second]) ? ix->map.erase(it) : std::next(it);
   return n;
+}
+
+// ---- KV annotator: summed-area table over the attention matrix (Sec. 4.2.1, Steps 1-3) ----------
+
+// Fixed-point image of an attention weight: x * 2^32 rounded to the nearest integer (ties to even).
+// Entries above the diagonal (a token does not attend to later tokens) and values that are not
+// finite or not in [-2^20, 2^20] count as 0.
+static int64_t quantise(float x, uint32_t i, uint32_t j) {
+  if (j > i || !(std::fabs(x) <= 1048576.0f)) return 0;
+  return (int64_t)std::nearbyint((double)x * 4294967296.0);  // default rounding mode: to nearest even
+}
+
+// Step 1: T[i,j] = A[i,j] + T[i-1,j] + T[i,j-1] - T[i-1,j-1], indices below 0 count as zero.
+extern "C" void cpo_sat_build(const float *attn, uint32_t n, uint64_t ld, int64_t *T) {
+  for (uint32_t i = 0; i < n; ++i)
+    for (uint32_t j = 0; j < n; ++j) {
+      int64_t up = i ? T[(uint64_t)(i - 1) * n + j] : 0;
+      int64_t left = j ? T[(uint64_t)i * n + j - 1] : 0;
+      int64_t diag = (i && j) ? T[(uint64_t)(i - 1) * n + j - 1] : 0;
+      T[(uint64_t)i * n + j] = quantise(attn[(uint64_t)i * ld + j], i, j) + up + left - diag;
+    }
+}
+
+// Sum of the original matrix over rows x1..x2 and columns y1..y2 (inclusive; an empty range gives 0).
+static int64_t rect(const int64_t *T, uint32_t n, int64_t x1, int64_t x2, int64_t y1, int64_t y2) {
+  if (x2 < x1 || y2 < y1) return 0;
+  auto at = [&](int64_t x, int64_t y) -> int64_t { return (x < 0 || y < 0) ? 0 : T[(uint64_t)x * n + y]; };
+  return at(x2, y2) - at(x1 - 1, y2) - at(x2, y1 - 1) + at(x1 - 1, y1 - 1);
+}
+
+extern "C" int64_t cpo_sat_rect(const int64_t *T, uint32_t n, int64_t x1, int64_t x2, int64_t y1,
+                                int64_t y2) {
+  return rect(T, n, x1, x2, y1, y2);
+}
+
+// Steps 2 and 3 for every coarse segment (maximal run of tokens with mask 0).
+extern "C" void cpo_annotate(const int64_t *T, uint32_t n, const uint8_t *mask, uint32_t min_len,
+                             uint32_t rho_percent, uint32_t *best_l, uint32_t *best_r,
+                             int64_t *best_score, uint8_t *reusable, uint8_t *recompute) {
+  for (uint32_t i = 0; i < n; ++i) {
+    best_l[i] = best_r[i] = 0xFFFFFFFFu;
+    best_score[i] = 0;
+    reusable[i] = recompute[i] = 0;
+  }
+  if (min_len == 0) min_len = 1;
+  uint32_t a = 0;
+  while (a < n) {
+    if (mask[a]) {
+      ++a;
+      continue;
+    }
+    uint32_t b = a;
+    while (b + 1 < n && !mask[b + 1]) ++b;  // coarse segment [a, b]
+    // Step 2: the substring with the largest intra - inter attention; the first one on ties
+    bool found = false;
+    int64_t best = 0;
+    uint32_t bl = 0, br = 0;
+    for (uint32_t l = a; l <= b; ++l)
+      for (uint32_t r = l; r <= b; ++r) {
+        if (r - l + 1 < min_len) continue;
+        int64_t intra = rect(T, n, l, r, l, r);                // rows l..r, columns l..r
+        int64_t inter = rect(T, n, l, r, 0, (int64_t)l - 1);   // rows l..r, columns before l
+        int64_t score = intra - inter;
+        if (!found || score > best) {
+          found = true;
+          best = score;
+          bl = l;
+          br = r;
+        }
+      }
+    if (found) {
+      for (uint32_t i = a; i <= b; ++i) {
+        best_l[i] = bl;
+        best_r[i] = br;
+        best_score[i] = best;
+      }
+      // Step 3: rank the tokens of the chosen substring by inter - intra attention (their own row),
+      // largest first, earlier token first on ties; the top rho percent are recomputed
+      const uint32_t len = br - bl + 1;
+      std::vector<int64_t> d(len);
+      for (uint32_t i = bl; i <= br; ++i) {
+        int64_t inter_i = rect(T, n, i, i, 0, (int64_t)bl - 1);
+        int64_t intra_i = rect(T, n, i, i, bl, i);
+        d[i - bl] = inter_i - intra_i;
+        reusable[i] = 1;
+      }
+      std::vector<uint32_t> order(len);
+      for (uint32_t k = 0; k < len; ++k) order[k] = k;
+      std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return d[x] > d[y]; });
+      const uint32_t n_marked = (uint32_t)((uint64_t)len * rho_percent / 100);
+      for (uint32_t k = 0; k < n_marked; ++k) recompute[bl + order[k]] = 1;
+    }
+    a = b + 1;
+  }
 }

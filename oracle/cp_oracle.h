@@ -189,6 +189,28 @@ uint32_t cpo_lru_threshold(const uint32_t *slot_stamp, uint32_t n_pool_slots, ui
 uint32_t cpo_evict(cpo_index *, uint32_t *slot_stamp, uint32_t n_pool_slots, uint32_t threshold,
                    uint32_t *freed_slots, cpo_text *text /* nullable */,
                    uint8_t *slot_recompute /* nullable */);
+/* ---- KV annotator (Sec. 4.2.1 "C1", Steps 1-3) ----
+ * attn: n x n attention weights of one request, row i = what token i attends to, row stride ld
+ * (elements).  Arithmetic is exact: every weight is first turned into the integer
+ * round(x * 2^32) (entries above the diagonal and non-finite or huge values count as 0), and all
+ * sums are 64-bit integers, so no result depends on the order of the additions.
+ * Step 1, cpo_sat_build: the summed-area table by the recurrence
+ *     T[i,j] = A[i,j] + T[i-1,j] + T[i,j-1] - T[i-1,j-1]        (T dense, n x n).
+ * cpo_sat_rect: sum of A over rows x1..x2, columns y1..y2 from four table entries.
+ * Steps 2-3, cpo_annotate, for every coarse segment (maximal run of mask = 0 tokens):
+ *   Step 2: among its substrings [l, r] of at least min_len tokens, the one that maximises
+ *     IntraAttn - InterAttn = sum(rows l..r, cols l..r) - sum(rows l..r, cols < l);
+ *     ties: smallest l, then smallest r.  best_l / best_r / best_score are written for every token
+ *     of the segment (0xFFFFFFFF, 0 if the segment is shorter than min_len or the token sensitive);
+ *     reusable[i] = 1 inside the chosen substring.
+ *   Step 3: tokens of the chosen substring are ranked by (their row's attention to columns < l)
+ *     - (their row's attention to columns l..i), largest first, earlier token first on ties;
+ *     the first floor(len * rho_percent / 100) get recompute[i] = 1. */
+void cpo_sat_build(const float *attn, uint32_t n, uint64_t ld, int64_t *T);
+int64_t cpo_sat_rect(const int64_t *T, uint32_t n, int64_t x1, int64_t x2, int64_t y1, int64_t y2);
+void cpo_annotate(const int64_t *T, uint32_t n, const uint8_t *mask, uint32_t min_len,
+                  uint32_t rho_percent, uint32_t *best_l, uint32_t *best_r, int64_t *best_score,
+                  uint8_t *reusable, uint8_t *recompute);
 /* Building blocks exposed so that tests can pin them one by one. */
 double cpo_bf16_to_double(uint16_t bits);
 uint16_t cpo_double_to_bf16(double x); /* round-to-nearest-even, one rounding */
