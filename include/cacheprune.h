@@ -315,6 +315,35 @@ int32_t cp_evict(void *stream, cp_table table, uint32_t *slot_stamp, uint32_t n_
                  void *scratch, size_t scratch_bytes);
 int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags);
 
+/* ---- KV annotator: which tokens of a finished request are worth storing ------------------------
+ * Sec. 4.2.1 ("C1"), Steps 1-3.  attn (device, float[n][ld], ld >= n): attention weight from token
+ * i (row) to token j (column) of one request.  mask (device, u8[n]): 1 = sensitive; sensitive
+ * tokens cut the request into coarse segments.
+ *
+ * Exact arithmetic: a weight x counts as the integer round(x * 2^32), ties to even; entries above
+ * the diagonal, non-finite values and |x| > 2^20 count as 0; all sums are 64-bit integers.
+ *
+ * cp_sat_build (Step 1): T (device, int64[n][n], dense) = summed-area table,
+ *     T[i][j] = sum of the weights of rows <= i and columns <= j.
+ * cp_annotate (Steps 2, 3), for every coarse segment [a, b]:
+ *   - among its substrings [l, r] with at least min_len tokens (0 counts as 1) the one with the
+ *     largest  IntraAttn - InterAttn = sum(rows l..r, columns l..r) - sum(rows l..r, columns < l);
+ *     ties: smallest l, then smallest r.  For every token i of the segment best_l[i], best_r[i],
+ *     best_score[i] describe that substring (0xFFFFFFFF, 0xFFFFFFFF, 0 for sensitive tokens and for
+ *     segments shorter than min_len); reusable[i] = 1 iff best_l <= i <= best_r; store_mask (may be
+ *     NULL) = 1 - reusable: the mask to hash and insert the request with, so that only the chosen
+ *     substrings are stored;
+ *   - the tokens of the chosen substring are ranked by (their row's weight on columns < l) - (their
+ *     row's weight on columns l..i), largest first, earlier token first on ties, and the first
+ *     floor(len * rho_percent / 100) get recompute[i] = 1 (input of cp_mark_recompute).
+ * n <= 2^20.  Scratch: cp_sat_scratch_bytes(n), 256-byte aligned, for either call. */
+size_t cp_sat_scratch_bytes(uint32_t n);
+int32_t cp_sat_build(void *stream, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
+                     size_t scratch_bytes);
+int32_t cp_annotate(void *stream, const int64_t *T, uint32_t n, const uint8_t *mask, uint32_t min_len,
+                    uint32_t rho_percent, uint32_t *best_l, uint32_t *best_r, int64_t *best_score, uint8_t *reusable,
+                    uint8_t *recompute, uint8_t *store_mask, void *scratch, size_t scratch_bytes);
+
 #ifdef __cplusplus
 }
 #endif

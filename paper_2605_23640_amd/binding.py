@@ -33,7 +33,7 @@ EXPORTS = [
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
     "cp_insert_kv_chain", "cp_verify_chain",
     "cp_filter_matches", "cp_mark_recompute", "cp_fill_unmatched", "cp_touch", "cp_lru_threshold", "cp_evict",
-    "cp_table_compact",
+    "cp_table_compact", "cp_sat_scratch_bytes", "cp_sat_build", "cp_annotate",
 ]
 PARENT_POISON = 0xFFFFFFFE
 LRU_MAX_AGE = 4096
@@ -130,6 +130,12 @@ def lib():
         L.cp_evict.argtypes = [vp, TableStruct, vp, u32, vp, vp, vp, vp, vp, vp, sz]
         L.cp_table_compact.restype = i32
         L.cp_table_compact.argtypes = [vp, TableStruct, TableStruct, vp]
+        L.cp_sat_scratch_bytes.restype = sz
+        L.cp_sat_scratch_bytes.argtypes = [u32]
+        L.cp_sat_build.restype = i32
+        L.cp_sat_build.argtypes = [vp, vp, u32, u64, vp, vp, sz]
+        L.cp_annotate.restype = i32
+        L.cp_annotate.argtypes = [vp, vp, u32, vp, u32, u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_probe2.restype = i32
         L.cp_probe2.argtypes = [vp, TableStruct, vp, vp, u32, vp]
         L.cp_build_spans.restype = i32
@@ -347,6 +353,33 @@ def cp_evict(table: Table, slot_stamp, n_pool_slots, threshold, freed_slots, n_f
 def cp_table_compact(src: Table, dst: Table, status_flags, stream=None):
     _need_cuda(status_flags)
     _check("cp_table_compact", lib().cp_table_compact(_stream(stream), src.struct, dst.struct, _ptr(status_flags)))
+
+
+def new_sat_scratch(n, device="cuda"):
+    return torch.empty(int(lib().cp_sat_scratch_bytes(int(n))), dtype=torch.uint8, device=device)
+
+
+def cp_sat_build(attn, T, scratch, stream=None):
+    """attn float32[n][ld] -> T int64[n][n]."""
+    _need_cuda(attn, T, scratch)
+    n, ld = attn.shape[0], attn.stride(0)
+    assert attn.dtype == torch.float32 and attn.stride(1) == 1 and T.dtype == torch.int64
+    assert T.is_contiguous() and T.shape == (n, n)
+    _check("cp_sat_build", lib().cp_sat_build(_stream(stream), _ptr(attn), n, ld, _ptr(T), _ptr(scratch),
+                                              scratch.numel()))
+    return T
+
+
+def cp_annotate(T, mask, min_len, rho_percent, best_l, best_r, best_score, reusable, recompute, store_mask, scratch,
+                stream=None):
+    _need_cuda(T, mask, best_l, best_r, best_score, reusable, recompute, store_mask, scratch)
+    n = T.shape[0]
+    assert T.dtype == torch.int64 and T.is_contiguous() and T.shape == (n, n) and mask.numel() == n
+    for t in (best_l, best_r, best_score, reusable, recompute):
+        assert t.numel() == n
+    _check("cp_annotate", lib().cp_annotate(_stream(stream), _ptr(T), n, _ptr(mask), int(min_len), int(rho_percent),
+                                            _ptr(best_l), _ptr(best_r), _ptr(best_score), _ptr(reusable),
+                                            _ptr(recompute), _ptr(store_mask), _ptr(scratch), scratch.numel()))
 
 
 def cp_probe2(table: Table, hash_a, hash_b, slot_out, stream=None):

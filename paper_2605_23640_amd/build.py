@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libcacheprune.so")
-SOURCES = ["hash.hip", "table.hip", "verify.hip", "policy.hip", "spans.hip", "kv_move.hip"]
+SOURCES = ["hash.hip", "table.hip", "verify.hip", "policy.hip", "annotate.hip", "spans.hip", "kv_move.hip"]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
                # packed-FP32 instructions are kept out of all device code on the test machines
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
