@@ -88,6 +88,79 @@ def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False,
     }
 
 
+def annotator_bench(args):
+    """Side benchmark (not the headline metric): the KV annotator on one n x n attention matrix."""
+    import numpy as np
+    import torch
+
+    import oracle as O
+    from cp_workload import attn as AT
+    from paper_2605_23640_amd import binding as B
+    from paper_2605_23640_amd import harness as G
+
+    n, K = args.annotator, args.steps
+    t0 = time.time()
+    a = AT.make_attention(n)
+    mask = AT.make_mask(n, run_mean=8.0, cover=0.01)  # few, short sensitive runs: segments of ~800 tokens
+    log(f"[bench] attention matrix {n} x {n} generated ({time.time() - t0:.1f}s)")
+    d_a, d_mask = torch.from_numpy(a).to(G.DEV), torch.from_numpy(mask).to(G.DEV)
+    T = torch.empty((n, n), dtype=torch.int64, device=G.DEV)
+    scratch = B.new_sat_scratch(n, G.DEV)
+    i32 = lambda: torch.empty(n, dtype=torch.int32, device=G.DEV)  # noqa: E731
+    u8 = lambda: torch.empty(n, dtype=torch.uint8, device=G.DEV)  # noqa: E731
+    bl, br, bs, reus, rec, sm = i32(), i32(), torch.empty(n, dtype=torch.int64, device=G.DEV), u8(), u8(), u8()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3 * K)]
+
+    def step(k=None):
+        if k is not None:
+            ev[3 * k].record()
+        B.cp_sat_build(d_a, T, scratch)
+        if k is not None:
+            ev[3 * k + 1].record()
+        B.cp_annotate(T, d_mask, args.min_len if args.min_len > 1 else 128, 25, bl, br, bs, reus, rec, sm, scratch)
+        if k is not None:
+            ev[3 * k + 2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(K):
+        step(k)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t_start) / K * 1e3
+    sat_ms = float(np.mean([ev[3 * k].elapsed_time(ev[3 * k + 1]) for k in range(K)]))
+    ann_ms = float(np.mean([ev[3 * k + 1].elapsed_time(ev[3 * k + 2]) for k in range(K)]))
+    sat_bytes = 12.0 * n * n  # algorithmic: every weight read once (4 B), every table entry written once (8 B)
+    out = {
+        "metric": "KV annotator: attention matrix entries per second (summed-area table + segment search + marks)",
+        "value": n * n / (ms * 1e-3), "unit": "entries/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 weights as 2^-32 fixed point, int64 sums", "data": "synthetic",
+        "config": {"workload": f"one request of {n} tokens, {int(mask.sum())} sensitive, min_len "
+                               f"{args.min_len if args.min_len > 1 else 128}, rho 25 %",
+                   "reusable_tokens": int(reus.sum().item()), "recompute_tokens": int(rec.sum().item())},
+        "sat_build_ms": sat_ms, "annotate_ms": ann_ms,
+        "roofline": {"kernel": "cp_sat_build (5 launches)", "bound": "hbm", "achieved": sat_bytes / (sat_ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": sat_bytes / (sat_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": None},
+    }
+    if args.cpu_requests > 0:
+        t = time.perf_counter()
+        oT = O.sat_build(a)
+        t_sat = time.perf_counter() - t
+        t = time.perf_counter()
+        want = O.annotate(oT, mask, args.min_len if args.min_len > 1 else 128, 25)
+        t_ann = time.perf_counter() - t
+        same = bool(np.array_equal(T.cpu().numpy(), oT)) and all(
+            np.array_equal(g.cpu().numpy().view(w.dtype), w) for g, w in zip((bl, br, bs, reus, rec), want))
+        out["cpu_baseline"] = {"value": n * n / (t_sat + t_ann), "unit": "entries/s", "cores": 1, "kind": "oracle",
+                               "sample": "the same matrix, whole", "seconds": {"sat": round(t_sat, 3),
+                                                                                "annotate": round(t_ann, 3)},
+                               "gpu_result_identical": same}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -103,6 +176,8 @@ def main():
                     help="fraction of the stored tokens marked for recomputation (seeded, uniform): not served")
     ap.add_argument("--zero-fill", action="store_true", help="write zero rows for every token that is not served")
     ap.add_argument("--lru", action="store_true", help="keep last-use stamps for eviction")
+    ap.add_argument("--annotator", type=int, default=0, metavar="N",
+                    help="side benchmark: run the KV annotator on one N x N attention matrix instead of the KV path")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
     ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
     ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
@@ -125,6 +200,9 @@ def main():
     import paper_2605_23640_amd as cp
     from cp_workload import gen
     from paper_2605_23640_amd import harness as G
+
+    if args.annotator:
+        return annotator_bench(args)
 
     for key, val in enumerate([args.multicast, args.blocks_per_cu, args.nontemporal, args.unroll]):
         if val is not None:

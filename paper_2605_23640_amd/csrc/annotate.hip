@@ -34,27 +34,31 @@ __device__ __forceinline__ int64_t quantise(float x, uint32_t i, uint32_t j) {
   return (int64_t)__double2ll_rn((double)x * 4294967296.0);
 }
 
-__device__ __forceinline__ int64_t shfl_up_i64(int64_t v, int d) {
-  uint32_t lo = __shfl_up((uint32_t)v, d, kWave), hi = __shfl_up((uint32_t)((uint64_t)v >> 32), d, kWave);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
+// 64-bit wave scans through DPP moves (no LDS traffic).  dpp_add adds to v the value of the lane that
+// the DPP control selects, or 0 where that lane does not exist or the row is masked off.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int64_t dpp_add(int64_t v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, ROW_MASK, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((uint64_t)v >> 32), CTRL, ROW_MASK, 0xF, false);
+  return v + (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
 }
-__device__ __forceinline__ int64_t shfl_xor_i64(int64_t v, int m) {
-  uint32_t lo = __shfl_xor((uint32_t)v, m, kWave), hi = __shfl_xor((uint32_t)((uint64_t)v >> 32), m, kWave);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
+// Inclusive prefix sum over the 64 lanes: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the
+// last lane of row 0 / 2 is broadcast into row 1 / 3, then the last lane of row 1 into rows 2 and 3.
 __device__ __forceinline__ int64_t wave_inclusive_sum(int64_t v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    int64_t up = shfl_up_i64(v, d);
-    if (lane >= d) v += up;
-  }
+  v = dpp_add<0x111, 0xF>(v);  // row_shr:1
+  v = dpp_add<0x112, 0xF>(v);  // row_shr:2
+  v = dpp_add<0x114, 0xF>(v);  // row_shr:4
+  v = dpp_add<0x118, 0xF>(v);  // row_shr:8
+  v = dpp_add<0x142, 0xA>(v);  // row_bcast:15 into rows 1 and 3
+  v = dpp_add<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
   return v;
 }
+// Sum over the 64 lanes, valid in every lane.
 __device__ __forceinline__ int64_t wave_sum(int64_t v) {
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) v += shfl_xor_i64(v, m);
-  return v;
+  v = wave_inclusive_sum(v);
+  const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, 63);
+  const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), 63);
+  return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
 // colsum[I][c]: sum of column c over the rows of tile row I;  rowsum[J][r]: sum of row r over the
@@ -82,12 +86,25 @@ __global__ __launch_bounds__(64) void sat_tile_sums_kernel(const float *__restri
   colsum[(uint64_t)I * n_pad + c] = col;
 }
 
-// In place: a[k][x] <- sum of a[k'][x] over k' < k   (x < n_pad, k < n_k).
-__global__ __launch_bounds__(256) void sat_exclusive_over_tiles_kernel(int64_t *a, uint32_t n_k, uint32_t n_pad) {
+// In place, for both arrays (blockIdx.y picks one): a[k][x] <- sum of a[k'][x] over k' < k   (x < n_pad, k < n_k).
+__global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a0, int64_t *a1, uint32_t n_k,
+                                                                      uint32_t n_pad) {
+  int64_t *a = blockIdx.y ? a1 : a0;
   const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
   if (x >= n_pad) return;
   int64_t run = 0;
-  for (uint32_t k = 0; k < n_k; ++k) {
+  uint32_t k = 0;
+  for (; k + 8 <= n_k; k += 8) {  // eight independent loads in flight
+    int64_t v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = a[(uint64_t)(k + u) * n_pad + x];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      a[(uint64_t)(k + u) * n_pad + x] = run;
+      run += v[u];
+    }
+  }
+  for (; k < n_k; ++k) {
     const int64_t v = a[(uint64_t)k * n_pad + x];
     a[(uint64_t)k * n_pad + x] = run;
     run += v;
@@ -223,7 +240,7 @@ __global__ __launch_bounds__(256) void annotate_finish_kernel(const int64_t *__r
                                                               int64_t *__restrict__ out_score,
                                                               uint8_t *__restrict__ reusable,
                                                               uint8_t *__restrict__ store_mask,
-                                                              int64_t *__restrict__ d) {
+                                                              int64_t *__restrict__ d, uint32_t *__restrict__ rank) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   uint32_t bl = kNone, br = kNone;
@@ -250,30 +267,61 @@ __global__ __launch_bounds__(256) void annotate_finish_kernel(const int64_t *__r
   reusable[i] = inside ? 1 : 0;
   if (store_mask) store_mask[i] = inside ? 0 : 1;
   d[i] = di;
+  rank[i] = 0;
 }
 
 // Rank of every token of a chosen substring among that substring's tokens by d, largest first,
-// earlier token first on ties; the first floor(len * rho / 100) are marked.
+// earlier token first on ties.  Block (x, y): tokens i of block x against the tokens j of chunk y;
+// the partial counts are added up in rank[] (zeroed by the finish kernel).
+constexpr uint32_t kRankChunk = 256;
 __global__ __launch_bounds__(256) void annotate_rank_kernel(uint32_t n, const uint32_t *__restrict__ out_l,
                                                             const uint32_t *__restrict__ out_r,
                                                             const uint8_t *__restrict__ reusable,
-                                                            const int64_t *__restrict__ d, uint32_t rho_percent,
+                                                            const int64_t *__restrict__ d, uint32_t *rank) {
+  __shared__ int64_t dj[kRankChunk];
+  __shared__ uint32_t lo_all, hi_all;
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t j0 = blockIdx.y * kRankChunk;
+  const bool mine = i < n && reusable[i];
+  const uint32_t bl = mine ? out_l[i] : kNone, br = mine ? out_r[i] : 0u;
+  if (threadIdx.x == 0) {
+    lo_all = kNone;
+    hi_all = 0;
+  }
+  __syncthreads();
+  if (mine) {
+    atomicMin(&lo_all, bl);
+    atomicMax(&hi_all, br);
+  }
+  __syncthreads();
+  if (lo_all == kNone || j0 > hi_all || j0 + kRankChunk <= lo_all) return;  // no token here looks at this chunk
+  const uint32_t j = j0 + threadIdx.x;
+  dj[threadIdx.x] = j < n ? d[j] : 0;
+  __syncthreads();
+  if (!mine) return;
+  const uint32_t from = bl > j0 ? bl : j0, to = br < j0 + kRankChunk - 1 ? br : j0 + kRankChunk - 1;  // inclusive
+  if (from > to) return;
+  const int64_t di = d[i];
+  uint32_t count = 0;
+  for (uint32_t jj = from; jj <= to; ++jj) {
+    const int64_t v = dj[jj - j0];
+    count += (v > di || (v == di && jj < i)) ? 1u : 0u;
+  }
+  if (count) atomicAdd(&rank[i], count);
+}
+
+// The first floor(len * rho / 100) tokens of that order are marked.
+__global__ __launch_bounds__(256) void annotate_mark_kernel(uint32_t n, const uint32_t *__restrict__ out_l,
+                                                            const uint32_t *__restrict__ out_r,
+                                                            const uint8_t *__restrict__ reusable,
+                                                            const uint32_t *__restrict__ rank, uint32_t rho_percent,
                                                             uint8_t *__restrict__ recompute) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   uint8_t mark = 0;
   if (reusable[i]) {
-    const uint32_t bl = out_l[i], br = out_r[i];
-    const uint32_t n_marked = (uint32_t)((uint64_t)(br - bl + 1) * rho_percent / 100);
-    if (n_marked) {
-      const int64_t di = d[i];
-      uint32_t rank = 0;
-      for (uint32_t j = bl; j <= br && rank < n_marked; ++j) {
-        const int64_t dj = d[j];
-        rank += (dj > di || (dj == di && j < i)) ? 1u : 0u;
-      }
-      mark = rank < n_marked ? 1 : 0;
-    }
+    const uint32_t n_marked = (uint32_t)((uint64_t)(out_r[i] - out_l[i] + 1) * rho_percent / 100);
+    mark = rank[i] < n_marked ? 1 : 0;
   }
   recompute[i] = mark;
 }
@@ -308,8 +356,7 @@ extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, ui
   if ((uint64_t)n_t * n_pad >= 0x80000000ull) return CP_ERR_UNSUPPORTED;
   const dim3 tiles(n_t, n_t);
   sat_tile_sums_kernel<<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad, colsum, rowsum);
-  sat_exclusive_over_tiles_kernel<<<div_up(n_pad, 256), 256, 0, stream>>>(colsum, n_t, n_pad);
-  sat_exclusive_over_tiles_kernel<<<div_up(n_pad, 256), 256, 0, stream>>>(rowsum, n_t, n_pad);
+  sat_exclusive_over_tiles_kernel<<<dim3(div_up(n_pad, 64), 2), 64, 0, stream>>>(colsum, rowsum, n_t, n_pad);
   RunningRowsOp op{rowsum, n_pad, n_t * n_pad};
   if (int32_t rc = run_scan<RunningRowsOp>(stream, op, n_t * n_pad, agg)) return rc;
   sat_apply_kernel<<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad, colsum, rowsum, T);
@@ -336,7 +383,8 @@ extern "C" int32_t cp_annotate(void *stream_, const int64_t *T, uint32_t n, cons
   uint64_t *best_u = sc.take<uint64_t>(n);
   uint64_t *best_lr = sc.take<uint64_t>(n);
   int64_t *d = sc.take<int64_t>(n);
-  if (!agg || !seg_a || !diag || !best_u || !best_lr || !d) return CP_ERR_SCRATCH;
+  uint32_t *rank = sc.take<uint32_t>(n);
+  if (!agg || !seg_a || !diag || !best_u || !best_lr || !d || !rank) return CP_ERR_SCRATCH;
   SegStartOp so{mask, seg_a, n};
   if (int32_t rc = run_scan<SegStartOp>(stream, so, n, agg)) return rc;
   const uint32_t blocks = div_up(n, 256), n_t = div_up(n, kTile);
@@ -344,7 +392,9 @@ extern "C" int32_t cp_annotate(void *stream_, const int64_t *T, uint32_t n, cons
   for (int pass = 0; pass < 2; ++pass)
     annotate_search_kernel<<<dim3(n_t, n_t), 256, 0, stream>>>(T, n, diag, seg_a, min_len, pass, best_u, best_lr);
   annotate_finish_kernel<<<blocks, 256, 0, stream>>>(T, n, diag, seg_a, best_u, best_lr, best_l, best_r, best_score,
-                                                     reusable, store_mask, d);
-  annotate_rank_kernel<<<blocks, 256, 0, stream>>>(n, best_l, best_r, reusable, d, rho_percent, recompute);
+                                                     reusable, store_mask, d, rank);
+  if (rho_percent)
+    annotate_rank_kernel<<<dim3(blocks, div_up(n, kRankChunk)), 256, 0, stream>>>(n, best_l, best_r, reusable, d, rank);
+  annotate_mark_kernel<<<blocks, 256, 0, stream>>>(n, best_l, best_r, reusable, rank, rho_percent, recompute);
   return check_launch();
 }
