@@ -321,10 +321,12 @@ int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *sta
  * tokens cut the request into coarse segments.
  *
  * Exact arithmetic: a weight x counts as the integer round(x * 2^32), ties to even; entries above
- * the diagonal, non-finite values and |x| > 2^20 count as 0; all sums are 64-bit integers.
+ * the diagonal, non-finite values and |x| > 2^18 count as 0; all sums are 64-bit integers.
  *
  * cp_sat_build (Step 1): T (device, int64[n][n], dense) = summed-area table,
- *     T[i][j] = sum of the weights of rows <= i and columns <= j.
+ *     T[i][j] = sum of the weights of rows <= i and columns <= j,
+ *   valid for every j <= i.  No token attends to a later one, so T[i][j] = T[i][i] for j > i;
+ *   those entries are not needed, cp_annotate never reads them, and most of them are not written.
  * cp_annotate (Steps 2, 3), for every coarse segment [a, b]:
  *   - among its substrings [l, r] with at least min_len tokens (0 counts as 1) the one with the
  *     largest  IntraAttn - InterAttn = sum(rows l..r, columns l..r) - sum(rows l..r, columns < l);

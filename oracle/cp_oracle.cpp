@@ -473,9 +473,9 @@ extern "C" uint32_t cpo_evict(cpo_index *ix, uint32_t *slot_stamp, uint32_t n_po
 
 // Fixed-point image of an attention weight: x * 2^32 rounded to the nearest integer (ties to even).
 // Entries above the diagonal (a token does not attend to later tokens) and values that are not
-// finite or not in [-2^20, 2^20] count as 0.
+// finite or not in [-2^18, 2^18] count as 0.
 static int64_t quantise(float x, uint32_t i, uint32_t j) {
-  if (j > i || !(std::fabs(x) <= 1048576.0f)) return 0;
+  if (j > i || !(std::fabs(x) <= 262144.0f)) return 0;
   return (int64_t)std::nearbyint((double)x * 4294967296.0);  // default rounding mode: to nearest even
 }
 

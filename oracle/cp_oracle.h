@@ -192,7 +192,7 @@ uint32_t cpo_evict(cpo_index *, uint32_t *slot_stamp, uint32_t n_pool_slots, uin
 /* ---- KV annotator (Sec. 4.2.1 "C1", Steps 1-3) ----
  * attn: n x n attention weights of one request, row i = what token i attends to, row stride ld
  * (elements).  Arithmetic is exact: every weight is first turned into the integer
- * round(x * 2^32) (entries above the diagonal and non-finite or huge values count as 0), and all
+ * round(x * 2^32) (entries above the diagonal and non-finite values and |x| > 2^18 count as 0), and all
  * sums are 64-bit integers, so no result depends on the order of the additions.
  * Step 1, cpo_sat_build: the summed-area table by the recurrence
  *     T[i,j] = A[i,j] + T[i-1,j] + T[i,j-1] - T[i-1,j-1]        (T dense, n x n).

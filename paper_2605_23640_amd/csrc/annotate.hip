@@ -7,31 +7,49 @@
 // associative, so the table does not depend on how the work is split, the maximum over the
 // substrings is decided without rounding, and results are reproducible bit for bit.
 //
-// Step 1 (cp_sat_build), three sweeps over 64 x 64 tiles, one wavefront per tile, lane = column:
-//   sums   per tile: the sum of every column over the tile's rows and of every row over its columns
+// No token attends to a later one, so T[i][j] = T[i][i] for j > i: tiles strictly above the diagonal
+// are neither computed nor written, and nothing here reads them.
+//
+// Step 1 (cp_sat_build), three sweeps over tiles of 64 rows x 128 columns that reach the diagonal or
+// lie below it, one wavefront per tile, every lane owning two adjacent columns:
+//   sums   per tile: the sum of every column over the tile's rows (lane-local) and of every row over
+//          its columns (two values per lane, then one wave scan)
 //   carry  exclusive scans of those sums over the tile rows / tile columns, then a running sum of the
 //          "left of this tile column" row sums down all rows
-//   apply  per tile: prefix sums inside the tile (wave scan along the row, running sum down the
-//          rows) + what lies above the tile in its columns + what lies left of it in rows <= i
-// The matrix is read twice (4 bytes per entry each) and the table written once (8 bytes per entry).
+//   apply  per tile and row: prefix over the lane's two columns, one wave scan across lanes, running
+//          sum down the rows, + what lies above the tile in its columns + what lies left of it in
+//          rows <= i
+// Wave scans are DPP moves (no LDS).  When the row strides allow it a lane reads its two weights as
+// one 8-byte vector and stores its two table entries as one 16-byte vector, so that a wavefront's
+// store is one contiguous KiB.  Loads of the next eight rows are issued before the current eight
+// are summed.  The lower half of the matrix is read twice
+// (4 bytes per entry each) and the lower half of the table written once (8 bytes per entry).
 //
-// Step 2 (cp_annotate): score(l, r) = T[r,r] - T[l-1,r] - 2 T[r,l-1] + 2 T[l-1,l-1]; all (l, r) of a
-// 64 x 64 block of the (l, r) triangle take T[l-1, r] straight from global memory (lanes along r) and
-// T[r, l-1] through a transposing LDS tile.  First sweep: maximum score per segment (64-bit atomic
-// max); second sweep: smallest (l, r) among the candidates that reach it (64-bit atomic min).
+// Step 2 (cp_annotate): score(l, r) = Intra - Inter = T[r,r] - T[l-1,r] - 2 T[r,l-1] + 2 T[l-1,l-1]
+// = T[r,r] + T[l-1,l-1] - 2 T[r,l-1]  (T[l-1,r] = T[l-1,l-1], see above).  A workgroup takes a 64 x 64
+// block of the (l, r) triangle: lanes along r, T[r, l-1] through a transposing LDS tile.  First sweep:
+// maximum score per segment (64-bit atomic max); second sweep: smallest (l, r) among the candidates
+// that reach it (64-bit atomic min).
 #include "cp_device.h"
 #include "cp_internal.h"
 
 namespace cp {
 namespace {
 
-constexpr uint32_t kTile = 64;
+constexpr uint32_t kTile = 64;    // rows of a table tile; also the block edge of the (l, r) search
+constexpr uint32_t kTileC = 128;  // columns of a table tile: two per lane
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 constexpr uint64_t kBias = 0x8000000000000000ull;  // signed -> unsigned, order preserving
 
+// round(x * 2^32), ties to even, as a 64-bit integer; 0 above the diagonal and for values that are not
+// finite or beyond 2^18 in magnitude.  x * 2^32 is exact in double; adding 2^52 + 2^51 leaves a double
+// whose unit in the last place is 1, i.e. the hardware addition does the rounding, and the integer is
+// the difference of the bit patterns.
 __device__ __forceinline__ int64_t quantise(float x, uint32_t i, uint32_t j) {
-  if (j > i || !(fabsf(x) <= 1048576.0f)) return 0;
-  return (int64_t)__double2ll_rn((double)x * 4294967296.0);
+  if (j > i || !(fabsf(x) <= 262144.0f)) return 0;
+  const double magic = 6755399441055744.0;
+  const double d = (double)x * 4294967296.0 + magic;
+  return (int64_t)(__double_as_longlong(d) - __double_as_longlong(magic));
 }
 
 // 64-bit wave scans through DPP moves (no LDS traffic).  dpp_add adds to v the value of the lane that
@@ -53,43 +71,104 @@ __device__ __forceinline__ int64_t wave_inclusive_sum(int64_t v) {
   v = dpp_add<0x143, 0xC>(v);  // row_bcast:31 into rows 2 and 3
   return v;
 }
-// Sum over the 64 lanes, valid in every lane.
-__device__ __forceinline__ int64_t wave_sum(int64_t v) {
-  v = wave_inclusive_sum(v);
-  const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, 63);
-  const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), 63);
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
+  const uint32_t lo = __shfl_xor((uint32_t)v, m, kWave), hi = __shfl_xor((uint32_t)(v >> 32), m, kWave);
+  return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ int64_t readlane_i64(int64_t v, uint32_t lane) {  // lane: same for the whole wave
+  const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+  const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), lane);
   return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-// colsum[I][c]: sum of column c over the rows of tile row I;  rowsum[J][r]: sum of row r over the
-// columns of tile column J.  Both arrays are padded to whole tiles (n_pad columns / rows).
-__global__ __launch_bounds__(64) void sat_tile_sums_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
-                                                           uint32_t n_pad, int64_t *__restrict__ colsum,
-                                                           int64_t *__restrict__ rowsum) {
-  const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
-  const uint32_t c = J * kTile + lane, r0 = I * kTile;
-  int64_t col = 0;
-  if (J <= I) {  // tiles above the diagonal hold no weight
-#pragma unroll 8
-    for (uint32_t k = 0; k < kTile; ++k) {
-      const uint32_t r = r0 + k;
-      float x = 0.0f;
-      if (r < n && c < n && c <= r) x = attn[(uint64_t)r * ld + c];
-      const int64_t q = quantise(x, r, c);
-      col += q;
-      const int64_t row = wave_sum(q);
-      if (lane == 0) rowsum[(uint64_t)J * n_pad + r] = row;
-    }
-  } else {
-    rowsum[(uint64_t)J * n_pad + r0 + lane] = 0;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef long long i64x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kRowGroup = 8;  // rows whose loads are in flight while the previous rows are being summed
+
+// Weights of one row, columns c and c+1 (c even), from p = &attn[row][c].
+// INTERIOR: the whole tile lies on or below the diagonal and inside the matrix, nothing to check;
+// otherwise columns beyond the row index r (and rows beyond n) read as 0.
+template <bool VEC, bool INTERIOR>
+__device__ __forceinline__ f32x2 load_x2(const float *__restrict__ p, uint32_t n, uint32_t r, uint32_t c) {
+  if (INTERIOR) {
+    if (VEC) return *reinterpret_cast<const f32x2 *>(p);
+    return f32x2{p[0], p[1]};
   }
-  colsum[(uint64_t)I * n_pad + c] = col;
+  f32x2 v = {0.0f, 0.0f};
+  if (r < n && c <= r) {
+    if (VEC && c + 1 <= r) {  // c + 1 <= r < n <= ld: both inside the row
+      v = *reinterpret_cast<const f32x2 *>(p);
+    } else {
+      v.x = p[0];
+      if (c + 1 <= r) v.y = p[1];
+    }
+  }
+  return v;
+}
+template <bool VEC, bool INTERIOR>
+__device__ __forceinline__ void load_group(const float *__restrict__ p, uint64_t ld, uint32_t n, uint32_t r_first,
+                                           uint32_t c, f32x2 x[kRowGroup]) {
+#pragma unroll
+  for (int u = 0; u < kRowGroup; ++u) x[u] = load_x2<VEC, INTERIOR>(p + (uint64_t)u * ld, n, r_first + u, c);
+}
+// In an interior tile every column is at or left of the diagonal: only the range check remains.
+template <bool INTERIOR>
+__device__ __forceinline__ void quantise2(f32x2 v, uint32_t r, uint32_t c, int64_t q[2]) {
+  const uint32_t i = INTERIOR ? 0xFFFFFFFFu : r;
+  q[0] = quantise(v.x, i, c), q[1] = quantise(v.y, i, c + 1);
 }
 
-// In place, for both arrays (blockIdx.y picks one): a[k][x] <- sum of a[k'][x] over k' < k   (x < n_pad, k < n_k).
-__global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a0, int64_t *a1, uint32_t n_k,
-                                                                      uint32_t n_pad) {
+template <bool VEC, bool INTERIOR>
+__device__ __forceinline__ void tile_sums(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
+                                          uint32_t c, int64_t *__restrict__ rowsum_tile, int64_t col[2]) {
+  const float *p = attn + (uint64_t)r0 * ld + c;
+  f32x2 cur[kRowGroup], nxt[kRowGroup];
+  load_group<VEC, INTERIOR>(p, ld, n, r0, c, cur);
+#pragma unroll 1
+  for (uint32_t g = 0; g < kTile / kRowGroup; ++g) {
+    p += (uint64_t)kRowGroup * ld;
+    if (g + 1 < kTile / kRowGroup) load_group<VEC, INTERIOR>(p, ld, n, r0 + (g + 1) * kRowGroup, c, nxt);
+#pragma unroll
+    for (int u = 0; u < kRowGroup; ++u) {
+      const uint32_t k = g * kRowGroup + u;
+      int64_t q[2];
+      quantise2<INTERIOR>(cur[u], r0 + k, c, q);
+      col[0] += q[0], col[1] += q[1];
+      const int64_t row = wave_inclusive_sum(q[0] + q[1]);
+      if (threadIdx.x == kWave - 1) rowsum_tile[k] = row;
+    }
+#pragma unroll
+    for (int u = 0; u < kRowGroup; ++u) cur[u] = nxt[u];
+  }
+}
+
+// colsum[I][c]: sum of column c over the 64 rows of tile row I (width n_pad_c);  rowsum[J][r]: sum of
+// row r over the 128 columns of tile column J (width n_pad_r).
+template <bool VEC>
+__global__ __launch_bounds__(64) void sat_tile_sums_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
+                                                           uint32_t n_pad_c, uint32_t n_pad_r,
+                                                           int64_t *__restrict__ colsum, int64_t *__restrict__ rowsum) {
+  const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
+  const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
+  int64_t col[2] = {0, 0};
+  int64_t *rowsum_tile = rowsum + (uint64_t)J * n_pad_r + r0;
+  if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n) {
+    tile_sums<VEC, true>(attn, n, ld, r0, c, rowsum_tile, col);
+  } else if (c0 <= r0 + kTile - 1) {
+    tile_sums<VEC, false>(attn, n, ld, r0, c, rowsum_tile, col);
+  } else {  // the whole tile lies above the diagonal and holds no weight
+    rowsum_tile[lane] = 0;
+  }
+  colsum[(uint64_t)I * n_pad_c + c] = col[0];
+  colsum[(uint64_t)I * n_pad_c + c + 1] = col[1];
+}
+
+// In place, for both arrays (blockIdx.y picks one): a[k][x] <- sum of a[k'][x] over k' < k   (x < width, k < n_k).
+__global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a0, uint32_t n_k0, uint32_t width0,
+                                                                      int64_t *a1, uint32_t n_k1, uint32_t width1) {
   int64_t *a = blockIdx.y ? a1 : a0;
+  const uint32_t n_k = blockIdx.y ? n_k1 : n_k0, n_pad = blockIdx.y ? width1 : width0;
   const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
   if (x >= n_pad) return;
   int64_t run = 0;
@@ -127,26 +206,68 @@ struct RunningRowsOp {
   __device__ __forceinline__ void finish(T) const {}
 };
 
+template <bool VEC_LD, bool VEC_ST, bool INTERIOR>
+__device__ __forceinline__ void tile_apply(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
+                                           uint32_t c, const int64_t above_pref[2], int64_t left_row,
+                                           int64_t *__restrict__ T) {
+  int64_t acc[2] = {0, 0};  // this tile's rows so far, tile's columns up to each of this lane's
+  const float *p = attn + (uint64_t)r0 * ld + c;
+  int64_t *t = T + (uint64_t)r0 * n + c;
+  f32x2 cur[kRowGroup], nxt[kRowGroup];
+  load_group<VEC_LD, INTERIOR>(p, ld, n, r0, c, cur);
+#pragma unroll 1
+  for (uint32_t g = 0; g < kTile / kRowGroup; ++g) {
+    if (!INTERIOR && r0 + g * kRowGroup >= n) break;  // same for the whole wave
+    p += (uint64_t)kRowGroup * ld;
+    if (g + 1 < kTile / kRowGroup) load_group<VEC_LD, INTERIOR>(p, ld, n, r0 + (g + 1) * kRowGroup, c, nxt);
+#pragma unroll
+    for (int u = 0; u < kRowGroup; ++u) {
+      const uint32_t k = g * kRowGroup + u, r = r0 + k;
+      int64_t q[2];
+      quantise2<INTERIOR>(cur[u], r, c, q);
+      q[1] += q[0];
+      const int64_t before = wave_inclusive_sum(q[1]) - q[1];
+      const int64_t lv = readlane_i64(left_row, k);
+      acc[0] += before + q[0], acc[1] += before + q[1];
+      const int64_t out0 = acc[0] + above_pref[0] + lv, out1 = acc[1] + above_pref[1] + lv;
+      if (INTERIOR || r < n) {  // same for the whole wave
+        int64_t *o = t + (uint64_t)u * n;
+        if (VEC_ST && (INTERIOR || c + 1 < n)) {  // the wave writes 1 KiB in one piece
+          __builtin_nontemporal_store(i64x2{out0, out1}, reinterpret_cast<i64x2 *>(o));
+        } else {
+          if (c < n) o[0] = out0;
+          if (c + 1 < n) o[1] = out1;
+        }
+      }
+    }
+    t += (uint64_t)kRowGroup * n;
+#pragma unroll
+    for (int u = 0; u < kRowGroup; ++u) cur[u] = nxt[u];
+  }
+}
+
+template <bool VEC_LD, bool VEC_ST>
 __global__ __launch_bounds__(64) void sat_apply_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
-                                                       uint32_t n_pad, const int64_t *__restrict__ above,
+                                                       uint32_t n_pad_c, uint32_t n_pad_r,
+                                                       const int64_t *__restrict__ above,
                                                        const int64_t *__restrict__ left, int64_t *__restrict__ T) {
   const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
-  const uint32_t c = J * kTile + lane, r0 = I * kTile;
-  // everything above the tile, in the tile's columns up to this lane's
-  const int64_t above_pref = wave_inclusive_sum(above[(uint64_t)I * n_pad + c]);
-  int64_t acc = 0;  // this tile's rows so far, tile's columns up to this lane's
-  const bool weight = J <= I;
-#pragma unroll 8
-  for (uint32_t k = 0; k < kTile; ++k) {
-    const uint32_t r = r0 + k;
-    if (r >= n) break;  // same for the whole wave
-    if (weight) {
-      float x = 0.0f;
-      if (c < n && c <= r) x = attn[(uint64_t)r * ld + c];
-      acc += wave_inclusive_sum(quantise(x, r, c));
-    }
-    if (c < n) T[(uint64_t)r * n + c] = acc + above_pref + left[(uint64_t)J * n_pad + r];
+  const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
+  if (c0 > r0 + kTile - 1) return;  // above the diagonal: not written
+  // everything above the tile, in the tile's columns up to each of this lane's
+  int64_t above_pref[2];
+  {
+    above_pref[0] = above[(uint64_t)I * n_pad_c + c];
+    above_pref[1] = above_pref[0] + above[(uint64_t)I * n_pad_c + c + 1];
+    const int64_t before = wave_inclusive_sum(above_pref[1]) - above_pref[1];  // the lanes to the left
+    above_pref[0] += before, above_pref[1] += before;
   }
+  // everything left of the tile in rows <= r0 + lane
+  const int64_t left_row = left[(uint64_t)J * n_pad_r + r0 + lane];
+  if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n)
+    tile_apply<VEC_LD, VEC_ST, true>(attn, n, ld, r0, c, above_pref, left_row, T);
+  else
+    tile_apply<VEC_LD, VEC_ST, false>(attn, n, ld, r0, c, above_pref, left_row, T);
 }
 
 // ---- segments ----
@@ -166,54 +287,60 @@ struct SegStartOp {
   __device__ __forceinline__ void finish(T) const {}
 };
 __global__ __launch_bounds__(256) void annotate_init_kernel(const int64_t *__restrict__ T, uint32_t n,
+                                                            const uint32_t *__restrict__ seg_a,
                                                             int64_t *__restrict__ diag, uint64_t *best_u,
-                                                            uint64_t *best_lr) {
+                                                            uint64_t *best_lr, uint32_t *__restrict__ tile_min_a) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   diag[i] = T[(uint64_t)i * n + i];
   best_u[i] = 0;        // below every biased score
   best_lr[i] = ~0ull;   // above every packed (l, r)
+  if (i % kTile == 0) {  // earliest segment start among the 64 tokens from i on (kNone if all are sensitive)
+    uint32_t m = kNone;
+    for (uint32_t k = 0; k < kTile && i + k < n; ++k) m = seg_a[i + k] < m ? seg_a[i + k] : m;
+    tile_min_a[i / kTile] = m;
+  }
 }
 
-// One workgroup per 64 x 64 block of candidates: l in [lt*64, +64), r in [rt*64, +64), lt <= rt.
+// Candidates (l, r) are visited in 64 x 64 blocks: l in [lt*64, +64), r in [rt*64, +64), lt <= rt.
+// Workgroup (rt, y) takes the blocks lt = first, first + kSearchSplit, ... <= rt of its r tile, where
+// first is the tile of the earliest segment start among the tile's r (no candidate lies left of it).
 // pass 0: best_u[seg] = max biased score; pass 1: best_lr[seg] = min packed (l, r) among the maxima.
+constexpr uint32_t kSearchSplit = 8;
 __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__restrict__ T, uint32_t n,
                                                               const int64_t *__restrict__ diag,
-                                                              const uint32_t *__restrict__ seg_a, uint32_t min_len,
+                                                              const uint32_t *__restrict__ seg_a,
+                                                              const uint32_t *__restrict__ tile_min_a, uint32_t min_len,
                                                               int pass, uint64_t *best_u, uint64_t *best_lr) {
-  const uint32_t rt = blockIdx.x, lt = blockIdx.y;
-  if (lt > rt) return;
+  const uint32_t rt = blockIdx.x;
+  const uint32_t min_a = tile_min_a[rt];
+  if (min_a == kNone) return;  // every token of this tile is sensitive
   __shared__ int64_t colT[kTile][kTile + 1];  // colT[r'][l'] = T[r0 + r'][l0 + l' - 1]
-  __shared__ uint32_t any_valid;
-  const uint32_t l0 = lt * kTile, r0 = rt * kTile;
+  const uint32_t r0 = rt * kTile;
   const uint32_t rl = threadIdx.x & (kTile - 1), grp = threadIdx.x / kTile;  // lane along r; 4 groups of 16 l's
   const uint32_t r = r0 + rl;
   const uint32_t a_r = r < n ? seg_a[r] : kNone;  // kNone: r is sensitive or past the end
-  // candidates exist iff some r of the block has its segment start at or before the block's last l
-  if (threadIdx.x == 0) any_valid = 0;
-  __syncthreads();
-  if (a_r != kNone && a_r <= l0 + kTile - 1 && r + 1 >= min_len + (a_r > l0 ? a_r : l0)) atomicOr(&any_valid, 1u);
-  __syncthreads();
-  if (!any_valid) return;
-  // stage T[r][l-1] for the block: rows r0.., columns l0-1 .. l0+62, loaded along the rows
-  for (uint32_t e = threadIdx.x; e < kTile * kTile; e += blockDim.x) {
-    const uint32_t rr = e / kTile, ll = e % kTile;
-    const uint32_t gr = r0 + rr, gl = l0 + ll;  // gl = l; column wanted = l - 1
-    colT[rr][ll] = (gr < n && gl >= 1 && gl - 1 < n) ? T[(uint64_t)gr * n + (gl - 1)] : 0;
-  }
-  __syncthreads();
+  const int64_t d_r = a_r != kNone ? diag[r] : 0;
   bool have = false;
   int64_t best = 0;
   uint32_t best_l = 0;
-  if (a_r != kNone) {
-    const int64_t d_r = diag[r];
+  for (uint32_t lt = min_a / kTile + blockIdx.y; lt <= rt; lt += kSearchSplit) {  // ascending l
+    const uint32_t l0 = lt * kTile;
+    __syncthreads();  // the previous block's tile is no longer read
+    // stage T[r][l-1] for the block: rows r0.., columns l0-1 .. l0+62 (all at or left of the diagonal tile)
+    for (uint32_t e = threadIdx.x; e < kTile * kTile; e += blockDim.x) {
+      const uint32_t rr = e / kTile, ll = e % kTile;
+      const uint32_t gr = r0 + rr, gl = l0 + ll;  // gl = l; column wanted = l - 1
+      colT[rr][ll] = (gr < n && gl >= 1 && gl - 1 < n) ? T[(uint64_t)gr * n + (gl - 1)] : 0;
+    }
+    __syncthreads();
+    if (a_r == kNone) continue;
 #pragma unroll 4
     for (uint32_t k = 0; k < kTile / 4; ++k) {
       const uint32_t ll = grp * (kTile / 4) + k, l = l0 + ll;
       if (l > r || l < a_r || r - l + 1 < min_len) continue;
-      const int64_t up = l ? T[(uint64_t)(l - 1) * n + r] : 0;  // T[l-1][r], lanes along r
       const int64_t dl = l ? diag[l - 1] : 0;
-      const int64_t score = d_r - up - 2 * colT[rl][ll] + 2 * dl;
+      const int64_t score = d_r + dl - 2 * colT[rl][ll];
       if (!have || score > best) {  // l ascending: the smallest l stays on ties
         have = true;
         best = score;
@@ -221,12 +348,36 @@ __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__r
       }
     }
   }
-  if (!have) return;
-  const uint64_t u = (uint64_t)best ^ kBias;
+  // One atomic per wavefront where all its lanes look at the same segment (the usual case), else one per lane.
+  const uint32_t a_first = __builtin_amdgcn_readfirstlane(a_r);
+  const bool one_segment = __all(a_r == a_first) && a_first != kNone;
   if (pass == 0) {
-    if (best_u[a_r] < u) atomicMax((unsigned long long *)&best_u[a_r], (unsigned long long)u);
-  } else if (u == best_u[a_r]) {
-    atomicMin((unsigned long long *)&best_lr[a_r], ((unsigned long long)best_l << 32) | r);
+    uint64_t u = have ? (uint64_t)best ^ kBias : 0;  // 0: below every biased score
+    if (one_segment) {
+#pragma unroll
+      for (int m = 1; m < kWave; m <<= 1) {
+        const uint64_t o = shfl_xor_u64(u, m);
+        u = o > u ? o : u;
+      }
+      if ((threadIdx.x & (kWave - 1)) == 0 && u != 0 && best_u[a_first] < u)
+        atomicMax((unsigned long long *)&best_u[a_first], (unsigned long long)u);
+    } else if (have && best_u[a_r] < u) {
+      atomicMax((unsigned long long *)&best_u[a_r], (unsigned long long)u);
+    }
+  } else {
+    const bool top = have && ((uint64_t)best ^ kBias) == best_u[a_r];
+    uint64_t lr = top ? (((uint64_t)best_l << 32) | r) : ~0ull;  // ~0: above every packed (l, r)
+    if (one_segment) {
+#pragma unroll
+      for (int m = 1; m < kWave; m <<= 1) {
+        const uint64_t o = shfl_xor_u64(lr, m);
+        lr = o < lr ? o : lr;
+      }
+      if ((threadIdx.x & (kWave - 1)) == 0 && lr != ~0ull)
+        atomicMin((unsigned long long *)&best_lr[a_first], (unsigned long long)lr);
+    } else if (top) {
+      atomicMin((unsigned long long *)&best_lr[a_r], (unsigned long long)lr);
+    }
   }
 }
 
@@ -253,10 +404,10 @@ __global__ __launch_bounds__(256) void annotate_finish_kernel(const int64_t *__r
     score = (int64_t)(best_u[a] ^ kBias);
     inside = bl <= i && i <= br;
     if (inside) {
-      // inter_i = T[i][bl-1] - T[i-1][bl-1];  intra_i = T[i][i] - T[i-1][i] - inter_i
+      // inter_i = T[i][bl-1] - T[i-1][bl-1];  intra_i = T[i][i] - T[i-1][i] - inter_i, T[i-1][i] = T[i-1][i-1]
       const int64_t t_i = bl ? T[(uint64_t)i * n + bl - 1] : 0;
       const int64_t t_p = (bl && i) ? T[(uint64_t)(i - 1) * n + bl - 1] : 0;
-      const int64_t up = i ? T[(uint64_t)(i - 1) * n + i] : 0;
+      const int64_t up = i ? diag[i - 1] : 0;
       const int64_t inter = t_i - t_p;
       di = inter - (diag[i] - up - inter);
     }
@@ -326,16 +477,15 @@ __global__ __launch_bounds__(256) void annotate_mark_kernel(uint32_t n, const ui
   recompute[i] = mark;
 }
 
-inline uint32_t pad_to_tile(uint32_t n) { return (n + kTile - 1) / kTile * kTile; }
-
 }  // namespace
 }  // namespace cp
 
 extern "C" size_t cp_sat_scratch_bytes(uint32_t n) {
   using namespace cp;
-  const uint64_t n_pad = pad_to_tile(n), n_t = n_pad / kTile;
-  // column sums and row sums per tile row / tile column, scan totals, per-token arrays of cp_annotate
-  return (size_t)(2 * n_t * n_pad * 8 + ((2 * n_t * n_pad) / kScanTile + 2) * 16 + 56ull * n + 16 * 256);
+  const uint64_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
+  const uint64_t cols = n_i * (n_j * kTileC), rows = n_j * (n_i * kTile);
+  // column sums per tile row, row sums per tile column, scan totals, per-token arrays of cp_annotate
+  return (size_t)((cols + rows) * 8 + (rows / kScanTile + 2) * 16 + 64ull * n + 16 * 256);
 }
 
 extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
@@ -343,23 +493,36 @@ extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, ui
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (n == 0) return CP_OK;
-  if (n > (1u << 20)) return CP_ERR_UNSUPPORTED;  // sums of n * n weights of at most 2^52 each stay below 2^63 ... for sane weights
+  if (n > (1u << 20)) return CP_ERR_UNSUPPORTED;
   if (!attn || !T || ld < n || !scratch || !aligned(scratch, 256) || !aligned(attn, 4) || !aligned(T, 8))
     return CP_ERR_INVALID_ARG;
   if (scratch_bytes < cp_sat_scratch_bytes(n)) return CP_ERR_SCRATCH;
-  const uint32_t n_pad = pad_to_tile(n), n_t = n_pad / kTile;
+  const uint32_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
+  const uint32_t n_pad_c = n_j * kTileC, n_pad_r = n_i * kTile;
   Scratch sc(scratch, scratch_bytes);
-  int64_t *colsum = sc.take<int64_t>((size_t)n_t * n_pad);
-  int64_t *rowsum = sc.take<int64_t>((size_t)n_t * n_pad);
-  RunningRowsOp::T *agg = sc.take<RunningRowsOp::T>(div_up((uint64_t)n_t * n_pad, kScanTile) + 1);
+  int64_t *colsum = sc.take<int64_t>((size_t)n_i * n_pad_c);
+  int64_t *rowsum = sc.take<int64_t>((size_t)n_j * n_pad_r);
+  RunningRowsOp::T *agg = sc.take<RunningRowsOp::T>(div_up((uint64_t)n_j * n_pad_r, kScanTile) + 1);
   if (!colsum || !rowsum || !agg) return CP_ERR_SCRATCH;
-  if ((uint64_t)n_t * n_pad >= 0x80000000ull) return CP_ERR_UNSUPPORTED;
-  const dim3 tiles(n_t, n_t);
-  sat_tile_sums_kernel<<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad, colsum, rowsum);
-  sat_exclusive_over_tiles_kernel<<<dim3(div_up(n_pad, 64), 2), 64, 0, stream>>>(colsum, rowsum, n_t, n_pad);
-  RunningRowsOp op{rowsum, n_pad, n_t * n_pad};
-  if (int32_t rc = run_scan<RunningRowsOp>(stream, op, n_t * n_pad, agg)) return rc;
-  sat_apply_kernel<<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad, colsum, rowsum, T);
+  if ((uint64_t)n_j * n_pad_r >= 0x80000000ull) return CP_ERR_UNSUPPORTED;
+  const bool vec_ld = ld % 2 == 0 && aligned(attn, 8);  // every (row, column pair) starts on 8 bytes
+  const bool vec_st = n % 2 == 0 && aligned(T, 16);
+  const dim3 tiles(n_j, n_i);
+  if (vec_ld) sat_tile_sums_kernel<true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum);
+  else sat_tile_sums_kernel<false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum);
+  const uint32_t widest = n_pad_c > n_pad_r ? n_pad_c : n_pad_r;
+  sat_exclusive_over_tiles_kernel<<<dim3(div_up(widest, 64), 2), 64, 0, stream>>>(colsum, n_i, n_pad_c, rowsum, n_j,
+                                                                                  n_pad_r);
+  RunningRowsOp op{rowsum, n_pad_r, n_j * n_pad_r};
+  if (int32_t rc = run_scan<RunningRowsOp>(stream, op, n_j * n_pad_r, agg)) return rc;
+  if (vec_ld && vec_st)
+    sat_apply_kernel<true, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
+  else if (vec_ld)
+    sat_apply_kernel<true, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
+  else if (vec_st)
+    sat_apply_kernel<false, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
+  else
+    sat_apply_kernel<false, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
   return check_launch();
 }
 
@@ -384,13 +547,14 @@ extern "C" int32_t cp_annotate(void *stream_, const int64_t *T, uint32_t n, cons
   uint64_t *best_lr = sc.take<uint64_t>(n);
   int64_t *d = sc.take<int64_t>(n);
   uint32_t *rank = sc.take<uint32_t>(n);
-  if (!agg || !seg_a || !diag || !best_u || !best_lr || !d || !rank) return CP_ERR_SCRATCH;
+  uint32_t *tile_min_a = sc.take<uint32_t>(div_up(n, kTile));
+  if (!agg || !seg_a || !diag || !best_u || !best_lr || !d || !rank || !tile_min_a) return CP_ERR_SCRATCH;
   SegStartOp so{mask, seg_a, n};
   if (int32_t rc = run_scan<SegStartOp>(stream, so, n, agg)) return rc;
   const uint32_t blocks = div_up(n, 256), n_t = div_up(n, kTile);
-  annotate_init_kernel<<<blocks, 256, 0, stream>>>(T, n, diag, best_u, best_lr);
+  annotate_init_kernel<<<blocks, 256, 0, stream>>>(T, n, seg_a, diag, best_u, best_lr, tile_min_a);
   for (int pass = 0; pass < 2; ++pass)
-    annotate_search_kernel<<<dim3(n_t, n_t), 256, 0, stream>>>(T, n, diag, seg_a, min_len, pass, best_u, best_lr);
+    annotate_search_kernel<<<dim3(n_t, kSearchSplit), 256, 0, stream>>>(T, n, diag, seg_a, tile_min_a, min_len, pass, best_u, best_lr);
   annotate_finish_kernel<<<blocks, 256, 0, stream>>>(T, n, diag, seg_a, best_u, best_lr, best_l, best_r, best_score,
                                                      reusable, store_mask, d, rank);
   if (rho_percent)

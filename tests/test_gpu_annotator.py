@@ -31,7 +31,9 @@ def gpu_annotate(G, a, mask, min_len, rho):
 def check(G, a, mask, min_len, rho):
     T, bl, br, bs, reus, rec, sm = gpu_annotate(G, a, mask, min_len, rho)
     oT = O.sat_build(a)
-    assert np.array_equal(T, oT)
+    n = len(mask)
+    assert np.array_equal(np.tril(T), np.tril(oT))  # what the library promises: every j <= i
+    assert np.array_equal(np.triu(oT, 1), np.triu(np.repeat(np.diag(oT)[:, None], n, axis=1), 1))  # T[i][j>i] = T[i][i]
     want = O.annotate(oT, mask, min_len, rho)
     for g, w, name in zip((bl, br, bs, reus, rec), want, ("best_l", "best_r", "best_score", "reusable", "recompute")):
         assert np.array_equal(g, w), name
@@ -47,6 +49,18 @@ def test_annotator_small(G, n, min_len, rho):
     bl, br, bs, reus, rec = check(G, a, mask, min_len, rho)
     if n >= 200 and min_len <= 32:
         assert reus.sum() > 0 and (rho == 0 or rec.sum() > 0)
+
+
+def test_annotator_full_size(G):
+    """n = 10,000 (the size the side benchmark runs): 400 MB of weights, an 800 MB table."""
+    n = 10000
+    a = AT.make_attention(n)
+    mask = AT.make_mask(n, run_mean=8.0, cover=0.01)
+    bl, br, bs, reus, rec = check(G, a, mask, 128, 25)
+    assert reus.sum() > 0.8 * n and abs(int(rec.sum()) - int(reus.sum()) // 4) < 20
+    one = np.zeros(n, np.uint8)  # a single segment: every (l, r) pair is a candidate
+    bl, br, bs, reus, rec = check(G, a, one, 128, 25)
+    assert bl[0] != X
 
 
 def test_annotator_edge_inputs(G):
@@ -66,7 +80,7 @@ def test_annotator_edge_inputs(G):
     check(G, np.zeros((n, 132), np.float32), z, 2, 50)  # all scores tie at zero
     check(G, eye, np.ones(n, np.uint8), 1, 25)  # everything sensitive
     junk = AT.make_attention(n, seed=5)
-    junk[3, 1], junk[9, 2], junk[11, 4] = np.nan, np.inf, -3e9
+    junk[3, 1], junk[9, 2], junk[11, 4], junk[12, 5], junk[13, 6] = np.nan, np.inf, -3e9, 262144.0, 262145.0
     junk[2, 100] = 0.7  # above the diagonal
     junk[20, 7], junk[20, 8] = 2.0 ** -33, 3 * 2.0 ** -33
     mk = AT.make_mask(n, seed=6, run_mean=2.0, cover=0.1)
@@ -76,6 +90,10 @@ def test_annotator_edge_inputs(G):
     wide[:, :132] = AT.make_attention(n, seed=8)
     wide[:, 140:] = 5.0  # padding the library must never read as weights
     check(G, wide, mk, 1, 25)
+    # a row stride that is no multiple of four floats: the library falls back to scalar loads
+    odd = np.zeros((n, 133), np.float32)
+    odd[:, :132] = AT.make_attention(n, seed=9)
+    check(G, odd, mk, 2, 25)
 
 
 def test_annotator_feeds_the_pool(G):

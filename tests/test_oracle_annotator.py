@@ -16,7 +16,7 @@ def q_matrix(a):
     n = a.shape[0]
     q = np.rint(a[:, :n].astype(np.float64) * S)
     q[~np.isfinite(q)] = 0
-    q[np.abs(a[:, :n].astype(np.float64)) > 2.0 ** 20] = 0
+    q[np.abs(a[:, :n].astype(np.float64)) > 2.0 ** 18] = 0
     return np.tril(q).astype(np.int64)
 
 
