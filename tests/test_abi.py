@@ -40,3 +40,52 @@ def test_binding_refuses_host_tensors():
     t = torch.zeros(4, dtype=torch.int32)
     with pytest.raises(ValueError):
         cp.cp_hash_segments(t, t.view(torch.uint8)[:4], t[:2], torch.zeros(4, dtype=torch.int64), t.view(torch.uint8))
+
+
+def test_argument_errors_are_found_on_the_host():
+    """Bad arguments are rejected before anything is enqueued, so this runs without a GPU.  Pointers here
+    are made-up aligned addresses that the library must not (and, failing first, does not) touch."""
+    B = cp.binding
+    L = B.lib()
+    P, Q, S = 0x10000, 0x20000, 0x30000  # "device pointers", 64 KiB aligned
+    big = 1 << 30
+    tab = B.TableStruct(P, Q, 1024)
+    lay = B.KVLayout.token_major(2, 2, 64)
+    INV, UNS, SCR = B.ERR_INVALID_ARG, B.ERR_UNSUPPORTED, B.ERR_SCRATCH
+    # empty batches are no-ops
+    assert L.cp_hash_segments(None, None, None, None, 0, 0, B.BASE, None, None, 0) == B.OK
+    assert L.cp_probe(None, tab, None, 0, None) == B.OK
+    assert L.cp_verify_chain(None, None, None, None, 0, None, None, 0, 0, None, None, 0) == B.OK
+    assert L.cp_filter_matches(None, None, None, 0, 0, 1, None, 0, None, None, 0) == B.OK
+    assert L.cp_sat_build(None, None, 0, 0, None, None, 0) == B.OK
+    # null or inconsistent arguments
+    assert L.cp_hash_segments(None, None, Q, S, 4, 1, B.BASE, P, S, big) == INV
+    assert L.cp_hash_segments(None, P, Q, S, 4, 0, B.BASE, P, S, big) == INV  # no requests
+    assert L.cp_hash_runs(None, P, Q, S, 4, 1, B.BASE, P, None, S, big) == INV  # run_off missing
+    assert L.cp_hash_segments(None, P, Q, S, 4, 1, B.BASE, P, S, 1) == SCR  # scratch too small
+    assert L.cp_hash_segments(None, P, Q, S, 4, 1, B.BASE, P, S + 8, big) == INV  # scratch misaligned
+    assert L.cp_probe(None, B.TableStruct(None, Q, 1024), P, 4, Q) == INV
+    assert L.cp_probe(None, B.TableStruct(P, Q, 1000), P, 4, Q) == INV  # capacity not a multiple of 16
+    assert L.cp_probe(None, B.TableStruct(P + 8, Q, 1024), P, 4, Q) == INV  # keys misaligned
+    assert L.cp_probe2(None, tab, P, None, 4, Q) == INV
+    assert L.cp_insert_anchors(None, tab, P, Q, 4, 0, S) == INV  # W = 0
+    assert L.cp_hash_floating(None, tab, P, Q, 4, B.BASE, 0, P, None, S, big) == INV
+    assert L.cp_build_spans(None, None, Q, 4, 1, None, 4, P, P, P, None, None, Q, Q, S, big) == INV
+    assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, None, lay, P, lay, 16, P, Q, S, S, S, big) == INV
+    assert L.cp_insert_kv_chain(None, tab, P, Q, Q, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, None, None, Q, S, S, S,
+                                big) == INV
+    assert L.cp_verify_chain(None, P, P, Q, 4, P, P, 16, 0, Q, S, big) == INV  # cand and slot_out are one array
+    assert L.cp_filter_matches(None, None, Q, 4, 1, 1, None, 0, P, S, big) == INV
+    assert L.cp_mark_recompute(None, P, None, 4, 16, Q) == INV
+    assert L.cp_fill_unmatched(None, None, 4, P, lay) == INV
+    assert L.cp_fill_unmatched(None, P, 4, Q, B.KVLayout(2, 2, 3, 96, 24, 12)) == UNS  # rows of 12 bytes
+    assert L.cp_touch(None, P, 4, 0, 16, Q) == INV  # epoch 0 means "free"
+    assert L.cp_lru_threshold(None, None, 16, 5, 1, P, S, big) == INV
+    assert L.cp_evict(None, tab, None, 16, P, Q, S, None, None, S, big) == INV
+    assert L.cp_table_compact(None, tab, tab, S) == INV  # source and destination share memory
+    assert L.cp_sat_build(None, P, 100, 64, Q, S, big) == INV  # row stride shorter than a row
+    assert L.cp_sat_build(None, P, (1 << 20) + 1, 1 << 21, Q, S, big) == UNS
+    assert L.cp_sat_build(None, P, 100, 100, Q, S, 16) == SCR
+    assert L.cp_annotate(None, P, 100, Q, 1, 101, P, P, P, Q, Q, None, S, big) == INV  # rho above 100 %
+    assert L.cp_tune(99, 1) == INV
+    assert L.cp_sat_scratch_bytes(10000) > (157 * 10112 + 79 * 10048) * 8  # tile carries of a 10,000-token request
