@@ -36,7 +36,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command, scaled by what the same counters read for kernels of known size
 # (profiles/gather_rows_kernel_<workload>.txt); None for workloads not profiled that way.
-MEASURED_TRAFFIC = {"llama3-8b": 9038385933, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522}
+MEASURED_TRAFFIC = {"llama3-8b": 9038385933, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
+                    "annotator-10000": 942963312}
 
 
 def log(*a):
@@ -144,7 +145,7 @@ def annotator_bench(args):
         "sat_build_ms": sat_ms, "annotate_ms": ann_ms,
         "roofline": {"kernel": "cp_sat_build (5 launches)", "bound": "hbm", "achieved": sat_bytes / (sat_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": sat_bytes / (sat_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC.get(f"annotator-{n}")},
     }
     if args.cpu_requests > 0:
         t = time.perf_counter()
