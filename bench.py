@@ -298,6 +298,18 @@ def main():
         own_read_ms = gather_alone()
         cp.cp_tune(0, 1 if args.multicast is None else args.multicast)
 
+    # the retriever's share alone: hashing, table lookups, (verification, filters,) span building; no KV moved
+    front_ms = None
+    if not args.no_extras:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pool.lookup(tok, mask, off, dst, buf, gather=False)
+        e0.record()
+        for _ in range(K):
+            pool.lookup(tok, mask, off, dst, buf, gather=False)
+        e1.record()
+        torch.cuda.synchronize()
+        front_ms = e0.elapsed_time(e1) / K
+
     # the same step replayed from a HIP graph (lookup + insert recorded once; the table resets stay eager)
     graph_ms = None
     if not args.no_extras:
@@ -375,6 +387,8 @@ def main():
         "gather_ms": gather_ms, "insert_ms": insert_ms,
         "front_and_reset_ms": ms_per_step - gather_ms - insert_ms,
         "ms_per_step_from_hip_graph": graph_ms,
+        "retrieval_front_end_ms": front_ms,
+        "retrieval_front_end_ms_per_10k_tokens": None if front_ms is None else front_ms * 1e4 / N,
         # bytes that must cross HBM when every distinct source row is read once: written + distinct read
         "gather_min_hbm_GBps": sh.tok_bytes * (matched + unique_src) / (gather_ms * 1e-3) / 1e9,
         "gather_GBps_without_read_sharing": None if own_read_ms is None else gather_bytes / (own_read_ms * 1e-3) / 1e9,
