@@ -117,14 +117,20 @@ class KVPool:
     def n_free(self):
         return self.free_slots.numel() - self.n_used
 
-    def evict(self, n_needed, scratch, stream=None):
+    def evict(self, n_needed, scratch, stream=None, compact=True):
         """Free at least ``n_needed`` slots, least recently used batches first (whole batches
-        at a time); the freed slots go to the end of the free list.  Reads one count back."""
+        at a time); the freed slots go to the end of the free list.  Reads one count back.
+        With ``compact`` the live entries then move to a fresh table, so that the keys of
+        evicted slots do not pile up and fill it."""
         assert self.slot_stamp is not None, "pool was created without lru=True"
         freed = torch.empty(self.n_slots, dtype=torch.int32, device=self.device)
         B.cp_lru_threshold(self.slot_stamp, self.n_slots, self.epoch, n_needed, self.threshold, scratch, stream=stream)
         B.cp_evict(self.table, self.slot_stamp, self.n_slots, self.threshold, freed, self.n_freed, self.slot_parent,
                    self.slot_recompute, scratch, stream=stream)
+        if compact:
+            fresh = B.Table(self.table.capacity, self.device, stream=stream)
+            B.cp_table_compact(self.table, fresh, self.flags, stream=stream)
+            self.table = fresh
         n = int(self.n_freed.item())
         self.free_slots = torch.cat([self.free_slots[self.n_used:], freed[:n]])
         self.n_used = 0

@@ -115,7 +115,7 @@ def test_touch_and_lru_threshold(G, seed):
 class Lifecycle:
     """The same multi-batch scenario driven through the GPU pool and through the oracle."""
 
-    def __init__(self, G, S, shape, seed, verify, min_len=1, marks=False, zero_fill=False):
+    def __init__(self, G, S, shape, seed, verify, min_len=1, marks=False, zero_fill=False, anchor_window=None):
         import paper_2605_23640_amd as cp
         self.G, self.cp, self.sh, self.S, self.seed = G, cp, shape, S, seed
         rng = np.random.default_rng(seed)
@@ -123,8 +123,11 @@ class Lifecycle:
         self.pool = cp.KVPool(shape.n_layers, shape.n_kv_heads, shape.head_dim, S, 4 * S,
                               torch.from_numpy(free.view(np.int32)), device=G.DEV,
                               pool_tensor=G.poison_tensor(S * shape.tok_bytes), verify=verify, min_len=min_len,
-                              recompute_marks=marks, zero_fill=zero_fill, lru=True)
+                              recompute_marks=marks, zero_fill=zero_fill, lru=True, anchor_window=anchor_window,
+                              anchor_capacity=4 * S)
         # oracle side
+        self.W = anchor_window
+        self.anchors = O.AnchorSet() if anchor_window is not None else None
         self.ix = O.Index()
         self.text = O.Text(S) if verify else None
         self.opool = np.full((S, shape.n_layers, 2, shape.row_bytes // 2), kvgen.POISON16, np.uint16)
@@ -147,9 +150,16 @@ class Lifecycle:
         # oracle lookup
         h = O.hash_segments(tok, mask, off)
         ro = O.run_offsets(mask, off)
-        got = O.probe(self.ix, h)
+        plain = O.probe(self.ix, h)
         if self.text is not None:
-            got = O.verify(self.text, tok, ro, got)
+            got = O.verify(self.text, tok, ro, plain)
+            if self.anchors is not None:
+                hf, fo = O.hash_floating(self.anchors, h, ro, self.W, with_offsets=True)
+                got = O.verify(self.text, tok, fo, O.probe(self.ix, hf), merge_into=got)
+        elif self.anchors is not None:
+            got = O.probe2(self.ix, h, O.hash_floating(self.anchors, h, ro, self.W))
+        else:
+            got = plain
         O.touch(got, epoch, self.stamps)
         served = O.filter_matches(got, off, self.min_len, self.marks)
         src, dpos, ln, delta, n, fl = O.build_spans(served, off)
@@ -162,7 +172,7 @@ class Lifecycle:
             assert np.array_equal(G.host_u32(buf.served), served), epoch
         assert np.array_equal(G.dst_as_rows(dst, sh, N), odst), epoch
         # room for what this batch will store
-        new_keys = len({int(x) for x, g in zip(h, got) if g == NONE and x != O.HASH_NONE})
+        new_keys = len({int(x) for x, g in zip(h, plain) if g == NONE and x != O.HASH_NONE})
         if new_keys > len(self.free):
             T = O.lru_threshold(self.stamps, epoch, new_keys - len(self.free))
             freed = O.evict(self.ix, self.stamps, T, self.text, self.marks)
@@ -181,6 +191,8 @@ class Lifecycle:
         n_g = self.pool.insert(d_tok, d_mask, d_off, kv, buf.hash, sout, buf.scratch, run_off_buf=roff,
                                recompute=_u8(rec, G.DEV) if self.marks is not None else None)
         okv = OH.gen_buffer(self.seed, sh, uid0, N)
+        if self.anchors is not None:
+            O.insert_anchors(self.anchors, h, ro, self.W)
         so, n_new, fl = O.insert_kv(self.ix, h, off, self.free, okv, OH.buf_layout(sh, N), self.opool, OH.pool_layout(sh),
                                     self.slot_pos)
         self.free = self.free[n_new:]
@@ -214,6 +226,29 @@ def test_pool_lifecycle_with_eviction(G, verify, min_len, marks, zero_fill):
         rec = (rng.random(len(tok)) < 0.25).astype(np.uint8)
         life.batch(epoch, tok, mask, off, rec)
     assert life.evictions >= 2
+
+
+@pytest.mark.parametrize("seed,vocab,W,verify", [(1, 3, 2, False), (2, 3, 2, True), (3, 4, 3, True), (4, 32000, 4, True),
+                                                 (5, 2, 1, True), (6, 5, None, True)])
+def test_pool_lifecycle_small_vocabulary_with_anchors(G, seed, vocab, W, verify):
+    """Few distinct tokens: shared prefixes, duplicate runs inside a batch, chance anchors and evictions all
+    occur often; floating anchors, verification, filter, marks and zero fill are on together."""
+    rng = np.random.default_rng(seed)
+    sh = gen.KVShape(1, 2, 64)
+    life = Lifecycle(G, 300, sh, 0xC0FFEE09 + seed, verify, min_len=2, marks=True, zero_fill=True, anchor_window=W)
+    corpus = [rng.integers(0, vocab, 60).astype(np.uint32) for _ in range(6)]
+    for epoch in range(1, 26):
+        parts = []
+        for d in rng.choice(6, 3, replace=False):
+            lead = rng.integers(0, vocab, int(rng.integers(0, 6))).astype(np.uint32)  # text in front of the shared one
+            a = int(rng.integers(0, 20))
+            parts.append(np.concatenate([lead, corpus[d][a:a + int(rng.integers(10, 41))]]))
+        tok = np.concatenate(parts).astype(np.uint32)
+        mask = (rng.random(len(tok)) < 0.08).astype(np.uint8)
+        off = np.concatenate([[0], np.cumsum([len(x) for x in parts])]).astype(np.uint32)
+        rec = (rng.random(len(tok)) < 0.25).astype(np.uint8)
+        life.batch(epoch, tok, mask, off, rec)
+    assert life.evictions >= 1
 
 
 def test_table_compact_after_eviction(G):
