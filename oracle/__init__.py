@@ -177,8 +177,8 @@ class Text:
         self._h = lib().cpo_text_new(int(n_slots))
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().cpo_text_free(self._h)
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.cpo_text_free(self._h)
             self._h = None
 
 
