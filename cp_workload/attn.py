@@ -44,10 +44,12 @@ def make_mask(n, seed=0xA77E0002, run_mean=6.0, cover=0.05):
     """Sensitive runs (geometric length) covering about ``cover`` of the tokens."""
     rng = np.random.default_rng(seed)
     m = np.zeros(n, np.uint8)
+    if cover <= 0.0:
+        return m
     gap_mean = run_mean * (1.0 - cover) / cover
     i, sens = 0, False
     while i < n:
-        ln = int(rng.geometric(1.0 / (run_mean if sens else gap_mean)))
+        ln = int(rng.geometric(1.0 / max(1.0, run_mean if sens else gap_mean)))
         if sens:
             m[i:i + ln] = 1
         i += ln
