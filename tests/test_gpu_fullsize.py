@@ -155,3 +155,40 @@ def test_full_size_float_anchors_verified_policies(G):
     del gst, glk, view
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def test_more_than_256_scan_tiles(G):
+    """About 600,000 tokens in one batch: the ordered scans run over some 600 tiles, so their single-workgroup carry
+    pass loops over several chunks of 256 tile totals (the configurations above stay below one chunk).
+    Tiny KV rows; floating anchors, verification, minimum length and marks on, so every scan takes part."""
+    from test_gpu_parity import compare_all
+
+    rng = np.random.default_rng(0xC0FFEE0A)
+    docs = [rng.integers(0, gen.VOCAB, 30000).astype(np.uint32) for _ in range(12)]
+    dmask = [(rng.random(30000) < 0.02).astype(np.uint8) for _ in range(12)]
+    parts_t, parts_m = [], []
+    for r in range(50):
+        pt, pm = [], []
+        for d in rng.choice(12, 3, replace=False):
+            a = int(rng.integers(0, 20000))
+            ln = int(rng.integers(2000, 6000))
+            lead = int(rng.integers(0, 30))
+            pt += [rng.integers(0, gen.VOCAB, lead).astype(np.uint32), docs[d][a:a + ln]]
+            pm += [np.zeros(lead, np.uint8), dmask[d][a:a + ln]]
+        parts_t.append(np.concatenate(pt))
+        parts_m.append(np.concatenate(pm))
+    tok, mask = np.concatenate(parts_t), np.concatenate(parts_m)
+    off = np.concatenate([[0], np.cumsum([len(p) for p in parts_t])]).astype(np.uint32)
+    dtok, dm = np.concatenate(docs), np.concatenate(dmask)
+    doff = (np.arange(13) * 30000).astype(np.uint32)
+    S = 1 << 19
+    wl = gen.Workload(name="many-tiles", seed=0xC0FFEE0A, shape=gen.KVShape(1, 1, 8), tok=tok, mask=mask, off=off,
+                      donor_tok=dtok, donor_mask=dm, donor_off=doff, donor_batches=[(0, 12)], pool_slots=S,
+                      free_slots=rng.permutation(S).astype(np.uint32), table_capacity=2 * S,
+                      donor_u=rng.random(len(dtok), dtype=np.float32))
+    assert wl.n_tokens > 256 * 1024 * 2 and len(dtok) > 256 * 1024
+    rec = (wl.donor_u < 0.25).astype(np.uint8)
+    ost, olk, gst, glk = compare_all(G, wl, anchor_window=16, verify=True, min_len=24, recompute=rec, zero_fill=True)
+    print(f"\n[many-tiles] {wl.n_tokens} tokens, {(olk.slot != O.SLOT_NONE).sum()} matched, "
+          f"{(olk.served != O.SLOT_NONE).sum()} served, {olk.n_spans} spans", flush=True)
+    assert (olk.served != O.SLOT_NONE).sum() > 100000
