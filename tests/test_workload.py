@@ -49,3 +49,33 @@ def test_full_size_shapes_match_the_stated_configurations():
     b = gen.make("llama3-70b")
     assert (b.n_requests, b.n_tokens, b.pool_slots, b.shape.tok_bytes) == (4, 131072, 393216, 320 * 1024)
     assert b.pool_slots * b.shape.tok_bytes == 120 * 2**30 and 0.06 < b.mask.mean() < 0.11
+
+
+def test_float_workload_and_recompute_draws():
+    f = gen.make("float", scale=0.25)
+    g = gen.make("float", scale=0.25)
+    assert np.array_equal(f.tok, g.tok) and np.array_equal(f.donor_u, g.donor_u)
+    assert (f.n_requests, f.n_tokens) == (4, 4096) and len(f.donor_off) - 1 == 16
+    # documents are stored on their own; in the requests they sit behind text of the request's own
+    first_doc = f.donor_tok[f.donor_off[0]:f.donor_off[1]]
+    assert not any(np.array_equal(f.tok[o:o + 8], first_doc[:8]) for o in f.off[:-1])  # no request starts with a document
+    # the recompute draw travels with the text: the shared prefix of the 8B-shaped donors carries one draw
+    a = gen.make("llama3-8b", scale=1 / 16)
+    p = 64  # prefix length at this scale
+    assert np.array_equal(a.donor_tok[:p], a.donor_tok[a.donor_off[1]:a.donor_off[1] + p])
+    assert np.array_equal(a.donor_u[:p], a.donor_u[a.donor_off[1]:a.donor_off[1] + p])
+    assert a.donor_u.dtype == np.float32 and 0.2 < (f.donor_u < 0.25).mean() < 0.3  # float: no repeated text
+    sub = gen.subsample(a, 1)
+    assert len(sub.donor_u) == len(sub.donor_tok)
+
+
+def test_attention_generator():
+    from cp_workload import attn as AT
+    a, b = AT.make_attention(300), AT.make_attention(300)
+    assert np.array_equal(a, b) and a.shape == (300, 300) and a.dtype == np.float32
+    assert (np.triu(a, 1) == 0).all() and np.allclose(a.sum(axis=1), 1.0, atol=1e-5) and (a >= 0).all()
+    assert a[:, :4].sum() > 4 * a[:, 4:8].sum() * 0.5  # the sink tokens draw visible weight
+    assert AT.make_attention(10, ld=16).shape == (10, 16)
+    m = AT.make_mask(20000, run_mean=8.0, cover=0.01)
+    assert 0.004 < m.mean() < 0.02 and AT.make_mask(50, cover=0.0).sum() == 0
+    assert 0.4 < AT.make_mask(5000, run_mean=1.0, cover=0.6).mean() < 0.8
