@@ -38,6 +38,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # (profiles/gather_rows_kernel_<workload>.txt); None for workloads not profiled that way.
 MEASURED_TRAFFIC = {"llama3-8b": 9038385933, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
                     "annotator-10000": 942963312}
+# (the float workload was profiled with all added rows on: profiles/gather_rows_kernel_float_all_rows.txt)
 
 
 def log(*a):
