@@ -40,6 +40,7 @@ class LookupResult:
     span_delta: torch.Tensor
     span_off: torch.Tensor  # int32[max_spans + 1]
     n_spans: torch.Tensor  # int32[1], device
+    served: torch.Tensor = None  # int32[N]: slot of the tokens that pass the pool's policies (slot itself without policies)
 
 
 class LookupBuffers:
@@ -190,7 +191,7 @@ class KVPool:
             if self.zero_fill:
                 B.cp_fill_unmatched(served, dst, self.request_layout(N), stream=stream)
         return LookupResult(buf.hash, buf.slot, buf.span_src, buf.span_dst, buf.span_len, buf.span_delta,
-                            buf.span_off, buf.n_spans)
+                            buf.span_off, buf.n_spans, served)
 
     def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None,
                run_off_buf=None, recompute=None):
