@@ -195,7 +195,10 @@ int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const ui
  * slot_tok[cand[i]] == tok[i], and slot_parent[cand[i]] == cand[i-1] (CP_SLOT_NONE at offset 0); by
  * induction cand[i] then holds exactly the segment's tokens up to i.  slot_out[i] = cand[i] if
  * accepted, else CP_SLOT_NONE; with merge != 0 only entries of slot_out that are CP_SLOT_NONE are
- * written (second key stream).  cand and slot_out must not be the same array. */
+ * written (second key stream).  stream_out (may be NULL) receives this stream's own result for
+ * every token whatever slot_out held: a token that both streams accept is served from the first,
+ * but the second stream's slots were used to get there and count as used for eviction (cp_touch).
+ * cand must not be the same array as slot_out or stream_out. */
 #define CP_PARENT_POISON 0xFFFFFFFEu
 int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, const uint32_t *tok,
                            const uint32_t *run_off, const uint32_t *off, uint32_t N, uint32_t R,
@@ -205,7 +208,7 @@ int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, c
                            uint32_t *status_flags, void *scratch, size_t scratch_bytes);
 int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand, uint32_t N,
                         const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots, int32_t merge,
-                        uint32_t *slot_out, void *scratch, size_t scratch_bytes);
+                        uint32_t *slot_out, uint32_t *stream_out, void *scratch, size_t scratch_bytes);
 
 /* Run-length pass: turn per-token slots into copy descriptors (the "token
  * spans" of the retriever's metadata, Sec. 4.3.1).  A span is a maximal run of
@@ -291,9 +294,11 @@ int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const u
  * slot_stamp[s] (u32[n_pool_slots]) = number (epoch >= 1) of the last batch that used slot s, 0 =
  * the slot is free.
  *   cp_touch: slot_stamp[slot[i]] = max(itself, epoch) for every token with a slot.  Call it with
- *     the unfiltered slots of a lookup and with the slot_out of an insert; since a match at a token
- *     implies matches at the tokens before it in its segment, a token is then never older than the
- *     tokens stored behind it.
+ *     the unfiltered slots of a lookup - with two key streams, with what EACH stream accepted
+ *     (cp_verify_chain's stream_out), not only with the merged result - and with the slot_out of an
+ *     insert; since a match at a token implies matches of the same stream at the tokens before it
+ *     in its segment, a token is then never older than the tokens stored behind it, and eviction by
+ *     age never takes the head of a stored run whose tail stays.
  *   cp_lru_threshold: *threshold_out (device) = the smallest T = epoch_now - a + 1, 0 <= a <
  *     CP_LRU_MAX_AGE, such that at least n_needed slots in use have stamp < T (slots of age
  *     CP_LRU_MAX_AGE - 1 or more count as one class; stamps above epoch_now are never chosen);

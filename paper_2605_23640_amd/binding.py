@@ -115,7 +115,7 @@ def lib():
         L.cp_insert_kv_chain.argtypes = [vp, TableStruct, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
                                          u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_verify_chain.restype = i32
-        L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, sz]
+        L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, vp, sz]
         L.cp_filter_matches.restype = i32
         L.cp_filter_matches.argtypes = [vp, vp, vp, u32, u32, u32, vp, u32, vp, vp, sz]
         L.cp_mark_recompute.restype = i32
@@ -277,14 +277,15 @@ def cp_hash_floating(anchors: Table, hashes, run_off, W, hash_float_out, scratch
     return hash_float_out
 
 
-def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, merge, slot_out, scratch, stream=None):
-    _need_cuda(tok, seg_off, cand, slot_tok, slot_parent, slot_out, scratch)
+def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, merge, slot_out, scratch, stream=None,
+                    stream_out=None):
+    _need_cuda(tok, seg_off, cand, slot_tok, slot_parent, slot_out, scratch, stream_out)
     N = tok.numel()
     assert seg_off.numel() == N and cand.numel() == N and slot_out.numel() == N
     assert slot_tok.numel() >= n_pool_slots and slot_parent.numel() >= n_pool_slots
     _check("cp_verify_chain", lib().cp_verify_chain(_stream(stream), _ptr(tok), _ptr(seg_off), _ptr(cand), N,
                                                     _ptr(slot_tok), _ptr(slot_parent), n_pool_slots, 1 if merge else 0,
-                                                    _ptr(slot_out), _ptr(scratch), scratch.numel()))
+                                                    _ptr(slot_out), _ptr(stream_out), _ptr(scratch), scratch.numel()))
     return slot_out
 
 

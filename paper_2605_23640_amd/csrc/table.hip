@@ -421,7 +421,7 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
     // confirm every token's slot against the recorded chains (new slots are consistent by construction,
     // slots found under an existing key need not be), then take the unconfirmed new slots out of play
     if (int32_t rc = launch_chain_verify(stream, tok, run_off, cand, N, slot_tok, slot_parent, n_pool_slots, 0,
-                                         slot_out, agg))
+                                         slot_out, nullptr, agg))
       return rc;
     insert_poison_kernel<<<blocks, 256, 0, stream>>>(owner, cand, slot_out, N, n_pool_slots, slot_parent);
     if (int32_t rc = check_launch()) return rc;

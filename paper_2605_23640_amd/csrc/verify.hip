@@ -24,6 +24,7 @@ struct ChainOp {
   const uint32_t *slot_tok;
   const uint32_t *slot_parent;
   uint32_t *slot_out;
+  uint32_t *stream_out;  // nullable: this stream's own result, whatever slot_out already held
   uint32_t N, n_pool_slots, merge;
 
   static __device__ __forceinline__ T identity() { return 0u; }
@@ -46,6 +47,7 @@ struct ChainOp {
   __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
     const uint32_t r = (incl & 1u) ? CP_SLOT_NONE : cand[i];
     if (!merge || slot_out[i] == CP_SLOT_NONE) slot_out[i] = r;
+    if (stream_out) stream_out[i] = r;
   }
   __device__ __forceinline__ void finish(T) const {}
 };
@@ -54,8 +56,8 @@ struct ChainOp {
 
 int32_t launch_chain_verify(hipStream_t stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
                             uint32_t N, const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots,
-                            uint32_t merge, uint32_t *slot_out, uint32_t *agg) {
-  ChainOp op{tok, seg_off, cand, slot_tok, slot_parent, slot_out, N, n_pool_slots, merge};
+                            uint32_t merge, uint32_t *slot_out, uint32_t *stream_out, uint32_t *agg) {
+  ChainOp op{tok, seg_off, cand, slot_tok, slot_parent, slot_out, stream_out, N, n_pool_slots, merge};
   return run_scan<ChainOp>(stream, op, N, agg);
 }
 
@@ -63,18 +65,18 @@ int32_t launch_chain_verify(hipStream_t stream, const uint32_t *tok, const uint3
 
 extern "C" int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
                                    uint32_t N, const uint32_t *slot_tok, const uint32_t *slot_parent,
-                                   uint32_t n_pool_slots, int32_t merge, uint32_t *slot_out, void *scratch,
-                                   size_t scratch_bytes) {
+                                   uint32_t n_pool_slots, int32_t merge, uint32_t *slot_out, uint32_t *stream_out,
+                                   void *scratch, size_t scratch_bytes) {
   using namespace cp;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (!tok || !seg_off || !cand || !slot_tok || !slot_parent || !slot_out || !scratch || !aligned(scratch, 256))
     return CP_ERR_INVALID_ARG;
-  if (cand == slot_out) return CP_ERR_INVALID_ARG;  // neighbours read cand while results are written
+  if (cand == slot_out || cand == stream_out) return CP_ERR_INVALID_ARG;  // neighbours read cand while results are written
   if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
   uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
   if (!agg) return CP_ERR_SCRATCH;
   return launch_chain_verify((hipStream_t)stream, tok, seg_off, cand, N, slot_tok, slot_parent, n_pool_slots,
-                             merge ? 1u : 0u, slot_out, agg);
+                             merge ? 1u : 0u, slot_out, stream_out, agg);
 }

@@ -56,6 +56,7 @@ class LookupBuffers:
         self.float_off = torch.empty(N, dtype=i32, device=device)
         self.cand = torch.empty(N, dtype=i32, device=device)  # unconfirmed slots (pools that verify)
         self.slot = torch.empty(N, dtype=i32, device=device)  # slot of every matched token
+        self.slot_b = torch.empty(N, dtype=i32, device=device)  # what the floating-key stream alone accepted
         self.served = torch.empty(N, dtype=i32, device=device)  # ... of those that pass the pool's policies
         m = max(1, self.max_spans)
         self.span_src = torch.empty(m, dtype=i32, device=device)
@@ -160,8 +161,13 @@ class KVPool:
                 B.cp_hash_floating(self.anchors, buf.hash, buf.run_off, self.anchor_window, buf.hash_float,
                                    buf.scratch, stream=stream, float_off_out=buf.float_off)
                 B.cp_probe(self.table, buf.hash_float, buf.cand, stream=stream)
+                lru = self.slot_stamp is not None
                 B.cp_verify_chain(tok, buf.float_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, True,
-                                  buf.slot, buf.scratch, stream=stream)
+                                  buf.slot, buf.scratch, stream=stream, stream_out=buf.slot_b if lru else None)
+                if lru:
+                    # where both streams are accepted the first one serves, but the second one's slots led to the
+                    # tokens it does serve: they count as used, or a stored run could lose its head to eviction
+                    B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         elif self.anchors is None:
             B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
             B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)

@@ -55,7 +55,7 @@ def test_argument_errors_are_found_on_the_host():
     # empty batches are no-ops
     assert L.cp_hash_segments(None, None, None, None, 0, 0, B.BASE, None, None, 0) == B.OK
     assert L.cp_probe(None, tab, None, 0, None) == B.OK
-    assert L.cp_verify_chain(None, None, None, None, 0, None, None, 0, 0, None, None, 0) == B.OK
+    assert L.cp_verify_chain(None, None, None, None, 0, None, None, 0, 0, None, None, None, 0) == B.OK
     assert L.cp_filter_matches(None, None, None, 0, 0, 1, None, 0, None, None, 0) == B.OK
     assert L.cp_sat_build(None, None, 0, 0, None, None, 0) == B.OK
     # null or inconsistent arguments
@@ -74,7 +74,7 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, None, lay, P, lay, 16, P, Q, S, S, S, big) == INV
     assert L.cp_insert_kv_chain(None, tab, P, Q, Q, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, None, None, Q, S, S, S,
                                 big) == INV
-    assert L.cp_verify_chain(None, P, P, Q, 4, P, P, 16, 0, Q, S, big) == INV  # cand and slot_out are one array
+    assert L.cp_verify_chain(None, P, P, Q, 4, P, P, 16, 0, Q, None, S, big) == INV  # cand and slot_out are one array
     assert L.cp_filter_matches(None, None, Q, 4, 1, 1, None, 0, P, S, big) == INV
     assert L.cp_mark_recompute(None, P, None, 4, 16, Q) == INV
     assert L.cp_fill_unmatched(None, None, 4, P, lay) == INV

@@ -155,6 +155,8 @@ class Lifecycle:
             got = O.verify(self.text, tok, ro, plain)
             if self.anchors is not None:
                 hf, fo = O.hash_floating(self.anchors, h, ro, self.W, with_offsets=True)
+                own_b = O.verify(self.text, tok, fo, O.probe(self.ix, hf))
+                O.touch(own_b, epoch, self.stamps)  # slots the floating stream walked through count as used
                 got = O.verify(self.text, tok, fo, O.probe(self.ix, hf), merge_into=got)
         elif self.anchors is not None:
             got = O.probe2(self.ix, h, O.hash_floating(self.anchors, h, ro, self.W))

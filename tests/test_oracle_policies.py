@@ -199,3 +199,62 @@ def test_lru_pool_lifecycle_against_hash_free_model(seed, vocab):
             if len(key) > 1:
                 assert key[:-1] in model.stored and model.stamp[model.stored[key[:-1]]] >= model.stamp[s]
     assert evictions >= 2
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_two_key_streams_keep_stored_runs_prefix_closed_under_lru(seed):
+    """With floating anchors a token can be served from the run-start stream while the floating stream,
+    which serves a later token, also walked through that position.  Both streams' accepted slots must be
+    stamped: then no stored text is ever newer than the text one token shorter, so evicting by age never
+    takes the head of a run whose tail stays (which exact verification would then refuse to follow)."""
+    rng = np.random.default_rng(40 + seed)
+    vocab, W, S = 4, int(rng.integers(1, 6)), 200
+    free = rng.permutation(S).astype(np.uint32)
+    ix, text, anchors = O.Index(), O.Text(S), O.AnchorSet()
+    stamps = np.zeros(S, np.uint32)
+    pool, slot_pos = np.zeros((S, 1, 2, 8), np.uint16), np.zeros(S, np.int32)
+    corpus = [rng.integers(0, vocab, 50).astype(np.uint32) for _ in range(5)]
+    live = {}  # stored text -> slot, kept by the test
+
+    def closed():
+        return all(t[:-1] in live and stamps[live[t[:-1]]] >= stamps[s] for t, s in live.items() if len(t) > 1)
+
+    for epoch in range(1, 16):
+        parts = []
+        for d in rng.choice(5, int(rng.integers(1, 4)), replace=False):
+            lead = rng.integers(0, vocab, int(rng.integers(0, 5))).astype(np.uint32)
+            a = int(rng.integers(0, 20))
+            parts.append(np.concatenate([lead, corpus[d][a:a + int(rng.integers(1, 31))]]))
+        tok = np.concatenate(parts).astype(np.uint32)
+        mask = (rng.random(len(tok)) < 0.05).astype(np.uint8)
+        off = np.concatenate([[0], np.cumsum([len(x) for x in parts])]).astype(np.uint32)
+        h, ro = O.hash_segments(tok, mask, off), O.run_offsets(mask, off)
+        plain = O.probe(ix, h)
+        hf, fo = O.hash_floating(anchors, h, ro, W, with_offsets=True)
+        own_a = O.verify(text, tok, ro, plain)
+        own_b = O.verify(text, tok, fo, O.probe(ix, hf))
+        O.touch(own_a, epoch, stamps)
+        O.touch(own_b, epoch, stamps)
+        assert closed(), ("lookup", epoch)
+        new_keys = len({int(x) for x, g in zip(h, plain) if g == NONE and x != O.HASH_NONE})
+        if new_keys > len(free):
+            freed = O.evict(ix, stamps, O.lru_threshold(stamps, epoch, new_keys - len(free)), text)
+            gone = set(freed.tolist())
+            live = {t: s for t, s in live.items() if s not in gone}
+            free = np.concatenate([free, freed])
+            assert closed(), ("eviction", epoch)
+        kv = np.zeros((1, 2, len(tok), 8), np.uint16)
+        lay = O.Layout(1, 1, 8, 16, 2 * len(tok) * 16, len(tok) * 16)
+        O.insert_anchors(anchors, h, ro, W)
+        so, n_new, _ = O.insert_kv(ix, h, off, free, kv, lay, pool, O.Layout(1, 1, 8, 32, 32, 16), slot_pos)
+        fresh, free = set(free[:n_new].tolist()), free[n_new:]
+        so = O.text_record(text, tok, ro, so)
+        for _, a, b in runs(tok, mask, off):
+            for i in range(a, b):
+                if so[i] != NONE and int(so[i]) in fresh:
+                    live[tuple(int(t) for t in tok[a:i + 1])] = int(so[i])
+        O.touch(so, epoch, stamps)
+        assert closed(), ("insert", epoch)
+        # everything the batch just stored or found is found again, whole
+        again = O.verify(text, tok, ro, O.probe(ix, h))
+        assert np.array_equal(again != NONE, so != NONE), epoch
