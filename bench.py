@@ -233,8 +233,8 @@ def main():
     slot_out = torch.empty(N, dtype=torch.int32, device=G.DEV)
     ins_scratch = cp.binding.new_scratch(N, 0, G.DEV)
     keys0, vals0 = pool.table.keys.clone(), pool.table.vals.clone()
-    if pool.anchors is not None:
-        akeys0, avals0 = pool.anchors.keys.clone(), pool.anchors.vals.clone()
+    if pool.slot_anchor is not None:
+        anchor0 = pool.slot_anchor.clone()
     K = args.steps
     hev = cp.binding.HipEvents(2 * K + 2)  # pairs around the gather's mover kernel, on the launch stream
     ev_ins = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
@@ -251,9 +251,8 @@ def main():
             ev_ins[k][1].record()
         pool.table.keys.copy_(keys0, non_blocking=True)
         pool.table.vals.copy_(vals0, non_blocking=True)
-        if pool.anchors is not None:
-            pool.anchors.keys.copy_(akeys0, non_blocking=True)
-            pool.anchors.vals.copy_(avals0, non_blocking=True)
+        if pool.slot_anchor is not None:
+            pool.slot_anchor.copy_(anchor0, non_blocking=True)
 
     for _ in range(args.warmup):
         step()
@@ -329,9 +328,8 @@ def main():
         def restore_tables():
             pool.table.keys.copy_(keys0, non_blocking=True)
             pool.table.vals.copy_(vals0, non_blocking=True)
-            if pool.anchors is not None:
-                pool.anchors.keys.copy_(akeys0, non_blocking=True)
-                pool.anchors.vals.copy_(avals0, non_blocking=True)
+            if pool.slot_anchor is not None:
+                pool.slot_anchor.copy_(anchor0, non_blocking=True)
 
         restore_tables()
         for _ in range(2):

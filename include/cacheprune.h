@@ -147,12 +147,15 @@ int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N,
  * hash of any substring follows in O(1) from prefix hashes and a power of the base.  Here:
  *   - cp_hash_runs is cp_hash_segments that also returns run_off[i], the number of tokens between
  *     the start of token i's run and i (0xFFFFFFFF for sensitive tokens);
- *   - cp_insert_anchors stores, for every run of at least W tokens, the chain hash of its W-th
- *     token (= the hash of its first W tokens) in a second table `anchors` used as a set
- *     (CP_FLAG_TABLE_FULL if it has no room);
+ *   - the hash of a stored run's first W tokens is the table key of the run's W-th token, so the
+ *     set of stored prefix hashes is kept as one mark byte per pool slot, slot_anchor
+ *     (u8[n_pool_slots], caller-owned, initialised to 0): the keys whose slot is marked are the
+ *     prefix hashes.  cp_insert_anchors, called after an insert with the slot_out it reported, sets
+ *     slot_anchor[slot[i]] = 1 for every token with run_off[i] == W - 1 and a slot.  A prefix hash
+ *     thus lives exactly as long as the run's W-th token is stored (cp_evict clears the mark);
  *   - cp_hash_floating marks as anchor every position a after its run's start whose W-token window
- *     lies inside the run and hashes to a key of `anchors`, and gives every token i the key of the
- *     request's tokens a..i for the latest anchor a <= i of its run:
+ *     lies inside the run and hashes to a key of `table` whose slot is marked, and gives every token
+ *     i the key of the request's tokens a..i for the latest anchor a <= i of its run:
  *         hash_float_out[i] = hash[i] - hash[a-1] * base^(i-a+1)   (mod 2^64; CP_HASH_NONE -> NONE-1),
  *     CP_HASH_NONE where there is no such anchor.  That key equals the chain hash the same tokens
  *     get as the beginning of a stored run, so it is looked up in the ordinary table;
@@ -162,12 +165,12 @@ int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N,
 int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
                      uint32_t R, uint64_t base, uint64_t *hash_out, uint32_t *run_off_out, void *scratch,
                      size_t scratch_bytes);
-int32_t cp_insert_anchors(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
-                          uint32_t N, uint32_t W, uint32_t *status_flags);
+int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, const uint32_t *slot, uint32_t N, uint32_t W,
+                          uint32_t n_pool_slots, uint8_t *slot_anchor);
 /* float_off_out (device u32[N], may be NULL): i - a for a token with an anchor, 0xFFFFFFFF otherwise. */
-int32_t cp_hash_floating(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
-                         uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out, uint32_t *float_off_out,
-                         void *scratch, size_t scratch_bytes);
+int32_t cp_hash_floating(void *stream, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,
+                         const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
+                         uint64_t *hash_float_out, uint32_t *float_off_out, void *scratch, size_t scratch_bytes);
 int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                   uint32_t *slot_out);
 
@@ -305,8 +308,8 @@ int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const u
  *     epoch_now + 1 if all slots in use together are fewer; 0 if n_needed == 0.
  *   cp_evict: every slot in use with stamp < *threshold (device) is freed: the value of its key's
  *     table entry becomes CP_SLOT_NONE (the key stays and is reused if the text is stored again),
- *     its stamp becomes 0, its slot_parent CP_PARENT_POISON and its slot_recompute 0 (both arrays
- *     may be NULL).  freed_slots (u32[n_pool_slots]) receives the freed slots in ascending order,
+ *     its stamp becomes 0, its slot_parent CP_PARENT_POISON, its slot_recompute and slot_anchor 0
+ *     (each of the three arrays may be NULL).  freed_slots (u32[n_pool_slots]) receives the freed slots in ascending order,
  *     *n_freed (device) their number: append them to the free list.
  *   cp_table_compact: copy the live entries (value != CP_SLOT_NONE) of src into dst, which must be
  *     initialised and must not share memory with src; drops the keys eviction left behind.
@@ -324,7 +327,7 @@ int32_t cp_lru_threshold(void *stream, const uint32_t *slot_stamp, uint32_t n_po
                          uint32_t n_needed, uint32_t *threshold_out, void *scratch, size_t scratch_bytes);
 int32_t cp_evict(void *stream, cp_table table, uint32_t *slot_stamp, uint32_t n_pool_slots, const uint32_t *threshold,
                  uint32_t *freed_slots, uint32_t *n_freed, uint32_t *slot_parent, uint8_t *slot_recompute,
-                 void *scratch, size_t scratch_bytes);
+                 uint8_t *slot_anchor, void *scratch, size_t scratch_bytes);
 int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags);
 
 /* ---- KV annotator: which tokens of a finished request are worth storing ------------------------

@@ -80,7 +80,7 @@ def lib():
         L.cpo_anchor_set_size.restype = u64
         L.cpo_anchor_set_size.argtypes = [vp]
         L.cpo_run_offsets.argtypes = [vp, vp, u32, vp]
-        L.cpo_insert_anchors.argtypes = [vp, vp, vp, u32, u32]
+        L.cpo_insert_anchors.argtypes = [vp, vp, vp, vp, u32, u32]
         L.cpo_hash_floating.argtypes = [vp, vp, vp, u32, u64, u32, vp, vp]
         L.cpo_text_new.restype = vp
         L.cpo_text_new.argtypes = [u32]
@@ -94,7 +94,7 @@ def lib():
         L.cpo_lru_threshold.restype = u32
         L.cpo_lru_threshold.argtypes = [vp, u32, u32, u32, u32]
         L.cpo_evict.restype = u32
-        L.cpo_evict.argtypes = [vp, vp, u32, u32, vp, vp, vp]
+        L.cpo_evict.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
         L.cpo_sat_build.argtypes = [vp, u32, u64, vp]
         L.cpo_sat_rect.restype = C.c_int64
         L.cpo_sat_rect.argtypes = [vp, u32, C.c_int64, C.c_int64, C.c_int64, C.c_int64]
@@ -156,9 +156,10 @@ def run_offsets(mask, off):
     return out
 
 
-def insert_anchors(anchors: AnchorSet, hashes, run_off, W):
-    hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
-    lib().cpo_insert_anchors(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], int(W))
+def insert_anchors(anchors: AnchorSet, hashes, run_off, slot, W):
+    """``slot``: what the insert of the same tokens reported; a run's prefix hash is kept while its W-th token is."""
+    hashes, run_off, slot = _arr(hashes, np.uint64), _arr(run_off, np.uint32), _arr(slot, np.uint32)
+    lib().cpo_insert_anchors(anchors._h, _p(hashes), _p(run_off), _p(slot), hashes.shape[0], int(W))
 
 
 def hash_floating(anchors: AnchorSet, hashes, run_off, W, base=BASE, with_offsets=False):
@@ -241,12 +242,14 @@ def lru_threshold(slot_stamp, epoch_now, n_needed, max_age=LRU_MAX_AGE):
     return int(lib().cpo_lru_threshold(_p(slot_stamp), slot_stamp.shape[0], int(epoch_now), int(n_needed), int(max_age)))
 
 
-def evict(index: Index, slot_stamp, threshold, text: "Text | None" = None, slot_recompute=None):
+def evict(index: Index, slot_stamp, threshold, text: "Text | None" = None, slot_recompute=None,
+          anchors: "AnchorSet | None" = None):
     """Frees slots in place; returns the freed slots (ascending)."""
     assert slot_stamp.dtype == np.uint32 and slot_stamp.flags.c_contiguous
     freed = np.empty(slot_stamp.shape[0], np.uint32)
     n = lib().cpo_evict(index._h, _p(slot_stamp), slot_stamp.shape[0], int(threshold), _p(freed),
-                        None if text is None else text._h, None if slot_recompute is None else _p(slot_recompute))
+                        None if text is None else text._h, None if slot_recompute is None else _p(slot_recompute),
+                        None if anchors is None else anchors._h)
     return freed[:n].copy()
 
 

@@ -228,7 +228,7 @@ extern "C" uint32_t cpo_insert_kv(cpo_index *ix, const uint64_t *hash, const uin
 // ---- floating anchors (Sec. 4.2.2 Step 1 and Step 2) -------------------------------------------
 
 struct cpo_anchor_set {
-  std::unordered_set<uint64_t> set;
+  std::unordered_map<uint64_t, uint32_t> set;  // prefix hash -> slot of the run's W-th token
 };
 
 extern "C" cpo_anchor_set *cpo_anchor_set_new(void) { return new cpo_anchor_set(); }
@@ -251,9 +251,10 @@ extern "C" void cpo_run_offsets(const uint8_t *mask, const uint32_t *off, uint32
 }
 
 extern "C" void cpo_insert_anchors(cpo_anchor_set *as, const uint64_t *hash, const uint32_t *run_off,
-                                   uint32_t N, uint32_t W) {
+                                   const uint32_t *slot, uint32_t N, uint32_t W) {
   for (uint32_t i = 0; i < N; ++i)
-    if (hash[i] != CPO_HASH_NONE && run_off[i] == W - 1) as->set.insert(hash[i]);
+    if (hash[i] != CPO_HASH_NONE && run_off[i] == W - 1 && slot[i] != CPO_SLOT_NONE)
+      as->set.emplace(hash[i], slot[i]);
 }
 
 extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const uint64_t *hash,
@@ -453,7 +454,7 @@ extern "C" uint32_t cpo_lru_threshold(const uint32_t *slot_stamp, uint32_t n_poo
 
 extern "C" uint32_t cpo_evict(cpo_index *ix, uint32_t *slot_stamp, uint32_t n_pool_slots,
                               uint32_t threshold, uint32_t *freed_slots, cpo_text *text,
-                              uint8_t *slot_recompute) {
+                              uint8_t *slot_recompute, cpo_anchor_set *anchors) {
   std::vector<uint8_t> gone(n_pool_slots, 0);
   uint32_t n = 0;
   for (uint32_t s = 0; s < n_pool_slots; ++s) {
@@ -466,6 +467,9 @@ extern "C" uint32_t cpo_evict(cpo_index *ix, uint32_t *slot_stamp, uint32_t n_po
   }
   for (auto it = ix->map.begin(); it != ix->map.end();)
     it = (it->second < n_pool_slots && gone[it->second]) ? ix->map.erase(it) : std::next(it);
+  if (anchors)
+    for (auto it = anchors->set.begin(); it != anchors->set.end();)
+      it = (it->second < n_pool_slots && gone[it->second]) ? anchors->set.erase(it) : std::next(it);
   return n;
 }
 

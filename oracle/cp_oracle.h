@@ -116,7 +116,7 @@ uint32_t cpo_insert_kv(cpo_index *, const uint64_t *hash, const uint32_t *off, u
  * there on get a second key: the hash of the request's tokens from the anchor through the token,
  * computed in O(1) from the run's chain hashes and a power of the base.  A token is served under
  * its run-start key if that hits, else under the key of the latest anchor at or before it. */
-typedef struct cpo_anchor_set cpo_anchor_set; /* set of prefix hashes. Opaque. */
+typedef struct cpo_anchor_set cpo_anchor_set; /* prefix hash -> slot of the run's W-th token. Opaque. */
 cpo_anchor_set *cpo_anchor_set_new(void);
 void cpo_anchor_set_free(cpo_anchor_set *);
 uint64_t cpo_anchor_set_size(const cpo_anchor_set *);
@@ -125,9 +125,11 @@ uint64_t cpo_anchor_set_size(const cpo_anchor_set *);
  * (0 for the first token of a run), 0xFFFFFFFF for sensitive tokens. */
 void cpo_run_offsets(const uint8_t *mask, const uint32_t *off, uint32_t R, uint32_t *run_off_out);
 
-/* Store the prefix hash of every run that has at least W tokens: the chain hash of its W-th token. */
-void cpo_insert_anchors(cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off, uint32_t N,
-                        uint32_t W);
+/* Store the prefix hash of every run whose first W tokens are in the pool: the chain hash of its W-th
+ * token, for every such token that has a slot (slot[i], as an insert reported it, is not NONE).  The
+ * prefix hash lives as long as that slot does: cpo_evict drops it with the slot. */
+void cpo_insert_anchors(cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off,
+                        const uint32_t *slot, uint32_t N, uint32_t W);
 
 /* hash_float_out[i] = hash of the tokens from the latest anchor a <= i of i's run through i, where
  * an anchor is a position a > run start such that the W tokens from a lie inside the run and their
@@ -180,15 +182,16 @@ void cpo_fill_unmatched(const uint32_t *slot, uint32_t N, void *dst, cpo_layout 
  * cpo_lru_threshold returns the smallest T of the form epoch_now - a + 1, a < max_age, such that at
  * least n_needed slots were last used before T (all slots of age max_age - 1 or more count as one
  * class); epoch_now + 1 if even that is not enough, 0 if n_needed = 0.  cpo_evict frees every slot
- * in use with stamp < threshold: its key leaves the index, its stamp, mark and text are cleared; the
- * freed slots are listed in ascending order; returns their number. */
+ * in use with stamp < threshold: its key leaves the index, its stamp, mark and text are cleared, a
+ * prefix hash recorded for it leaves the anchor set; the freed slots are listed in ascending order;
+ * returns their number. */
 void cpo_touch(const uint32_t *slot, uint32_t N, uint32_t epoch, uint32_t n_pool_slots,
                uint32_t *slot_stamp);
 uint32_t cpo_lru_threshold(const uint32_t *slot_stamp, uint32_t n_pool_slots, uint32_t epoch_now,
                            uint32_t n_needed, uint32_t max_age);
 uint32_t cpo_evict(cpo_index *, uint32_t *slot_stamp, uint32_t n_pool_slots, uint32_t threshold,
                    uint32_t *freed_slots, cpo_text *text /* nullable */,
-                   uint8_t *slot_recompute /* nullable */);
+                   uint8_t *slot_recompute /* nullable */, cpo_anchor_set *anchors /* nullable */);
 /* ---- KV annotator (Sec. 4.2.1 "C1", Steps 1-3) ----
  * attn: n x n attention weights of one request, row i = what token i attends to, row stride ld
  * (elements).  Arithmetic is exact: every weight is first turned into the integer

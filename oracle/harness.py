@@ -72,7 +72,6 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
     st.donor_hash = O.hash_segments(wl.donor_tok, wl.donor_mask, wl.donor_off)
     if anchor_window is not None:
         st.anchors, st.anchor_window = O.AnchorSet(), int(anchor_window)
-        O.insert_anchors(st.anchors, st.donor_hash, O.run_offsets(wl.donor_mask, wl.donor_off), st.anchor_window)
     if verify:
         st.text = O.Text(wl.pool_slots)
     if recompute is not None:  # uint8 per donor token: the annotator's recompute marks
@@ -93,6 +92,9 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
             slot_out = O.text_record(st.text, wl.donor_tok[t0:t1], O.run_offsets(wl.donor_mask[t0:t1], off), raw)
         if st.marks is not None:
             O.mark_recompute(slot_out, recompute[t0:t1], st.marks)
+        if st.anchors is not None:
+            O.insert_anchors(st.anchors, st.donor_hash[t0:t1], O.run_offsets(wl.donor_mask[t0:t1], off), slot_out,
+                             st.anchor_window)
         st.donor_slot[t0:t1] = slot_out
         st.n_used += n_new
         flags |= fl

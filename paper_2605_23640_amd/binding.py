@@ -108,9 +108,9 @@ def lib():
         L.cp_hash_runs.restype = i32
         L.cp_hash_runs.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, vp, sz]
         L.cp_insert_anchors.restype = i32
-        L.cp_insert_anchors.argtypes = [vp, TableStruct, vp, vp, u32, u32, vp]
+        L.cp_insert_anchors.argtypes = [vp, vp, vp, u32, u32, u32, vp]
         L.cp_hash_floating.restype = i32
-        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, vp, u32, u64, u32, vp, vp, vp, sz]
+        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, u32, vp, vp, u32, u64, u32, vp, vp, vp, sz]
         L.cp_insert_kv_chain.restype = i32
         L.cp_insert_kv_chain.argtypes = [vp, TableStruct, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
                                          u32, vp, vp, vp, vp, vp, vp, vp, sz]
@@ -127,7 +127,7 @@ def lib():
         L.cp_lru_threshold.restype = i32
         L.cp_lru_threshold.argtypes = [vp, vp, u32, u32, u32, vp, vp, sz]
         L.cp_evict.restype = i32
-        L.cp_evict.argtypes = [vp, TableStruct, vp, u32, vp, vp, vp, vp, vp, vp, sz]
+        L.cp_evict.argtypes = [vp, TableStruct, vp, u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_table_compact.restype = i32
         L.cp_table_compact.argtypes = [vp, TableStruct, TableStruct, vp]
         L.cp_sat_scratch_bytes.restype = sz
@@ -259,21 +259,23 @@ def cp_hash_runs(tok, mask, off, hash_out, run_off_out, scratch, base=BASE, stre
     return hash_out
 
 
-def cp_insert_anchors(anchors: Table, hashes, run_off, W, status_flags, stream=None):
-    _need_cuda(hashes, run_off, status_flags)
-    _check("cp_insert_anchors", lib().cp_insert_anchors(_stream(stream), anchors.struct, _ptr(hashes), _ptr(run_off),
-                                                        hashes.numel(), int(W), _ptr(status_flags)))
+def cp_insert_anchors(run_off, slot, W, n_pool_slots, slot_anchor, stream=None):
+    _need_cuda(run_off, slot, slot_anchor)
+    assert slot.numel() == run_off.numel() and slot_anchor.numel() >= n_pool_slots
+    _check("cp_insert_anchors", lib().cp_insert_anchors(_stream(stream), _ptr(run_off), _ptr(slot), run_off.numel(),
+                                                        int(W), n_pool_slots, _ptr(slot_anchor)))
 
 
-def cp_hash_floating(anchors: Table, hashes, run_off, W, hash_float_out, scratch, base=BASE, stream=None,
-                     float_off_out=None):
-    _need_cuda(hashes, run_off, hash_float_out, scratch, float_off_out)
+def cp_hash_floating(table: Table, slot_anchor, n_pool_slots, hashes, run_off, W, hash_float_out, scratch, base=BASE,
+                     stream=None, float_off_out=None):
+    _need_cuda(slot_anchor, hashes, run_off, hash_float_out, scratch, float_off_out)
     N = hashes.numel()
-    assert run_off.numel() == N and hash_float_out.numel() == N
+    assert run_off.numel() == N and hash_float_out.numel() == N and slot_anchor.numel() >= n_pool_slots
     assert float_off_out is None or float_off_out.numel() == N
-    _check("cp_hash_floating", lib().cp_hash_floating(_stream(stream), anchors.struct, _ptr(hashes), _ptr(run_off), N,
-                                                      base, int(W), _ptr(hash_float_out), _ptr(float_off_out),
-                                                      _ptr(scratch), scratch.numel()))
+    _check("cp_hash_floating", lib().cp_hash_floating(_stream(stream), table.struct, _ptr(slot_anchor), n_pool_slots,
+                                                      _ptr(hashes), _ptr(run_off), N, base, int(W),
+                                                      _ptr(hash_float_out), _ptr(float_off_out), _ptr(scratch),
+                                                      scratch.numel()))
     return hash_float_out
 
 
@@ -343,12 +345,12 @@ def cp_lru_threshold(slot_stamp, n_pool_slots, epoch_now, n_needed, threshold_ou
 
 
 def cp_evict(table: Table, slot_stamp, n_pool_slots, threshold, freed_slots, n_freed, slot_parent, slot_recompute,
-             scratch, stream=None):
-    _need_cuda(slot_stamp, threshold, freed_slots, n_freed, slot_parent, slot_recompute, scratch)
+             slot_anchor, scratch, stream=None):
+    _need_cuda(slot_stamp, threshold, freed_slots, n_freed, slot_parent, slot_recompute, slot_anchor, scratch)
     assert slot_stamp.numel() >= n_pool_slots and freed_slots.numel() >= n_pool_slots
     _check("cp_evict", lib().cp_evict(_stream(stream), table.struct, _ptr(slot_stamp), n_pool_slots, _ptr(threshold),
                                       _ptr(freed_slots), _ptr(n_freed), _ptr(slot_parent), _ptr(slot_recompute),
-                                      _ptr(scratch), scratch.numel()))
+                                      _ptr(slot_anchor), _ptr(scratch), scratch.numel()))
 
 
 def cp_table_compact(src: Table, dst: Table, status_flags, stream=None):

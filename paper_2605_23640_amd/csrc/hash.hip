@@ -130,15 +130,17 @@ extern "C" int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t
   return hash_common(stream, tok, mask, off, N, R, base, hash_out, run_off_out, scratch, scratch_bytes);
 }
 
-extern "C" int32_t cp_hash_floating(void *stream_, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
-                                    uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out,
-                                    uint32_t *float_off_out, void *scratch, size_t scratch_bytes) {
+extern "C" int32_t cp_hash_floating(void *stream_, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,
+                                    const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base,
+                                    uint32_t W, uint64_t *hash_float_out, uint32_t *float_off_out, void *scratch,
+                                    size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
-  if (W == 0 || !hash || !run_off || !hash_float_out || !scratch || !aligned(scratch, 256) || !aligned(hash, 8) ||
-      !aligned(hash_float_out, 8))
+  if (n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (W == 0 || !slot_anchor || !hash || !run_off || !hash_float_out || !scratch || !aligned(scratch, 256) ||
+      !aligned(hash, 8) || !aligned(hash_float_out, 8))
     return CP_ERR_INVALID_ARG;
   if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
@@ -148,7 +150,7 @@ extern "C" int32_t cp_hash_floating(void *stream_, cp_table anchors, const uint6
   uint64_t pw = 1;  // base^W mod 2^64
   for (uint64_t b = base, k = W; k; k >>= 1, b *= b)
     if (k & 1) pw *= b;
-  if (int32_t rc = launch_window_hits(stream, anchors, hash, run_off, N, W, pw, hit)) return rc;
+  if (int32_t rc = launch_window_hits(stream, table, slot_anchor, n_pool_slots, hash, run_off, N, W, pw, hit)) return rc;
   FloatKeyOp op{hash, run_off, hit, hash_float_out, float_off_out, base, N, W};
   return run_scan<FloatKeyOp>(stream, op, N, agg);
 }

@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void evict_table_kernel(cp_table t, const uint
 
 __global__ __launch_bounds__(256) void evict_slots_kernel(uint32_t *slot_stamp, const uint32_t *__restrict__ threshold,
                                                           uint32_t n_pool_slots, uint32_t *slot_parent,
-                                                          uint8_t *slot_recompute) {
+                                                          uint8_t *slot_recompute, uint8_t *slot_anchor) {
   uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
   if (s >= n_pool_slots) return;
   const uint32_t st = slot_stamp[s];
@@ -214,6 +214,7 @@ __global__ __launch_bounds__(256) void evict_slots_kernel(uint32_t *slot_stamp, 
   slot_stamp[s] = 0;
   if (slot_parent) slot_parent[s] = CP_PARENT_POISON;
   if (slot_recompute) slot_recompute[s] = 0;
+  if (slot_anchor) slot_anchor[s] = 0;
 }
 
 }  // namespace
@@ -287,7 +288,7 @@ extern "C" int32_t cp_lru_threshold(void *stream_, const uint32_t *slot_stamp, u
 
 extern "C" int32_t cp_evict(void *stream_, cp_table table, uint32_t *slot_stamp, uint32_t n_pool_slots,
                             const uint32_t *threshold, uint32_t *freed_slots, uint32_t *n_freed, uint32_t *slot_parent,
-                            uint8_t *slot_recompute, void *scratch, size_t scratch_bytes) {
+                            uint8_t *slot_recompute, uint8_t *slot_anchor, void *scratch, size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (!table.keys || !table.vals || table.capacity == 0 || table.capacity % CP_TABLE_BUCKET) return CP_ERR_INVALID_ARG;
@@ -302,6 +303,6 @@ extern "C" int32_t cp_evict(void *stream_, cp_table table, uint32_t *slot_stamp,
   evict_table_kernel<<<div_up(table.capacity, 256), 256, 0, stream>>>(table, slot_stamp, threshold, n_pool_slots);
   if (n_pool_slots)
     evict_slots_kernel<<<div_up(n_pool_slots, 256), 256, 0, stream>>>(slot_stamp, threshold, n_pool_slots, slot_parent,
-                                                                      slot_recompute);
+                                                                      slot_recompute, slot_anchor);
   return check_launch();
 }

@@ -88,7 +88,11 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const 
 
 // Floating-anchor lookup, step 1: does the W-token window ending at token i match a stored prefix
 // hash?  Only windows that lie inside one run and start after the run's first token are looked at.
-__global__ __launch_bounds__(kProbeThreads) void window_hit_kernel(cp_table anchors,
+// The prefix hash of a stored run is the table key of the run's W-th token, so the set of prefix
+// hashes is the set of keys whose (live) slot carries the anchor mark.
+__global__ __launch_bounds__(kProbeThreads) void window_hit_kernel(cp_table table,
+                                                                   const uint8_t *__restrict__ slot_anchor,
+                                                                   uint32_t n_pool_slots,
                                                                    const uint64_t *__restrict__ hash,
                                                                    const uint32_t *__restrict__ run_off, uint32_t N,
                                                                    uint32_t W, uint64_t base_pow_w,
@@ -99,8 +103,8 @@ __global__ __launch_bounds__(kProbeThreads) void window_hit_kernel(cp_table anch
     wh = hash[i] - hash[i - W] * base_pow_w;  // tokens i-W+1 .. i; token i-W is in the same run
     if (wh == CP_HASH_NONE) wh = CP_HASH_NONE - 1;
   }
-  const uint32_t r = group_lookup(anchors, wh);
-  if (i < N && (threadIdx.x & (kBucket - 1)) == 0) hit[i] = r != CP_SLOT_NONE;
+  const uint32_t s = group_lookup(table, wh);
+  if (i < N && (threadIdx.x & (kBucket - 1)) == 0) hit[i] = s < n_pool_slots && slot_anchor[s] != 0;
 }
 
 // Index of the entry that holds key h, taking a free entry for it if there is none yet; CP_SLOT_NONE
@@ -143,20 +147,15 @@ __device__ __forceinline__ uint32_t group_claim(const cp_table &t, uint64_t h) {
   return entry;
 }
 
-// Store the prefix hash of every run of at least W tokens (the chain hash of its W-th token) in the
-// anchor table: a set, so the order of arrival does not matter.
-__global__ __launch_bounds__(kProbeThreads) void insert_anchor_kernel(cp_table t, const uint64_t *__restrict__ hash,
-                                                                      const uint32_t *__restrict__ run_off,
-                                                                      uint32_t N, uint32_t W,
-                                                                      uint32_t *status_flags) {
-  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
-  const uint32_t sub = threadIdx.x & (kBucket - 1);
-  const uint64_t h = (q < N && run_off[q] == W - 1) ? hash[q] : CP_HASH_NONE;
-  const uint32_t entry = group_claim(t, h);
-  if (q < N && sub == 0 && h != CP_HASH_NONE) {
-    if (entry != CP_SLOT_NONE) t.vals[entry] = 0;  // any value other than NONE marks membership
-    else atomicOr(status_flags, CP_FLAG_TABLE_FULL);
-  }
+// Record the prefix hash of every run whose W-th token has a slot: that token's key is the hash of
+// the run's first W tokens, so a mark on its slot is all it takes.  Several tokens may name one
+// slot; all write the same byte.
+__global__ __launch_bounds__(kProbeThreads) void mark_anchor_kernel(const uint32_t *__restrict__ run_off,
+                                                                    const uint32_t *__restrict__ slot, uint32_t N,
+                                                                    uint32_t W, uint32_t n_pool_slots,
+                                                                    uint8_t *__restrict__ slot_anchor) {
+  const uint32_t i = blockIdx.x * kProbeThreads + threadIdx.x;
+  if (i < N && run_off[i] == W - 1 && slot[i] < n_pool_slots) slot_anchor[slot[i]] = 1;
 }
 
 // Copy of the live entries of one table into another (fresh) one: the keys of evicted slots, which
@@ -355,24 +354,24 @@ extern "C" int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_
   return probe_common(stream, table, hash_a, hash_b, N, slot_out);
 }
 
-extern "C" int32_t cp_insert_anchors(void *stream, cp_table anchors, const uint64_t *hash, const uint32_t *run_off,
-                                     uint32_t N, uint32_t W, uint32_t *status_flags) {
+extern "C" int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, const uint32_t *slot, uint32_t N,
+                                     uint32_t W, uint32_t n_pool_slots, uint8_t *slot_anchor) {
   using namespace cp;
-  if (N == 0) return CP_OK;
-  if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
-  if (int32_t rc = table_ok(anchors)) return rc;
-  if (W == 0 || !hash || !run_off || !status_flags || !aligned(hash, 8)) return CP_ERR_INVALID_ARG;
-  insert_anchor_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(
-      anchors, hash, run_off, N, W, status_flags);
+  if (N == 0 || n_pool_slots == 0) return CP_OK;
+  if (N >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (W == 0 || !run_off || !slot || !slot_anchor) return CP_ERR_INVALID_ARG;
+  mark_anchor_kernel<<<div_up(N, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(run_off, slot, N, W,
+                                                                                          n_pool_slots, slot_anchor);
   return check_launch();
 }
 
 namespace cp {
-int32_t launch_window_hits(hipStream_t stream, const cp_table &anchors, const uint64_t *hash, const uint32_t *run_off,
-                           uint32_t N, uint32_t W, uint64_t base_pow_w, uint8_t *hit) {
-  if (int32_t rc = table_ok(anchors)) return rc;
-  window_hit_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(anchors, hash, run_off,
-                                                                                                N, W, base_pow_w, hit);
+int32_t launch_window_hits(hipStream_t stream, const cp_table &table, const uint8_t *slot_anchor,
+                           uint32_t n_pool_slots, const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint32_t W,
+                           uint64_t base_pow_w, uint8_t *hit) {
+  if (int32_t rc = table_ok(table)) return rc;
+  window_hit_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
+      table, slot_anchor, n_pool_slots, hash, run_off, N, W, base_pow_w, hit);
   return check_launch();
 }
 }  // namespace cp

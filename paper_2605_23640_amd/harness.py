@@ -54,7 +54,7 @@ class GpuState:
     flags: int
 
 
-def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, anchor_capacity=None, verify=False, **policies) -> cp.KVPool:
+def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, verify=False, **policies) -> cp.KVPool:
     sh = wl.shape
     rope = cp.binding.Rope(wl.rope_theta, wl.rope_style) if wl.rope_theta is not None else None
     fs = wl.free_slots if free_slots is None else free_slots
@@ -63,7 +63,7 @@ def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, anchor_capac
     pool = cp.KVPool(sh.n_layers, sh.n_kv_heads, sh.head_dim, wl.pool_slots, wl.table_capacity,
                      torch.from_numpy(fs.view(np.int32)), rope=rope, device=DEV,
                      pool_tensor=poison_tensor(wl.pool_slots * sh.tok_bytes), anchor_window=anchor_window,
-                     anchor_capacity=anchor_capacity, verify=verify, **policies)
+                     verify=verify, **policies)
     pool.slot_pos.fill_(np.iinfo(np.int32).min)
     return pool
 
@@ -87,7 +87,7 @@ def prefill(wl, pool: cp.KVPool = None, recompute=None) -> GpuState:
         hbuf = torch.empty(n, dtype=torch.int64, device=DEV)
         sout = torch.empty(n, dtype=torch.int32, device=DEV)
         scratch = cp.binding.new_scratch(max(1, n), 0, DEV)
-        roff = torch.empty(max(1, n), dtype=torch.int32, device=DEV) if (pool.anchors is not None or pool.verify) else None
+        roff = torch.empty(max(1, n), dtype=torch.int32, device=DEV) if (pool.slot_anchor is not None or pool.verify) else None
         rec = None if recompute is None else torch.from_numpy(np.ascontiguousarray(recompute[t0:t1], np.uint8)).to(DEV)
         counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch, run_off_buf=roff, recompute=rec))
         donor_hash[t0:t1] = host_u64(hbuf)
@@ -126,7 +126,7 @@ def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=T
                    gather=gather)
     torch.cuda.synchronize()
     n = int(buf.n_spans.item())
-    anch = st.pool.anchors is not None
+    anch = st.pool.slot_anchor is not None
     runs = anch or st.pool.verify
     return GpuLookup(host_u64(buf.hash), host_u32(buf.slot), host_u32(buf.span_src)[:n], host_u32(buf.span_dst)[:n],
                      host_u32(buf.span_len)[:n], buf.span_delta.cpu().numpy()[:n], host_u32(buf.span_off)[:n + 1], n,

@@ -7,13 +7,13 @@ sequences of the two paths through libcacheprune.
 and, for a pool with floating anchors (window W),
 
     lookup :  cp_hash_runs -> cp_hash_floating -> cp_probe2 -> cp_build_spans -> cp_gather_kv
-    insert :  cp_hash_runs -> cp_insert_anchors -> cp_insert_kv
+    insert :  cp_hash_runs -> cp_insert_kv -> cp_insert_anchors
 
 and, for a pool that confirms every match exactly (``verify=True``),
 
     lookup :  cp_hash_runs -> cp_probe -> cp_verify_chain [-> cp_hash_floating -> cp_probe -> cp_verify_chain]
               -> cp_build_spans -> cp_gather_kv
-    insert :  cp_hash_runs [-> cp_insert_anchors] -> cp_insert_kv_chain
+    insert :  cp_hash_runs -> cp_insert_kv_chain [-> cp_insert_anchors]
 
 Policies hook in after the slots are known: cp_touch (LRU stamps), cp_filter_matches (minimum
 length, recompute marks) before cp_build_spans, cp_fill_unmatched after the gather;
@@ -73,7 +73,7 @@ class KVPool:
     cached position of every slot and the free list (hand-out order)."""
 
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
-                 device="cuda", pool_tensor=None, anchor_window=None, anchor_capacity=None, verify=False,
+                 device="cuda", pool_tensor=None, anchor_window=None, verify=False,
                  min_len=1, recompute_marks=False, zero_fill=False, lru=False):
         self.device = device
         self.n_slots = int(n_slots)
@@ -89,12 +89,12 @@ class KVPool:
         self.flags = torch.zeros(1, dtype=torch.int32, device=device)
         self.n_inserted = torch.zeros(1, dtype=torch.int32, device=device)
         self.rope = rope  # binding.Rope or None
-        # floating anchors: window length W and the set of stored runs' prefix hashes (None: run-start keys only)
+        # floating anchors: window length W (None: run-start keys only) and one mark per slot; the keys of the
+        # marked slots are the stored runs' prefix hashes
         self.anchor_window = anchor_window
-        self.anchors = None
+        self.slot_anchor = None
         if anchor_window is not None:
-            cap = anchor_capacity if anchor_capacity is not None else max(1024, self.n_slots // 4)
-            self.anchors = B.Table((int(cap) + B.TABLE_BUCKET - 1) // B.TABLE_BUCKET * B.TABLE_BUCKET, device)
+            self.slot_anchor = torch.zeros(self.n_slots, dtype=torch.uint8, device=device)
 
         # exact verification: per slot, the token it was stored for and the slot of its predecessor in the run
         self.verify = bool(verify)
@@ -128,7 +128,7 @@ class KVPool:
         freed = torch.empty(self.n_slots, dtype=torch.int32, device=self.device)
         B.cp_lru_threshold(self.slot_stamp, self.n_slots, self.epoch, n_needed, self.threshold, scratch, stream=stream)
         B.cp_evict(self.table, self.slot_stamp, self.n_slots, self.threshold, freed, self.n_freed, self.slot_parent,
-                   self.slot_recompute, scratch, stream=stream)
+                   self.slot_recompute, self.slot_anchor, scratch, stream=stream)
         if compact:
             fresh = B.Table(self.table.capacity, self.device, stream=stream)
             B.cp_table_compact(self.table, fresh, self.flags, stream=stream)
@@ -157,9 +157,10 @@ class KVPool:
             B.cp_probe(self.table, buf.hash, buf.cand, stream=stream)
             B.cp_verify_chain(tok, buf.run_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, False,
                               buf.slot, buf.scratch, stream=stream)
-            if self.anchors is not None:
-                B.cp_hash_floating(self.anchors, buf.hash, buf.run_off, self.anchor_window, buf.hash_float,
-                                   buf.scratch, stream=stream, float_off_out=buf.float_off)
+            if self.slot_anchor is not None:
+                B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off,
+                                   self.anchor_window, buf.hash_float, buf.scratch, stream=stream,
+                                   float_off_out=buf.float_off)
                 B.cp_probe(self.table, buf.hash_float, buf.cand, stream=stream)
                 lru = self.slot_stamp is not None
                 B.cp_verify_chain(tok, buf.float_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, True,
@@ -168,13 +169,13 @@ class KVPool:
                     # where both streams are accepted the first one serves, but the second one's slots led to the
                     # tokens it does serve: they count as used, or a stored run could lose its head to eviction
                     B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
-        elif self.anchors is None:
+        elif self.slot_anchor is None:
             B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
             B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
         else:
             B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
-            B.cp_hash_floating(self.anchors, buf.hash, buf.run_off, self.anchor_window, buf.hash_float, buf.scratch,
-                               stream=stream)
+            B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off, self.anchor_window,
+                               buf.hash_float, buf.scratch, stream=stream)
             B.cp_probe2(self.table, buf.hash, buf.hash_float, buf.slot, stream=stream)
         if self.slot_stamp is not None:
             B.cp_touch(buf.slot, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
@@ -208,13 +209,10 @@ class KVPool:
         filled here unless ``hashes_ready``).  ``recompute`` (uint8[N]): tokens the
         annotator marked for recomputation when their segment is reused."""
         N = tok.numel()
-        if self.anchors is not None or self.verify:
+        if self.slot_anchor is not None or self.verify:
             assert run_off_buf is not None, "a pool with floating anchors or verification needs run_off_buf"
             if not hashes_ready:
                 B.cp_hash_runs(tok, mask, off, hash_buf, run_off_buf, scratch, stream=stream)
-            if self.anchors is not None:
-                B.cp_insert_anchors(self.anchors, hash_buf, run_off_buf, self.anchor_window, self.flags,
-                                    stream=stream)
         elif not hashes_ready:
             B.cp_hash_segments(tok, mask, off, hash_buf, scratch, stream=stream)
         n_free = self.free_slots.numel() - self.n_used
@@ -227,6 +225,8 @@ class KVPool:
             B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src,
                            self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos, slot_out,
                            self.n_inserted, self.flags, scratch, stream=stream)
+        if self.slot_anchor is not None:  # a run's prefix hash is known from the moment its W-th token has a slot
+            B.cp_insert_anchors(run_off_buf, slot_out, self.anchor_window, self.n_slots, self.slot_anchor, stream=stream)
         if recompute is not None:
             assert self.slot_recompute is not None, "pool was created without recompute_marks=True"
             B.cp_mark_recompute(slot_out, recompute, self.n_slots, self.slot_recompute, stream=stream)

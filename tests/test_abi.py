@@ -68,8 +68,10 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_probe(None, B.TableStruct(P, Q, 1000), P, 4, Q) == INV  # capacity not a multiple of 16
     assert L.cp_probe(None, B.TableStruct(P + 8, Q, 1024), P, 4, Q) == INV  # keys misaligned
     assert L.cp_probe2(None, tab, P, None, 4, Q) == INV
-    assert L.cp_insert_anchors(None, tab, P, Q, 4, 0, S) == INV  # W = 0
-    assert L.cp_hash_floating(None, tab, P, Q, 4, B.BASE, 0, P, None, S, big) == INV
+    assert L.cp_insert_anchors(None, Q, Q, 4, 0, 16, S) == INV  # W = 0
+    assert L.cp_insert_anchors(None, Q, Q, 4, 2, 16, None) == INV  # no mark array
+    assert L.cp_hash_floating(None, tab, S, 16, P, Q, 4, B.BASE, 0, P, None, S, big) == INV  # W = 0
+    assert L.cp_hash_floating(None, tab, None, 16, P, Q, 4, B.BASE, 2, P, None, S, big) == INV  # no mark array
     assert L.cp_build_spans(None, None, Q, 4, 1, None, 4, P, P, P, None, None, Q, Q, S, big) == INV
     assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, None, lay, P, lay, 16, P, Q, S, S, S, big) == INV
     assert L.cp_insert_kv_chain(None, tab, P, Q, Q, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, None, None, Q, S, S, S,
@@ -81,7 +83,7 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_fill_unmatched(None, P, 4, Q, B.KVLayout(2, 2, 3, 96, 24, 12)) == UNS  # rows of 12 bytes
     assert L.cp_touch(None, P, 4, 0, 16, Q) == INV  # epoch 0 means "free"
     assert L.cp_lru_threshold(None, None, 16, 5, 1, P, S, big) == INV
-    assert L.cp_evict(None, tab, None, 16, P, Q, S, None, None, S, big) == INV
+    assert L.cp_evict(None, tab, None, 16, P, Q, S, None, None, None, S, big) == INV
     assert L.cp_table_compact(None, tab, tab, S) == INV  # source and destination share memory
     assert L.cp_sat_build(None, P, 100, 64, Q, S, big) == INV  # row stride shorter than a row
     assert L.cp_sat_build(None, P, (1 << 20) + 1, 1 << 21, Q, S, big) == UNS

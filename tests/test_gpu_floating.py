@@ -51,17 +51,25 @@ def test_rope_with_anchors(G):
     assert (glk.span_delta != 0).mean() > 0.5
 
 
-def test_anchor_table_full_is_flagged(G):
-    from paper_2605_23640_amd import binding as B
+@pytest.mark.parametrize("n_free", [None, 300])
+def test_a_prefix_hash_lives_with_its_token(G, n_free):
+    """The set of stored prefix hashes is the set of slots that hold a run's W-th token: one mark per
+    such slot and no other, also when the pool runs full and some W-th tokens get no slot."""
+    from oracle import harness as OH
 
+    W = 5
     wl = small_float(scale=0.5)
-    pool = G.make_pool(wl, anchor_window=2, anchor_capacity=16)  # one bucket: 16 anchors at most
-    gst = G.prefill(wl, pool)
-    assert gst.flags & B.FLAG_TABLE_FULL
-    # what did get in still serves lookups consistently: every hit names a slot holding that token's key
-    glk = G.lookup(gst)
-    hit = glk.slot != NONE
-    stored = dict(zip(gst.donor_hash.tolist(), gst.donor_slot.tolist()))
-    for i in np.flatnonzero(hit)[:2000]:
-        s = int(glk.slot[i])
-        assert stored.get(int(glk.hash[i])) == s or stored.get(int(glk.hash_float[i])) == s
+    if n_free is not None:
+        wl.free_slots = wl.free_slots[:n_free]
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=W))
+    ost = OH.prefill(wl, anchor_window=W)
+    assert np.array_equal(gst.donor_slot, ost.donor_slot)
+    ro = O.run_offsets(wl.donor_mask, wl.donor_off)
+    want = np.unique(ost.donor_slot[(ro == W - 1) & (ost.donor_slot != NONE)])
+    assert len(want) == len(ost.anchors) and len(want) > 0
+    got = np.flatnonzero(gst.pool.slot_anchor.cpu().numpy())
+    assert np.array_equal(got, want)
+    if n_free is not None:
+        assert ((ro == W - 1) & (ost.donor_slot == NONE) & (wl.donor_mask == 0)).any()  # some runs lost their W-th token
+    glk, olk = G.lookup(gst), OH.lookup(ost)
+    assert np.array_equal(glk.hash_float, olk.hash_float) and np.array_equal(glk.slot, olk.slot)

@@ -26,7 +26,7 @@ def test_step_replays_from_a_graph(G, kw):
     ins_scratch = cp.binding.new_scratch(N, 0, G.DEV)
     keys0, vals0 = pool.table.keys.clone(), pool.table.vals.clone()
     pool0 = pool.pool.clone()
-    anchors0 = (pool.anchors.keys.clone(), pool.anchors.vals.clone()) if pool.anchors is not None else None
+    anchors0 = pool.slot_anchor.clone() if pool.slot_anchor is not None else None
 
     def step():
         pool.lookup(tok, mask, off, dst, buf)
@@ -37,8 +37,7 @@ def test_step_replays_from_a_graph(G, kw):
         pool.table.vals.copy_(vals0)
         pool.pool.copy_(pool0)
         if anchors0 is not None:
-            pool.anchors.keys.copy_(anchors0[0])
-            pool.anchors.vals.copy_(anchors0[1])
+            pool.slot_anchor.copy_(anchors0)
         dst.copy_(G.poison_tensor(N * sh.tok_bytes))
         slot_out.fill_(-7)
 

@@ -29,13 +29,13 @@ def bf16_ordinal(bits):
     return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
 
 
-def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, anchor_capacity=None, verify=False, min_len=1,
+def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, verify=False, min_len=1,
                 recompute=None, zero_fill=False):
     """Run prefill + lookup on both sides and compare everything."""
     fl = []
     ost = OH.prefill(wl, flags_out=fl, anchor_window=anchor_window, verify=verify, recompute=recompute)
     olk = OH.lookup(ost, min_len=min_len, zero_fill=zero_fill)
-    gst = G.prefill(wl, G.make_pool(wl, anchor_window=anchor_window, anchor_capacity=anchor_capacity, verify=verify,
+    gst = G.prefill(wl, G.make_pool(wl, anchor_window=anchor_window, verify=verify,
                                     min_len=min_len, recompute_marks=recompute is not None, zero_fill=zero_fill),
                     recompute=recompute)
     glk = G.lookup(gst)

@@ -123,8 +123,7 @@ class Lifecycle:
         self.pool = cp.KVPool(shape.n_layers, shape.n_kv_heads, shape.head_dim, S, 4 * S,
                               torch.from_numpy(free.view(np.int32)), device=G.DEV,
                               pool_tensor=G.poison_tensor(S * shape.tok_bytes), verify=verify, min_len=min_len,
-                              recompute_marks=marks, zero_fill=zero_fill, lru=True, anchor_window=anchor_window,
-                              anchor_capacity=4 * S)
+                              recompute_marks=marks, zero_fill=zero_fill, lru=True, anchor_window=anchor_window)
         # oracle side
         self.W = anchor_window
         self.anchors = O.AnchorSet() if anchor_window is not None else None
@@ -177,7 +176,7 @@ class Lifecycle:
         new_keys = len({int(x) for x, g in zip(h, plain) if g == NONE and x != O.HASH_NONE})
         if new_keys > len(self.free):
             T = O.lru_threshold(self.stamps, epoch, new_keys - len(self.free))
-            freed = O.evict(self.ix, self.stamps, T, self.text, self.marks)
+            freed = O.evict(self.ix, self.stamps, T, self.text, self.marks, self.anchors)
             self.free = np.concatenate([self.free, freed])
             g_freed = self.pool.evict(new_keys - self.pool.n_free(), buf.scratch)
             assert int(G.host_u32(self.pool.threshold)[0]) == T
@@ -193,8 +192,6 @@ class Lifecycle:
         n_g = self.pool.insert(d_tok, d_mask, d_off, kv, buf.hash, sout, buf.scratch, run_off_buf=roff,
                                recompute=_u8(rec, G.DEV) if self.marks is not None else None)
         okv = OH.gen_buffer(self.seed, sh, uid0, N)
-        if self.anchors is not None:
-            O.insert_anchors(self.anchors, h, ro, self.W)
         so, n_new, fl = O.insert_kv(self.ix, h, off, self.free, okv, OH.buf_layout(sh, N), self.opool, OH.pool_layout(sh),
                                     self.slot_pos)
         self.free = self.free[n_new:]
@@ -203,6 +200,9 @@ class Lifecycle:
             so = O.text_record(self.text, tok, ro, so)
         if self.marks is not None:
             O.mark_recompute(so, rec, self.marks)
+        if self.anchors is not None:
+            O.insert_anchors(self.anchors, h, ro, so, self.W)
+            assert int(self.pool.slot_anchor.sum().item()) == len(self.anchors), epoch
         O.touch(so, epoch, self.stamps)
         assert n_g == n_new and np.array_equal(G.host_u32(sout), so), epoch
         assert np.array_equal(G.host_u32(self.pool.slot_stamp), self.stamps), epoch

@@ -56,9 +56,7 @@ def test_sensitive_token_ids_do_not_matter(G, name, scale, kw):
     assert torch.equal(la.dst, lb.dst) and torch.equal(sa.pool.pool, sb.pool.pool)
     assert np.array_equal(sa.donor_hash, sb.donor_hash) and np.array_equal(sa.donor_slot, sb.donor_slot)
     assert torch.equal(sa.pool.slot_pos, sb.pool.slot_pos)
-    for f in ("slot_tok", "slot_parent", "slot_recompute", "slot_stamp"):
+    for f in ("slot_tok", "slot_parent", "slot_recompute", "slot_stamp", "slot_anchor"):
         if getattr(sa.pool, f) is not None:
             assert torch.equal(getattr(sa.pool, f), getattr(sb.pool, f)), f
     assert np.array_equal(np.sort(G.host_u64(sa.pool.table.keys)), np.sort(G.host_u64(sb.pool.table.keys)))
-    if sa.pool.anchors is not None:
-        assert np.array_equal(np.sort(G.host_u64(sa.pool.anchors.keys)), np.sort(G.host_u64(sb.pool.anchors.keys)))

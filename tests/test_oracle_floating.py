@@ -62,7 +62,7 @@ def test_substring_key_equals_chain_hash_of_the_substring():
     off1 = np.array([0, 40], np.uint32)
     h_seg = O.hash_segments(seg, np.zeros(40, np.uint8), off1)
     anchors = O.AnchorSet()
-    O.insert_anchors(anchors, h_seg, O.run_offsets(np.zeros(40, np.uint8), off1), W)
+    O.insert_anchors(anchors, h_seg, O.run_offsets(np.zeros(40, np.uint8), off1), np.arange(40, dtype=np.uint32), W)
     assert len(anchors) == 1
     req = np.concatenate([rng.integers(0, 32000, 13).astype(np.uint32), seg, rng.integers(0, 32000, 5).astype(np.uint32)])
     m = np.zeros(len(req), np.uint8)
@@ -97,9 +97,9 @@ def test_floating_lookup_against_brute_force(seed, vocab, W):
             tok[10:50] = base_text[:40]
         h = O.hash_segments(tok, mask, off)
         ro = O.run_offsets(mask, off)
-        _, n_new, _ = O.insert_kv(ix, h, off, free[used:], _kv(len(tok)), L1(len(tok)), pool, POOL1, slot_pos)
+        so, n_new, _ = O.insert_kv(ix, h, off, free[used:], _kv(len(tok)), L1(len(tok)), pool, POOL1, slot_pos)
         used += n_new
-        O.insert_anchors(anchors, h, ro, W)
+        O.insert_anchors(anchors, h, ro, so, W)
         bp.insert(tok, mask, off)
         stored_runs += [[int(t) for t in tok[a:b]] for _, a, b in runs(tok, mask, off)]
         if vocab == 32000:

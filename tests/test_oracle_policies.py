@@ -238,23 +238,25 @@ def test_two_key_streams_keep_stored_runs_prefix_closed_under_lru(seed):
         assert closed(), ("lookup", epoch)
         new_keys = len({int(x) for x, g in zip(h, plain) if g == NONE and x != O.HASH_NONE})
         if new_keys > len(free):
-            freed = O.evict(ix, stamps, O.lru_threshold(stamps, epoch, new_keys - len(free)), text)
+            freed = O.evict(ix, stamps, O.lru_threshold(stamps, epoch, new_keys - len(free)), text, anchors=anchors)
             gone = set(freed.tolist())
             live = {t: s for t, s in live.items() if s not in gone}
             free = np.concatenate([free, freed])
             assert closed(), ("eviction", epoch)
+            assert len(anchors) == sum(1 for t in live if len(t) == W)  # prefix hashes go with their runs
         kv = np.zeros((1, 2, len(tok), 8), np.uint16)
         lay = O.Layout(1, 1, 8, 16, 2 * len(tok) * 16, len(tok) * 16)
-        O.insert_anchors(anchors, h, ro, W)
         so, n_new, _ = O.insert_kv(ix, h, off, free, kv, lay, pool, O.Layout(1, 1, 8, 32, 32, 16), slot_pos)
         fresh, free = set(free[:n_new].tolist()), free[n_new:]
         so = O.text_record(text, tok, ro, so)
+        O.insert_anchors(anchors, h, ro, so, W)
         for _, a, b in runs(tok, mask, off):
             for i in range(a, b):
                 if so[i] != NONE and int(so[i]) in fresh:
                     live[tuple(int(t) for t in tok[a:i + 1])] = int(so[i])
         O.touch(so, epoch, stamps)
         assert closed(), ("insert", epoch)
+        assert len(anchors) == sum(1 for t in live if len(t) == W)  # one prefix hash per stored run of >= W tokens
         # everything the batch just stored or found is found again, whole
         again = O.verify(text, tok, ro, O.probe(ix, h))
         assert np.array_equal(again != NONE, so != NONE), epoch

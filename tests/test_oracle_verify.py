@@ -190,7 +190,7 @@ def test_floating_segments_are_verified_from_their_anchor():
     seg = rng.integers(0, 32000, 30).astype(np.uint32)
     z, off = np.zeros(30, np.uint8), np.array([0, 30], np.uint32)
     so = P.insert(seg, z, off)
-    O.insert_anchors(anchors, O.hash_segments(seg, z, off), O.run_offsets(z, off), W)
+    O.insert_anchors(anchors, O.hash_segments(seg, z, off), O.run_offsets(z, off), so, W)
     req = np.concatenate([rng.integers(0, 32000, 7).astype(np.uint32), seg[:20], [123456], seg[21:]]).astype(np.uint32)
     m, roff = np.zeros(len(req), np.uint8), np.array([0, len(req)], np.uint32)
     h = O.hash_segments(req, m, roff)
