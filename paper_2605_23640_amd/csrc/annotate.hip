@@ -12,13 +12,13 @@
 //
 // Step 1 (cp_sat_build), three sweeps over tiles of 64 rows x 128 columns that reach the diagonal or
 // lie below it, one wavefront per tile, every lane owning two adjacent columns:
-//   sums   per tile: the sum of every column over the tile's rows (lane-local) and of every row over
-//          its columns (two values per lane, then one wave scan)
-//   carry  exclusive scans of those sums over the tile rows / tile columns, then a running sum of the
-//          "left of this tile column" row sums down all rows
+//   sums   per tile: the sum of every column over the tile's rows (lane-local), the running sum of the
+//          row totals down the tile's rows (eight rows are reduced over the lanes together, see
+//          sum8_over_lanes) and the tile's total
+//   carry  exclusive scans of the three over the tile rows / tile columns / tile rows
 //   apply  per tile and row: prefix over the lane's two columns, one wave scan across lanes, running
 //          sum down the rows, + what lies above the tile in its columns + what lies left of it in
-//          rows <= i
+//          rows <= i (left of it in the tile's own rows + the totals of the tiles above those)
 // Wave scans are DPP moves (no LDS).  When the row strides allow it a lane reads its two weights as
 // one 8-byte vector and stores its two table entries as one 16-byte vector, so that a wavefront's
 // store is one contiguous KiB.  Loads of the next eight rows are issued before the current eight
@@ -81,6 +81,39 @@ __device__ __forceinline__ int64_t readlane_i64(int64_t v, uint32_t lane) {  // 
   return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// a + b with the halves of the wavefront (HALF = 32) or the odd and even rows of 16 lanes (HALF = 16)
+// exchanged first: lanes whose bit HALF is clear get a[lane] + a[lane ^ HALF], the others
+// b[lane] + b[lane ^ HALF].  One swap instruction per 32-bit half, no select.
+template <int HALF>
+__device__ __forceinline__ int64_t swap_add(int64_t a, int64_t b) {
+  const uint32_t alo = (uint32_t)a, ahi = (uint32_t)((uint64_t)a >> 32);
+  const uint32_t blo = (uint32_t)b, bhi = (uint32_t)((uint64_t)b >> 32);
+  const auto lo = HALF == 32 ? __builtin_amdgcn_permlane32_swap(alo, blo, false, false)
+                             : __builtin_amdgcn_permlane16_swap(alo, blo, false, false);
+  const auto hi = HALF == 32 ? __builtin_amdgcn_permlane32_swap(ahi, bhi, false, false)
+                             : __builtin_amdgcn_permlane16_swap(ahi, bhi, false, false);
+  return (int64_t)(((uint64_t)hi[0] << 32) | lo[0]) + (int64_t)(((uint64_t)hi[1] << 32) | lo[1]);
+}
+// Eight sums over the 64 lanes at once: returns, in every lane L, the sum of v[L >> 3] over all lanes.
+// Each exchange halves the number of values a lane still carries (8 -> 4 -> 2 -> 1), then three
+// more steps add up the eight lanes that hold parts of the same sum: 10 exchanges instead of 48.
+__device__ __forceinline__ int64_t sum8_over_lanes(const int64_t v[8]) {
+  int64_t w[4], x[2];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) w[u] = swap_add<32>(v[u], v[u + 4]);  // lane bit 5 picks v[u] or v[u + 4]
+#pragma unroll
+  for (int u = 0; u < 2; ++u) x[u] = swap_add<16>(w[u], w[u + 2]);  // lane bit 4
+  const bool up = (threadIdx.x & 8) != 0;                           // lane bit 3
+  const int64_t keep = up ? x[1] : x[0], send = up ? x[0] : x[1];
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)send, 0x128, 0xF, 0xF, false);  // row_ror:8 = lane ^ 8
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((uint64_t)send >> 32), 0x128, 0xF, 0xF, false);
+  int64_t y = keep + (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+  y = dpp_add<0xB1, 0xF>(y);   // quad_perm [1,0,3,2]: lane ^ 1
+  y = dpp_add<0x4E, 0xF>(y);   // quad_perm [2,3,0,1]: lane ^ 2
+  y = dpp_add<0x141, 0xF>(y);  // row_half_mirror: the other quad of the same eight lanes
+  return y;
+}
+
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef long long i64x2 __attribute__((ext_vector_type(2)));
 
@@ -119,56 +152,70 @@ __device__ __forceinline__ void quantise2(f32x2 v, uint32_t r, uint32_t c, int64
   q[0] = quantise(v.x, i, c), q[1] = quantise(v.y, i, c + 1);
 }
 
+// col[0..1]: this lane's two column sums over the tile's rows.  Returns in lane k the sum of the tile's
+// rows 0..k (all columns); lane 63 thus holds the tile's total.
 template <bool VEC, bool INTERIOR>
-__device__ __forceinline__ void tile_sums(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
-                                          uint32_t c, int64_t *__restrict__ rowsum_tile, int64_t col[2]) {
+__device__ __forceinline__ int64_t tile_sums(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
+                                             uint32_t c, int64_t col[2]) {
+  static_assert(kRowGroup == 8, "sum8_over_lanes reduces eight rows at a time");
   const float *p = attn + (uint64_t)r0 * ld + c;
   f32x2 cur[kRowGroup], nxt[kRowGroup];
   load_group<VEC, INTERIOR>(p, ld, n, r0, c, cur);
+  int64_t running = 0, mine = 0;  // running: the same in every lane
 #pragma unroll 1
   for (uint32_t g = 0; g < kTile / kRowGroup; ++g) {
     p += (uint64_t)kRowGroup * ld;
     if (g + 1 < kTile / kRowGroup) load_group<VEC, INTERIOR>(p, ld, n, r0 + (g + 1) * kRowGroup, c, nxt);
+    int64_t part[kRowGroup];
 #pragma unroll
     for (int u = 0; u < kRowGroup; ++u) {
-      const uint32_t k = g * kRowGroup + u;
       int64_t q[2];
-      quantise2<INTERIOR>(cur[u], r0 + k, c, q);
+      quantise2<INTERIOR>(cur[u], r0 + g * kRowGroup + u, c, q);
       col[0] += q[0], col[1] += q[1];
-      const int64_t row = wave_inclusive_sum(q[0] + q[1]);
-      if (threadIdx.x == kWave - 1) rowsum_tile[k] = row;
+      part[u] = q[0] + q[1];
+    }
+    const int64_t rows = sum8_over_lanes(part);  // lanes 8u .. 8u+7: the total of row u of this group
+#pragma unroll
+    for (int u = 0; u < kRowGroup; ++u) {
+      running += readlane_i64(rows, 8 * u);
+      if (threadIdx.x == g * kRowGroup + u) mine = running;
     }
 #pragma unroll
     for (int u = 0; u < kRowGroup; ++u) cur[u] = nxt[u];
   }
+  return mine;
 }
 
-// colsum[I][c]: sum of column c over the 64 rows of tile row I (width n_pad_c);  rowsum[J][r]: sum of
-// row r over the 128 columns of tile column J (width n_pad_r).
+// colsum[I][c]: sum of column c over the 64 rows of tile row I (width n_pad_c);  rowrun[J][r]: sum of
+// the rows r0..r of r's tile row over the 128 columns of tile column J (width n_pad_r);
+// tilesum[I][J]: the tile's total (width n_j).
 template <bool VEC>
 __global__ __launch_bounds__(64) void sat_tile_sums_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
                                                            uint32_t n_pad_c, uint32_t n_pad_r,
-                                                           int64_t *__restrict__ colsum, int64_t *__restrict__ rowsum) {
+                                                           int64_t *__restrict__ colsum, int64_t *__restrict__ rowrun,
+                                                           int64_t *__restrict__ tilesum) {
   const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
   const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
   int64_t col[2] = {0, 0};
-  int64_t *rowsum_tile = rowsum + (uint64_t)J * n_pad_r + r0;
+  int64_t run = 0;  // a tile that lies above the diagonal as a whole holds no weight
   if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n) {
-    tile_sums<VEC, true>(attn, n, ld, r0, c, rowsum_tile, col);
+    run = tile_sums<VEC, true>(attn, n, ld, r0, c, col);
   } else if (c0 <= r0 + kTile - 1) {
-    tile_sums<VEC, false>(attn, n, ld, r0, c, rowsum_tile, col);
-  } else {  // the whole tile lies above the diagonal and holds no weight
-    rowsum_tile[lane] = 0;
+    run = tile_sums<VEC, false>(attn, n, ld, r0, c, col);
   }
+  rowrun[(uint64_t)J * n_pad_r + r0 + lane] = run;
+  if (lane == kWave - 1) tilesum[(uint64_t)I * gridDim.x + J] = run;
   colsum[(uint64_t)I * n_pad_c + c] = col[0];
   colsum[(uint64_t)I * n_pad_c + c + 1] = col[1];
 }
 
-// In place, for both arrays (blockIdx.y picks one): a[k][x] <- sum of a[k'][x] over k' < k   (x < width, k < n_k).
+// In place, for three arrays (blockIdx.y picks one): a[k][x] <- sum of a[k'][x] over k' < k   (x < width, k < n_k).
 __global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a0, uint32_t n_k0, uint32_t width0,
-                                                                      int64_t *a1, uint32_t n_k1, uint32_t width1) {
-  int64_t *a = blockIdx.y ? a1 : a0;
-  const uint32_t n_k = blockIdx.y ? n_k1 : n_k0, n_pad = blockIdx.y ? width1 : width0;
+                                                                      int64_t *a1, uint32_t n_k1, uint32_t width1,
+                                                                      int64_t *a2, uint32_t n_k2, uint32_t width2) {
+  int64_t *a = blockIdx.y == 0 ? a0 : blockIdx.y == 1 ? a1 : a2;
+  const uint32_t n_k = blockIdx.y == 0 ? n_k0 : blockIdx.y == 1 ? n_k1 : n_k2;
+  const uint32_t n_pad = blockIdx.y == 0 ? width0 : blockIdx.y == 1 ? width1 : width2;
   const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
   if (x >= n_pad) return;
   int64_t run = 0;
@@ -189,22 +236,6 @@ __global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a
     run += v;
   }
 }
-
-// In place, for every tile column J: left[J][r] <- sum of left[J][r'] over r' <= r (element e = J * n_pad + r).
-struct RunningRowsOp {
-  struct T {
-    int64_t v;
-    uint32_t reset, pad;
-  };
-  int64_t *a;
-  uint32_t n_pad, total;
-  static __device__ __forceinline__ T identity() { return T{0, 0u, 0u}; }
-  static __device__ __forceinline__ T combine(T f, T g) { return g.reset ? g : T{f.v + g.v, f.reset, 0u}; }
-  __device__ __forceinline__ uint32_t count() const { return total; }
-  __device__ __forceinline__ T load(uint32_t e) const { return T{a[e], (e % n_pad) == 0 ? 1u : 0u, 0u}; }
-  __device__ __forceinline__ void store(uint32_t e, T, T incl) const { a[e] = incl.v; }
-  __device__ __forceinline__ void finish(T) const {}
-};
 
 template <bool VEC_LD, bool VEC_ST, bool INTERIOR>
 __device__ __forceinline__ void tile_apply(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
@@ -250,7 +281,9 @@ template <bool VEC_LD, bool VEC_ST>
 __global__ __launch_bounds__(64) void sat_apply_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
                                                        uint32_t n_pad_c, uint32_t n_pad_r,
                                                        const int64_t *__restrict__ above,
-                                                       const int64_t *__restrict__ left, int64_t *__restrict__ T) {
+                                                       const int64_t *__restrict__ left,
+                                                       const int64_t *__restrict__ tiles_above,
+                                                       int64_t *__restrict__ T) {
   const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
   const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
   if (c0 > r0 + kTile - 1) return;  // above the diagonal: not written
@@ -262,8 +295,13 @@ __global__ __launch_bounds__(64) void sat_apply_kernel(const float *__restrict__
     const int64_t before = wave_inclusive_sum(above_pref[1]) - above_pref[1];  // the lanes to the left
     above_pref[0] += before, above_pref[1] += before;
   }
-  // everything left of the tile in rows <= r0 + lane
-  const int64_t left_row = left[(uint64_t)J * n_pad_r + r0 + lane];
+  // everything left of the tile in rows <= r0 + lane: in the tile's own rows, plus the tiles above those
+  int64_t left_row = left[(uint64_t)J * n_pad_r + r0 + lane];
+  {
+    int64_t part = 0;  // tiles_above[I][j]: total of the tiles (I', j), I' < I
+    for (uint32_t j = lane; j < J; j += kWave) part += tiles_above[(uint64_t)I * gridDim.x + j];
+    left_row += readlane_i64(wave_inclusive_sum(part), kWave - 1);
+  }
   if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n)
     tile_apply<VEC_LD, VEC_ST, true>(attn, n, ld, r0, c, above_pref, left_row, T);
   else
@@ -484,8 +522,8 @@ extern "C" size_t cp_sat_scratch_bytes(uint32_t n) {
   using namespace cp;
   const uint64_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
   const uint64_t cols = n_i * (n_j * kTileC), rows = n_j * (n_i * kTile);
-  // column sums per tile row, row sums per tile column, scan totals, per-token arrays of cp_annotate
-  return (size_t)((cols + rows) * 8 + (rows / kScanTile + 2) * 16 + 64ull * n + 16 * 256);
+  // column sums per tile row, running row sums per tile column, tile totals, per-token arrays of cp_annotate
+  return (size_t)((cols + rows + n_i * n_j) * 8 + 64ull * n + 16 * 256);
 }
 
 extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
@@ -502,27 +540,28 @@ extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, ui
   Scratch sc(scratch, scratch_bytes);
   int64_t *colsum = sc.take<int64_t>((size_t)n_i * n_pad_c);
   int64_t *rowsum = sc.take<int64_t>((size_t)n_j * n_pad_r);
-  RunningRowsOp::T *agg = sc.take<RunningRowsOp::T>(div_up((uint64_t)n_j * n_pad_r, kScanTile) + 1);
-  if (!colsum || !rowsum || !agg) return CP_ERR_SCRATCH;
-  if ((uint64_t)n_j * n_pad_r >= 0x80000000ull) return CP_ERR_UNSUPPORTED;
+  int64_t *tilesum = sc.take<int64_t>((size_t)n_i * n_j);
+  if (!colsum || !rowsum || !tilesum) return CP_ERR_SCRATCH;
   const bool vec_ld = ld % 2 == 0 && aligned(attn, 8);  // every (row, column pair) starts on 8 bytes
   const bool vec_st = n % 2 == 0 && aligned(T, 16);
   const dim3 tiles(n_j, n_i);
-  if (vec_ld) sat_tile_sums_kernel<true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum);
-  else sat_tile_sums_kernel<false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum);
-  const uint32_t widest = n_pad_c > n_pad_r ? n_pad_c : n_pad_r;
-  sat_exclusive_over_tiles_kernel<<<dim3(div_up(widest, 64), 2), 64, 0, stream>>>(colsum, n_i, n_pad_c, rowsum, n_j,
-                                                                                  n_pad_r);
-  RunningRowsOp op{rowsum, n_pad_r, n_j * n_pad_r};
-  if (int32_t rc = run_scan<RunningRowsOp>(stream, op, n_j * n_pad_r, agg)) return rc;
-  if (vec_ld && vec_st)
-    sat_apply_kernel<true, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
-  else if (vec_ld)
-    sat_apply_kernel<true, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
-  else if (vec_st)
-    sat_apply_kernel<false, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
+  if (vec_ld)
+    sat_tile_sums_kernel<true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum);
   else
-    sat_apply_kernel<false, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, T);
+    sat_tile_sums_kernel<false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum);
+  // above the tile (column sums over the tile rows before), left of it in its own rows (running row sums
+  // over the tile columns before), and the totals of the tiles above each tile
+  const uint32_t widest = n_pad_c > n_pad_r ? n_pad_c : n_pad_r;
+  sat_exclusive_over_tiles_kernel<<<dim3(div_up(widest, 64), 3), 64, 0, stream>>>(
+      colsum, n_i, n_pad_c, rowsum, n_j, n_pad_r, tilesum, n_i, n_j);
+  if (vec_ld && vec_st)
+    sat_apply_kernel<true, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+  else if (vec_ld)
+    sat_apply_kernel<true, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+  else if (vec_st)
+    sat_apply_kernel<false, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+  else
+    sat_apply_kernel<false, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
   return check_launch();
 }
 

@@ -63,6 +63,34 @@ def test_annotator_full_size(G):
     assert bl[0] != X
 
 
+def test_annotator_table_beyond_4_gib(G):
+    """n = 24,000: the table holds 4.6 GB, byte offsets no longer fit 32 bits; compared in row blocks."""
+    from paper_2605_23640_amd import binding as B
+    n = 24000
+    a = AT.make_attention(n, seed=3)
+    mask = AT.make_mask(n, seed=4, run_mean=8.0, cover=0.01)
+    d_a = torch.from_numpy(a).to(G.DEV)
+    T = torch.empty((n, n), dtype=torch.int64, device=G.DEV)
+    scratch = B.new_sat_scratch(n, G.DEV)
+    B.cp_sat_build(d_a, T, scratch)
+    i32 = lambda: torch.empty(n, dtype=torch.int32, device=G.DEV)  # noqa: E731
+    u8 = lambda: torch.empty(n, dtype=torch.uint8, device=G.DEV)  # noqa: E731
+    bl, br, bs, reus, rec, sm = i32(), i32(), torch.empty(n, dtype=torch.int64, device=G.DEV), u8(), u8(), u8()
+    B.cp_annotate(T, torch.from_numpy(mask).to(G.DEV), 128, 25, bl, br, bs, reus, rec, sm, scratch)
+    torch.cuda.synchronize()
+    oT = O.sat_build(a)
+    cols = np.arange(n)[None, :]
+    for r0 in range(0, n, 2000):
+        rows = np.arange(r0, r0 + 2000)[:, None]
+        g, w = T[r0:r0 + 2000].cpu().numpy(), oT[r0:r0 + 2000]
+        assert not ((g != w) & (cols <= rows)).any(), r0
+    want = O.annotate(oT, mask, 128, 25)
+    got = (G.host_u32(bl), G.host_u32(br), bs.cpu().numpy(), reus.cpu().numpy(), rec.cpu().numpy())
+    for g, w, name in zip(got, want, ("best_l", "best_r", "best_score", "reusable", "recompute")):
+        assert np.array_equal(g, w), name
+    assert want[3].sum() > 0.8 * n
+
+
 def test_annotator_edge_inputs(G):
     n = 130
     z = np.zeros(n, np.uint8)
