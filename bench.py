@@ -37,8 +37,10 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # command, scaled by what the same counters read for kernels of known size
 # (profiles/gather_rows_kernel_<workload>.txt); None for workloads not profiled that way.
 MEASURED_TRAFFIC = {"llama3-8b": 9038385933, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
-                    "annotator-10000": 924620701}
+                    "annotator-10000": 924614651}
 # (the float workload was profiled with all added rows on: profiles/gather_rows_kernel_float_all_rows.txt)
+# the read part of the same measurements (FETCH_SIZE, scaled)
+MEASURED_FETCH = {"llama3-8b": 3098945050, "rope": 2762280080, "llama3-70b": 25303251909, "frag": 7420215123}
 
 
 def log(*a):
@@ -361,6 +363,8 @@ def main():
         copy_gbps = 5 * 2.0 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del a, b
 
+    # the stored counter readings belong to the gather of the default options
+    same_gather = args.anchor_window is None and args.min_len <= 1 and args.recompute == 0
     out = {
         "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
         "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -395,7 +399,11 @@ def main():
         "roofline": {
             "kernel": "gather_rows_kernel (cp_gather_kv)", "bound": "hbm", "achieved": gather_gbps,
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC.get(wl.name),
+            "traffic": MEASURED_TRAFFIC.get(wl.name) if same_gather else None,
+            # of the bytes the profiler saw the kernel fetch, the part that are pool rows some request
+            # asked for (every distinct source row once); the rest is descriptors, lists, re-fetches
+            "fetched_bytes_landing_in_output": (sh.tok_bytes * unique_src / MEASURED_FETCH[wl.name]
+                                                if wl.name in MEASURED_FETCH and same_gather else None),
         },
     }
     hev.close()

@@ -52,6 +52,16 @@ __device__ __forceinline__ int64_t quantise(float x, uint32_t i, uint32_t j) {
   return (int64_t)(__double_as_longlong(d) - __double_as_longlong(magic));
 }
 
+// The same integer plus the bit pattern of the rounding constant (kMagicBits): what the hardware addition
+// leaves behind.  Sums of these are corrected once, by the number of terms times kMagicBits, instead of
+// once per weight; a weight that counts as 0 is replaced before the conversion, so it contributes
+// exactly kMagicBits.
+constexpr uint64_t kMagicBits = 0x4338000000000000ull;  // 2^52 + 2^51 as a double
+__device__ __forceinline__ uint64_t quantise_biased(float x, uint32_t i, uint32_t j) {
+  if (j > i || !(fabsf(x) <= 262144.0f)) x = 0.0f;
+  return (uint64_t)__double_as_longlong((double)x * 4294967296.0 + 6755399441055744.0);
+}
+
 // 64-bit wave scans through DPP moves (no LDS traffic).  dpp_add adds to v the value of the lane that
 // the DPP control selects, or 0 where that lane does not exist or the row is masked off.
 template <int CTRL, int ROW_MASK>
@@ -81,36 +91,39 @@ __device__ __forceinline__ int64_t readlane_i64(int64_t v, uint32_t lane) {  // 
   return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// The sums below run modulo 2^64 on unsigned words (they carry multiples of kMagicBits that wrap).
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_move_u64(uint64_t v) {  // CTRL: a permutation inside rows, every lane has a source
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, 0xF, 0xF, false);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), CTRL, 0xF, 0xF, false);
+  return ((uint64_t)hi << 32) | lo;
+}
 // a + b with the halves of the wavefront (HALF = 32) or the odd and even rows of 16 lanes (HALF = 16)
 // exchanged first: lanes whose bit HALF is clear get a[lane] + a[lane ^ HALF], the others
 // b[lane] + b[lane ^ HALF].  One swap instruction per 32-bit half, no select.
 template <int HALF>
-__device__ __forceinline__ int64_t swap_add(int64_t a, int64_t b) {
-  const uint32_t alo = (uint32_t)a, ahi = (uint32_t)((uint64_t)a >> 32);
-  const uint32_t blo = (uint32_t)b, bhi = (uint32_t)((uint64_t)b >> 32);
+__device__ __forceinline__ uint64_t swap_add(uint64_t a, uint64_t b) {
+  const uint32_t alo = (uint32_t)a, ahi = (uint32_t)(a >> 32), blo = (uint32_t)b, bhi = (uint32_t)(b >> 32);
   const auto lo = HALF == 32 ? __builtin_amdgcn_permlane32_swap(alo, blo, false, false)
                              : __builtin_amdgcn_permlane16_swap(alo, blo, false, false);
   const auto hi = HALF == 32 ? __builtin_amdgcn_permlane32_swap(ahi, bhi, false, false)
                              : __builtin_amdgcn_permlane16_swap(ahi, bhi, false, false);
-  return (int64_t)(((uint64_t)hi[0] << 32) | lo[0]) + (int64_t)(((uint64_t)hi[1] << 32) | lo[1]);
+  return (((uint64_t)hi[0] << 32) | lo[0]) + (((uint64_t)hi[1] << 32) | lo[1]);
 }
 // Eight sums over the 64 lanes at once: returns, in every lane L, the sum of v[L >> 3] over all lanes.
 // Each exchange halves the number of values a lane still carries (8 -> 4 -> 2 -> 1), then three
 // more steps add up the eight lanes that hold parts of the same sum: 10 exchanges instead of 48.
-__device__ __forceinline__ int64_t sum8_over_lanes(const int64_t v[8]) {
-  int64_t w[4], x[2];
+__device__ __forceinline__ uint64_t sum8_over_lanes(const uint64_t v[8]) {
+  uint64_t w[4], x[2];
 #pragma unroll
   for (int u = 0; u < 4; ++u) w[u] = swap_add<32>(v[u], v[u + 4]);  // lane bit 5 picks v[u] or v[u + 4]
 #pragma unroll
   for (int u = 0; u < 2; ++u) x[u] = swap_add<16>(w[u], w[u + 2]);  // lane bit 4
   const bool up = (threadIdx.x & 8) != 0;                           // lane bit 3
-  const int64_t keep = up ? x[1] : x[0], send = up ? x[0] : x[1];
-  const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)send, 0x128, 0xF, 0xF, false);  // row_ror:8 = lane ^ 8
-  const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((uint64_t)send >> 32), 0x128, 0xF, 0xF, false);
-  int64_t y = keep + (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
-  y = dpp_add<0xB1, 0xF>(y);   // quad_perm [1,0,3,2]: lane ^ 1
-  y = dpp_add<0x4E, 0xF>(y);   // quad_perm [2,3,0,1]: lane ^ 2
-  y = dpp_add<0x141, 0xF>(y);  // row_half_mirror: the other quad of the same eight lanes
+  uint64_t y = (up ? x[1] : x[0]) + dpp_move_u64<0x128>(up ? x[0] : x[1]);  // row_ror:8 = lane ^ 8
+  y += dpp_move_u64<0xB1>(y);   // quad_perm [1,0,3,2]: lane ^ 1
+  y += dpp_move_u64<0x4E>(y);   // quad_perm [2,3,0,1]: lane ^ 2
+  y += dpp_move_u64<0x141>(y);  // row_half_mirror: the other quad of the same eight lanes
   return y;
 }
 
@@ -161,29 +174,31 @@ __device__ __forceinline__ int64_t tile_sums(const float *__restrict__ attn, uin
   const float *p = attn + (uint64_t)r0 * ld + c;
   f32x2 cur[kRowGroup], nxt[kRowGroup];
   load_group<VEC, INTERIOR>(p, ld, n, r0, c, cur);
-  int64_t running = 0, mine = 0;  // running: the same in every lane
+  // every sum here carries kMagicBits per weight (modulo 2^64), taken off where the sum is complete
+  uint64_t col0 = 0, col1 = 0, running = 0, mine = 0;  // running: the same in every lane
 #pragma unroll 1
   for (uint32_t g = 0; g < kTile / kRowGroup; ++g) {
     p += (uint64_t)kRowGroup * ld;
     if (g + 1 < kTile / kRowGroup) load_group<VEC, INTERIOR>(p, ld, n, r0 + (g + 1) * kRowGroup, c, nxt);
-    int64_t part[kRowGroup];
+    uint64_t part[kRowGroup];
 #pragma unroll
     for (int u = 0; u < kRowGroup; ++u) {
-      int64_t q[2];
-      quantise2<INTERIOR>(cur[u], r0 + g * kRowGroup + u, c, q);
-      col[0] += q[0], col[1] += q[1];
-      part[u] = q[0] + q[1];
+      const uint32_t i = INTERIOR ? 0xFFFFFFFFu : r0 + g * kRowGroup + u;
+      const uint64_t q0 = quantise_biased(cur[u].x, i, c), q1 = quantise_biased(cur[u].y, i, c + 1);
+      col0 += q0, col1 += q1;
+      part[u] = q0 + q1;
     }
-    const int64_t rows = sum8_over_lanes(part);  // lanes 8u .. 8u+7: the total of row u of this group
+    const uint64_t rows = sum8_over_lanes(part);  // lanes 8u .. 8u+7: the total of row u of this group
 #pragma unroll
     for (int u = 0; u < kRowGroup; ++u) {
-      running += readlane_i64(rows, 8 * u);
+      running += (uint64_t)readlane_i64((int64_t)rows, 8 * u) - (uint64_t)kTileC * kMagicBits;
       if (threadIdx.x == g * kRowGroup + u) mine = running;
     }
 #pragma unroll
     for (int u = 0; u < kRowGroup; ++u) cur[u] = nxt[u];
   }
-  return mine;
+  col[0] = (int64_t)(col0 - (uint64_t)kTile * kMagicBits), col[1] = (int64_t)(col1 - (uint64_t)kTile * kMagicBits);
+  return (int64_t)mine;
 }
 
 // colsum[I][c]: sum of column c over the 64 rows of tile row I (width n_pad_c);  rowrun[J][r]: sum of
