@@ -27,9 +27,9 @@
 //
 // Step 2 (cp_annotate): score(l, r) = Intra - Inter = T[r,r] - T[l-1,r] - 2 T[r,l-1] + 2 T[l-1,l-1]
 // = T[r,r] + T[l-1,l-1] - 2 T[r,l-1]  (T[l-1,r] = T[l-1,l-1], see above).  A workgroup takes a 64 x 64
-// block of the (l, r) triangle: lanes along r, T[r, l-1] through a transposing LDS tile.  First sweep:
-// maximum score per segment (64-bit atomic max); second sweep: smallest (l, r) among the candidates
-// that reach it (64-bit atomic min).
+// block of the (l, r) triangle: lanes along r, T[r, l-1] through a transposing LDS tile, and keeps for
+// every r the best (score, smallest l).  Two small passes over the tokens then find every segment's
+// maximum score (64-bit atomic max) and the smallest (l, r) among the r that reach it (atomic min).
 #include "cp_device.h"
 #include "cp_internal.h"
 
@@ -357,18 +357,21 @@ __global__ __launch_bounds__(256) void annotate_init_kernel(const int64_t *__res
 
 // Candidates (l, r) are visited in 64 x 64 blocks: l in [lt*64, +64), r in [rt*64, +64), lt <= rt.
 // Workgroup (rt, y) takes the blocks lt = first, first + kSearchSplit, ... <= rt of its r tile, where
-// first is the tile of the earliest segment start among the tile's r (no candidate lies left of it).
-// pass 0: best_u[seg] = max biased score; pass 1: best_lr[seg] = min packed (l, r) among the maxima.
+// first is the tile of the earliest segment start among the tile's r (no candidate lies left of it),
+// and leaves, for every r of the tile, the best (score, l) it saw: part_u[y][r] = biased score
+// (0 = no candidate), part_l[y][r] = the smallest l that reaches it.
 constexpr uint32_t kSearchSplit = 8;
 __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__restrict__ T, uint32_t n,
                                                               const int64_t *__restrict__ diag,
                                                               const uint32_t *__restrict__ seg_a,
                                                               const uint32_t *__restrict__ tile_min_a, uint32_t min_len,
-                                                              int pass, uint64_t *best_u, uint64_t *best_lr) {
+                                                              uint64_t *__restrict__ part_u,
+                                                              uint32_t *__restrict__ part_l) {
   const uint32_t rt = blockIdx.x;
-  const uint32_t min_a = tile_min_a[rt];
-  if (min_a == kNone) return;  // every token of this tile is sensitive
+  const uint32_t min_a = tile_min_a[rt];  // kNone: every token of this tile is sensitive
   __shared__ int64_t colT[kTile][kTile + 1];  // colT[r'][l'] = T[r0 + r'][l0 + l' - 1]
+  __shared__ uint64_t group_u[4][kTile];
+  __shared__ uint32_t group_l[4][kTile];
   const uint32_t r0 = rt * kTile;
   const uint32_t rl = threadIdx.x & (kTile - 1), grp = threadIdx.x / kTile;  // lane along r; 4 groups of 16 l's
   const uint32_t r = r0 + rl;
@@ -377,7 +380,8 @@ __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__r
   bool have = false;
   int64_t best = 0;
   uint32_t best_l = 0;
-  for (uint32_t lt = min_a / kTile + blockIdx.y; lt <= rt; lt += kSearchSplit) {  // ascending l
+  const uint32_t lt_first = min_a == kNone ? rt + 1 : min_a / kTile + blockIdx.y;
+  for (uint32_t lt = lt_first; lt <= rt; lt += kSearchSplit) {  // ascending l
     const uint32_t l0 = lt * kTile;
     __syncthreads();  // the previous block's tile is no longer read
     // stage T[r][l-1] for the block: rows r0.., columns l0-1 .. l0+62 (all at or left of the diagonal tile)
@@ -401,37 +405,73 @@ __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__r
       }
     }
   }
-  // One atomic per wavefront where all its lanes look at the same segment (the usual case), else one per lane.
-  const uint32_t a_first = __builtin_amdgcn_readfirstlane(a_r);
-  const bool one_segment = __all(a_r == a_first) && a_first != kNone;
-  if (pass == 0) {
-    uint64_t u = have ? (uint64_t)best ^ kBias : 0;  // 0: below every biased score
-    if (one_segment) {
+  // the four groups looked at different l for the same r: the larger score wins, then the smaller l
+  group_u[grp][rl] = have ? (uint64_t)best ^ kBias : 0;
+  group_l[grp][rl] = best_l;
+  __syncthreads();
+  if (grp == 0 && r < n) {
+    uint64_t u = group_u[0][rl];
+    uint32_t l = group_l[0][rl];
 #pragma unroll
-      for (int m = 1; m < kWave; m <<= 1) {
-        const uint64_t o = shfl_xor_u64(u, m);
-        u = o > u ? o : u;
-      }
-      if ((threadIdx.x & (kWave - 1)) == 0 && u != 0 && best_u[a_first] < u)
-        atomicMax((unsigned long long *)&best_u[a_first], (unsigned long long)u);
-    } else if (have && best_u[a_r] < u) {
-      atomicMax((unsigned long long *)&best_u[a_r], (unsigned long long)u);
+    for (int g = 1; g < 4; ++g) {
+      const uint64_t ug = group_u[g][rl];
+      const uint32_t lg = group_l[g][rl];
+      if (ug > u || (ug == u && ug != 0 && lg < l)) u = ug, l = lg;
     }
-  } else {
-    const bool top = have && ((uint64_t)best ^ kBias) == best_u[a_r];
-    uint64_t lr = top ? (((uint64_t)best_l << 32) | r) : ~0ull;  // ~0: above every packed (l, r)
-    if (one_segment) {
-#pragma unroll
-      for (int m = 1; m < kWave; m <<= 1) {
-        const uint64_t o = shfl_xor_u64(lr, m);
-        lr = o < lr ? o : lr;
-      }
-      if ((threadIdx.x & (kWave - 1)) == 0 && lr != ~0ull)
-        atomicMin((unsigned long long *)&best_lr[a_first], (unsigned long long)lr);
-    } else if (top) {
-      atomicMin((unsigned long long *)&best_lr[a_r], (unsigned long long)lr);
-    }
+    part_u[(uint64_t)blockIdx.y * n + r] = u;
+    part_l[(uint64_t)blockIdx.y * n + r] = l;
   }
+}
+
+// Per r: the best (score, l) over the kSearchSplit parts; the maximum score of r's segment (atomic max).
+__global__ __launch_bounds__(256) void annotate_best_score_kernel(uint32_t n, const uint32_t *__restrict__ seg_a,
+                                                                  const uint64_t *__restrict__ part_u,
+                                                                  const uint32_t *__restrict__ part_l,
+                                                                  uint64_t *__restrict__ cand_u,
+                                                                  uint32_t *__restrict__ cand_l, uint64_t *best_u) {
+  const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;  // no lane leaves early: the wavefront reduces together
+  uint64_t u = 0;
+  uint32_t a = kNone;
+  if (r < n) {
+    u = part_u[r];
+    uint32_t l = part_l[r];
+#pragma unroll
+    for (uint32_t y = 1; y < kSearchSplit; ++y) {
+      const uint64_t uy = part_u[(uint64_t)y * n + r];
+      const uint32_t ly = part_l[(uint64_t)y * n + r];
+      if (uy > u || (uy == u && uy != 0 && ly < l)) u = uy, l = ly;
+    }
+    cand_u[r] = u;
+    cand_l[r] = l;
+    a = seg_a[r];
+  }
+  if (a == kNone) u = 0;  // sensitive or past the end: nothing to report
+  // One atomic per wavefront where all lanes that have a segment have the same one (the usual case), else one per lane.
+  const unsigned long long with_segment = __ballot(a != kNone);
+  if (with_segment == 0) return;  // the same for the whole wavefront
+  const uint32_t a_ref = __builtin_amdgcn_readlane(a, __ffsll(with_segment) - 1);
+  if (__all(a == kNone || a == a_ref)) {
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+      const uint64_t o = shfl_xor_u64(u, m);
+      u = o > u ? o : u;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0 && u != 0 && best_u[a_ref] < u)
+      atomicMax((unsigned long long *)&best_u[a_ref], (unsigned long long)u);
+  } else if (u != 0 && best_u[a] < u) {
+    atomicMax((unsigned long long *)&best_u[a], (unsigned long long)u);
+  }
+}
+// Among the r whose best score is their segment's maximum: the smallest (l, r) (atomic min).
+__global__ __launch_bounds__(256) void annotate_best_lr_kernel(uint32_t n, const uint32_t *__restrict__ seg_a,
+                                                               const uint64_t *__restrict__ cand_u,
+                                                               const uint32_t *__restrict__ cand_l,
+                                                               const uint64_t *__restrict__ best_u, uint64_t *best_lr) {
+  const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n) return;
+  const uint32_t a = seg_a[r];
+  if (a == kNone || cand_u[r] == 0 || cand_u[r] != best_u[a]) return;
+  atomicMin((unsigned long long *)&best_lr[a], (unsigned long long)(((uint64_t)cand_l[r] << 32) | r));
 }
 
 // Per token: the chosen substring of its segment, and d = inter - intra attention of its own row.
@@ -538,7 +578,7 @@ extern "C" size_t cp_sat_scratch_bytes(uint32_t n) {
   const uint64_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
   const uint64_t cols = n_i * (n_j * kTileC), rows = n_j * (n_i * kTile);
   // column sums per tile row, running row sums per tile column, tile totals, per-token arrays of cp_annotate
-  return (size_t)((cols + rows + n_i * n_j) * 8 + 64ull * n + 16 * 256);
+  return (size_t)((cols + rows + n_i * n_j) * 8 + 192ull * n + 32 * 256);
 }
 
 extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
@@ -602,13 +642,21 @@ extern "C" int32_t cp_annotate(void *stream_, const int64_t *T, uint32_t n, cons
   int64_t *d = sc.take<int64_t>(n);
   uint32_t *rank = sc.take<uint32_t>(n);
   uint32_t *tile_min_a = sc.take<uint32_t>(div_up(n, kTile));
-  if (!agg || !seg_a || !diag || !best_u || !best_lr || !d || !rank || !tile_min_a) return CP_ERR_SCRATCH;
+  uint64_t *part_u = sc.take<uint64_t>((size_t)kSearchSplit * n);
+  uint32_t *part_l = sc.take<uint32_t>((size_t)kSearchSplit * n);
+  uint64_t *cand_u = sc.take<uint64_t>(n);
+  uint32_t *cand_l = sc.take<uint32_t>(n);
+  if (!agg || !seg_a || !diag || !best_u || !best_lr || !d || !rank || !tile_min_a || !part_u || !part_l || !cand_u ||
+      !cand_l)
+    return CP_ERR_SCRATCH;
   SegStartOp so{mask, seg_a, n};
   if (int32_t rc = run_scan<SegStartOp>(stream, so, n, agg)) return rc;
   const uint32_t blocks = div_up(n, 256), n_t = div_up(n, kTile);
   annotate_init_kernel<<<blocks, 256, 0, stream>>>(T, n, seg_a, diag, best_u, best_lr, tile_min_a);
-  for (int pass = 0; pass < 2; ++pass)
-    annotate_search_kernel<<<dim3(n_t, kSearchSplit), 256, 0, stream>>>(T, n, diag, seg_a, tile_min_a, min_len, pass, best_u, best_lr);
+  annotate_search_kernel<<<dim3(n_t, kSearchSplit), 256, 0, stream>>>(T, n, diag, seg_a, tile_min_a, min_len, part_u,
+                                                                      part_l);
+  annotate_best_score_kernel<<<blocks, 256, 0, stream>>>(n, seg_a, part_u, part_l, cand_u, cand_l, best_u);
+  annotate_best_lr_kernel<<<blocks, 256, 0, stream>>>(n, seg_a, cand_u, cand_l, best_u, best_lr);
   annotate_finish_kernel<<<blocks, 256, 0, stream>>>(T, n, diag, seg_a, best_u, best_lr, best_l, best_r, best_score,
                                                      reusable, store_mask, d, rank);
   if (rho_percent)
