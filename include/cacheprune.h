@@ -347,10 +347,11 @@ int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *sta
  *     largest  IntraAttn - InterAttn = sum(rows l..r, columns l..r) - sum(rows l..r, columns < l);
  *     ties: smallest l, then smallest r.  For every token i of the segment best_l[i], best_r[i],
  *     best_score[i] describe that substring (0xFFFFFFFF, 0xFFFFFFFF, 0 for sensitive tokens and for
- *     segments shorter than min_len); reusable[i] = 1 iff best_l <= i <= best_r; store_mask (may be
- *     NULL) = 1 - reusable: the mask to hash and insert the request with, so that only the chosen
- *     substrings are stored;
- *   - the tokens of the chosen substring are ranked by (their row's weight on columns < l) - (their
+ *     segments shorter than min_len); the substring is reusable if it meets the reuse criterion of
+ *     Sec. 4.2.1, IntraAttn > InterAttn, i.e. best_score > 0: reusable[i] = 1 iff that holds and
+ *     best_l <= i <= best_r; store_mask (may be NULL) = 1 - reusable: the mask to hash and insert
+ *     the request with, so that only the chosen substrings are stored;
+ *   - the tokens of a reusable chosen substring are ranked by (their row's weight on columns < l) - (their
  *     row's weight on columns l..i), largest first, earlier token first on ties, and the first
  *     floor(len * rho_percent / 100) get recompute[i] = 1 (input of cp_mark_recompute).
  * n <= 2^20.  Scratch: cp_sat_scratch_bytes(n), 256-byte aligned, for either call. */

@@ -541,12 +541,14 @@ extern "C" void cpo_annotate(const int64_t *T, uint32_t n, const uint8_t *mask, 
           br = r;
         }
       }
-    if (found) {
+    if (found)
       for (uint32_t i = a; i <= b; ++i) {
         best_l[i] = bl;
         best_r[i] = br;
         best_score[i] = best;
       }
+    // Reuse criterion: a substring is reusable if its intra-attention exceeds its inter-attention.
+    if (found && best > 0) {
       // Step 3: rank the tokens of the chosen substring by inter - intra attention (their own row),
       // largest first, earlier token first on ties; the top rho percent are recomputed
       const uint32_t len = br - bl + 1;

@@ -205,8 +205,9 @@ uint32_t cpo_evict(cpo_index *, uint32_t *slot_stamp, uint32_t n_pool_slots, uin
  *     IntraAttn - InterAttn = sum(rows l..r, cols l..r) - sum(rows l..r, cols < l);
  *     ties: smallest l, then smallest r.  best_l / best_r / best_score are written for every token
  *     of the segment (0xFFFFFFFF, 0 if the segment is shorter than min_len or the token sensitive);
- *     reusable[i] = 1 inside the chosen substring.
- *   Step 3: tokens of the chosen substring are ranked by (their row's attention to columns < l)
+ *     reusable[i] = 1 inside the chosen substring if it meets the reuse criterion
+ *     IntraAttn > InterAttn (best_score > 0); otherwise the segment yields nothing to store.
+ *   Step 3: tokens of a chosen substring that is reusable are ranked by (their row's attention to columns < l)
  *     - (their row's attention to columns l..i), largest first, earlier token first on ties;
  *     the first floor(len * rho_percent / 100) get recompute[i] = 1. */
 void cpo_sat_build(const float *attn, uint32_t n, uint64_t ld, int64_t *T);

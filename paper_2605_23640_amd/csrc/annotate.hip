@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void annotate_finish_kernel(const int64_t *__r
     bl = (uint32_t)(best_lr[a] >> 32);
     br = (uint32_t)best_lr[a];
     score = (int64_t)(best_u[a] ^ kBias);
-    inside = bl <= i && i <= br;
+    inside = bl <= i && i <= br && score > 0;  // reuse criterion: intra-attention exceeds inter-attention
     if (inside) {
       // inter_i = T[i][bl-1] - T[i-1][bl-1];  intra_i = T[i][i] - T[i-1][i] - inter_i, T[i-1][i] = T[i-1][i-1]
       const int64_t t_i = bl ? T[(uint64_t)i * n + bl - 1] : 0;

@@ -103,9 +103,17 @@ def test_annotator_edge_inputs(G):
     m = z.copy()
     m[0] = 1
     bl, br, bs, reus, rec = check(G, first, m, 1, 0)
-    assert bl[1] == 1 and br[1] == 1
+    assert bl[1] == 1 and br[1] == 1 and not reus.any()  # the best substring fails Intra > Inter: nothing reusable
     check(G, first, m, 70, 10)  # ties over many candidates: the first window of 70 tokens
-    check(G, np.zeros((n, 132), np.float32), z, 2, 50)  # all scores tie at zero
+    bl, br, bs, reus, rec = check(G, np.zeros((n, 132), np.float32), z, 2, 50)  # all scores tie at zero
+    assert bl[0] == 0 and br[0] == 1 and not reus.any() and not rec.any()
+    both = eye.copy()  # one segment passes the criterion, the next one (attending to token 0 only) does not
+    both[70:, :] = 0
+    both[70:, 0] = 1
+    cut = z.copy()
+    cut[69] = 1
+    bl, br, bs, reus, rec = check(G, both, cut, 1, 50)
+    assert reus[:69].all() and not reus[69:].any() and bs[70] < 0
     check(G, eye, np.ones(n, np.uint8), 1, 25)  # everything sensitive
     junk = AT.make_attention(n, seed=5)
     junk[3, 1], junk[9, 2], junk[11, 4], junk[12, 5], junk[13, 6] = np.nan, np.inf, -3e9, 262144.0, 262145.0

@@ -72,6 +72,7 @@ def brute(qm, mask, min_len, rho):
         if best is not None:
             sc, l, r = best
             bl[a:b + 1], br[a:b + 1], bs[a:b + 1] = l, r, sc
+        if best is not None and best[0] > 0:  # reuse criterion: IntraAttn(l, r) > InterAttn(l, r)
             reus[l:r + 1] = 1
             d = [sum(int(qm[i, j]) for j in range(0, l)) - sum(int(qm[i, j]) for j in range(l, i + 1))
                  for i in range(l, r + 1)]
@@ -112,7 +113,8 @@ def test_annotate_closed_forms():
     m = z.copy()
     m[0] = 1
     bl, br, bs, reus, _ = O.annotate(O.sat_build(first), m, 1, 0)
-    assert bl[0] == X and bl[1] == 1 and br[1] == 1 and bs[1] == -S and list(np.flatnonzero(reus)) == [1]
+    assert bl[0] == X and bl[1] == 1 and br[1] == 1 and bs[1] == -S
+    assert not reus.any()  # ... but fails the reuse criterion (inter-attention exceeds intra-attention): nothing to store
     # the minimum length then forces the first window of that length
     bl, br, bs, _, _ = O.annotate(O.sat_build(first), m, 4, 0)
     assert bl[1] == 1 and br[1] == 4 and bs[1] == -4 * S
@@ -121,8 +123,17 @@ def test_annotate_closed_forms():
     bl, br, bs, reus, _ = O.annotate(O.sat_build(eye), m2, 3, 0)
     assert list(bl) == [X, X, X, 3, 3, 3, 3, X, X, X] and list(br[3:7]) == [6] * 4 and list(reus) == [0, 0, 0, 1, 1, 1, 1, 0, 0, 0]
     # all-zero attention: every score ties at 0, the first candidate wins
-    bl, br, bs, _, _ = O.annotate(O.sat_build(np.zeros((n, n), np.float32)), z, 2, 0)
+    bl, br, bs, reus, rec = O.annotate(O.sat_build(np.zeros((n, n), np.float32)), z, 2, 50)
     assert bl[0] == 0 and br[0] == 1 and bs[0] == 0
+    assert not reus.any() and not rec.any()  # intra-attention must exceed inter-attention, not equal it
+    # a segment is judged by its own best substring: one passes the criterion, the other does not
+    two = np.zeros((n, n), np.float32)
+    two[np.arange(4), np.arange(4)] = 1  # tokens 0..3 attend to themselves
+    two[5:, 0] = 1                       # tokens 5..9 attend to token 0, outside their segment
+    m3 = z.copy()
+    m3[4] = 1
+    bl, br, bs, reus, rec = O.annotate(O.sat_build(two), m3, 1, 50)
+    assert list(reus) == [1, 1, 1, 1, 0, 0, 0, 0, 0, 0] and bs[0] == 4 * S and bs[5] == -S and rec.sum() == 2
 
 
 def test_generator_shapes():
