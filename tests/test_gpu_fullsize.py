@@ -192,3 +192,42 @@ def test_more_than_256_scan_tiles(G):
     print(f"\n[many-tiles] {wl.n_tokens} tokens, {(olk.slot != O.SLOT_NONE).sum()} matched, "
           f"{(olk.served != O.SLOT_NONE).sum()} served, {olk.n_spans} spans", flush=True)
     assert (olk.served != O.SLOT_NONE).sum() > 100000
+
+
+@pytest.mark.parametrize("all_rows", [False, True])
+def test_pool_life_cycle_at_pool_scale(G, all_rows):
+    """The pool of the 8B configuration (262,144 slots) through twelve batches of 16 x 4096 tokens drawn from a
+    corpus larger than the pool: it fills up and least-recently-used batches are evicted several times.  Every
+    output of every batch (slots, served slots, request buffers, stamps, marks, freed lists, thresholds, free
+    list, flags) is compared with the oracle; KV rows are small so that the host can mirror the pool.
+    ``all_rows``: floating anchors, exact verification, minimum length, recompute marks and zero fill on."""
+    from test_gpu_policies import Lifecycle
+
+    rng = np.random.default_rng(0xC0FFEE0B)
+    S = 262144
+    life = Lifecycle(G, S, gen.KVShape(1, 1, 64), 0xC0FFEE0B, verify=all_rows, min_len=32 if all_rows else 1,
+                     marks=all_rows, zero_fill=all_rows, anchor_window=16 if all_rows else None)
+    prefix = rng.integers(0, gen.VOCAB, 1024).astype(np.uint32)
+    docs = [rng.integers(0, gen.VOCAB, int(rng.integers(512, 1025))).astype(np.uint32) for _ in range(450)]
+    dmask = [(rng.random(len(d)) < 0.02).astype(np.uint8) for d in docs]
+    drec = [(rng.random(len(d)) < 0.25).astype(np.uint8) for d in docs]  # marks travel with the text
+    for epoch in range(1, 13):
+        pt, pm, pr, lens = [], [], [], []
+        recent = rng.choice(450, 120, replace=False)  # this batch's working set: some documents stay hot
+        for r in range(16):
+            lead = int(rng.integers(0, 40)) if all_rows else 0  # text in front of the first document
+            t, m, c = [prefix, rng.integers(0, gen.VOCAB, lead).astype(np.uint32)], [np.zeros(1024 + lead, np.uint8)], \
+                [np.zeros(1024 + lead, np.uint8)]
+            for d in rng.choice(recent, 3, replace=False):
+                t.append(docs[d]), m.append(dmask[d]), c.append(drec[d])
+            n = sum(len(x) for x in t)
+            t.append(rng.integers(0, gen.VOCAB, 4096 - n).astype(np.uint32))
+            um = (rng.random(4096 - n) < 0.15).astype(np.uint8)
+            um[0] = 1  # the user's text starts with a sensitive token: it never extends a document's run
+            m.append(um), c.append(np.zeros(4096 - n, np.uint8))
+            pt.append(np.concatenate(t)), pm.append(np.concatenate(m)), pr.append(np.concatenate(c)), lens.append(4096)
+        tok, mask, rec = np.concatenate(pt).astype(np.uint32), np.concatenate(pm), np.concatenate(pr)
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
+        life.batch(epoch, tok, mask, off, rec)
+        print("epoch", epoch, "free", len(life.free), "evictions", life.evictions, flush=True)
+    assert life.evictions >= 2 and life.flags == 0
