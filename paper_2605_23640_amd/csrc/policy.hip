@@ -116,15 +116,39 @@ __global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, uint32_t n
   if (i < n) p[i] = 0;
 }
 
+// Histogram of slot ages, the last bin open-ended.  Right after a few large batches nearly all slots share a
+// handful of ages, so plain atomics would queue up on a few words: the lanes of a wavefront that hold the same
+// age add once, into a histogram in LDS, and every workgroup adds its non-empty bins to the global one at the end.
 __global__ __launch_bounds__(256) void age_histogram_kernel(const uint32_t *__restrict__ slot_stamp,
-                                                            uint32_t n_pool_slots, uint32_t epoch_now, uint32_t max_age,
-                                                            uint32_t *hist) {
-  uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s >= n_pool_slots) return;
-  const uint32_t st = slot_stamp[s];
-  if (st == 0 || st > epoch_now) return;  // free, or stamped in the future: never chosen
-  const uint32_t age = epoch_now - st;
-  atomicAdd(&hist[age < max_age - 1 ? age : max_age - 1], 1u);
+                                                            uint32_t n_pool_slots, uint32_t epoch_now, uint32_t *hist) {
+  __shared__ uint32_t local[CP_LRU_MAX_AGE];
+  for (uint32_t a = threadIdx.x; a < CP_LRU_MAX_AGE; a += blockDim.x) local[a] = 0;
+  __syncthreads();
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  for (uint32_t base = blockIdx.x * blockDim.x; base < n_pool_slots; base += gridDim.x * blockDim.x) {
+    const uint32_t s = base + threadIdx.x;  // base is the same for the whole workgroup
+    uint32_t bin = kNone;
+    if (s < n_pool_slots) {
+      const uint32_t st = slot_stamp[s];
+      if (st != 0 && st <= epoch_now) {  // else free, or stamped in the future: never chosen
+        const uint32_t age = epoch_now - st;
+        bin = age < CP_LRU_MAX_AGE - 1 ? age : CP_LRU_MAX_AGE - 1;
+      }
+    }
+    bool todo = bin != kNone;
+    unsigned long long left = __ballot(todo);
+    while (left) {  // the same for the whole wavefront; every round retires at least one lane
+      const uint32_t first = (uint32_t)__ffsll(left) - 1;
+      const uint32_t b = __builtin_amdgcn_readlane(bin, first);
+      const unsigned long long same = __ballot(todo && bin == b);
+      if (lane == first) atomicAdd(&local[b], (uint32_t)__popcll(same));
+      if (bin == b) todo = false;
+      left = __ballot(todo);
+    }
+  }
+  __syncthreads();
+  for (uint32_t a = threadIdx.x; a < CP_LRU_MAX_AGE; a += blockDim.x)
+    if (local[a]) atomicAdd(&hist[a], local[a]);
 }
 
 // One workgroup.  Largest age a such that the slots of age >= a are at least n_needed; threshold =
@@ -280,8 +304,8 @@ extern "C" int32_t cp_lru_threshold(void *stream_, const uint32_t *slot_stamp, u
   if (!hist) return CP_ERR_SCRATCH;
   zero_words_kernel<<<div_up(CP_LRU_MAX_AGE, 256), 256, 0, stream>>>(hist, CP_LRU_MAX_AGE);
   if (n_pool_slots)
-    age_histogram_kernel<<<div_up(n_pool_slots, 256), 256, 0, stream>>>(slot_stamp, n_pool_slots, epoch_now,
-                                                                        CP_LRU_MAX_AGE, hist);
+    age_histogram_kernel<<<std::min<uint32_t>(div_up(n_pool_slots, 256), 512), 256, 0, stream>>>(slot_stamp, n_pool_slots,
+                                                                                                 epoch_now, hist);
   lru_pick_kernel<<<1, 256, 0, stream>>>(hist, CP_LRU_MAX_AGE, epoch_now, n_needed, threshold_out);
   return check_launch();
 }
