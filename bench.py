@@ -47,6 +47,20 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def host_info():
+    """CPU model and logical CPU count of the machine the oracle is timed on."""
+    model = None
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"cpu": model, "logical_cpus": os.cpu_count(), "oracle_threads": 1}
+
+
 def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False, min_len=1, recompute=0.0,
                  zero_fill=False):
     """The CPU oracle, as it stands, on the first ``n_requests`` requests of the workload."""
@@ -89,6 +103,7 @@ def cpu_baseline(wl, n_requests, G, torch, np, anchor_window=None, verify=False,
                   f"same step (lookup + insert), pool of {sw.pool_slots} slots with the donors those requests use",
         "reused_tokens_per_s": matched / t_total,
         "seconds": {**{k: round(v, 4) for k, v in lk.times.items()}, "insert": round(t_ins, 4)},
+        "host": host_info(),
     }
 
 
@@ -162,7 +177,7 @@ def annotator_bench(args):
         out["cpu_baseline"] = {"value": n * n / (t_sat + t_ann), "unit": "entries/s", "cores": 1, "kind": "oracle",
                                "sample": "the same matrix, whole", "seconds": {"sat": round(t_sat, 3),
                                                                                 "annotate": round(t_ann, 3)},
-                               "gpu_result_identical": same}
+                               "gpu_result_identical": same, "host": host_info()}
     print(json.dumps(out), flush=True)
 
 
