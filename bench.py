@@ -196,6 +196,8 @@ def main():
                     help="fraction of the stored tokens marked for recomputation (seeded, uniform): not served")
     ap.add_argument("--zero-fill", action="store_true", help="write zero rows for every token that is not served")
     ap.add_argument("--lru", action="store_true", help="keep last-use stamps for eviction")
+    ap.add_argument("--pool-layout", default="token", choices=["token", "layer"],
+                    help="token: a token's rows are contiguous in the pool (default); layer: one plane per (layer, K|V)")
     ap.add_argument("--annotator", type=int, default=0, metavar="N",
                     help="side benchmark: run the KV annotator on one N x N attention matrix instead of the KV path")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
@@ -239,7 +241,8 @@ def main():
         assert wl.donor_u is not None, "this workload draws no recompute marks"
         rec = (wl.donor_u < args.recompute).astype(np.uint8)
     gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window, verify=args.verify, min_len=args.min_len,
-                                    recompute_marks=rec is not None, zero_fill=args.zero_fill, lru=args.lru),
+                                    recompute_marks=rec is not None, zero_fill=args.zero_fill, lru=args.lru,
+                                    pool_layout=args.pool_layout),
                     recompute=rec)
     pool = gst.pool
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
@@ -379,7 +382,8 @@ def main():
         del a, b
 
     # the stored counter readings belong to the gather of the default options
-    same_gather = args.anchor_window is None and args.min_len <= 1 and args.recompute == 0
+    same_gather = (args.anchor_window is None and args.min_len <= 1 and args.recompute == 0
+                   and args.pool_layout == "token")
     out = {
         "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
         "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -392,14 +396,19 @@ def main():
             "workload": f"{wl.name}: {wl.n_requests} requests x {N // wl.n_requests} tokens, "
                         f"{sh.n_layers} layers x {sh.n_kv_heads} KV heads x {sh.head_dim} bf16 "
                         f"({sh.tok_bytes // 1024} KiB/token), pool {wl.pool_slots} slots "
-                        f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) token-major, slots in random order",
+                        f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) {args.pool_layout}-major, slots in random order",
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
             "anchor_window": args.anchor_window, "verify": args.verify, "min_len": args.min_len,
             "recompute_fraction": args.recompute, "zero_fill": args.zero_fill, "lru_stamps": args.lru,
+            "pool_layout": args.pool_layout,
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
             "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,
         },
-        "reused_tokens_per_s": matched / (ms_per_step * 1e-3),
+        "reused_tokens_per_s": matched / (ms_per_step * 1e-3),  # over the whole step, insert included
+        # over the lookup alone (hash, probe, spans, gather on one stream) and over the gather's mover kernel alone
+        "reused_tokens_per_s_lookup": None if front_ms is None else matched / ((front_ms + gather_ms) * 1e-3),
+        "reused_tokens_per_s_gather": matched / (gather_ms * 1e-3),
+        "insert_GBps": 2.0 * sh.tok_bytes * inserted / (insert_ms * 1e-3) / 1e9 if insert_ms > 0 else None,
         "gather_GBps": gather_gbps,
         "gather_pct_of_hbm_peak": 100.0 * gather_gbps / HBM_PEAK_GBPS,
         "gather_ms": gather_ms, "insert_ms": insert_ms,
@@ -419,6 +428,10 @@ def main():
             # asked for (every distinct source row once); the rest is descriptors, lists, re-fetches
             "fetched_bytes_landing_in_output": (sh.tok_bytes * unique_src / MEASURED_FETCH[wl.name]
                                                 if wl.name in MEASURED_FETCH and same_gather else None),
+            # bytes the requests asked for (one row set per reused token) over bytes fetched: above 1 where
+            # several requests are served from one fetch of a shared slot
+            "useful_over_fetched": (sh.tok_bytes * matched / MEASURED_FETCH[wl.name]
+                                    if wl.name in MEASURED_FETCH and same_gather else None),
         },
     }
     hev.close()

@@ -74,13 +74,18 @@ class KVPool:
 
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
                  device="cuda", pool_tensor=None, anchor_window=None, verify=False,
-                 min_len=1, recompute_marks=False, zero_fill=False, lru=False):
+                 min_len=1, recompute_marks=False, zero_fill=False, lru=False, pool_layout="token"):
         self.device = device
         self.n_slots = int(n_slots)
-        self.layout = B.KVLayout.token_major(n_layers, n_kv_heads, head_dim)
+        # "token": [slot][layer][K|V][head][dim], a token's rows are contiguous (the default);
+        # "layer": [layer][K|V][slot][head][dim], every row of a token lies in another plane (for comparison)
+        assert pool_layout in ("token", "layer")
+        self.layout = (B.KVLayout.token_major(n_layers, n_kv_heads, head_dim) if pool_layout == "token"
+                       else B.KVLayout.layer_major(n_layers, n_kv_heads, head_dim, self.n_slots))
         self.shape = (n_layers, n_kv_heads, head_dim)
         if pool_tensor is None:
-            pool_tensor = torch.empty(self.n_slots * self.layout.tok_stride, dtype=torch.uint8, device=device)
+            pool_tensor = torch.empty(self.n_slots * 2 * n_layers * n_kv_heads * head_dim * 2, dtype=torch.uint8,
+                                      device=device)
         self.pool = pool_tensor
         self.table = B.Table((int(table_capacity) + B.TABLE_BUCKET - 1) // B.TABLE_BUCKET * B.TABLE_BUCKET, device)
         self.slot_pos = torch.zeros(self.n_slots, dtype=torch.int32, device=device)

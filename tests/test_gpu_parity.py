@@ -30,13 +30,14 @@ def bf16_ordinal(bits):
 
 
 def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, verify=False, min_len=1,
-                recompute=None, zero_fill=False):
+                recompute=None, zero_fill=False, pool_layout="token"):
     """Run prefill + lookup on both sides and compare everything."""
     fl = []
     ost = OH.prefill(wl, flags_out=fl, anchor_window=anchor_window, verify=verify, recompute=recompute)
     olk = OH.lookup(ost, min_len=min_len, zero_fill=zero_fill)
     gst = G.prefill(wl, G.make_pool(wl, anchor_window=anchor_window, verify=verify,
-                                    min_len=min_len, recompute_marks=recompute is not None, zero_fill=zero_fill),
+                                    min_len=min_len, recompute_marks=recompute is not None, zero_fill=zero_fill,
+                                    pool_layout=pool_layout),
                     recompute=recompute)
     glk = G.lookup(gst)
     assert np.array_equal(glk.served, olk.served)
@@ -85,6 +86,16 @@ def test_llama8b_shape_small(G):
     wl = gen.make_docs("llama3-8b-small", 0xC0FFEE02, gen.KVShape(32, 8, 128), R=3, T=1371, prefix_len=300, n_docs=6,
                        doc_len=(150, 300), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096)
     compare_all(G, wl)
+
+
+def test_layer_major_pool_whole_path(G):
+    """The pool's layout is the caller's choice (three strides): insert, lookup and re-rotation with one plane per
+    (layer, K|V) instead of contiguous tokens give the same slots, spans and rows."""
+    wl = gen.make_docs("llama3-8b-small", 0xC0FFEE02, gen.KVShape(32, 8, 128), R=3, T=1371, prefix_len=300, n_docs=6,
+                       doc_len=(150, 300), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096)
+    compare_all(G, wl, pool_layout="layer")
+    compare_all(G, gen.make_rope(scale=1 / 32, shape=gen.KVShape(3, 2, 128)), pool_layout="layer", anchor_window=8,
+                verify=True)
 
 
 def test_llama70b_shape_small(G):
