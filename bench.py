@@ -196,6 +196,8 @@ def main():
                     help="fraction of the stored tokens marked for recomputation (seeded, uniform): not served")
     ap.add_argument("--zero-fill", action="store_true", help="write zero rows for every token that is not served")
     ap.add_argument("--lru", action="store_true", help="keep last-use stamps for eviction")
+    ap.add_argument("--free-list", default="random", choices=["random", "sequential"],
+                    help="order in which pool slots are handed out (the configurations say random)")
     ap.add_argument("--pool-layout", default="token", choices=["token", "layer"],
                     help="token: a token's rows are contiguous in the pool (default); layer: one plane per (layer, K|V)")
     ap.add_argument("--annotator", type=int, default=0, metavar="N",
@@ -232,6 +234,8 @@ def main():
 
     t0 = time.time()
     wl = gen.make(args.workload)
+    if args.free_list == "sequential":  # slots handed out in ascending order: matched runs become long spans
+        wl.free_slots = np.arange(wl.pool_slots, dtype=np.uint32)
     sh = wl.shape
     N = wl.n_tokens
     log(f"[bench] workload {wl.name}: {wl.n_requests} requests, {N} tokens, {sh.tok_bytes // 1024} KiB/token, "
@@ -383,7 +387,7 @@ def main():
 
     # the stored counter readings belong to the gather of the default options
     same_gather = (args.anchor_window is None and args.min_len <= 1 and args.recompute == 0
-                   and args.pool_layout == "token")
+                   and args.pool_layout == "token" and args.free_list == "random")
     out = {
         "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
         "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -396,11 +400,11 @@ def main():
             "workload": f"{wl.name}: {wl.n_requests} requests x {N // wl.n_requests} tokens, "
                         f"{sh.n_layers} layers x {sh.n_kv_heads} KV heads x {sh.head_dim} bf16 "
                         f"({sh.tok_bytes // 1024} KiB/token), pool {wl.pool_slots} slots "
-                        f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) {args.pool_layout}-major, slots in random order",
+                        f"({wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB) {args.pool_layout}-major, slots in {args.free_list} order",
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
             "anchor_window": args.anchor_window, "verify": args.verify, "min_len": args.min_len,
             "recompute_fraction": args.recompute, "zero_fill": args.zero_fill, "lru_stamps": args.lru,
-            "pool_layout": args.pool_layout,
+            "pool_layout": args.pool_layout, "free_list": args.free_list,
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
             "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,
         },
