@@ -91,3 +91,22 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_annotate(None, P, 100, Q, 1, 101, P, P, P, Q, Q, None, S, big) == INV  # rho above 100 %
     assert L.cp_tune(99, 1) == INV
     assert L.cp_sat_scratch_bytes(10000) > (157 * 10112 + 79 * 10048) * 8  # tile carries of a 10,000-token request
+
+
+def test_header_and_library_from_plain_c(tmp_path):
+    """include/cacheprune.h is a C header: it compiles as C99 on its own, and a C program that passes the
+    structs by value gets the documented answers from the host-side checks (no GPU involved)."""
+    import os
+    import subprocess
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-x", "c",
+                    os.path.join(inc, "cacheprune.h")], check=True)
+    lib = cp.binding.lib()._name
+    exe = str(tmp_path / "abi_c_check")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", inc, "-o", exe,
+                    os.path.join(root, "tests", "abi_c_check.c"), lib, "-Wl,-rpath," + os.path.dirname(lib),
+                    "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    run = subprocess.run([exe], capture_output=True, text=True)
+    assert run.returncode == 0 and run.stdout.strip() == "abi ok", (run.returncode, run.stdout, run.stderr)
