@@ -360,7 +360,7 @@ __global__ __launch_bounds__(256) void annotate_init_kernel(const int64_t *__res
 // first is the tile of the earliest segment start among the tile's r (no candidate lies left of it),
 // and leaves, for every r of the tile, the best (score, l) it saw: part_u[y][r] = biased score
 // (0 = no candidate), part_l[y][r] = the smallest l that reaches it.
-constexpr uint32_t kSearchSplit = 8;
+constexpr uint32_t kSearchSplit = 16;
 __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__restrict__ T, uint32_t n,
                                                               const int64_t *__restrict__ diag,
                                                               const uint32_t *__restrict__ seg_a,
@@ -578,7 +578,7 @@ extern "C" size_t cp_sat_scratch_bytes(uint32_t n) {
   const uint64_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
   const uint64_t cols = n_i * (n_j * kTileC), rows = n_j * (n_i * kTile);
   // column sums per tile row, running row sums per tile column, tile totals, per-token arrays of cp_annotate
-  return (size_t)((cols + rows + n_i * n_j) * 8 + 192ull * n + 32 * 256);
+  return (size_t)((cols + rows + n_i * n_j) * 8 + 320ull * n + 32 * 256);
 }
 
 extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
