@@ -36,11 +36,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command, scaled by what the same counters read for kernels of known size
 # (profiles/gather_rows_kernel_<workload>.txt); None for workloads not profiled that way.
-MEASURED_TRAFFIC = {"llama3-8b": 9038385933, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
+MEASURED_TRAFFIC = {"llama3-8b": 9038240601, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
                     "annotator-10000": 924614651}
 # (the float workload was profiled with all added rows on: profiles/gather_rows_kernel_float_all_rows.txt)
 # the read part of the same measurements (FETCH_SIZE, scaled)
-MEASURED_FETCH = {"llama3-8b": 3098945050, "rope": 2762280080, "llama3-70b": 25303251909, "frag": 7420215123}
+MEASURED_FETCH = {"llama3-8b": 3098951142, "rope": 2762280080, "llama3-70b": 25303251909, "frag": 7420215123}
 
 
 def log(*a):
