@@ -13,9 +13,10 @@ namespace cp {
 struct Tuning {
   uint32_t move_multicast = 1;       // 1: tokens that read the same pool slot are served by one read
   uint32_t move_blocks_per_cu = 2;   // resident workgroups per compute unit for the row mover
-  uint32_t move_blocks_per_cu_rope = 6;  // the same for gathers that re-rotate keys (more arithmetic per byte)
+  uint32_t move_blocks_per_cu_rope = 4;  // the same for gathers that re-rotate keys: as many as their registers let a unit hold
   uint32_t move_nontemporal = 2;     // bit 0: non-temporal loads, bit 1: non-temporal stores
   uint32_t move_unroll = 8;          // 16-byte loads a lane issues before its first store (4 or 8)
+  uint32_t move_unroll_rope = 4;     // the same for gathers that re-rotate keys
   hipEvent_t gather_start = nullptr; // if set (cp_gather_events): recorded right before / after the
   hipEvent_t gather_stop = nullptr;  // gather's row-mover launch, on the call's stream
 };

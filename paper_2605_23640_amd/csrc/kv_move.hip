@@ -474,12 +474,16 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
     scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                \
         items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope)
   const uint32_t nt = tn.move_nontemporal & 3u;
-  if constexpr (ROPE) {  // rotation keeps the short form: it needs the registers
-    switch (nt) {
+  if constexpr (ROPE) {  // rotation defaults to the short form: it needs the registers
+    switch (nt | (tn.move_unroll_rope >= 8 ? 4u : 0u)) {
       case 0: CP_LAUNCH(false, false, 4); break;
       case 1: CP_LAUNCH(true, false, 4); break;
       case 2: CP_LAUNCH(false, true, 4); break;
-      default: CP_LAUNCH(true, true, 4); break;
+      case 3: CP_LAUNCH(true, true, 4); break;
+      case 4: CP_LAUNCH(false, false, 8); break;
+      case 5: CP_LAUNCH(true, false, 8); break;
+      case 6: CP_LAUNCH(false, true, 8); break;
+      default: CP_LAUNCH(true, true, 8); break;
     }
   } else {
     switch (nt | (tn.move_unroll >= 8 ? 4u : 0u)) {
@@ -623,6 +627,7 @@ extern "C" int32_t cp_tune(int32_t key, uint32_t value) {
     case 2: t.move_nontemporal = value; return CP_OK;
     case 3: t.move_unroll = value; return CP_OK;
     case 4: t.move_blocks_per_cu_rope = value; return CP_OK;
+    case 5: t.move_unroll_rope = value; return CP_OK;
     default: return CP_ERR_INVALID_ARG;
   }
 }
