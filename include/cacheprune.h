@@ -343,6 +343,11 @@ int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *sta
  *     T[i][j] = sum of the weights of rows <= i and columns <= j,
  *   valid for every j <= i.  No token attends to a later one, so T[i][j] = T[i][i] for j > i;
  *   those entries are not needed, cp_annotate never reads them, and most of them are not written.
+ *   mask (device, u8[n], may be NULL): if given, only the part of the table that cp_annotate can
+ *   read for this mask is written - the diagonal entries and, for the rows of a coarse segment
+ *   [a, b], the columns from a - 64 on (in whole tiles) - and nothing else of T is defined.  A
+ *   search only looks inside segments, so with sensitive tokens every few hundred positions most of
+ *   the table is never asked for.  The weights are still all read (every sum needs them).
  * cp_annotate (Steps 2, 3), for every coarse segment [a, b]:
  *   - among its substrings [l, r] with at least min_len tokens (0 counts as 1) the one with the
  *     largest  IntraAttn - InterAttn = sum(rows l..r, columns l..r) - sum(rows l..r, columns < l);
@@ -357,8 +362,8 @@ int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *sta
  *     floor(len * rho_percent / 100) get recompute[i] = 1 (input of cp_mark_recompute).
  * n <= 2^20.  Scratch: cp_sat_scratch_bytes(n), 256-byte aligned, for either call. */
 size_t cp_sat_scratch_bytes(uint32_t n);
-int32_t cp_sat_build(void *stream, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
-                     size_t scratch_bytes);
+int32_t cp_sat_build(void *stream, const float *attn, uint32_t n, uint64_t ld, const uint8_t *mask, int64_t *T,
+                     void *scratch, size_t scratch_bytes);
 int32_t cp_annotate(void *stream, const int64_t *T, uint32_t n, const uint8_t *mask, uint32_t min_len,
                     uint32_t rho_percent, uint32_t *best_l, uint32_t *best_r, int64_t *best_score, uint8_t *reusable,
                     uint8_t *recompute, uint8_t *store_mask, void *scratch, size_t scratch_bytes);

@@ -133,7 +133,7 @@ def lib():
         L.cp_sat_scratch_bytes.restype = sz
         L.cp_sat_scratch_bytes.argtypes = [u32]
         L.cp_sat_build.restype = i32
-        L.cp_sat_build.argtypes = [vp, vp, u32, u64, vp, vp, sz]
+        L.cp_sat_build.argtypes = [vp, vp, u32, u64, vp, vp, vp, sz]
         L.cp_annotate.restype = i32
         L.cp_annotate.argtypes = [vp, vp, u32, vp, u32, u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_probe2.restype = i32
@@ -362,14 +362,15 @@ def new_sat_scratch(n, device="cuda"):
     return torch.empty(int(lib().cp_sat_scratch_bytes(int(n))), dtype=torch.uint8, device=device)
 
 
-def cp_sat_build(attn, T, scratch, stream=None):
-    """attn float32[n][ld] -> T int64[n][n]."""
-    _need_cuda(attn, T, scratch)
+def cp_sat_build(attn, T, scratch, stream=None, mask=None):
+    """attn float32[n][ld] -> T int64[n][n]; with ``mask`` (uint8[n]) only the part cp_annotate reads for it."""
+    _need_cuda(attn, T, scratch, mask)
+    assert mask is None or (mask.dtype == torch.uint8 and mask.numel() == attn.shape[0])
     n, ld = attn.shape[0], attn.stride(0)
     assert attn.dtype == torch.float32 and attn.stride(1) == 1 and T.dtype == torch.int64
     assert T.is_contiguous() and T.shape == (n, n)
-    _check("cp_sat_build", lib().cp_sat_build(_stream(stream), _ptr(attn), n, ld, _ptr(T), _ptr(scratch),
-                                              scratch.numel()))
+    _check("cp_sat_build", lib().cp_sat_build(_stream(stream), _ptr(attn), n, ld, _ptr(mask), _ptr(T),
+                                              _ptr(scratch), scratch.numel()))
     return T
 
 

@@ -292,16 +292,69 @@ __device__ __forceinline__ void tile_apply(const float *__restrict__ attn, uint3
   }
 }
 
+// With the sensitivity mask known, the table is needed only where a substring search can look: in the
+// rows of a coarse segment [a, b], the columns from a - 1 on (and the diagonal, for every row).
+// need_from[I] = the smallest such a over the non-sensitive rows of tile row I (kNone: all its rows are
+// sensitive).  One workgroup: per tile row its first non-sensitive row and its last sensitive one, a
+// running maximum over the latter, and the segment start follows from the two.
+constexpr uint32_t kMaxTileRows = 4096;  // 2^18 rows / 64; larger requests get the whole table
+__global__ __launch_bounds__(1024) void sat_need_from_kernel(const uint8_t *__restrict__ mask, uint32_t n,
+                                                             uint32_t n_i, uint32_t *__restrict__ need_from) {
+  __shared__ uint32_t first[kMaxTileRows];  // the first non-sensitive row of tile row I (kNone: none)
+  __shared__ uint32_t last[kMaxTileRows];   // 1 + the last sensitive row at or before the end of tile row I (0: none)
+  __shared__ uint32_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  // a wavefront's 64 lanes are the 64 rows of one tile row: two ballots say where it stands
+  for (uint32_t r0 = threadIdx.x / kWave * kTile; r0 < n; r0 += blockDim.x) {  // the same for a whole wavefront
+    const uint32_t r = r0 + (threadIdx.x & (kWave - 1));
+    const unsigned long long sens = __ballot(r < n && mask[r] != 0), open = __ballot(r < n && mask[r] == 0);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+      first[r0 / kTile] = open ? r0 + (uint32_t)__ffsll(open) - 1 : kNone;
+      last[r0 / kTile] = sens ? r0 + 64 - (uint32_t)__clzll(sens) : 0;
+    }
+  }
+  __syncthreads();
+  // inclusive running maximum over last[], a chunk of blockDim.x entries at a time
+  for (uint32_t base = 0; base < n_i; base += blockDim.x) {
+    const uint32_t I = base + threadIdx.x;
+    const uint32_t width = n_i - base < blockDim.x ? n_i - base : blockDim.x;
+    for (uint32_t step = 1; step < width; step <<= 1) {
+      uint32_t other = 0;
+      if (I < n_i && threadIdx.x >= step) other = last[I - step];
+      __syncthreads();
+      if (I < n_i && other > last[I]) last[I] = other;
+      __syncthreads();
+    }
+    if (I < n_i && carry > last[I]) last[I] = carry;
+    __syncthreads();
+    if (threadIdx.x == 0) carry = last[base + width - 1];
+    __syncthreads();
+  }
+  for (uint32_t I = threadIdx.x; I < n_i; I += blockDim.x) {
+    uint32_t a = first[I];
+    // a segment that starts inside the tile row starts at its first non-sensitive row (the rows before it are
+    // sensitive); one that reaches in from above starts right after the last sensitive row before the tile row
+    if (a != kNone && a == I * kTile) a = I ? last[I - 1] : 0;
+    need_from[I] = a;
+  }
+}
+
 template <bool VEC_LD, bool VEC_ST>
 __global__ __launch_bounds__(64) void sat_apply_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
                                                        uint32_t n_pad_c, uint32_t n_pad_r,
                                                        const int64_t *__restrict__ above,
                                                        const int64_t *__restrict__ left,
                                                        const int64_t *__restrict__ tiles_above,
+                                                       const uint32_t *__restrict__ need_from /* nullable */,
                                                        int64_t *__restrict__ T) {
   const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
   const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
   if (c0 > r0 + kTile - 1) return;  // above the diagonal: not written
+  if (need_from && c0 + kTileC <= r0) {  // not the tile that holds these rows' diagonal entries
+    // the search stages whole 64-column blocks, so it loads columns down to a - 64
+    const uint32_t a = need_from[I];
+    if (a == kNone || c0 + kTileC + kTile <= a) return;  // left of everything a search looks at in these rows
+  }
   // everything above the tile, in the tile's columns up to each of this lane's
   int64_t above_pref[2];
   {
@@ -578,11 +631,11 @@ extern "C" size_t cp_sat_scratch_bytes(uint32_t n) {
   const uint64_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
   const uint64_t cols = n_i * (n_j * kTileC), rows = n_j * (n_i * kTile);
   // column sums per tile row, running row sums per tile column, tile totals, per-token arrays of cp_annotate
-  return (size_t)((cols + rows + n_i * n_j) * 8 + 320ull * n + 32 * 256);
+  return (size_t)((cols + rows + n_i * n_j) * 8 + 4 * n_i + 320ull * n + 33 * 256);
 }
 
-extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, int64_t *T, void *scratch,
-                                size_t scratch_bytes) {
+extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, const uint8_t *mask,
+                                int64_t *T, void *scratch, size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (n == 0) return CP_OK;
@@ -596,10 +649,13 @@ extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, ui
   int64_t *colsum = sc.take<int64_t>((size_t)n_i * n_pad_c);
   int64_t *rowsum = sc.take<int64_t>((size_t)n_j * n_pad_r);
   int64_t *tilesum = sc.take<int64_t>((size_t)n_i * n_j);
-  if (!colsum || !rowsum || !tilesum) return CP_ERR_SCRATCH;
+  if (n_i > kMaxTileRows) mask = nullptr;
+  uint32_t *need_from = mask ? sc.take<uint32_t>(n_i) : nullptr;
+  if (!colsum || !rowsum || !tilesum || (mask && !need_from)) return CP_ERR_SCRATCH;
   const bool vec_ld = ld % 2 == 0 && aligned(attn, 8);  // every (row, column pair) starts on 8 bytes
   const bool vec_st = n % 2 == 0 && aligned(T, 16);
   const dim3 tiles(n_j, n_i);
+  if (mask) sat_need_from_kernel<<<1, 1024, 0, stream>>>(mask, n, n_i, need_from);
   if (vec_ld)
     sat_tile_sums_kernel<true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum);
   else
@@ -610,13 +666,13 @@ extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, ui
   sat_exclusive_over_tiles_kernel<<<dim3(div_up(widest, 64), 3), 64, 0, stream>>>(
       colsum, n_i, n_pad_c, rowsum, n_j, n_pad_r, tilesum, n_i, n_j);
   if (vec_ld && vec_st)
-    sat_apply_kernel<true, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+    sat_apply_kernel<true, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
   else if (vec_ld)
-    sat_apply_kernel<true, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+    sat_apply_kernel<true, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
   else if (vec_st)
-    sat_apply_kernel<false, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+    sat_apply_kernel<false, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
   else
-    sat_apply_kernel<false, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, T);
+    sat_apply_kernel<false, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
   return check_launch();
 }
 

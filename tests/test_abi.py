@@ -57,7 +57,7 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_probe(None, tab, None, 0, None) == B.OK
     assert L.cp_verify_chain(None, None, None, None, 0, None, None, 0, 0, None, None, None, 0) == B.OK
     assert L.cp_filter_matches(None, None, None, 0, 0, 1, None, 0, None, None, 0) == B.OK
-    assert L.cp_sat_build(None, None, 0, 0, None, None, 0) == B.OK
+    assert L.cp_sat_build(None, None, 0, 0, None, None, None, 0) == B.OK
     # null or inconsistent arguments
     assert L.cp_hash_segments(None, None, Q, S, 4, 1, B.BASE, P, S, big) == INV
     assert L.cp_hash_segments(None, P, Q, S, 4, 0, B.BASE, P, S, big) == INV  # no requests
@@ -85,9 +85,9 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_lru_threshold(None, None, 16, 5, 1, P, S, big) == INV
     assert L.cp_evict(None, tab, None, 16, P, Q, S, None, None, None, S, big) == INV
     assert L.cp_table_compact(None, tab, tab, S) == INV  # source and destination share memory
-    assert L.cp_sat_build(None, P, 100, 64, Q, S, big) == INV  # row stride shorter than a row
-    assert L.cp_sat_build(None, P, (1 << 20) + 1, 1 << 21, Q, S, big) == UNS
-    assert L.cp_sat_build(None, P, 100, 100, Q, S, 16) == SCR
+    assert L.cp_sat_build(None, P, 100, 64, None, Q, S, big) == INV  # row stride shorter than a row
+    assert L.cp_sat_build(None, P, (1 << 20) + 1, 1 << 21, None, Q, S, big) == UNS
+    assert L.cp_sat_build(None, P, 100, 100, None, Q, S, 16) == SCR
     assert L.cp_annotate(None, P, 100, Q, 1, 101, P, P, P, Q, Q, None, S, big) == INV  # rho above 100 %
     assert L.cp_tune(99, 1) == INV
     assert L.cp_sat_scratch_bytes(10000) > (157 * 10112 + 79 * 10048) * 8  # tile carries of a 10,000-token request

@@ -12,13 +12,17 @@ pytestmark = pytest.mark.gpu
 X = 0xFFFFFFFF
 
 
-def gpu_annotate(G, a, mask, min_len, rho):
+UNWRITTEN = -7777777
+
+
+def gpu_annotate(G, a, mask, min_len, rho, masked=False):
+    """``masked``: the table build is told the mask and writes only what a search can read."""
     from paper_2605_23640_amd import binding as B
     n = a.shape[0]
     d_a = torch.from_numpy(a).to(G.DEV)
-    T = torch.empty((n, n), dtype=torch.int64, device=G.DEV)
+    T = torch.full((n, n), UNWRITTEN, dtype=torch.int64, device=G.DEV)
     scratch = B.new_sat_scratch(n, G.DEV)
-    B.cp_sat_build(d_a, T, scratch)
+    B.cp_sat_build(d_a, T, scratch, mask=torch.from_numpy(mask).to(G.DEV) if masked else None)
     i32 = lambda: torch.empty(n, dtype=torch.int32, device=G.DEV)  # noqa: E731
     u8 = lambda: torch.empty(n, dtype=torch.uint8, device=G.DEV)  # noqa: E731
     bl, br, bs, reus, rec, sm = i32(), i32(), torch.empty(n, dtype=torch.int64, device=G.DEV), u8(), u8(), u8()
@@ -38,6 +42,24 @@ def check(G, a, mask, min_len, rho):
     for g, w, name in zip((bl, br, bs, reus, rec), want, ("best_l", "best_r", "best_score", "reusable", "recompute")):
         assert np.array_equal(g, w), name
     assert np.array_equal(sm, 1 - reus)
+    # the same with a table build that knows the mask: identical decisions, and the table is right wherever a
+    # search may look (rows of a segment [a, b] x columns a-1 .. row, and the diagonal)
+    T2, *outs2 = gpu_annotate(G, a, mask, min_len, rho, masked=True)
+    for g, w, name in zip(outs2, (bl, br, bs, reus, rec, sm), ("best_l", "best_r", "best_score", "reusable", "recompute", "store")):
+        assert np.array_equal(g, w), ("masked build", name)
+    need = np.eye(n, dtype=bool)
+    i = 0
+    while i < n:
+        if mask[i]:
+            i += 1
+            continue
+        j = i
+        while j + 1 < n and not mask[j + 1]:
+            j += 1
+        need[i:j + 1, max(i - 1, 0):j + 1] = True
+        i = j + 1
+    need &= np.tri(n, dtype=bool)
+    assert np.array_equal(T2[need], oT[need])
     return want
 
 
@@ -58,6 +80,8 @@ def test_annotator_full_size(G):
     mask = AT.make_mask(n, run_mean=8.0, cover=0.01)
     bl, br, bs, reus, rec = check(G, a, mask, 128, 25)
     assert reus.sum() > 0.8 * n and abs(int(rec.sum()) - int(reus.sum()) // 4) < 20
+    T2 = gpu_annotate(G, a, mask, 128, 25, masked=True)[0]
+    assert (np.tril(T2) == UNWRITTEN).mean() > 0.3  # with a dozen segments most of the triangle is never asked for
     one = np.zeros(n, np.uint8)  # a single segment: every (l, r) pair is a candidate
     bl, br, bs, reus, rec = check(G, a, one, 128, 25)
     assert bl[0] != X
