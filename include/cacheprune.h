@@ -348,6 +348,8 @@ int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *sta
  *   [a, b], the columns from a - 64 on (in whole tiles) - and nothing else of T is defined.  A
  *   search only looks inside segments, so with sensitive tokens every few hundred positions most of
  *   the table is never asked for.  The weights are still all read (every sum needs them).
+ *   cp_annotate must then be given the same mask (with another one it would read undefined
+ *   entries: wrong decisions, though never memory outside T).
  * cp_annotate (Steps 2, 3), for every coarse segment [a, b]:
  *   - among its substrings [l, r] with at least min_len tokens (0 counts as 1) the one with the
  *     largest  IntraAttn - InterAttn = sum(rows l..r, columns l..r) - sum(rows l..r, columns < l);
