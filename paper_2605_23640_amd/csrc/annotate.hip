@@ -568,17 +568,18 @@ __global__ __launch_bounds__(256) void annotate_finish_kernel(const int64_t *__r
 }
 
 // Rank of every token of a chosen substring among that substring's tokens by d, largest first,
-// earlier token first on ties.  Block (x, y): tokens i of block x against the tokens j of chunk y;
-// the partial counts are added up in rank[] (zeroed by the finish kernel).
-constexpr uint32_t kRankChunk = 256;
+// earlier token first on ties.  Block (x, y): the 64 tokens i of block x against the chunks of tokens j that
+// their substrings cover, every kRankSplit-th of them starting with the y-th; the partial counts are
+// added up in rank[] (zeroed by the finish kernel).
+constexpr uint32_t kRankChunk = 256, kRankSplit = 8;
 __global__ __launch_bounds__(256) void annotate_rank_kernel(uint32_t n, const uint32_t *__restrict__ out_l,
                                                             const uint32_t *__restrict__ out_r,
                                                             const uint8_t *__restrict__ reusable,
                                                             const int64_t *__restrict__ d, uint32_t *rank) {
   __shared__ int64_t dj[kRankChunk];
   __shared__ uint32_t lo_all, hi_all;
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint32_t j0 = blockIdx.y * kRankChunk;
+  // a wavefront's lanes are 64 tokens; the workgroup's four wavefronts take a quarter of every chunk each
+  const uint32_t i = blockIdx.x * kWave + (threadIdx.x & (kWave - 1)), quarter = threadIdx.x / kWave;
   const bool mine = i < n && reusable[i];
   const uint32_t bl = mine ? out_l[i] : kNone, br = mine ? out_r[i] : 0u;
   if (threadIdx.x == 0) {
@@ -586,23 +587,35 @@ __global__ __launch_bounds__(256) void annotate_rank_kernel(uint32_t n, const ui
     hi_all = 0;
   }
   __syncthreads();
-  if (mine) {
-    atomicMin(&lo_all, bl);
-    atomicMax(&hi_all, br);
+  {  // the span of tokens this workgroup's substrings cover: reduced inside each wavefront, then four atomics
+    uint32_t lo = bl, hi = br;
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+      const uint32_t ol = __shfl_xor(lo, m, kWave), oh = __shfl_xor(hi, m, kWave);
+      lo = ol < lo ? ol : lo;
+      hi = oh > hi ? oh : hi;
+    }
+    if ((threadIdx.x & (kWave - 1)) == 0 && lo != kNone) {
+      atomicMin(&lo_all, lo);
+      atomicMax(&hi_all, hi);
+    }
   }
   __syncthreads();
-  if (lo_all == kNone || j0 > hi_all || j0 + kRankChunk <= lo_all) return;  // no token here looks at this chunk
-  const uint32_t j = j0 + threadIdx.x;
-  dj[threadIdx.x] = j < n ? d[j] : 0;
-  __syncthreads();
-  if (!mine) return;
-  const uint32_t from = bl > j0 ? bl : j0, to = br < j0 + kRankChunk - 1 ? br : j0 + kRankChunk - 1;  // inclusive
-  if (from > to) return;
-  const int64_t di = d[i];
+  if (lo_all == kNone) return;  // nothing reusable among these tokens
+  const int64_t di = mine ? d[i] : 0;
   uint32_t count = 0;
-  for (uint32_t jj = from; jj <= to; ++jj) {
-    const int64_t v = dj[jj - j0];
-    count += (v > di || (v == di && jj < i)) ? 1u : 0u;
+  for (uint32_t chunk = lo_all / kRankChunk + blockIdx.y; chunk <= hi_all / kRankChunk; chunk += kRankSplit) {  // same for all
+    const uint32_t j0 = chunk * kRankChunk, j = j0 + threadIdx.x;
+    __syncthreads();  // the previous chunk is no longer read
+    dj[threadIdx.x] = j < n ? d[j] : 0;
+    __syncthreads();
+    if (!mine) continue;
+    const uint32_t q0 = j0 + quarter * (kRankChunk / 4), q1 = q0 + kRankChunk / 4 - 1;
+    const uint32_t from = bl > q0 ? bl : q0, to = br < q1 ? br : q1;  // inclusive
+    for (uint32_t jj = from; jj <= to; ++jj) {  // (empty if the substring does not reach into this quarter)
+      const int64_t v = dj[jj - j0];
+      count += (v > di || (v == di && jj < i)) ? 1u : 0u;
+    }
   }
   if (count) atomicAdd(&rank[i], count);
 }
@@ -716,7 +729,7 @@ extern "C" int32_t cp_annotate(void *stream_, const int64_t *T, uint32_t n, cons
   annotate_finish_kernel<<<blocks, 256, 0, stream>>>(T, n, diag, seg_a, best_u, best_lr, best_l, best_r, best_score,
                                                      reusable, store_mask, d, rank);
   if (rho_percent)
-    annotate_rank_kernel<<<dim3(blocks, div_up(n, kRankChunk)), 256, 0, stream>>>(n, best_l, best_r, reusable, d, rank);
+    annotate_rank_kernel<<<dim3(div_up(n, kWave), kRankSplit), 256, 0, stream>>>(n, best_l, best_r, reusable, d, rank);
   annotate_mark_kernel<<<blocks, 256, 0, stream>>>(n, best_l, best_r, reusable, rank, rho_percent, recompute);
   return check_launch();
 }
