@@ -396,16 +396,21 @@ __global__ __launch_bounds__(256) void annotate_init_kernel(const int64_t *__res
                                                             const uint32_t *__restrict__ seg_a,
                                                             int64_t *__restrict__ diag, uint64_t *best_u,
                                                             uint64_t *best_lr, uint32_t *__restrict__ tile_min_a) {
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  diag[i] = T[(uint64_t)i * n + i];
-  best_u[i] = 0;        // below every biased score
-  best_lr[i] = ~0ull;   // above every packed (l, r)
-  if (i % kTile == 0) {  // earliest segment start among the 64 tokens from i on (kNone if all are sensitive)
-    uint32_t m = kNone;
-    for (uint32_t k = 0; k < kTile && i + k < n; ++k) m = seg_a[i + k] < m ? seg_a[i + k] : m;
-    tile_min_a[i / kTile] = m;
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;  // no lane leaves early: the wavefront reduces together
+  uint32_t m = kNone;
+  if (i < n) {
+    diag[i] = T[(uint64_t)i * n + i];
+    best_u[i] = 0;        // below every biased score
+    best_lr[i] = ~0ull;   // above every packed (l, r)
+    m = seg_a[i];
   }
+  // a wavefront is one tile of 64 tokens: the earliest segment start among them (kNone if all are sensitive)
+#pragma unroll
+  for (int s = 1; s < kWave; s <<= 1) {
+    const uint32_t o = __shfl_xor(m, s, kWave);
+    m = o < m ? o : m;
+  }
+  if ((threadIdx.x & (kWave - 1)) == 0 && i < n) tile_min_a[i / kTile] = m;
 }
 
 // Candidates (l, r) are visited in 64 x 64 blocks: l in [lt*64, +64), r in [rt*64, +64), lt <= rt.
