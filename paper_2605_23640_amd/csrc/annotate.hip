@@ -27,9 +27,9 @@
 //
 // Step 2 (cp_annotate): score(l, r) = Intra - Inter = T[r,r] - T[l-1,r] - 2 T[r,l-1] + 2 T[l-1,l-1]
 // = T[r,r] + T[l-1,l-1] - 2 T[r,l-1]  (T[l-1,r] = T[l-1,l-1], see above).  A workgroup takes a 64 x 64
-// block of the (l, r) triangle: lanes along r, T[r, l-1] through a transposing LDS tile, and keeps for
-// every r the best (score, smallest l).  Two small passes over the tokens then find every segment's
-// maximum score (64-bit atomic max) and the smallest (l, r) among the r that reach it (atomic min).
+// block of the (l, r) triangle: lanes along l, so that T[r, l-1] is read row by row in contiguous pieces,
+// and keeps for every l the best (score, smallest r).  Two small passes over the tokens then find every
+// segment's maximum score (64-bit atomic max) and the smallest (l, r) among the l that reach it (atomic min).
 #include "cp_device.h"
 #include "cp_internal.h"
 
@@ -414,94 +414,97 @@ __global__ __launch_bounds__(256) void annotate_init_kernel(const int64_t *__res
 }
 
 // Candidates (l, r) are visited in 64 x 64 blocks: l in [lt*64, +64), r in [rt*64, +64), lt <= rt.
-// Workgroup (rt, y) takes the blocks lt = first, first + kSearchSplit, ... <= rt of its r tile, where
-// first is the tile of the earliest segment start among the tile's r (no candidate lies left of it),
-// and leaves, for every r of the tile, the best (score, l) it saw: part_u[y][r] = biased score
-// (0 = no candidate), part_l[y][r] = the smallest l that reaches it.
+// Lanes run along l, so a row T[r][l0-1 ..] is read as one contiguous piece and nothing needs transposing.
+// Workgroup (lt, y) takes the blocks rt = lt + y, lt + y + kSearchSplit, ... of its l tile, up to the
+// first r tile all of whose segments start beyond the tile's l (segment starts never decrease with r);
+// its four wavefronts take 16 rows of every block each.  It leaves, for every l of the tile, the best
+// (score, r) it saw: part_u[y][l] = biased score (0 = no candidate), part_r[y][l] = the smallest r that
+// reaches it.
 constexpr uint32_t kSearchSplit = 16;
 __global__ __launch_bounds__(256) void annotate_search_kernel(const int64_t *__restrict__ T, uint32_t n,
                                                               const int64_t *__restrict__ diag,
                                                               const uint32_t *__restrict__ seg_a,
                                                               const uint32_t *__restrict__ tile_min_a, uint32_t min_len,
                                                               uint64_t *__restrict__ part_u,
-                                                              uint32_t *__restrict__ part_l) {
-  const uint32_t rt = blockIdx.x;
-  const uint32_t min_a = tile_min_a[rt];  // kNone: every token of this tile is sensitive
-  __shared__ int64_t colT[kTile][kTile + 1];  // colT[r'][l'] = T[r0 + r'][l0 + l' - 1]
+                                                              uint32_t *__restrict__ part_r) {
   __shared__ uint64_t group_u[4][kTile];
-  __shared__ uint32_t group_l[4][kTile];
-  const uint32_t r0 = rt * kTile;
-  const uint32_t rl = threadIdx.x & (kTile - 1), grp = threadIdx.x / kTile;  // lane along r; 4 groups of 16 l's
-  const uint32_t r = r0 + rl;
-  const uint32_t a_r = r < n ? seg_a[r] : kNone;  // kNone: r is sensitive or past the end
-  const int64_t d_r = a_r != kNone ? diag[r] : 0;
+  __shared__ uint32_t group_r[4][kTile];
+  const uint32_t lt = blockIdx.x, n_t = gridDim.x;
+  const uint32_t lane = threadIdx.x & (kWave - 1), quarter = threadIdx.x / kWave;
+  const uint32_t l = lt * kTile + lane, l_last = lt * kTile + kTile - 1;
+  const int64_t d_l = (l >= 1 && l - 1 < n) ? diag[l - 1] : 0;
+  const int64_t *col = T + (l ? l - 1 : 0);  // column l - 1 (not read for l = 0)
   bool have = false;
   int64_t best = 0;
-  uint32_t best_l = 0;
-  const uint32_t lt_first = min_a == kNone ? rt + 1 : min_a / kTile + blockIdx.y;
-  for (uint32_t lt = lt_first; lt <= rt; lt += kSearchSplit) {  // ascending l
-    const uint32_t l0 = lt * kTile;
-    __syncthreads();  // the previous block's tile is no longer read
-    // stage T[r][l-1] for the block: rows r0.., columns l0-1 .. l0+62 (all at or left of the diagonal tile)
-    for (uint32_t e = threadIdx.x; e < kTile * kTile; e += blockDim.x) {
-      const uint32_t rr = e / kTile, ll = e % kTile;
-      const uint32_t gr = r0 + rr, gl = l0 + ll;  // gl = l; column wanted = l - 1
-      colT[rr][ll] = (gr < n && gl >= 1 && gl - 1 < n) ? T[(uint64_t)gr * n + (gl - 1)] : 0;
-    }
-    __syncthreads();
-    if (a_r == kNone) continue;
-#pragma unroll 4
+  uint32_t best_r = 0;
+  for (uint32_t rt = lt + blockIdx.y; rt < n_t; rt += kSearchSplit) {  // ascending r
+    const uint32_t min_a = tile_min_a[rt];  // kNone: every token of that tile is sensitive
+    if (min_a == kNone || min_a > l_last) break;  // it and every later r belong to segments that start after this tile
+    const uint32_t r_first = rt * kTile + quarter * (kTile / 4);
+    // everything this block needs is asked for before any of it is used: 16 table entries per lane, and the
+    // segment start and diagonal entry of the 16 rows in lanes 0..15 (handed round with readlane below)
+    uint32_t a_mine = kNone;
+    int64_t d_mine = 0;
+    if (r_first + (lane & 15) < n) a_mine = seg_a[r_first + (lane & 15)], d_mine = diag[r_first + (lane & 15)];
+    int64_t tv[kTile / 4];
+#pragma unroll
     for (uint32_t k = 0; k < kTile / 4; ++k) {
-      const uint32_t ll = grp * (kTile / 4) + k, l = l0 + ll;
-      if (l > r || l < a_r || r - l + 1 < min_len) continue;
-      const int64_t dl = l ? diag[l - 1] : 0;
-      const int64_t score = d_r + dl - 2 * colT[rl][ll];
-      if (!have || score > best) {  // l ascending: the smallest l stays on ties
+      const uint32_t r = r_first + k;
+      tv[k] = (r < n && l >= 1 && l <= r) ? col[(uint64_t)r * n] : 0;  // (entries outside r's segment are not used)
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < kTile / 4; ++k) {
+      const uint32_t r = r_first + k;  // the same for the whole wavefront
+      const uint32_t a_r = __builtin_amdgcn_readlane(a_mine, k);  // kNone: r is sensitive or past the end
+      const int64_t d_r = readlane_i64(d_mine, k);
+      if (a_r == kNone || l < a_r || l > r || r - l + 1 < min_len) continue;
+      const int64_t score = d_r + d_l - 2 * tv[k];
+      if (!have || score > best) {  // r ascending: the smallest r stays on ties
         have = true;
         best = score;
-        best_l = l;
+        best_r = r;
       }
     }
   }
-  // the four groups looked at different l for the same r: the larger score wins, then the smaller l
-  group_u[grp][rl] = have ? (uint64_t)best ^ kBias : 0;
-  group_l[grp][rl] = best_l;
+  // the four wavefronts looked at different r for the same l: the larger score wins, then the smaller r
+  group_u[quarter][lane] = have ? (uint64_t)best ^ kBias : 0;
+  group_r[quarter][lane] = best_r;
   __syncthreads();
-  if (grp == 0 && r < n) {
-    uint64_t u = group_u[0][rl];
-    uint32_t l = group_l[0][rl];
+  if (quarter == 0 && l < n) {
+    uint64_t u = group_u[0][lane];
+    uint32_t r = group_r[0][lane];
 #pragma unroll
     for (int g = 1; g < 4; ++g) {
-      const uint64_t ug = group_u[g][rl];
-      const uint32_t lg = group_l[g][rl];
-      if (ug > u || (ug == u && ug != 0 && lg < l)) u = ug, l = lg;
+      const uint64_t ug = group_u[g][lane];
+      const uint32_t rg = group_r[g][lane];
+      if (ug > u || (ug == u && ug != 0 && rg < r)) u = ug, r = rg;
     }
-    part_u[(uint64_t)blockIdx.y * n + r] = u;
-    part_l[(uint64_t)blockIdx.y * n + r] = l;
+    part_u[(uint64_t)blockIdx.y * n + l] = u;
+    part_r[(uint64_t)blockIdx.y * n + l] = r;
   }
 }
 
-// Per r: the best (score, l) over the kSearchSplit parts; the maximum score of r's segment (atomic max).
+// Per l: the best (score, r) over the kSearchSplit parts; the maximum score of l's segment (atomic max).
 __global__ __launch_bounds__(256) void annotate_best_score_kernel(uint32_t n, const uint32_t *__restrict__ seg_a,
                                                                   const uint64_t *__restrict__ part_u,
-                                                                  const uint32_t *__restrict__ part_l,
+                                                                  const uint32_t *__restrict__ part_r,
                                                                   uint64_t *__restrict__ cand_u,
-                                                                  uint32_t *__restrict__ cand_l, uint64_t *best_u) {
-  const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;  // no lane leaves early: the wavefront reduces together
+                                                                  uint32_t *__restrict__ cand_r, uint64_t *best_u) {
+  const uint32_t l = blockIdx.x * blockDim.x + threadIdx.x;  // no lane leaves early: the wavefront reduces together
   uint64_t u = 0;
   uint32_t a = kNone;
-  if (r < n) {
-    u = part_u[r];
-    uint32_t l = part_l[r];
+  if (l < n) {
+    u = part_u[l];
+    uint32_t r = part_r[l];
 #pragma unroll
     for (uint32_t y = 1; y < kSearchSplit; ++y) {
-      const uint64_t uy = part_u[(uint64_t)y * n + r];
-      const uint32_t ly = part_l[(uint64_t)y * n + r];
-      if (uy > u || (uy == u && uy != 0 && ly < l)) u = uy, l = ly;
+      const uint64_t uy = part_u[(uint64_t)y * n + l];
+      const uint32_t ry = part_r[(uint64_t)y * n + l];
+      if (uy > u || (uy == u && uy != 0 && ry < r)) u = uy, r = ry;
     }
-    cand_u[r] = u;
-    cand_l[r] = l;
-    a = seg_a[r];
+    cand_u[l] = u;
+    cand_r[l] = r;
+    a = seg_a[l];
   }
   if (a == kNone) u = 0;  // sensitive or past the end: nothing to report
   // One atomic per wavefront where all lanes that have a segment have the same one (the usual case), else one per lane.
@@ -520,16 +523,16 @@ __global__ __launch_bounds__(256) void annotate_best_score_kernel(uint32_t n, co
     atomicMax((unsigned long long *)&best_u[a], (unsigned long long)u);
   }
 }
-// Among the r whose best score is their segment's maximum: the smallest (l, r) (atomic min).
+// Among the l whose best score is their segment's maximum: the smallest (l, r) (atomic min).
 __global__ __launch_bounds__(256) void annotate_best_lr_kernel(uint32_t n, const uint32_t *__restrict__ seg_a,
                                                                const uint64_t *__restrict__ cand_u,
-                                                               const uint32_t *__restrict__ cand_l,
+                                                               const uint32_t *__restrict__ cand_r,
                                                                const uint64_t *__restrict__ best_u, uint64_t *best_lr) {
-  const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= n) return;
-  const uint32_t a = seg_a[r];
-  if (a == kNone || cand_u[r] == 0 || cand_u[r] != best_u[a]) return;
-  atomicMin((unsigned long long *)&best_lr[a], (unsigned long long)(((uint64_t)cand_l[r] << 32) | r));
+  const uint32_t l = blockIdx.x * blockDim.x + threadIdx.x;
+  if (l >= n) return;
+  const uint32_t a = seg_a[l];
+  if (a == kNone || cand_u[l] == 0 || cand_u[l] != best_u[a]) return;
+  atomicMin((unsigned long long *)&best_lr[a], (unsigned long long)(((uint64_t)l << 32) | cand_r[l]));
 }
 
 // Per token: the chosen substring of its segment, and d = inter - intra attention of its own row.
