@@ -234,21 +234,16 @@ __global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a
   const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
   if (x >= n_pad) return;
   int64_t run = 0;
-  uint32_t k = 0;
-  for (; k + 8 <= n_k; k += 8) {  // eight independent loads in flight
-    int64_t v[8];
+  constexpr int kBatch = 32;  // independent loads in flight: the walk down a column is latency, not bandwidth
+  for (uint32_t k = 0; k < n_k; k += kBatch) {
+    int64_t v[kBatch];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = a[(uint64_t)(k + u) * n_pad + x];
+    for (int u = 0; u < kBatch; ++u) v[u] = k + u < n_k ? a[(uint64_t)(k + u) * n_pad + x] : 0;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      a[(uint64_t)(k + u) * n_pad + x] = run;
+    for (int u = 0; u < kBatch; ++u) {
+      if (k + u < n_k) a[(uint64_t)(k + u) * n_pad + x] = run;
       run += v[u];
     }
-  }
-  for (; k < n_k; ++k) {
-    const int64_t v = a[(uint64_t)k * n_pad + x];
-    a[(uint64_t)k * n_pad + x] = run;
-    run += v;
   }
 }
 
