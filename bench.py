@@ -234,6 +234,7 @@ def main():
     ap.add_argument("--unroll", type=int, default=None, help="cp_tune key 3")
     ap.add_argument("--blocks-per-cu-rope", type=int, default=None, help="cp_tune key 4")
     ap.add_argument("--unroll-rope", type=int, default=None, help="cp_tune key 5")
+    ap.add_argument("--fanout", type=int, default=None, help="cp_tune key 6")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the side measurements (gather without read sharing, plain copy): used under the profiler")
     ap.add_argument("--calibrate", action="store_true",
@@ -256,7 +257,7 @@ def main():
         return annotator_bench(args)
 
     for key, val in enumerate([args.multicast, args.blocks_per_cu, args.nontemporal, args.unroll,
-                               args.blocks_per_cu_rope, args.unroll_rope]):
+                               args.blocks_per_cu_rope, args.unroll_rope, args.fanout]):
         if val is not None:
             cp.cp_tune(key, val)
 

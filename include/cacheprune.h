@@ -106,7 +106,9 @@ int32_t cp_last_hip_error(void);
  *   key 2: bit 0 non-temporal loads, bit 1 non-temporal stores
  *   key 3: 16-byte loads a lane issues before its first store (4 or 8)
  *   key 4: resident workgroups per compute unit for gathers that re-rotate keys
- *   key 5: key 3 for gathers that re-rotate keys (default 4) */
+ *   key 5: key 3 for gathers that re-rotate keys (default 4)
+ *   key 6: destinations written per pass over the rows of a slot that several tokens read
+ *          (1..16, default 16; fewer means the rows are fetched again, normally from cache) */
 int32_t cp_tune(int32_t key, uint32_t value);
 
 /* Timing hook for benchmarks: two hipEvent_t (host handles passed as void*, the

@@ -17,6 +17,7 @@ struct Tuning {
   uint32_t move_nontemporal = 2;     // bit 0: non-temporal loads, bit 1: non-temporal stores
   uint32_t move_unroll = 8;          // 16-byte loads a lane issues before its first store (4 or 8)
   uint32_t move_unroll_rope = 4;     // the same for gathers that re-rotate keys
+  uint32_t move_fanout = 16;         // destinations written per pass over a shared slot's rows (1..16)
   hipEvent_t gather_start = nullptr; // if set (cp_gather_events): recorded right before / after the
   hipEvent_t gather_stop = nullptr;  // gather's row-mover launch, on the call's stream
 };

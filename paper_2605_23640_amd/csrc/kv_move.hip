@@ -460,6 +460,7 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   const uint64_t max_units = (uint64_t)max_items * (ROPE ? 2 : 1);
   if (grid > max_units) grid = max_units;
   uint32_t fanout = kMaxFanout;
+  if (tn.move_fanout >= 1 && tn.move_fanout < fanout) fanout = tn.move_fanout;
   if (ROPE) {
     uint32_t cap = kTrigDoubles / (fl.head_dim / 2);
     if (fanout > cap) fanout = cap;
@@ -628,6 +629,7 @@ extern "C" int32_t cp_tune(int32_t key, uint32_t value) {
     case 3: t.move_unroll = value; return CP_OK;
     case 4: t.move_blocks_per_cu_rope = value; return CP_OK;
     case 5: t.move_unroll_rope = value; return CP_OK;
+    case 6: t.move_fanout = value; return CP_OK;
     default: return CP_ERR_INVALID_ARG;
   }
 }
