@@ -263,3 +263,32 @@ def test_verify_kernel_counts_real_differences(G):
     assert G.verify_rows(buf, lay, uids, 98) > 0.9 * n * L * 2 * H * D  # another seed: everything differs
     buf.view(torch.int16)[7] += 1  # a single flipped element is seen
     assert G.verify_rows(buf, lay, uids, 99) == 1
+
+
+def test_explicit_stream_and_two_pools_side_by_side(G):
+    """Every call takes the caller's stream: the same lookup issued on a stream of its own, while another pool's
+    lookup runs on a second stream, gives what the default stream gives (the library keeps no state between
+    calls apart from the launch-shape knobs; each pool has its own scratch)."""
+    import paper_2605_23640_amd as cp
+
+    wl = gen.make_docs("streams", 0xC0FFEE0E, gen.KVShape(4, 2, 64), R=3, T=900, prefix_len=200, n_docs=6,
+                       doc_len=(100, 200), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096)
+    st_a = G.prefill(wl, G.make_pool(wl, anchor_window=8, verify=True, min_len=4))
+    st_b = G.prefill(wl, G.make_pool(wl))
+    want_a, want_b = G.lookup(st_a), G.lookup(st_b)  # default stream
+    N, sh = wl.n_tokens, wl.shape
+    tok, mask, off = G.dev_i32(wl.tok), torch.from_numpy(wl.mask.copy()).to(G.DEV), G.dev_i32(wl.off)
+    bufs = [cp.LookupBuffers(N, N, G.DEV, n_pool_slots=st.pool.n_slots) for st in (st_a, st_b)]
+    dsts = [G.poison_tensor(N * sh.tok_bytes) for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]  # default priority
+    torch.cuda.synchronize()
+    for _ in range(3):  # interleaved launches on the two streams
+        for st, buf, dst, s in zip((st_a, st_b), bufs, dsts, streams):
+            st.pool.lookup(tok, mask, off, dst, buf, stream=s)
+    for s in streams:
+        s.synchronize()
+    for want, buf, dst, st in zip((want_a, want_b), bufs, dsts, (st_a, st_b)):
+        assert np.array_equal(G.host_u32(buf.slot), want.slot)
+        assert np.array_equal(G.host_u32(buf.served if st.pool.filters else buf.slot), want.served)
+        assert np.array_equal(G.dst_as_rows(dst, sh, N), G.dst_as_rows(want.dst, sh, N))
+        assert int(st.pool.flags.item()) == 0
