@@ -228,13 +228,12 @@ def main():
     ap.add_argument("--annotator", type=int, default=0, metavar="N",
                     help="side benchmark: run the KV annotator on one N x N attention matrix instead of the KV path")
     ap.add_argument("--cpu-requests", type=int, default=16, help="requests in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--multicast", type=int, default=None, help="cp_tune key 0")
-    ap.add_argument("--blocks-per-cu", type=int, default=None, help="cp_tune key 1")
-    ap.add_argument("--nontemporal", type=int, default=None, help="cp_tune key 2")
-    ap.add_argument("--unroll", type=int, default=None, help="cp_tune key 3")
-    ap.add_argument("--blocks-per-cu-rope", type=int, default=None, help="cp_tune key 4")
-    ap.add_argument("--unroll-rope", type=int, default=None, help="cp_tune key 5")
-    ap.add_argument("--fanout", type=int, default=None, help="cp_tune key 6")
+    # launch options of the row mover (cp_launch_opts; 0 = the library's default)
+    ap.add_argument("--read-sharing", type=int, default=0, help="1 = tokens reading one slot share the read, 2 = not")
+    ap.add_argument("--blocks-per-cu", type=int, default=0, help="resident workgroups per compute unit")
+    ap.add_argument("--nontemporal", type=int, default=0, help="1 + (bit 0: non-temporal loads, bit 1: stores)")
+    ap.add_argument("--loads-in-flight", type=int, default=0, help="16-byte loads per lane before the first store")
+    ap.add_argument("--fanout", type=int, default=0, help="destinations written per pass over a shared slot")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the side measurements (gather without read sharing, plain copy): used under the profiler")
     ap.add_argument("--calibrate", action="store_true",
@@ -256,10 +255,8 @@ def main():
     if args.annotator:
         return annotator_bench(args)
 
-    for key, val in enumerate([args.multicast, args.blocks_per_cu, args.nontemporal, args.unroll,
-                               args.blocks_per_cu_rope, args.unroll_rope, args.fanout]):
-        if val is not None:
-            cp.cp_tune(key, val)
+    opts = cp.binding.LaunchOpts(args.read_sharing, args.blocks_per_cu, args.nontemporal, args.loads_in_flight,
+                                 args.fanout)
 
     t0 = time.time()
     wl = gen.make(args.workload)
@@ -275,7 +272,7 @@ def main():
         rec = (wl.donor_u < args.recompute).astype(np.uint8)
     gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window, verify=args.verify, min_len=args.min_len,
                                     recompute_marks=rec is not None, zero_fill=args.zero_fill, lru=args.lru,
-                                    pool_layout=args.pool_layout),
+                                    pool_layout=args.pool_layout, gather_opts=opts, insert_opts=opts),
                     recompute=rec)
     pool = gst.pool
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
@@ -289,17 +286,18 @@ def main():
     if pool.slot_anchor is not None:
         anchor0 = pool.slot_anchor.clone()
     K = args.steps
-    hev = cp.binding.HipEvents(2 * K + 2)  # pairs around the gather's mover kernel, on the launch stream
+    # hipEvent pairs that the library records around its two row-mover kernels (gather, scatter), on the launch stream
+    hev = cp.binding.HipEvents(4 * K + 2)
     ev_ins = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
 
     def step(k=None):
-        if k is not None:
-            cp.binding.cp_gather_events(hev.ev[2 * k], hev.ev[2 * k + 1])
-        pool.lookup(tok, mask, off, dst, buf)
+        pool.lookup(tok, mask, off, dst, buf,
+                    gather_opts=None if k is None else opts.with_events(hev.ev[4 * k], hev.ev[4 * k + 1]))
         if k is not None:
             ev_ins[k][0].record()
         pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False,
-                    run_off_buf=buf.run_off)
+                    run_off_buf=buf.run_off,
+                    insert_opts=None if k is None else opts.with_events(hev.ev[4 * k + 2], hev.ev[4 * k + 3]))
         if k is not None:
             ev_ins[k][1].record()
         pool.table.keys.copy_(keys0, non_blocking=True)
@@ -315,7 +313,6 @@ def main():
         step(k)
     torch.cuda.synchronize()
     t_total = time.perf_counter() - t_start
-    cp.binding.cp_gather_events(None, None)
 
     n_spans = int(buf.n_spans.item())
     matched = int(buf.span_off[n_spans].item())
@@ -323,33 +320,33 @@ def main():
     flags = int(pool.flags.item())
     slots = G.host_u32(buf.served if pool.filters else buf.slot)
     unique_src = int(len(np.unique(slots[slots != 0xFFFFFFFF])))
-    gather_ms = float(np.mean([hev.elapsed_ms(2 * k, 2 * k + 1) for k in range(K)]))
-    insert_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_ins]))
+    gather_ms = float(np.mean([hev.elapsed_ms(4 * k, 4 * k + 1) for k in range(K)]))
+    insert_ms = float(np.mean([a.elapsed_time(b) for a, b in ev_ins]))  # the whole cp_insert_kv call
+    scatter_ms = float(np.mean([hev.elapsed_ms(4 * k + 2, 4 * k + 3) for k in range(K)])) if inserted else None
     ms_per_step = t_total / K * 1e3
     gather_bytes = 2.0 * sh.tok_bytes * matched  # algorithmic: every reused row read once and written once
     step_bytes = 2.0 * sh.tok_bytes * (matched + inserted)
     gather_gbps = gather_bytes / (gather_ms * 1e-3) / 1e9
 
-    def gather_alone(reps=5):
+    def gather_alone(o, reps=5):
         """cp_gather_kv alone on the spans of the last step; returns ms of its mover kernel."""
         ms = []
+        o = o.with_events(hev.ev[4 * K], hev.ev[4 * K + 1])
         for r in range(reps + 1):
-            cp.binding.cp_gather_events(hev.ev[2 * K], hev.ev[2 * K + 1])
             cp.cp_gather_kv(pool.pool, pool.layout, pool.n_slots, dst, pool.request_layout(N), N, buf.span_src,
                             buf.span_dst, buf.span_len, buf.span_delta if pool.rope is not None else None,
-                            buf.span_off, buf.n_spans, buf.max_spans, pool.rope, pool.flags, buf.scratch)
+                            buf.span_off, buf.n_spans, buf.max_spans, pool.rope, pool.flags, buf.scratch, opts=o)
             torch.cuda.synchronize()
             if r:
-                ms.append(hev.elapsed_ms(2 * K, 2 * K + 1))
-        cp.binding.cp_gather_events(None, None)
+                ms.append(hev.elapsed_ms(4 * K, 4 * K + 1))
         return float(np.mean(ms))
 
     # the same gather with every token reading its own copy of the source rows (no sharing of reads)
     own_read_ms = None
     if not args.no_extras:
-        cp.cp_tune(0, 0)
-        own_read_ms = gather_alone()
-        cp.cp_tune(0, 1 if args.multicast is None else args.multicast)
+        own = opts.with_events(None, None)
+        own.read_sharing = 2
+        own_read_ms = gather_alone(own)
 
     # the retriever's share alone: hashing, table lookups, (verification, filters,) span building; no KV moved
     front_ms = None

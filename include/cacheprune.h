@@ -18,7 +18,8 @@
  *     calls on one stream runs in order.
  *   - Unless a parameter says "host", every pointer is a DEVICE pointer owned
  *     by the caller.  The library allocates and frees nothing and keeps no state
- *     besides the last HIP error code.
+ *     between calls besides each host thread's last HIP error code: every option
+ *     of a call is an argument of that call.
  *   - `scratch` is caller-provided device memory of at least
  *     cp_scratch_bytes(N, max_spans, n_pool_slots) bytes, 256-byte aligned, whose contents are
  *     meaningless between calls; calls that share a scratch buffer must be on
@@ -98,25 +99,25 @@ size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots);
 /* hipError_t of the last failed launch of this thread's calls (0 = none). */
 int32_t cp_last_hip_error(void);
 
-/* Launch-shape knobs of the row mover behind cp_gather_kv / cp_insert_kv (host
- * state, process wide; results never depend on them).
- *   key 0: 1 (default) = tokens of one call that read the same pool slot share one
- *          read of it ("read once, write many"); 0 = every token reads for itself
- *   key 1: resident workgroups per compute unit
- *   key 2: bit 0 non-temporal loads, bit 1 non-temporal stores
- *   key 3: 16-byte loads a lane issues before its first store (4 or 8)
- *   key 4: resident workgroups per compute unit for gathers that re-rotate keys
- *   key 5: key 3 for gathers that re-rotate keys (default 4)
- *   key 6: destinations written per pass over the rows of a slot that several tokens read
- *          (1..16, default 16; fewer means the rows are fetched again, normally from cache) */
-int32_t cp_tune(int32_t key, uint32_t value);
-
-/* Timing hook for benchmarks: two hipEvent_t (host handles passed as void*, the
- * caller creates and destroys them) that every following cp_gather_kv records
- * on its stream right before and right after its row-mover kernel, so that the
- * kernel can be timed apart from the small set-up kernels of the call.
- * NULL, NULL switches the hook off.  Host state, process wide. */
-int32_t cp_gather_events(void *start_event, void *stop_event);
+/* Launch options of the row mover behind cp_gather_kv / cp_insert_kv* (the one kernel of a call
+ * that is bound by HBM).  Passed per call as a HOST pointer that is read before the call returns;
+ * NULL, or a zeroed struct, means the defaults.  Results never depend on these options.
+ *   read_sharing     0/1 = tokens of one gather that read the same pool slot share one read of it
+ *                    ("read once, write many"; the default), 2 = every token reads for itself
+ *   blocks_per_cu    resident workgroups per compute unit (0 = default)
+ *   nontemporal      0 = default, else 1 + (bit 0: non-temporal loads, bit 1: non-temporal stores)
+ *   loads_in_flight  16-byte loads a lane issues before its first store (0 = default, 4 or 8)
+ *   fanout           destinations written per pass over the rows of a shared slot (0 = default 16,
+ *                    1..16; fewer means the rows are fetched again, normally from cache)
+ *   start_event, stop_event   two hipEvent_t (host handles as void*, created and destroyed by the
+ *                    caller; NULL = none) recorded on the call's stream right before and right
+ *                    after the row-mover kernel, so that a benchmark can time it apart from the
+ *                    small set-up kernels of the call. */
+typedef struct {
+  uint32_t read_sharing, blocks_per_cu, nontemporal, loads_in_flight, fanout;
+  uint32_t reserved[3]; /* must be 0 */
+  void *start_event, *stop_event;
+} cp_launch_opts;
 
 /* hipEvent helpers for callers without their own HIP binding: create a timing
  * event (NULL on failure), milliseconds between two recorded events (negative
@@ -211,7 +212,7 @@ int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, c
                            const uint32_t *free_slots, uint32_t n_free, const void *src, cp_kv_layout src_l,
                            void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, int32_t *slot_pos,
                            uint32_t *slot_tok, uint32_t *slot_parent, uint32_t *slot_out, uint32_t *n_inserted,
-                           uint32_t *status_flags, void *scratch, size_t scratch_bytes);
+                           uint32_t *status_flags, void *scratch, size_t scratch_bytes, const cp_launch_opts *opts);
 int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand, uint32_t N,
                         const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots, int32_t merge,
                         uint32_t *slot_out, uint32_t *stream_out, void *scratch, size_t scratch_bytes);
@@ -248,12 +249,13 @@ int32_t cp_build_spans(void *stream, const uint32_t *slot, const uint32_t *off, 
  * cp_build_spans produced.  Spans must not overlap in dst.  pool_l and dst_l must agree on n_layers, n_kv_heads and head_dim;
  * rotation needs head_dim a power of two in [16, 512].  The pool holds
  * n_pool_slots slots and dst n_dst_tokens tokens: a token of a span that falls
- * outside either is skipped and CP_FLAG_BAD_INDEX is set. */
+ * outside either is skipped and CP_FLAG_BAD_INDEX is set.  opts: see cp_launch_opts (may be NULL). */
 int32_t cp_gather_kv(void *stream, const void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, void *dst,
                      cp_kv_layout dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
                      const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
                      const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
-                     const cp_rope *rope, uint32_t *status_flags, void *scratch, size_t scratch_bytes);
+                     const cp_rope *rope, uint32_t *status_flags, void *scratch, size_t scratch_bytes,
+                     const cp_launch_opts *opts);
 
 /* Insert-if-absent with the matching scatter (post-inference storing, Sec. 4.1
  * "Workflow"; one copy of a duplicate, Sec. 4.3.5 "Lifecycle management").
@@ -270,12 +272,13 @@ int32_t cp_gather_kv(void *stream, const void *pool, cp_kv_layout pool_l, uint32
  * were dropped is unspecified: size the table for the keys it must hold.
  *   slot_out [N]: slot holding each token's key after the call, CP_SLOT_NONE
  *                 for sensitive or dropped tokens.
- *   *n_inserted (device): number of tokens stored by this call. */
+ *   *n_inserted (device): number of tokens stored by this call.
+ *   opts: launch options of the scatter (may be NULL); read_sharing and fanout do not apply. */
 int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
                      uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
                      cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
                      int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
-                     void *scratch, size_t scratch_bytes);
+                     void *scratch, size_t scratch_bytes, const cp_launch_opts *opts);
 
 /* ---- Pool policies -----------------------------------------------------------------------------
  * All arrays are device memory owned by the caller; scratch as for the other calls

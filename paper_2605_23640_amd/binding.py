@@ -27,8 +27,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH = 0, -1, -2, -3, -4
 FLAG_SPANS_OVERFLOW, FLAG_POOL_FULL, FLAG_TABLE_FULL, FLAG_BAD_INDEX = 1, 2, 4, 8
 
 EXPORTS = [
-    "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_tune", "cp_table_init",
-    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv", "cp_gather_events",
+    "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_table_init",
+    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
     "cp_insert_kv_chain", "cp_verify_chain",
@@ -78,6 +78,20 @@ class Rope(C.Structure):
     _fields_ = [("theta", C.c_double), ("style", C.c_uint32)]
 
 
+class LaunchOpts(C.Structure):
+    """``cp_launch_opts``: per-call launch options of the row mover; zero = default everywhere."""
+
+    _fields_ = [("read_sharing", C.c_uint32), ("blocks_per_cu", C.c_uint32), ("nontemporal", C.c_uint32),
+                ("loads_in_flight", C.c_uint32), ("fanout", C.c_uint32), ("reserved", C.c_uint32 * 3),
+                ("start_event", C.c_void_p), ("stop_event", C.c_void_p)]
+
+    def with_events(self, start, stop):
+        """A copy that also asks for the two hipEvent_t handles to be recorded around the mover kernel."""
+        o = LaunchOpts(self.read_sharing, self.blocks_per_cu, self.nontemporal, self.loads_in_flight, self.fanout)
+        o.start_event, o.stop_event = start, stop
+        return o
+
+
 _lib = None
 
 
@@ -95,10 +109,6 @@ def lib():
         L.cp_scratch_bytes.restype = sz
         L.cp_scratch_bytes.argtypes = [u32, u32, u32]
         L.cp_last_hip_error.restype = i32
-        L.cp_tune.restype = i32
-        L.cp_tune.argtypes = [i32, u32]
-        L.cp_gather_events.restype = i32
-        L.cp_gather_events.argtypes = [vp, vp]
         L.cp_table_init.restype = i32
         L.cp_table_init.argtypes = [vp, TableStruct]
         L.cp_hash_segments.restype = i32
@@ -113,7 +123,7 @@ def lib():
         L.cp_hash_floating.argtypes = [vp, TableStruct, vp, u32, vp, vp, u32, u64, u32, vp, vp, vp, sz]
         L.cp_insert_kv_chain.restype = i32
         L.cp_insert_kv_chain.argtypes = [vp, TableStruct, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
-                                         u32, vp, vp, vp, vp, vp, vp, vp, sz]
+                                         u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_verify_chain.restype = i32
         L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, vp, sz]
         L.cp_filter_matches.restype = i32
@@ -141,10 +151,11 @@ def lib():
         L.cp_build_spans.restype = i32
         L.cp_build_spans.argtypes = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_gather_kv.restype = i32
-        L.cp_gather_kv.argtypes = [vp, vp, KVLayout, u32, vp, KVLayout, u32, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, sz]
+        L.cp_gather_kv.argtypes = [vp, vp, KVLayout, u32, vp, KVLayout, u32, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, sz,
+                                   vp]
         L.cp_insert_kv.restype = i32
         L.cp_insert_kv.argtypes = [vp, TableStruct, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout, u32, vp, vp,
-                                   vp, vp, vp, sz]
+                                   vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -178,13 +189,8 @@ def cp_scratch_bytes(N, max_spans=0, n_pool_slots=0):
     return int(lib().cp_scratch_bytes(int(N), int(max_spans), int(n_pool_slots)))
 
 
-def cp_tune(key, value):
-    _check("cp_tune", lib().cp_tune(int(key), int(value)))
-
-
-def cp_gather_events(start_event, stop_event):
-    """hipEvent_t handles (ints / c_void_p, or None) recorded around the gather's row-mover kernel."""
-    _check("cp_gather_events", lib().cp_gather_events(start_event, stop_event))
+def _opts(opts):
+    return None if opts is None else C.byref(opts)
 
 
 class HipEvents:
@@ -293,7 +299,7 @@ def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, mer
 
 def cp_insert_kv_chain(table: Table, hashes, tok, run_off, off, free_slots, n_free, src, src_l: KVLayout, pool,
                        pool_l: KVLayout, n_pool_slots, slot_pos, slot_tok, slot_parent, slot_out, n_inserted,
-                       status_flags, scratch, stream=None):
+                       status_flags, scratch, stream=None, opts: LaunchOpts | None = None):
     _need_cuda(hashes, tok, run_off, off, free_slots, src, pool, slot_pos, slot_tok, slot_parent, slot_out, n_inserted,
                status_flags, scratch)
     N, R = hashes.numel(), off.numel() - 1
@@ -303,7 +309,7 @@ def cp_insert_kv_chain(table: Table, hashes, tok, run_off, off, free_slots, n_fr
     _check("cp_insert_kv_chain", lib().cp_insert_kv_chain(
         _stream(stream), table.struct, _ptr(hashes), _ptr(tok), _ptr(run_off), _ptr(off), N, R, _ptr(free_slots),
         n_free, _ptr(src), src_l, _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_tok), _ptr(slot_parent),
-        _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags), _ptr(scratch), scratch.numel()))
+        _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags), _ptr(scratch), scratch.numel(), _opts(opts)))
 
 
 def cp_filter_matches(slot_in, off, min_len, slot_recompute, n_pool_slots, slot_out, scratch, stream=None):
@@ -417,21 +423,22 @@ def cp_build_spans(slot, off, slot_pos, max_spans, span_src, span_dst, span_len,
 
 def cp_gather_kv(pool, pool_l: KVLayout, n_pool_slots, dst, dst_l: KVLayout, n_dst_tokens, span_src, span_dst,
                  span_len, span_delta, span_off, n_spans, max_spans, rope: Rope | None, status_flags, scratch,
-                 stream=None):
+                 stream=None, opts: LaunchOpts | None = None):
     _need_cuda(pool, dst, span_src, span_dst, span_len, span_delta, span_off, n_spans, status_flags, scratch)
     _check("cp_gather_kv", lib().cp_gather_kv(
         _stream(stream), _ptr(pool), pool_l, n_pool_slots, _ptr(dst), dst_l, n_dst_tokens, _ptr(span_src),
         _ptr(span_dst), _ptr(span_len), _ptr(span_delta), _ptr(span_off), _ptr(n_spans), max_spans,
         C.byref(rope) if rope is not None else None, _ptr(status_flags), _ptr(scratch),
-        scratch.numel() if scratch is not None else 0))
+        scratch.numel() if scratch is not None else 0, _opts(opts)))
 
 
 def cp_insert_kv(table: Table, hashes, off, free_slots, n_free, src, src_l: KVLayout, pool, pool_l: KVLayout,
-                 n_pool_slots, slot_pos, slot_out, n_inserted, status_flags, scratch, stream=None):
+                 n_pool_slots, slot_pos, slot_out, n_inserted, status_flags, scratch, stream=None,
+                 opts: LaunchOpts | None = None):
     _need_cuda(hashes, off, free_slots, src, pool, slot_pos, slot_out, n_inserted, status_flags, scratch)
     N, R = hashes.numel(), off.numel() - 1
     assert slot_out.numel() == N and (free_slots is None or free_slots.numel() >= n_free)
     _check("cp_insert_kv", lib().cp_insert_kv(
         _stream(stream), table.struct, _ptr(hashes), _ptr(off), N, R, _ptr(free_slots), n_free, _ptr(src), src_l,
         _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags),
-        _ptr(scratch), scratch.numel()))
+        _ptr(scratch), scratch.numel(), _opts(opts)))

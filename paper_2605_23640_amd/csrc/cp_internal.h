@@ -9,19 +9,18 @@
 
 namespace cp {
 
-// Tunables (set through cp_tune; defaults chosen from measurements on MI355X).
-struct Tuning {
-  uint32_t move_multicast = 1;       // 1: tokens that read the same pool slot are served by one read
-  uint32_t move_blocks_per_cu = 2;   // resident workgroups per compute unit for the row mover
-  uint32_t move_blocks_per_cu_rope = 4;  // the same for gathers that re-rotate keys: as many as their registers let a unit hold
-  uint32_t move_nontemporal = 2;     // bit 0: non-temporal loads, bit 1: non-temporal stores
-  uint32_t move_unroll = 8;          // 16-byte loads a lane issues before its first store (4 or 8)
-  uint32_t move_unroll_rope = 4;     // the same for gathers that re-rotate keys
-  uint32_t move_fanout = 16;         // destinations written per pass over a shared slot's rows (1..16)
-  hipEvent_t gather_start = nullptr; // if set (cp_gather_events): recorded right before / after the
-  hipEvent_t gather_stop = nullptr;  // gather's row-mover launch, on the call's stream
+// Launch options of the row mover, resolved from a call's cp_launch_opts (defaults chosen from
+// measurements on MI355X).  Held by value for the duration of one call; nothing is process wide.
+struct MoveOpts {
+  bool share_reads;         // tokens that read the same pool slot are served by one read
+  uint32_t blocks_per_cu;   // resident workgroups per compute unit
+  uint32_t nontemporal;     // bit 0: non-temporal loads, bit 1: non-temporal stores
+  uint32_t loads_in_flight; // 16-byte loads a lane issues before its first store (4 or 8)
+  uint32_t fanout;          // destinations written per pass over a shared slot's rows (1..16)
+  hipEvent_t start, stop;   // recorded right before / after the row-mover launch, if not null
 };
-Tuning &tuning();
+// opts may be null (defaults); false if a field holds a value outside its documented range.
+bool resolve_opts(const cp_launch_opts *opts, bool rotating, MoveOpts *out);
 
 // Bump allocator over the caller's scratch buffer (256-byte aligned pieces).
 struct Scratch {
@@ -59,7 +58,8 @@ struct alignas(16) MoveItem {
 // and flagged.
 int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &src_l, uint32_t n_src_tokens,
                        void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, const MoveItem *items,
-                       const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags);
+                       const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags,
+                       const MoveOpts &mo);
 
 // Exclusive prefix sums of span_len[0 .. *n_spans) into span_off[0 .. *n_spans],
 // agg = div_up(max_spans, 1024) + 1 words of scratch.

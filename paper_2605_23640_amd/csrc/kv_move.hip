@@ -35,9 +35,25 @@
 
 namespace cp {
 
-Tuning &tuning() {
-  static Tuning t;
-  return t;
+bool resolve_opts(const cp_launch_opts *o, bool rotating, MoveOpts *out) {
+  // defaults: the copy form runs best with 2 workgroups per unit and 8 loads in flight; the rotating
+  // form needs its registers for arithmetic and hides latency with more workgroups instead
+  MoveOpts m{true, rotating ? 4u : 2u, 2u, rotating ? 4u : 8u, 16u, nullptr, nullptr};
+  if (o) {
+    if (o->read_sharing > 2 || o->blocks_per_cu > 64 || o->nontemporal > 4 || o->fanout > 16) return false;
+    if (o->loads_in_flight != 0 && o->loads_in_flight != 4 && o->loads_in_flight != 8) return false;
+    if (o->reserved[0] | o->reserved[1] | o->reserved[2]) return false;
+    if ((o->start_event == nullptr) != (o->stop_event == nullptr)) return false;
+    if (o->read_sharing == 2) m.share_reads = false;
+    if (o->blocks_per_cu) m.blocks_per_cu = o->blocks_per_cu;
+    if (o->nontemporal) m.nontemporal = o->nontemporal - 1;
+    if (o->loads_in_flight) m.loads_in_flight = o->loads_in_flight;
+    if (o->fanout) m.fanout = o->fanout;
+    m.start = (hipEvent_t)o->start_event;
+    m.stop = (hipEvent_t)o->stop_event;
+  }
+  *out = m;
+  return true;
 }
 
 int32_t &last_hip_error() {
@@ -228,6 +244,17 @@ __device__ __forceinline__ u32x4 rotate_pairs(const Pairs4 &p, const Trig4 &t, b
   }
   return u32x4{f64x2_to_bf16x2(y1[0], y2[0]), f64x2_to_bf16x2(y1[1], y2[1]), f64x2_to_bf16x2(y1[2], y2[2]),
                f64x2_to_bf16x2(y1[3], y2[3])};
+}
+
+// Scratch bytes any call needs: tile totals (at most 32 bytes each), four per-token words (insert),
+// one 16-byte descriptor per token (gather, insert) and two flag bytes per token (floating anchors,
+// chain-recording insert), span offsets, one chain head per pool slot, the cos/sin digit tables;
+// pieces padded to 256 bytes.
+constexpr size_t scratch_bytes_for(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots) {
+  const uint64_t n = N > max_spans ? N : max_spans;
+  return (size_t)(((n + kScanTile - 1) / kScanTile + 2) * 32 + (4ull * 4 + 16 + 2) * N +
+                  4ull * ((uint64_t)max_spans + 1) + 4ull * n_pool_slots +
+                  (size_t)kTrigLevels * kTrigDigit * kMaxHalfDim * 16 + 16 * 256);
 }
 
 // ---- gather front end: clear the per-slot chain heads, expand spans, link chains -------------
@@ -452,15 +479,14 @@ uint32_t cu_count() {
 template <class RA, bool ROPE, bool GATHER>
 int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n_items, uint32_t max_items,
                     const uint32_t *head, uint32_t *counter, const void *from, const cp_kv_layout &fl, uint32_t n_from,
-                    void *to, const cp_kv_layout &tl, uint32_t n_to, uint32_t *status_flags, const RA &rope) {
+                    void *to, const cp_kv_layout &tl, uint32_t n_to, uint32_t *status_flags, const RA &rope,
+                    const MoveOpts &mo) {
   if (max_items == 0) return CP_OK;
-  const Tuning &tn = tuning();
-  uint32_t bpc = ROPE ? tn.move_blocks_per_cu_rope : tn.move_blocks_per_cu;
-  uint64_t grid = (uint64_t)cu_count() * (bpc ? bpc : 2);
+  if (mo.start && hipEventRecord(mo.start, stream) != hipSuccess) return CP_ERR_HIP;
+  uint64_t grid = (uint64_t)cu_count() * mo.blocks_per_cu;
   const uint64_t max_units = (uint64_t)max_items * (ROPE ? 2 : 1);
   if (grid > max_units) grid = max_units;
-  uint32_t fanout = kMaxFanout;
-  if (tn.move_fanout >= 1 && tn.move_fanout < fanout) fanout = tn.move_fanout;
+  uint32_t fanout = mo.fanout < kMaxFanout ? mo.fanout : kMaxFanout;
   if (ROPE) {
     uint32_t cap = kTrigDoubles / (fl.head_dim / 2);
     if (fanout > cap) fanout = cap;
@@ -474,57 +500,46 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   else                                                                                                       \
     scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                \
         items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope)
-  const uint32_t nt = tn.move_nontemporal & 3u;
-  if constexpr (ROPE) {  // rotation defaults to the short form: it needs the registers
-    switch (nt | (tn.move_unroll_rope >= 8 ? 4u : 0u)) {
-      case 0: CP_LAUNCH(false, false, 4); break;
-      case 1: CP_LAUNCH(true, false, 4); break;
-      case 2: CP_LAUNCH(false, true, 4); break;
-      case 3: CP_LAUNCH(true, true, 4); break;
-      case 4: CP_LAUNCH(false, false, 8); break;
-      case 5: CP_LAUNCH(true, false, 8); break;
-      case 6: CP_LAUNCH(false, true, 8); break;
-      default: CP_LAUNCH(true, true, 8); break;
-    }
-  } else {
-    switch (nt | (tn.move_unroll >= 8 ? 4u : 0u)) {
-      case 0: CP_LAUNCH(false, false, 4); break;
-      case 1: CP_LAUNCH(true, false, 4); break;
-      case 2: CP_LAUNCH(false, true, 4); break;
-      case 3: CP_LAUNCH(true, true, 4); break;
-      case 4: CP_LAUNCH(false, false, 8); break;
-      case 5: CP_LAUNCH(true, false, 8); break;
-      case 6: CP_LAUNCH(false, true, 8); break;
-      default: CP_LAUNCH(true, true, 8); break;
-    }
+  switch ((mo.nontemporal & 3u) | (mo.loads_in_flight >= 8 ? 4u : 0u)) {
+    case 0: CP_LAUNCH(false, false, 4); break;
+    case 1: CP_LAUNCH(true, false, 4); break;
+    case 2: CP_LAUNCH(false, true, 4); break;
+    case 3: CP_LAUNCH(true, true, 4); break;
+    case 4: CP_LAUNCH(false, false, 8); break;
+    case 5: CP_LAUNCH(true, false, 8); break;
+    case 6: CP_LAUNCH(false, true, 8); break;
+    default: CP_LAUNCH(true, true, 8); break;
   }
 #undef CP_LAUNCH
-  return check_launch();
+  if (int32_t rc = check_launch()) return rc;
+  if (mo.stop && hipEventRecord(mo.stop, stream) != hipSuccess) return CP_ERR_HIP;
+  return CP_OK;
 }
 
 }  // namespace
 
 int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &src_l, uint32_t n_src_tokens,
                        void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, const MoveItem *items,
-                       const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags) {
+                       const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags,
+                       const MoveOpts &mo) {
   NoRope none{};
   return launch_move<NoRope, false, false>(stream, items, n_items, max_items, nullptr, counter, src, src_l, n_src_tokens, pool,
-                                    pool_l, n_pool_slots, status_flags, none);
+                                    pool_l, n_pool_slots, status_flags, none, mo);
 }
 
 }  // namespace cp
 
-extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, void *dst,
-                                cp_kv_layout dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
-                                const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
-                                const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
-                                const cp_rope *rope, uint32_t *status_flags, void *scratch, size_t scratch_bytes) {
-  using namespace cp;
-  hipStream_t stream = (hipStream_t)stream_;
-  if (max_spans == 0 || n_dst_tokens == 0 || n_pool_slots == 0) return CP_OK;
+namespace cp {
+namespace {
+
+int32_t gather_impl(hipStream_t stream, const void *pool, const cp_kv_layout &pool_l, uint32_t n_pool_slots, void *dst,
+                    const cp_kv_layout &dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
+                    const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
+                    const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans, const cp_rope *rope,
+                    uint32_t *status_flags, void *work, size_t work_bytes, const cp_launch_opts *opts) {
   if (n_dst_tokens >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (!pool || !dst || !span_src || !span_dst || !span_len || !n_spans || !status_flags) return CP_ERR_INVALID_ARG;
-  if (!scratch || !aligned(scratch, 256) || !aligned(pool, 16) || !aligned(dst, 16)) return CP_ERR_INVALID_ARG;
+  if (!aligned(pool, 16) || !aligned(dst, 16)) return CP_ERR_INVALID_ARG;
   if (!layout_ok(pool_l) || !layout_ok(dst_l) || !layouts_match(pool_l, dst_l)) return CP_ERR_UNSUPPORTED;
   const bool use_rope = rope != nullptr && span_delta != nullptr;
   if (use_rope) {
@@ -533,13 +548,15 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
     if (D < 16 || D > 2 * kMaxHalfDim || (D & (D - 1))) return CP_ERR_UNSUPPORTED;
     if (rope->style > 1 || !(rope->theta > 0.0)) return CP_ERR_INVALID_ARG;
   }
-  if (scratch_bytes < cp_scratch_bytes(n_dst_tokens, max_spans, n_pool_slots)) return CP_ERR_SCRATCH;
-  Scratch sc(scratch, scratch_bytes);
+  MoveOpts mo;
+  if (!resolve_opts(opts, use_rope, &mo)) return CP_ERR_INVALID_ARG;
+  if (work_bytes < scratch_bytes_for(n_dst_tokens, max_spans, n_pool_slots)) return CP_ERR_SCRATCH;
+  Scratch sc(work, work_bytes);
   uint32_t *agg = sc.take<uint32_t>(div_up(max_spans, kScanTile) + 1);
   uint32_t *offs = sc.take<uint32_t>((size_t)max_spans + 1);
   uint32_t *counters = sc.take<uint32_t>(2);  // [0] work counter, [1] item count
   MoveItem *items = sc.take<MoveItem>(n_dst_tokens);
-  const bool group = tuning().move_multicast != 0;
+  const bool group = mo.share_reads;
   uint32_t *head = group ? sc.take<uint32_t>(n_pool_slots) : nullptr;
   double2 *tables = use_rope ? sc.take<double2>((size_t)kTrigLevels * kTrigDigit * (pool_l.head_dim / 2)) : nullptr;
   if (!agg || !offs || !counters || !items || (group && !head) || (use_rope && !tables)) return CP_ERR_SCRATCH;
@@ -560,28 +577,33 @@ extern "C" int32_t cp_gather_kv(void *stream_, const void *pool, cp_kv_layout po
       span_src, span_dst, span_off, use_rope ? span_delta : nullptr, n_spans, max_spans, n_pool_slots, n_dst_tokens,
       items, head, counters + 1, status_flags);
   if (int32_t rc = check_launch()) return rc;
-  const Tuning &tn = tuning();
-  if (tn.gather_start && hipEventRecord(tn.gather_start, stream) != hipSuccess) return CP_ERR_HIP;
-  int32_t rc;
-  if (use_rope && rope->style == 0) {
-    rc = launch_move<RopeArg<0>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                             n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<0>{tables});
-  } else if (use_rope) {
-    rc = launch_move<RopeArg<1>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                             n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<1>{tables});
-  } else {
-    NoRope none{};
-    rc = launch_move<NoRope, false, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                    n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, none);
-  }
-  if (tn.gather_stop && hipEventRecord(tn.gather_stop, stream) != hipSuccess) return CP_ERR_HIP;
-  return rc;
+  if (use_rope && rope->style == 0)
+    return launch_move<RopeArg<0>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                               n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<0>{tables},
+                                               mo);
+  if (use_rope)
+    return launch_move<RopeArg<1>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                               n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<1>{tables},
+                                               mo);
+  NoRope none{};
+  return launch_move<NoRope, false, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
+                                          n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, none, mo);
 }
 
-extern "C" int32_t cp_gather_events(void *start_event, void *stop_event) {
-  cp::tuning().gather_start = (hipEvent_t)start_event;
-  cp::tuning().gather_stop = (hipEvent_t)stop_event;
-  return CP_OK;
+}  // namespace
+}  // namespace cp
+
+extern "C" int32_t cp_gather_kv(void *stream, const void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, void *dst,
+                                cp_kv_layout dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
+                                const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
+                                const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
+                                const cp_rope *rope, uint32_t *status_flags, void *scratch_arg, size_t scratch_bytes,
+                                const cp_launch_opts *opts) {
+  if (max_spans == 0 || n_dst_tokens == 0 || n_pool_slots == 0) return CP_OK;
+  if (!scratch_arg || !cp::aligned(scratch_arg, 256)) return CP_ERR_INVALID_ARG;
+  return cp::gather_impl((hipStream_t)stream, pool, pool_l, n_pool_slots, dst, dst_l, n_dst_tokens, span_src, span_dst,
+                         span_len, span_delta, span_off, n_spans, max_spans, rope, status_flags, scratch_arg,
+                         scratch_bytes, opts);
 }
 
 extern "C" void *cp_event_create(void) {
@@ -609,27 +631,7 @@ extern "C" void cp_event_destroy(void *event) {
 }
 
 extern "C" size_t cp_scratch_bytes(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots) {
-  using namespace cp;
-  uint64_t n = N > max_spans ? N : max_spans;
-  // tile totals (at most 32 bytes each), four per-token words (insert), one 16-byte descriptor per
-  // token (gather, insert) and two flag bytes per token (floating anchors, chain-recording insert),
-  // span offsets, one chain head per pool slot, the cos/sin digit tables; pieces padded to 256 bytes
-  return (size_t)(((uint64_t)div_up(n, kScanTile) + 2) * 32 + (4ull * 4 + 16 + 2) * N + 4ull * ((uint64_t)max_spans + 1) +
-                  4ull * n_pool_slots + (size_t)kTrigLevels * kTrigDigit * kMaxHalfDim * sizeof(double2) + 16 * 256);
+  return cp::scratch_bytes_for(N, max_spans, n_pool_slots);
 }
 
 extern "C" int32_t cp_last_hip_error(void) { return cp::last_hip_error(); }
-
-extern "C" int32_t cp_tune(int32_t key, uint32_t value) {
-  cp::Tuning &t = cp::tuning();
-  switch (key) {
-    case 0: t.move_multicast = value; return CP_OK;
-    case 1: t.move_blocks_per_cu = value; return CP_OK;
-    case 2: t.move_nontemporal = value; return CP_OK;
-    case 3: t.move_unroll = value; return CP_OK;
-    case 4: t.move_blocks_per_cu_rope = value; return CP_OK;
-    case 5: t.move_unroll_rope = value; return CP_OK;
-    case 6: t.move_fanout = value; return CP_OK;
-    default: return CP_ERR_INVALID_ARG;
-  }
-}

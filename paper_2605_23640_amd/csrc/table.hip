@@ -381,7 +381,7 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
                              cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
                              int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
                              void *scratch, size_t scratch_bytes, const uint32_t *tok, const uint32_t *run_off,
-                             uint32_t *slot_tok, uint32_t *slot_parent) {
+                             uint32_t *slot_tok, uint32_t *slot_parent, const cp_launch_opts *opts) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   const bool chain = slot_tok != nullptr;
@@ -393,6 +393,8 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
   if (n_free && !free_slots) return CP_ERR_INVALID_ARG;
   if (!aligned(hash, 8) || !aligned(src, 16) || !aligned(pool, 16)) return CP_ERR_INVALID_ARG;
   if (!layout_ok(src_l) || !layout_ok(pool_l) || !layouts_match(src_l, pool_l)) return CP_ERR_UNSUPPORTED;
+  MoveOpts mo;
+  if (!resolve_opts(opts, false, &mo)) return CP_ERR_INVALID_ARG;
   if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
   uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
@@ -427,17 +429,17 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
   }
   uint32_t max_items = N < n_free ? N : n_free;
   return launch_scatter(stream, src, src_l, N, pool, pool_l, n_pool_slots, items, n_inserted, max_items, counter,
-                        status_flags);
+                        status_flags, mo);
 }
 
 extern "C" int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const uint32_t *off, uint32_t N,
                                 uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
                                 cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
                                 int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
-                                void *scratch, size_t scratch_bytes) {
+                                void *scratch, size_t scratch_bytes, const cp_launch_opts *opts) {
   return insert_common(stream, table, hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
                        slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, nullptr, nullptr, nullptr,
-                       nullptr);
+                       nullptr, opts);
 }
 
 extern "C" int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, const uint32_t *tok,
@@ -446,11 +448,11 @@ extern "C" int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64
                                       void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, int32_t *slot_pos,
                                       uint32_t *slot_tok, uint32_t *slot_parent, uint32_t *slot_out,
                                       uint32_t *n_inserted, uint32_t *status_flags, void *scratch,
-                                      size_t scratch_bytes) {
+                                      size_t scratch_bytes, const cp_launch_opts *opts) {
   if (!slot_tok || !slot_parent) return CP_ERR_INVALID_ARG;
   return insert_common(stream, table, hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
                        slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, tok, run_off, slot_tok,
-                       slot_parent);
+                       slot_parent, opts);
 }
 
 extern "C" int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags) {

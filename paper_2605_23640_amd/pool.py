@@ -74,8 +74,11 @@ class KVPool:
 
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
                  device="cuda", pool_tensor=None, anchor_window=None, verify=False,
-                 min_len=1, recompute_marks=False, zero_fill=False, lru=False, pool_layout="token"):
+                 min_len=1, recompute_marks=False, zero_fill=False, lru=False, pool_layout="token",
+                 gather_opts=None, insert_opts=None):
         self.device = device
+        # launch options (binding.LaunchOpts or None = defaults) handed to every gather / insert of this pool
+        self.gather_opts, self.insert_opts = gather_opts, insert_opts
         self.n_slots = int(n_slots)
         # "token": [slot][layer][K|V][head][dim], a token's rows are contiguous (the default);
         # "layer": [layer][K|V][slot][head][dim], every row of a token lies in another plane (for comparison)
@@ -134,10 +137,15 @@ class KVPool:
         B.cp_lru_threshold(self.slot_stamp, self.n_slots, self.epoch, n_needed, self.threshold, scratch, stream=stream)
         B.cp_evict(self.table, self.slot_stamp, self.n_slots, self.threshold, freed, self.n_freed, self.slot_parent,
                    self.slot_recompute, self.slot_anchor, scratch, stream=stream)
+        old = self.table
         if compact:
             fresh = B.Table(self.table.capacity, self.device, stream=stream)
             B.cp_table_compact(self.table, fresh, self.flags, stream=stream)
             self.table = fresh
+        # the count is read on the host: wait for the stream the kernels were enqueued on (it need not
+        # be torch's current one), which also keeps the old table's memory alive until they are done
+        (torch.cuda.current_stream() if stream is None else stream).synchronize()
+        del old
         n = int(self.n_freed.item())
         self.free_slots = torch.cat([self.free_slots[self.n_used:], freed[:n]])
         self.n_used = 0
@@ -151,11 +159,10 @@ class KVPool:
         return B.cp_hash_segments(tok, mask, off, out, scratch, stream=stream)
 
     def lookup(self, tok, mask, off, dst, buf: LookupBuffers, gather=True, stream=None,
-               gather_events=None) -> LookupResult:
+               gather_opts=None) -> LookupResult:
         """Serve a request batch: after the call the rows of every matched token of
         ``dst`` (layer-major, N tokens) hold the pooled KV.  No host synchronisation.
-        ``gather_events`` = (start, end) torch events recorded on the stream around
-        the gather call alone (for timing)."""
+        ``gather_opts`` overrides the pool's launch options for this call."""
         N = tok.numel()
         if self.verify:
             B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
@@ -192,21 +199,17 @@ class KVPool:
                          buf.span_dst, buf.span_len, buf.span_delta, buf.span_off, buf.n_spans, self.flags,
                          buf.scratch, stream=stream)
         if gather:
-            if gather_events is not None:
-                gather_events[0].record(stream)
             B.cp_gather_kv(self.pool, self.layout, self.n_slots, dst, self.request_layout(N), N, buf.span_src,
                            buf.span_dst, buf.span_len, buf.span_delta if self.rope is not None else None,
                            buf.span_off, buf.n_spans, buf.max_spans, self.rope, self.flags, buf.scratch,
-                           stream=stream)
-            if gather_events is not None:
-                gather_events[1].record(stream)
+                           stream=stream, opts=self.gather_opts if gather_opts is None else gather_opts)
             if self.zero_fill:
                 B.cp_fill_unmatched(served, dst, self.request_layout(N), stream=stream)
         return LookupResult(buf.hash, buf.slot, buf.span_src, buf.span_dst, buf.span_len, buf.span_delta,
                             buf.span_off, buf.n_spans, served)
 
     def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None,
-               run_off_buf=None, recompute=None):
+               run_off_buf=None, recompute=None, insert_opts=None):
         """Store the non-sensitive tokens of a batch that the pool does not hold yet,
         taking their KV rows from ``src`` (layer-major, N tokens).  With ``sync`` the
         host free-list cursor is advanced (one device-to-host read).  A pool with
@@ -221,15 +224,16 @@ class KVPool:
         elif not hashes_ready:
             B.cp_hash_segments(tok, mask, off, hash_buf, scratch, stream=stream)
         n_free = self.free_slots.numel() - self.n_used
+        iopts = self.insert_opts if insert_opts is None else insert_opts
         if self.verify:
             B.cp_insert_kv_chain(self.table, hash_buf, tok, run_off_buf, off, self.free_slots[self.n_used:], n_free,
                                  src, self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos,
                                  self.slot_tok, self.slot_parent, slot_out, self.n_inserted, self.flags, scratch,
-                                 stream=stream)
+                                 stream=stream, opts=iopts)
         else:
             B.cp_insert_kv(self.table, hash_buf, off, self.free_slots[self.n_used:], n_free, src,
                            self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos, slot_out,
-                           self.n_inserted, self.flags, scratch, stream=stream)
+                           self.n_inserted, self.flags, scratch, stream=stream, opts=iopts)
         if self.slot_anchor is not None:  # a run's prefix hash is known from the moment its W-th token has a slot
             B.cp_insert_anchors(run_off_buf, slot_out, self.anchor_window, self.n_slots, self.slot_anchor, stream=stream)
         if recompute is not None:
@@ -238,6 +242,8 @@ class KVPool:
         if self.slot_stamp is not None:
             B.cp_touch(slot_out, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         if sync:
+            if stream is not None:  # the count comes from kernels on that stream, not torch's current one
+                stream.synchronize()
             n = int(self.n_inserted.item())
             self.n_used += n
             return n

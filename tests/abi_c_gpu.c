@@ -83,12 +83,16 @@ int main(void) {
   CHECK_CP(cp_table_init(NULL, table));
   CHECK_CP(cp_hash_segments(NULL, d_tok, d_mask, d_off, N, R, 0x100000001B3ull, d_hash, d_scratch, scratch_bytes));
   CHECK_CP(cp_insert_kv(NULL, table, d_hash, d_off, N, R, d_free, S, d_src, buf_l, d_pool, pool_l, S, d_slot_pos,
-                        d_slot_out, d_counts + 0, d_counts + 2, d_scratch, scratch_bytes));
+                        d_slot_out, d_counts + 0, d_counts + 2, d_scratch, scratch_bytes, NULL));
   CHECK_CP(cp_probe(NULL, table, d_hash, N, d_slot));
   CHECK_CP(cp_build_spans(NULL, d_slot, d_off, N, R, NULL, N, sp_src, sp_dst, sp_len, sp_delta, sp_off, d_counts + 1,
                           d_counts + 2, d_scratch, scratch_bytes));
+  cp_launch_opts opts;  /* explicit options: no sharing of reads, 4 workgroups per unit */
+  memset(&opts, 0, sizeof opts);
+  opts.read_sharing = 2;
+  opts.blocks_per_cu = 4;
   CHECK_CP(cp_gather_kv(NULL, d_pool, pool_l, S, d_dst, buf_l, N, sp_src, sp_dst, sp_len, NULL, sp_off, d_counts + 1, N,
-                        NULL, d_counts + 2, d_scratch, scratch_bytes));
+                        NULL, d_counts + 2, d_scratch, scratch_bytes, &opts));
   CHECK_HIP(hipDeviceSynchronize());
   uint32_t counts[3];
   CHECK_HIP(hipMemcpy(counts, d_counts, sizeof counts, hipMemcpyDeviceToHost));

@@ -73,9 +73,9 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_hash_floating(None, tab, S, 16, P, Q, 4, B.BASE, 0, P, None, S, big) == INV  # W = 0
     assert L.cp_hash_floating(None, tab, None, 16, P, Q, 4, B.BASE, 2, P, None, S, big) == INV  # no mark array
     assert L.cp_build_spans(None, None, Q, 4, 1, None, 4, P, P, P, None, None, Q, Q, S, big) == INV
-    assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, None, lay, P, lay, 16, P, Q, S, S, S, big) == INV
+    assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, None, lay, P, lay, 16, P, Q, S, S, S, big, None) == INV
     assert L.cp_insert_kv_chain(None, tab, P, Q, Q, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, None, None, Q, S, S, S,
-                                big) == INV
+                                big, None) == INV
     assert L.cp_verify_chain(None, P, P, Q, 4, P, P, 16, 0, Q, None, S, big) == INV  # cand and slot_out are one array
     assert L.cp_filter_matches(None, None, Q, 4, 1, 1, None, 0, P, S, big) == INV
     assert L.cp_mark_recompute(None, P, None, 4, 16, Q) == INV
@@ -89,7 +89,18 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_sat_build(None, P, (1 << 20) + 1, 1 << 21, None, Q, S, big) == UNS
     assert L.cp_sat_build(None, P, 100, 100, None, Q, S, 16) == SCR
     assert L.cp_annotate(None, P, 100, Q, 1, 101, P, P, P, Q, Q, None, S, big) == INV  # rho above 100 %
-    assert L.cp_tune(99, 1) == INV
+    # launch options outside their documented ranges
+    gather = lambda o: L.cp_gather_kv(None, P, lay, 16, Q, lay, 4, S, S, S, None, None, S, 4, None, S, S, big,  # noqa: E731
+                                      ctypes.byref(o))
+    assert gather(B.LaunchOpts(read_sharing=3)) == INV
+    assert gather(B.LaunchOpts(loads_in_flight=5)) == INV
+    assert gather(B.LaunchOpts(fanout=17)) == INV
+    assert gather(B.LaunchOpts(start_event=P)) == INV  # one event without the other
+    o = B.LaunchOpts()
+    o.reserved[1] = 1
+    assert gather(o) == INV
+    assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, Q, S, S, S, big,
+                          ctypes.byref(B.LaunchOpts(nontemporal=5))) == INV
     assert L.cp_sat_scratch_bytes(10000) > (157 * 10112 + 79 * 10048) * 8  # tile carries of a 10,000-token request
 
 
