@@ -51,6 +51,7 @@ extern "C" {
 #define CP_ERR_UNSUPPORTED (-2) /* shape or size outside the limits above                  */
 #define CP_ERR_HIP (-3)         /* a launch failed; see cp_last_hip_error()                */
 #define CP_ERR_SCRATCH (-4)     /* scratch_bytes smaller than cp_scratch_bytes() demands   */
+#define CP_ERR_STATIC_LIMIT (-5) /* cp_gather_kv_static: a size above CP_STATIC_MAX_*      */
 
 #define CP_FLAG_SPANS_OVERFLOW 1u /* more than max_spans spans: only the first max_spans kept  */
 #define CP_FLAG_POOL_FULL 2u      /* free list used up: later new tokens were not stored       */
@@ -256,6 +257,26 @@ int32_t cp_gather_kv(void *stream, const void *pool, cp_kv_layout pool_l, uint32
                      const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
                      const cp_rope *rope, uint32_t *status_flags, void *scratch, size_t scratch_bytes,
                      const cp_launch_opts *opts);
+
+/* cp_gather_kv for callers that cannot allocate device memory or have nowhere to keep a scratch
+ * buffer: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and results as cp_gather_kv without `scratch`: the working memory (span offsets,
+ * per-token descriptors, chain heads, rotation tables) is an array inside the library's device code,
+ * about 10 MiB, which every GPU the library runs on holds from the library's first use there until the
+ * process ends.  Sizes are limited to n_dst_tokens <= CP_STATIC_MAX_TOKENS, max_spans <=
+ * CP_STATIC_MAX_SPANS and n_pool_slots <= CP_STATIC_MAX_SLOTS; anything larger returns
+ * CP_ERR_STATIC_LIMIT and enqueues nothing.  The call allocates and frees nothing.  The stream must
+ * belong to the calling thread's current device.  All calls on one GPU share the one array: calls
+ * that may overlap on a GPU (different streams, different threads) race and must be ordered by the
+ * caller; calls on one stream are ordered already. */
+#define CP_STATIC_MAX_TOKENS 131072u
+#define CP_STATIC_MAX_SPANS 131072u
+#define CP_STATIC_MAX_SLOTS 524288u
+int32_t cp_gather_kv_static(void *stream, const void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, void *dst,
+                            cp_kv_layout dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
+                            const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
+                            const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
+                            const cp_rope *rope, uint32_t *status_flags, const cp_launch_opts *opts);
 
 /* Insert-if-absent with the matching scatter (post-inference storing, Sec. 4.1
  * "Workflow"; one copy of a duplicate, Sec. 4.3.5 "Lifecycle management").

@@ -23,12 +23,13 @@ SLOT_NONE = 0xFFFFFFFF
 BASE = 0x100000001B3  # polynomial base of the chain hash
 TABLE_BUCKET = 16
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH, ERR_STATIC_LIMIT = 0, -1, -2, -3, -4, -5
+STATIC_MAX_TOKENS, STATIC_MAX_SPANS, STATIC_MAX_SLOTS = 131072, 131072, 524288
 FLAG_SPANS_OVERFLOW, FLAG_POOL_FULL, FLAG_TABLE_FULL, FLAG_BAD_INDEX = 1, 2, 4, 8
 
 EXPORTS = [
     "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_table_init",
-    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_insert_kv",
+    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_gather_kv_static", "cp_insert_kv",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
     "cp_insert_kv_chain", "cp_verify_chain",
@@ -41,7 +42,8 @@ LRU_MAX_AGE = 4096
 
 class CpError(RuntimeError):
     def __init__(self, fn, code):
-        names = {-1: "CP_ERR_INVALID_ARG", -2: "CP_ERR_UNSUPPORTED", -3: "CP_ERR_HIP", -4: "CP_ERR_SCRATCH"}
+        names = {-1: "CP_ERR_INVALID_ARG", -2: "CP_ERR_UNSUPPORTED", -3: "CP_ERR_HIP", -4: "CP_ERR_SCRATCH",
+                 -5: "CP_ERR_STATIC_LIMIT (more than 131072 tokens or spans, or 524288 pool slots)"}
         extra = f" (hipError {lib().cp_last_hip_error()})" if code == ERR_HIP else ""
         super().__init__(f"{fn} failed: {names.get(code, code)}{extra}")
         self.code = code
@@ -153,6 +155,8 @@ def lib():
         L.cp_gather_kv.restype = i32
         L.cp_gather_kv.argtypes = [vp, vp, KVLayout, u32, vp, KVLayout, u32, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, sz,
                                    vp]
+        L.cp_gather_kv_static.restype = i32
+        L.cp_gather_kv_static.argtypes = [vp, vp, KVLayout, u32, vp, KVLayout, u32, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp]
         L.cp_insert_kv.restype = i32
         L.cp_insert_kv.argtypes = [vp, TableStruct, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout, u32, vp, vp,
                                    vp, vp, vp, sz, vp]
@@ -430,6 +434,17 @@ def cp_gather_kv(pool, pool_l: KVLayout, n_pool_slots, dst, dst_l: KVLayout, n_d
         _ptr(span_dst), _ptr(span_len), _ptr(span_delta), _ptr(span_off), _ptr(n_spans), max_spans,
         C.byref(rope) if rope is not None else None, _ptr(status_flags), _ptr(scratch),
         scratch.numel() if scratch is not None else 0, _opts(opts)))
+
+
+def cp_gather_kv_static(pool, pool_l: KVLayout, n_pool_slots, dst, dst_l: KVLayout, n_dst_tokens, span_src, span_dst,
+                        span_len, span_delta, span_off, n_spans, max_spans, rope: Rope | None, status_flags,
+                        stream=None, opts: LaunchOpts | None = None):
+    """cp_gather_kv without a scratch argument: the library's own device array is the working memory."""
+    _need_cuda(pool, dst, span_src, span_dst, span_len, span_delta, span_off, n_spans, status_flags)
+    _check("cp_gather_kv_static", lib().cp_gather_kv_static(
+        _stream(stream), _ptr(pool), pool_l, n_pool_slots, _ptr(dst), dst_l, n_dst_tokens, _ptr(span_src),
+        _ptr(span_dst), _ptr(span_len), _ptr(span_delta), _ptr(span_off), _ptr(n_spans), max_spans,
+        C.byref(rope) if rope is not None else None, _ptr(status_flags), _opts(opts)))
 
 
 def cp_insert_kv(table: Table, hashes, off, free_slots, n_free, src, src_l: KVLayout, pool, pool_l: KVLayout,

@@ -32,6 +32,7 @@
 #include "cp_internal.h"
 
 #include <cmath>
+#include <mutex>
 
 namespace cp {
 
@@ -590,6 +591,49 @@ int32_t gather_impl(hipStream_t stream, const void *pool, const cp_kv_layout &po
                                           n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, none, mo);
 }
 
+// ---- the entry point that brings its own scratch memory -----------------------------------------
+
+// Largest call cp_gather_kv_static accepts, and the scratch it needs for that.
+constexpr uint32_t kStaticMaxTokens = CP_STATIC_MAX_TOKENS, kStaticMaxSpans = CP_STATIC_MAX_SPANS,
+                   kStaticMaxSlots = CP_STATIC_MAX_SLOTS;
+constexpr size_t kStaticScratchBytes = 10u << 20;
+static_assert(scratch_bytes_for(kStaticMaxTokens, kStaticMaxSpans, kStaticMaxSlots) <= kStaticScratchBytes,
+              "the static scratch array must hold the largest accepted call");
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+}  // namespace cp
+
+// Device memory that exists from the moment the code object is loaded on a GPU until the process
+// ends, one copy per GPU.  In host code this name is only a handle for hipGetSymbolAddress; the
+// array's address on the current GPU is looked up once and used from then on.
+static __device__ __align__(256) uint8_t scratch[cp::kStaticScratchBytes];
+
+namespace cp {
+namespace {
+
+// Address of `scratch` on the current device (looked up once per device), or null with *rc set.
+void *static_scratch(int32_t *rc) {
+  static std::mutex mu;
+  static void *ptr[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices)) e = hipErrorInvalidDevice;
+  if (e == hipSuccess) {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+      void *p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e == hipSuccess && !p) e = hipErrorInvalidSymbol;
+      if (e == hipSuccess) ptr[dev] = p;
+    }
+    if (e == hipSuccess) return ptr[dev];
+  }
+  last_hip_error() = (int32_t)e;
+  *rc = CP_ERR_HIP;
+  return nullptr;
+}
+
 }  // namespace
 }  // namespace cp
 
@@ -604,6 +648,23 @@ extern "C" int32_t cp_gather_kv(void *stream, const void *pool, cp_kv_layout poo
   return cp::gather_impl((hipStream_t)stream, pool, pool_l, n_pool_slots, dst, dst_l, n_dst_tokens, span_src, span_dst,
                          span_len, span_delta, span_off, n_spans, max_spans, rope, status_flags, scratch_arg,
                          scratch_bytes, opts);
+}
+
+extern "C" int32_t cp_gather_kv_static(void *stream, const void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
+                                       void *dst, cp_kv_layout dst_l, uint32_t n_dst_tokens, const uint32_t *span_src,
+                                       const uint32_t *span_dst, const uint32_t *span_len, const int32_t *span_delta,
+                                       const uint32_t *span_off, const uint32_t *n_spans, uint32_t max_spans,
+                                       const cp_rope *rope, uint32_t *status_flags, const cp_launch_opts *opts) {
+  using namespace cp;
+  if (max_spans == 0 || n_dst_tokens == 0 || n_pool_slots == 0) return CP_OK;
+  if (n_dst_tokens > kStaticMaxTokens || max_spans > kStaticMaxSpans || n_pool_slots > kStaticMaxSlots)
+    return CP_ERR_STATIC_LIMIT;
+  int32_t rc = CP_OK;
+  void *mem = static_scratch(&rc);  // the array's address on this GPU, never the array's name
+  if (!mem) return rc;
+  return gather_impl((hipStream_t)stream, pool, pool_l, n_pool_slots, dst, dst_l, n_dst_tokens, span_src, span_dst,
+                     span_len, span_delta, span_off, n_spans, max_spans, rope, status_flags, mem, kStaticScratchBytes,
+                     opts);
 }
 
 extern "C" void *cp_event_create(void) {
