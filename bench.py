@@ -33,15 +33,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
-# HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command, scaled by what the same counters read for kernels of known size
-# (profiles/gather_rows_kernel_<workload>.txt); None for workloads not profiled that way.
-MEASURED_TRAFFIC = {"llama3-8b": 9038240601, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
-                    "annotator-10000-full": 924614651,
-                    "annotator-10000": 376097535}
-# (the float workload was profiled with all added rows on: profiles/gather_rows_kernel_float_all_rows.txt)
-# the read part of the same measurements (FETCH_SIZE, scaled)
-MEASURED_FETCH = {"llama3-8b": 3098951142, "rope": 2762280080, "llama3-70b": 25303251909, "frag": 7420215123}
+# HBM bytes of one gather launch as the profiler's counters saw them: rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this command (defaults, per workload), each scaled by what the same counter
+# reads for a plain streaming kernel of known size.  They are copied from the summaries under profiles/
+# (gather_rows_kernel_<workload>.txt; annotator_<n>.txt): measurements of an earlier run of the same
+# code, not of this run, and the bench line says so next to them.
+PROFILED_TRAFFIC = {"llama3-8b": 9038240601, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
+                    "annotator-10000-full": 924614651, "annotator-10000": 376097535}
+PROFILED_FETCH = {"llama3-8b": 3098951142, "rope": 2762280080, "llama3-70b": 25303251909, "frag": 7420215123}
+PROFILED_SCATTER = {}  # scatter_rows_kernel of the default step: {"llama3-8b": (fetched, written)}
 
 
 def log(*a):
@@ -185,7 +185,8 @@ def annotator_bench(args):
         "roofline": {"kernel": "cp_sat_build (3 launches)" if args.full_table else "cp_sat_build (4 launches, mask known)",
                      "bound": "hbm", "achieved": sat_bytes / (sat_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": sat_bytes / (sat_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get(f"annotator-{n}" + ("-full" if args.full_table else ""))},
+                     "traffic": PROFILED_TRAFFIC.get(f"annotator-{n}" + ("-full" if args.full_table else "")),
+                     "traffic_source": f"profiles/annotator_{n}.txt (rocprofv3 counters of an earlier run, not of this run)"},
     }
     if args.cpu_requests > 0:
         t = time.perf_counter()
@@ -234,6 +235,7 @@ def main():
     ap.add_argument("--nontemporal", type=int, default=0, help="1 + (bit 0: non-temporal loads, bit 1: stores)")
     ap.add_argument("--loads-in-flight", type=int, default=0, help="16-byte loads per lane before the first store")
     ap.add_argument("--fanout", type=int, default=0, help="destinations written per pass over a shared slot")
+    ap.add_argument("--workgroups", type=int, default=0, help="grid size of the row mover (overrides --blocks-per-cu)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the side measurements (gather without read sharing, plain copy): used under the profiler")
     ap.add_argument("--calibrate", action="store_true",
@@ -256,7 +258,7 @@ def main():
         return annotator_bench(args)
 
     opts = cp.binding.LaunchOpts(args.read_sharing, args.blocks_per_cu, args.nontemporal, args.loads_in_flight,
-                                 args.fanout)
+                                 args.fanout, args.workgroups)
 
     t0 = time.time()
     wl = gen.make(args.workload)
@@ -327,6 +329,8 @@ def main():
     gather_bytes = 2.0 * sh.tok_bytes * matched  # algorithmic: every reused row read once and written once
     step_bytes = 2.0 * sh.tok_bytes * (matched + inserted)
     gather_gbps = gather_bytes / (gather_ms * 1e-3) / 1e9
+    min_hbm_bytes = sh.tok_bytes * (matched + unique_src)
+    min_hbm_gbps = min_hbm_bytes / (gather_ms * 1e-3) / 1e9
 
     def gather_alone(o, reps=5):
         """cp_gather_kv alone on the spans of the last step; returns ms of its mover kernel."""
@@ -395,21 +399,34 @@ def main():
         assert int(buf.n_spans.item()) == n_spans and int(pool.n_inserted.item()) == inserted
         del graph
 
-    # plain device-to-device copy of the same volume, for context
-    copy_gbps = None
+    # what this GPU reaches for plain contiguous streams (16-byte accesses over the request buffers: read all
+    # of it, write all of it, copy its first half to its second), and torch's device-to-device copy
+    ceilings = None
     if not args.no_extras:
-        a = torch.empty(int(gather_bytes // 2), dtype=torch.uint8, device=G.DEV)
-        b = torch.empty_like(a)
-        for _ in range(2):
-            b.copy_(a)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            b.copy_(a)
-        e1.record()
-        torch.cuda.synchronize()
-        copy_gbps = 5 * 2.0 * a.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del a, b
+        from cp_workload import kvgen
+        sink = torch.zeros(64, dtype=torch.int32, device=G.DEV)
+        span = (dst.numel() // 2) // 131072 * 131072  # bytes of one half, whole 128 KiB chunks
+        a_ptr, b_ptr = C.c_void_p(dst.data_ptr()), C.c_void_p(dst.data_ptr() + span)
+
+        def timed(fn, reps=5):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e-3
+
+        sp, snk = G.stream_ptr(), C.c_void_p(sink.data_ptr())
+        t_r = timed(lambda: kvgen.stream(sp, "read", a_ptr, None, 2 * span, snk))
+        t_w = timed(lambda: kvgen.stream(sp, "write", None, a_ptr, 2 * span, snk))
+        t_c = timed(lambda: kvgen.stream(sp, "copy", a_ptr, b_ptr, span, snk))
+        half = dst[:span], dst[span:2 * span]
+        t_t = timed(lambda: half[1].copy_(half[0]))
+        ceilings = {"read_GBps": 2 * span / t_r / 1e9, "write_GBps": 2 * span / t_w / 1e9,
+                    "copy_GBps_read_plus_write": 2 * span / t_c / 1e9, "torch_d2d_copy_GBps_read_plus_write": 2 * span / t_t / 1e9,
+                    "bytes": 2 * span, "kernels": "cp_workload/kvgen.hip stream_{read,write,copy}_kernel"}
 
     # the stored counter readings belong to the gather of the default options
     same_gather = (args.anchor_window is None and args.min_len <= 1 and args.recompute == 0
@@ -441,27 +458,45 @@ def main():
         "insert_GBps": 2.0 * sh.tok_bytes * inserted / (insert_ms * 1e-3) / 1e9 if insert_ms > 0 else None,
         "gather_GBps": gather_gbps,
         "gather_pct_of_hbm_peak": 100.0 * gather_gbps / HBM_PEAK_GBPS,
-        "gather_ms": gather_ms, "insert_ms": insert_ms,
+        "gather_ms": gather_ms, "insert_ms": insert_ms, "scatter_kernel_ms": scatter_ms,
         "front_and_reset_ms": ms_per_step - gather_ms - insert_ms,
         "ms_per_step_from_hip_graph": graph_ms,
         "retrieval_front_end_ms": front_ms,
         "retrieval_front_end_ms_per_10k_tokens": None if front_ms is None else front_ms * 1e4 / N,
-        # bytes that must cross HBM when every distinct source row is read once: written + distinct read
-        "gather_min_hbm_GBps": sh.tok_bytes * (matched + unique_src) / (gather_ms * 1e-3) / 1e9,
         "gather_GBps_without_read_sharing": None if own_read_ms is None else gather_bytes / (own_read_ms * 1e-3) / 1e9,
-        "d2d_copy_GBps_same_volume": copy_gbps,
+        "streaming_ceilings": ceilings,
         "roofline": {
-            "kernel": "gather_rows_kernel (cp_gather_kv)", "bound": "hbm", "achieved": gather_gbps,
-            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC.get(wl.name) if same_gather else None,
+            "kernel": "gather_rows_kernel (cp_gather_kv)", "bound": "hbm",
+            # algorithmic bytes (every reused row read once and written once) / kernel time
+            "achieved": gather_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
+            # bytes that must cross HBM in this run when every distinct source row is read once (rows
+            # written + distinct rows read, counted from this run's slots) / this run's kernel time
+            "hbm_bytes_min": min_hbm_bytes, "hbm_achieved": min_hbm_gbps, "hbm_frac": min_hbm_gbps / HBM_PEAK_GBPS,
+            # the same kernel with every token reading for itself: algorithmic bytes = bytes crossing HBM
+            "frac_without_read_sharing": (None if own_read_ms is None
+                                          else gather_bytes / (own_read_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),
+            "traffic": PROFILED_TRAFFIC.get(wl.name) if same_gather else None,
+            "traffic_source": (f"profiles/gather_rows_kernel_{wl.name}.txt: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier "
+                               "run of this command, not of this run" if same_gather and wl.name in PROFILED_TRAFFIC else None),
             # of the bytes the profiler saw the kernel fetch, the part that are pool rows some request
             # asked for (every distinct source row once); the rest is descriptors, lists, re-fetches
-            "fetched_bytes_landing_in_output": (sh.tok_bytes * unique_src / MEASURED_FETCH[wl.name]
-                                                if wl.name in MEASURED_FETCH and same_gather else None),
+            "fetched_bytes_landing_in_output": (sh.tok_bytes * unique_src / PROFILED_FETCH[wl.name]
+                                                if wl.name in PROFILED_FETCH and same_gather else None),
             # bytes the requests asked for (one row set per reused token) over bytes fetched: above 1 where
             # several requests are served from one fetch of a shared slot
-            "useful_over_fetched": (sh.tok_bytes * matched / MEASURED_FETCH[wl.name]
-                                    if wl.name in MEASURED_FETCH and same_gather else None),
+            "useful_over_fetched": (sh.tok_bytes * matched / PROFILED_FETCH[wl.name]
+                                    if wl.name in PROFILED_FETCH and same_gather else None),
+        },
+        # the scatter half of cp_insert_kv: every stored token's rows read from the request buffers and
+        # written to its pool slot, nothing shared
+        "roofline_insert": None if not scatter_ms else {
+            "kernel": "scatter_rows_kernel (cp_insert_kv)", "bound": "hbm",
+            "achieved": 2.0 * sh.tok_bytes * inserted / (scatter_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": 2.0 * sh.tok_bytes * inserted / (scatter_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "tokens_stored": inserted, "kernel_ms": scatter_ms, "whole_call_ms": insert_ms,
+            "traffic": sum(PROFILED_SCATTER[wl.name]) if wl.name in PROFILED_SCATTER and same_gather else None,
+            "traffic_source": (f"profiles/scatter_rows_kernel_{wl.name}.txt (earlier run, not this run)"
+                               if wl.name in PROFILED_SCATTER and same_gather else None),
         },
     }
     hev.close()
@@ -473,7 +508,13 @@ def main():
         kvgen.fill(G.stream_ptr(), C.c_void_p(dst.data_ptr()), G.gen_layout(lay), N, wl.seed, uid_base=0)
         bad = G.verify_rows(dst, lay, np.arange(N, dtype=np.uint64), wl.seed)
         torch.cuda.synchronize()
+        snk = torch.zeros(64, dtype=torch.int32, device=G.DEV)
+        whole = dst.numel() // 131072 * 131072
+        kvgen.stream(G.stream_ptr(), "read", C.c_void_p(dst.data_ptr()), None, whole, C.c_void_p(snk.data_ptr()))
+        kvgen.stream(G.stream_ptr(), "write", None, C.c_void_p(dst.data_ptr()), whole, C.c_void_p(snk.data_ptr()))
+        torch.cuda.synchronize()
         out["calibration"] = {"fill_kernel_bytes_written": N * sh.tok_bytes, "verify_kernel_bytes_read": N * sh.tok_bytes,
+                              "stream_read_kernel_bytes_read": whole, "stream_write_kernel_bytes_written": whole,
                               "verify_mismatches": bad, "gather_bytes_written": sh.tok_bytes * matched,
                               "gather_bytes_read_algorithmic": sh.tok_bytes * matched,
                               "gather_bytes_read_distinct": sh.tok_bytes * unique_src}

@@ -83,6 +83,59 @@ __global__ void verify_kernel(const uint8_t *base, GenLayout lay, const uint64_t
   if (bad) atomicAdd(n_bad, (unsigned long long)bad);
 }
 
+// Plain streaming kernels over a contiguous buffer, 16-byte accesses: what this GPU reaches for a pure
+// read, a pure write and a copy.  Benchmarks quote them beside the row mover's rate, and their known
+// byte counts calibrate the profiler's HBM counters.  Workgroup w takes the chunks w, w + grid, ...
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int U>
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint8_t *__restrict__ a, uint64_t bytes, uint64_t chunk,
+                                                          uint32_t *sink) {
+  const uint64_t n_chunks = bytes / chunk;
+  uint32_t acc = 0;
+  for (uint64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+    const uint8_t *s = a + ch * chunk;
+    for (uint64_t i = (uint64_t)threadIdx.x * 16; i < chunk; i += 256ull * 16 * U) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load((const u32x4 *)(s + i + (uint64_t)u * 256 * 16));
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc += v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+    }
+  }
+  if (acc == 0x12345678u) sink[0] = acc;  // keeps the loads alive; practically never true
+}
+
+template <int U>
+__global__ __launch_bounds__(256) void stream_write_kernel(uint8_t *__restrict__ b, uint64_t bytes, uint64_t chunk) {
+  const uint64_t n_chunks = bytes / chunk;
+  const u32x4 v = {0xC0DEC0DEu, 0xC0DEC0DEu, 0xC0DEC0DEu, 0xC0DEC0DEu};
+  for (uint64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+    uint8_t *d = b + ch * chunk;
+    for (uint64_t i = (uint64_t)threadIdx.x * 16; i < chunk; i += 256ull * 16 * U) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v, (u32x4 *)(d + i + (uint64_t)u * 256 * 16));
+    }
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint8_t *__restrict__ a, uint8_t *__restrict__ b,
+                                                          uint64_t bytes, uint64_t chunk) {
+  const uint64_t n_chunks = bytes / chunk;
+  for (uint64_t ch = blockIdx.x; ch < n_chunks; ch += gridDim.x) {
+    const uint8_t *s = a + ch * chunk;
+    uint8_t *d = b + ch * chunk;
+    for (uint64_t i = (uint64_t)threadIdx.x * 16; i < chunk; i += 256ull * 16 * U) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) v[u] = *(const u32x4 *)(s + i + (uint64_t)u * 256 * 16);
+#pragma unroll
+      for (int u = 0; u < U; ++u) __builtin_nontemporal_store(v[u], (u32x4 *)(d + i + (uint64_t)u * 256 * 16));
+    }
+  }
+}
+
 uint32_t grid_for(uint64_t n_rows) {
   uint64_t g = n_rows < 65536 ? n_rows : 65536;
   return (uint32_t)(g ? g : 1);
@@ -104,5 +157,16 @@ extern "C" int kvgen_verify(hipStream_t stream, const void *base, GenLayout lay,
   uint64_t n_rows = (uint64_t)n_tok * lay.n_layers * 2;
   verify_kernel<<<grid_for(n_rows), 256, 0, stream>>>((const uint8_t *)base, lay, uid, skip_k, n_tok, seed,
                                                       (unsigned long long *)n_bad);
+  return (int)hipGetLastError();
+}
+
+// mode 0: read `bytes` of a; 1: write `bytes` of b (with the poison pattern); 2: copy a -> b.  bytes must be a
+// multiple of 128 KiB; a and b 16-byte aligned, not overlapping.  Shapes chosen from a sweep on MI355X.
+extern "C" int kvgen_stream(hipStream_t stream, int mode, const void *a, void *b, uint64_t bytes, uint32_t *sink) {
+  if (bytes == 0 || bytes % 131072) return (int)hipErrorInvalidValue;
+  if (mode == 0) stream_read_kernel<8><<<1024, 256, 0, stream>>>((const uint8_t *)a, bytes, 131072, sink);
+  else if (mode == 1) stream_write_kernel<1><<<65536, 256, 0, stream>>>((uint8_t *)b, bytes, 4096);
+  else if (mode == 2) stream_copy_kernel<4><<<65536, 256, 0, stream>>>((const uint8_t *)a, (uint8_t *)b, bytes, 16384);
+  else return (int)hipErrorInvalidValue;
   return (int)hipGetLastError();
 }

@@ -143,6 +143,8 @@ def lib():
         L.kvgen_fill.argtypes = [vp, vp, GenLayout, vp, u64, u32, u64]
         L.kvgen_verify.restype = C.c_int
         L.kvgen_verify.argtypes = [vp, vp, GenLayout, vp, vp, u32, u64, vp]
+        L.kvgen_stream.restype = C.c_int
+        L.kvgen_stream.argtypes = [vp, C.c_int, vp, vp, u64, vp]
         _lib = L
     return _lib
 
@@ -163,3 +165,11 @@ def verify(stream, base_ptr, layout: GenLayout, uid_ptr, n_tok, seed, n_bad_ptr,
     rc = lib().kvgen_verify(stream, base_ptr, layout, uid_ptr, skip_k_ptr, n_tok, seed, n_bad_ptr)
     if rc != 0:
         raise RuntimeError(f"kvgen_verify failed: hipError {rc}")
+
+
+def stream(stream, mode, a_ptr, b_ptr, n_bytes, sink_ptr):
+    """Plain streaming kernel over a contiguous device buffer: mode "read" (a), "write" (b) or "copy" (a -> b);
+    ``n_bytes`` a multiple of 128 KiB.  For bandwidth ceilings and profiler-counter calibration."""
+    rc = lib().kvgen_stream(stream, {"read": 0, "write": 1, "copy": 2}[mode], a_ptr, b_ptr, n_bytes, sink_ptr)
+    if rc != 0:
+        raise RuntimeError(f"kvgen_stream failed: hipError {rc}")

@@ -105,9 +105,14 @@ int32_t cp_last_hip_error(void);
  * NULL, or a zeroed struct, means the defaults.  Results never depend on these options.
  *   read_sharing     0/1 = tokens of one gather that read the same pool slot share one read of it
  *                    ("read once, write many"; the default), 2 = every token reads for itself
- *   blocks_per_cu    resident workgroups per compute unit (0 = default)
- *   nontemporal      0 = default, else 1 + (bit 0: non-temporal loads, bit 1: non-temporal stores)
- *   loads_in_flight  16-byte loads a lane issues before its first store (0 = default, 4 or 8)
+ *   blocks_per_cu    resident workgroups per compute unit (0 = default: one workgroup on seven of
+ *                    every eight units where a token's rows allow 16 loads in flight, else 2; 3 for a
+ *                    gather that re-rotates keys)
+ *   nontemporal      0 = default (stores only), else 1 + (bit 0: non-temporal loads, bit 1: non-temporal stores)
+ *   loads_in_flight  16-byte loads a lane issues before its first store (0 = default: 16 for the
+ *                    Llama row shapes, fewer for small tokens, 4 for a gather that re-rotates keys;
+ *                    4, 8 or 16, a rotating gather at most 8)
+ *   workgroups       grid size of the kernel; overrides blocks_per_cu (0 = not given)
  *   fanout           destinations written per pass over the rows of a shared slot (0 = default 16,
  *                    1..16; fewer means the rows are fetched again, normally from cache)
  *   start_event, stop_event   two hipEvent_t (host handles as void*, created and destroyed by the
@@ -115,8 +120,8 @@ int32_t cp_last_hip_error(void);
  *                    after the row-mover kernel, so that a benchmark can time it apart from the
  *                    small set-up kernels of the call. */
 typedef struct {
-  uint32_t read_sharing, blocks_per_cu, nontemporal, loads_in_flight, fanout;
-  uint32_t reserved[3]; /* must be 0 */
+  uint32_t read_sharing, blocks_per_cu, nontemporal, loads_in_flight, fanout, workgroups;
+  uint32_t reserved[2]; /* must be 0 */
   void *start_event, *stop_event;
 } cp_launch_opts;
 

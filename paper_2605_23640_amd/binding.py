@@ -84,12 +84,14 @@ class LaunchOpts(C.Structure):
     """``cp_launch_opts``: per-call launch options of the row mover; zero = default everywhere."""
 
     _fields_ = [("read_sharing", C.c_uint32), ("blocks_per_cu", C.c_uint32), ("nontemporal", C.c_uint32),
-                ("loads_in_flight", C.c_uint32), ("fanout", C.c_uint32), ("reserved", C.c_uint32 * 3),
+                ("loads_in_flight", C.c_uint32), ("fanout", C.c_uint32), ("workgroups", C.c_uint32),
+                ("reserved", C.c_uint32 * 2),
                 ("start_event", C.c_void_p), ("stop_event", C.c_void_p)]
 
     def with_events(self, start, stop):
         """A copy that also asks for the two hipEvent_t handles to be recorded around the mover kernel."""
-        o = LaunchOpts(self.read_sharing, self.blocks_per_cu, self.nontemporal, self.loads_in_flight, self.fanout)
+        o = LaunchOpts(self.read_sharing, self.blocks_per_cu, self.nontemporal, self.loads_in_flight, self.fanout,
+                       self.workgroups)
         o.start_event, o.stop_event = start, stop
         return o
 

@@ -13,9 +13,10 @@ namespace cp {
 // measurements on MI355X).  Held by value for the duration of one call; nothing is process wide.
 struct MoveOpts {
   bool share_reads;         // tokens that read the same pool slot are served by one read
-  uint32_t blocks_per_cu;   // resident workgroups per compute unit
+  uint32_t blocks_per_cu;   // resident workgroups per compute unit (0 = chosen at launch)
+  uint32_t workgroups;      // grid size, overrides blocks_per_cu (0 = not given)
   uint32_t nontemporal;     // bit 0: non-temporal loads, bit 1: non-temporal stores
-  uint32_t loads_in_flight; // 16-byte loads a lane issues before its first store (4 or 8)
+  uint32_t loads_in_flight; // 16-byte loads a lane issues before its first store (4, 8, 16; 0 = chosen at launch)
   uint32_t fanout;          // destinations written per pass over a shared slot's rows (1..16)
   hipEvent_t start, stop;   // recorded right before / after the row-mover launch, if not null
 };

@@ -33,17 +33,21 @@
 
 #include <cmath>
 #include <mutex>
+#include <type_traits>
 
 namespace cp {
 
 bool resolve_opts(const cp_launch_opts *o, bool rotating, MoveOpts *out) {
-  // defaults: the copy form runs best with 2 workgroups per unit and 8 loads in flight; the rotating
-  // form needs its registers for arithmetic and hides latency with more workgroups instead
-  MoveOpts m{true, rotating ? 4u : 2u, 2u, rotating ? 4u : 8u, 16u, nullptr, nullptr};
+  // defaults: non-temporal stores; loads in flight and workgroups are chosen at launch from the row shape
+  // (0 here): 16 loads in flight per lane and one workgroup per compute unit for the Llama shapes
+  (void)rotating;
+  MoveOpts m{true, 0u, 0u, 2u, 0u, 16u, nullptr, nullptr};
   if (o) {
     if (o->read_sharing > 2 || o->blocks_per_cu > 64 || o->nontemporal > 4 || o->fanout > 16) return false;
-    if (o->loads_in_flight != 0 && o->loads_in_flight != 4 && o->loads_in_flight != 8) return false;
-    if (o->reserved[0] | o->reserved[1] | o->reserved[2]) return false;
+    if (o->loads_in_flight != 0 && o->loads_in_flight != 4 && o->loads_in_flight != 8 && o->loads_in_flight != 16)
+      return false;
+    if (o->workgroups > (1u << 20) || o->reserved[0] | o->reserved[1]) return false;
+    if (o->workgroups) m.workgroups = o->workgroups;
     if ((o->start_event == nullptr) != (o->stop_event == nullptr)) return false;
     if (o->read_sharing == 2) m.share_reads = false;
     if (o->blocks_per_cu) m.blocks_per_cu = o->blocks_per_cu;
@@ -76,10 +80,11 @@ bool layouts_match(const cp_kv_layout &a, const cp_kv_layout &b) {
 
 namespace {
 
-constexpr int kMoveThreads = 256;
+constexpr int kMoveThreads = 256;                   // lanes of a workgroup that move rows
+constexpr int kBlockThreads = kMoveThreads + kWave;  // ... plus one scout wavefront
 constexpr uint32_t kMaxHalfDim = 256;    // head_dim <= 512 when rotating
 constexpr uint32_t kMaxFanout = 16;      // destinations served per pass over the source rows
-constexpr uint32_t kTrigDoubles = 2048;  // LDS doubles for cos (and as many for sin): fan-out * head_dim/2 <= this
+constexpr uint32_t kTrigDoubles = 1024;  // LDS doubles for cos (and as many for sin) per descriptor: fan-out * head_dim/2 <= this
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 
 // cos/sin of (delta * inv_freq[j]) for any 32-bit delta come from five small
@@ -248,12 +253,12 @@ __device__ __forceinline__ u32x4 rotate_pairs(const Pairs4 &p, const Trig4 &t, b
 }
 
 // Scratch bytes any call needs: tile totals (at most 32 bytes each), four per-token words (insert),
-// one 16-byte descriptor per token (gather, insert) and two flag bytes per token (floating anchors,
-// chain-recording insert), span offsets, one chain head per pool slot, the cos/sin digit tables;
+// one 16-byte descriptor per token (gather, insert), a work-list entry per token (gather) and two flag
+// bytes per token (floating anchors, chain-recording insert), span offsets, one chain head per pool slot, the cos/sin digit tables;
 // pieces padded to 256 bytes.
 constexpr size_t scratch_bytes_for(uint32_t N, uint32_t max_spans, uint32_t n_pool_slots) {
   const uint64_t n = N > max_spans ? N : max_spans;
-  return (size_t)(((n + kScanTile - 1) / kScanTile + 2) * 32 + (4ull * 4 + 16 + 2) * N +
+  return (size_t)(((n + kScanTile - 1) / kScanTile + 2) * 32 + (4ull * 4 + 16 + 2 + 4) * N +
                   4ull * ((uint64_t)max_spans + 1) + 4ull * n_pool_slots +
                   (size_t)kTrigLevels * kTrigDigit * kMaxHalfDim * 16 + 16 * 256);
 }
@@ -264,7 +269,7 @@ __global__ __launch_bounds__(256) void gather_init_kernel(uint32_t *__restrict__
                                                           uint32_t *__restrict__ counter) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_head) head[i] = kNone;
-  if (i == 0) *counter = 0;
+  if (i == 0) counter[0] = counter[2] = counter[3] = 0;  // work counter, work-list counts ([1] is set by the expansion)
 }
 
 // One thread per token of the concatenated spans.
@@ -297,29 +302,91 @@ __global__ __launch_bounds__(256) void gather_expand_kernel(
   items[w] = it;
 }
 
+// The work list of a gather that shares reads: the chain heads, chains of several tokens first and
+// single tokens behind them (so that the long units are not the last ones running).  One thread per
+// token; the lanes of a wavefront that hold heads of one kind take their places with one atomic.
+// counts[0] = chains taken from the front, counts[1] = single tokens taken from the back.
+__global__ __launch_bounds__(256) void gather_heads_kernel(const MoveItem *__restrict__ items,
+                                                           const uint32_t *__restrict__ n_items_ptr,
+                                                           uint32_t max_items, const uint32_t *__restrict__ head,
+                                                           uint32_t *__restrict__ units, uint32_t *counts) {
+  uint32_t n = *n_items_ptr;
+  if (n > max_items) n = max_items;
+  const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+  bool is_head = false, chain = false;
+  if (w < n) {
+    const MoveItem it = items[w];
+    is_head = it.from != kNone && head[it.from] == w;
+    chain = is_head && it.next != kNone;
+  }
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const unsigned long long below = (1ull << lane) - 1ull;
+  const unsigned long long mc = __ballot(chain), ms = __ballot(is_head && !chain);
+  uint32_t base_c = 0, base_s = 0;
+  if (lane == 0) {
+    if (mc) base_c = atomicAdd(&counts[0], (uint32_t)__popcll(mc));
+    if (ms) base_s = atomicAdd(&counts[1], (uint32_t)__popcll(ms));
+  }
+  base_c = __shfl(base_c, 0, kWave);
+  base_s = __shfl(base_s, 0, kWave);
+  // chains and single tokens together are at most n, so the two ends never meet
+  if (chain) units[base_c + __popcll(mc & below)] = w;
+  else if (is_head) units[max_items - 1 - (base_s + __popcll(ms & below))] = w;
+}
+
 // ---- the mover ---------------------------------------------------------------------------------
+
+// One work unit = one chain = all rows of one source token, written to every destination of the chain
+// (at most `fanout` of them per pass).  A workgroup is four mover wavefronts plus one scout wavefront:
+//   - the scout takes the next unit from the atomic counter while the movers are busy with the current
+//     one: it skips tokens that are not the head of a chain, walks the chain, and leaves the unit's
+//     source, destination offsets, deltas and (rotating gather) cos/sin values in the other half of a
+//     double-buffered descriptor in LDS.  Everything serial and latency-bound (dependent loads through
+//     items[] and head[], the trigonometric table products) is thus off the movers' path, and a unit
+//     costs one barrier;
+//   - the 256 mover lanes walk the (row, 16-byte column) space row-major; a round is U vectors per lane:
+//     all of a round's loads are issued before its first store, and a vector goes to all of its
+//     destinations before the next vector is touched.  Rows alternate K, V; with RoPE a lane rotates the
+//     vectors of its K rows (for the Llama shapes a wavefront holds only K or only V rows, so two SIMDs
+//     rotate while two copy).
+// Every wavefront executes exactly one barrier per unit and leaves when the scout reports that the
+// counter has passed the item count, which every workgroup's scout eventually sees.
+// Items that reach the mover name a destination inside `to`: cp_gather_kv's expansion and
+// cp_insert_kv's commit step take out (and flag) every item that does not, so only the source index is
+// checked here.
+struct UnitDesc {
+  uint64_t tobase[kMaxFanout];  // byte offset of every destination token
+  int32_t delta[kMaxFanout];
+  uint32_t from;  // source token; kNone = no more work
+  uint32_t k;     // destinations in this pass
+};
 
 template <class RA, bool ROPE, bool NTL, bool NTS, int U>
 __device__ __forceinline__ void move_rows_body(
     const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
-    const uint32_t *__restrict__ head /* nullable: every item is its own chain */, uint32_t *counter,
-    const uint8_t *__restrict__ from, const cp_kv_layout &fl, uint32_t n_from, uint8_t *__restrict__ to,
-    const cp_kv_layout &tl, uint32_t n_to, uint32_t fanout, uint32_t *status_flags, const RA &rope) {
-  __shared__ uint32_t s_next_w;     // next work item of this workgroup
-  __shared__ uint32_t s_k, s_more;  // destinations in this pass; chain node to continue with
-  __shared__ uint32_t s_to[kMaxFanout];
-  __shared__ int32_t s_delta[kMaxFanout];
-  __shared__ double s_cos[ROPE ? kTrigDoubles : 1], s_sin[ROPE ? kTrigDoubles : 1];
+    const uint32_t *__restrict__ units /* nullable: every item is a unit of its own */,
+    const uint32_t *__restrict__ unit_counts, uint32_t *counter, const uint8_t *__restrict__ from,
+    const cp_kv_layout &fl, uint32_t n_from, uint8_t *__restrict__ to, const cp_kv_layout &tl, uint32_t fanout,
+    uint32_t *status_flags, const RA &rope) {
+  __shared__ UnitDesc s_unit[2];
+  __shared__ double s_cos[2][ROPE ? kTrigDoubles : 1], s_sin[2][ROPE ? kTrigDoubles : 1];
 
   uint32_t n_items = *n_items_ptr;
   if (n_items > max_items) n_items = max_items;
-  // A rotating gather hands out two work units per item: the K rows (arithmetic on every element)
-  // and the V rows (plain copies).  Workgroups of both kinds share a compute unit, so the copies'
-  // memory traffic overlaps the rotations' arithmetic.  Otherwise a unit is all rows of the item.
-  const uint32_t parts = ROPE ? 2u : 1u;
-  const uint32_t n_units = n_items * parts;
-  const uint32_t n_rows = ROPE ? fl.n_layers : fl.n_layers * 2;  // rows of one unit
-  const uint32_t vpr = fl.n_kv_heads * fl.head_dim / 8;          // 16-byte vectors per row
+  // with a work list: its chains are entries 0 .. n_chains-1, its single tokens the last n_single entries
+  uint32_t n_chains = 0, n_units = n_items;
+  if (units) {
+    n_chains = unit_counts[0] < max_items ? unit_counts[0] : max_items;
+    const uint32_t n_single = unit_counts[1] < max_items - n_chains ? unit_counts[1] : max_items - n_chains;
+    n_units = n_chains + n_single;
+  }
+  const uint32_t half = fl.head_dim / 2;
+  const bool scout = threadIdx.x >= kMoveThreads;  // the fifth wavefront
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+
+  // ---- mover lanes: geometry that does not change ----
+  const uint32_t n_rows = fl.n_layers * 2;               // rows of one token: K, V of layer 0, K, V of layer 1, ..
+  const uint32_t vpr = fl.n_kv_heads * fl.head_dim / 8;  // 16-byte vectors per row
   // lane t starts at vector t of the unit and advances by 256 vectors per step
   const uint32_t r_step = kMoveThreads / vpr, c_step = kMoveThreads % vpr;
   const uint32_t r_init = threadIdx.x / vpr, c_init = threadIdx.x % vpr;
@@ -327,50 +394,67 @@ __device__ __forceinline__ void move_rows_body(
   // column of this lane inside its head: the same at every step, because the lane stride (256
   // vectors) and the row length are both multiples of the vectors per head
   const uint32_t cih = threadIdx.x % vph;
-  const bool second = cih >= vph / 2;                          // lane holds second-half elements of its head
+  const bool second = cih >= vph / 2;                                    // lane holds second-half elements of its head
   const uint32_t j_first = first_freq<RA::style>(fl.head_dim / 2, cih);  // its four frequencies start here
-  const uint32_t half = fl.head_dim / 2;
   const uint32_t steps = (n_rows * vpr + kMoveThreads - 1) / kMoveThreads;  // same for every lane
 
-  if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);
-  __syncthreads();
-  while (true) {
-    const uint32_t unit = s_next_w;  // same value in every lane
-    if (unit >= n_units) break;      // the counter only grows: every workgroup gets here
-    const uint32_t w = unit / parts, part = unit % parts;  // part: 0 = K rows, 1 = V rows (rotating gather)
-    const bool rotating = ROPE && part == 0;
-    MoveItem cur = items[w];
-    const bool leader = cur.from != kNone && (head == nullptr || head[cur.from] == w);
-    __syncthreads();  // everyone has read s_next_w
-    if (threadIdx.x == 0) s_next_w = atomicAdd(counter, 1u);  // fetched while this unit is being moved
-    if (leader && cur.from < n_from) {
-      const uint8_t *fbase = from + (uint64_t)cur.from * fl.tok_stride;
-      uint32_t node = w;
-      do {  // passes of at most `fanout` destinations over the same source rows
-        if (threadIdx.x == 0) {
-          uint32_t k = 0, nd = node;
-          MoveItem it = nd == w ? cur : items[nd];
-          while (true) {
-            if (it.to < n_to) {
-              s_to[k] = it.to;
-              s_delta[k] = it.delta;
-              ++k;
-            }
-            nd = it.next;
-            if (nd == kNone || nd >= n_items || k == fanout) break;
-            it = items[nd];
+  // ---- scout state (the same in all 64 lanes of the scout) ----
+  uint32_t more_node = kNone, more_from = kNone;  // chain to continue in the next pass, and its source
+
+  for (uint32_t turn = 0;; ++turn) {
+    const uint32_t b = turn & 1u;
+    if (scout) {
+      // Describe the unit of turn `turn` into s_unit[b]; for turn 0 the movers wait at the barrier
+      // below, afterwards they are moving the unit of turn - 1 out of s_unit[b ^ 1] meanwhile.
+      uint32_t node = more_node, src = more_from;
+      if (node == kNone) {  // a new unit: the next one the counter hands out
+        while (true) {
+          uint32_t i = 0;
+          if (lane == 0) i = atomicAdd(counter, 1u);
+          i = __shfl(i, 0, kWave);
+          if (i >= n_units) break;  // the counter only grows: every scout gets here
+          uint32_t w = i;
+          if (units) w = units[i < n_chains ? i : max_items - 1 - (i - n_chains)];
+          if (w >= n_items) continue;
+          const MoveItem it = items[w];
+          if (it.from == kNone) continue;  // an item that was taken out
+          if (it.from >= n_from) {
+            if (lane == 0) atomicOr(status_flags, CP_FLAG_BAD_INDEX);
+            continue;
           }
-          s_k = k;
-          s_more = (nd != kNone && nd < n_items) ? nd : kNone;
+          node = w;
+          src = it.from;
+          break;
         }
-        __syncthreads();
-        const uint32_t K = s_k;
-        if (rotating) {
-          for (uint32_t i = threadIdx.x; i < K * half; i += kMoveThreads) {
-            const uint32_t k = i / half, j = i - k * half;
-            const int32_t dl = s_delta[k];
-            if (dl != 0) {
-              uint32_t a = dl < 0 ? 0u - (uint32_t)dl : (uint32_t)dl;  // |delta|, digit by digit
+      }
+      uint32_t K = 0;
+      int32_t dl[kMaxFanout];
+#pragma unroll
+      for (uint32_t k = 0; k < kMaxFanout; ++k) {
+        dl[k] = 0;
+        if (k < fanout && node != kNone && node < n_items) {
+          const MoveItem it = items[node];
+          dl[k] = it.delta;
+          if (lane == 0) {
+            s_unit[b].tobase[k] = (uint64_t)it.to * tl.tok_stride;
+            s_unit[b].delta[k] = it.delta;
+          }
+          node = it.next;
+          K = k + 1;
+        }
+      }
+      more_node = (node != kNone && node < n_items) ? node : kNone;
+      more_from = more_node != kNone ? src : kNone;
+      if (lane == 0) {
+        s_unit[b].from = K ? src : kNone;
+        s_unit[b].k = K;
+      }
+      if (ROPE) {
+#pragma unroll
+        for (uint32_t k = 0; k < kMaxFanout; ++k) {
+          if (k < K && dl[k] != 0) {
+            for (uint32_t j = lane; j < half; j += kWave) {
+              uint32_t a = dl[k] < 0 ? 0u - (uint32_t)dl[k] : (uint32_t)dl[k];  // |delta|, digit by digit
               double2 t = rope.tables[(a & (kTrigDigit - 1)) * half + j];
               double cs = t.x, sn = t.y;
 #pragma unroll
@@ -381,88 +465,105 @@ __device__ __forceinline__ void move_rows_body(
                 sn = sn * t.x + cs * t.y;
                 cs = c2;
               }
-              s_cos[i] = cs;
-              s_sin[i] = dl < 0 ? -sn : sn;
-            }
-          }
-          __syncthreads();
-        }
-        uint32_t r = r_init, c = c_init;
-        for (uint32_t j = 0; j < steps; j += U) {
-          u32x4 v[U];
-          uint64_t doff[U];
-          bool ok[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            ok[u] = r < n_rows;  // r only grows, so the valid steps of a lane are a prefix
-            const uint64_t l = ROPE ? r : r >> 1, kv = ROPE ? part : r & 1;
-            doff[u] = l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
-            v[u] = u32x4{0, 0, 0, 0};
-            if (ok[u]) v[u] = load16<NTL>(fbase + l * fl.layer_stride + kv * fl.kv_stride + (uint64_t)c * 16);
-            c += c_step;
-            r += r_step;
-            if (c >= vpr) {
-              c -= vpr;
-              r += 1;
-            }
-          }
-          if (rotating) {
-            // vector-outer, destination-inner: the double-precision copies of one vector's elements
-            // are the only ones alive while its destinations are served
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-              if (!ok[u]) continue;
-              // a lane and its partner are in the same row, so both are here for the exchanges
-              const Pairs4 pairs = widen_pairs<RA::style>(v[u], second, (int)(vph / 2));
-              for (uint32_t k = 0; k < K; ++k) {
-                uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
-                u32x4 x = v[u];
-                if (s_delta[k] != 0)
-                  x = rotate_pairs<RA::style>(pairs, load_trig(j_first, s_cos + k * half, s_sin + k * half), second,
-                                              (int)(vph / 2));
-                store16<NTS>(tbase + doff[u], x);
-              }
-            }
-          } else {
-            for (uint32_t k = 0; k < K; ++k) {
-              uint8_t *tbase = to + (uint64_t)s_to[k] * tl.tok_stride;
-#pragma unroll
-              for (int u = 0; u < U; ++u)
-                if (ok[u]) store16<NTS>(tbase + doff[u], v[u]);
+              s_cos[b][k * half + j] = cs;
+              s_sin[b][k * half + j] = dl[k] < 0 ? -sn : sn;
             }
           }
         }
-        node = s_more;
-        __syncthreads();  // lists and tables are free for the next pass / unit
-      } while (node != kNone);
-    } else {
-      if (cur.from != kNone && cur.from >= n_from && threadIdx.x == 0) atomicOr(status_flags, CP_FLAG_BAD_INDEX);
-      __syncthreads();  // s_next_w is written
+      }
     }
+    __syncthreads();  // s_unit[b] is complete; nobody reads s_unit[b ^ 1] any more
+    const uint32_t src = s_unit[b].from;
+    if (src == kNone) break;  // same value in every lane of the workgroup
+    if (scout) continue;      // on to the next unit's description
+    const uint32_t K = s_unit[b].k;
+    const uint8_t *fbase = from + (uint64_t)src * fl.tok_stride;
+    uint8_t *to0 = to + s_unit[b].tobase[0];  // first destination: known before the loads are issued
+    const bool rot0 = ROPE && s_unit[b].delta[0] != 0;
+    uint32_t r = r_init, c = c_init;
+    // One round: U loads per lane, then the stores.  The first destination's stores are straight-line
+    // code right behind the loads (each waits only for its own load); further destinations of a chain
+    // follow in a loop, when every load has arrived anyway.  FULL: every lane has U valid vectors.
+    auto round = [&](auto full_tag) {
+      constexpr bool FULL = decltype(full_tag)::value;
+      u32x4 v[U];
+      uint64_t doff[U];
+      bool ok[U], is_k[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        ok[u] = FULL || r < n_rows;  // r only grows, so the valid steps of a lane are a prefix
+        is_k[u] = (r & 1u) == 0;
+        const uint64_t l = r >> 1, kv = r & 1u;
+        doff[u] = l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
+        v[u] = u32x4{0, 0, 0, 0};
+        if (ok[u]) v[u] = load16<NTL>(fbase + l * fl.layer_stride + kv * fl.kv_stride + (uint64_t)c * 16);
+        c += c_step;
+        r += r_step;
+        if (c >= vpr) {
+          c -= vpr;
+          r += 1;
+        }
+      }
+      // all of the round's loads are in flight before anything waits for one of them: neither the
+      // compiler nor the instruction scheduler may pair a load with its store
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      Trig4 trig{};
+      if (rot0) trig = load_trig(j_first, s_cos[b], s_sin[b]);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (!ok[u]) continue;
+        u32x4 x = v[u];
+        if (ROPE && is_k[u]) {
+          // a lane and its partner are in the same row, so both are here for the exchanges
+          if (rot0) x = rotate_pairs<RA::style>(widen_pairs<RA::style>(v[u], second, (int)(vph / 2)), trig, second,
+                                                (int)(vph / 2));
+        }
+        store16<NTS>(to0 + doff[u], x);
+      }
+      for (uint32_t k = 1; k < K; ++k) {
+        uint8_t *tk = to + s_unit[b].tobase[k];
+        const bool rot = ROPE && s_unit[b].delta[k] != 0;
+        if (rot) trig = load_trig(j_first, s_cos[b] + k * half, s_sin[b] + k * half);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (!ok[u]) continue;
+          u32x4 x = v[u];
+          // (the double-precision copies are made again per destination: keeping them for all U vectors
+          // would cost the registers that let more wavefronts stay resident)
+          if (ROPE && is_k[u] && rot)
+            x = rotate_pairs<RA::style>(widen_pairs<RA::style>(v[u], second, (int)(vph / 2)), trig, second,
+                                        (int)(vph / 2));
+          store16<NTS>(tk + doff[u], x);
+        }
+      }
+    };
+    const uint32_t full_steps = (n_rows * vpr) / (kMoveThreads * U) * U;  // steps of whole rounds in which every lane works
+    uint32_t j = 0;
+    for (; j < full_steps; j += U) round(std::true_type{});
+    for (; j < steps; j += U) round(std::false_type{});
   }
 }
 
 // The two users of the mover get kernels of their own name, so that profiles tell them apart.
-// (at least 4 wavefronts per SIMD: caps the rotating form at 128 registers so that memory latency
-// hides behind the other wavefronts' arithmetic)
 template <class RA, bool ROPE, bool NTL, bool NTS, int U>
-__global__ __launch_bounds__(kMoveThreads, 4) void gather_rows_kernel(
+__global__ __launch_bounds__(kBlockThreads) void gather_rows_kernel(
     const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
-    const uint32_t *__restrict__ head, uint32_t *counter, const uint8_t *__restrict__ pool, cp_kv_layout pool_l,
-    uint32_t n_pool_slots, uint8_t *__restrict__ dst, cp_kv_layout dst_l, uint32_t n_dst_tokens, uint32_t fanout,
-    uint32_t *status_flags, RA rope) {
-  move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, head, counter, pool, pool_l, n_pool_slots, dst,
-                                        dst_l, n_dst_tokens, fanout, status_flags, rope);
+    const uint32_t *__restrict__ units, const uint32_t *__restrict__ unit_counts, uint32_t *counter,
+    const uint8_t *__restrict__ pool, cp_kv_layout pool_l, uint32_t n_pool_slots, uint8_t *__restrict__ dst,
+    cp_kv_layout dst_l, uint32_t fanout, uint32_t *status_flags, RA rope) {
+  move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, units, unit_counts, counter, pool, pool_l,
+                                        n_pool_slots, dst, dst_l, fanout, status_flags, rope);
 }
 
 template <class RA, bool ROPE, bool NTL, bool NTS, int U>
-__global__ __launch_bounds__(kMoveThreads) void scatter_rows_kernel(
+__global__ __launch_bounds__(kBlockThreads) void scatter_rows_kernel(
     const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
-    const uint32_t *__restrict__ head, uint32_t *counter, const uint8_t *__restrict__ src, cp_kv_layout src_l,
-    uint32_t n_src_tokens, uint8_t *__restrict__ pool, cp_kv_layout pool_l, uint32_t n_pool_slots, uint32_t fanout,
-    uint32_t *status_flags, RA rope) {
-  move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, head, counter, src, src_l, n_src_tokens, pool,
-                                        pool_l, n_pool_slots, fanout, status_flags, rope);
+    const uint32_t *__restrict__ units, const uint32_t *__restrict__ unit_counts, uint32_t *counter,
+    const uint8_t *__restrict__ src, cp_kv_layout src_l, uint32_t n_src_tokens, uint8_t *__restrict__ pool,
+    cp_kv_layout pool_l, uint32_t fanout, uint32_t *status_flags, RA rope) {
+  move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, units, unit_counts, counter, src, src_l,
+                                        n_src_tokens, pool, pool_l, fanout, status_flags, rope);
 }
 
 uint32_t cu_count() {
@@ -479,14 +580,26 @@ uint32_t cu_count() {
 
 template <class RA, bool ROPE, bool GATHER>
 int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n_items, uint32_t max_items,
-                    const uint32_t *head, uint32_t *counter, const void *from, const cp_kv_layout &fl, uint32_t n_from,
-                    void *to, const cp_kv_layout &tl, uint32_t n_to, uint32_t *status_flags, const RA &rope,
-                    const MoveOpts &mo) {
+                    const uint32_t *units, const uint32_t *unit_counts, uint32_t *counter, const void *from,
+                    const cp_kv_layout &fl, uint32_t n_from, void *to, const cp_kv_layout &tl, uint32_t *status_flags,
+                    const RA &rope, const MoveOpts &mo) {
   if (max_items == 0) return CP_OK;
   if (mo.start && hipEventRecord(mo.start, stream) != hipSuccess) return CP_ERR_HIP;
-  uint64_t grid = (uint64_t)cu_count() * mo.blocks_per_cu;
-  const uint64_t max_units = (uint64_t)max_items * (ROPE ? 2 : 1);
-  if (grid > max_units) grid = max_units;
+  // Defaults, measured on MI355X with the Llama row shapes.  Copy form: 16 loads in flight per lane and
+  // one workgroup on seven of every eight compute units (224 of 256; one per unit is 1 % slower, two per
+  // unit with 8 loads 3-6 % slower).  Rotating form: the arithmetic wants more wavefronts with fewer
+  // registers: 4 loads in flight, three workgroups per unit (8 loads: a third slower).  Small tokens
+  // get as many loads as they have steps for.
+  const uint64_t steps = div_up((uint64_t)fl.n_layers * 2 * (fl.n_kv_heads * fl.head_dim / 8), kMoveThreads);
+  uint32_t lif = mo.loads_in_flight ? mo.loads_in_flight : ROPE ? 4u : (steps >= 32 ? 16u : steps >= 16 ? 8u : 4u);
+  if (ROPE && lif > 8) lif = 8;  // the rotating form is not built with 16: it needs its registers for arithmetic
+  const uint32_t cus = cu_count();
+  uint64_t grid = mo.workgroups      ? mo.workgroups
+                  : mo.blocks_per_cu ? (uint64_t)cus * mo.blocks_per_cu
+                  : ROPE             ? (uint64_t)cus * 3
+                  : lif >= 16        ? cus - cus / 8
+                                     : (uint64_t)cus * 2;
+  if (grid > max_items) grid = max_items;
   uint32_t fanout = mo.fanout < kMaxFanout ? mo.fanout : kMaxFanout;
   if (ROPE) {
     uint32_t cap = kTrigDoubles / (fl.head_dim / 2);
@@ -496,12 +609,12 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   uint8_t *t = (uint8_t *)to;
 #define CP_LAUNCH(NTL, NTS, UN)                                                                              \
   if constexpr (GATHER)                                                                                      \
-    gather_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                 \
-        items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope);   \
+    gather_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kBlockThreads, 0, stream>>>(                 \
+        items, n_items, max_items, units, unit_counts, counter, f, fl, n_from, t, tl, fanout, status_flags, rope); \
   else                                                                                                       \
-    scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kMoveThreads, 0, stream>>>(                \
-        items, n_items, max_items, head, counter, f, fl, n_from, t, tl, n_to, fanout, status_flags, rope)
-  switch ((mo.nontemporal & 3u) | (mo.loads_in_flight >= 8 ? 4u : 0u)) {
+    scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kBlockThreads, 0, stream>>>(                \
+        items, n_items, max_items, units, unit_counts, counter, f, fl, n_from, t, tl, fanout, status_flags, rope)
+  switch ((mo.nontemporal & 3u) | (lif >= 16 ? 8u : lif >= 8 ? 4u : 0u)) {
     case 0: CP_LAUNCH(false, false, 4); break;
     case 1: CP_LAUNCH(true, false, 4); break;
     case 2: CP_LAUNCH(false, true, 4); break;
@@ -509,7 +622,17 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
     case 4: CP_LAUNCH(false, false, 8); break;
     case 5: CP_LAUNCH(true, false, 8); break;
     case 6: CP_LAUNCH(false, true, 8); break;
-    default: CP_LAUNCH(true, true, 8); break;
+    case 7: CP_LAUNCH(true, true, 8); break;
+    default:
+      if constexpr (!ROPE) {
+        switch (mo.nontemporal & 3u) {
+          case 0: CP_LAUNCH(false, false, 16); break;
+          case 1: CP_LAUNCH(true, false, 16); break;
+          case 2: CP_LAUNCH(false, true, 16); break;
+          default: CP_LAUNCH(true, true, 16); break;
+        }
+      }
+      break;
   }
 #undef CP_LAUNCH
   if (int32_t rc = check_launch()) return rc;
@@ -524,8 +647,9 @@ int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &
                        const uint32_t *n_items, uint32_t max_items, uint32_t *counter, uint32_t *status_flags,
                        const MoveOpts &mo) {
   NoRope none{};
-  return launch_move<NoRope, false, false>(stream, items, n_items, max_items, nullptr, counter, src, src_l, n_src_tokens, pool,
-                                    pool_l, n_pool_slots, status_flags, none, mo);
+  (void)n_pool_slots;  // the commit step has checked every slot it put on the list
+  return launch_move<NoRope, false, false>(stream, items, n_items, max_items, nullptr, nullptr, counter, src, src_l,
+                                           n_src_tokens, pool, pool_l, status_flags, none, mo);
 }
 
 }  // namespace cp
@@ -555,12 +679,13 @@ int32_t gather_impl(hipStream_t stream, const void *pool, const cp_kv_layout &po
   Scratch sc(work, work_bytes);
   uint32_t *agg = sc.take<uint32_t>(div_up(max_spans, kScanTile) + 1);
   uint32_t *offs = sc.take<uint32_t>((size_t)max_spans + 1);
-  uint32_t *counters = sc.take<uint32_t>(2);  // [0] work counter, [1] item count
+  uint32_t *counters = sc.take<uint32_t>(4);  // [0] work counter, [1] item count, [2] chains and [3] single tokens on the work list
   MoveItem *items = sc.take<MoveItem>(n_dst_tokens);
   const bool group = mo.share_reads;
   uint32_t *head = group ? sc.take<uint32_t>(n_pool_slots) : nullptr;
+  uint32_t *units = group ? sc.take<uint32_t>(n_dst_tokens) : nullptr;
   double2 *tables = use_rope ? sc.take<double2>((size_t)kTrigLevels * kTrigDigit * (pool_l.head_dim / 2)) : nullptr;
-  if (!agg || !offs || !counters || !items || (group && !head) || (use_rope && !tables)) return CP_ERR_SCRATCH;
+  if (!agg || !offs || !counters || !items || (group && (!head || !units)) || (use_rope && !tables)) return CP_ERR_SCRATCH;
   if (use_rope) {
     InvFreq inv{};
     const uint32_t D = pool_l.head_dim;
@@ -577,18 +702,21 @@ int32_t gather_impl(hipStream_t stream, const void *pool, const cp_kv_layout &po
   gather_expand_kernel<<<div_up(n_dst_tokens, 256), 256, 0, stream>>>(
       span_src, span_dst, span_off, use_rope ? span_delta : nullptr, n_spans, max_spans, n_pool_slots, n_dst_tokens,
       items, head, counters + 1, status_flags);
+  if (group)
+    gather_heads_kernel<<<div_up(n_dst_tokens, 256), 256, 0, stream>>>(items, counters + 1, n_dst_tokens, head, units,
+                                                                       counters + 2);
   if (int32_t rc = check_launch()) return rc;
   if (use_rope && rope->style == 0)
-    return launch_move<RopeArg<0>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                               n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<0>{tables},
+    return launch_move<RopeArg<0>, true, true>(stream, items, counters + 1, n_dst_tokens, units, counters + 2, counters,
+                                               pool, pool_l, n_pool_slots, dst, dst_l, status_flags, RopeArg<0>{tables},
                                                mo);
   if (use_rope)
-    return launch_move<RopeArg<1>, true, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                               n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, RopeArg<1>{tables},
+    return launch_move<RopeArg<1>, true, true>(stream, items, counters + 1, n_dst_tokens, units, counters + 2, counters,
+                                               pool, pool_l, n_pool_slots, dst, dst_l, status_flags, RopeArg<1>{tables},
                                                mo);
   NoRope none{};
-  return launch_move<NoRope, false, true>(stream, items, counters + 1, n_dst_tokens, head, counters, pool, pool_l,
-                                          n_pool_slots, dst, dst_l, n_dst_tokens, status_flags, none, mo);
+  return launch_move<NoRope, false, true>(stream, items, counters + 1, n_dst_tokens, units, counters + 2, counters, pool,
+                                          pool_l, n_pool_slots, dst, dst_l, status_flags, none, mo);
 }
 
 // ---- the entry point that brings its own scratch memory -----------------------------------------
