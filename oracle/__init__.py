@@ -81,7 +81,9 @@ def lib():
         L.cpo_anchor_set_size.argtypes = [vp]
         L.cpo_run_offsets.argtypes = [vp, vp, u32, vp]
         L.cpo_insert_anchors.argtypes = [vp, vp, vp, vp, u32, u32]
-        L.cpo_hash_floating.argtypes = [vp, vp, vp, u32, u64, u32, vp, vp]
+        L.cpo_hash_floating.argtypes = [vp, vp, vp, vp, u32, u64, u32, vp, vp, vp, vp]
+        L.cpo_probe3.restype = None
+        L.cpo_probe3.argtypes = [vp, vp, vp, vp, u32, vp]
         L.cpo_text_new.restype = vp
         L.cpo_text_new.argtypes = [u32]
         L.cpo_text_free.argtypes = [vp]
@@ -162,13 +164,38 @@ def insert_anchors(anchors: AnchorSet, hashes, run_off, slot, W):
     lib().cpo_insert_anchors(anchors._h, _p(hashes), _p(run_off), _p(slot), hashes.shape[0], int(W))
 
 
-def hash_floating(anchors: AnchorSet, hashes, run_off, W, base=BASE, with_offsets=False):
+def hash_floating(anchors: AnchorSet, index: Index, hashes, run_off, W, base=BASE):
+    """Keys of the two candidate streams: (hash_early, early_off, hash_late, late_off)."""
     hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
-    out = np.empty(hashes.shape[0], np.uint64)
-    foff = np.empty(hashes.shape[0], np.uint32) if with_offsets else None
-    lib().cpo_hash_floating(anchors._h, _p(hashes), _p(run_off), hashes.shape[0], base, int(W), _p(out),
-                            _p(foff) if with_offsets else None)
-    return (out, foff) if with_offsets else out
+    n = hashes.shape[0]
+    he, hl = np.empty(n, np.uint64), np.empty(n, np.uint64)
+    eo, lo = np.empty(n, np.uint32), np.empty(n, np.uint32)
+    lib().cpo_hash_floating(anchors._h, index._h, _p(hashes), _p(run_off), n, base, int(W), _p(he), _p(eo), _p(hl),
+                            _p(lo))
+    return he, eo, hl, lo
+
+
+def match_streams(index: Index, tok, hashes, run_off, anchors: AnchorSet = None, W=None, text: "Text" = None):
+    """What every key stream of a lookup finds, in the order in which they serve a token: the run-start
+    keys, then (pools with floating anchors) the earliest-candidate keys and the latest-candidate keys.
+    With ``text`` each stream's slots are confirmed against the stored text along its own segments."""
+    streams = [(hashes, run_off)]
+    if anchors is not None:
+        he, eo, hl, lo = hash_floating(anchors, index, hashes, run_off, W)
+        streams += [(he, eo), (hl, lo)]
+    out = []
+    for keys, seg_off in streams:
+        s = probe(index, keys)
+        out.append(s if text is None else verify(text, tok, seg_off, s))
+    return out
+
+
+def merge_streams(streams):
+    """A token is served from the first stream that has a slot for it."""
+    out = np.array(streams[0], np.uint32, copy=True)
+    for s in streams[1:]:
+        out = np.where(out == SLOT_NONE, s, out).astype(np.uint32)
+    return out
 
 
 class Text:
@@ -202,6 +229,16 @@ def probe2(index: Index, hash_a, hash_b):
     hash_a, hash_b = _arr(hash_a, np.uint64), _arr(hash_b, np.uint64)
     out = np.empty(hash_a.shape[0], np.uint32)
     lib().cpo_probe2(index._h, _p(hash_a), _p(hash_b), hash_a.shape[0], _p(out))
+    return out
+
+
+def probe3(index: Index, hash_a, hash_b=None, hash_c=None):
+    hash_a = _arr(hash_a, np.uint64)
+    hash_b = None if hash_b is None else _arr(hash_b, np.uint64)
+    hash_c = None if hash_c is None else _arr(hash_c, np.uint64)
+    out = np.empty(hash_a.shape[0], np.uint32)
+    lib().cpo_probe3(index._h, _p(hash_a), None if hash_b is None else _p(hash_b), None if hash_c is None else _p(hash_c),
+                     hash_a.shape[0], _p(out))
     return out
 
 

@@ -257,47 +257,86 @@ extern "C" void cpo_insert_anchors(cpo_anchor_set *as, const uint64_t *hash, con
       as->set.emplace(hash[i], slot[i]);
 }
 
-extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const uint64_t *hash,
+extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const cpo_index *ix, const uint64_t *hash,
                                   const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
-                                  uint64_t *hash_float_out, uint32_t *float_off_out) {
+                                  uint64_t *hash_early_out, uint32_t *early_off_out,
+                                  uint64_t *hash_late_out, uint32_t *late_off_out) {
   // precomputed powers of the base
   std::vector<uint64_t> pw((size_t)N + 1);
   pw[0] = 1;
   for (uint32_t k = 1; k <= N; ++k) pw[k] = pw[k - 1] * base;
-  // hash of tokens a..i of one run, from the run's chain hashes: h[i] - h[a-1] * base^(i-a+1)
+  // key of tokens a..i of one run, from the run's chain hashes: h[i] - h[a-1] * base^(i-a+1)
   auto sub = [&](uint32_t a, uint32_t i) {
     uint64_t before = run_off[a] == 0 ? 0 : hash[a - 1];
-    return hash[i] - before * pw[i - a + 1];
+    uint64_t h = hash[i] - before * pw[i - a + 1];
+    return h == CPO_HASH_NONE ? CPO_HASH_NONE - 1 : h;  // stored hashes never take the reserved value
   };
-  // Step 1: slide the window; window ending at i starts at a = i - W + 1
-  std::vector<uint8_t> anchor_at(N, 0);
   for (uint32_t i = 0; i < N; ++i) {
-    if (hash[i] == CPO_HASH_NONE || run_off[i] + 1 < W) continue;  // window would leave the run
-    uint32_t a = i - (W - 1);
-    if (run_off[a] == 0) continue;  // at the run start the plain chain hash already is this key
-    uint64_t wh = sub(a, i);
-    if (wh == CPO_HASH_NONE) wh = CPO_HASH_NONE - 1;  // stored hashes never take the reserved value
-    if (as->set.count(wh)) anchor_at[a] = 1;
+    hash_early_out[i] = CPO_HASH_NONE;
+    if (early_off_out) early_off_out[i] = 0xFFFFFFFFu;
+    if (hash_late_out) hash_late_out[i] = CPO_HASH_NONE;
+    if (late_off_out) late_off_out[i] = 0xFFFFFFFFu;
   }
-  // Step 2: key of every token from its latest anchor
-  bool have = false;
-  uint32_t a = 0;
-  for (uint32_t i = 0; i < N; ++i) {
-    hash_float_out[i] = CPO_HASH_NONE;
-    if (float_off_out) float_off_out[i] = 0xFFFFFFFFu;
-    if (hash[i] == CPO_HASH_NONE) {
-      have = false;
+  // run by run
+  for (uint32_t s0 = 0; s0 < N;) {
+    if (hash[s0] == CPO_HASH_NONE) {
+      ++s0;
       continue;
     }
-    if (run_off[i] == 0) have = false;  // a new run
-    if (anchor_at[i]) {
-      have = true;
-      a = i;
+    uint32_t s1 = s0 + 1;  // the run is s0 .. s1-1
+    while (s1 < N && hash[s1] != CPO_HASH_NONE && run_off[s1] != 0) ++s1;
+    // Step 1: the candidates.  A window that starts at a (after the run's first token: there the
+    // plain chain hash already is this key) and lies inside the run is compared with the stored
+    // prefix hashes.
+    std::vector<uint32_t> cand;
+    for (uint32_t a = s0 + 1; a + W <= s1; ++a)
+      if (as->set.count(sub(a, a + W - 1))) cand.push_back(a);
+    // Step 2, pre-check by substring hashes: how far does the stored text that starts at candidate a
+    // go on?  ext[c] = last token e such that every key (a .. j), a+W-1 <= j <= e, is stored.
+    std::vector<uint32_t> ext(cand.size());
+    for (size_t c = 0; c < cand.size(); ++c) {
+      uint32_t e = cand[c] + W - 1;
+      while (e + 1 < s1 && ix->map.count(sub(cand[c], e + 1))) ++e;
+      ext[c] = e;
     }
-    if (have) {
-      uint64_t h = sub(a, i);
-      hash_float_out[i] = (h == CPO_HASH_NONE) ? CPO_HASH_NONE - 1 : h;
-      if (float_off_out) float_off_out[i] = i - a;
+    for (uint32_t i = s0 + 1; i < s1; ++i) {
+      // the earliest candidate whose stored text reaches token i ...
+      size_t first = cand.size();
+      for (size_t c = 0; c < cand.size() && cand[c] <= i; ++c)
+        if (ext[c] >= i) {
+          first = c;
+          break;
+        }
+      // ... counts if it starts on text that no earlier candidate covers (a candidate that starts inside
+      // an earlier one's text is left to the second stream)
+      if (first != cand.size()) {
+        bool inside_earlier = false;
+        for (size_t c = 0; c < first; ++c) inside_earlier = inside_earlier || ext[c] >= cand[first];
+        if (!inside_earlier) {
+          hash_early_out[i] = sub(cand[first], i);
+          if (early_off_out) early_off_out[i] = i - cand[first];
+        }
+      }
+      // the latest candidate at or before token i
+      size_t last = cand.size();
+      for (size_t c = 0; c < cand.size() && cand[c] <= i; ++c) last = c;
+      if (last != cand.size()) {
+        if (hash_late_out) hash_late_out[i] = sub(cand[last], i);
+        if (late_off_out) late_off_out[i] = i - cand[last];
+      }
+    }
+    s0 = s1;
+  }
+}
+
+extern "C" void cpo_probe3(const cpo_index *ix, const uint64_t *hash_a, const uint64_t *hash_b,
+                           const uint64_t *hash_c, uint32_t N, uint32_t *slot_out) {
+  for (uint32_t i = 0; i < N; ++i) {
+    slot_out[i] = CPO_SLOT_NONE;
+    for (const uint64_t *keys : {hash_a, hash_b, hash_c}) {
+      if (slot_out[i] != CPO_SLOT_NONE || keys == nullptr || keys[i] == CPO_HASH_NONE) continue;
+      auto it = ix->map.find(keys[i]);
+      if (it != ix->map.end()) slot_out[i] = it->second;
     }
   }
 }

@@ -114,8 +114,12 @@ uint32_t cpo_insert_kv(cpo_index *, const uint64_t *hash, const uint32_t *off, u
  * tokens.  A lookup slides a W-token window over each run of the request; where the window's hash is
  * one of the stored prefix hashes, a stored run may start there ("anchor"), and the tokens from
  * there on get a second key: the hash of the request's tokens from the anchor through the token,
- * computed in O(1) from the run's chain hashes and a power of the base.  A token is served under
- * its run-start key if that hits, else under the key of the latest anchor at or before it. */
+ * computed in O(1) from the run's chain hashes and a power of the base.  Step 1 yields a set of
+ * candidates and Step 2 checks each of them over the text stored behind it; a request token can lie in
+ * the text of several candidates.  Two key streams carry them: the earliest candidate whose stored
+ * text reaches the token (if that candidate starts on text no earlier candidate covers), and the
+ * latest candidate at or before the token.  A token is served under its run-start key if that hits,
+ * else under the first stream's key, else under the second's. */
 typedef struct cpo_anchor_set cpo_anchor_set; /* prefix hash -> slot of the run's W-th token. Opaque. */
 cpo_anchor_set *cpo_anchor_set_new(void);
 void cpo_anchor_set_free(cpo_anchor_set *);
@@ -131,16 +135,26 @@ void cpo_run_offsets(const uint8_t *mask, const uint32_t *off, uint32_t R, uint3
 void cpo_insert_anchors(cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off,
                         const uint32_t *slot, uint32_t N, uint32_t W);
 
-/* hash_float_out[i] = hash of the tokens from the latest anchor a <= i of i's run through i, where
- * an anchor is a position a > run start such that the W tokens from a lie inside the run and their
- * hash is in the set; CPO_HASH_NONE where there is no such anchor (and for sensitive tokens). */
-void cpo_hash_floating(const cpo_anchor_set *, const uint64_t *hash, const uint32_t *run_off,
-                       uint32_t N, uint64_t base, uint32_t W, uint64_t *hash_float_out,
-                       uint32_t *float_off_out /* nullable: i - a, 0xFFFFFFFF without an anchor */);
+/* A candidate is a position a after its run's first token such that the W tokens from a lie inside the
+ * run and their hash is in the set.  Its stored text reaches e = ext(a): the last token of the run
+ * such that every key (tokens a..j), a+W-1 <= j <= e, is in the index (the pre-check by substring
+ * hashes of Step 2).
+ *   hash_early_out[i] = key of tokens a..i for the earliest candidate a <= i of i's run with
+ *     ext(a) >= i, provided no earlier candidate's text reaches a (ext(b) >= a for some b < a);
+ *   hash_late_out[i]  = key of tokens a..i for the latest candidate a <= i of i's run;
+ * CPO_HASH_NONE where there is none (and for sensitive tokens).  *_off_out (nullable): i - a, or
+ * 0xFFFFFFFF.  hash_late_out may be NULL. */
+void cpo_hash_floating(const cpo_anchor_set *, const cpo_index *, const uint64_t *hash,
+                       const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
+                       uint64_t *hash_early_out, uint32_t *early_off_out, uint64_t *hash_late_out,
+                       uint32_t *late_off_out);
 
 /* Lookup with two keys per token: slot under hash_a if present, else under hash_b, else NONE. */
 void cpo_probe2(const cpo_index *, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                 uint32_t *slot_out);
+/* ... with three keys (hash_b, hash_c may be NULL). */
+void cpo_probe3(const cpo_index *, const uint64_t *hash_a, const uint64_t *hash_b, const uint64_t *hash_c,
+                uint32_t N, uint32_t *slot_out);
 
 /* ---- Exact verification (Sec. 4.2.2, Step 2 "full verification") ----
  * A hash match is only a candidate.  The paper confirms it with a cryptographic hash of the

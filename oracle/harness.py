@@ -143,18 +143,13 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
     times["hash"] = time.perf_counter() - t
     hf = roff = None
     t = time.perf_counter()
-    if st.text is not None:
-        roff = O.run_offsets(mask, off)
-        slot = O.verify(st.text, tok, roff, O.probe(st.index, h))
-        if st.anchors is not None:
-            hf, foff = O.hash_floating(st.anchors, h, roff, st.anchor_window, with_offsets=True)
-            slot = O.verify(st.text, tok, foff, O.probe(st.index, hf), merge_into=slot)
-    elif st.anchors is None:
+    if st.text is None and st.anchors is None:
         slot = O.probe(st.index, h)
     else:
         roff = O.run_offsets(mask, off)
-        hf = O.hash_floating(st.anchors, h, roff, st.anchor_window)
-        slot = O.probe2(st.index, h, hf)
+        if st.anchors is not None:
+            hf = O.hash_floating(st.anchors, st.index, h, roff, st.anchor_window)[0]
+        slot = O.merge_streams(O.match_streams(st.index, tok, h, roff, st.anchors, st.anchor_window, st.text))
     times["probe"] = time.perf_counter() - t
     use_rope = wl.rope_theta is not None
     served = slot

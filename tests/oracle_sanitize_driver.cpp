@@ -53,19 +53,25 @@ void life_cycle(uint32_t seed, uint32_t vocab, uint32_t W, bool rope) {
     const uint32_t N = (uint32_t)tok.size();
     std::vector<uint8_t> mask(N), rec(N);
     for (uint32_t i = 0; i < N; ++i) mask[i] = rng() % 12 == 0, rec[i] = rng() % 4 == 0;
-    std::vector<uint64_t> h(N), hf(N);
-    std::vector<uint32_t> ro(N), fo(N), cand(N), got(N), own_b(N), served(N);
+    std::vector<uint64_t> h(N), hf(N), hl(N);
+    std::vector<uint32_t> ro(N), fo(N), lo(N), cand(N), got(N), own_b(N), own_c(N), served(N);
     cpo_hash_segments(tok.data(), mask.data(), off.data(), R, 0x100000001B3ull, h.data());
     cpo_run_offsets(mask.data(), off.data(), R, ro.data());
-    // lookup: run-start keys, floating keys, both confirmed, merged; policies; spans; gather; zero fill
+    // lookup: run-start keys and the two candidate streams, each confirmed, merged; policies; spans; gather; zero fill
     cpo_probe(ix, h.data(), N, cand.data());
     cpo_verify(text, tok.data(), ro.data(), cand.data(), N, 0, got.data());
-    cpo_hash_floating(anchors, h.data(), ro.data(), N, 0x100000001B3ull, W, hf.data(), fo.data());
+    cpo_hash_floating(anchors, ix, h.data(), ro.data(), N, 0x100000001B3ull, W, hf.data(), fo.data(), hl.data(), lo.data());
     cpo_probe(ix, hf.data(), N, cand.data());
     cpo_verify(text, tok.data(), fo.data(), cand.data(), N, 0, own_b.data());
     cpo_verify(text, tok.data(), fo.data(), cand.data(), N, 1, got.data());
+    cpo_probe(ix, hl.data(), N, cand.data());
+    cpo_verify(text, tok.data(), lo.data(), cand.data(), N, 0, own_c.data());
+    cpo_verify(text, tok.data(), lo.data(), cand.data(), N, 1, got.data());
     cpo_probe2(ix, h.data(), hf.data(), N, cand.data());
+    cpo_probe3(ix, h.data(), hf.data(), hl.data(), N, cand.data());
+    cpo_probe3(ix, h.data(), nullptr, nullptr, N, cand.data());
     cpo_touch(own_b.data(), N, epoch, S, stamps.data());
+    cpo_touch(own_c.data(), N, epoch, S, stamps.data());
     cpo_touch(got.data(), N, epoch, S, stamps.data());
     cpo_filter_matches(got.data(), off.data(), R, 1 + seed % 4, marks.data(), S, served.data());
     const uint32_t max_spans = N ? 1 + rng() % N : 1;  // sometimes too few: the overflow path

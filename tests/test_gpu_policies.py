@@ -150,17 +150,10 @@ class Lifecycle:
         h = O.hash_segments(tok, mask, off)
         ro = O.run_offsets(mask, off)
         plain = O.probe(self.ix, h)
-        if self.text is not None:
-            got = O.verify(self.text, tok, ro, plain)
-            if self.anchors is not None:
-                hf, fo = O.hash_floating(self.anchors, h, ro, self.W, with_offsets=True)
-                own_b = O.verify(self.text, tok, fo, O.probe(self.ix, hf))
-                O.touch(own_b, epoch, self.stamps)  # slots the floating stream walked through count as used
-                got = O.verify(self.text, tok, fo, O.probe(self.ix, hf), merge_into=got)
-        elif self.anchors is not None:
-            got = O.probe2(self.ix, h, O.hash_floating(self.anchors, h, ro, self.W))
-        else:
-            got = plain
+        streams = O.match_streams(self.ix, tok, h, ro, self.anchors, self.W, self.text)
+        for own in streams[1:]:  # slots a candidate stream walked through count as used, whichever stream serves
+            O.touch(own, epoch, self.stamps)
+        got = O.merge_streams(streams)
         O.touch(got, epoch, self.stamps)
         served = O.filter_matches(got, off, self.min_len, self.marks)
         src, dpos, ln, delta, n, fl = O.build_spans(served, off)

@@ -230,11 +230,8 @@ def test_two_key_streams_keep_stored_runs_prefix_closed_under_lru(seed):
         off = np.concatenate([[0], np.cumsum([len(x) for x in parts])]).astype(np.uint32)
         h, ro = O.hash_segments(tok, mask, off), O.run_offsets(mask, off)
         plain = O.probe(ix, h)
-        hf, fo = O.hash_floating(anchors, h, ro, W, with_offsets=True)
-        own_a = O.verify(text, tok, ro, plain)
-        own_b = O.verify(text, tok, fo, O.probe(ix, hf))
-        O.touch(own_a, epoch, stamps)
-        O.touch(own_b, epoch, stamps)
+        for own in O.match_streams(ix, tok, h, ro, anchors, W, text):  # what every key stream accepted counts as used
+            O.touch(own, epoch, stamps)
         assert closed(), ("lookup", epoch)
         new_keys = len({int(x) for x, g in zip(h, plain) if g == NONE and x != O.HASH_NONE})
         if new_keys > len(free):

@@ -195,9 +195,14 @@ def test_floating_segments_are_verified_from_their_anchor():
     m, roff = np.zeros(len(req), np.uint8), np.array([0, len(req)], np.uint32)
     h = O.hash_segments(req, m, roff)
     ro = O.run_offsets(m, roff)
-    hf, fo = O.hash_floating(anchors, h, ro, W, with_offsets=True)
-    assert list(fo[:7]) == [X] * 7 and list(fo[7:]) == list(range(len(req) - 7))
+    hf, fo, hl, lo = O.hash_floating(anchors, P.ix, h, ro, W)
+    # the stored text reaches 20 tokens from the candidate; the latest candidate stays the latest to the run's end
+    assert list(fo[:7]) == [X] * 7 and list(fo[7:27]) == list(range(20)) and list(fo[27:]) == [X] * (len(req) - 27)
+    assert list(lo[:7]) == [X] * 7 and list(lo[7:]) == list(range(len(req) - 7))
     a = O.verify(P.text, req, ro, O.probe(P.ix, h))
     assert (a == NONE).all()  # nothing matches from the run start
-    b = O.verify(P.text, req, fo, O.probe(P.ix, hf), merge_into=a)
-    assert np.array_equal(b[7:27], so[:20]) and (b[27:] == NONE).all() and (b[:7] == NONE).all()
+    for keys, seg in ((hf, fo), (hl, lo)):
+        b = O.verify(P.text, req, seg, O.probe(P.ix, keys), merge_into=a)
+        assert np.array_equal(b[7:27], so[:20]) and (b[27:] == NONE).all() and (b[:7] == NONE).all()
+    streams = O.match_streams(P.ix, req, h, ro, anchors, W, P.text)
+    assert np.array_equal(O.merge_streams(streams), b)
