@@ -7,7 +7,7 @@
  *
  * and, further down, the calls that widen it to the paper's retrieval and pool
  * life cycle: floating anchors (cp_hash_runs, cp_insert_anchors, cp_hash_floating,
- * cp_probe2), exact confirmation of matches (cp_insert_kv_chain, cp_verify_chain),
+ * cp_probe2, cp_probe3), exact confirmation of matches (cp_insert_kv_chain, cp_verify_chain),
  * pool policies (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch,
  * cp_lru_threshold, cp_evict, cp_table_compact) and the KV annotator
  * (cp_sat_build, cp_annotate).
@@ -153,8 +153,9 @@ int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N,
 
 /* ---- Floating anchors: matches that do not start at the start of a run --------------------------
  * Sec. 4.2.2 Step 1 ("prefix filtering"): every stored segment keeps the hash of its first W tokens;
- * a W-token window slides over the request and is compared with those prefix hashes.  Step 2: the
- * hash of any substring follows in O(1) from prefix hashes and a power of the base.  Here:
+ * a W-token window slides over the request and is compared with those prefix hashes, which yields a
+ * set of candidates.  Step 2: each candidate is checked over the text stored behind it; the hash of
+ * any substring follows in O(1) from prefix hashes and a power of the base.  Here:
  *   - cp_hash_runs is cp_hash_segments that also returns run_off[i], the number of tokens between
  *     the start of token i's run and i (0xFFFFFFFF for sensitive tokens);
  *   - the hash of a stored run's first W tokens is the table key of the run's W-th token, so the
@@ -163,26 +164,39 @@ int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N,
  *     prefix hashes.  cp_insert_anchors, called after an insert with the slot_out it reported, sets
  *     slot_anchor[slot[i]] = 1 for every token with run_off[i] == W - 1 and a slot.  A prefix hash
  *     thus lives exactly as long as the run's W-th token is stored (cp_evict clears the mark);
- *   - cp_hash_floating marks as anchor every position a after its run's start whose W-token window
- *     lies inside the run and hashes to a key of `table` whose slot is marked, and gives every token
- *     i the key of the request's tokens a..i for the latest anchor a <= i of its run:
- *         hash_float_out[i] = hash[i] - hash[a-1] * base^(i-a+1)   (mod 2^64; CP_HASH_NONE -> NONE-1),
- *     CP_HASH_NONE where there is no such anchor.  That key equals the chain hash the same tokens
- *     get as the beginning of a stored run, so it is looked up in the ordinary table;
- *   - cp_probe2 looks every token up under hash_a and, if that misses, under hash_b.
- * A token is thus served under its run-start key if possible, else from its latest anchor.
+ *   - a candidate is a position a after its run's first token whose W-token window lies inside the
+ *     run and hashes to a key of `table` whose slot is marked.  Its stored text reaches ext(a), the
+ *     last token e of the run such that the key of the request's tokens a..j,
+ *         hash[j] - hash[a-1] * base^(j-a+1)   (mod 2^64; CP_HASH_NONE -> NONE-1),
+ *     is in `table` for every j from the window's end through e.  That key equals the chain hash the
+ *     same tokens get as the beginning of a stored run, so it is looked up in the ordinary table.
+ *     (Stored runs are closed under taking prefixes - every insert, truncation and eviction of this
+ *     library keeps them so - and ext(a) is found by bisection.)
+ *   - a token can lie in the text of several candidates.  cp_hash_floating gives every token i two
+ *     keys: hash_early_out[i] = key of a..i for the earliest candidate a <= i of its run with
+ *     ext(a) >= i, provided a starts on text that no earlier candidate reaches (no candidate b < a
+ *     with ext(b) >= a); hash_late_out[i] = key of a..i for the latest candidate a <= i of its run.
+ *     CP_HASH_NONE where there is none.  early_off_out / late_off_out (device u32[N], may be NULL):
+ *     i - a, or 0xFFFFFFFF.  hash_late_out may be NULL.
+ *   - cp_probe2 / cp_probe3 look every token up under the first key and, while that misses, under
+ *     the next.
+ * A token is thus served under its run-start key if possible, else from the earliest candidate
+ * whose text reaches it, else from the latest candidate: every token that one or two candidates'
+ * texts cover is served; where three or more overlap at a token, one of them may go unused.
  * `base` must be odd.  W >= 1. */
 int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
                      uint32_t R, uint64_t base, uint64_t *hash_out, uint32_t *run_off_out, void *scratch,
                      size_t scratch_bytes);
 int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, const uint32_t *slot, uint32_t N, uint32_t W,
                           uint32_t n_pool_slots, uint8_t *slot_anchor);
-/* float_off_out (device u32[N], may be NULL): i - a for a token with an anchor, 0xFFFFFFFF otherwise. */
 int32_t cp_hash_floating(void *stream, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,
                          const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
-                         uint64_t *hash_float_out, uint32_t *float_off_out, void *scratch, size_t scratch_bytes);
+                         uint64_t *hash_early_out, uint32_t *early_off_out, uint64_t *hash_late_out,
+                         uint32_t *late_off_out, void *scratch, size_t scratch_bytes);
 int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                   uint32_t *slot_out);
+int32_t cp_probe3(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, const uint64_t *hash_c,
+                  uint32_t N, uint32_t *slot_out);
 
 /* ---- Exact matches: no false match from a collision of the rolling hash -------------------------
  * Sec. 4.2.2 Step 2 ("full verification"): a candidate found through the rolling hash is confirmed
@@ -202,8 +216,8 @@ int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const ui
  * last kind is consumed but can never match (its parent is set to CP_PARENT_POISON).
  *
  * cp_verify_chain confirms the candidates of one key stream of a lookup.  seg_off[i] = offset of
- * token i in its segment: run_off for run-start keys, float_off for floating keys; 0xFFFFFFFF = in
- * no segment.  cand[i] = slot found under that stream's key (cp_probe).  Token i is accepted iff
+ * token i in its segment: run_off for run-start keys, early_off / late_off for the two floating
+ * streams; 0xFFFFFFFF = in no segment.  cand[i] = slot found under that stream's key (cp_probe).  Token i is accepted iff
  * every token from its segment's start through i is consistent: cand < n_pool_slots,
  * slot_tok[cand[i]] == tok[i], and slot_parent[cand[i]] == cand[i-1] (CP_SLOT_NONE at offset 0); by
  * induction cand[i] then holds exactly the segment's tokens up to i.  slot_out[i] = cand[i] if

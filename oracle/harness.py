@@ -123,9 +123,10 @@ class Lookup:
     flags: int
     dst: np.ndarray | None  # uint16[L][2][N][row_elems]
     times: dict
-    hash_float: np.ndarray | None = None
+    hash_float: np.ndarray | None = None  # keys of the earliest-candidate stream (pools with floating anchors)
     run_off: np.ndarray | None = None
     served: np.ndarray | None = None  # slots after minimum length / recompute marks
+    hash_late: np.ndarray | None = None  # keys of the latest-candidate stream
 
 
 def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_spans=None, min_len=1,
@@ -141,14 +142,14 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
     t = time.perf_counter()
     h = O.hash_segments(tok, mask, off)
     times["hash"] = time.perf_counter() - t
-    hf = roff = None
+    hf = hl = roff = None
     t = time.perf_counter()
     if st.text is None and st.anchors is None:
         slot = O.probe(st.index, h)
     else:
         roff = O.run_offsets(mask, off)
         if st.anchors is not None:
-            hf = O.hash_floating(st.anchors, st.index, h, roff, st.anchor_window)[0]
+            hf, _, hl, _ = O.hash_floating(st.anchors, st.index, h, roff, st.anchor_window)
         slot = O.merge_streams(O.match_streams(st.index, tok, h, roff, st.anchors, st.anchor_window, st.text))
     times["probe"] = time.perf_counter() - t
     use_rope = wl.rope_theta is not None
@@ -171,4 +172,4 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
             t = time.perf_counter()
             O.fill_unmatched(served, buf, buf_layout(sh, N))
             times["fill"] = time.perf_counter() - t
-    return Lookup(h, slot, src, dst, ln, delta, n, fl, buf, times, hf, roff, served)
+    return Lookup(h, slot, src, dst, ln, delta, n, fl, buf, times, hf, roff, served, hl)

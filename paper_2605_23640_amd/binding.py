@@ -31,7 +31,7 @@ EXPORTS = [
     "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_table_init",
     "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_gather_kv_static", "cp_insert_kv",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
-    "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2",
+    "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2", "cp_probe3",
     "cp_insert_kv_chain", "cp_verify_chain",
     "cp_filter_matches", "cp_mark_recompute", "cp_fill_unmatched", "cp_touch", "cp_lru_threshold", "cp_evict",
     "cp_table_compact", "cp_sat_scratch_bytes", "cp_sat_build", "cp_annotate",
@@ -124,7 +124,7 @@ def lib():
         L.cp_insert_anchors.restype = i32
         L.cp_insert_anchors.argtypes = [vp, vp, vp, u32, u32, u32, vp]
         L.cp_hash_floating.restype = i32
-        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, u32, vp, vp, u32, u64, u32, vp, vp, vp, sz]
+        L.cp_hash_floating.argtypes = [vp, TableStruct, vp, u32, vp, vp, u32, u64, u32, vp, vp, vp, vp, vp, sz]
         L.cp_insert_kv_chain.restype = i32
         L.cp_insert_kv_chain.argtypes = [vp, TableStruct, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
                                          u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -152,6 +152,8 @@ def lib():
         L.cp_annotate.argtypes = [vp, vp, u32, vp, u32, u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_probe2.restype = i32
         L.cp_probe2.argtypes = [vp, TableStruct, vp, vp, u32, vp]
+        L.cp_probe3.restype = i32
+        L.cp_probe3.argtypes = [vp, TableStruct, vp, vp, vp, u32, vp]
         L.cp_build_spans.restype = i32
         L.cp_build_spans.argtypes = [vp, vp, vp, u32, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_gather_kv.restype = i32
@@ -278,17 +280,18 @@ def cp_insert_anchors(run_off, slot, W, n_pool_slots, slot_anchor, stream=None):
                                                         int(W), n_pool_slots, _ptr(slot_anchor)))
 
 
-def cp_hash_floating(table: Table, slot_anchor, n_pool_slots, hashes, run_off, W, hash_float_out, scratch, base=BASE,
-                     stream=None, float_off_out=None):
-    _need_cuda(slot_anchor, hashes, run_off, hash_float_out, scratch, float_off_out)
+def cp_hash_floating(table: Table, slot_anchor, n_pool_slots, hashes, run_off, W, hash_early_out, scratch, base=BASE,
+                     stream=None, early_off_out=None, hash_late_out=None, late_off_out=None):
+    _need_cuda(slot_anchor, hashes, run_off, hash_early_out, scratch, early_off_out, hash_late_out, late_off_out)
     N = hashes.numel()
-    assert run_off.numel() == N and hash_float_out.numel() == N and slot_anchor.numel() >= n_pool_slots
-    assert float_off_out is None or float_off_out.numel() == N
+    assert run_off.numel() == N and hash_early_out.numel() == N and slot_anchor.numel() >= n_pool_slots
+    for t in (early_off_out, hash_late_out, late_off_out):
+        assert t is None or t.numel() == N
     _check("cp_hash_floating", lib().cp_hash_floating(_stream(stream), table.struct, _ptr(slot_anchor), n_pool_slots,
                                                       _ptr(hashes), _ptr(run_off), N, base, int(W),
-                                                      _ptr(hash_float_out), _ptr(float_off_out), _ptr(scratch),
-                                                      scratch.numel()))
-    return hash_float_out
+                                                      _ptr(hash_early_out), _ptr(early_off_out), _ptr(hash_late_out),
+                                                      _ptr(late_off_out), _ptr(scratch), scratch.numel()))
+    return hash_early_out
 
 
 def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, merge, slot_out, scratch, stream=None,
@@ -403,6 +406,15 @@ def cp_probe2(table: Table, hash_a, hash_b, slot_out, stream=None):
     N = hash_a.numel()
     assert hash_b.numel() == N and slot_out.numel() == N
     _check("cp_probe2", lib().cp_probe2(_stream(stream), table.struct, _ptr(hash_a), _ptr(hash_b), N, _ptr(slot_out)))
+    return slot_out
+
+
+def cp_probe3(table: Table, hash_a, hash_b, hash_c, slot_out, stream=None):
+    _need_cuda(hash_a, hash_b, hash_c, slot_out)
+    N = hash_a.numel()
+    assert hash_b.numel() == N and hash_c.numel() == N and slot_out.numel() == N
+    _check("cp_probe3", lib().cp_probe3(_stream(stream), table.struct, _ptr(hash_a), _ptr(hash_b), _ptr(hash_c), N,
+                                        _ptr(slot_out)))
     return slot_out
 
 

@@ -67,11 +67,12 @@ int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &
 int32_t launch_span_offsets(hipStream_t stream, const uint32_t *span_len, const uint32_t *n_spans, uint32_t max_spans,
                             uint32_t *span_off, uint32_t *agg);
 
-// hit[i] = 1 if token i lies at least W tokens into its run and the hash of the W tokens ending at
-// i is a key of `table` whose slot carries an anchor mark, else 0.  base_pow_w = base^W mod 2^64.
-int32_t launch_window_hits(hipStream_t stream, const cp_table &table, const uint8_t *slot_anchor,
-                           uint32_t n_pool_slots, const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint32_t W,
-                           uint64_t base_pow_w, uint8_t *hit);
+// ext1[a] = 1 + the last token t such that the key of tokens a..t is stored, for every position a that is a
+// candidate (a W-token window starting at a, inside one run and after the run's first token, hashes to a
+// key of `table` whose slot carries an anchor mark); 0 for every other position.
+int32_t launch_anchor_extents(hipStream_t stream, const cp_table &table, const uint8_t *slot_anchor,
+                              uint32_t n_pool_slots, const uint64_t *hash, const uint32_t *run_off, uint32_t N,
+                              uint32_t W, uint64_t base, uint32_t *ext1);
 
 // Segmented prefix AND of the per-token chain checks (see verify.hip): slot_out[i] = cand[i] if every
 // token from the start of i's segment through i is consistent with slot_tok / slot_parent, else

@@ -60,42 +60,86 @@ __device__ __forceinline__ uint64_t pow_u64(uint64_t b, uint32_t k) {  // b^k mo
   return r;
 }
 
-// Latest floating anchor at or before every token: a plain running maximum of (position + 1) over
-// the anchor flags; whether that anchor lies in the token's own run is checked when storing.
-struct FloatKeyOp {
-  using T = uint32_t;
+// Key of the request's tokens a..i, a after its run's first token: the chain hash those tokens get as
+// the beginning of a run (Sec. 4.2.2 Step 2: substring hash from prefix hashes and a power of the base).
+__device__ __forceinline__ uint64_t substring_key(const uint64_t *__restrict__ hash, uint64_t base, uint32_t a,
+                                                  uint32_t i) {
+  uint64_t key = hash[i] - hash[a - 1] * pow_u64(base, i - a + 1);
+  return key == CP_HASH_NONE ? CP_HASH_NONE - 1 : key;
+}
+
+// Scan over the candidates' reach (ext1[a] = 1 + last token whose key from candidate a is stored, 0 where
+// a is no candidate), restarting at every run: the running maximum of the reach, stored per token for the
+// search for the earliest candidate, and the latest candidate at or before every token, whose key is the
+// second candidate stream.
+struct FloatOp {
+  struct T {
+    uint32_t reach, latest, reset;  // max ext1; 1 + position of the latest candidate; piece contains a run start
+  };
   const uint64_t *hash;
   const uint32_t *run_off;
-  const uint8_t *hit;  // hit[i]: the W-token window ending at i matches a stored prefix hash
-  uint64_t *out;
-  uint32_t *float_off;  // nullable: i - a for tokens with an anchor, else 0xFFFFFFFF
+  const uint32_t *ext1;
+  uint32_t *reach_out;      // [N]
+  uint64_t *hash_late_out;  // nullable
+  uint32_t *late_off_out;   // nullable
   uint64_t base;
-  uint32_t N, W;
+  uint32_t N;
 
-  static __device__ __forceinline__ T identity() { return 0u; }
-  static __device__ __forceinline__ T combine(T a, T b) { return a > b ? a : b; }
+  static __device__ __forceinline__ T identity() { return T{0u, 0u, 0u}; }
+  static __device__ __forceinline__ T combine(T f, T g) {
+    if (g.reset) return g;
+    return T{f.reach > g.reach ? f.reach : g.reach, f.latest > g.latest ? f.latest : g.latest, f.reset};
+  }
   __device__ __forceinline__ uint32_t count() const { return N; }
-  __device__ __forceinline__ T load(uint32_t a) const {
-    const uint64_t end = (uint64_t)a + W - 1;  // last token of the window that starts at a
-    return (end < N && hit[end]) ? a + 1 : 0u;
+  __device__ __forceinline__ T load(uint32_t i) const {
+    const uint32_t ro = run_off[i];
+    if (ro == 0 || ro == 0xFFFFFFFFu) return T{0u, 0u, 1u};  // a run's first token is never a candidate
+    const uint32_t e = ext1[i];
+    return T{e, e ? i + 1 : 0u, 0u};
   }
   __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
+    reach_out[i] = incl.reach;
     uint64_t key = CP_HASH_NONE;
-    uint32_t fo = 0xFFFFFFFFu;
-    const uint32_t ro = run_off[i];
-    if (hash[i] != CP_HASH_NONE && incl != 0) {
-      const uint32_t a = incl - 1;
-      if (a > i - ro) {  // inside this run and after its start (a window at the run start is the plain key)
-        key = hash[i] - hash[a - 1] * pow_u64(base, i - a + 1);
-        if (key == CP_HASH_NONE) key = CP_HASH_NONE - 1;
-        fo = i - a;
-      }
+    uint32_t lo = 0xFFFFFFFFu;
+    if (hash[i] != CP_HASH_NONE && incl.latest != 0) {
+      const uint32_t a = incl.latest - 1;
+      key = substring_key(hash, base, a, i);
+      lo = i - a;
     }
-    out[i] = key;
-    if (float_off) float_off[i] = fo;
+    if (hash_late_out) hash_late_out[i] = key;
+    if (late_off_out) late_off_out[i] = lo;
   }
   __device__ __forceinline__ void finish(T) const {}
 };
+
+// First candidate stream: the earliest candidate whose stored text reaches token i, taken only if it
+// starts on text that no earlier candidate reaches.  reach[] is non-decreasing inside a run, so the
+// earliest candidate with reach > i is where reach[] first exceeds i: a bisection over the run so far.
+__global__ __launch_bounds__(256) void early_key_kernel(const uint64_t *__restrict__ hash,
+                                                        const uint32_t *__restrict__ run_off,
+                                                        const uint32_t *__restrict__ reach, uint32_t N, uint64_t base,
+                                                        uint64_t *__restrict__ hash_early_out,
+                                                        uint32_t *__restrict__ early_off_out) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= N) return;
+  uint64_t key = CP_HASH_NONE;
+  uint32_t eo = 0xFFFFFFFFu;
+  const uint32_t ro = run_off[i];
+  if (hash[i] != CP_HASH_NONE && ro != 0xFFFFFFFFu && ro > 0 && reach[i] > i) {
+    uint32_t lo = i - ro, hi = i;  // reach[lo] = 0 (run start), reach[hi] > i
+    while (hi - lo > 1) {
+      const uint32_t mid = lo + (hi - lo) / 2;
+      if (reach[mid] > i) hi = mid; else lo = mid;
+    }
+    const uint32_t a = hi;        // a candidate: reach[] rises only at candidates
+    if (reach[a - 1] <= a) {      // no earlier candidate's text reaches token a
+      key = substring_key(hash, base, a, i);
+      eo = i - a;
+    }
+  }
+  hash_early_out[i] = key;
+  if (early_off_out) early_off_out[i] = eo;
+}
 
 }  // namespace
 }  // namespace cp
@@ -132,25 +176,27 @@ extern "C" int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t
 
 extern "C" int32_t cp_hash_floating(void *stream_, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,
                                     const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base,
-                                    uint32_t W, uint64_t *hash_float_out, uint32_t *float_off_out, void *scratch,
+                                    uint32_t W, uint64_t *hash_early_out, uint32_t *early_off_out,
+                                    uint64_t *hash_late_out, uint32_t *late_off_out, void *scratch,
                                     size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
-  if (W == 0 || !slot_anchor || !hash || !run_off || !hash_float_out || !scratch || !aligned(scratch, 256) ||
-      !aligned(hash, 8) || !aligned(hash_float_out, 8))
+  if (W == 0 || !slot_anchor || !hash || !run_off || !hash_early_out || !scratch || !aligned(scratch, 256) ||
+      !aligned(hash, 8) || !aligned(hash_early_out, 8) || !aligned(hash_late_out, 8))
     return CP_ERR_INVALID_ARG;
   if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
-  uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
-  uint8_t *hit = sc.take<uint8_t>(N);
-  if (!agg || !hit) return CP_ERR_SCRATCH;
-  uint64_t pw = 1;  // base^W mod 2^64
-  for (uint64_t b = base, k = W; k; k >>= 1, b *= b)
-    if (k & 1) pw *= b;
-  if (int32_t rc = launch_window_hits(stream, table, slot_anchor, n_pool_slots, hash, run_off, N, W, pw, hit)) return rc;
-  FloatKeyOp op{hash, run_off, hit, hash_float_out, float_off_out, base, N, W};
-  return run_scan<FloatKeyOp>(stream, op, N, agg);
+  FloatOp::T *agg = sc.take<FloatOp::T>(div_up(N, kScanTile) + 1);
+  uint32_t *ext1 = sc.take<uint32_t>(N);
+  uint32_t *reach = sc.take<uint32_t>(N);
+  if (!agg || !ext1 || !reach) return CP_ERR_SCRATCH;
+  if (int32_t rc = launch_anchor_extents(stream, table, slot_anchor, n_pool_slots, hash, run_off, N, W, base, ext1))
+    return rc;
+  FloatOp op{hash, run_off, ext1, reach, hash_late_out, late_off_out, base, N};
+  if (int32_t rc = run_scan<FloatOp>(stream, op, N, agg)) return rc;
+  early_key_kernel<<<div_up(N, 256), 256, 0, stream>>>(hash, run_off, reach, N, base, hash_early_out, early_off_out);
+  return check_launch();
 }

@@ -72,9 +72,11 @@ __device__ __forceinline__ uint32_t group_lookup(const cp_table &t, uint64_t h) 
   return result >= kPending ? CP_SLOT_NONE : result;
 }
 
-// One group of 16 lanes per token.  hash_b (nullable): second key, tried when the first misses.
+// One group of 16 lanes per token.  hash_b, hash_c (nullable): further keys, tried in this order while
+// the ones before miss.
 __global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const uint64_t *__restrict__ hash,
-                                                              const uint64_t *__restrict__ hash_b, uint32_t N,
+                                                              const uint64_t *__restrict__ hash_b,
+                                                              const uint64_t *__restrict__ hash_c, uint32_t N,
                                                               uint32_t *__restrict__ slot_out) {
   const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
   uint32_t result = group_lookup(t, q < N ? hash[q] : CP_HASH_NONE);
@@ -83,28 +85,85 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const 
     const uint32_t r2 = group_lookup(t, h2);
     if (result == CP_SLOT_NONE) result = r2;
   }
+  if (hash_c) {
+    const uint64_t h3 = (q < N && result == CP_SLOT_NONE) ? hash_c[q] : CP_HASH_NONE;
+    const uint32_t r3 = group_lookup(t, h3);
+    if (result == CP_SLOT_NONE) result = r3;
+  }
   if (q < N && (threadIdx.x & (kBucket - 1)) == 0) slot_out[q] = result;
 }
 
-// Floating-anchor lookup, step 1: does the W-token window ending at token i match a stored prefix
-// hash?  Only windows that lie inside one run and start after the run's first token are looked at.
-// The prefix hash of a stored run is the table key of the run's W-th token, so the set of prefix
-// hashes is the set of keys whose (live) slot carries the anchor mark.
-__global__ __launch_bounds__(kProbeThreads) void window_hit_kernel(cp_table table,
-                                                                   const uint8_t *__restrict__ slot_anchor,
-                                                                   uint32_t n_pool_slots,
-                                                                   const uint64_t *__restrict__ hash,
-                                                                   const uint32_t *__restrict__ run_off, uint32_t N,
-                                                                   uint32_t W, uint64_t base_pow_w,
-                                                                   uint8_t *__restrict__ hit) {
-  const uint32_t i = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
-  uint64_t wh = CP_HASH_NONE;
-  if (i < N && hash[i] != CP_HASH_NONE && run_off[i] >= W && run_off[i] != 0xFFFFFFFFu) {
-    wh = hash[i] - hash[i - W] * base_pow_w;  // tokens i-W+1 .. i; token i-W is in the same run
-    if (wh == CP_HASH_NONE) wh = CP_HASH_NONE - 1;
+__device__ __forceinline__ uint64_t pow_u64(uint64_t b, uint32_t k) {  // b^k mod 2^64
+  uint64_t r = 1;
+  while (k) {
+    if (k & 1) r *= b;
+    b *= b;
+    k >>= 1;
+  }
+  return r;
+}
+
+// Floating-anchor lookup, Step 1 and the pre-check of Step 2 (Sec. 4.2.2), one group of 16 lanes per
+// position a of the batch.  Step 1: is a a candidate, i.e. does the W-token window that starts at a lie
+// inside one run, after the run's first token, and hash to a stored prefix hash?  (The prefix hash of a
+// stored run is the table key of the run's W-th token, so the stored prefix hashes are the keys whose
+// live slot carries the anchor mark.)  Step 2's pre-check: how far does the stored text go on?  The key
+// of tokens a..t follows in O(1) from the run's chain hashes and a power of the base; stored runs are
+// closed under taking prefixes, so "key of a..t is stored" is true up to some last token and false
+// beyond it: that token is found by doubling steps and bisection, about 2 log2(length) lookups.
+// ext1[a] = 1 + last token whose key from a is stored, 0 if a is no candidate.
+__global__ __launch_bounds__(kProbeThreads) void anchor_extent_kernel(cp_table table,
+                                                                      const uint8_t *__restrict__ slot_anchor,
+                                                                      uint32_t n_pool_slots,
+                                                                      const uint64_t *__restrict__ hash,
+                                                                      const uint32_t *__restrict__ run_off, uint32_t N,
+                                                                      uint32_t W, uint64_t base,
+                                                                      uint32_t *__restrict__ ext1) {
+  const uint32_t a = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint64_t end64 = (uint64_t)a + W - 1;  // last token of the window
+  uint64_t wh = CP_HASH_NONE, before = 0;
+  uint32_t end = 0, ro_end = 0;
+  if (a < N && end64 < N) {
+    end = (uint32_t)end64;
+    ro_end = run_off[end];
+    // the window lies inside the run and starts after the run's first token: at least W tokens before its end
+    if (hash[end] != CP_HASH_NONE && ro_end != 0xFFFFFFFFu && ro_end >= W) {
+      before = hash[a - 1];  // token a-1 is in the same run
+      wh = hash[end] - before * pow_u64(base, W);
+      if (wh == CP_HASH_NONE) wh = CP_HASH_NONE - 1;
+    }
   }
   const uint32_t s = group_lookup(table, wh);
-  if (i < N && (threadIdx.x & (kBucket - 1)) == 0) hit[i] = s < n_pool_slots && slot_anchor[s] != 0;
+  const bool cand = s < n_pool_slots && slot_anchor[s] != 0;
+  // lo = last token known to be stored from a, hi = first token known not to be (0 = none known yet)
+  uint32_t lo = end, hi = 0, step = 1;
+  bool searching = cand;
+  while (__any(searching)) {  // wavefront-uniform loop; groups drop out one by one
+    uint64_t key = CP_HASH_NONE;
+    uint32_t t = 0;
+    if (searching) {
+      const uint64_t t64 = hi ? (uint64_t)lo + (hi - lo) / 2 : (uint64_t)lo + step;
+      // token t continues the run of the window iff its offset in the run says so
+      if (t64 < N && run_off[(uint32_t)t64] == ro_end + (uint32_t)(t64 - end)) {
+        t = (uint32_t)t64;
+        key = hash[t] - before * pow_u64(base, t - a + 1);
+        if (key == CP_HASH_NONE) key = CP_HASH_NONE - 1;
+      } else {
+        t = (uint32_t)(t64 < N ? t64 : N);  // beyond the run (or the batch): not stored
+      }
+    }
+    const bool stored = group_lookup(table, key) != CP_SLOT_NONE;
+    if (searching) {
+      if (stored) {
+        lo = t;
+        if (!hi) step = step < 0x40000000u ? step * 2 : step;
+      } else {
+        hi = t;
+      }
+      if (hi && hi - lo <= 1) searching = false;
+    }
+  }
+  if (a < N && (threadIdx.x & (kBucket - 1)) == 0) ext1[a] = cand ? lo + 1 : 0u;
 }
 
 // Index of the entry that holds key h, taking a free entry for it if there is none yet; CP_SLOT_NONE
@@ -333,25 +392,32 @@ extern "C" int32_t cp_table_init(void *stream, cp_table table) {
 }
 
 static int32_t probe_common(void *stream, const cp_table &table, const uint64_t *hash, const uint64_t *hash_b,
-                            uint32_t N, uint32_t *slot_out) {
+                            const uint64_t *hash_c, uint32_t N, uint32_t *slot_out) {
   using namespace cp;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (int32_t rc = table_ok(table)) return rc;
-  if (!hash || !slot_out || !aligned(hash, 8) || !aligned(hash_b, 8) || !aligned(slot_out, 4)) return CP_ERR_INVALID_ARG;
+  if (!hash || !slot_out || !aligned(hash, 8) || !aligned(hash_b, 8) || !aligned(hash_c, 8) || !aligned(slot_out, 4))
+    return CP_ERR_INVALID_ARG;
   probe_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(
-      table, hash, hash_b, N, slot_out);
+      table, hash, hash_b, hash_c, N, slot_out);
   return check_launch();
 }
 
 extern "C" int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out) {
-  return probe_common(stream, table, hash, nullptr, N, slot_out);
+  return probe_common(stream, table, hash, nullptr, nullptr, N, slot_out);
 }
 
 extern "C" int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                              uint32_t *slot_out) {
   if (N && !hash_b) return CP_ERR_INVALID_ARG;
-  return probe_common(stream, table, hash_a, hash_b, N, slot_out);
+  return probe_common(stream, table, hash_a, hash_b, nullptr, N, slot_out);
+}
+
+extern "C" int32_t cp_probe3(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b,
+                             const uint64_t *hash_c, uint32_t N, uint32_t *slot_out) {
+  if (N && (!hash_b || !hash_c)) return CP_ERR_INVALID_ARG;
+  return probe_common(stream, table, hash_a, hash_b, hash_c, N, slot_out);
 }
 
 extern "C" int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, const uint32_t *slot, uint32_t N,
@@ -366,12 +432,12 @@ extern "C" int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, cons
 }
 
 namespace cp {
-int32_t launch_window_hits(hipStream_t stream, const cp_table &table, const uint8_t *slot_anchor,
-                           uint32_t n_pool_slots, const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint32_t W,
-                           uint64_t base_pow_w, uint8_t *hit) {
+int32_t launch_anchor_extents(hipStream_t stream, const cp_table &table, const uint8_t *slot_anchor,
+                              uint32_t n_pool_slots, const uint64_t *hash, const uint32_t *run_off, uint32_t N,
+                              uint32_t W, uint64_t base, uint32_t *ext1) {
   if (int32_t rc = table_ok(table)) return rc;
-  window_hit_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
-      table, slot_anchor, n_pool_slots, hash, run_off, N, W, base_pow_w, hit);
+  anchor_extent_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
+      table, slot_anchor, n_pool_slots, hash, run_off, N, W, base, ext1);
   return check_launch();
 }
 }  // namespace cp

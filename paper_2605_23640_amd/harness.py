@@ -109,8 +109,9 @@ class GpuLookup:
     flags: int
     dst: torch.Tensor  # uint8 device tensor, layer-major [L][2][N][row_bytes]
     served: np.ndarray = None  # slots after the pool's policies (= slot without policies)
-    hash_float: np.ndarray = None  # pools with floating anchors only
+    hash_float: np.ndarray = None  # pools with floating anchors only: keys of the earliest-candidate stream
     run_off: np.ndarray = None
+    hash_late: np.ndarray = None  # ... and of the latest-candidate stream
 
 
 def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=True) -> GpuLookup:
@@ -132,7 +133,7 @@ def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=T
                      host_u32(buf.span_len)[:n], buf.span_delta.cpu().numpy()[:n], host_u32(buf.span_off)[:n + 1], n,
                      int(st.pool.flags.item()), dst, host_u32(buf.served) if st.pool.filters else host_u32(buf.slot),
                      host_u64(buf.hash_float) if anch else None,
-                     host_u32(buf.run_off) if runs else None)
+                     host_u32(buf.run_off) if runs else None, host_u64(buf.hash_late) if anch else None)
 
 
 def dst_as_rows(dst, sh, N):

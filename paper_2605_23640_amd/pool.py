@@ -6,12 +6,12 @@ sequences of the two paths through libcacheprune.
 
 and, for a pool with floating anchors (window W),
 
-    lookup :  cp_hash_runs -> cp_hash_floating -> cp_probe2 -> cp_build_spans -> cp_gather_kv
+    lookup :  cp_hash_runs -> cp_hash_floating -> cp_probe3 -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_runs -> cp_insert_kv -> cp_insert_anchors
 
 and, for a pool that confirms every match exactly (``verify=True``),
 
-    lookup :  cp_hash_runs -> cp_probe -> cp_verify_chain [-> cp_hash_floating -> cp_probe -> cp_verify_chain]
+    lookup :  cp_hash_runs -> cp_probe -> cp_verify_chain [-> cp_hash_floating -> 2 x (cp_probe -> cp_verify_chain)]
               -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_runs -> cp_insert_kv_chain [-> cp_insert_anchors]
 
@@ -51,12 +51,15 @@ class LookupBuffers:
         self.max_spans = N if max_spans is None else max_spans
         i32, i64 = torch.int32, torch.int64
         self.hash = torch.empty(N, dtype=i64, device=device)
-        self.hash_float = torch.empty(N, dtype=i64, device=device)  # floating-anchor keys (if the pool uses them)
+        # floating anchors (if the pool uses them): keys of the earliest-candidate and the latest-candidate stream
+        self.hash_float = torch.empty(N, dtype=i64, device=device)
+        self.hash_late = torch.empty(N, dtype=i64, device=device)
         self.run_off = torch.empty(N, dtype=i32, device=device)
         self.float_off = torch.empty(N, dtype=i32, device=device)
+        self.late_off = torch.empty(N, dtype=i32, device=device)
         self.cand = torch.empty(N, dtype=i32, device=device)  # unconfirmed slots (pools that verify)
         self.slot = torch.empty(N, dtype=i32, device=device)  # slot of every matched token
-        self.slot_b = torch.empty(N, dtype=i32, device=device)  # what the floating-key stream alone accepted
+        self.slot_b = torch.empty(N, dtype=i32, device=device)  # what one candidate stream alone found / accepted
         self.served = torch.empty(N, dtype=i32, device=device)  # ... of those that pass the pool's policies
         m = max(1, self.max_spans)
         self.span_src = torch.empty(m, dtype=i32, device=device)
@@ -164,31 +167,35 @@ class KVPool:
         ``dst`` (layer-major, N tokens) hold the pooled KV.  No host synchronisation.
         ``gather_opts`` overrides the pool's launch options for this call."""
         N = tok.numel()
-        if self.verify:
-            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
-            B.cp_probe(self.table, buf.hash, buf.cand, stream=stream)
-            B.cp_verify_chain(tok, buf.run_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, False,
-                              buf.slot, buf.scratch, stream=stream)
-            if self.slot_anchor is not None:
-                B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off,
-                                   self.anchor_window, buf.hash_float, buf.scratch, stream=stream,
-                                   float_off_out=buf.float_off)
-                B.cp_probe(self.table, buf.hash_float, buf.cand, stream=stream)
-                lru = self.slot_stamp is not None
-                B.cp_verify_chain(tok, buf.float_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, True,
-                                  buf.slot, buf.scratch, stream=stream, stream_out=buf.slot_b if lru else None)
-                if lru:
-                    # where both streams are accepted the first one serves, but the second one's slots led to the
-                    # tokens it does serve: they count as used, or a stored run could lose its head to eviction
-                    B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
-        elif self.slot_anchor is None:
+        lru = self.slot_stamp is not None
+        if self.slot_anchor is None and not self.verify:
             B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
             B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
         else:
             B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
-            B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off, self.anchor_window,
-                               buf.hash_float, buf.scratch, stream=stream)
-            B.cp_probe2(self.table, buf.hash, buf.hash_float, buf.slot, stream=stream)
+            streams = [(buf.hash, buf.run_off)]  # (keys, offset of every token in its segment), in serving order
+            if self.slot_anchor is not None:
+                B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off,
+                                   self.anchor_window, buf.hash_float, buf.scratch, stream=stream,
+                                   early_off_out=buf.float_off, hash_late_out=buf.hash_late,
+                                   late_off_out=buf.late_off)
+                streams += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
+            if self.verify:
+                for k, (keys, seg_off) in enumerate(streams):
+                    B.cp_probe(self.table, keys, buf.cand, stream=stream)
+                    B.cp_verify_chain(tok, seg_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, k > 0,
+                                      buf.slot, buf.scratch, stream=stream,
+                                      stream_out=buf.slot_b if lru and k > 0 else None)
+                    if lru and k > 0:
+                        # where an earlier stream serves a token, this one's slots still led to the tokens it
+                        # does serve: they count as used, or a stored run could lose its head to eviction
+                        B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
+            else:
+                B.cp_probe3(self.table, buf.hash, buf.hash_float, buf.hash_late, buf.slot, stream=stream)
+                if lru:  # the same for a pool that does not confirm: every stream's own finds count as used
+                    for keys, _ in streams[1:]:
+                        B.cp_probe(self.table, keys, buf.slot_b, stream=stream)
+                        B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         if self.slot_stamp is not None:
             B.cp_touch(buf.slot, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         served = buf.slot  # buf.slot: every matched token; served: those that pass the policies

@@ -70,8 +70,9 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_probe2(None, tab, P, None, 4, Q) == INV
     assert L.cp_insert_anchors(None, Q, Q, 4, 0, 16, S) == INV  # W = 0
     assert L.cp_insert_anchors(None, Q, Q, 4, 2, 16, None) == INV  # no mark array
-    assert L.cp_hash_floating(None, tab, S, 16, P, Q, 4, B.BASE, 0, P, None, S, big) == INV  # W = 0
-    assert L.cp_hash_floating(None, tab, None, 16, P, Q, 4, B.BASE, 2, P, None, S, big) == INV  # no mark array
+    assert L.cp_hash_floating(None, tab, S, 16, P, Q, 4, B.BASE, 0, P, None, None, None, S, big) == INV  # W = 0
+    assert L.cp_hash_floating(None, tab, None, 16, P, Q, 4, B.BASE, 2, P, None, None, None, S, big) == INV  # no mark array
+    assert L.cp_probe3(None, tab, P, P, None, 4, Q) == INV
     assert L.cp_build_spans(None, None, Q, 4, 1, None, 4, P, P, P, None, None, Q, Q, S, big) == INV
     assert L.cp_insert_kv(None, tab, P, Q, 4, 1, S, 4, None, lay, P, lay, 16, P, Q, S, S, S, big, None) == INV
     assert L.cp_insert_kv_chain(None, tab, P, Q, Q, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, None, None, Q, S, S, S,

@@ -19,6 +19,9 @@ def small_float(shape=gen.KVShape(2, 2, 64), scale=0.5):
     return wl
 
 
+HITS = {}
+
+
 @pytest.mark.parametrize("W", [1, 3, 16, 64])
 def test_float_workload(G, W):
     wl = small_float()
@@ -27,7 +30,32 @@ def test_float_workload(G, W):
     gained = (olk.slot != NONE).sum() - (start_only != NONE).sum()
     print(f"W={W}: hits {np.mean(olk.slot != NONE):.3f}, of which through floating keys {gained / len(olk.slot):.3f}")
     assert gained > 0.3 * len(olk.slot)  # most of this workload is reachable through an anchor only
-    assert (olk.hash_float != O.HASH_NONE).sum() >= gained
+    assert ((olk.hash_float != O.HASH_NONE) | (olk.hash_late != O.HASH_NONE)).sum() >= gained
+    HITS[W] = glk.slot != NONE
+    if W == 3:  # a one-token window makes many chance candidates; none of them may cost a match
+        assert (HITS[3] <= HITS[1]).all(), "W = 1 serves fewer tokens than W = 3"
+
+
+def test_overlapping_and_nested_candidates(G):
+    """Stored texts that contain one another or overlap inside a request: a later window hit must not cost what
+    an earlier candidate covers (every token of 'abcdefgh' with 'defg' also stored), and the part only the later
+    one covers is served from it ('XY' + 'YZ' against 'XYZ').  Hand-built donors, checked against the oracle."""
+    rng = np.random.default_rng(77)
+    V = lambda n: rng.integers(0, 32000, n).astype(np.uint32)  # noqa: E731
+    long_text, X, Y, Z = V(40), V(12), V(15), V(9)
+    donors = [long_text, long_text[10:25], np.concatenate([X, Y]), np.concatenate([Y, Z])]
+    reqs = [np.concatenate([V(5), long_text, V(3)]), np.concatenate([V(2), X, Y, Z, V(4)]),
+            np.concatenate([V(1), long_text[10:40], V(2), Y, Z])]
+    wl = gen.from_prompts("overlap", 0xC0FFEE21, gen.KVShape(2, 2, 64), donors, reqs, pool_slots=512)
+    for W in (1, 2, 4):
+        ost, olk, gst, glk = compare_all(G, wl, anchor_window=W)
+        o = wl.off
+        assert (glk.slot[o[0] + 5:o[0] + 45] != NONE).all()  # all of the long text, its last tokens included
+        assert (glk.slot[o[1] + 2:o[1] + 2 + 12 + 15 + 9] != NONE).all()  # X Y Z whole
+        # the third request enters the long text at its 11th token: only the shorter stored text starts there
+        assert (glk.slot[o[2] + 1:o[2] + 16] != NONE).all() and (glk.slot[o[2] + 16:o[2] + 31] == NONE).all()
+        assert (glk.slot[o[2] + 33:o[2] + 33 + 24] != NONE).all()  # Y Z behind other text
+    compare_all(G, wl, anchor_window=2, verify=True)
 
 
 def test_window_longer_than_every_run(G):

@@ -131,7 +131,7 @@ def test_full_size_float_anchors_verified_policies(G):
     assert np.array_equal(gst.pool.slot_recompute.cpu().numpy(), ost.marks)
     assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0
     glk = G.lookup(gst)
-    for f in ("hash", "hash_float", "run_off", "slot", "served", "span_src", "span_dst", "span_len"):
+    for f in ("hash", "hash_float", "hash_late", "run_off", "slot", "served", "span_src", "span_dst", "span_len"):
         assert np.array_equal(getattr(glk, f), getattr(olk, f)), f
     served = olk.served != O.SLOT_NONE
     matched = olk.slot != O.SLOT_NONE

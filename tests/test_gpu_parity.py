@@ -46,6 +46,7 @@ def compare_all(G, wl, max_ulp_sample=None, anchor_window=None, verify=False, mi
     if anchor_window is not None:
         assert np.array_equal(glk.run_off, olk.run_off)
         assert np.array_equal(glk.hash_float, olk.hash_float)
+        assert np.array_equal(glk.hash_late, olk.hash_late)
     N = wl.n_tokens
     assert np.array_equal(gst.donor_hash, ost.donor_hash)
     assert np.array_equal(gst.donor_slot, ost.donor_slot)

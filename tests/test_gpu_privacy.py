@@ -50,7 +50,7 @@ def test_sensitive_token_ids_do_not_matter(G, name, scale, kw):
     for f in ("hash", "slot", "served", "span_src", "span_dst", "span_len", "span_off", "n_spans", "flags"):
         a, b = getattr(la, f), getattr(lb, f)
         assert np.array_equal(a, b), f
-    for f in ("hash_float", "run_off"):
+    for f in ("hash_float", "hash_late", "run_off"):
         if getattr(la, f) is not None:
             assert np.array_equal(getattr(la, f), getattr(lb, f)), f
     assert torch.equal(la.dst, lb.dst) and torch.equal(sa.pool.pool, sb.pool.pool)
