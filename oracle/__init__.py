@@ -82,6 +82,12 @@ def lib():
         L.cpo_run_offsets.argtypes = [vp, vp, u32, vp]
         L.cpo_insert_anchors.argtypes = [vp, vp, vp, vp, u32, u32]
         L.cpo_hash_floating.argtypes = [vp, vp, vp, vp, u32, u64, u32, vp, vp, vp, vp]
+        L.cpo_insert_keys.restype = None
+        L.cpo_insert_keys.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, vp]
+        L.cpo_insert_kv_dedup.restype = u32
+        L.cpo_insert_kv_dedup.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, Layout, vp, Layout, vp, vp, vp, vp, vp]
+        L.cpo_text_record_dedup.restype = None
+        L.cpo_text_record_dedup.argtypes = [vp, vp, vp, vp, u32, vp]
         L.cpo_probe3.restype = None
         L.cpo_probe3.argtypes = [vp, vp, vp, vp, u32, vp]
         L.cpo_text_new.restype = vp
@@ -175,7 +181,8 @@ def hash_floating(anchors: AnchorSet, index: Index, hashes, run_off, W, base=BAS
     return he, eo, hl, lo
 
 
-def match_streams(index: Index, tok, hashes, run_off, anchors: AnchorSet = None, W=None, text: "Text" = None):
+def match_streams(index: Index, tok, hashes, run_off, anchors: AnchorSet = None, W=None, text: "Text" = None,
+                  with_offsets=False):
     """What every key stream of a lookup finds, in the order in which they serve a token: the run-start
     keys, then (pools with floating anchors) the earliest-candidate keys and the latest-candidate keys.
     With ``text`` each stream's slots are confirmed against the stored text along its own segments."""
@@ -186,7 +193,8 @@ def match_streams(index: Index, tok, hashes, run_off, anchors: AnchorSet = None,
     out = []
     for keys, seg_off in streams:
         s = probe(index, keys)
-        out.append(s if text is None else verify(text, tok, seg_off, s))
+        s = s if text is None else verify(text, tok, seg_off, s)
+        out.append((seg_off, s) if with_offsets else s)
     return out
 
 
@@ -369,6 +377,43 @@ def insert_kv(index: Index, hashes, off, free_slots, src, src_l: Layout, pool, p
     n = lib().cpo_insert_kv(index._h, _p(hashes), _p(off), len(off) - 1, _p(free_slots), len(free_slots), _p(src),
                             src_l, _p(pool), pool_l, _p(slot_pos), _p(slot_out), _p(flags), _p(tok), _p(slot_tok))
     return slot_out, int(n), int(flags[0])
+
+
+def insert_keys(hashes, run_off, streams, base=BASE):
+    """``streams``: list of (seg_off, slot) per lookup stream, in serving order.  Returns (ins_hash, ins_off, found)."""
+    hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
+    n, k = hashes.shape[0], len(streams)
+    segs = [_arr(so, np.uint32) for so, _ in streams]
+    slots = [_arr(sl, np.uint32) for _, sl in streams]
+    seg_p = (C.c_void_p * k)(*[a.ctypes.data for a in segs])
+    slot_p = (C.c_void_p * k)(*[a.ctypes.data for a in slots])
+    ih, io, fo = np.empty(n, np.uint64), np.empty(n, np.uint32), np.empty(n, np.uint32)
+    lib().cpo_insert_keys(_p(hashes), _p(run_off), seg_p, slot_p, k, n, base, _p(ih), _p(io), _p(fo))
+    return ih, io, fo
+
+
+def insert_kv_dedup(index: Index, ins_hash, found, off, free_slots, src, src_l: Layout, pool, pool_l: Layout, slot_pos,
+                    tok=None, slot_tok=None):
+    """insert_kv under the keys of ``insert_keys``, leaving out the tokens that were found."""
+    ins_hash, found = _arr(ins_hash, np.uint64), _arr(found, np.uint32)
+    off, free_slots = _arr(off, np.uint32), _arr(free_slots, np.uint32)
+    assert slot_pos.dtype == np.int32 and slot_pos.flags.c_contiguous
+    if tok is not None:
+        tok = _arr(tok, np.uint32)
+        assert slot_tok is not None and slot_tok.dtype == np.uint32
+    slot_out = np.empty(ins_hash.shape[0], np.uint32)
+    flags = np.zeros(1, np.uint32)
+    n = lib().cpo_insert_kv_dedup(index._h, _p(ins_hash), _p(found), _p(off), len(off) - 1, _p(free_slots),
+                                  len(free_slots), _p(src), src_l, _p(pool), pool_l, _p(slot_pos), _p(slot_out),
+                                  _p(flags), _p(tok), _p(slot_tok))
+    return slot_out, int(n), int(flags[0])
+
+
+def text_record_dedup(text: "Text", tok, ins_off, found, slot_out):
+    tok, ins_off, found = _arr(tok, np.uint32), _arr(ins_off, np.uint32), _arr(found, np.uint32)
+    out = np.array(slot_out, dtype=np.uint32, copy=True)
+    lib().cpo_text_record_dedup(text._h, _p(tok), _p(ins_off), _p(found), tok.shape[0], _p(out))
+    return out
 
 
 def bf16_to_double(bits: int) -> float:

@@ -191,17 +191,21 @@ extern "C" void cpo_gather_kv(const void *pool, cpo_layout pool_l, void *dst, cp
 
 // Sec. 4.1 "Workflow" (post-inference storing) and Sec. 4.3.5 (one copy of a
 // duplicate): first occurrence in packed order owns the key.
-extern "C" uint32_t cpo_insert_kv(cpo_index *ix, const uint64_t *hash, const uint32_t *off,
-                                  uint32_t R, const uint32_t *free_slots, uint32_t n_free,
-                                  const void *src, cpo_layout src_l, void *pool, cpo_layout pool_l,
-                                  int32_t *slot_pos, uint32_t *slot_out, uint32_t *flags,
-                                  const uint32_t *tok, uint32_t *slot_tok) {
+static uint32_t insert_tokens(cpo_index *ix, const uint64_t *hash, const uint32_t *found,
+                              const uint32_t *off, uint32_t R, const uint32_t *free_slots,
+                              uint32_t n_free, const void *src, cpo_layout src_l, void *pool,
+                              cpo_layout pool_l, int32_t *slot_pos, uint32_t *slot_out, uint32_t *flags,
+                              const uint32_t *tok, uint32_t *slot_tok) {
   const size_t row_bytes = (size_t)pool_l.n_kv_heads * pool_l.head_dim * 2;
   uint32_t n_new = 0;
   for (uint32_t r = 0; r < R; ++r) {
     for (uint32_t i = off[r]; i < off[r + 1]; ++i) {
       slot_out[i] = CPO_SLOT_NONE;
       if (hash[i] == CPO_HASH_NONE) continue;
+      if (found && found[i] != CPO_SLOT_NONE) {  // its text is in the pool already: kept once
+        slot_out[i] = found[i];
+        continue;
+      }
       auto it = ix->map.find(hash[i]);
       if (it != ix->map.end()) {
         slot_out[i] = it->second;
@@ -223,6 +227,52 @@ extern "C" uint32_t cpo_insert_kv(cpo_index *ix, const uint64_t *hash, const uin
     }
   }
   return n_new;
+}
+
+extern "C" uint32_t cpo_insert_kv(cpo_index *ix, const uint64_t *hash, const uint32_t *off,
+                                  uint32_t R, const uint32_t *free_slots, uint32_t n_free,
+                                  const void *src, cpo_layout src_l, void *pool, cpo_layout pool_l,
+                                  int32_t *slot_pos, uint32_t *slot_out, uint32_t *flags,
+                                  const uint32_t *tok, uint32_t *slot_tok) {
+  return insert_tokens(ix, hash, nullptr, off, R, free_slots, n_free, src, src_l, pool, pool_l, slot_pos,
+                       slot_out, flags, tok, slot_tok);
+}
+
+// Sec. 4.3.5 "Lifecycle management": a text that the pool already holds inside a longer stored text,
+// or behind other text, is kept once.
+extern "C" void cpo_insert_keys(const uint64_t *hash, const uint32_t *run_off, const uint32_t *const *seg_off,
+                                const uint32_t *const *slot, uint32_t n_streams, uint32_t N, uint64_t base,
+                                uint64_t *ins_hash_out, uint32_t *ins_off_out, uint32_t *found_out) {
+  std::vector<uint64_t> pw((size_t)N + 1);
+  pw[0] = 1;
+  for (uint32_t k = 1; k <= N; ++k) pw[k] = pw[k - 1] * base;
+  uint32_t c = 0;  // where the stored text that the current token continues starts
+  for (uint32_t i = 0; i < N; ++i) {
+    ins_hash_out[i] = CPO_HASH_NONE;
+    ins_off_out[i] = 0xFFFFFFFFu;
+    found_out[i] = CPO_SLOT_NONE;
+    if (hash[i] == CPO_HASH_NONE) continue;
+    if (run_off[i] == 0) c = i;  // a new run starts a text of its own ...
+    for (uint32_t k = 0; k < n_streams; ++k)
+      if (slot[k][i] != CPO_SLOT_NONE) {  // ... unless a lookup stream finds the token: then that text goes on
+        found_out[i] = slot[k][i];
+        c = i - seg_off[k][i];
+        break;
+      }
+    ins_off_out[i] = i - c;
+    const uint64_t before = run_off[c] == 0 ? 0 : hash[c - 1];
+    const uint64_t h = hash[i] - before * pw[i - c + 1];
+    ins_hash_out[i] = h == CPO_HASH_NONE ? CPO_HASH_NONE - 1 : h;
+  }
+}
+
+extern "C" uint32_t cpo_insert_kv_dedup(cpo_index *ix, const uint64_t *ins_hash, const uint32_t *found,
+                                        const uint32_t *off, uint32_t R, const uint32_t *free_slots,
+                                        uint32_t n_free, const void *src, cpo_layout src_l, void *pool,
+                                        cpo_layout pool_l, int32_t *slot_pos, uint32_t *slot_out,
+                                        uint32_t *flags, const uint32_t *tok, uint32_t *slot_tok) {
+  return insert_tokens(ix, ins_hash, found, off, R, free_slots, n_free, src, src_l, pool, pool_l, slot_pos,
+                       slot_out, flags, tok, slot_tok);
 }
 
 // ---- floating anchors (Sec. 4.2.2 Step 1 and Step 2) -------------------------------------------
@@ -365,8 +415,8 @@ static bool text_equals(const cpo_text *t, uint32_t s, const uint32_t *tok, uint
   return true;
 }
 
-extern "C" void cpo_text_record(cpo_text *t, const uint32_t *tok, const uint32_t *run_off, uint32_t N,
-                                uint32_t *slot_out) {
+static void text_record(cpo_text *t, const uint32_t *tok, const uint32_t *run_off, const uint32_t *found,
+                        uint32_t N, uint32_t *slot_out) {
   const uint64_t base = t->archive.size();
   t->archive.insert(t->archive.end(), tok, tok + N);
   bool prev_ok = false;
@@ -378,7 +428,10 @@ extern "C" void cpo_text_record(cpo_text *t, const uint32_t *tok, const uint32_t
     const bool start_ok = run_off[i] == 0 || prev_ok;
     const uint32_t s = slot_out[i], n = run_off[i] + 1;
     bool ok = false;
-    if (s < t->len.size()) {
+    if (found && found[i] != CPO_SLOT_NONE) {
+      // a token that a confirmed lookup found: its slot holds exactly the n tokens that end here
+      ok = text_equals(t, s, tok, i, n);
+    } else if (s < t->len.size()) {
       if (t->len[s] == 0) {  // a slot filled by this batch, seen at its first (storing) token
         if (start_ok) {
           t->last[s] = base + i;
@@ -394,6 +447,16 @@ extern "C" void cpo_text_record(cpo_text *t, const uint32_t *tok, const uint32_t
     if (!ok) slot_out[i] = CPO_SLOT_NONE;
     prev_ok = ok;
   }
+}
+
+extern "C" void cpo_text_record(cpo_text *t, const uint32_t *tok, const uint32_t *run_off, uint32_t N,
+                                uint32_t *slot_out) {
+  text_record(t, tok, run_off, nullptr, N, slot_out);
+}
+
+extern "C" void cpo_text_record_dedup(cpo_text *t, const uint32_t *tok, const uint32_t *ins_off,
+                                      const uint32_t *found, uint32_t N, uint32_t *slot_out) {
+  text_record(t, tok, ins_off, found, N, slot_out);
 }
 
 extern "C" void cpo_verify(const cpo_text *t, const uint32_t *tok, const uint32_t *seg_off,

@@ -109,6 +109,27 @@ uint32_t cpo_insert_kv(cpo_index *, const uint64_t *hash, const uint32_t *off, u
                        uint32_t *slot_out, uint32_t *flags, const uint32_t *tok,
                        uint32_t *slot_tok);
 
+/* ---- One copy of a text that is stored already (Sec. 4.3.5 "Lifecycle management": a segment that another
+ * stored segment contains is kept once) ----
+ * Before a batch is stored, a lookup says which of its tokens the pool already has: slot[k][i] is what key
+ * stream k (run-start keys, then the candidate streams) found for token i and seg_off[k][i] the token's offset
+ * in that stream's segment.  A token that some stream finds is not stored again.  Every other token is stored
+ * as the continuation of the text that the latest found token before it (in its run) belongs to: behind a
+ * token found at offset o of a stored text, the next tokens extend that stored text; a run in which nothing was
+ * found yet starts a text of its own, as in cpo_insert_kv.
+ *   ins_off_out[i]  = offset of token i in the text it belongs to (0xFFFFFFFF for sensitive tokens),
+ *   ins_hash_out[i] = chain hash of that text from its first token through token i (the table key),
+ *   found_out[i]    = slot of the first stream that found token i, else CPO_SLOT_NONE.
+ * cpo_insert_kv_dedup is cpo_insert_kv with these keys, skipping the found tokens (slot_out = found).
+ * Texts stored within one batch do not see each other: only what earlier batches stored is found. */
+void cpo_insert_keys(const uint64_t *hash, const uint32_t *run_off, const uint32_t *const *seg_off,
+                     const uint32_t *const *slot, uint32_t n_streams, uint32_t N, uint64_t base,
+                     uint64_t *ins_hash_out, uint32_t *ins_off_out, uint32_t *found_out);
+uint32_t cpo_insert_kv_dedup(cpo_index *, const uint64_t *ins_hash, const uint32_t *found, const uint32_t *off,
+                             uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
+                             cpo_layout src_l, void *pool, cpo_layout pool_l, int32_t *slot_pos,
+                             uint32_t *slot_out, uint32_t *flags, const uint32_t *tok, uint32_t *slot_tok);
+
 /* ---- Floating anchors (Sec. 4.2.2, Step 1 "prefix filtering" and Step 2's O(1) substring hash) ----
  * The pool also keeps, for every stored run of at least W tokens, the rolling hash of its first W
  * tokens.  A lookup slides a W-token window over each run of the request; where the window's hash is
@@ -173,6 +194,10 @@ void cpo_text_free(cpo_text *);
  * first filled by such a token never matches anything. */
 void cpo_text_record(cpo_text *, const uint32_t *tok, const uint32_t *run_off, uint32_t N,
                      uint32_t *slot_out);
+/* The same after cpo_insert_kv_dedup, with ins_off in place of run_off; a token that the lookup found
+ * is checked against its slot's whole text, whatever came before it. */
+void cpo_text_record_dedup(cpo_text *, const uint32_t *tok, const uint32_t *ins_off, const uint32_t *found,
+                           uint32_t N, uint32_t *slot_out);
 /* seg_off[i] = offset of token i in its segment (0 = first, 0xFFFFFFFF = in none); cand[i] = the
  * slot found under the segment's key for i.  slot_out[i] = cand[i] if accepted, else NONE; with
  * merge != 0 only entries of slot_out that are NONE are written. */
