@@ -252,9 +252,11 @@ def make_docs(name, seed, shape, R, T, prefix_len, n_docs, doc_len, docs_per_req
     )
 
 
-def from_prompts(name, seed, shape, donors, requests, pool_slots, donor_masks=None, request_masks=None):
-    """A workload from explicit token lists: ``donors`` are stored one after the other in one batch,
-    ``requests`` are looked up.  Masks default to "nothing sensitive".  For hand-built test cases."""
+def from_prompts(name, seed, shape, donors, requests, pool_slots, donor_masks=None, request_masks=None,
+                 donor_batch_tokens=1 << 17):
+    """A workload from explicit token lists: ``donors`` are stored one after the other, in batches of at most
+    ``donor_batch_tokens`` tokens; ``requests`` are looked up.  Masks default to "nothing sensitive".  For
+    hand-built test cases."""
     rng = np.random.default_rng(seed)
     as_u32 = lambda xs: [np.asarray(x, np.uint32) for x in xs]  # noqa: E731
     zeros = lambda xs: [np.zeros(len(x), np.uint8) for x in xs]  # noqa: E731
@@ -262,7 +264,7 @@ def from_prompts(name, seed, shape, donors, requests, pool_slots, donor_masks=No
     dt, dm, doff = _pack(donors, donor_masks or zeros(donors))
     tok, mask, off = _pack(requests, request_masks or zeros(requests))
     return Workload(name=name, seed=seed, shape=shape, tok=tok, mask=mask, off=off, donor_tok=dt, donor_mask=dm,
-                    donor_off=doff, donor_batches=_batches(doff, 1 << 17), pool_slots=pool_slots,
+                    donor_off=doff, donor_batches=_batches(doff, donor_batch_tokens), pool_slots=pool_slots,
                     free_slots=rng.permutation(pool_slots).astype(np.uint32), table_capacity=2 * pool_slots)
 
 

@@ -8,7 +8,7 @@
  * and, further down, the calls that widen it to the paper's retrieval and pool
  * life cycle: floating anchors (cp_hash_runs, cp_insert_anchors, cp_hash_floating,
  * cp_probe2, cp_probe3), exact confirmation of matches (cp_insert_kv_chain, cp_verify_chain),
- * pool policies (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch,
+ * one copy of stored text (cp_insert_keys, cp_insert_kv_dedup), pool policies (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch,
  * cp_lru_threshold, cp_evict, cp_table_compact) and the KV annotator
  * (cp_sat_build, cp_annotate).
  *
@@ -319,6 +319,38 @@ int32_t cp_insert_kv(void *stream, cp_table table, const uint64_t *hash, const u
                      cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
                      int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
                      void *scratch, size_t scratch_bytes, const cp_launch_opts *opts);
+
+/* ---- One copy of a text that the pool already holds -------------------------------------------
+ * Sec. 4.3.5 "Lifecycle management": the pool keeps one copy of duplicated segments, and of a
+ * segment that another stored segment contains.  cp_insert_kv alone keeps one copy of equal run
+ * beginnings; with floating anchors a batch can also be checked for text that is stored behind other
+ * text or as a run of its own.  Before storing, look the batch up: per key stream k (run-start keys,
+ * then the candidate streams) slot_k[i] = what the stream found for token i (confirmed, if the pool
+ * confirms matches) and seg_off_k[i] = the token's offset in the stream's segment.
+ *   cp_insert_keys: for every non-sensitive token, the stored text it belongs to starts at
+ *     c = i - seg_off_k[i] for the first stream k that found it; else at the c of its left neighbour
+ *     in its run; else (first token of a run) at i.  ins_off_out[i] = i - c, ins_hash_out[i] = chain
+ *     hash of the request's tokens c..i (the table key), found_out[i] = slot_k[i] or CP_SLOT_NONE.
+ *     A token that was not found thus continues the stored text before it, so stored texts stay closed
+ *     under taking prefixes.  Unused streams: both pointers NULL.  Sensitive tokens: CP_HASH_NONE,
+ *     0xFFFFFFFF, CP_SLOT_NONE.
+ *   cp_insert_kv_dedup: cp_insert_kv (slot_tok == slot_parent == NULL) or cp_insert_kv_chain under
+ *     the keys ins_hash, with ins_off in the place of run_off, that leaves out every token with
+ *     found[i] != CP_SLOT_NONE: it gets no table entry and no slot, slot_out[i] = found[i], and for
+ *     the chain records it counts as confirmed.  Pass ins_off and slot_out on to cp_insert_anchors.
+ * Texts stored by one call do not see each other (the lookup ran before): two requests of a batch
+ * that bring the same new text behind different leads each store it. */
+int32_t cp_insert_keys(void *stream, const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base,
+                       const uint32_t *seg_off_a, const uint32_t *slot_a, const uint32_t *seg_off_b,
+                       const uint32_t *slot_b, const uint32_t *seg_off_c, const uint32_t *slot_c,
+                       uint64_t *ins_hash_out, uint32_t *ins_off_out, uint32_t *found_out, void *scratch,
+                       size_t scratch_bytes);
+int32_t cp_insert_kv_dedup(void *stream, cp_table table, const uint64_t *ins_hash, const uint32_t *found,
+                           const uint32_t *tok, const uint32_t *ins_off, const uint32_t *off, uint32_t N, uint32_t R,
+                           const uint32_t *free_slots, uint32_t n_free, const void *src, cp_kv_layout src_l,
+                           void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots, int32_t *slot_pos,
+                           uint32_t *slot_tok, uint32_t *slot_parent, uint32_t *slot_out, uint32_t *n_inserted,
+                           uint32_t *status_flags, void *scratch, size_t scratch_bytes, const cp_launch_opts *opts);
 
 /* ---- Pool policies -----------------------------------------------------------------------------
  * All arrays are device memory owned by the caller; scratch as for the other calls

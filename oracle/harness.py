@@ -53,7 +53,7 @@ class OracleState:
 
 
 def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None, verify=False,
-            recompute=None) -> OracleState:
+            recompute=None, dedup=False) -> OracleState:
     """Insert the donor prompts batch by batch.  ``src_provider(first_tok, n_tok)``
     returns the layer-major KV buffer of a donor batch (default: host generator,
     uid = packed donor index).  With ``anchor_window`` = W the hash of every
@@ -84,17 +84,31 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         src = src_provider(t0, n) if src_provider else gen_buffer(wl.seed, sh, t0, n)
         off = (wl.donor_off[first : last + 1] - wl.donor_off[first]).astype(np.uint32)
         before = st.n_used
-        slot_out, n_new, fl = O.insert_kv(
-            st.index, st.donor_hash[t0:t1], off, wl.free_slots[st.n_used :], src, buf_layout(sh, n), st.pool,
-            pool_layout(sh), st.slot_pos, tok=wl.donor_tok[t0:t1], slot_tok=st.slot_tok)
-        if st.text is not None:
+        b_tok, b_mask, b_hash = wl.donor_tok[t0:t1], wl.donor_mask[t0:t1], st.donor_hash[t0:t1]
+        b_roff = O.run_offsets(b_mask, off)
+        if dedup:  # every text once: look the batch up first, leave out what the pool has (Sec. 4.3.5)
+            streams = O.match_streams(st.index, b_tok, b_hash, b_roff, st.anchors, st.anchor_window, st.text,
+                                      with_offsets=True)
+            ins_hash, ins_off, found = O.insert_keys(b_hash, b_roff, streams)
+            slot_out, n_new, fl = O.insert_kv_dedup(
+                st.index, ins_hash, found, off, wl.free_slots[st.n_used :], src, buf_layout(sh, n), st.pool,
+                pool_layout(sh), st.slot_pos, tok=b_tok, slot_tok=st.slot_tok)
             raw = slot_out
-            slot_out = O.text_record(st.text, wl.donor_tok[t0:t1], O.run_offsets(wl.donor_mask[t0:t1], off), raw)
+            if st.text is not None:
+                slot_out = O.text_record_dedup(st.text, b_tok, ins_off, found, raw)
+            st.donor_hash[t0:t1] = ins_hash
+            b_hash, b_roff = ins_hash, ins_off
+        else:
+            slot_out, n_new, fl = O.insert_kv(
+                st.index, b_hash, off, wl.free_slots[st.n_used :], src, buf_layout(sh, n), st.pool,
+                pool_layout(sh), st.slot_pos, tok=b_tok, slot_tok=st.slot_tok)
+            if st.text is not None:
+                raw = slot_out
+                slot_out = O.text_record(st.text, b_tok, b_roff, raw)
         if st.marks is not None:
             O.mark_recompute(slot_out, recompute[t0:t1], st.marks)
         if st.anchors is not None:
-            O.insert_anchors(st.anchors, st.donor_hash[t0:t1], O.run_offsets(wl.donor_mask[t0:t1], off), slot_out,
-                             st.anchor_window)
+            O.insert_anchors(st.anchors, b_hash, b_roff, slot_out, st.anchor_window)
         st.donor_slot[t0:t1] = slot_out
         st.n_used += n_new
         flags |= fl

@@ -32,7 +32,7 @@ EXPORTS = [
     "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_gather_kv_static", "cp_insert_kv",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2", "cp_probe3",
-    "cp_insert_kv_chain", "cp_verify_chain",
+    "cp_insert_kv_chain", "cp_verify_chain", "cp_insert_keys", "cp_insert_kv_dedup",
     "cp_filter_matches", "cp_mark_recompute", "cp_fill_unmatched", "cp_touch", "cp_lru_threshold", "cp_evict",
     "cp_table_compact", "cp_sat_scratch_bytes", "cp_sat_build", "cp_annotate",
 ]
@@ -127,6 +127,11 @@ def lib():
         L.cp_hash_floating.argtypes = [vp, TableStruct, vp, u32, vp, vp, u32, u64, u32, vp, vp, vp, vp, vp, sz]
         L.cp_insert_kv_chain.restype = i32
         L.cp_insert_kv_chain.argtypes = [vp, TableStruct, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
+                                         u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.cp_insert_keys.restype = i32
+        L.cp_insert_keys.argtypes = [vp, vp, vp, u32, u64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz]
+        L.cp_insert_kv_dedup.restype = i32
+        L.cp_insert_kv_dedup.argtypes = [vp, TableStruct, vp, vp, vp, vp, vp, u32, u32, vp, u32, vp, KVLayout, vp, KVLayout,
                                          u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_verify_chain.restype = i32
         L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, vp, sz]
@@ -319,6 +324,32 @@ def cp_insert_kv_chain(table: Table, hashes, tok, run_off, off, free_slots, n_fr
         _stream(stream), table.struct, _ptr(hashes), _ptr(tok), _ptr(run_off), _ptr(off), N, R, _ptr(free_slots),
         n_free, _ptr(src), src_l, _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_tok), _ptr(slot_parent),
         _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags), _ptr(scratch), scratch.numel(), _opts(opts)))
+
+
+def cp_insert_keys(hashes, run_off, streams, ins_hash_out, ins_off_out, found_out, scratch, base=BASE, stream=None):
+    """``streams``: up to three (seg_off, slot) tensor pairs, one per lookup stream in serving order."""
+    _need_cuda(hashes, run_off, ins_hash_out, ins_off_out, found_out, scratch, *[t for p in streams for t in p])
+    N = hashes.numel()
+    assert 1 <= len(streams) <= 3 and all(a.numel() == N and b.numel() == N for a, b in streams)
+    assert ins_hash_out.numel() == N and ins_off_out.numel() == N and found_out.numel() == N
+    ptrs = [_ptr(t) for p in streams for t in p] + [None] * (6 - 2 * len(streams))
+    _check("cp_insert_keys", lib().cp_insert_keys(_stream(stream), _ptr(hashes), _ptr(run_off), N, base, *ptrs,
+                                                  _ptr(ins_hash_out), _ptr(ins_off_out), _ptr(found_out), _ptr(scratch),
+                                                  scratch.numel()))
+
+
+def cp_insert_kv_dedup(table: Table, ins_hash, found, tok, ins_off, off, free_slots, n_free, src, src_l: KVLayout, pool,
+                       pool_l: KVLayout, n_pool_slots, slot_pos, slot_tok, slot_parent, slot_out, n_inserted,
+                       status_flags, scratch, stream=None, opts: LaunchOpts | None = None):
+    _need_cuda(ins_hash, found, tok, ins_off, off, free_slots, src, pool, slot_pos, slot_tok, slot_parent, slot_out,
+               n_inserted, status_flags, scratch)
+    N, R = ins_hash.numel(), off.numel() - 1
+    assert found.numel() == N and slot_out.numel() == N and (free_slots is None or free_slots.numel() >= n_free)
+    _check("cp_insert_kv_dedup", lib().cp_insert_kv_dedup(
+        _stream(stream), table.struct, _ptr(ins_hash), _ptr(found), _ptr(tok), _ptr(ins_off), _ptr(off), N, R,
+        _ptr(free_slots), n_free, _ptr(src), src_l, _ptr(pool), pool_l, n_pool_slots, _ptr(slot_pos), _ptr(slot_tok),
+        _ptr(slot_parent), _ptr(slot_out), _ptr(n_inserted), _ptr(status_flags), _ptr(scratch), scratch.numel(),
+        _opts(opts)))
 
 
 def cp_filter_matches(slot_in, off, min_len, slot_recompute, n_pool_slots, slot_out, scratch, stream=None):

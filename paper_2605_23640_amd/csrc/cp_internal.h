@@ -80,6 +80,7 @@ int32_t launch_anchor_extents(hipStream_t stream, const cp_table &table, const u
 // the same values without regard to merge.  agg: div_up(N, 1024) + 1 words.
 int32_t launch_chain_verify(hipStream_t stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
                             uint32_t N, const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots,
-                            uint32_t merge, uint32_t *slot_out, uint32_t *stream_out, uint32_t *agg);
+                            uint32_t merge, uint32_t *slot_out, uint32_t *stream_out, uint32_t *agg,
+                            const uint32_t *trusted /* nullable: tokens with trusted[i] != NONE pass and start anew */);
 
 }  // namespace cp

@@ -141,6 +141,59 @@ __global__ __launch_bounds__(256) void early_key_kernel(const uint64_t *__restri
   if (early_off_out) early_off_out[i] = eo;
 }
 
+// Keys under which a batch is stored when every text is kept once (Sec. 4.3.5 "Lifecycle management").
+// A token that a lookup stream found belongs to the stored text that stream's segment starts; a token
+// that nothing found continues the text of the latest found token before it in its run (or starts a
+// text with its run).  "Start of the text I belong to" is thus a value that found tokens and run starts
+// define and every other token inherits from its left neighbour: a scan that keeps the latest
+// defined value.
+struct InsertKeyOp {
+  using T = uint32_t;  // 1 + start of the text, 0 = not defined by this piece
+  const uint64_t *hash;
+  const uint32_t *run_off;
+  const uint32_t *seg_off[3];  // per lookup stream, in serving order (unused streams: null)
+  const uint32_t *slot[3];
+  uint64_t *ins_hash_out;
+  uint32_t *ins_off_out, *found_out;
+  uint64_t base;
+  uint32_t N;
+
+  static __device__ __forceinline__ T identity() { return 0u; }
+  static __device__ __forceinline__ T combine(T f, T g) { return g ? g : f; }
+  __device__ __forceinline__ uint32_t count() const { return N; }
+  __device__ __forceinline__ uint32_t found_in(uint32_t i, uint32_t *start) const {
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+      if (slot[k] && slot[k][i] != CP_SLOT_NONE) {
+        *start = i - seg_off[k][i];
+        return slot[k][i];
+      }
+    return CP_SLOT_NONE;
+  }
+  __device__ __forceinline__ T load(uint32_t i) const {
+    const uint32_t ro = run_off[i];
+    if (ro == 0xFFFFFFFFu) return 0u;  // sensitive: the token after it starts a run
+    uint32_t start = i - ro;
+    if (found_in(i, &start) != CP_SLOT_NONE) return start + 1;
+    return ro == 0 ? i + 1 : 0u;
+  }
+  __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
+    uint64_t key = CP_HASH_NONE;
+    uint32_t io = 0xFFFFFFFFu, f = CP_SLOT_NONE;
+    if (hash[i] != CP_HASH_NONE && incl != 0) {
+      const uint32_t c = incl - 1;
+      uint32_t unused;
+      f = found_in(i, &unused);
+      io = i - c;
+      key = io == run_off[i] ? hash[i] : substring_key(hash, base, c, i);  // a text that starts its run: the plain chain hash
+    }
+    ins_hash_out[i] = key;
+    ins_off_out[i] = io;
+    found_out[i] = f;
+  }
+  __device__ __forceinline__ void finish(T) const {}
+};
+
 }  // namespace
 }  // namespace cp
 
@@ -199,4 +252,27 @@ extern "C" int32_t cp_hash_floating(void *stream_, cp_table table, const uint8_t
   if (int32_t rc = run_scan<FloatOp>(stream, op, N, agg)) return rc;
   early_key_kernel<<<div_up(N, 256), 256, 0, stream>>>(hash, run_off, reach, N, base, hash_early_out, early_off_out);
   return check_launch();
+}
+
+extern "C" int32_t cp_insert_keys(void *stream, const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base,
+                                  const uint32_t *seg_off_a, const uint32_t *slot_a, const uint32_t *seg_off_b,
+                                  const uint32_t *slot_b, const uint32_t *seg_off_c, const uint32_t *slot_c,
+                                  uint64_t *ins_hash_out, uint32_t *ins_off_out, uint32_t *found_out, void *scratch,
+                                  size_t scratch_bytes) {
+  using namespace cp;
+  if (N == 0) return CP_OK;
+  if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (!hash || !run_off || !ins_hash_out || !ins_off_out || !found_out || !scratch || !aligned(scratch, 256) ||
+      !aligned(hash, 8) || !aligned(ins_hash_out, 8))
+    return CP_ERR_INVALID_ARG;
+  if ((seg_off_a == nullptr) != (slot_a == nullptr) || (seg_off_b == nullptr) != (slot_b == nullptr) ||
+      (seg_off_c == nullptr) != (slot_c == nullptr))
+    return CP_ERR_INVALID_ARG;
+  if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
+  Scratch sc(scratch, scratch_bytes);
+  uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
+  if (!agg) return CP_ERR_SCRATCH;
+  InsertKeyOp op{hash, run_off, {seg_off_a, seg_off_b, seg_off_c}, {slot_a, slot_b, slot_c}, ins_hash_out, ins_off_out,
+                 found_out, base, N};
+  return run_scan<InsertKeyOp>((hipStream_t)stream, op, N, agg);
 }

@@ -239,11 +239,13 @@ __global__ __launch_bounds__(kProbeThreads) void table_compact_kernel(cp_table s
 // Insert, step 1: find or claim the table entry of every token's key and leave
 // in vals[] the smallest packed index that asked for a not-yet-stored key.
 __global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t, const uint64_t *__restrict__ hash,
+                                                                     const uint32_t *__restrict__ found /* nullable */,
                                                                      uint32_t N, uint32_t *__restrict__ entry_of,
                                                                      uint32_t *status_flags) {
   const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
   const uint32_t sub = threadIdx.x & (kBucket - 1);
-  const uint64_t h = q < N ? hash[q] : CP_HASH_NONE;
+  // a token whose text the pool holds already (found) asks for no entry: it is not stored again
+  const uint64_t h = (q < N && !(found && found[q] != CP_SLOT_NONE)) ? hash[q] : CP_HASH_NONE;
   const uint32_t entry = group_claim(t, h);
   if (q < N && sub == 0) {
     entry_of[q] = entry;
@@ -289,13 +291,16 @@ __global__ __launch_bounds__(256) void insert_resolve_kernel(const uint32_t *__r
                                                              const uint32_t *__restrict__ rank,
                                                              const uint32_t *__restrict__ free_slots, uint32_t n_free,
                                                              uint32_t n_pool_slots, uint32_t N,
+                                                             const uint32_t *__restrict__ found /* nullable */,
                                                              uint32_t *__restrict__ slot_out,
                                                              uint8_t *__restrict__ owner) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
   if (owner) owner[i] = 0;  // set again by the commit step for the tokens that store
   uint32_t e = entry_of[i], s = CP_SLOT_NONE;
-  if (e != CP_SLOT_NONE) {
+  if (found && found[i] != CP_SLOT_NONE) {
+    s = found[i];  // the slot that already holds this token's text
+  } else if (e != CP_SLOT_NONE) {
     uint32_t v = vals[e];
     if (v < kPending) {
       s = v;  // stored by an earlier call
@@ -447,7 +452,8 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
                              cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
                              int32_t *slot_pos, uint32_t *slot_out, uint32_t *n_inserted, uint32_t *status_flags,
                              void *scratch, size_t scratch_bytes, const uint32_t *tok, const uint32_t *run_off,
-                             uint32_t *slot_tok, uint32_t *slot_parent, const cp_launch_opts *opts) {
+                             uint32_t *slot_tok, uint32_t *slot_parent, const cp_launch_opts *opts,
+                             const uint32_t *found = nullptr) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   const bool chain = slot_tok != nullptr;
@@ -474,12 +480,12 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
   const uint32_t blocks = div_up(N, 256);
   if (N)
     insert_claim_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
-        table, hash, N, entry_of, status_flags);
+        table, hash, found, N, entry_of, status_flags);
   OwnerRankOp op{entry_of, table.vals, rank, n_inserted, status_flags, N, n_free};
   if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, agg)) return rc;
   if (N == 0) return CP_OK;
   insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, N,
-                                                    cand, owner);
+                                                    found, cand, owner);
   ChainRecord rec{tok, run_off, cand, slot_tok, slot_parent, owner};
   insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, off, R,
                                                    N, slot_pos, items, counter, chain ? rec : ChainRecord{});
@@ -488,7 +494,7 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
     // confirm every token's slot against the recorded chains (new slots are consistent by construction,
     // slots found under an existing key need not be), then take the unconfirmed new slots out of play
     if (int32_t rc = launch_chain_verify(stream, tok, run_off, cand, N, slot_tok, slot_parent, n_pool_slots, 0,
-                                         slot_out, nullptr, agg))
+                                         slot_out, nullptr, agg, found))
       return rc;
     insert_poison_kernel<<<blocks, 256, 0, stream>>>(owner, cand, slot_out, N, n_pool_slots, slot_parent);
     if (int32_t rc = check_launch()) return rc;
@@ -519,6 +525,20 @@ extern "C" int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64
   return insert_common(stream, table, hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
                        slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, tok, run_off, slot_tok,
                        slot_parent, opts);
+}
+
+extern "C" int32_t cp_insert_kv_dedup(void *stream, cp_table table, const uint64_t *ins_hash, const uint32_t *found,
+                                      const uint32_t *tok, const uint32_t *ins_off, const uint32_t *off, uint32_t N,
+                                      uint32_t R, const uint32_t *free_slots, uint32_t n_free, const void *src,
+                                      cp_kv_layout src_l, void *pool, cp_kv_layout pool_l, uint32_t n_pool_slots,
+                                      int32_t *slot_pos, uint32_t *slot_tok, uint32_t *slot_parent, uint32_t *slot_out,
+                                      uint32_t *n_inserted, uint32_t *status_flags, void *scratch,
+                                      size_t scratch_bytes, const cp_launch_opts *opts) {
+  if (N && !found) return CP_ERR_INVALID_ARG;
+  if ((slot_tok == nullptr) != (slot_parent == nullptr)) return CP_ERR_INVALID_ARG;
+  return insert_common(stream, table, ins_hash, off, N, R, free_slots, n_free, src, src_l, pool, pool_l, n_pool_slots,
+                       slot_pos, slot_out, n_inserted, status_flags, scratch, scratch_bytes, tok, ins_off, slot_tok,
+                       slot_parent, opts, found);
 }
 
 extern "C" int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags) {

@@ -24,7 +24,8 @@ struct ChainOp {
   const uint32_t *slot_tok;
   const uint32_t *slot_parent;
   uint32_t *slot_out;
-  uint32_t *stream_out;  // nullable: this stream's own result, whatever slot_out already held
+  uint32_t *stream_out;     // nullable: this stream's own result, whatever slot_out already held
+  const uint32_t *trusted;  // nullable: trusted[i] != NONE = the caller has confirmed cand[i] already
   uint32_t N, n_pool_slots, merge;
 
   static __device__ __forceinline__ T identity() { return 0u; }
@@ -33,6 +34,7 @@ struct ChainOp {
   __device__ __forceinline__ T load(uint32_t i) const {
     const uint32_t k = seg_off[i];
     if (k == 0xFFFFFFFFu) return 3u;  // in no segment: fails, and nothing carries over it
+    if (trusted && trusted[i] != CP_SLOT_NONE) return 2u;  // confirmed elsewhere: passes, whatever came before it
     const uint32_t s = cand[i];
     bool ok = s < n_pool_slots;
     uint32_t want_parent = CP_SLOT_NONE;
@@ -56,8 +58,9 @@ struct ChainOp {
 
 int32_t launch_chain_verify(hipStream_t stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
                             uint32_t N, const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots,
-                            uint32_t merge, uint32_t *slot_out, uint32_t *stream_out, uint32_t *agg) {
-  ChainOp op{tok, seg_off, cand, slot_tok, slot_parent, slot_out, stream_out, N, n_pool_slots, merge};
+                            uint32_t merge, uint32_t *slot_out, uint32_t *stream_out, uint32_t *agg,
+                            const uint32_t *trusted) {
+  ChainOp op{tok, seg_off, cand, slot_tok, slot_parent, slot_out, stream_out, trusted, N, n_pool_slots, merge};
   return run_scan<ChainOp>(stream, op, N, agg);
 }
 
@@ -78,5 +81,5 @@ extern "C" int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint
   uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
   if (!agg) return CP_ERR_SCRATCH;
   return launch_chain_verify((hipStream_t)stream, tok, seg_off, cand, N, slot_tok, slot_parent, n_pool_slots,
-                             merge ? 1u : 0u, slot_out, stream_out, agg);
+                             merge ? 1u : 0u, slot_out, stream_out, agg, nullptr);
 }

@@ -89,7 +89,10 @@ def prefill(wl, pool: cp.KVPool = None, recompute=None) -> GpuState:
         scratch = cp.binding.new_scratch(max(1, n), 0, DEV)
         roff = torch.empty(max(1, n), dtype=torch.int32, device=DEV) if (pool.slot_anchor is not None or pool.verify) else None
         rec = None if recompute is None else torch.from_numpy(np.ascontiguousarray(recompute[t0:t1], np.uint8)).to(DEV)
-        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch, run_off_buf=roff, recompute=rec))
+        lbuf = cp.LookupBuffers(n, 0, DEV) if pool.dedup else None
+        counts.append(pool.insert(tok, mask, off, src, hbuf, sout, scratch, run_off_buf=roff, recompute=rec, buf=lbuf))
+        if pool.dedup:  # the keys the batch was stored under
+            hbuf = lbuf.ins_hash
         donor_hash[t0:t1] = host_u64(hbuf)
         donor_slot[t0:t1] = host_u32(sout)
         del src

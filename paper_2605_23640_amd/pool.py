@@ -59,7 +59,12 @@ class LookupBuffers:
         self.late_off = torch.empty(N, dtype=i32, device=device)
         self.cand = torch.empty(N, dtype=i32, device=device)  # unconfirmed slots (pools that verify)
         self.slot = torch.empty(N, dtype=i32, device=device)  # slot of every matched token
-        self.slot_b = torch.empty(N, dtype=i32, device=device)  # what one candidate stream alone found / accepted
+        # what each key stream alone found / accepted (run-start keys, earliest candidate, latest candidate)
+        self.stream_slot = [torch.empty(N, dtype=i32, device=device) for _ in range(3)]
+        # storing every text once: key, offset in its stored text and "the pool has it" per token
+        self.ins_hash = torch.empty(N, dtype=i64, device=device)
+        self.ins_off = torch.empty(N, dtype=i32, device=device)
+        self.found = torch.empty(N, dtype=i32, device=device)
         self.served = torch.empty(N, dtype=i32, device=device)  # ... of those that pass the pool's policies
         m = max(1, self.max_spans)
         self.span_src = torch.empty(m, dtype=i32, device=device)
@@ -78,11 +83,15 @@ class KVPool:
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
                  device="cuda", pool_tensor=None, anchor_window=None, verify=False,
                  min_len=1, recompute_marks=False, zero_fill=False, lru=False, pool_layout="token",
-                 gather_opts=None, insert_opts=None):
+                 gather_opts=None, insert_opts=None, dedup=False):
         self.device = device
         # launch options (binding.LaunchOpts or None = defaults) handed to every gather / insert of this pool
         self.gather_opts, self.insert_opts = gather_opts, insert_opts
         self.n_slots = int(n_slots)
+        # store a text once: what a lookup of the batch finds (also behind other text, through the floating
+        # anchors) is not stored again, and new tokens continue the stored text before them
+        self.dedup = bool(dedup)
+        assert not dedup or anchor_window is not None, "dedup needs floating anchors (anchor_window)"
         # "token": [slot][layer][K|V][head][dim], a token's rows are contiguous (the default);
         # "layer": [layer][K|V][slot][head][dim], every row of a token lies in another plane (for comparison)
         assert pool_layout in ("token", "layer")
@@ -161,41 +170,48 @@ class KVPool:
     def hash(self, tok, mask, off, out, scratch, stream=None):
         return B.cp_hash_segments(tok, mask, off, out, scratch, stream=stream)
 
+    def _match(self, tok, mask, off, buf: LookupBuffers, stream, per_stream, touch):
+        """Hashes and slots of a batch: buf.slot = slot serving every token.  Returns the key streams as
+        (offset of every token in its segment, that stream's own finds) in serving order; the finds are
+        only filled in with ``per_stream`` (LRU stamps and storing-once need them).  ``touch``: stamp what
+        the candidate streams found (the merged result is stamped by the caller)."""
+        lru = touch and self.slot_stamp is not None
+        if self.slot_anchor is None and not self.verify:
+            B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
+            B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
+            return [(None, buf.slot)]
+        B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
+        keys = [(buf.hash, buf.run_off)]
+        if self.slot_anchor is not None:
+            B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off, self.anchor_window,
+                               buf.hash_float, buf.scratch, stream=stream, early_off_out=buf.float_off,
+                               hash_late_out=buf.hash_late, late_off_out=buf.late_off)
+            keys += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
+        if self.verify:
+            for k, (key, seg_off) in enumerate(keys):
+                B.cp_probe(self.table, key, buf.cand, stream=stream)
+                B.cp_verify_chain(tok, seg_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, k > 0,
+                                  buf.slot, buf.scratch, stream=stream,
+                                  stream_out=buf.stream_slot[k] if per_stream else None)
+        else:
+            B.cp_probe3(self.table, buf.hash, buf.hash_float, buf.hash_late, buf.slot, stream=stream)
+            if per_stream:
+                for k, (key, _) in enumerate(keys):
+                    B.cp_probe(self.table, key, buf.stream_slot[k], stream=stream)
+        if lru:
+            # where an earlier stream serves a token, a later one's slots still led to the tokens it does
+            # serve: they count as used, or a stored run could lose its head to eviction
+            for k in range(1, len(keys)):
+                B.cp_touch(buf.stream_slot[k], self.epoch, self.n_slots, self.slot_stamp, stream=stream)
+        return [(seg_off, buf.stream_slot[k]) for k, (_, seg_off) in enumerate(keys)]
+
     def lookup(self, tok, mask, off, dst, buf: LookupBuffers, gather=True, stream=None,
                gather_opts=None) -> LookupResult:
         """Serve a request batch: after the call the rows of every matched token of
         ``dst`` (layer-major, N tokens) hold the pooled KV.  No host synchronisation.
         ``gather_opts`` overrides the pool's launch options for this call."""
         N = tok.numel()
-        lru = self.slot_stamp is not None
-        if self.slot_anchor is None and not self.verify:
-            B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
-            B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
-        else:
-            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
-            streams = [(buf.hash, buf.run_off)]  # (keys, offset of every token in its segment), in serving order
-            if self.slot_anchor is not None:
-                B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off,
-                                   self.anchor_window, buf.hash_float, buf.scratch, stream=stream,
-                                   early_off_out=buf.float_off, hash_late_out=buf.hash_late,
-                                   late_off_out=buf.late_off)
-                streams += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
-            if self.verify:
-                for k, (keys, seg_off) in enumerate(streams):
-                    B.cp_probe(self.table, keys, buf.cand, stream=stream)
-                    B.cp_verify_chain(tok, seg_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, k > 0,
-                                      buf.slot, buf.scratch, stream=stream,
-                                      stream_out=buf.slot_b if lru and k > 0 else None)
-                    if lru and k > 0:
-                        # where an earlier stream serves a token, this one's slots still led to the tokens it
-                        # does serve: they count as used, or a stored run could lose its head to eviction
-                        B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
-            else:
-                B.cp_probe3(self.table, buf.hash, buf.hash_float, buf.hash_late, buf.slot, stream=stream)
-                if lru:  # the same for a pool that does not confirm: every stream's own finds count as used
-                    for keys, _ in streams[1:]:
-                        B.cp_probe(self.table, keys, buf.slot_b, stream=stream)
-                        B.cp_touch(buf.slot_b, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
+        self._match(tok, mask, off, buf, stream, per_stream=self.slot_stamp is not None, touch=True)
         if self.slot_stamp is not None:
             B.cp_touch(buf.slot, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         served = buf.slot  # buf.slot: every matched token; served: those that pass the policies
@@ -216,7 +232,7 @@ class KVPool:
                             buf.span_off, buf.n_spans, served)
 
     def insert(self, tok, mask, off, src, hash_buf, slot_out, scratch, hashes_ready=False, sync=True, stream=None,
-               run_off_buf=None, recompute=None, insert_opts=None):
+               run_off_buf=None, recompute=None, insert_opts=None, buf: LookupBuffers = None):
         """Store the non-sensitive tokens of a batch that the pool does not hold yet,
         taking their KV rows from ``src`` (layer-major, N tokens).  With ``sync`` the
         host free-list cursor is advanced (one device-to-host read).  A pool with
@@ -224,6 +240,8 @@ class KVPool:
         filled here unless ``hashes_ready``).  ``recompute`` (uint8[N]): tokens the
         annotator marked for recomputation when their segment is reused."""
         N = tok.numel()
+        if self.dedup:
+            return self._insert_once(tok, mask, off, src, slot_out, sync, stream, recompute, insert_opts, buf)
         if self.slot_anchor is not None or self.verify:
             assert run_off_buf is not None, "a pool with floating anchors or verification needs run_off_buf"
             if not hashes_ready:
@@ -250,6 +268,32 @@ class KVPool:
             B.cp_touch(slot_out, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
         if sync:
             if stream is not None:  # the count comes from kernels on that stream, not torch's current one
+                stream.synchronize()
+            n = int(self.n_inserted.item())
+            self.n_used += n
+            return n
+        return None
+
+    def _insert_once(self, tok, mask, off, src, slot_out, sync, stream, recompute, insert_opts, buf):
+        """insert() of a pool that stores every text once: the batch is looked up first (all key streams, no
+        stamps), what the pool has is left out, and new tokens continue the stored text before them."""
+        assert buf is not None and buf.N == tok.numel(), "a pool with dedup needs the batch's LookupBuffers"
+        N = tok.numel()
+        streams = self._match(tok, mask, off, buf, stream, per_stream=True, touch=False)
+        B.cp_insert_keys(buf.hash, buf.run_off, streams, buf.ins_hash, buf.ins_off, buf.found, buf.scratch, stream=stream)
+        n_free = self.free_slots.numel() - self.n_used
+        B.cp_insert_kv_dedup(self.table, buf.ins_hash, buf.found, tok, buf.ins_off, off, self.free_slots[self.n_used:],
+                             n_free, src, self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos,
+                             self.slot_tok, self.slot_parent, slot_out, self.n_inserted, self.flags, buf.scratch,
+                             stream=stream, opts=self.insert_opts if insert_opts is None else insert_opts)
+        B.cp_insert_anchors(buf.ins_off, slot_out, self.anchor_window, self.n_slots, self.slot_anchor, stream=stream)
+        if recompute is not None:
+            assert self.slot_recompute is not None, "pool was created without recompute_marks=True"
+            B.cp_mark_recompute(slot_out, recompute, self.n_slots, self.slot_recompute, stream=stream)
+        if self.slot_stamp is not None:
+            B.cp_touch(slot_out, self.epoch, self.n_slots, self.slot_stamp, stream=stream)
+        if sync:
+            if stream is not None:
                 stream.synchronize()
             n = int(self.n_inserted.item())
             self.n_used += n
