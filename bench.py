@@ -220,6 +220,9 @@ def main():
                     help="fraction of the stored tokens marked for recomputation (seeded, uniform): not served")
     ap.add_argument("--zero-fill", action="store_true", help="write zero rows for every token that is not served")
     ap.add_argument("--lru", action="store_true", help="keep last-use stamps for eviction")
+    ap.add_argument("--dedup", action="store_true",
+                    help="store every text once: what a lookup of a batch finds (also behind other text) is not stored again "
+                         "(needs --anchor-window)")
     ap.add_argument("--free-list", default="random", choices=["random", "sequential"],
                     help="order in which pool slots are handed out (the configurations say random)")
     ap.add_argument("--pool-layout", default="token", choices=["token", "layer"],
@@ -274,7 +277,7 @@ def main():
         rec = (wl.donor_u < args.recompute).astype(np.uint8)
     gst = G.prefill(wl, G.make_pool(wl, anchor_window=args.anchor_window, verify=args.verify, min_len=args.min_len,
                                     recompute_marks=rec is not None, zero_fill=args.zero_fill, lru=args.lru,
-                                    pool_layout=args.pool_layout, gather_opts=opts, insert_opts=opts),
+                                    pool_layout=args.pool_layout, gather_opts=opts, insert_opts=opts, dedup=args.dedup),
                     recompute=rec)
     pool = gst.pool
     log(f"[bench] pool prefilled: {pool.n_used} tokens stored ({time.time() - t0:.1f}s)")
@@ -284,6 +287,7 @@ def main():
     dst = G.poison_tensor(N * sh.tok_bytes)
     slot_out = torch.empty(N, dtype=torch.int32, device=G.DEV)
     ins_scratch = cp.binding.new_scratch(N, 0, G.DEV)
+    ins_buf = cp.LookupBuffers(N, 0, G.DEV) if args.dedup else None  # the lookup that precedes a storing-once insert
     keys0, vals0 = pool.table.keys.clone(), pool.table.vals.clone()
     if pool.slot_anchor is not None:
         anchor0 = pool.slot_anchor.clone()
@@ -298,7 +302,7 @@ def main():
         if k is not None:
             ev_ins[k][0].record()
         pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False,
-                    run_off_buf=buf.run_off,
+                    run_off_buf=buf.run_off, buf=ins_buf,
                     insert_opts=None if k is None else opts.with_events(hev.ev[4 * k + 2], hev.ev[4 * k + 3]))
         if k is not None:
             ev_ins[k][1].record()
@@ -377,7 +381,7 @@ def main():
         with torch.cuda.graph(graph, stream=side):
             pool.lookup(tok, mask, off, dst, buf)
             pool.insert(tok, mask, off, dst, buf.hash, slot_out, ins_scratch, hashes_ready=True, sync=False,
-                        run_off_buf=buf.run_off)
+                        run_off_buf=buf.run_off, buf=ins_buf)
 
         def restore_tables():
             pool.table.keys.copy_(keys0, non_blocking=True)
@@ -429,7 +433,7 @@ def main():
                     "bytes": 2 * span, "kernels": "cp_workload/kvgen.hip stream_{read,write,copy}_kernel"}
 
     # the stored counter readings belong to the gather of the default options
-    same_gather = (args.anchor_window is None and args.min_len <= 1 and args.recompute == 0
+    same_gather = (args.anchor_window is None and args.min_len <= 1 and args.recompute == 0 and not args.dedup
                    and args.pool_layout == "token" and args.free_list == "random")
     out = {
         "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
@@ -447,6 +451,7 @@ def main():
             "step": "hash+probe+spans+gather, insert of the batch's new tokens, table reset",
             "anchor_window": args.anchor_window, "verify": args.verify, "min_len": args.min_len,
             "recompute_fraction": args.recompute, "zero_fill": args.zero_fill, "lru_stamps": args.lru,
+            "store_once": args.dedup, "pool_tokens_after_prefill": pool.n_used,
             "pool_layout": args.pool_layout, "free_list": args.free_list,
             "tokens": N, "reused_tokens": matched, "hit_fraction": matched / N, "spans": n_spans,
             "distinct_source_slots": unique_src, "stored_tokens_per_step": inserted, "status_flags": flags,

@@ -103,8 +103,9 @@ int32_t cp_last_hip_error(void);
 /* Launch options of the row mover behind cp_gather_kv / cp_insert_kv* (the one kernel of a call
  * that is bound by HBM).  Passed per call as a HOST pointer that is read before the call returns;
  * NULL, or a zeroed struct, means the defaults.  Results never depend on these options.
- *   read_sharing     0/1 = tokens of one gather that read the same pool slot share one read of it
- *                    ("read once, write many"; the default), 2 = every token reads for itself
+ *   read_sharing     1 = tokens of one gather that read the same pool slot share one read of it
+ *                    ("read once, write many"), 2 = every token reads for itself, 0 = default: shared
+ *                    from 4096 destination tokens on (below that the two extra launches cost more)
  *   blocks_per_cu    resident workgroups per compute unit (0 = default: one workgroup on seven of
  *                    every eight units where a token's rows allow 16 loads in flight, else 2; 3 for a
  *                    gather that re-rotates keys)
@@ -150,6 +151,14 @@ int32_t cp_hash_segments(void *stream, const uint32_t *tok, const uint8_t *mask,
  * slot_out[i] = slot stored under hash[i], or CP_SLOT_NONE if the key is absent
  * or hash[i] is CP_HASH_NONE.  A sensitive token is therefore never served. */
 int32_t cp_probe(void *stream, cp_table table, const uint64_t *hash, uint32_t N, uint32_t *slot_out);
+
+/* cp_hash_segments (or cp_hash_runs, if run_off_out is not NULL) and cp_probe in one pass: every
+ * token's hash is looked up where it is computed, which saves a launch on the way to the slots
+ * (a single request is bound by its launches, Sec. 5.4.2 measures the retriever per request).
+ * Same results as the two calls. */
+int32_t cp_hash_probe(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
+                      uint32_t R, uint64_t base, cp_table table, uint64_t *hash_out, uint32_t *run_off_out,
+                      uint32_t *slot_out, void *scratch, size_t scratch_bytes);
 
 /* ---- Floating anchors: matches that do not start at the start of a run --------------------------
  * Sec. 4.2.2 Step 1 ("prefix filtering"): every stored segment keeps the hash of its first W tokens;

@@ -29,7 +29,7 @@ FLAG_SPANS_OVERFLOW, FLAG_POOL_FULL, FLAG_TABLE_FULL, FLAG_BAD_INDEX = 1, 2, 4, 
 
 EXPORTS = [
     "cp_table_capacity_for", "cp_scratch_bytes", "cp_last_hip_error", "cp_table_init",
-    "cp_hash_segments", "cp_probe", "cp_build_spans", "cp_gather_kv", "cp_gather_kv_static", "cp_insert_kv",
+    "cp_hash_segments", "cp_probe", "cp_hash_probe", "cp_build_spans", "cp_gather_kv", "cp_gather_kv_static", "cp_insert_kv",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2", "cp_probe3",
     "cp_insert_kv_chain", "cp_verify_chain", "cp_insert_keys", "cp_insert_kv_dedup",
@@ -117,6 +117,8 @@ def lib():
         L.cp_table_init.argtypes = [vp, TableStruct]
         L.cp_hash_segments.restype = i32
         L.cp_hash_segments.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, sz]
+        L.cp_hash_probe.restype = i32
+        L.cp_hash_probe.argtypes = [vp, vp, vp, vp, u32, u32, u64, TableStruct, vp, vp, vp, vp, sz]
         L.cp_probe.restype = i32
         L.cp_probe.argtypes = [vp, TableStruct, vp, u32, vp]
         L.cp_hash_runs.restype = i32
@@ -266,6 +268,18 @@ def cp_hash_segments(tok, mask, off, hash_out, scratch, base=BASE, stream=None):
     _check("cp_hash_segments", lib().cp_hash_segments(_stream(stream), _ptr(tok), _ptr(mask), _ptr(off), N, R, base,
                                                       _ptr(hash_out), _ptr(scratch), scratch.numel()))
     return hash_out
+
+
+def cp_hash_probe(tok, mask, off, table: Table, hash_out, run_off_out, slot_out, scratch, base=BASE, stream=None):
+    """cp_hash_segments / cp_hash_runs (``run_off_out`` may be None) and cp_probe in one pass."""
+    _need_cuda(tok, mask, off, hash_out, run_off_out, slot_out, scratch)
+    N, R = tok.numel(), off.numel() - 1
+    assert mask.numel() == N and hash_out.numel() == N and slot_out.numel() == N
+    assert run_off_out is None or run_off_out.numel() == N
+    _check("cp_hash_probe", lib().cp_hash_probe(_stream(stream), _ptr(tok), _ptr(mask), _ptr(off), N, R, base,
+                                                table.struct, _ptr(hash_out), _ptr(run_off_out), _ptr(slot_out),
+                                                _ptr(scratch), scratch.numel()))
+    return slot_out
 
 
 def cp_hash_runs(tok, mask, off, hash_out, run_off_out, scratch, base=BASE, stream=None):

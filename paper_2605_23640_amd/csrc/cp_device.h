@@ -1,5 +1,5 @@
 // Device-side building blocks shared by the kernels of libcacheprune:
-// an ordered three-pass scan over a user-defined monoid, request lookup, and
+// an ordered scan over a user-defined monoid, request lookup, and
 // launch / error plumbing.  gfx950 only (64-lane wavefronts).
 #pragma once
 
@@ -91,14 +91,51 @@ __device__ __forceinline__ typename Op::T block_exclusive_scan(typename Op::T v,
   return Op::combine(before, excl);
 }
 
-// ---- three-pass ordered scan over n = op.count() elements -------------------
+// ---- ordered scan over n = op.count() elements -------------------------------
 // Op supplies:  T, identity(), combine(a, b), count(), load(i),
 //               store(i, exclusive, inclusive), finish(total)
-// pass 1  scan_reduce  : per-tile totals            -> agg[tile]
-// pass 2  scan_carry   : one workgroup turns agg[] into exclusive tile prefixes
-//                        and calls op.finish(total of everything)
-// pass 3  scan_apply   : per-tile scan seeded with its prefix, op.store per element
-// Tiles past the end do nothing, so the grid may be sized for an upper bound of n.
+// Three forms, chosen by the number of tiles (kScanTile elements each):
+//   one tile            scan_single: one workgroup, one launch
+//   up to 512 tiles     scan_reduce (per-tile totals -> agg[tile]), then scan_apply_self: every tile
+//                       combines the totals of the tiles before it by itself (at most two loads per
+//                       thread) and scans its elements; the last tile calls op.finish.  Two launches.
+//   more                scan_reduce, scan_carry (one workgroup turns agg[] into exclusive tile
+//                       prefixes and calls op.finish), scan_apply.  Three launches.
+// No form waits for another workgroup.  Tiles past the end do nothing, so the grid may be sized for
+// an upper bound of n.
+constexpr uint32_t kSelfCarryTiles = 512;
+
+// Scan of one tile seeded with `prefix`; returns the tile's total combined onto the prefix.
+template <class Op>
+__device__ __forceinline__ typename Op::T scan_tile(const Op &op, uint32_t n, uint64_t base, typename Op::T prefix) {
+  using T = typename Op::T;
+  T item[kScanItems];
+  T acc = Op::identity();
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) {
+    uint64_t i = base + (uint64_t)threadIdx.x * kScanItems + k;
+    item[k] = i < n ? op.load((uint32_t)i) : Op::identity();
+    acc = Op::combine(acc, item[k]);
+  }
+  T total;
+  T excl = block_exclusive_scan<Op>(acc, &total);
+  T run = Op::combine(prefix, excl);
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) {
+    uint64_t i = base + (uint64_t)threadIdx.x * kScanItems + k;
+    T incl = Op::combine(run, item[k]);
+    if (i < n) op.store((uint32_t)i, run, incl);
+    run = incl;
+  }
+  return Op::combine(prefix, total);
+}
+
+template <class Op>
+__global__ __launch_bounds__(kScanThreads) void scan_single(Op op) {
+  const uint32_t n = op.count();  // at most kScanTile
+  typename Op::T total = scan_tile<Op>(op, n, 0, Op::identity());
+  if (threadIdx.x == 0) op.finish(total);
+}
 
 template <class Op>
 __global__ __launch_bounds__(kScanThreads) void scan_reduce(Op op, typename Op::T *__restrict__ agg) {
@@ -136,38 +173,52 @@ __global__ __launch_bounds__(kScanThreads) void scan_carry(Op op, typename Op::T
 
 template <class Op>
 __global__ __launch_bounds__(kScanThreads) void scan_apply(Op op, const typename Op::T *__restrict__ agg) {
-  using T = typename Op::T;
   const uint32_t n = op.count();
   const uint64_t base = (uint64_t)blockIdx.x * kScanTile;
   if (base >= n) return;
-  T item[kScanItems];
-  T acc = Op::identity();
-#pragma unroll
-  for (int k = 0; k < kScanItems; ++k) {
-    uint64_t i = base + (uint64_t)threadIdx.x * kScanItems + k;
-    item[k] = i < n ? op.load((uint32_t)i) : Op::identity();
-    acc = Op::combine(acc, item[k]);
-  }
-  T total;
-  T excl = block_exclusive_scan<Op>(acc, &total);
-  T run = Op::combine(agg[blockIdx.x], excl);
-#pragma unroll
-  for (int k = 0; k < kScanItems; ++k) {
-    uint64_t i = base + (uint64_t)threadIdx.x * kScanItems + k;
-    T incl = Op::combine(run, item[k]);
-    if (i < n) op.store((uint32_t)i, run, incl);
-    run = incl;
-  }
+  scan_tile<Op>(op, n, base, agg[blockIdx.x]);
 }
 
-// Enqueue the three passes.  max_n bounds op.count() and sizes the grids;
+// agg[] holds the tiles' totals (scan_reduce); at most kSelfCarryTiles tiles.
+template <class Op>
+__global__ __launch_bounds__(kScanThreads) void scan_apply_self(Op op, const typename Op::T *__restrict__ agg) {
+  using T = typename Op::T;
+  const uint32_t n = op.count();
+  const uint64_t base = (uint64_t)blockIdx.x * kScanTile;
+  if (n == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) op.finish(Op::identity());
+    return;
+  }
+  if (base >= n) return;
+  // totals of the tiles before this one, in order: thread t takes entries 2t and 2t + 1
+  static_assert(kSelfCarryTiles <= 2 * kScanThreads, "two entries per thread must cover every earlier tile");
+  T mine = Op::identity();
+#pragma unroll
+  for (uint32_t k = 0; k < 2; ++k) {
+    const uint32_t t = 2 * threadIdx.x + k;
+    if (t < blockIdx.x) mine = Op::combine(mine, agg[t]);
+  }
+  T prefix;
+  block_exclusive_scan<Op>(mine, &prefix);
+  const T total = scan_tile<Op>(op, n, base, prefix);
+  if (threadIdx.x == 0 && base + kScanTile >= n) op.finish(total);  // the tile that holds the last element
+}
+
+// Enqueue the passes.  max_n bounds op.count() and sizes the grids;
 // agg needs div_up(max_n, kScanTile) entries (at least one).
 template <class Op>
 int32_t run_scan(hipStream_t stream, const Op &op, uint32_t max_n, typename Op::T *agg) {
   uint32_t tiles = div_up(max_n, kScanTile);
-  if (tiles) scan_reduce<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
-  scan_carry<Op><<<1, kScanThreads, 0, stream>>>(op, agg);
-  if (tiles) scan_apply<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
+  if (tiles <= 1) {
+    scan_single<Op><<<1, kScanThreads, 0, stream>>>(op);
+  } else if (tiles <= kSelfCarryTiles) {
+    scan_reduce<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
+    scan_apply_self<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
+  } else {
+    scan_reduce<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
+    scan_carry<Op><<<1, kScanThreads, 0, stream>>>(op, agg);
+    scan_apply<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
+  }
   return check_launch();
 }
 

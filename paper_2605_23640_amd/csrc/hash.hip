@@ -13,6 +13,7 @@
 // The same scan counts the tokens of the run so far (restart flag + length).
 #include "cp_device.h"
 #include "cp_internal.h"
+#include "cp_table_device.h"
 
 namespace cp {
 namespace {
@@ -29,6 +30,8 @@ struct HashOp {
   uint32_t *run_off;  // nullable
   uint64_t base;
   uint32_t N, R;
+  cp_table table;      // cp_hash_probe: the pool index, looked up under every token's hash right away
+  uint32_t *slot_out;  // nullable: no lookup
 
   static __device__ __forceinline__ T identity() { return T{1ull, 0ull, 0u, 0u}; }
   static __device__ __forceinline__ T combine(T f, T g) {
@@ -46,6 +49,7 @@ struct HashOp {
     const bool sensitive = mask[i] != 0;
     out[i] = sensitive ? CP_HASH_NONE : h;
     if (run_off) run_off[i] = sensitive ? 0xFFFFFFFFu : incl.len - 1;
+    if (slot_out) slot_out[i] = lane_lookup(table, sensitive ? CP_HASH_NONE : h);
   }
   __device__ __forceinline__ void finish(T) const {}
 };
@@ -199,7 +203,7 @@ struct InsertKeyOp {
 
 static int32_t hash_common(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
                            uint32_t R, uint64_t base, uint64_t *hash_out, uint32_t *run_off_out, void *scratch,
-                           size_t scratch_bytes) {
+                           size_t scratch_bytes, cp_table table = cp_table{}, uint32_t *slot_out = nullptr) {
   using namespace cp;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
@@ -210,7 +214,7 @@ static int32_t hash_common(void *stream, const uint32_t *tok, const uint8_t *mas
   Scratch sc(scratch, scratch_bytes);
   HashOp::T *agg = sc.take<HashOp::T>(div_up(N, kScanTile) + 1);
   if (!agg) return CP_ERR_SCRATCH;
-  HashOp op{tok, mask, off, hash_out, run_off_out, base, N, R};
+  HashOp op{tok, mask, off, hash_out, run_off_out, base, N, R, table, slot_out};
   return run_scan<HashOp>((hipStream_t)stream, op, N, agg);
 }
 
@@ -225,6 +229,17 @@ extern "C" int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t
                                 void *scratch, size_t scratch_bytes) {
   if (N && !run_off_out) return CP_ERR_INVALID_ARG;
   return hash_common(stream, tok, mask, off, N, R, base, hash_out, run_off_out, scratch, scratch_bytes);
+}
+
+extern "C" int32_t cp_hash_probe(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
+                                 uint32_t R, uint64_t base, cp_table table, uint64_t *hash_out, uint32_t *run_off_out,
+                                 uint32_t *slot_out, void *scratch, size_t scratch_bytes) {
+  if (N == 0) return CP_OK;
+  if (!table.keys || !table.vals || table.capacity == 0 || table.capacity % CP_TABLE_BUCKET ||
+      !cp::aligned(table.keys, 128) || !cp::aligned(table.vals, 64) || !slot_out)
+    return CP_ERR_INVALID_ARG;
+  if (table.capacity >= 0x100000000ull) return CP_ERR_UNSUPPORTED;
+  return hash_common(stream, tok, mask, off, N, R, base, hash_out, run_off_out, scratch, scratch_bytes, table, slot_out);
 }
 
 extern "C" int32_t cp_hash_floating(void *stream_, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,

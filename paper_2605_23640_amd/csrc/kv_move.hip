@@ -86,6 +86,7 @@ constexpr uint32_t kMaxHalfDim = 256;    // head_dim <= 512 when rotating
 constexpr uint32_t kMaxFanout = 16;      // destinations served per pass over the source rows
 constexpr uint32_t kTrigDoubles = 1024;  // LDS doubles for cos (and as many for sin) per descriptor: fan-out * head_dim/2 <= this
 constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kShareReadsFrom = 4096;  // destination tokens from which a gather shares reads by default
 
 // cos/sin of (delta * inv_freq[j]) for any 32-bit delta come from five small
 // tables, one per 7-bit digit of |delta|: entry [level][m][j] holds cos and sin of
@@ -277,14 +278,17 @@ __global__ __launch_bounds__(256) void gather_expand_kernel(
     const uint32_t *__restrict__ span_src, const uint32_t *__restrict__ span_dst,
     const uint32_t *__restrict__ span_off, const int32_t *__restrict__ span_delta, const uint32_t *__restrict__ n_spans,
     uint32_t max_spans, uint32_t n_pool_slots, uint32_t n_dst_tokens, MoveItem *__restrict__ items,
-    uint32_t *__restrict__ head /* nullable: no grouping */, uint32_t *__restrict__ n_items,
+    uint32_t *__restrict__ head /* nullable: no grouping */, uint32_t *__restrict__ counters,
     uint32_t *__restrict__ status_flags) {
   uint32_t n = *n_spans;
   if (n > max_spans) n = max_spans;
   uint32_t total = span_off[n];
   if (total > n_dst_tokens) total = n_dst_tokens;  // spans that do not overlap cannot cover more
   const uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
-  if (w == 0) *n_items = total;
+  if (w == 0) {
+    counters[1] = total;            // item count
+    if (!head) counters[0] = 0;     // work counter of the mover (with grouping, gather_init_kernel has cleared it)
+  }
   if (w >= total) return;
   uint32_t lo = 0, hi = n;  // invariant: span_off[lo] <= w < span_off[hi]
   while (hi - lo > 1) {
@@ -675,6 +679,8 @@ int32_t gather_impl(hipStream_t stream, const void *pool, const cp_kv_layout &po
   }
   MoveOpts mo;
   if (!resolve_opts(opts, use_rope, &mo)) return CP_ERR_INVALID_ARG;
+  // a small batch is bound by its launches, not by its bytes: grouping (two more launches) is left out
+  if ((!opts || opts->read_sharing == 0) && n_dst_tokens < kShareReadsFrom) mo.share_reads = false;
   if (work_bytes < scratch_bytes_for(n_dst_tokens, max_spans, n_pool_slots)) return CP_ERR_SCRATCH;
   Scratch sc(work, work_bytes);
   uint32_t *agg = sc.take<uint32_t>(div_up(max_spans, kScanTile) + 1);
@@ -696,12 +702,11 @@ int32_t gather_impl(hipStream_t stream, const void *pool, const cp_kv_layout &po
     if (int32_t rc = launch_span_offsets(stream, span_len, n_spans, max_spans, offs, agg)) return rc;
     span_off = offs;
   }
-  gather_init_kernel<<<group ? div_up(n_pool_slots, 256) : 1, 256, 0, stream>>>(head, group ? n_pool_slots : 0,
-                                                                                counters);
+  if (group) gather_init_kernel<<<div_up(n_pool_slots, 256), 256, 0, stream>>>(head, n_pool_slots, counters);
   // spans do not overlap in dst, so they cover at most n_dst_tokens tokens
   gather_expand_kernel<<<div_up(n_dst_tokens, 256), 256, 0, stream>>>(
       span_src, span_dst, span_off, use_rope ? span_delta : nullptr, n_spans, max_spans, n_pool_slots, n_dst_tokens,
-      items, head, counters + 1, status_flags);
+      items, head, counters, status_flags);
   if (group)
     gather_heads_kernel<<<div_up(n_dst_tokens, 256), 256, 0, stream>>>(items, counters + 1, n_dst_tokens, head, units,
                                                                        counters + 2);

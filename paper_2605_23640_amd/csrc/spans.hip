@@ -3,10 +3,11 @@
 //
 // Token i opens a span ("head") when its slot is valid and it does not continue
 // its left neighbour (same request, neighbour's slot + 1, same position delta).
-// An ordered scan carries (number of heads so far, index of the latest head):
-// the head count gives every span its output index, so spans come out in
-// (request, position) order, and the latest-head index lets the last token of
-// a span write the span's length.
+// An ordered scan carries (number of heads so far, index of the latest head,
+// number of tokens with a slot so far): the head count gives every span its
+// output index, so spans come out in (request, position) order, the latest-head
+// index lets the last token of a span write the span's length, and the token
+// count before a head is the number of tokens the earlier spans cover (span_off).
 #include "cp_device.h"
 #include "cp_internal.h"
 
@@ -14,7 +15,7 @@ namespace cp {
 namespace {
 
 struct SpanOp {
-  struct T { uint32_t heads, last; };  // last = 1 + index of the latest head, 0 if none
+  struct T { uint32_t heads, last, covered; };  // last = 1 + index of the latest head, 0 if none; covered = tokens in spans
   const uint32_t *slot;
   const uint32_t *off;
   const int32_t *slot_pos;  // nullable
@@ -23,8 +24,10 @@ struct SpanOp {
   uint32_t *n_spans, *status_flags;
   uint32_t N, R, max_spans;
 
-  static __device__ __forceinline__ T identity() { return T{0u, 0u}; }
-  static __device__ __forceinline__ T combine(T a, T b) { return T{a.heads + b.heads, b.last ? b.last : a.last}; }
+  static __device__ __forceinline__ T identity() { return T{0u, 0u, 0u}; }
+  static __device__ __forceinline__ T combine(T a, T b) {
+    return T{a.heads + b.heads, b.last ? b.last : a.last, a.covered + b.covered};
+  }
   __device__ __forceinline__ uint32_t count() const { return N; }
 
   // Does token i (valid slot s, i > 0) continue the span of token i - 1?
@@ -41,11 +44,16 @@ struct SpanOp {
     if (s == CP_SLOT_NONE) return false;
     return i == 0 || !continues(i, s);
   }
-  __device__ __forceinline__ T load(uint32_t i) const { return is_head(i) ? T{1u, i + 1} : T{0u, 0u}; }
-  __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
+  __device__ __forceinline__ T load(uint32_t i) const {
+    if (slot[i] == CP_SLOT_NONE) return T{0u, 0u, 0u};
+    return is_head(i) ? T{1u, i + 1, 1u} : T{0u, 0u, 1u};
+  }
+  __device__ __forceinline__ void store(uint32_t i, T excl, T incl) const {
     uint32_t s = slot[i];
     if (s == CP_SLOT_NONE) return;
     uint32_t k = incl.heads - 1, head = incl.last - 1;  // a valid token always lies in a span
+    // tokens that the spans before span k cover; for the first span that is dropped: what the kept ones cover
+    if (span_off && head == i && k <= max_spans) span_off[k] = excl.covered;
     if (k >= max_spans) return;
     if (head == i) {
       span_src[k] = s;
@@ -65,6 +73,7 @@ struct SpanOp {
   __device__ __forceinline__ void finish(T total) const {
     *n_spans = total.heads < max_spans ? total.heads : max_spans;
     if (total.heads > max_spans) atomicOr(status_flags, CP_FLAG_SPANS_OVERFLOW);
+    else if (span_off) span_off[total.heads] = total.covered;  // (on overflow the first dropped span wrote it)
   }
 };
 
@@ -112,7 +121,5 @@ extern "C" int32_t cp_build_spans(void *stream_, const uint32_t *slot, const uin
   SpanOp::T *agg = sc.take<SpanOp::T>(tiles);
   if (!agg) return CP_ERR_SCRATCH;
   SpanOp op{slot, off, slot_pos, span_src, span_dst, span_len, span_off, span_delta, n_spans, status_flags, N, R, max_spans};
-  if (int32_t rc = run_scan<SpanOp>(stream, op, N, agg)) return rc;
-  if (span_off) return launch_span_offsets(stream, span_len, n_spans, max_spans, span_off, (uint32_t *)agg);
-  return CP_OK;
+  return run_scan<SpanOp>(stream, op, N, agg);
 }

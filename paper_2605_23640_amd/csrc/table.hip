@@ -16,22 +16,12 @@
 // kPending | i naming the lowest packed token index i that wants the entry.
 #include "cp_device.h"
 #include "cp_internal.h"
+#include "cp_table_device.h"
 
 namespace cp {
 namespace {
 
-constexpr uint32_t kBucket = CP_TABLE_BUCKET;
-constexpr uint32_t kPending = 0x80000000u;
 constexpr int kProbeThreads = 256;
-
-__device__ __forceinline__ uint32_t home_bucket(uint64_t h, uint32_t n_buckets) {
-  h ^= h >> 32;
-  h *= 0xD6E8FEB86659FD93ull;
-  h ^= h >> 32;
-  h *= 0xD6E8FEB86659FD93ull;
-  h ^= h >> 32;
-  return __umulhi((uint32_t)h, n_buckets);  // uniform over [0, n_buckets) for any n_buckets
-}
 
 // 16-bit slice of a wavefront ballot belonging to this lane's group of 16.
 __device__ __forceinline__ uint32_t group_bits(unsigned long long ballot) {
@@ -342,11 +332,33 @@ __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__re
                                                             uint32_t n_pool_slots, const uint32_t *__restrict__ off,
                                                             uint32_t R, uint32_t N, int32_t *__restrict__ slot_pos,
                                                             MoveItem *__restrict__ items,
-                                                            uint32_t *__restrict__ move_counter, ChainRecord chain) {
+                                                            uint32_t *__restrict__ move_counter, ChainRecord chain,
+                                                            const uint32_t *__restrict__ found,
+                                                            uint32_t *__restrict__ resolve_to) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) *move_counter = 0;  // work counter of the scatter that follows
   if (i >= N) return;
   uint32_t e = entry_of[i];
+  if (resolve_to) {
+    // Insert without chain records: step 3 (every token learns the slot that holds its key) is done here too.
+    // An owner may replace its marker while another token reads the entry; the reader then sees either the
+    // marker, and works the slot out from the owner's rank, or the slot the owner wrote: the same value.
+    uint32_t s = CP_SLOT_NONE;
+    if (found && found[i] != CP_SLOT_NONE) {
+      s = found[i];
+    } else if (e != CP_SLOT_NONE) {
+      const uint32_t v = __hip_atomic_load(&vals[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (v < kPending) {
+        s = v;
+      } else if (v != CP_SLOT_NONE) {
+        const uint32_t owner = v & ~kPending;
+        const uint32_t r = owner < N ? rank[owner] : n_free;
+        if (r < n_free) s = free_slots[r];
+        if (s >= n_pool_slots) s = CP_SLOT_NONE;
+      }
+    }
+    resolve_to[i] = s;
+  }
   if (e == CP_SLOT_NONE || vals[e] != (kPending | i)) return;  // only the owner touches its entry
   uint32_t r = rank[i], s = CP_SLOT_NONE;
   if (r < n_free) {
@@ -484,11 +496,15 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
   OwnerRankOp op{entry_of, table.vals, rank, n_inserted, status_flags, N, n_free};
   if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, agg)) return rc;
   if (N == 0) return CP_OK;
-  insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, N,
-                                                    found, cand, owner);
+  // with chain records the commit step needs every token's slot first (a stored token's parent is its left
+  // neighbour's slot); without them the two steps are one kernel
+  if (chain)
+    insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots,
+                                                      N, found, cand, owner);
   ChainRecord rec{tok, run_off, cand, slot_tok, slot_parent, owner};
   insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, off, R,
-                                                   N, slot_pos, items, counter, chain ? rec : ChainRecord{});
+                                                   N, slot_pos, items, counter, chain ? rec : ChainRecord{}, found,
+                                                   chain ? nullptr : cand);
   if (int32_t rc = check_launch()) return rc;
   if (chain) {
     // confirm every token's slot against the recorded chains (new slots are consistent by construction,

@@ -4,7 +4,8 @@ sequences of the two paths through libcacheprune.
     lookup :  cp_hash_segments -> cp_probe -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_segments -> cp_insert_kv
 
-and, for a pool with floating anchors (window W),
+(the first two steps of the lookup are issued as one call, cp_hash_probe) and, for a pool with floating anchors
+(window W),
 
     lookup :  cp_hash_runs -> cp_hash_floating -> cp_probe3 -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_runs -> cp_insert_kv -> cp_insert_anchors
@@ -177,10 +178,12 @@ class KVPool:
         the candidate streams found (the merged result is stamped by the caller)."""
         lru = touch and self.slot_stamp is not None
         if self.slot_anchor is None and not self.verify:
-            B.cp_hash_segments(tok, mask, off, buf.hash, buf.scratch, stream=stream)
-            B.cp_probe(self.table, buf.hash, buf.slot, stream=stream)
+            B.cp_hash_probe(tok, mask, off, self.table, buf.hash, None, buf.slot, buf.scratch, stream=stream)
             return [(None, buf.slot)]
-        B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
+        if self.verify:  # the run-start stream's candidates come with the hashes
+            B.cp_hash_probe(tok, mask, off, self.table, buf.hash, buf.run_off, buf.cand, buf.scratch, stream=stream)
+        else:
+            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
         keys = [(buf.hash, buf.run_off)]
         if self.slot_anchor is not None:
             B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off, self.anchor_window,
@@ -189,7 +192,8 @@ class KVPool:
             keys += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
         if self.verify:
             for k, (key, seg_off) in enumerate(keys):
-                B.cp_probe(self.table, key, buf.cand, stream=stream)
+                if k > 0:
+                    B.cp_probe(self.table, key, buf.cand, stream=stream)
                 B.cp_verify_chain(tok, seg_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, k > 0,
                                   buf.slot, buf.scratch, stream=stream,
                                   stream_out=buf.stream_slot[k] if per_stream else None)

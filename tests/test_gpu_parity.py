@@ -293,3 +293,29 @@ def test_explicit_stream_and_two_pools_side_by_side(G):
         assert np.array_equal(G.host_u32(buf.served if st.pool.filters else buf.slot), want.served)
         assert np.array_equal(G.dst_as_rows(dst, sh, N), G.dst_as_rows(want.dst, sh, N))
         assert int(st.pool.flags.item()) == 0
+
+
+def test_hash_and_probe_in_one_pass_equal_the_two_calls(G):
+    """cp_hash_probe against cp_hash_segments / cp_hash_runs followed by cp_probe, on a table at load 0.85
+    (walks over several buckets) and on batches of one tile, several tiles and more than 512 tiles."""
+    import paper_2605_23640_amd as cp
+
+    wl = gen.make_frag(scale=1 / 32, shape=gen.KVShape(2, 2, 64))
+    st = G.prefill(wl)
+    rng = np.random.default_rng(5)
+    for n_rep in (1, 3, 140):  # 4096 tokens per copy of the batch
+        tok = np.tile(wl.tok, n_rep)[: 4096 * n_rep if n_rep > 1 else 700]
+        mask = np.tile(wl.mask, n_rep)[: len(tok)]
+        off = np.unique(np.concatenate([[0, len(tok)], rng.integers(0, len(tok), 7)])).astype(np.uint32)
+        d_tok, d_mask, d_off = G.dev_i32(tok), torch.from_numpy(mask.copy()).to(G.DEV), G.dev_i32(off)
+        N = len(tok)
+        scratch = cp.binding.new_scratch(N, 0, G.DEV)
+        h1, h2 = (torch.empty(N, dtype=torch.int64, device=G.DEV) for _ in range(2))
+        r1, r2, s1, s2 = (torch.empty(N, dtype=torch.int32, device=G.DEV) for _ in range(4))
+        cp.cp_hash_runs(d_tok, d_mask, d_off, h1, r1, scratch)
+        cp.cp_probe(st.pool.table, h1, s1)
+        cp.cp_hash_probe(d_tok, d_mask, d_off, st.pool.table, h2, r2, s2, scratch)
+        torch.cuda.synchronize()
+        assert torch.equal(h1, h2) and torch.equal(r1, r2) and torch.equal(s1, s2), N
+        assert np.array_equal(G.host_u64(h1), O.hash_segments(tok, mask, off))
+        assert (G.host_u32(s1) != NONE).mean() > 0.3
