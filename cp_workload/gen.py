@@ -377,20 +377,28 @@ def make_frag(seed=0xC0FFEE03, scale=1.0, shape=KVShape(32, 8, 128), load=0.85, 
 def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=500000.0, max_shift=512):
     """Every reusable piece (system prefix, documents) sits in the donors at a
     nominal position and in each request at that position plus a shift drawn
-    uniformly from [-max_shift, max_shift].  Fillers between pieces are the
-    user's own text and end in a sensitive token, so each piece starts a run in
-    donor and request alike."""
+    uniformly from [-(max_shift - 64), max_shift - 64].  Inside a document the
+    sensitive runs are private text whose length differs from one copy to the
+    next (a name, a number: 0 to 8 extra tokens per run in every copy, donor
+    and request alike), so every reused span of a document sits at a position
+    delta of its own: the piece's shift plus the difference of the extra
+    tokens before it, over a thousand spans with several hundred different
+    (request, delta) pairs per batch, nearly all within [-max_shift, max_shift].  Fillers between pieces
+    are the user's own text and end in a sensitive token, so each piece starts
+    a run in donor and request alike."""
     rng = np.random.default_rng(seed)
     s = scale
     ms = max(2, round(max_shift * s))
+    piece_shift = max(1, ms - max(1, round(64 * s)))  # range of a piece's shift; the rest is for the spans' own drift
+    extra_max, extra_budget = max(1, round(8 * s)), max(2, round(192 * s))
     prefix_len = max(8, round(1024 * s))
-    doc_len = (max(4, round(512 * s)), max(8, round(1024 * s)))
+    doc_len = (max(4, round(448 * s)), max(8, round(832 * s)))
     n_docs, k_docs = max(6, round(64 * s)), 3
     pool_slots = max(256, round(262144 * s))
     run_mean, cover = 8.0, 0.25
-    spacing = doc_len[1] + 2 * ms
+    spacing = doc_len[1] + extra_budget + 2 * ms
     nominal = [ms] + [2 * ms + prefix_len + ms + k * spacing for k in range(k_docs)]  # piece 0 = the prefix
-    # 8 * 512 + 1024 + 3 * 1024 = 8192 at full scale
+    # 8 * 512 + 1024 + 3 * (832 + 192) = 8192 at full scale
     R, T = max(2, round(16 * s)), max(round(8192 * s), nominal[-1] + ms + doc_len[1])
     prefix = _tokens(rng, prefix_len)
     docs, dmasks, group = [], [], []
@@ -399,6 +407,24 @@ def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=50000
         docs.append(_tokens(rng, ln))
         dmasks.append(_mask_process(rng, ln, run_mean, cover))
         group.append(d % k_docs)  # a document is always used in the same place of the prompt
+
+    def stretch(t, m):
+        """A copy of a document whose sensitive runs are up to extra_max tokens longer each (other private
+        text of other length), at most extra_budget tokens in all."""
+        pt, pm, left, i, n = [], [], extra_budget, 0, len(t)
+        while i < n:
+            j = i
+            while j < n and m[j] == m[i]:
+                j += 1
+            pt.append(t[i:j])
+            pm.append(m[i:j])
+            if m[i] == 1 and left > 0:
+                x = min(left, int(rng.integers(0, extra_max + 1)))
+                pt.append(_tokens(rng, x))
+                pm.append(np.ones(x, np.uint8))
+                left -= x
+            i = j
+        return np.concatenate(pt), np.concatenate(pm)
 
     def filler(n, strict):
         """n tokens of private text ending in a sensitive token (n may be 0).  ``strict``: all of it is
@@ -425,16 +451,16 @@ def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=50000
 
     zeros = np.zeros(prefix_len, np.uint8)
     d_tok, d_mask = [], []
-    for d in range(n_docs):  # donor d: prefix and document d at their nominal places
-        t, m = compose([(prefix, zeros), (docs[d], dmasks[d])], [nominal[0], nominal[1 + group[d]]], None)
+    for d in range(n_docs):  # donor d: prefix and (a copy of) document d at their nominal places
+        t, m = compose([(prefix, zeros), stretch(docs[d], dmasks[d])], [nominal[0], nominal[1 + group[d]]], None)
         d_tok.append(t)
         d_mask.append(m)
     r_tok, r_mask, shifts = [], [], []
     by_group = [[d for d in range(n_docs) if group[d] == g] for g in range(k_docs)]
     for _ in range(R):
-        sh = rng.integers(-ms, ms + 1, size=1 + k_docs)
+        sh = rng.integers(-piece_shift, piece_shift + 1, size=1 + k_docs)
         chosen = [int(rng.choice(by_group[g])) for g in range(k_docs)]
-        pieces = [(prefix, zeros)] + [(docs[d], dmasks[d]) for d in chosen]
+        pieces = [(prefix, zeros)] + [stretch(docs[d], dmasks[d]) for d in chosen]
         starts = [nominal[k] + int(sh[k]) for k in range(1 + k_docs)]
         t, m = compose(pieces, starts, T)
         r_tok.append(t[:T])

@@ -55,7 +55,7 @@ extern "C" {
 
 #define CP_FLAG_SPANS_OVERFLOW 1u /* more than max_spans spans: only the first max_spans kept  */
 #define CP_FLAG_POOL_FULL 2u      /* free list used up: later new tokens were not stored       */
-#define CP_FLAG_TABLE_FULL 4u     /* no free table entry: affected tokens were not stored      */
+#define CP_FLAG_TABLE_FULL 4u     /* the table cannot take the batch's new keys: none was stored */
 #define CP_FLAG_BAD_INDEX 8u      /* a span / free-list entry points outside pool or buffer: skipped */
 
 #define CP_TABLE_BUCKET 16u /* table entries per bucket; capacity is a multiple of it */
@@ -316,9 +316,13 @@ int32_t cp_gather_kv_static(void *stream, const void *pool, cp_kv_layout pool_l,
  * free_slots[0], free_slots[1], .. in packed order of the storing tokens — the
  * result does not depend on scheduling.  When the n_free slots are used up the
  * remaining new tokens are dropped and CP_FLAG_POOL_FULL is set.  Free-list
- * entries >= n_pool_slots are never used (CP_FLAG_BAD_INDEX).  If the table has
- * no free entry left CP_FLAG_TABLE_FULL is set and which of the affected tokens
- * were dropped is unspecified: size the table for the keys it must hold.
+ * entries >= n_pool_slots are never used (CP_FLAG_BAD_INDEX).  A key takes a
+ * table entry when an insert first sees it and keeps it, also without a slot
+ * (pool full, evicted), until the table is rebuilt (cp_table_compact).  If the
+ * table cannot take every new key of the call, CP_FLAG_TABLE_FULL is set and the
+ * call stores nothing (slot_out still reports the keys that were stored before;
+ * *n_inserted = 0); which of the new keys took the last entries is unspecified,
+ * so rebuild the table into a larger one before storing again.
  *   slot_out [N]: slot holding each token's key after the call, CP_SLOT_NONE
  *                 for sensitive or dropped tokens.
  *   *n_inserted (device): number of tokens stored by this call.

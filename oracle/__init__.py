@@ -19,6 +19,7 @@ HASH_NONE = 0xFFFFFFFFFFFFFFFF
 SLOT_NONE = 0xFFFFFFFF
 FLAG_SPANS_OVERFLOW = 1
 FLAG_POOL_FULL = 2
+FLAG_TABLE_FULL = 4
 BASE = 0x100000001B3
 
 
@@ -68,6 +69,10 @@ def lib():
         L.cpo_index_free.argtypes = [vp]
         L.cpo_index_size.restype = u64
         L.cpo_index_size.argtypes = [vp]
+        L.cpo_index_rebuild.restype = None
+        L.cpo_index_rebuild.argtypes = [vp, u64]
+        L.cpo_index_entries.restype = u64
+        L.cpo_index_entries.argtypes = [vp]
         L.cpo_hash_segments.argtypes = [vp, vp, vp, u32, u64, vp]
         L.cpo_probe.argtypes = [vp, vp, u32, vp]
         L.cpo_build_spans.restype = u32
@@ -135,6 +140,15 @@ class Index:
 
     def __len__(self):
         return int(lib().cpo_index_size(self._h))
+
+    def rebuild(self, capacity):
+        """From now on a table of ``capacity`` entries that holds the keys with a slot (0 = unbounded)."""
+        lib().cpo_index_rebuild(self._h, int(capacity))
+
+    @property
+    def entries(self):
+        """Keys that hold a table entry (with or without a slot) since the last rebuild."""
+        return int(lib().cpo_index_entries(self._h))
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

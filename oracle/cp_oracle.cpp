@@ -15,11 +15,23 @@
 
 struct cpo_index {
   std::unordered_map<uint64_t, uint32_t> map;
+  // Bookkeeping for a table of bounded size (capacity 0 = unbounded): the keys that hold a table entry.
+  // A key takes an entry when it is first seen by an insert and keeps it while its token is stored, after
+  // its token was dropped for lack of a pool slot, and after its slot was evicted; only rebuilding the
+  // table (cpo_index_rebuild) gives the entries of keys without a slot back.
+  std::unordered_set<uint64_t> entries;
+  uint64_t capacity = 0;
 };
 
 extern "C" cpo_index *cpo_index_new(void) { return new cpo_index(); }
 extern "C" void cpo_index_free(cpo_index *ix) { delete ix; }
 extern "C" uint64_t cpo_index_size(const cpo_index *ix) { return ix->map.size(); }
+extern "C" void cpo_index_rebuild(cpo_index *ix, uint64_t capacity) {
+  ix->capacity = capacity;
+  ix->entries.clear();
+  for (const auto &kv : ix->map) ix->entries.insert(kv.first);
+}
+extern "C" uint64_t cpo_index_entries(const cpo_index *ix) { return ix->entries.size(); }
 
 // Sec. 4.2.1: sensitive tokens are separators; Sec. 4.2.2: polynomial rolling
 // hash.  Horner form of  sum (t_m + 1) * base^(k-m)  with unsigned wrap-around
@@ -197,6 +209,17 @@ static uint32_t insert_tokens(cpo_index *ix, const uint64_t *hash, const uint32_
                               cpo_layout pool_l, int32_t *slot_pos, uint32_t *slot_out, uint32_t *flags,
                               const uint32_t *tok, uint32_t *slot_tok) {
   const size_t row_bytes = (size_t)pool_l.n_kv_heads * pool_l.head_dim * 2;
+  // A table of bounded size: if it cannot take every key that the batch brings and it does not hold yet,
+  // the batch stores nothing (keys already stored are still reported).
+  bool table_full = false;
+  if (ix->capacity) {
+    std::unordered_set<uint64_t> fresh;
+    for (uint32_t i = 0; i < off[R]; ++i)
+      if (hash[i] != CPO_HASH_NONE && !(found && found[i] != CPO_SLOT_NONE) && !ix->entries.count(hash[i]))
+        fresh.insert(hash[i]);
+    table_full = ix->entries.size() + fresh.size() > ix->capacity;
+    if (table_full && flags) *flags |= CPO_FLAG_TABLE_FULL;
+  }
   uint32_t n_new = 0;
   for (uint32_t r = 0; r < R; ++r) {
     for (uint32_t i = off[r]; i < off[r + 1]; ++i) {
@@ -211,6 +234,8 @@ static uint32_t insert_tokens(cpo_index *ix, const uint64_t *hash, const uint32_
         slot_out[i] = it->second;
         continue;
       }
+      if (table_full) continue;
+      ix->entries.insert(hash[i]);  // the key has its entry from now on, with or without a slot
       if (n_new == n_free) {
         if (flags) *flags |= CPO_FLAG_POOL_FULL;
         continue;

@@ -41,6 +41,7 @@ extern "C" {
 
 #define CPO_FLAG_SPANS_OVERFLOW 1u /* more spans than max_spans; extra dropped */
 #define CPO_FLAG_POOL_FULL 2u      /* free list exhausted; later tokens dropped */
+#define CPO_FLAG_TABLE_FULL 4u     /* a bounded table cannot take the batch's new keys: none stored */
 
 /* Byte address of the row of (token or slot t, layer l, kv in {0 = K, 1 = V}):
  *   base + t * tok_stride + l * layer_stride + kv * kv_stride
@@ -62,6 +63,12 @@ typedef struct cpo_index cpo_index;
 cpo_index *cpo_index_new(void);
 void cpo_index_free(cpo_index *);
 uint64_t cpo_index_size(const cpo_index *);
+/* The index as a table of `capacity` entries (0 = unbounded, the default): start a fresh table that
+ * holds the keys with a slot.  A key takes an entry when an insert first sees it and keeps it also
+ * while it has no slot (dropped for lack of pool slots, evicted) until the next rebuild.  An insert
+ * whose new keys do not all fit sets CPO_FLAG_TABLE_FULL and stores nothing. */
+void cpo_index_rebuild(cpo_index *, uint64_t capacity);
+uint64_t cpo_index_entries(const cpo_index *);
 
 /* Chain hash of every token.  R requests are packed back to back, request r
  * holds tokens off[r] .. off[r+1]-1.  For a sensitive token hash_out = NONE

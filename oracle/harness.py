@@ -53,7 +53,7 @@ class OracleState:
 
 
 def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None, verify=False,
-            recompute=None, dedup=False) -> OracleState:
+            recompute=None, dedup=False, bounded_table=False) -> OracleState:
     """Insert the donor prompts batch by batch.  ``src_provider(first_tok, n_tok)``
     returns the layer-major KV buffer of a donor batch (default: host generator,
     uid = packed donor index).  With ``anchor_window`` = W the hash of every
@@ -69,6 +69,8 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         slot_tok=np.full(wl.pool_slots, 0xFFFFFFFF, np.uint32),
         slot_uid=np.full(wl.pool_slots, kvgen.UID_NONE, np.uint64),
     )
+    if bounded_table:  # the index as a table of the workload's capacity (in whole buckets of 16 entries)
+        st.index.rebuild((int(wl.table_capacity) + 15) // 16 * 16)
     st.donor_hash = O.hash_segments(wl.donor_tok, wl.donor_mask, wl.donor_off)
     if anchor_window is not None:
         st.anchors, st.anchor_window = O.AnchorSet(), int(anchor_window)

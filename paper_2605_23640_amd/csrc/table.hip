@@ -247,31 +247,39 @@ __global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t,
   }
 }
 
-// Insert, step 2: ordered count of the storing tokens (the owners of new keys).
+// Insert, step 2: ordered count of the storing tokens (the owners of new keys).  The same scan learns
+// whether any token found no table entry: then the table cannot hold the batch's new keys, and the call
+// stores none of them (room = 0), so that what a call stores never depends on which keys happened to get
+// the last entries.
 struct OwnerRankOp {
-  using T = uint32_t;
+  struct T { uint32_t n, failed; };
+  const uint64_t *hash;
+  const uint32_t *found;  // nullable
   const uint32_t *entry_of;
   const uint32_t *vals;
   uint32_t *rank;      // [N]  rank of token i among the owners, valid for owners only
   uint32_t *n_inserted;
+  uint32_t *room;      // free-list entries this call may use: n_free, or 0 if the table overflowed
   uint32_t *status_flags;
   uint32_t N, n_free;
 
-  static __device__ __forceinline__ T identity() { return 0; }
-  static __device__ __forceinline__ T combine(T a, T b) { return a + b; }
+  static __device__ __forceinline__ T identity() { return T{0u, 0u}; }
+  static __device__ __forceinline__ T combine(T a, T b) { return T{a.n + b.n, a.failed | b.failed}; }
   __device__ __forceinline__ uint32_t count() const { return N; }
   __device__ __forceinline__ T load(uint32_t i) const {
-    uint32_t e = entry_of[i];
-    return (e != CP_SLOT_NONE && vals[e] == (kPending | i)) ? 1u : 0u;
+    const uint32_t e = entry_of[i];
+    if (e == CP_SLOT_NONE)  // no entry: not asked for (sensitive, found already) or the table is full
+      return T{0u, (hash[i] != CP_HASH_NONE && !(found && found[i] != CP_SLOT_NONE)) ? 1u : 0u};
+    return T{vals[e] == (kPending | i) ? 1u : 0u, 0u};
   }
   __device__ __forceinline__ void store(uint32_t i, T excl, T incl) const {
-    if (incl != excl) {
-      rank[i] = excl;
-    }
+    if (incl.n != excl.n) rank[i] = excl.n;
   }
   __device__ __forceinline__ void finish(T total) const {
-    *n_inserted = total < n_free ? total : n_free;
-    if (total > n_free) atomicOr(status_flags, CP_FLAG_POOL_FULL);
+    const uint32_t r = total.failed ? 0u : n_free;
+    *room = r;
+    *n_inserted = total.n < r ? total.n : r;
+    if (!total.failed && total.n > n_free) atomicOr(status_flags, CP_FLAG_POOL_FULL);
   }
 };
 
@@ -279,13 +287,15 @@ struct OwnerRankOp {
 __global__ __launch_bounds__(256) void insert_resolve_kernel(const uint32_t *__restrict__ entry_of,
                                                              const uint32_t *__restrict__ vals,
                                                              const uint32_t *__restrict__ rank,
-                                                             const uint32_t *__restrict__ free_slots, uint32_t n_free,
+                                                             const uint32_t *__restrict__ free_slots,
+                                                             const uint32_t *__restrict__ room,
                                                              uint32_t n_pool_slots, uint32_t N,
                                                              const uint32_t *__restrict__ found /* nullable */,
                                                              uint32_t *__restrict__ slot_out,
                                                              uint8_t *__restrict__ owner) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
+  const uint32_t n_free = *room;
   if (owner) owner[i] = 0;  // set again by the commit step for the tokens that store
   uint32_t e = entry_of[i], s = CP_SLOT_NONE;
   if (found && found[i] != CP_SLOT_NONE) {
@@ -328,7 +338,8 @@ __global__ __launch_bounds__(256) void insert_poison_kernel(const uint8_t *__res
 // the free list ran out) and record the position their token had in its request.
 __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__restrict__ entry_of, uint32_t *vals,
                                                             const uint32_t *__restrict__ rank,
-                                                            const uint32_t *__restrict__ free_slots, uint32_t n_free,
+                                                            const uint32_t *__restrict__ free_slots,
+                                                            const uint32_t *__restrict__ room,
                                                             uint32_t n_pool_slots, const uint32_t *__restrict__ off,
                                                             uint32_t R, uint32_t N, int32_t *__restrict__ slot_pos,
                                                             MoveItem *__restrict__ items,
@@ -338,6 +349,7 @@ __global__ __launch_bounds__(256) void insert_commit_kernel(const uint32_t *__re
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) *move_counter = 0;  // work counter of the scatter that follows
   if (i >= N) return;
+  const uint32_t n_free = *room;
   uint32_t e = entry_of[i];
   if (resolve_to) {
     // Insert without chain records: step 3 (every token learns the slot that holds its key) is done here too.
@@ -481,10 +493,10 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
   if (!resolve_opts(opts, false, &mo)) return CP_ERR_INVALID_ARG;
   if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
-  uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
+  uint32_t *agg = sc.take<uint32_t>(2 * (div_up(N, kScanTile) + 1));  // tile totals of the scans (8 bytes each at most)
   uint32_t *entry_of = sc.take<uint32_t>(N);
   uint32_t *rank = sc.take<uint32_t>(N);
-  uint32_t *counter = sc.take<uint32_t>(1);
+  uint32_t *counter = sc.take<uint32_t>(2);  // [0] the scatter's work counter, [1] free-list entries the call may use
   MoveItem *items = sc.take<MoveItem>(N);
   uint32_t *cand = chain ? sc.take<uint32_t>(N) : slot_out;  // slot every token's key resolves to
   uint8_t *owner = chain ? sc.take<uint8_t>(N) : nullptr;
@@ -493,18 +505,18 @@ static int32_t insert_common(void *stream_, cp_table table, const uint64_t *hash
   if (N)
     insert_claim_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(
         table, hash, found, N, entry_of, status_flags);
-  OwnerRankOp op{entry_of, table.vals, rank, n_inserted, status_flags, N, n_free};
-  if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, agg)) return rc;
+  OwnerRankOp op{hash, found, entry_of, table.vals, rank, n_inserted, counter + 1, status_flags, N, n_free};
+  if (int32_t rc = run_scan<OwnerRankOp>(stream, op, N, (OwnerRankOp::T *)agg)) return rc;
   if (N == 0) return CP_OK;
   // with chain records the commit step needs every token's slot first (a stored token's parent is its left
   // neighbour's slot); without them the two steps are one kernel
   if (chain)
-    insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots,
+    insert_resolve_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, counter + 1, n_pool_slots,
                                                       N, found, cand, owner);
   ChainRecord rec{tok, run_off, cand, slot_tok, slot_parent, owner};
-  insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, n_free, n_pool_slots, off, R,
-                                                   N, slot_pos, items, counter, chain ? rec : ChainRecord{}, found,
-                                                   chain ? nullptr : cand);
+  insert_commit_kernel<<<blocks, 256, 0, stream>>>(entry_of, table.vals, rank, free_slots, counter + 1, n_pool_slots,
+                                                   off, R, N, slot_pos, items, counter, chain ? rec : ChainRecord{},
+                                                   found, chain ? nullptr : cand);
   if (int32_t rc = check_launch()) return rc;
   if (chain) {
     // confirm every token's slot against the recorded chains (new slots are consistent by construction,

@@ -86,24 +86,52 @@ def test_full_size(G, name):
         rotated = served & (delta != 0)
         # V rows everywhere and K rows of unshifted tokens: exact generator bytes
         assert G.verify_rows(glk.dst, lay, uid, wl.seed, skip_k=rotated.astype(np.uint8)) == 0
-        # K rows of a seeded sample of shifted tokens against the oracle's rotation
+        # K rows against the oracle's rotation on a stratified sample: one token of every re-rotated span of
+        # every request (every position delta that occurs, several hundred (request, delta) pairs), at most 4000
+        # of them, in the first, the middle and the last layer, every head
         rng = np.random.default_rng(wl.seed)
-        idx = np.sort(rng.choice(np.flatnonzero(rotated), size=192, replace=False))
+        req_of = np.searchsorted(wl.off, np.arange(N), side="right") - 1
+        run_start = np.flatnonzero(rotated & ~np.concatenate([[False], rotated[:-1] & (delta[1:] == delta[:-1])
+                                                               & (req_of[1:] == req_of[:-1])]))
+        run_end = np.concatenate([run_start[1:], [N]])
+        picks = []
+        for a, b in zip(run_start, run_end):  # a stretch of one delta: tokens a .. (first token that differs)
+            e = a
+            while e < b and rotated[e] and delta[e] == delta[a] and req_of[e] == req_of[a]:
+                e += 1
+            picks.append(int(rng.integers(a, e)))
+        picks = np.array(picks)
+        if len(picks) > 4000:
+            picks = np.sort(rng.choice(picks, 4000, replace=False))
+        idx = picks
+        n_pairs = len({(int(req_of[i]), int(delta[i])) for i in idx})
+        layers = sorted({0, sh.n_layers // 2, sh.n_layers - 1})
         re = sh.row_bytes // 2
         view = glk.dst.view(torch.int16).view(sh.n_layers, 2, N, re)
-        got = view[:, 0, torch.from_numpy(idx).to(G.DEV), :].cpu().numpy().view(np.uint16)  # [L][sample][re]
-        src = kvgen.rows_for_tokens(wl.seed, uid[idx], sh.n_layers, re)[:, :, 0, :]  # [sample][L][re]
-        hist = np.zeros(3, np.int64)
+        t_idx = torch.from_numpy(idx).to(G.DEV)
+        got = np.stack([view[l, 0, t_idx, :].cpu().numpy().view(np.uint16) for l in layers])  # [layer][sample][re]
+        src = kvgen.rows_for_tokens(wl.seed, uid[idx], sh.n_layers, re)[:, layers, 0, :]  # [sample][layer][re]
         D = sh.head_dim
-        for s, i in enumerate(idx):
-            for l in range(sh.n_layers):
+        hist = np.zeros((len(layers), 3), np.int64)
+        by_size = {}  # |delta| bucket -> histogram
+        for s_, i in enumerate(idx):
+            for li in range(len(layers)):
                 for h in range(sh.n_kv_heads):
-                    want = O.rope_head(src[s, l, h * D:(h + 1) * D], int(delta[i]), wl.rope_theta, wl.rope_style)
-                    d = np.abs(bf16_ordinal(got[l, s, h * D:(h + 1) * D]) - bf16_ordinal(want))
-                    hist += np.bincount(np.minimum(d, 2), minlength=3)
-        print(f"[{name}] bf16 distance of {hist.sum()} sampled re-rotated key elements {{0,1,>1}}: {hist.tolist()}",
-              flush=True)
-        assert hist[2] == 0 and hist[1] <= 1e-3 * hist.sum()
+                    want = O.rope_head(src[s_, li, h * D:(h + 1) * D], int(delta[i]), wl.rope_theta, wl.rope_style)
+                    d = np.abs(bf16_ordinal(got[li, s_, h * D:(h + 1) * D]) - bf16_ordinal(want))
+                    b = np.bincount(np.minimum(d, 2), minlength=3)
+                    hist[li] += b
+                    key = min(int(abs(int(delta[i]))).bit_length(), 12)
+                    by_size[key] = by_size.get(key, 0) + b
+        print(f"[{name}] {len(idx)} sampled tokens, {n_pairs} (request, delta) pairs, requests {len(set(req_of[idx]))}, "
+              f"deltas {int(delta[idx].min())} .. {int(delta[idx].max())}", flush=True)
+        for li, l in enumerate(layers):
+            print(f"[{name}]   layer {l}: bf16 distance {{0,1,>1}} {hist[li].tolist()}", flush=True)
+        for k in sorted(by_size):
+            print(f"[{name}]   |delta| < 2^{k}: {by_size[k].tolist()}", flush=True)
+        assert len(idx) >= 1000 and n_pairs >= 500 and len(set(req_of[idx])) == wl.n_requests
+        assert hist[:, 2].sum() == 0  # every element within one bf16 step of the double-precision result
+        assert hist[:, 1].sum() <= 1e-3 * hist.sum()
     del gst, glk
     gc.collect()
     torch.cuda.empty_cache()

@@ -1,6 +1,8 @@
 """Parity of libcacheprune (HIP, through the C ABI) against the CPU oracle on the
 same seeded inputs: hashes, slots, spans, inserted slots and copied rows bit for
 bit; re-rotated keys within one bf16 step."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -8,6 +10,7 @@ import torch
 import oracle as O
 from cp_workload import gen, kvgen
 from oracle import harness as OH
+from tests.exact_rope import exact_rotation
 
 pytestmark = pytest.mark.gpu
 
@@ -319,3 +322,93 @@ def test_hash_and_probe_in_one_pass_equal_the_two_calls(G):
         assert torch.equal(h1, h2) and torch.equal(r1, r2) and torch.equal(s1, s2), N
         assert np.array_equal(G.host_u64(h1), O.hash_segments(tok, mask, off))
         assert (G.host_u32(s1) != NONE).mean() > 0.3
+
+
+def test_table_overflow_stores_nothing_and_a_rebuilt_table_goes_on(G):
+    """A batch whose new keys do not fit the table sets TABLE_FULL and stores nothing, whatever the order in which
+    its tokens reached the table; after the table has been rebuilt into a larger one the same batch is stored."""
+    import paper_2605_23640_amd as cp
+
+    rng = np.random.default_rng(12)
+    V = lambda n: rng.integers(0, 32000, n).astype(np.uint32)  # noqa: E731
+    a, b, c = V(70), V(90), V(30)
+    donors = [a, np.concatenate([a[:40], b]), c]  # 70 keys fit 96 entries; the second batch brings 90 more; the third 30
+    wl = gen.from_prompts("table-overflow", 0xC0FFEE41, gen.KVShape(2, 2, 64), donors, [np.concatenate([a, V(3), c])],
+                          pool_slots=512, donor_batch_tokens=100)
+    wl.table_capacity = 96
+    assert len(wl.donor_batches) == 3
+    fl = []
+    ost = OH.prefill(wl, flags_out=fl, bounded_table=True)
+    gst = G.prefill(wl)
+    assert gst.pool.table.capacity == 96
+    assert fl[0] == O.FLAG_TABLE_FULL and gst.flags == fl[0]
+    assert np.array_equal(gst.donor_slot, ost.donor_slot) and gst.n_inserted == [70, 0, 0] and ost.n_used == 70
+    o = wl.donor_off
+    assert (ost.donor_slot[o[1]:o[1] + 40] != NONE).all() and (ost.donor_slot[o[1] + 40:] == NONE).all()
+    assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0
+    # rebuild into a larger table and store the two batches again
+    pool = gst.pool
+    fresh = cp.binding.Table(512, G.DEV)
+    cp.cp_table_compact(pool.table, fresh, pool.flags)
+    pool.table = fresh
+    pool.flags.zero_()
+    ost.index.rebuild(512)
+    for d in (1, 2):
+        t0, t1 = int(o[d]), int(o[d + 1])
+        n = t1 - t0
+        tok, mask, off = wl.donor_tok[t0:t1], wl.donor_mask[t0:t1], np.array([0, n], np.uint32)
+        src = torch.empty(n * wl.shape.tok_bytes, dtype=torch.uint8, device=G.DEV)
+        kvgen.fill(G.stream_ptr(), C.c_void_p(src.data_ptr()), G.gen_layout(pool.request_layout(n)), n, wl.seed, uid_base=t0)
+        hbuf = torch.empty(n, dtype=torch.int64, device=G.DEV)
+        sout = torch.empty(n, dtype=torch.int32, device=G.DEV)
+        got_n = pool.insert(G.dev_i32(tok), torch.from_numpy(mask.copy()).to(G.DEV), G.dev_i32(off), src, hbuf, sout,
+                            cp.binding.new_scratch(n, 0, G.DEV))
+        so, n_new, f2 = O.insert_kv(ost.index, O.hash_segments(tok, mask, off), off, wl.free_slots[ost.n_used:],
+                                    OH.gen_buffer(wl.seed, wl.shape, t0, n), OH.buf_layout(wl.shape, n), ost.pool,
+                                    OH.pool_layout(wl.shape), ost.slot_pos)
+        ost.n_used += n_new
+        assert f2 == 0 and int(pool.flags.item()) == 0 and got_n == n_new == (90 if d == 1 else 30)
+        assert np.array_equal(G.host_u32(sout), so)
+    glk, olk = G.lookup(gst), OH.lookup(ost)
+    assert np.array_equal(glk.slot, olk.slot) and (glk.slot != NONE).sum() == 70  # (the request has c behind other text)
+
+
+def test_rope_deltas_up_to_the_whole_int32_range(G):
+    """Position deltas of any size: every digit level of the kernel's cos/sin tables, INT_MAX, INT_MIN + 1 and
+    INT_MIN (whose magnitude does not fit an int32), element by element against an 80-digit reference (the
+    double-precision oracle's own angle delta * frequency is rounded to 2^-22 rad at such sizes, so it is
+    compared with the same reference, one step more loosely)."""
+    import paper_2605_23640_amd as cp
+
+    sh = gen.KVShape(2, 2, 128)
+    theta = 500000.0
+    deltas = np.array([1, -1, 127, 128, -16383, 16384, -2097151, 1 << 21, (1 << 28) + 12345, -(1 << 30), 1 << 30,
+                       2**31 - 1, -(2**31) + 1, -(2**31)], np.int64).astype(np.int32)
+    n = len(deltas)
+    pool_l = cp.binding.KVLayout.token_major(sh.n_layers, sh.n_kv_heads, sh.head_dim)
+    dst_l = cp.binding.KVLayout.layer_major(sh.n_layers, sh.n_kv_heads, sh.head_dim, n)
+    pool = torch.empty(n * sh.tok_bytes, dtype=torch.uint8, device=G.DEV)
+    kvgen.fill(G.stream_ptr(), C.c_void_p(pool.data_ptr()), G.gen_layout(pool_l), n, 77, uid_base=500)
+    dst = G.poison_tensor(n * sh.tok_bytes)
+    ar = torch.arange(n, dtype=torch.int32, device=G.DEV)
+    ones = torch.ones(n, dtype=torch.int32, device=G.DEV)
+    flags = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    n_spans = torch.tensor([n], dtype=torch.int32, device=G.DEV)
+    cp.cp_gather_kv(pool, pool_l, n, dst, dst_l, n, ar, ar, ones, torch.from_numpy(deltas).to(G.DEV), None, n_spans, n,
+                    cp.binding.Rope(theta, 0), flags, cp.binding.new_scratch(n, n, G.DEV, n))
+    torch.cuda.synchronize()
+    assert int(flags.item()) == 0
+    got = G.dst_as_rows(dst, sh, n)  # [L][2][n][row]
+    src = kvgen.rows_for_tokens(77, np.arange(500, 500 + n, dtype=np.uint64), sh.n_layers, sh.row_bytes // 2)
+    assert np.array_equal(got[:, 1], src[:, :, 1].transpose(1, 0, 2))  # V rows: bit exact
+    D = sh.head_dim
+    worst_gpu = worst_oracle = 0
+    for t, dl in enumerate(deltas):
+        for l in range(sh.n_layers):
+            for h in range(sh.n_kv_heads):
+                x = src[t, l, 0, h * D:(h + 1) * D]
+                want = exact_rotation(x, int(dl), theta, D)
+                worst_gpu = max(worst_gpu, int(np.abs(bf16_ordinal(got[l, 0, t, h * D:(h + 1) * D]) - bf16_ordinal(want)).max()))
+                worst_oracle = max(worst_oracle, int(np.abs(bf16_ordinal(O.rope_head(x, int(dl), theta, 0)) - bf16_ordinal(want)).max()))
+    print(f"bf16 distance from the 80-digit rotation: GPU <= {worst_gpu}, double-precision oracle <= {worst_oracle}")
+    assert worst_gpu <= 1 and worst_oracle <= 2

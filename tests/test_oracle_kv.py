@@ -201,3 +201,22 @@ def test_gather_with_rotation_touches_only_keys_of_shifted_spans():
     dst2 = np.full((L, 2, N, H * D), 0xAAAA, np.uint16)
     O.gather_kv(pool, pool_l, dst2, dst_l, src, dpos, ln, delta, None)
     assert np.array_equal(dst2[:, :, 6], pool[9])
+
+
+def test_rotation_against_80_digit_arithmetic():
+    """cpo_rope_head (double precision, libm) against cos/sin summed in 80-digit decimals, up to the largest deltas
+    an int32 holds: equal bf16 values up to |delta| ~ 2^21, at most one step apart beyond (there the product
+    delta * frequency is itself rounded to about 2^-22 rad in double precision)."""
+    from tests.exact_rope import exact_rotation
+
+    def ordinal(bits):
+        b = bits.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+    rng = np.random.default_rng(8)
+    for dl, tol in ((1, 0), (-3, 0), (511, 0), (-512, 0), (40000, 0), (-2097151, 0), ((1 << 28) + 12345, 1), (2**31 - 1, 1),
+                    (-(2**31), 1)):
+        x = (rng.standard_normal(128).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        got = O.rope_head(x, dl, 500000.0, 0)
+        want = exact_rotation(x, dl, 500000.0, 128)
+        assert np.abs(ordinal(got) - ordinal(want)).max() <= tol, dl

@@ -232,3 +232,35 @@ def test_workload_invariants(name, kw):
     assert lk.n_spans == len(lk.span_src)
     print(name, "tokens", N, "matched %.3f" % covered.mean(), "sensitive %.3f" % wl.mask.mean(), "spans", lk.n_spans,
           "pool used", st.n_used, "/", wl.pool_slots, "flags", fl)
+
+
+def test_a_table_that_cannot_take_the_new_keys_stores_nothing():
+    """Bounded table: a key holds an entry from the insert that first sees it (also when the pool had no slot for
+    it, and after its slot is evicted) until the table is rebuilt; a batch whose new keys do not all fit sets
+    TABLE_FULL and stores nothing, while keys stored before are still reported."""
+    ix = O.Index()
+    ix.rebuild(10)
+    pool, slot_pos = np.zeros((64, 1, 2, 8), np.uint16), np.zeros(64, np.int32)
+    lay = lambda n: O.Layout(1, 1, 8, 16, 2 * n * 16, n * 16)  # noqa: E731
+    P = O.Layout(1, 1, 8, 32, 32, 16)
+    free = np.arange(64, dtype=np.uint32)
+
+    def ins(tok, free_slots):
+        tok = np.asarray(tok, np.uint32)
+        n = len(tok)
+        h = O.hash_segments(tok, np.zeros(n, np.uint8), np.array([0, n], np.uint32))
+        return O.insert_kv(ix, h, np.array([0, n], np.uint32), free_slots, np.zeros((1, 2, n, 8), np.uint16), lay(n), pool, P,
+                           slot_pos)
+
+    so, n_new, fl = ins([1, 2, 3, 4, 5, 6], free[:4])  # six keys, four slots: two keys keep an entry without a slot
+    assert n_new == 4 and fl == O.FLAG_POOL_FULL and ix.entries == 6 and len(ix) == 4
+    so, n_new, fl = ins([1, 2, 3, 9, 9, 9, 9, 9, 9], free[4:])  # 3 known + 6 new keys: 12 > 10
+    assert fl == O.FLAG_TABLE_FULL and n_new == 0 and list(so[:3]) == [0, 1, 2] and (so[3:] == NONE).all()
+    assert ix.entries == 6 and len(ix) == 4
+    so, n_new, fl = ins([1, 2, 3, 4, 5, 6, 7, 8, 9, 10], free[4:])  # exactly fills the table: 6 entries + 4 new
+    assert fl == 0 and n_new == 6 and ix.entries == 10 and len(ix) == 10  # 5 and 6 get their slots now
+    so, n_new, fl = ins([7], free[10:])  # one more key does not fit any more
+    assert fl == O.FLAG_TABLE_FULL and n_new == 0
+    ix.rebuild(16)
+    so, n_new, fl = ins([7], free[10:])
+    assert fl == 0 and n_new == 1 and ix.entries == 11
