@@ -38,10 +38,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # reads for a plain streaming kernel of known size.  They are copied from the summaries under profiles/
 # (gather_rows_kernel_<workload>.txt; annotator_<n>.txt): measurements of an earlier run of the same
 # code, not of this run, and the bench line says so next to them.
-PROFILED_TRAFFIC = {"llama3-8b": 9038240601, "rope": 8494728118, "llama3-70b": 58263388037, "frag": 17229210522,
+PROFILED_TRAFFIC = {"llama3-8b": 9025016802, "rope": 7598864141, "llama3-70b": 58252203568, "frag": 17206620375,
                     "annotator-10000-full": 924614651, "annotator-10000": 376097535}
-PROFILED_FETCH = {"llama3-8b": 3098951142, "rope": 2762280080, "llama3-70b": 25303251909, "frag": 7420215123}
-PROFILED_SCATTER = {}  # scatter_rows_kernel of the default step: {"llama3-8b": (fetched, written)}
+PROFILED_FETCH = {"llama3-8b": 3093482481, "rope": 2457074203, "llama3-70b": 25345798377, "frag": 7416201917}
+# scatter_rows_kernel of the default step (scatter_rows_kernel_<workload>.txt and the gather files): (fetched, written)
+PROFILED_SCATTER = {"llama3-8b": (1687306500, 1683394669), "rope": (7851507940, 7831824211),
+                    "llama3-70b": (6636776366, 6623561757)}
 
 
 def log(*a):
@@ -500,7 +502,7 @@ def main():
             "frac": 2.0 * sh.tok_bytes * inserted / (scatter_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "tokens_stored": inserted, "kernel_ms": scatter_ms, "whole_call_ms": insert_ms,
             "traffic": sum(PROFILED_SCATTER[wl.name]) if wl.name in PROFILED_SCATTER and same_gather else None,
-            "traffic_source": (f"profiles/scatter_rows_kernel_{wl.name}.txt (earlier run, not this run)"
+            "traffic_source": (f"profiles/scatter_rows_kernel_{wl.name}.txt: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this command, not of this run"
                                if wl.name in PROFILED_SCATTER and same_gather else None),
         },
     }
