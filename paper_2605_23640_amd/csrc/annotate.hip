@@ -30,6 +30,8 @@
 // block of the (l, r) triangle: lanes along l, so that T[r, l-1] is read row by row in contiguous pieces,
 // and keeps for every l the best (score, smallest r).  Two small passes over the tokens then find every
 // segment's maximum score (64-bit atomic max) and the smallest (l, r) among the l that reach it (atomic min).
+#include <type_traits>
+
 #include "cp_device.h"
 #include "cp_internal.h"
 
@@ -41,26 +43,22 @@ constexpr uint32_t kTileC = 128;  // columns of a table tile: two per lane
 constexpr uint32_t kNone = 0xFFFFFFFFu;
 constexpr uint64_t kBias = 0x8000000000000000ull;  // signed -> unsigned, order preserving
 
-// round(x * 2^32), ties to even, as a 64-bit integer; 0 above the diagonal and for values that are not
-// finite or beyond 2^18 in magnitude.  x * 2^32 is exact in double; adding 2^52 + 2^51 leaves a double
-// whose unit in the last place is 1, i.e. the hardware addition does the rounding, and the integer is
-// the difference of the bit patterns.
-__device__ __forceinline__ int64_t quantise(float x, uint32_t i, uint32_t j) {
-  if (j > i || !(fabsf(x) <= 262144.0f)) return 0;
-  const double magic = 6755399441055744.0;
-  const double d = (double)x * 4294967296.0 + magic;
-  return (int64_t)(__double_as_longlong(d) - __double_as_longlong(magic));
+// A weight x counts as round(x * 2^32), ties to even, a 64-bit integer; 0 above the diagonal (read as 0.0f
+// by load_x2) and for values that are not finite or beyond 2^18 in magnitude (replaced by 0.0f by the callers).
+// A double in [2^20, 2^21) has a unit in the last place of 2^-32, so adding 2^20 + 2^19 to the weight makes
+// the hardware addition do the rounding, and the low 52 bits of the result are 2^51 + the wanted integer:
+// quantise_biased returns the integer plus kMagicBits.  Sums of these are corrected once, by the number of
+// terms times kMagicBits (modulo 2^64), instead of once per weight.
+constexpr double kMagic = 1572864.0;                    // 2^20 + 2^19
+constexpr uint64_t kMagicBits = 0x4138000000000000ull;  // its bit pattern
+__device__ __forceinline__ uint64_t quantise_biased(float x) {
+  return (uint64_t)__double_as_longlong((double)x + kMagic);
 }
-
-// The same integer plus the bit pattern of the rounding constant (kMagicBits): what the hardware addition
-// leaves behind.  Sums of these are corrected once, by the number of terms times kMagicBits, instead of
-// once per weight; a weight that counts as 0 is replaced before the conversion, so it contributes
-// exactly kMagicBits.
-constexpr uint64_t kMagicBits = 0x4338000000000000ull;  // 2^52 + 2^51 as a double
-__device__ __forceinline__ uint64_t quantise_biased(float x, uint32_t i, uint32_t j) {
-  if (j > i || !(fabsf(x) <= 262144.0f)) x = 0.0f;
-  return (uint64_t)__double_as_longlong((double)x * 4294967296.0 + 6755399441055744.0);
-}
+// All weights a lane holds in range?  Compared as integers: a float x >= 0 is in range iff its
+// bit pattern, read as a signed integer, is at most that of 2^18; a float with the sign bit set iff its
+// pattern, read as unsigned, is at most that of -2^18 (NaN and infinity lie above both bounds).
+constexpr int32_t kMaxPosBits = 0x48800000;
+constexpr uint32_t kMaxNegBits = 0xC8800000u;
 
 // 64-bit wave scans through DPP moves (no LDS traffic).  dpp_add adds to v the value of the lane that
 // the DPP control selects, or 0 where that lane does not exist or the row is masked off.
@@ -152,153 +150,173 @@ __device__ __forceinline__ f32x2 load_x2(const float *__restrict__ p, uint32_t n
   }
   return v;
 }
+// Eight rows from r_first on.  row0 = &attn[r_first][first column of the tile] is the same for the whole
+// wavefront and the lane's part of the address is the 32-bit offset c_in_tile, so that the loads take their
+// base from scalar registers and no lane computes a 64-bit address.
 template <bool VEC, bool INTERIOR>
-__device__ __forceinline__ void load_group(const float *__restrict__ p, uint64_t ld, uint32_t n, uint32_t r_first,
-                                           uint32_t c, f32x2 x[kRowGroup]) {
+__device__ __forceinline__ void load_group(const float *__restrict__ row0, uint64_t ld, uint32_t n, uint32_t r_first,
+                                           uint32_t c, uint32_t c_in_tile, f32x2 x[kRowGroup]) {
 #pragma unroll
-  for (int u = 0; u < kRowGroup; ++u) x[u] = load_x2<VEC, INTERIOR>(p + (uint64_t)u * ld, n, r_first + u, c);
+  for (int u = 0; u < kRowGroup; ++u)
+    x[u] = load_x2<VEC, INTERIOR>(row0 + (uint64_t)u * ld + c_in_tile, n, r_first + u, c);
 }
-// In an interior tile every column is at or left of the diagonal: only the range check remains.
-template <bool INTERIOR>
-__device__ __forceinline__ void quantise2(f32x2 v, uint32_t r, uint32_t c, int64_t q[2]) {
-  const uint32_t i = INTERIOR ? 0xFFFFFFFFu : r;
-  q[0] = quantise(v.x, i, c), q[1] = quantise(v.y, i, c + 1);
+// One group of eight rows: adds this lane's 16 weights to its two column sums and returns, in the lanes
+// 8u .. 8u+7, the total of row u over the wavefront's 128 columns.  Every sum carries kMagicBits per weight.
+template <bool CHECKED>
+__device__ __forceinline__ uint64_t sum_row_group(const f32x2 (&x)[kRowGroup], uint64_t &col0, uint64_t &col1) {
+  uint64_t part[kRowGroup];
+#pragma unroll
+  for (int u = 0; u < kRowGroup; ++u) {
+    float a = x[u].x, b = x[u].y;
+    if (CHECKED) {
+      a = fabsf(a) <= 262144.0f ? a : 0.0f;
+      b = fabsf(b) <= 262144.0f ? b : 0.0f;
+    }
+    const uint64_t q0 = quantise_biased(a), q1 = quantise_biased(b);
+    col0 += q0, col1 += q1;
+    part[u] = q0 + q1;
+  }
+  return sum8_over_lanes(part);
 }
 
-// col[0..1]: this lane's two column sums over the tile's rows.  Returns in lane k the sum of the tile's
-// rows 0..k (all columns); lane 63 thus holds the tile's total.
+// A workgroup of four wavefronts sums one tile; wavefront w takes the rows 16w .. 16w + 15 (two groups of eight,
+// all requested at once).  Returns this lane's two column sums over the wavefront's rows in col[], and in the lanes
+// k < 16 the sum of the wavefront's rows 0 .. k over all columns (lane 15: all its rows; 0 in the other lanes).
+// Weights above the diagonal or outside the matrix were read as 0 (load_x2), so only the range of the values is left
+// to check, and that is done for a group at once: the per-weight test runs only where a wavefront has met a value
+// out of range.
+constexpr uint32_t kSumWaves = 4, kSumRows = kTile / kSumWaves;
 template <bool VEC, bool INTERIOR>
-__device__ __forceinline__ int64_t tile_sums(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
-                                             uint32_t c, int64_t col[2]) {
-  static_assert(kRowGroup == 8, "sum8_over_lanes reduces eight rows at a time");
-  const float *p = attn + (uint64_t)r0 * ld + c;
-  f32x2 cur[kRowGroup], nxt[kRowGroup];
-  load_group<VEC, INTERIOR>(p, ld, n, r0, c, cur);
-  // every sum here carries kMagicBits per weight (modulo 2^64), taken off where the sum is complete
-  uint64_t col0 = 0, col1 = 0, running = 0, mine = 0;  // running: the same in every lane
-#pragma unroll 1
-  for (uint32_t g = 0; g < kTile / kRowGroup; ++g) {
-    p += (uint64_t)kRowGroup * ld;
-    if (g + 1 < kTile / kRowGroup) load_group<VEC, INTERIOR>(p, ld, n, r0 + (g + 1) * kRowGroup, c, nxt);
-    uint64_t part[kRowGroup];
+__device__ __forceinline__ int64_t quarter_tile_sums(const float *__restrict__ attn, uint32_t n, uint64_t ld,
+                                                     uint32_t r_first, uint32_t c, uint32_t lane, int64_t col[2]) {
+  static_assert(kRowGroup == 8 && kSumRows == 16, "two groups of eight rows; sum8_over_lanes reduces eight rows at a time");
+  const uint32_t c_in_tile = 2 * lane;
+  const float *p = attn + (uint64_t)r_first * ld + (c - c_in_tile);  // the first weight of these rows: the same in every lane
+  uint64_t col0 = 0, col1 = 0, keep = 0;
+  auto take = [&](const f32x2 (&x)[kRowGroup], uint32_t g) {
+    int32_t hi_pos = (int32_t)0x80000000;
+    uint32_t hi_neg = 0;
 #pragma unroll
     for (int u = 0; u < kRowGroup; ++u) {
-      const uint32_t i = INTERIOR ? 0xFFFFFFFFu : r0 + g * kRowGroup + u;
-      const uint64_t q0 = quantise_biased(cur[u].x, i, c), q1 = quantise_biased(cur[u].y, i, c + 1);
-      col0 += q0, col1 += q1;
-      part[u] = q0 + q1;
+      const uint32_t bx = __float_as_uint(x[u].x), by = __float_as_uint(x[u].y);
+      hi_pos = max(hi_pos, max((int32_t)bx, (int32_t)by));
+      hi_neg = max(hi_neg, max(bx, by));
     }
-    const uint64_t rows = sum8_over_lanes(part);  // lanes 8u .. 8u+7: the total of row u of this group
-#pragma unroll
-    for (int u = 0; u < kRowGroup; ++u) {
-      running += (uint64_t)readlane_i64((int64_t)rows, 8 * u) - (uint64_t)kTileC * kMagicBits;
-      if (threadIdx.x == g * kRowGroup + u) mine = running;
-    }
-#pragma unroll
-    for (int u = 0; u < kRowGroup; ++u) cur[u] = nxt[u];
-  }
-  col[0] = (int64_t)(col0 - (uint64_t)kTile * kMagicBits), col[1] = (int64_t)(col1 - (uint64_t)kTile * kMagicBits);
-  return (int64_t)mine;
+    const bool out_of_range = hi_pos > kMaxPosBits || hi_neg > kMaxNegBits;
+    const uint64_t rows = __builtin_expect(__ballot(out_of_range) != 0, 0) ? sum_row_group<true>(x, col0, col1)
+                                                                           : sum_row_group<false>(x, col0, col1);
+    if ((lane & 7) == g) keep = rows;  // lane 8u + g: the total of row 8g + u
+  };
+  f32x2 xa[kRowGroup], xb[kRowGroup];
+  load_group<VEC, INTERIOR>(p, ld, n, r_first, c, c_in_tile, xa);
+  load_group<VEC, INTERIOR>(p + (uint64_t)kRowGroup * ld, ld, n, r_first + kRowGroup, c, c_in_tile, xb);
+  take(xa, 0);
+  take(xb, 1);
+  col[0] = (int64_t)(col0 - (uint64_t)kSumRows * kMagicBits), col[1] = (int64_t)(col1 - (uint64_t)kSumRows * kMagicBits);
+  // lane k < 16 fetches the total of row k = 8g + u from lane 8u + g, then the running sum down the rows is one wave scan
+  const uint32_t from = 8 * (lane & 7) + ((lane >> 3) & 1);
+  const uint32_t lo = __shfl((uint32_t)keep, (int)from, kWave), hi = __shfl((uint32_t)(keep >> 32), (int)from, kWave);
+  const uint64_t row_total = lane < kSumRows ? (((uint64_t)hi << 32) | lo) - (uint64_t)kTileC * kMagicBits : 0;
+  return wave_inclusive_sum((int64_t)row_total);
+}
+
+// Tiles that reach the diagonal or lie below it: tile row I holds the tile columns 0 .. I/2, so the rows 2m and
+// 2m + 1 hold m + 1 tiles each and m(m + 1) tiles come before row 2m.  Tiles are numbered in that order.
+__host__ __device__ inline uint64_t tiles_before_row(uint32_t I) {
+  const uint64_t m = I / 2;
+  return m * (m + 1) + (I & 1 ? m + 1 : 0);
+}
+__device__ __forceinline__ void tile_of(uint32_t t, uint32_t &I, uint32_t &J) {
+  uint32_t m = (uint32_t)((sqrt(4.0 * (double)t + 1.0) - 1.0) * 0.5);
+  while ((uint64_t)m * (m + 1) > t) --m;
+  while ((uint64_t)(m + 1) * (m + 2) <= t) ++m;
+  const uint32_t rest = t - m * (m + 1);
+  // (computed with vector instructions from a value every lane shares: hand the results back to scalar registers)
+  I = __builtin_amdgcn_readfirstlane(rest <= m ? 2 * m : 2 * m + 1);
+  J = __builtin_amdgcn_readfirstlane(rest <= m ? rest : rest - (m + 1));
 }
 
 // colsum[I][c]: sum of column c over the 64 rows of tile row I (width n_pad_c);  rowrun[J][r]: sum of
 // the rows r0..r of r's tile row over the 128 columns of tile column J (width n_pad_r);
-// tilesum[I][J]: the tile's total (width n_j).
+// tilesum[I][J]: the tile's total (width n_j).  One workgroup per tile on or below the diagonal; the
+// entries of the three arrays that belong to tiles above it are neither written nor read.
 template <bool VEC>
-__global__ __launch_bounds__(64) void sat_tile_sums_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
-                                                           uint32_t n_pad_c, uint32_t n_pad_r,
-                                                           int64_t *__restrict__ colsum, int64_t *__restrict__ rowrun,
-                                                           int64_t *__restrict__ tilesum) {
-  const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
-  const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
-  int64_t col[2] = {0, 0};
-  int64_t run = 0;  // a tile that lies above the diagonal as a whole holds no weight
-  if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n) {
-    run = tile_sums<VEC, true>(attn, n, ld, r0, c, col);
-  } else if (c0 <= r0 + kTile - 1) {
-    run = tile_sums<VEC, false>(attn, n, ld, r0, c, col);
-  }
-  rowrun[(uint64_t)J * n_pad_r + r0 + lane] = run;
-  if (lane == kWave - 1) tilesum[(uint64_t)I * gridDim.x + J] = run;
-  colsum[(uint64_t)I * n_pad_c + c] = col[0];
-  colsum[(uint64_t)I * n_pad_c + c + 1] = col[1];
-}
-
-// In place, for three arrays (blockIdx.y picks one): a[k][x] <- sum of a[k'][x] over k' < k   (x < width, k < n_k).
-__global__ __launch_bounds__(64) void sat_exclusive_over_tiles_kernel(int64_t *a0, uint32_t n_k0, uint32_t width0,
-                                                                      int64_t *a1, uint32_t n_k1, uint32_t width1,
-                                                                      int64_t *a2, uint32_t n_k2, uint32_t width2) {
-  int64_t *a = blockIdx.y == 0 ? a0 : blockIdx.y == 1 ? a1 : a2;
-  const uint32_t n_k = blockIdx.y == 0 ? n_k0 : blockIdx.y == 1 ? n_k1 : n_k2;
-  const uint32_t n_pad = blockIdx.y == 0 ? width0 : blockIdx.y == 1 ? width1 : width2;
-  const uint32_t x = blockIdx.x * blockDim.x + threadIdx.x;
-  if (x >= n_pad) return;
-  int64_t run = 0;
-  constexpr int kBatch = 32;  // independent loads in flight: the walk down a column is latency, not bandwidth
-  for (uint32_t k = 0; k < n_k; k += kBatch) {
-    int64_t v[kBatch];
+__global__ __launch_bounds__(kSumWaves *kWave) void sat_tile_sums_kernel(
+    const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t n_pad_c, uint32_t n_pad_r, uint32_t n_j,
+    int64_t *__restrict__ colsum, int64_t *__restrict__ rowrun, int64_t *__restrict__ tilesum) {
+  __shared__ int64_t colpart[kSumWaves][kWave][2];
+  __shared__ int64_t rows_total[kSumWaves];
+  uint32_t I, J;
+  tile_of(blockIdx.x, I, J);
+  const uint32_t lane = threadIdx.x & (kWave - 1), w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane, r_first = r0 + w * kSumRows;
+  int64_t col[2];
+  int64_t run;
+  if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n)
+    run = quarter_tile_sums<VEC, true>(attn, n, ld, r_first, c, lane, col);
+  else
+    run = quarter_tile_sums<VEC, false>(attn, n, ld, r_first, c, lane, col);
+  colpart[w][lane][0] = col[0], colpart[w][lane][1] = col[1];
+  if (lane == kSumRows - 1) rows_total[w] = run;
+  __syncthreads();
+  int64_t rows_before = 0;
+  for (uint32_t q = 0; q < w; ++q) rows_before += rows_total[q];
+  if (lane < kSumRows) rowrun[(uint64_t)J * n_pad_r + r_first + lane] = rows_before + run;
+  if (w == kSumWaves - 1) {
+    if (lane == kSumRows - 1) tilesum[(uint64_t)I * n_j + J] = rows_before + run;
+  } else if (w == 0) {
+    int64_t s0 = 0, s1 = 0;
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) v[u] = k + u < n_k ? a[(uint64_t)(k + u) * n_pad + x] : 0;
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      if (k + u < n_k) a[(uint64_t)(k + u) * n_pad + x] = run;
-      run += v[u];
-    }
-  }
-}
-
-template <bool VEC_LD, bool VEC_ST, bool INTERIOR>
-__device__ __forceinline__ void tile_apply(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
-                                           uint32_t c, const int64_t above_pref[2], int64_t left_row,
-                                           int64_t *__restrict__ T) {
-  int64_t acc[2] = {0, 0};  // this tile's rows so far, tile's columns up to each of this lane's
-  const float *p = attn + (uint64_t)r0 * ld + c;
-  int64_t *t = T + (uint64_t)r0 * n + c;
-  f32x2 cur[kRowGroup], nxt[kRowGroup];
-  load_group<VEC_LD, INTERIOR>(p, ld, n, r0, c, cur);
-#pragma unroll 1
-  for (uint32_t g = 0; g < kTile / kRowGroup; ++g) {
-    if (!INTERIOR && r0 + g * kRowGroup >= n) break;  // same for the whole wave
-    p += (uint64_t)kRowGroup * ld;
-    if (g + 1 < kTile / kRowGroup) load_group<VEC_LD, INTERIOR>(p, ld, n, r0 + (g + 1) * kRowGroup, c, nxt);
-#pragma unroll
-    for (int u = 0; u < kRowGroup; ++u) {
-      const uint32_t k = g * kRowGroup + u, r = r0 + k;
-      int64_t q[2];
-      quantise2<INTERIOR>(cur[u], r, c, q);
-      q[1] += q[0];
-      const int64_t before = wave_inclusive_sum(q[1]) - q[1];
-      const int64_t lv = readlane_i64(left_row, k);
-      acc[0] += before + q[0], acc[1] += before + q[1];
-      const int64_t out0 = acc[0] + above_pref[0] + lv, out1 = acc[1] + above_pref[1] + lv;
-      if (INTERIOR || r < n) {  // same for the whole wave
-        int64_t *o = t + (uint64_t)u * n;
-        if (VEC_ST && (INTERIOR || c + 1 < n)) {  // the wave writes 1 KiB in one piece
-          __builtin_nontemporal_store(i64x2{out0, out1}, reinterpret_cast<i64x2 *>(o));
-        } else {
-          if (c < n) o[0] = out0;
-          if (c + 1 < n) o[1] = out1;
-        }
-      }
-    }
-    t += (uint64_t)kRowGroup * n;
-#pragma unroll
-    for (int u = 0; u < kRowGroup; ++u) cur[u] = nxt[u];
+    for (uint32_t q = 0; q < kSumWaves; ++q) s0 += colpart[q][lane][0], s1 += colpart[q][lane][1];
+    colsum[(uint64_t)I * n_pad_c + c] = s0;
+    colsum[(uint64_t)I * n_pad_c + c + 1] = s1;
   }
 }
 
 // With the sensitivity mask known, the table is needed only where a substring search can look: in the
-// rows of a coarse segment [a, b], the columns from a - 1 on (and the diagonal, for every row).
-// need_from[I] = the smallest such a over the non-sensitive rows of tile row I (kNone: all its rows are
-// sensitive).  One workgroup: per tile row its first non-sensitive row and its last sensitive one, a
-// running maximum over the latter, and the segment start follows from the two.
+// rows of a coarse segment [a, b], the columns from a - 1 on (and the diagonal, for every row).  The search
+// stages whole 64-column blocks, so it reads columns down to a - 64.  For tile row I, with a the smallest
+// segment start over its non-sensitive rows, that is the tile columns from (a - 64) / 128 on (none but the one
+// that holds the rows' diagonal entries, I / 2, if all its rows are sensitive).  list_tiles (one workgroup)
+// finds a per tile row -- its first non-sensitive row and its last sensitive one, a running maximum over the
+// latter -- and writes the list of the tiles to build, tile rows ascending: tile_list[t] = pack_tile(I, J) for
+// t < *n_listed.  It runs as one workgroup of the carry kernel below.
 constexpr uint32_t kMaxTileRows = 4096;  // 2^18 rows / 64; larger requests get the whole table
-__global__ __launch_bounds__(1024) void sat_need_from_kernel(const uint8_t *__restrict__ mask, uint32_t n,
-                                                             uint32_t n_i, uint32_t *__restrict__ need_from) {
-  __shared__ uint32_t first[kMaxTileRows];  // the first non-sensitive row of tile row I (kNone: none)
+constexpr uint32_t kListedGrid = 2048;   // workgroups that share out a tile list
+__device__ __forceinline__ uint32_t pack_tile(uint32_t I, uint32_t J) { return (I << 12) | J; }  // I < 4096, J <= I / 2
+__device__ __forceinline__ void unpack_tile(uint32_t t, uint32_t &I, uint32_t &J) { I = t >> 12, J = t & 0xFFFu; }
+
+// In place over LDS: v[i] <- v[0] (+) ... (+) v[i] for i < count, a chunk of blockDim.x entries at a time.
+template <typename Combine>
+__device__ __forceinline__ void block_inclusive_scan(uint32_t *v, uint32_t count, uint32_t identity, uint32_t *carry,
+                                                     Combine combine) {
+  if (threadIdx.x == 0) *carry = identity;
+  __syncthreads();
+  for (uint32_t base = 0; base < count; base += blockDim.x) {
+    const uint32_t i = base + threadIdx.x;
+    const uint32_t width = count - base < blockDim.x ? count - base : blockDim.x;
+    for (uint32_t step = 1; step < width; step <<= 1) {
+      uint32_t other = identity;
+      if (i < count && threadIdx.x >= step) other = v[i - step];
+      __syncthreads();
+      if (i < count) v[i] = combine(other, v[i]);
+      __syncthreads();
+    }
+    if (i < count) v[i] = combine(*carry, v[i]);
+    __syncthreads();
+    if (threadIdx.x == 0) *carry = v[base + width - 1];
+    __syncthreads();
+  }
+}
+
+constexpr uint32_t kCarryThreads = 1024;  // workgroup of the carry kernel: 16 wavefronts
+constexpr uint32_t kCarrySlices = kCarryThreads / kWave;
+__device__ __forceinline__ void list_tiles(const uint8_t *__restrict__ mask, uint32_t n, uint32_t n_i,
+                                           uint32_t *__restrict__ tile_list, uint32_t *__restrict__ n_listed) {
+  __shared__ uint32_t first[kMaxTileRows];  // the first non-sensitive row of tile row I (kNone: none); later: its first tile column
   __shared__ uint32_t last[kMaxTileRows];   // 1 + the last sensitive row at or before the end of tile row I (0: none)
+  __shared__ uint32_t upto[kMaxTileRows];   // tiles listed for the tile rows 0 .. I
   __shared__ uint32_t carry;
-  if (threadIdx.x == 0) carry = 0;
   // a wavefront's 64 lanes are the 64 rows of one tile row: two ballots say where it stands
   for (uint32_t r0 = threadIdx.x / kWave * kTile; r0 < n; r0 += blockDim.x) {  // the same for a whole wavefront
     const uint32_t r = r0 + (threadIdx.x & (kWave - 1));
@@ -309,66 +327,216 @@ __global__ __launch_bounds__(1024) void sat_need_from_kernel(const uint8_t *__re
     }
   }
   __syncthreads();
-  // inclusive running maximum over last[], a chunk of blockDim.x entries at a time
-  for (uint32_t base = 0; base < n_i; base += blockDim.x) {
-    const uint32_t I = base + threadIdx.x;
-    const uint32_t width = n_i - base < blockDim.x ? n_i - base : blockDim.x;
-    for (uint32_t step = 1; step < width; step <<= 1) {
-      uint32_t other = 0;
-      if (I < n_i && threadIdx.x >= step) other = last[I - step];
-      __syncthreads();
-      if (I < n_i && other > last[I]) last[I] = other;
-      __syncthreads();
-    }
-    if (I < n_i && carry > last[I]) last[I] = carry;
-    __syncthreads();
-    if (threadIdx.x == 0) carry = last[base + width - 1];
-    __syncthreads();
-  }
-  for (uint32_t I = threadIdx.x; I < n_i; I += blockDim.x) {
-    uint32_t a = first[I];
+  block_inclusive_scan(last, n_i, 0u, &carry, [](uint32_t x, uint32_t y) { return x > y ? x : y; });
+  uint32_t a_mine[kMaxTileRows / kCarryThreads];
+#pragma unroll
+  for (uint32_t k = 0; k < kMaxTileRows / kCarryThreads; ++k) {
+    const uint32_t I = k * kCarryThreads + threadIdx.x;
+    uint32_t a = I < n_i ? first[I] : kNone;
     // a segment that starts inside the tile row starts at its first non-sensitive row (the rows before it are
     // sensitive); one that reaches in from above starts right after the last sensitive row before the tile row
     if (a != kNone && a == I * kTile) a = I ? last[I - 1] : 0;
-    need_from[I] = a;
+    a_mine[k] = a;
+  }
+  __syncthreads();  // first[] and last[] have been read
+#pragma unroll
+  for (uint32_t k = 0; k < kMaxTileRows / kCarryThreads; ++k) {
+    const uint32_t I = k * kCarryThreads + threadIdx.x;
+    if (I >= n_i) continue;
+    const uint32_t a = a_mine[k], j_diag = I / 2;
+    uint32_t j_first = j_diag;
+    if (a != kNone) {
+      const uint32_t j = a >= kTile ? (a - kTile) / kTileC : 0;
+      j_first = j < j_diag ? j : j_diag;
+    }
+    first[I] = j_first;
+    upto[I] = j_diag - j_first + 1;
+  }
+  __syncthreads();
+  block_inclusive_scan(upto, n_i, 0u, &carry, [](uint32_t x, uint32_t y) { return x + y; });
+  for (uint32_t I = threadIdx.x; I < n_i; I += blockDim.x) {
+    uint32_t t = I ? upto[I - 1] : 0;
+    for (uint32_t J = first[I]; J <= I / 2; ++J) tile_list[t++] = pack_tile(I, J);
+  }
+  if (threadIdx.x == 0) *n_listed = upto[n_i - 1];
+}
+
+// The carries between tiles, in place, for the three arrays (blockIdx.y = 0, 1, 2):
+//   a[k][x] <- sum of a[k'][x] over the k' < k that belong to tiles on or below the diagonal, for the k that do.
+//   0: colsum[I][c], tile (I, c / 128): I >= 2 (c / 128)      1: rowrun[J][r], tile (r / 64, J): J <= (r / 64) / 2
+//   2: tilesum[I][J]: I >= 2 J
+// A workgroup takes 64 neighbouring x; its 16 wavefronts take a sixteenth of the k each (the walk down a column is
+// latency, not bandwidth): they add their slice up, exchange the sums, and write the prefixes of their slice --
+// from registers when the slice fits one batch of loads, else reading it again.
+// blockIdx.y = 3 (one workgroup, only with a mask): the list of the tiles to build, which needs nothing from
+// the sums and so costs no launch of its own.
+__global__ __launch_bounds__(kCarryThreads) void sat_carry_kernel(int64_t *colsum, uint32_t n_i, uint32_t n_pad_c,
+                                                                  int64_t *rowrun, uint32_t n_j, uint32_t n_pad_r,
+                                                                  int64_t *tilesum, const uint8_t *__restrict__ mask,
+                                                                  uint32_t n, uint32_t *__restrict__ tile_list,
+                                                                  uint32_t *__restrict__ n_listed) {
+  const uint32_t which = blockIdx.y;
+  if (which == 3) {
+    if (blockIdx.x == 0) list_tiles(mask, n, n_i, tile_list, n_listed);
+    return;
+  }
+  __shared__ int64_t slice_sum[kCarrySlices][kWave];
+  int64_t *a = which == 0 ? colsum : which == 1 ? rowrun : tilesum;
+  const uint32_t width = which == 0 ? n_pad_c : which == 1 ? n_pad_r : n_j;
+  const uint32_t lane = threadIdx.x & (kWave - 1), slice = threadIdx.x / kWave;
+  const uint32_t x = blockIdx.x * kWave + lane;
+  if (blockIdx.x * kWave >= width) return;  // the same for the whole workgroup
+  uint32_t k_from = 0, k_to = 0;            // [k_from, k_to); empty for x beyond the array
+  if (x < width) {
+    if (which == 0) k_from = 2 * (x / kTileC), k_to = n_i;
+    else if (which == 1) k_from = 0, k_to = (x / kTile) / 2 + 1;
+    else k_from = 2 * x, k_to = n_i;
+    if (k_from > k_to) k_from = k_to;
+  }
+  const uint32_t share = (k_to - k_from + kCarrySlices - 1) / kCarrySlices;
+  const uint32_t k0 = k_from + slice * share < k_to ? k_from + slice * share : k_to;
+  const uint32_t k1 = k0 + share < k_to ? k0 + share : k_to;
+  constexpr int kBatch = 16;  // independent loads in flight
+  int64_t v[kBatch];
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) v[u] = 0;
+  int64_t total = 0;
+  for (uint32_t k = k0; k < k1; k += kBatch) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) v[u] = k + u < k1 ? a[(uint64_t)(k + u) * width + x] : 0;
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) total += v[u];
+  }
+  slice_sum[slice][lane] = total;
+  __syncthreads();
+  int64_t run = 0;
+  for (uint32_t q = 0; q < slice; ++q) run += slice_sum[q][lane];
+  if (k1 - k0 <= (uint32_t)kBatch) {  // v[] still holds the whole slice
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (k0 + u < k1) a[(uint64_t)(k0 + u) * width + x] = run;
+      run += v[u];
+    }
+    return;
+  }
+  for (uint32_t k = k0; k < k1; k += kBatch) {
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) v[u] = k + u < k1 ? a[(uint64_t)(k + u) * width + x] : 0;
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      if (k + u < k1) a[(uint64_t)(k + u) * width + x] = run;
+      run += v[u];
+    }
   }
 }
 
-template <bool VEC_LD, bool VEC_ST>
-__global__ __launch_bounds__(64) void sat_apply_kernel(const float *__restrict__ attn, uint32_t n, uint64_t ld,
-                                                       uint32_t n_pad_c, uint32_t n_pad_r,
-                                                       const int64_t *__restrict__ above,
-                                                       const int64_t *__restrict__ left,
-                                                       const int64_t *__restrict__ tiles_above,
-                                                       const uint32_t *__restrict__ need_from /* nullable */,
-                                                       int64_t *__restrict__ T) {
-  const uint32_t J = blockIdx.x, I = blockIdx.y, lane = threadIdx.x;
-  const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
-  if (c0 > r0 + kTile - 1) return;  // above the diagonal: not written
-  if (need_from && c0 + kTileC <= r0) {  // not the tile that holds these rows' diagonal entries
-    // the search stages whole 64-column blocks, so it loads columns down to a - 64
-    const uint32_t a = need_from[I];
-    if (a == kNone || c0 + kTileC + kTile <= a) return;  // left of everything a search looks at in these rows
+// A workgroup of four wavefronts builds one tile of the table; wavefront w takes the rows 16w .. 16w + 15, every
+// lane two adjacent columns.  All 16 rows of a wavefront are requested at once and stay in registers: first their
+// column sums go to the wavefronts below through LDS (what the tile's earlier rows add to every later row), then per
+// row: prefix over the lane's two columns, one wave scan across the lanes, running sum down the rows, + what lies
+// above the tile in its columns + what lies left of it in rows <= i (left of it in the tile's own rows + the totals
+// of the tiles above those).  LISTED: the workgroups share out the tiles of tile_list (the part of the table a search
+// can read); otherwise workgroup b takes tile b of the triangle.
+constexpr uint32_t kApplyWaves = 4, kApplyRows = kTile / kApplyWaves;
+template <bool VEC_LD, bool VEC_ST, bool INTERIOR>
+__device__ __forceinline__ void tile_apply(const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t r0,
+                                           uint32_t c, uint32_t lane, uint32_t w, const int64_t above_pref[2],
+                                           int64_t left_row, int64_t (*colpart)[kWave][2], int64_t *__restrict__ T) {
+  const uint32_t c_in_tile = 2 * lane, r_first = r0 + w * kApplyRows;
+  const float *p = attn + (uint64_t)r_first * ld + (c - c_in_tile);  // the first weight and table entry of the
+  int64_t *t = T + (uint64_t)r_first * n + (c - c_in_tile);          // wavefront's rows: the same in every lane
+  f32x2 x[kApplyRows];
+#pragma unroll
+  for (uint32_t u = 0; u < kApplyRows; ++u)
+    x[u] = load_x2<VEC_LD, INTERIOR>(p + (uint64_t)u * ld + c_in_tile, n, r_first + u, c);
+  // weights above the diagonal or outside the matrix were read as 0; values out of range count as 0 too
+  int32_t hi_pos = (int32_t)0x80000000;
+  uint32_t hi_neg = 0;
+#pragma unroll
+  for (uint32_t u = 0; u < kApplyRows; ++u) {
+    const uint32_t bx = __float_as_uint(x[u].x), by = __float_as_uint(x[u].y);
+    hi_pos = max(hi_pos, max((int32_t)bx, (int32_t)by));
+    hi_neg = max(hi_neg, max(bx, by));
   }
-  // everything above the tile, in the tile's columns up to each of this lane's
-  int64_t above_pref[2];
+  if (__builtin_expect(__ballot(hi_pos > kMaxPosBits || hi_neg > kMaxNegBits) != 0, 0)) {
+#pragma unroll
+    for (uint32_t u = 0; u < kApplyRows; ++u) {
+      x[u].x = fabsf(x[u].x) <= 262144.0f ? x[u].x : 0.0f;
+      x[u].y = fabsf(x[u].y) <= 262144.0f ? x[u].y : 0.0f;
+    }
+  }
+  uint64_t s0 = 0, s1 = 0;
+#pragma unroll
+  for (uint32_t u = 0; u < kApplyRows; ++u) s0 += quantise_biased(x[u].x), s1 += quantise_biased(x[u].y);
+  colpart[w][lane][0] = (int64_t)(s0 - (uint64_t)kApplyRows * kMagicBits);
+  colpart[w][lane][1] = (int64_t)(s1 - (uint64_t)kApplyRows * kMagicBits);
+  __syncthreads();
+  int64_t acc[2] = {0, 0};  // the tile's rows before this one, the tile's columns up to each of this lane's
+  for (uint32_t q = 0; q < w; ++q) acc[0] += colpart[q][lane][0], acc[1] += colpart[q][lane][1];
+  acc[1] += acc[0];
   {
-    above_pref[0] = above[(uint64_t)I * n_pad_c + c];
-    above_pref[1] = above_pref[0] + above[(uint64_t)I * n_pad_c + c + 1];
-    const int64_t before = wave_inclusive_sum(above_pref[1]) - above_pref[1];  // the lanes to the left
-    above_pref[0] += before, above_pref[1] += before;
+    const int64_t before = wave_inclusive_sum(acc[1]) - acc[1];
+    acc[0] += before, acc[1] += before;
   }
-  // everything left of the tile in rows <= r0 + lane: in the tile's own rows, plus the tiles above those
-  int64_t left_row = left[(uint64_t)J * n_pad_r + r0 + lane];
-  {
-    int64_t part = 0;  // tiles_above[I][j]: total of the tiles (I', j), I' < I
-    for (uint32_t j = lane; j < J; j += kWave) part += tiles_above[(uint64_t)I * gridDim.x + j];
-    left_row += readlane_i64(wave_inclusive_sum(part), kWave - 1);
+#pragma unroll
+  for (uint32_t u = 0; u < kApplyRows; ++u) {
+    const uint32_t k = w * kApplyRows + u, r = r0 + k;  // the same for the whole wavefront
+    int64_t q[2] = {(int64_t)(quantise_biased(x[u].x) - kMagicBits), (int64_t)(quantise_biased(x[u].y) - kMagicBits)};
+    q[1] += q[0];
+    const int64_t before = wave_inclusive_sum(q[1]) - q[1];
+    const int64_t lv = readlane_i64(left_row, k);
+    acc[0] += before + q[0], acc[1] += before + q[1];
+    const int64_t out0 = acc[0] + above_pref[0] + lv, out1 = acc[1] + above_pref[1] + lv;
+    if (INTERIOR || r < n) {
+      int64_t *o = t + (uint64_t)u * n + c_in_tile;
+      if (VEC_ST && (INTERIOR || c + 1 < n)) {  // the wavefront writes 1 KiB in one piece
+        __builtin_nontemporal_store(i64x2{out0, out1}, reinterpret_cast<i64x2 *>(o));
+      } else {
+        if (c < n) o[0] = out0;
+        if (c + 1 < n) o[1] = out1;
+      }
+    }
   }
-  if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n)
-    tile_apply<VEC_LD, VEC_ST, true>(attn, n, ld, r0, c, above_pref, left_row, T);
-  else
-    tile_apply<VEC_LD, VEC_ST, false>(attn, n, ld, r0, c, above_pref, left_row, T);
+}
+
+template <bool VEC_LD, bool VEC_ST, bool LISTED>
+__global__ __launch_bounds__(kApplyWaves *kWave) void sat_apply_kernel(
+    const float *__restrict__ attn, uint32_t n, uint64_t ld, uint32_t n_pad_c, uint32_t n_pad_r, uint32_t n_j,
+    const int64_t *__restrict__ above, const int64_t *__restrict__ left, const int64_t *__restrict__ tiles_above,
+    const uint32_t *__restrict__ tile_list, const uint32_t *__restrict__ n_listed, int64_t *__restrict__ T) {
+  __shared__ int64_t colpart[2][kApplyWaves][kWave][2];  // two sets: a tile's sums are still read while the next tile's are written
+  const uint32_t lane = threadIdx.x & (kWave - 1), w = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const uint32_t n_mine = LISTED ? *n_listed : gridDim.x;
+  uint32_t turn = 0;
+  for (uint32_t t = blockIdx.x; t < n_mine; t += gridDim.x, turn ^= 1) {  // (one turn unless LISTED)
+    uint32_t I, J;
+    if (LISTED) {
+      unpack_tile(tile_list[t], I, J);
+      I = __builtin_amdgcn_readfirstlane(I), J = __builtin_amdgcn_readfirstlane(J);
+    } else {
+      tile_of(t, I, J);
+    }
+    const uint32_t c0 = J * kTileC, r0 = I * kTile, c = c0 + 2 * lane;
+    // everything above the tile, in the tile's columns up to each of this lane's
+    int64_t above_pref[2];
+    {
+      above_pref[0] = above[(uint64_t)I * n_pad_c + c];
+      above_pref[1] = above_pref[0] + above[(uint64_t)I * n_pad_c + c + 1];
+      const int64_t before = wave_inclusive_sum(above_pref[1]) - above_pref[1];  // the lanes to the left
+      above_pref[0] += before, above_pref[1] += before;
+    }
+    // everything left of the tile in rows <= r0 + lane: in the tile's own rows, plus the tiles above those
+    int64_t left_row = left[(uint64_t)J * n_pad_r + r0 + lane];
+    {
+      int64_t part = 0;  // tiles_above[I][j]: total of the tiles (I', j), I' < I
+      for (uint32_t j = lane; j < J; j += kWave) part += tiles_above[(uint64_t)I * n_j + j];
+      left_row += readlane_i64(wave_inclusive_sum(part), kWave - 1);
+    }
+    if (c0 + kTileC - 1 <= r0 && r0 + kTile <= n)
+      tile_apply<VEC_LD, VEC_ST, true>(attn, n, ld, r0, c, lane, w, above_pref, left_row, colpart[turn], T);
+    else
+      tile_apply<VEC_LD, VEC_ST, false>(attn, n, ld, r0, c, lane, w, above_pref, left_row, colpart[turn], T);
+  }
 }
 
 // ---- segments ----
@@ -647,7 +815,8 @@ extern "C" size_t cp_sat_scratch_bytes(uint32_t n) {
   const uint64_t n_i = div_up(n, kTile), n_j = div_up(n, kTileC);
   const uint64_t cols = n_i * (n_j * kTileC), rows = n_j * (n_i * kTile);
   // column sums per tile row, running row sums per tile column, tile totals, per-token arrays of cp_annotate
-  return (size_t)((cols + rows + n_i * n_j) * 8 + 4 * n_i + 320ull * n + 33 * 256);
+  const uint64_t listed = n_i <= kMaxTileRows ? tiles_before_row((uint32_t)n_i) + 1 : 0;  // tile list and its length
+  return (size_t)((cols + rows + n_i * n_j) * 8 + 4 * listed + 320ull * n + 33 * 256);
 }
 
 extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, uint64_t ld, const uint8_t *mask,
@@ -666,29 +835,35 @@ extern "C" int32_t cp_sat_build(void *stream_, const float *attn, uint32_t n, ui
   int64_t *rowsum = sc.take<int64_t>((size_t)n_j * n_pad_r);
   int64_t *tilesum = sc.take<int64_t>((size_t)n_i * n_j);
   if (n_i > kMaxTileRows) mask = nullptr;
-  uint32_t *need_from = mask ? sc.take<uint32_t>(n_i) : nullptr;
-  if (!colsum || !rowsum || !tilesum || (mask && !need_from)) return CP_ERR_SCRATCH;
+  const uint32_t n_tiles = (uint32_t)tiles_before_row(n_i);  // on or below the diagonal; <= 2^26
+  uint32_t *tile_list = mask ? sc.take<uint32_t>(n_tiles) : nullptr;
+  uint32_t *n_listed = mask ? sc.take<uint32_t>(1) : nullptr;
+  if (!colsum || !rowsum || !tilesum || (mask && (!tile_list || !n_listed))) return CP_ERR_SCRATCH;
   const bool vec_ld = ld % 2 == 0 && aligned(attn, 8);  // every (row, column pair) starts on 8 bytes
   const bool vec_st = n % 2 == 0 && aligned(T, 16);
-  const dim3 tiles(n_j, n_i);
-  if (mask) sat_need_from_kernel<<<1, 1024, 0, stream>>>(mask, n, n_i, need_from);
   if (vec_ld)
-    sat_tile_sums_kernel<true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum);
+    sat_tile_sums_kernel<true><<<n_tiles, kSumWaves * kWave, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, n_j, colsum, rowsum, tilesum);
   else
-    sat_tile_sums_kernel<false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum);
+    sat_tile_sums_kernel<false><<<n_tiles, kSumWaves * kWave, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, n_j, colsum, rowsum, tilesum);
   // above the tile (column sums over the tile rows before), left of it in its own rows (running row sums
   // over the tile columns before), and the totals of the tiles above each tile
   const uint32_t widest = n_pad_c > n_pad_r ? n_pad_c : n_pad_r;
-  sat_exclusive_over_tiles_kernel<<<dim3(div_up(widest, 64), 3), 64, 0, stream>>>(
-      colsum, n_i, n_pad_c, rowsum, n_j, n_pad_r, tilesum, n_i, n_j);
-  if (vec_ld && vec_st)
-    sat_apply_kernel<true, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
-  else if (vec_ld)
-    sat_apply_kernel<true, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
-  else if (vec_st)
-    sat_apply_kernel<false, true><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
-  else
-    sat_apply_kernel<false, false><<<tiles, 64, 0, stream>>>(attn, n, ld, n_pad_c, n_pad_r, colsum, rowsum, tilesum, need_from, T);
+  sat_carry_kernel<<<dim3(div_up(widest, kWave), mask ? 4 : 3), kCarryThreads, 0, stream>>>(
+      colsum, n_i, n_pad_c, rowsum, n_j, n_pad_r, tilesum, mask, n, tile_list, n_listed);
+  // with a tile list its length is known on the device only: a fixed number of workgroups shares the tiles out
+  const uint32_t grid = mask ? (n_tiles < kListedGrid ? n_tiles : kListedGrid) : n_tiles;
+  auto apply = [&](auto vl, auto vs) {
+    if (mask)
+      sat_apply_kernel<decltype(vl)::value, decltype(vs)::value, true><<<grid, kApplyWaves * kWave, 0, stream>>>(
+          attn, n, ld, n_pad_c, n_pad_r, n_j, colsum, rowsum, tilesum, tile_list, n_listed, T);
+    else
+      sat_apply_kernel<decltype(vl)::value, decltype(vs)::value, false><<<grid, kApplyWaves * kWave, 0, stream>>>(
+          attn, n, ld, n_pad_c, n_pad_r, n_j, colsum, rowsum, tilesum, nullptr, nullptr, T);
+  };
+  if (vec_ld && vec_st) apply(std::true_type{}, std::true_type{});
+  else if (vec_ld) apply(std::true_type{}, std::false_type{});
+  else if (vec_st) apply(std::false_type{}, std::true_type{});
+  else apply(std::false_type{}, std::false_type{});
   return check_launch();
 }
 
