@@ -39,7 +39,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # (gather_rows_kernel_<workload>.txt; annotator_<n>.txt): measurements of an earlier run of the same
 # code, not of this run, and the bench line says so next to them.
 PROFILED_TRAFFIC = {"llama3-8b": 9025016802, "rope": 7598864141, "llama3-70b": 58252203568, "frag": 17206620375,
-                    "annotator-10000-full": 924614651, "annotator-10000": 376097535}
+                    "annotator-10000-full": 895904783, "annotator-10000": 347774253}
 PROFILED_FETCH = {"llama3-8b": 3093482481, "rope": 2457074203, "llama3-70b": 25345798377, "frag": 7416201917}
 # scatter_rows_kernel of the default step (scatter_rows_kernel_<workload>.txt and the gather files): (fetched, written)
 PROFILED_SCATTER = {"llama3-8b": (1687306500, 1683394669), "rope": (7851507940, 7831824211),
@@ -184,7 +184,7 @@ def annotator_bench(args):
                    "table": "whole lower triangle" if args.full_table else "only where a search can look",
                    "table_entries_owed": int(entries), "lower_triangle_entries": int(tri)},
         "sat_build_ms": sat_ms, "annotate_ms": ann_ms,
-        "roofline": {"kernel": "cp_sat_build (3 launches)" if args.full_table else "cp_sat_build (4 launches, mask known)",
+        "roofline": {"kernel": "cp_sat_build (3 launches)" if args.full_table else "cp_sat_build (3 launches, mask known)",
                      "bound": "hbm", "achieved": sat_bytes / (sat_ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": sat_bytes / (sat_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "traffic": PROFILED_TRAFFIC.get(f"annotator-{n}" + ("-full" if args.full_table else "")),
