@@ -17,13 +17,17 @@
 //     each 16-byte piece is loaded once and stored to every destination
 //     ("read once, write many").  The order inside a chain depends on timing,
 //     the bytes written do not;
-//   - work items (chains) are handed to workgroups through an atomic counter,
-//     so long chains and single tokens balance; every workgroup leaves the loop
-//     as soon as the counter passes the item count;
-//   - inside an item the 256 lanes walk the (row, 16-byte column) space in
-//     row-major order, so every wavefront touches whole contiguous 1 KiB pieces,
-//     several loads are issued before the first store, and both directions can
-//     be non-temporal (nothing is read back by this kernel).
+//   - the chain heads are gathered into a dense work list (chains of several tokens first, single
+//     tokens after them), so no workgroup ever meets a token that has nothing to do; units of
+//     work are taken from the list through an atomic counter, so long chains and single tokens
+//     balance, and every workgroup leaves the loop as soon as the counter passes the unit count;
+//   - a workgroup is four mover wavefronts plus one scout wavefront: the scout fetches and
+//     decodes the next unit (descriptor, chain links, rotation tables) into LDS while the movers
+//     copy the current one, so the movers never wait for a descriptor; one barrier per unit;
+//   - inside a unit the 256 mover lanes walk the (row, 16-byte column) space in row-major order,
+//     so every wavefront touches whole contiguous 1 KiB pieces; up to 16 loads per lane are
+//     issued before the first store, and both directions can be non-temporal (nothing is read
+//     back by this kernel).
 // Key re-rotation (textbook RoPE, not in the paper) is done in double precision
 // on the way through registers: cos/sin of delta * inv_freq[j] are computed once
 // per destination into LDS, the partner element of a pair comes from the

@@ -269,26 +269,28 @@ def test_verify_kernel_counts_real_differences(G):
     assert G.verify_rows(buf, lay, uids, 99) == 1
 
 
-def test_explicit_stream_and_two_pools_side_by_side(G):
-    """Every call takes the caller's stream: the same lookup issued on a stream of its own, while another pool's
-    lookup runs on a second stream, gives what the default stream gives (the library keeps no state between
-    calls apart from the launch-shape knobs; each pool has its own scratch)."""
+def test_two_pools_on_two_streams_with_different_launch_options(G):
+    """Every call takes the caller's stream and its own launch options: two pools' lookups, issued at the same
+    time on two streams with different options for the row mover, give what each gives alone on the default
+    stream with the default options (the library keeps no state between calls; each pool has its own scratch)."""
     import paper_2605_23640_amd as cp
 
     wl = gen.make_docs("streams", 0xC0FFEE0E, gen.KVShape(4, 2, 64), R=3, T=900, prefix_len=200, n_docs=6,
                        doc_len=(100, 200), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096)
     st_a = G.prefill(wl, G.make_pool(wl, anchor_window=8, verify=True, min_len=4))
     st_b = G.prefill(wl, G.make_pool(wl))
-    want_a, want_b = G.lookup(st_a), G.lookup(st_b)  # default stream
+    want_a, want_b = G.lookup(st_a), G.lookup(st_b)  # default stream, the pools' own options
     N, sh = wl.n_tokens, wl.shape
     tok, mask, off = G.dev_i32(wl.tok), torch.from_numpy(wl.mask.copy()).to(G.DEV), G.dev_i32(wl.off)
     bufs = [cp.LookupBuffers(N, N, G.DEV, n_pool_slots=st.pool.n_slots) for st in (st_a, st_b)]
     dsts = [G.poison_tensor(N * sh.tok_bytes) for _ in range(2)]
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]  # default priority
+    opts = [cp.binding.LaunchOpts(read_sharing=1, loads_in_flight=4, workgroups=64, fanout=2),
+            cp.binding.LaunchOpts(read_sharing=2, nontemporal=4, loads_in_flight=8, blocks_per_cu=2)]
     torch.cuda.synchronize()
     for _ in range(3):  # interleaved launches on the two streams
-        for st, buf, dst, s in zip((st_a, st_b), bufs, dsts, streams):
-            st.pool.lookup(tok, mask, off, dst, buf, stream=s)
+        for st, buf, dst, s, o in zip((st_a, st_b), bufs, dsts, streams, opts):
+            st.pool.lookup(tok, mask, off, dst, buf, stream=s, gather_opts=o)
     for s in streams:
         s.synchronize()
     for want, buf, dst, st in zip((want_a, want_b), bufs, dsts, (st_a, st_b)):
@@ -296,6 +298,54 @@ def test_explicit_stream_and_two_pools_side_by_side(G):
         assert np.array_equal(G.host_u32(buf.served if st.pool.filters else buf.slot), want.served)
         assert np.array_equal(G.dst_as_rows(dst, sh, N), G.dst_as_rows(want.dst, sh, N))
         assert int(st.pool.flags.item()) == 0
+
+
+def test_insert_and_evict_on_a_stream_that_is_not_the_current_one(G):
+    """insert() and evict() read a count back on the host: they must wait for the stream their kernels ran on.
+    The same life cycle (store, look up, evict, store more) on a side stream and on the default stream leaves
+    the same slots, free list and pool bytes."""
+    import paper_2605_23640_amd as cp
+
+    wl = gen.make_docs("side-stream", 0xC0FFEE0F, gen.KVShape(2, 2, 64), R=4, T=600, prefix_len=100, n_docs=8,
+                       doc_len=(80, 160), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=2048)
+    sh = wl.shape
+
+    def life_cycle(side):
+        pool = G.make_pool(wl, lru=True)
+        stream = torch.cuda.Stream() if side else None
+        out = []
+        with torch.cuda.stream(torch.cuda.default_stream()):  # the current stream stays the default one
+            for first, last in ((0, 2), (2, 4)):
+                t0, t1 = int(wl.off[first]), int(wl.off[last])
+                n = t1 - t0
+                src = torch.empty(n * sh.tok_bytes, dtype=torch.uint8, device=G.DEV)
+                kvgen.fill(G.stream_ptr(), C.c_void_p(src.data_ptr()), G.gen_layout(pool.request_layout(n)), n, wl.seed,
+                           uid_base=t0)
+                tok, mask = G.dev_i32(wl.tok[t0:t1]), torch.from_numpy(wl.mask[t0:t1].copy()).to(G.DEV)
+                off = G.dev_i32((wl.off[first:last + 1] - wl.off[first]).astype(np.uint32))
+                hbuf = torch.empty(n, dtype=torch.int64, device=G.DEV)
+                sout = torch.empty(n, dtype=torch.int32, device=G.DEV)
+                scratch = cp.binding.new_scratch(n, 0, G.DEV, pool.n_slots)
+                buf = cp.LookupBuffers(n, n, G.DEV, n_pool_slots=pool.n_slots)
+                dst = G.poison_tensor(n * sh.tok_bytes)
+                torch.cuda.synchronize()  # inputs were prepared on the default stream
+                pool.epoch += 1
+                pool.lookup(tok, mask, off, dst, buf, stream=stream)
+                stored = pool.insert(tok, mask, off, src, hbuf, sout, scratch, stream=stream)
+                freed = pool.evict(200, scratch, stream=stream) if first == 0 else None
+                torch.cuda.synchronize()
+                out.append((stored, G.host_u32(sout).copy(), G.host_u32(buf.slot).copy(),
+                            None if freed is None else G.host_u32(freed).copy(), pool.n_used,
+                            G.host_u32(pool.free_slots).copy(), dst.cpu().numpy().copy()))
+        return out, pool.pool.cpu().numpy()
+
+    (want, want_pool), (got, got_pool) = life_cycle(False), life_cycle(True)
+    assert want[0][0] > 0 and len(want[0][3]) >= 200 and want[1][0] > 0
+    for w, g in zip(want, got):
+        assert w[0] == g[0] and w[4] == g[4]
+        for x, y in zip(w[1:4] + w[5:], g[1:4] + g[5:]):
+            assert (x is None and y is None) or np.array_equal(x, y)
+    assert np.array_equal(want_pool, got_pool)
 
 
 def test_hash_and_probe_in_one_pass_equal_the_two_calls(G):
