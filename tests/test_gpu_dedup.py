@@ -102,3 +102,37 @@ def test_stored_once_with_a_full_pool_and_policies(G):
     olk, glk = OH.lookup(ost, min_len=16, zero_fill=True), G.lookup(gst)
     assert np.array_equal(glk.slot, olk.slot) and np.array_equal(glk.served, olk.served)
     assert np.array_equal(G.dst_as_rows(glk.dst, wl.shape, wl.n_tokens), olk.dst)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_life_cycles_with_evictions_stored_once(G, block):
+    """Fifteen batches over vocabularies of two to six tokens through a pool that is too small for them, so that
+    texts are found again, extended, evicted and stored anew; every output of every batch against the oracle."""
+    from test_gpu_policies import Lifecycle
+
+    evictions = 0
+    for seed in range(block * 8, block * 8 + 8):
+        rng = np.random.default_rng(77000 + seed)
+        vocab = int(rng.choice([2, 3, 4, 6, 32000]))
+        W = int(rng.choice([1, 2, 3, 5]))
+        verify, min_len = bool(rng.integers(0, 2)), int(rng.integers(1, 6))
+        marks, zf = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        S = int(rng.integers(80, 400))
+        print("case", dict(seed=seed, vocab=vocab, W=W, verify=verify, min_len=min_len, marks=marks, zf=zf, S=S), flush=True)
+        life = Lifecycle(G, S, gen.KVShape(1, 2, 64), 0xABE000 + seed, verify, min_len=min_len, marks=marks,
+                         zero_fill=zf, anchor_window=W, dedup=True)
+        corpus = [rng.integers(0, vocab, 50).astype(np.uint32) for _ in range(5)]
+        for epoch in range(1, 16):
+            parts = []
+            for d in rng.choice(5, int(rng.integers(1, 4)), replace=False):
+                lead = rng.integers(0, vocab, int(rng.integers(0, 5))).astype(np.uint32)
+                a = int(rng.integers(0, 20))
+                parts.append(np.concatenate([lead, corpus[d][a:a + int(rng.integers(1, 31))]]))
+            if rng.random() < 0.2:
+                parts.insert(int(rng.integers(0, len(parts) + 1)), np.zeros(0, np.uint32))  # an empty request
+            tok = np.concatenate(parts).astype(np.uint32)
+            mask = (rng.random(len(tok)) < rng.choice([0.0, 0.05, 0.3])).astype(np.uint8)
+            off = np.concatenate([[0], np.cumsum([len(x) for x in parts])]).astype(np.uint32)
+            life.batch(epoch, tok, mask, off, (rng.random(len(tok)) < 0.25).astype(np.uint8))
+        evictions += life.evictions
+    assert evictions > 0

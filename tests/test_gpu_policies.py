@@ -115,7 +115,8 @@ def test_touch_and_lru_threshold(G, seed):
 class Lifecycle:
     """The same multi-batch scenario driven through the GPU pool and through the oracle."""
 
-    def __init__(self, G, S, shape, seed, verify, min_len=1, marks=False, zero_fill=False, anchor_window=None):
+    def __init__(self, G, S, shape, seed, verify, min_len=1, marks=False, zero_fill=False, anchor_window=None,
+                 dedup=False):
         import paper_2605_23640_amd as cp
         self.G, self.cp, self.sh, self.S, self.seed = G, cp, shape, S, seed
         rng = np.random.default_rng(seed)
@@ -123,7 +124,9 @@ class Lifecycle:
         self.pool = cp.KVPool(shape.n_layers, shape.n_kv_heads, shape.head_dim, S, 4 * S,
                               torch.from_numpy(free.view(np.int32)), device=G.DEV,
                               pool_tensor=G.poison_tensor(S * shape.tok_bytes), verify=verify, min_len=min_len,
-                              recompute_marks=marks, zero_fill=zero_fill, lru=True, anchor_window=anchor_window)
+                              recompute_marks=marks, zero_fill=zero_fill, lru=True, anchor_window=anchor_window,
+                              dedup=dedup)
+        self.dedup = dedup
         # oracle side
         self.W = anchor_window
         self.anchors = O.AnchorSet() if anchor_window is not None else None
@@ -183,14 +186,21 @@ class Lifecycle:
         sout = torch.empty(N, dtype=torch.int32, device=G.DEV)
         roff = torch.empty(N, dtype=torch.int32, device=G.DEV)
         n_g = self.pool.insert(d_tok, d_mask, d_off, kv, buf.hash, sout, buf.scratch, run_off_buf=roff,
-                               recompute=_u8(rec, G.DEV) if self.marks is not None else None)
+                               recompute=_u8(rec, G.DEV) if self.marks is not None else None, buf=buf)
         okv = OH.gen_buffer(self.seed, sh, uid0, N)
-        so, n_new, fl = O.insert_kv(self.ix, h, off, self.free, okv, OH.buf_layout(sh, N), self.opool, OH.pool_layout(sh),
-                                    self.slot_pos)
+        if self.dedup:  # every text once: what a lookup of the batch finds now (after the eviction) is left out
+            streams = O.match_streams(self.ix, tok, h, ro, self.anchors, self.W, self.text, with_offsets=True)
+            h, ro, found = O.insert_keys(h, ro, streams)  # from here on: the keys and offsets the batch is stored under
+            so, n_new, fl = O.insert_kv_dedup(self.ix, h, found, off, self.free, okv, OH.buf_layout(sh, N), self.opool,
+                                              OH.pool_layout(sh), self.slot_pos)
+            assert np.array_equal(G.host_u64(buf.ins_hash), h), epoch
+        else:
+            so, n_new, fl = O.insert_kv(self.ix, h, off, self.free, okv, OH.buf_layout(sh, N), self.opool,
+                                        OH.pool_layout(sh), self.slot_pos)
         self.free = self.free[n_new:]
         self.flags |= fl
         if self.text is not None:
-            so = O.text_record(self.text, tok, ro, so)
+            so = O.text_record_dedup(self.text, tok, ro, found, so) if self.dedup else O.text_record(self.text, tok, ro, so)
         if self.marks is not None:
             O.mark_recompute(so, rec, self.marks)
         if self.anchors is not None:
