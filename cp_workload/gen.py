@@ -374,105 +374,68 @@ def make_frag(seed=0xC0FFEE03, scale=1.0, shape=KVShape(32, 8, 128), load=0.85, 
 # workload 4: reuse at shifted positions (key re-rotation)
 
 
-def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=500000.0, max_shift=512):
-    """Every reusable piece (system prefix, documents) sits in the donors at a
-    nominal position and in each request at that position plus a shift drawn
-    uniformly from [-(max_shift - 64), max_shift - 64].  Inside a document the
-    sensitive runs are private text whose length differs from one copy to the
-    next (a name, a number: 0 to 8 extra tokens per run in every copy, donor
-    and request alike), so every reused span of a document sits at a position
-    delta of its own: the piece's shift plus the difference of the extra
-    tokens before it, over a thousand spans with several hundred different
-    (request, delta) pairs per batch, nearly all within [-max_shift, max_shift].  Fillers between pieces
-    are the user's own text and end in a sensitive token, so each piece starts
-    a run in donor and request alike."""
+def _stretches(mask):
+    """Maximal non-sensitive stretches [a, b) of one prompt's mask."""
+    m = np.concatenate([[1], mask, [1]]).astype(np.int8)
+    d = np.diff(m)
+    return list(zip(np.flatnonzero(d == -1).tolist(), np.flatnonzero(d == 1).tolist()))
+
+
+def make_rope(seed=0xC0FFEE04, scale=1.0, shape=KVShape(32, 8, 128), theta=500000.0, max_shift=512, fresh=0.3):
+    """Every reused span sits in the request at its cached position plus a delta of its own, drawn
+    uniformly from [-max_shift, max_shift].
+
+    Donor prompts and requests have the same length and the same sensitive-run process (geometric runs
+    of mean 8 covering 25 %).  A request is its own text except that a fraction 1 - ``fresh`` of its
+    non-sensitive stretches begin with a stored run: for a stretch that starts at position a, a delta is
+    drawn and the stretch takes the tokens of a donor run that starts at position a - delta (the first of
+    up to sixteen draws for which a donor has a run starting exactly there), as far as the shorter of the
+    two goes; what is left of the stretch is the request's own text.  A run starts right behind a
+    sensitive token (or at position 0) in donor and request alike, so the copied tokens match from
+    their first token on, at a position delta that no other span of the batch shares except by chance.
+    Different requests, and different stretches of one request, may copy the same donor run."""
     rng = np.random.default_rng(seed)
     s = scale
     ms = max(2, round(max_shift * s))
-    piece_shift = max(1, ms - max(1, round(64 * s)))  # range of a piece's shift; the rest is for the spans' own drift
-    extra_max, extra_budget = max(1, round(8 * s)), max(2, round(192 * s))
-    prefix_len = max(8, round(1024 * s))
-    doc_len = (max(4, round(448 * s)), max(8, round(832 * s)))
-    n_docs, k_docs = max(6, round(64 * s)), 3
+    R, T = max(2, round(16 * s)), max(32, round(8192 * s))
+    n_donors = max(8, round(28 * s))
     pool_slots = max(256, round(262144 * s))
     run_mean, cover = 8.0, 0.25
-    spacing = doc_len[1] + extra_budget + 2 * ms
-    nominal = [ms] + [2 * ms + prefix_len + ms + k * spacing for k in range(k_docs)]  # piece 0 = the prefix
-    # 8 * 512 + 1024 + 3 * (832 + 192) = 8192 at full scale
-    R, T = max(2, round(16 * s)), max(round(8192 * s), nominal[-1] + ms + doc_len[1])
-    prefix = _tokens(rng, prefix_len)
-    docs, dmasks, group = [], [], []
-    for d in range(n_docs):
-        ln = int(rng.integers(doc_len[0], doc_len[1] + 1))
-        docs.append(_tokens(rng, ln))
-        dmasks.append(_mask_process(rng, ln, run_mean, cover))
-        group.append(d % k_docs)  # a document is always used in the same place of the prompt
-
-    def stretch(t, m):
-        """A copy of a document whose sensitive runs are up to extra_max tokens longer each (other private
-        text of other length), at most extra_budget tokens in all."""
-        pt, pm, left, i, n = [], [], extra_budget, 0, len(t)
-        while i < n:
-            j = i
-            while j < n and m[j] == m[i]:
-                j += 1
-            pt.append(t[i:j])
-            pm.append(m[i:j])
-            if m[i] == 1 and left > 0:
-                x = min(left, int(rng.integers(0, extra_max + 1)))
-                pt.append(_tokens(rng, x))
-                pm.append(np.ones(x, np.uint8))
-                left -= x
-            i = j
-        return np.concatenate(pt), np.concatenate(pm)
-
-    def filler(n, strict):
-        """n tokens of private text ending in a sensitive token (n may be 0).  ``strict``: all of it is
-        sensitive (the donors' own user text is never shared, Sec. 4.3.3 policy 3)."""
-        if n == 0:
-            return np.zeros(0, np.uint32), np.zeros(0, np.uint8)
-        m = np.ones(n, np.uint8) if strict else _mask_process(rng, n, run_mean, cover)
-        m[-1] = 1
-        return _tokens(rng, n), m
-
-    def compose(pieces, starts, total):
-        pt, pm, cur = [], [], 0
-        for (t, m), st in zip(pieces, starts):
-            assert st >= cur, "pieces overlap"
-            ft, fm = filler(st - cur, strict=total is None)
-            pt += [ft, t]
-            pm += [fm, m]
-            cur = st + len(t)
-        if total is not None and cur < total:
-            ft, fm = filler(total - cur, strict=False)
-            pt.append(ft)
-            pm.append(fm)
-        return np.concatenate(pt), np.concatenate(pm)
-
-    zeros = np.zeros(prefix_len, np.uint8)
-    d_tok, d_mask = [], []
-    for d in range(n_docs):  # donor d: prefix and (a copy of) document d at their nominal places
-        t, m = compose([(prefix, zeros), stretch(docs[d], dmasks[d])], [nominal[0], nominal[1 + group[d]]], None)
-        d_tok.append(t)
-        d_mask.append(m)
-    r_tok, r_mask, shifts = [], [], []
-    by_group = [[d for d in range(n_docs) if group[d] == g] for g in range(k_docs)]
+    d_tok = [_tokens(rng, T) for _ in range(n_donors)]
+    d_mask = [_mask_process(rng, T, run_mean, cover) for _ in range(n_donors)]
+    runs_at = {}  # position -> [(donor, length)] of the stored runs that start there
+    for d in range(n_donors):
+        for a, b in _stretches(d_mask[d]):
+            runs_at.setdefault(a, []).append((d, b - a))
+    r_tok, r_mask, n_reused_runs = [], [], 0
     for _ in range(R):
-        sh = rng.integers(-piece_shift, piece_shift + 1, size=1 + k_docs)
-        chosen = [int(rng.choice(by_group[g])) for g in range(k_docs)]
-        pieces = [(prefix, zeros)] + [stretch(docs[d], dmasks[d]) for d in chosen]
-        starts = [nominal[k] + int(sh[k]) for k in range(1 + k_docs)]
-        t, m = compose(pieces, starts, T)
-        r_tok.append(t[:T])
-        r_mask.append(m[:T])
-        shifts.append([int(x) for x in sh])
+        m = _mask_process(rng, T, run_mean, cover)
+        t = _tokens(rng, T)
+        for a, b in _stretches(m):
+            if rng.random() < fresh:
+                continue
+            for _attempt in range(16):
+                q = a - int(rng.integers(-ms, ms + 1))
+                cands = runs_at.get(q)
+                if cands:
+                    break
+            else:
+                continue
+            long_enough = [c for c in cands if c[1] >= b - a]
+            d, ln = long_enough[int(rng.integers(0, len(long_enough)))] if long_enough else max(cands, key=lambda c: c[1])
+            n = min(b - a, ln)
+            t[a:a + n] = d_tok[d][q:q + n]
+            n_reused_runs += 1
+        r_tok.append(t)
+        r_mask.append(m)
     tok, mask, off = _pack(r_tok, r_mask)
     dt, dm, doff = _pack(d_tok, d_mask)
     return Workload(
         name="rope", seed=seed, shape=shape, tok=tok, mask=mask, off=off,
         donor_tok=dt, donor_mask=dm, donor_off=doff, donor_batches=_batches(doff, 1 << 17),
         pool_slots=pool_slots, free_slots=rng.permutation(pool_slots).astype(np.uint32),
-        table_capacity=2 * pool_slots, rope_theta=theta, rope_style=0, notes={"shifts": shifts, "max_shift": ms},
+        table_capacity=2 * pool_slots, rope_theta=theta, rope_style=0,
+        notes={"max_shift": ms, "reused_runs": n_reused_runs},
     )
 
 

@@ -107,11 +107,11 @@ int32_t cp_last_hip_error(void);
  *                    ("read once, write many"), 2 = every token reads for itself, 0 = default: shared
  *                    from 4096 destination tokens on (below that the two extra launches cost more)
  *   blocks_per_cu    resident workgroups per compute unit (0 = default: one workgroup on seven of
- *                    every eight units where a token's rows allow 16 loads in flight, else 2; 3 for a
+ *                    every eight units where a token's rows allow 16 loads in flight, else 2; 2 for a
  *                    gather that re-rotates keys)
  *   nontemporal      0 = default (stores only), else 1 + (bit 0: non-temporal loads, bit 1: non-temporal stores)
  *   loads_in_flight  16-byte loads a lane issues before its first store (0 = default: 16 for the
- *                    Llama row shapes, fewer for small tokens, 4 for a gather that re-rotates keys;
+ *                    Llama row shapes, fewer for small tokens, 8 for a gather that re-rotates keys;
  *                    4, 8 or 16, a rotating gather at most 8)
  *   workgroups       grid size of the kernel; overrides blocks_per_cu (0 = not given)
  *   fanout           destinations written per pass over the rows of a shared slot (0 = default 16,

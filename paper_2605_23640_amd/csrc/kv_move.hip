@@ -405,6 +405,11 @@ __device__ __forceinline__ void move_rows_body(
   const bool second = cih >= vph / 2;                                    // lane holds second-half elements of its head
   const uint32_t j_first = first_freq<RA::style>(fl.head_dim / 2, cih);  // its four frequencies start here
   const uint32_t steps = (n_rows * vpr + kMoveThreads - 1) / kMoveThreads;  // same for every lane
+  // A rotating gather evens out who rotates: where a step of the 256 lanes covers whole (K, V) row pairs, a
+  // lane's row parity never changes, so for the Llama shapes two wavefronts would rotate K rows all the time
+  // while the other two only copy V rows.  Swapping K and V inside the pair on every other step of a round is
+  // still a walk over every (row, column) once, and gives every wavefront half of the rotations.
+  const uint32_t alternate = (ROPE && kMoveThreads % (2 * vpr) == 0) ? 1u : 0u;
 
   // ---- scout state (the same in all 64 lanes of the scout) ----
   uint32_t more_node = kNone, more_from = kNone;  // chain to continue in the next pass, and its source
@@ -500,8 +505,9 @@ __device__ __forceinline__ void move_rows_body(
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         ok[u] = FULL || r < n_rows;  // r only grows, so the valid steps of a lane are a prefix
-        is_k[u] = (r & 1u) == 0;
-        const uint64_t l = r >> 1, kv = r & 1u;
+        const uint32_t rr = r ^ (alternate & (uint32_t)u);  // (rounds start on even steps: U is even)
+        is_k[u] = (rr & 1u) == 0;
+        const uint64_t l = rr >> 1, kv = rr & 1u;
         doff[u] = l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
         v[u] = u32x4{0, 0, 0, 0};
         if (ok[u]) v[u] = load16<NTL>(fbase + l * fl.layer_stride + kv * fl.kv_stride + (uint64_t)c * 16);
@@ -595,16 +601,19 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   if (mo.start && hipEventRecord(mo.start, stream) != hipSuccess) return CP_ERR_HIP;
   // Defaults, measured on MI355X with the Llama row shapes.  Copy form: 16 loads in flight per lane and
   // one workgroup on seven of every eight compute units (224 of 256; one per unit is 1 % slower, two per
-  // unit with 8 loads 3-6 % slower).  Rotating form: the arithmetic wants more wavefronts with fewer
-  // registers: 4 loads in flight, three workgroups per unit (8 loads: a third slower).  Small tokens
-  // get as many loads as they have steps for.
+  // unit with 8 loads 3-6 % slower).  Rotating form: 8 loads in flight (155 registers), two workgroups per
+  // unit; with every wavefront taking half of the rotations (see `alternate` in the mover) that is 3 % faster
+  // than 4 loads and within 2 % of the copy form on the same spans.  Small tokens get as many loads as they
+  // have steps for.
   const uint64_t steps = div_up((uint64_t)fl.n_layers * 2 * (fl.n_kv_heads * fl.head_dim / 8), kMoveThreads);
-  uint32_t lif = mo.loads_in_flight ? mo.loads_in_flight : ROPE ? 4u : (steps >= 32 ? 16u : steps >= 16 ? 8u : 4u);
+  uint32_t lif = mo.loads_in_flight ? mo.loads_in_flight
+                 : ROPE             ? (steps >= 16 ? 8u : 4u)
+                                    : (steps >= 32 ? 16u : steps >= 16 ? 8u : 4u);
   if (ROPE && lif > 8) lif = 8;  // the rotating form is not built with 16: it needs its registers for arithmetic
   const uint32_t cus = cu_count();
   uint64_t grid = mo.workgroups      ? mo.workgroups
                   : mo.blocks_per_cu ? (uint64_t)cus * mo.blocks_per_cu
-                  : ROPE             ? (uint64_t)cus * 3
+                  : ROPE             ? (uint64_t)cus * 2
                   : lif >= 16        ? cus - cus / 8
                                      : (uint64_t)cus * 2;
   if (grid > max_items) grid = max_items;
