@@ -3,14 +3,15 @@
  * (gfx950).  C ABI of the data-parallel hot path of CachePrune:
  *
  *   lookup :  cp_hash_segments -> cp_probe -> cp_build_spans -> cp_gather_kv
+ *             (cp_hash_probe does the first two in one pass)
  *   insert :  cp_hash_segments -> cp_insert_kv
  *
  * and, further down, the calls that widen it to the paper's retrieval and pool
  * life cycle: floating anchors (cp_hash_runs, cp_insert_anchors, cp_hash_floating,
  * cp_probe2, cp_probe3), exact confirmation of matches (cp_insert_kv_chain, cp_verify_chain),
- * one copy of stored text (cp_insert_keys, cp_insert_kv_dedup), pool policies (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch,
- * cp_lru_threshold, cp_evict, cp_table_compact) and the KV annotator
- * (cp_sat_build, cp_annotate).
+ * one copy of stored text (cp_insert_keys, cp_insert_kv_dedup), pool policies
+ * (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch, cp_lru_threshold, cp_evict,
+ * cp_table_compact) and the KV annotator (cp_sat_build, cp_annotate).
  *
  * Conventions for every call
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
