@@ -131,6 +131,21 @@ def test_rope_small_head_dim_64_and_large_shifts(G):
     assert np.abs(glk.span_delta).max() > 1000
 
 
+@pytest.mark.parametrize("shape", [(2, 3, 64), (3, 5, 128), (1, 6, 16), (2, 7, 32), (1, 12, 64)])
+def test_head_counts_that_are_not_powers_of_two(G, shape):
+    """Rows of 24, 80, 12, 28 and 96 sixteen-byte vectors: a step of the mover's 256 lanes then ends in the
+    middle of a row, and a wavefront holds K and V rows side by side.  Copying and rotating gathers, both
+    pool layouts."""
+    sh = gen.KVShape(*shape)
+    compare_all(G, gen.make_docs("odd-heads", 0xC0FFEE40 + shape[1], sh, R=3, T=700, prefix_len=100, n_docs=6,
+                                 doc_len=(60, 200), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=4096))
+    for style, layout in ((0, "token"), (1, "layer")):
+        wl = gen.make_rope(seed=0xC0FFEE50 + shape[1], scale=1 / 16, shape=sh)
+        wl.rope_style = style
+        ost, olk, gst, glk = compare_all(G, wl, pool_layout=layout)
+        assert (glk.span_delta != 0).mean() > 0.8
+
+
 def test_contiguous_slots_give_long_spans(G):
     wl = gen.make_docs("contig", 7, gen.KVShape(4, 2, 64), R=4, T=1500, prefix_len=400, n_docs=5, doc_len=(200, 400),
                        docs_per_request=3, run_mean=8.0, cover=0.10, pool_slots=4096)
