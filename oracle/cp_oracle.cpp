@@ -334,8 +334,8 @@ extern "C" void cpo_insert_anchors(cpo_anchor_set *as, const uint64_t *hash, con
 
 extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const cpo_index *ix, const uint64_t *hash,
                                   const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
-                                  uint64_t *hash_early_out, uint32_t *early_off_out,
-                                  uint64_t *hash_late_out, uint32_t *late_off_out) {
+                                  uint64_t *hash_a_out, uint32_t *off_a_out, uint64_t *hash_b_out,
+                                  uint32_t *off_b_out) {
   // precomputed powers of the base
   std::vector<uint64_t> pw((size_t)N + 1);
   pw[0] = 1;
@@ -347,10 +347,10 @@ extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const cpo_index *ix,
     return h == CPO_HASH_NONE ? CPO_HASH_NONE - 1 : h;  // stored hashes never take the reserved value
   };
   for (uint32_t i = 0; i < N; ++i) {
-    hash_early_out[i] = CPO_HASH_NONE;
-    if (early_off_out) early_off_out[i] = 0xFFFFFFFFu;
-    if (hash_late_out) hash_late_out[i] = CPO_HASH_NONE;
-    if (late_off_out) late_off_out[i] = 0xFFFFFFFFu;
+    hash_a_out[i] = CPO_HASH_NONE;
+    if (off_a_out) off_a_out[i] = 0xFFFFFFFFu;
+    if (hash_b_out) hash_b_out[i] = CPO_HASH_NONE;
+    if (off_b_out) off_b_out[i] = 0xFFFFFFFFu;
   }
   // run by run
   for (uint32_t s0 = 0; s0 < N;) {
@@ -367,38 +367,41 @@ extern "C" void cpo_hash_floating(const cpo_anchor_set *as, const cpo_index *ix,
     for (uint32_t a = s0 + 1; a + W <= s1; ++a)
       if (as->set.count(sub(a, a + W - 1))) cand.push_back(a);
     // Step 2, pre-check by substring hashes: how far does the stored text that starts at candidate a
-    // go on?  ext[c] = last token e such that every key (a .. j), a+W-1 <= j <= e, is stored.
-    std::vector<uint32_t> ext(cand.size());
+    // go on?  end[c] = 1 + the last token e such that every key (a .. j), a+W-1 <= j <= e, is stored:
+    // candidate c covers the tokens cand[c] .. end[c]-1.
+    std::vector<uint32_t> end(cand.size());
     for (size_t c = 0; c < cand.size(); ++c) {
       uint32_t e = cand[c] + W - 1;
       while (e + 1 < s1 && ix->map.count(sub(cand[c], e + 1))) ++e;
-      ext[c] = e;
+      end[c] = e + 1;
     }
-    for (uint32_t i = s0 + 1; i < s1; ++i) {
-      // the earliest candidate whose stored text reaches token i ...
-      size_t first = cand.size();
-      for (size_t c = 0; c < cand.size() && cand[c] <= i; ++c)
-        if (ext[c] >= i) {
-          first = c;
-          break;
+    // Which candidate serves which token: the candidates' texts are laid over the run like intervals in
+    // the textbook greedy cover.  A piece of covered text begins at the first candidate not yet passed;
+    // then, as long as some candidate that starts inside the text covered so far reaches beyond it,
+    // the one that reaches furthest (the earliest of those) is taken next.  Every token that any
+    // candidate covers is then covered by a chosen one, and a chosen candidate overlaps only with the
+    // one chosen before it and the one chosen after it, so giving the chosen candidates of a piece
+    // alternately to stream a and stream b leaves each stream a sequence of whole texts that do not
+    // overlap.  Each chosen candidate keys all of its tokens in its stream.
+    size_t c = 0;
+    while (c < cand.size()) {
+      uint32_t stream = 0;  // a piece starts in stream a
+      for (;;) {
+        for (uint32_t i = cand[c]; i < end[c]; ++i) {
+          uint64_t *h = stream == 0 ? hash_a_out : hash_b_out;
+          uint32_t *o = stream == 0 ? off_a_out : off_b_out;
+          if (h) h[i] = sub(cand[c], i);
+          if (o) o[i] = i - cand[c];
         }
-      // ... counts if it starts on text that no earlier candidate covers (a candidate that starts inside
-      // an earlier one's text is left to the second stream)
-      if (first != cand.size()) {
-        bool inside_earlier = false;
-        for (size_t c = 0; c < first; ++c) inside_earlier = inside_earlier || ext[c] >= cand[first];
-        if (!inside_earlier) {
-          hash_early_out[i] = sub(cand[first], i);
-          if (early_off_out) early_off_out[i] = i - cand[first];
-        }
+        size_t best = cand.size();
+        for (size_t d = c + 1; d < cand.size() && cand[d] < end[c]; ++d)
+          if (end[d] > end[c] && (best == cand.size() || end[d] > end[best])) best = d;
+        if (best == cand.size()) break;
+        c = best;
+        stream ^= 1u;
       }
-      // the latest candidate at or before token i
-      size_t last = cand.size();
-      for (size_t c = 0; c < cand.size() && cand[c] <= i; ++c) last = c;
-      if (last != cand.size()) {
-        if (hash_late_out) hash_late_out[i] = sub(cand[last], i);
-        if (late_off_out) late_off_out[i] = i - cand[last];
-      }
+      const uint32_t covered_to = end[c];  // nothing that starts before this reaches further
+      while (c < cand.size() && cand[c] < covered_to) ++c;
     }
     s0 = s1;
   }

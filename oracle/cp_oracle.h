@@ -144,10 +144,10 @@ uint32_t cpo_insert_kv_dedup(cpo_index *, const uint64_t *ins_hash, const uint32
  * there on get a second key: the hash of the request's tokens from the anchor through the token,
  * computed in O(1) from the run's chain hashes and a power of the base.  Step 1 yields a set of
  * candidates and Step 2 checks each of them over the text stored behind it; a request token can lie in
- * the text of several candidates.  Two key streams carry them: the earliest candidate whose stored
- * text reaches the token (if that candidate starts on text no earlier candidate covers), and the
- * latest candidate at or before the token.  A token is served under its run-start key if that hits,
- * else under the first stream's key, else under the second's. */
+ * the text of several candidates.  Every token that some candidate's text covers is served: the
+ * candidates that serve are chosen like the intervals of a greedy cover and handed alternately to two
+ * key streams, so that the texts inside one stream do not overlap.  A token is served under its
+ * run-start key if that hits, else under the first stream's key, else under the second's. */
 typedef struct cpo_anchor_set cpo_anchor_set; /* prefix hash -> slot of the run's W-th token. Opaque. */
 cpo_anchor_set *cpo_anchor_set_new(void);
 void cpo_anchor_set_free(cpo_anchor_set *);
@@ -164,18 +164,19 @@ void cpo_insert_anchors(cpo_anchor_set *, const uint64_t *hash, const uint32_t *
                         const uint32_t *slot, uint32_t N, uint32_t W);
 
 /* A candidate is a position a after its run's first token such that the W tokens from a lie inside the
- * run and their hash is in the set.  Its stored text reaches e = ext(a): the last token of the run
- * such that every key (tokens a..j), a+W-1 <= j <= e, is in the index (the pre-check by substring
+ * run and their hash is in the set.  Its stored text covers the tokens a .. e: e the last token of the
+ * run such that every key (tokens a..j), a+W-1 <= j <= e, is in the index (the pre-check by substring
  * hashes of Step 2).
- *   hash_early_out[i] = key of tokens a..i for the earliest candidate a <= i of i's run with
- *     ext(a) >= i, provided no earlier candidate's text reaches a (ext(b) >= a for some b < a);
- *   hash_late_out[i]  = key of tokens a..i for the latest candidate a <= i of i's run;
- * CPO_HASH_NONE where there is none (and for sensitive tokens).  *_off_out (nullable): i - a, or
- * 0xFFFFFFFF.  hash_late_out may be NULL. */
+ * Choice of the candidates that serve, per run: a piece of covered text begins at the first candidate
+ * that no chosen text reaches; as long as a candidate that starts inside the text covered so far
+ * reaches beyond it, the one that reaches furthest (the earliest such) is chosen next.  The chosen
+ * candidates of a piece go alternately to stream a and stream b, the first to a.
+ *   hash_a_out[i] / hash_b_out[i] = key of tokens c..i if i lies in the text of a chosen candidate c
+ *     of that stream, else CPO_HASH_NONE (also for sensitive tokens);
+ *   off_*_out (nullable): i - c, or 0xFFFFFFFF.  hash_b_out may be NULL. */
 void cpo_hash_floating(const cpo_anchor_set *, const cpo_index *, const uint64_t *hash,
                        const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
-                       uint64_t *hash_early_out, uint32_t *early_off_out, uint64_t *hash_late_out,
-                       uint32_t *late_off_out);
+                       uint64_t *hash_a_out, uint32_t *off_a_out, uint64_t *hash_b_out, uint32_t *off_b_out);
 
 /* Lookup with two keys per token: slot under hash_a if present, else under hash_b, else NONE. */
 void cpo_probe2(const cpo_index *, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
