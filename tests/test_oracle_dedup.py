@@ -6,7 +6,7 @@ import pytest
 
 import oracle as O
 from tests.bruteforce import BrutePool, runs
-from tests.test_oracle_floating import brute_candidates
+from tests.test_oracle_floating import brute_candidates, brute_choice
 
 NONE = O.SLOT_NONE
 L1 = lambda n: O.Layout(1, 1, 8, 16, 2 * n * 16, n * 16)  # noqa: E731
@@ -21,24 +21,18 @@ class TextPool(BrutePool):
         self.W = W
         self.stored_runs = []  # every stored text that was a run's beginning when stored: the candidates' prefixes
 
-    def serving(self, run, i, cands):
-        """(slot, start of the stored text that serves token i of the run), by the lookup's rule."""
+    def serving(self, run, i, chosen):
+        """(slot, start of the stored text that serves token i of the run), by the lookup's rule: the run-start
+        match, else the serving candidate of the first stream that covers the token, else of the second."""
         s = self.find(run[: i + 1])
         if s is not None:
             return s, 0
-        reach = [(a, e) for a, e in cands if a <= i <= e]
-        if reach:
-            a = min(a for a, _ in reach)
-            if not any(b < a <= e for b, e in cands):
-                s = self.find(run[a: i + 1])
-                if s is not None:
-                    return s, a
-        before = [a for a, _ in cands if a <= i]
-        if before:
-            a = max(before)
-            s = self.find(run[a: i + 1])
-            if s is not None:
-                return s, a
+        for stream in (0, 1):
+            for a, e, st in chosen:
+                if st == stream and a <= i <= e:
+                    s = self.find(run[a: i + 1])
+                    if s is not None:
+                        return s, a
         return None, None
 
     def insert_once(self, tok, mask, off):
@@ -46,10 +40,10 @@ class TextPool(BrutePool):
         plan = []
         for _, a0, b0 in runs(tok, mask, off):  # what the pool holds is decided before anything is stored
             run = [int(t) for t in tok[a0:b0]]
-            cands = brute_candidates(self, self.stored_runs, run, self.W)
+            chosen = brute_choice(brute_candidates(self, self.stored_runs, run, self.W))
             c = 0
             for i in range(len(run)):
-                s, start = self.serving(run, i, cands)
+                s, start = self.serving(run, i, chosen)
                 if s is not None:
                     c = start
                 plan.append((a0 + i, s, run[c: i + 1]))

@@ -43,14 +43,36 @@ def brute_candidates(bp, stored_runs, run, W):
     return out
 
 
+def brute_choice(cands):
+    """Which candidates serve, and in which of the two streams: [(first token, last token, stream)].  A piece
+    of covered text begins at the first candidate that no chosen text reaches; as long as a candidate that
+    starts inside the covered text reaches beyond it, the one that reaches furthest (the earliest such) comes
+    next; the chosen candidates of a piece alternate between the streams."""
+    chosen, c = [], 0
+    while c < len(cands):
+        stream = 0
+        while True:
+            a, e = cands[c]
+            chosen.append((a, e, stream))
+            further = [d for d in range(c + 1, len(cands)) if cands[d][0] <= e and cands[d][1] > e]
+            if not further:
+                break
+            far = max(cands[d][1] for d in further)
+            c = min(d for d in further if cands[d][1] == far)
+            stream ^= 1
+        end = cands[c][1]
+        while c < len(cands) and cands[c][0] <= end:
+            c += 1
+    for st in (0, 1):  # the texts inside one stream do not overlap
+        segs = sorted((a, e) for a, e, s_ in chosen if s_ == st)
+        assert all(segs[k][1] < segs[k + 1][0] for k in range(len(segs) - 1))
+    return chosen
+
+
 def brute_floating(bp, stored_runs, tok, mask, off, W):
     """Expected slot of every request token, from the tokens alone: the run-start match first; else the
-    chosen candidate of the first stream whose stored text covers the token, else that of the second
-    stream.  The candidates that serve are chosen as Sec. 4.2.2's set of candidates allows any token that
-    some candidate covers to be served: a piece of covered text begins at the first candidate that no
-    chosen text reaches; as long as a candidate that starts inside the covered text reaches beyond it,
-    the one that reaches furthest (the earliest such) comes next; the chosen candidates of a piece
-    alternate between the two streams.  Also returns, per token, whether ANY candidate's stored text (or
+    chosen candidate (brute_choice) of the first stream whose stored text covers the token, else that of
+    the second stream.  Also returns, per token, whether ANY candidate's stored text (or
     the run-start match) covers it, every slot that would be a correct answer for it, and the largest
     number of candidates whose texts overlap at one token."""
     n = len(tok)
@@ -58,24 +80,7 @@ def brute_floating(bp, stored_runs, tok, mask, off, W):
     for _, a0, b0 in runs(tok, mask, off):
         run = [int(t) for t in tok[a0:b0]]
         cands = brute_candidates(bp, stored_runs, run, W)  # (first token, last token) of every candidate's text
-        chosen, c = [], 0
-        while c < len(cands):
-            stream = 0
-            while True:
-                a, e = cands[c]
-                chosen.append((a, e, stream))
-                further = [d for d in range(c + 1, len(cands)) if cands[d][0] <= e and cands[d][1] > e]
-                if not further:
-                    break
-                far = max(cands[d][1] for d in further)
-                c = min(d for d in further if cands[d][1] == far)
-                stream ^= 1
-            end = cands[c][1]
-            while c < len(cands) and cands[c][0] <= end:
-                c += 1
-        for st in (0, 1):  # the texts inside one stream do not overlap
-            segs = sorted((a, e) for a, e, s_ in chosen if s_ == st)
-            assert all(segs[k][1] < segs[k + 1][0] for k in range(len(segs) - 1))
+        chosen = brute_choice(cands)
         for i in range(len(run)):
             reach = [(a, e) for a, e in cands if a <= i <= e]  # all candidates whose text covers token i
             depth = max(depth, len(reach))

@@ -196,13 +196,13 @@ def test_floating_segments_are_verified_from_their_anchor():
     h = O.hash_segments(req, m, roff)
     ro = O.run_offsets(m, roff)
     hf, fo, hl, lo = O.hash_floating(anchors, P.ix, h, ro, W)
-    # the stored text reaches 20 tokens from the candidate; the latest candidate stays the latest to the run's end
+    # the stored text reaches 20 tokens from the candidate; it is the only candidate, so the second stream is empty
     assert list(fo[:7]) == [X] * 7 and list(fo[7:27]) == list(range(20)) and list(fo[27:]) == [X] * (len(req) - 27)
-    assert list(lo[:7]) == [X] * 7 and list(lo[7:]) == list(range(len(req) - 7))
+    assert list(lo) == [X] * len(req) and (hl == O.HASH_NONE).all()
     a = O.verify(P.text, req, ro, O.probe(P.ix, h))
     assert (a == NONE).all()  # nothing matches from the run start
-    for keys, seg in ((hf, fo), (hl, lo)):
-        b = O.verify(P.text, req, seg, O.probe(P.ix, keys), merge_into=a)
-        assert np.array_equal(b[7:27], so[:20]) and (b[27:] == NONE).all() and (b[:7] == NONE).all()
+    b = O.verify(P.text, req, fo, O.probe(P.ix, hf), merge_into=a)
+    assert np.array_equal(b[7:27], so[:20]) and (b[27:] == NONE).all() and (b[:7] == NONE).all()
+    assert np.array_equal(O.verify(P.text, req, lo, O.probe(P.ix, hl), merge_into=b), b)
     streams = O.match_streams(P.ix, req, h, ro, anchors, W, P.text)
     assert np.array_equal(O.merge_streams(streams), b)
