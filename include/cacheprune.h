@@ -182,17 +182,23 @@ int32_t cp_hash_probe(void *stream, const uint32_t *tok, const uint8_t *mask, co
  *     same tokens get as the beginning of a stored run, so it is looked up in the ordinary table.
  *     (Stored runs are closed under taking prefixes - every insert, truncation and eviction of this
  *     library keeps them so - and ext(a) is found by bisection.)
- *   - a token can lie in the text of several candidates.  cp_hash_floating gives every token i two
- *     keys: hash_early_out[i] = key of a..i for the earliest candidate a <= i of its run with
- *     ext(a) >= i, provided a starts on text that no earlier candidate reaches (no candidate b < a
- *     with ext(b) >= a); hash_late_out[i] = key of a..i for the latest candidate a <= i of its run.
- *     CP_HASH_NONE where there is none.  early_off_out / late_off_out (device u32[N], may be NULL):
- *     i - a, or 0xFFFFFFFF.  hash_late_out may be NULL.
+ *   - a token can lie in the text of several candidates, and every token that some candidate covers
+ *     is to be served.  The candidates that serve are chosen like the intervals of a greedy cover: a
+ *     piece of covered text begins at the first candidate that no earlier candidate's text reaches;
+ *     as long as a candidate that starts inside the text covered so far reaches beyond it, the one
+ *     that reaches furthest (the earliest such) is chosen next.  A chosen candidate then overlaps
+ *     only with the one chosen before it and the one chosen after it, and the chosen candidates of a
+ *     piece are handed alternately to two key streams, a and b (the first to a): inside a stream the
+ *     texts are whole and never overlap, which is what cp_verify_chain and cp_build_spans need.
+ *     cp_hash_floating gives every token its key in either stream: hash_a_out[i] / hash_b_out[i] =
+ *     key of c..i if i lies in the text of a chosen candidate c of that stream, else CP_HASH_NONE.
+ *     off_a_out / off_b_out (device u32[N], may be NULL): i - c, or 0xFFFFFFFF.  hash_b_out may be
+ *     NULL.
  *   - cp_probe2 / cp_probe3 look every token up under the first key and, while that misses, under
  *     the next.
- * A token is thus served under its run-start key if possible, else from the earliest candidate
- * whose text reaches it, else from the latest candidate: every token that one or two candidates'
- * texts cover is served; where three or more overlap at a token, one of them may go unused.
+ * A token is thus served under its run-start key if possible, else from the candidate chosen for it
+ * in stream a, else in stream b: every token that any candidate's stored text covers is served,
+ * however many candidates overlap there.
  * `base` must be odd.  W >= 1. */
 int32_t cp_hash_runs(void *stream, const uint32_t *tok, const uint8_t *mask, const uint32_t *off, uint32_t N,
                      uint32_t R, uint64_t base, uint64_t *hash_out, uint32_t *run_off_out, void *scratch,
@@ -201,8 +207,8 @@ int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, const uint32_t 
                           uint32_t n_pool_slots, uint8_t *slot_anchor);
 int32_t cp_hash_floating(void *stream, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,
                          const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base, uint32_t W,
-                         uint64_t *hash_early_out, uint32_t *early_off_out, uint64_t *hash_late_out,
-                         uint32_t *late_off_out, void *scratch, size_t scratch_bytes);
+                         uint64_t *hash_a_out, uint32_t *off_a_out, uint64_t *hash_b_out, uint32_t *off_b_out,
+                         void *scratch, size_t scratch_bytes);
 int32_t cp_probe2(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, uint32_t N,
                   uint32_t *slot_out);
 int32_t cp_probe3(void *stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b, const uint64_t *hash_c,
@@ -226,7 +232,7 @@ int32_t cp_probe3(void *stream, cp_table table, const uint64_t *hash_a, const ui
  * last kind is consumed but can never match (its parent is set to CP_PARENT_POISON).
  *
  * cp_verify_chain confirms the candidates of one key stream of a lookup.  seg_off[i] = offset of
- * token i in its segment: run_off for run-start keys, early_off / late_off for the two floating
+ * token i in its segment: run_off for run-start keys, off_a / off_b for the two floating
  * streams; 0xFFFFFFFF = in no segment.  cand[i] = slot found under that stream's key (cp_probe).  Token i is accepted iff
  * every token from its segment's start through i is consistent: cand < n_pool_slots,
  * slot_tok[cand[i]] == tok[i], and slot_parent[cand[i]] == cand[i-1] (CP_SLOT_NONE at offset 0); by

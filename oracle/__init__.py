@@ -185,7 +185,7 @@ def insert_anchors(anchors: AnchorSet, hashes, run_off, slot, W):
 
 
 def hash_floating(anchors: AnchorSet, index: Index, hashes, run_off, W, base=BASE):
-    """Keys of the two candidate streams: (hash_early, early_off, hash_late, late_off)."""
+    """Keys and segment offsets of the two candidate streams: (hash_a, off_a, hash_b, off_b)."""
     hashes, run_off = _arr(hashes, np.uint64), _arr(run_off, np.uint32)
     n = hashes.shape[0]
     he, hl = np.empty(n, np.uint64), np.empty(n, np.uint64)
@@ -198,7 +198,7 @@ def hash_floating(anchors: AnchorSet, index: Index, hashes, run_off, W, base=BAS
 def match_streams(index: Index, tok, hashes, run_off, anchors: AnchorSet = None, W=None, text: "Text" = None,
                   with_offsets=False):
     """What every key stream of a lookup finds, in the order in which they serve a token: the run-start
-    keys, then (pools with floating anchors) the earliest-candidate keys and the latest-candidate keys.
+    keys, then (pools with floating anchors) the keys of candidate stream a and of candidate stream b.
     With ``text`` each stream's slots are confirmed against the stored text along its own segments."""
     streams = [(hashes, run_off)]
     if anchors is not None:

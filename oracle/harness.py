@@ -139,10 +139,10 @@ class Lookup:
     flags: int
     dst: np.ndarray | None  # uint16[L][2][N][row_elems]
     times: dict
-    hash_float: np.ndarray | None = None  # keys of the earliest-candidate stream (pools with floating anchors)
+    hash_float: np.ndarray | None = None  # keys of candidate stream a (pools with floating anchors)
     run_off: np.ndarray | None = None
     served: np.ndarray | None = None  # slots after minimum length / recompute marks
-    hash_late: np.ndarray | None = None  # keys of the latest-candidate stream
+    hash_late: np.ndarray | None = None  # keys of candidate stream b
 
 
 def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_spans=None, min_len=1,

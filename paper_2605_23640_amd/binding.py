@@ -299,18 +299,18 @@ def cp_insert_anchors(run_off, slot, W, n_pool_slots, slot_anchor, stream=None):
                                                         int(W), n_pool_slots, _ptr(slot_anchor)))
 
 
-def cp_hash_floating(table: Table, slot_anchor, n_pool_slots, hashes, run_off, W, hash_early_out, scratch, base=BASE,
-                     stream=None, early_off_out=None, hash_late_out=None, late_off_out=None):
-    _need_cuda(slot_anchor, hashes, run_off, hash_early_out, scratch, early_off_out, hash_late_out, late_off_out)
+def cp_hash_floating(table: Table, slot_anchor, n_pool_slots, hashes, run_off, W, hash_a_out, scratch, base=BASE,
+                     stream=None, off_a_out=None, hash_b_out=None, off_b_out=None):
+    _need_cuda(slot_anchor, hashes, run_off, hash_a_out, scratch, off_a_out, hash_b_out, off_b_out)
     N = hashes.numel()
-    assert run_off.numel() == N and hash_early_out.numel() == N and slot_anchor.numel() >= n_pool_slots
-    for t in (early_off_out, hash_late_out, late_off_out):
+    assert run_off.numel() == N and hash_a_out.numel() == N and slot_anchor.numel() >= n_pool_slots
+    for t in (off_a_out, hash_b_out, off_b_out):
         assert t is None or t.numel() == N
     _check("cp_hash_floating", lib().cp_hash_floating(_stream(stream), table.struct, _ptr(slot_anchor), n_pool_slots,
                                                       _ptr(hashes), _ptr(run_off), N, base, int(W),
-                                                      _ptr(hash_early_out), _ptr(early_off_out), _ptr(hash_late_out),
-                                                      _ptr(late_off_out), _ptr(scratch), scratch.numel()))
-    return hash_early_out
+                                                      _ptr(hash_a_out), _ptr(off_a_out), _ptr(hash_b_out),
+                                                      _ptr(off_b_out), _ptr(scratch), scratch.numel()))
+    return hash_a_out
 
 
 def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, merge, slot_out, scratch, stream=None,

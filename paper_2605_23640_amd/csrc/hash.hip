@@ -72,27 +72,39 @@ __device__ __forceinline__ uint64_t substring_key(const uint64_t *__restrict__ h
   return key == CP_HASH_NONE ? CP_HASH_NONE - 1 : key;
 }
 
-// Scan over the candidates' reach (ext1[a] = 1 + last token whose key from candidate a is stored, 0 where
-// a is no candidate), restarting at every run: the running maximum of the reach, stored per token for the
-// search for the earliest candidate, and the latest candidate at or before every token, whose key is the
-// second candidate stream.
+// Which candidate serves which token (Sec. 4.2.2: Step 1 yields a set of candidates, Step 2 checks each over the
+// text stored behind it).  Candidate a covers the tokens a .. ext1[a]-1 (ext1[a] = 1 + last token whose key from a
+// is stored, 0 where a is no candidate).  The candidates that serve are chosen like the intervals of a greedy
+// cover: a piece of covered text begins at a candidate that no earlier candidate's text reaches; as long as a
+// candidate that starts inside the text covered so far reaches beyond it, the one that reaches furthest (the
+// earliest such) is chosen next.  Every token that any candidate covers is then covered by a chosen one, a chosen
+// candidate overlaps only with its two neighbours in the piece, and handing the chosen candidates of a piece
+// alternately to stream a and stream b (the first to a) leaves each stream a sequence of whole texts that do not
+// overlap: what the per-stream verification and the span builder need.
+//
+// In terms of reach[p] = the largest ext1 over the candidates at or before p in the run (a prefix maximum): a
+// piece begins at a candidate g with reach[g-1] <= g; its chosen candidates end at e1 = ext1[g], e2 = reach[e1-1],
+// e3 = reach[e2-1], ... while that grows; the candidate that ends at e is the first position where reach attains
+// e.  One scan gives every token reach[] and the piece it lies in; a token then walks its piece's ends.
 struct FloatOp {
   struct T {
-    uint32_t reach, latest, reset;  // max ext1; 1 + position of the latest candidate; piece contains a run start
+    uint32_t reach;  // max ext1
+    uint32_t piece;  // 1 + the latest candidate x with (the largest ext1 before x in this stretch) <= x; 0: none
+    uint32_t reset;  // the stretch contains a run start
   };
-  const uint64_t *hash;
   const uint32_t *run_off;
   const uint32_t *ext1;
-  uint32_t *reach_out;      // [N]
-  uint64_t *hash_late_out;  // nullable
-  uint32_t *late_off_out;   // nullable
-  uint64_t base;
+  uint32_t *reach_out;  // [N]
+  uint32_t *piece_out;  // [N]: 1 + the candidate at which the piece of covered text around the token begins
   uint32_t N;
 
   static __device__ __forceinline__ T identity() { return T{0u, 0u, 0u}; }
+  // A candidate of the right stretch begins a piece iff nothing before it reaches beyond it; only the latest such
+  // candidate is wanted, and if that one fails against the left stretch's reach every earlier one of the right
+  // stretch fails too (they are smaller), so one position per stretch is all that has to be carried.
   static __device__ __forceinline__ T combine(T f, T g) {
     if (g.reset) return g;
-    return T{f.reach > g.reach ? f.reach : g.reach, f.latest > g.latest ? f.latest : g.latest, f.reset};
+    return T{f.reach > g.reach ? f.reach : g.reach, (g.piece != 0 && g.piece - 1 >= f.reach) ? g.piece : f.piece, f.reset};
   }
   __device__ __forceinline__ uint32_t count() const { return N; }
   __device__ __forceinline__ T load(uint32_t i) const {
@@ -103,46 +115,58 @@ struct FloatOp {
   }
   __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
     reach_out[i] = incl.reach;
-    uint64_t key = CP_HASH_NONE;
-    uint32_t lo = 0xFFFFFFFFu;
-    if (hash[i] != CP_HASH_NONE && incl.latest != 0) {
-      const uint32_t a = incl.latest - 1;
-      key = substring_key(hash, base, a, i);
-      lo = i - a;
-    }
-    if (hash_late_out) hash_late_out[i] = key;
-    if (late_off_out) late_off_out[i] = lo;
+    piece_out[i] = incl.piece;
   }
   __device__ __forceinline__ void finish(T) const {}
 };
 
-// First candidate stream: the earliest candidate whose stored text reaches token i, taken only if it
-// starts on text that no earlier candidate reaches.  reach[] is non-decreasing inside a run, so the
-// earliest candidate with reach > i is where reach[] first exceeds i: a bisection over the run so far.
-__global__ __launch_bounds__(256) void early_key_kernel(const uint64_t *__restrict__ hash,
-                                                        const uint32_t *__restrict__ run_off,
-                                                        const uint32_t *__restrict__ reach, uint32_t N, uint64_t base,
-                                                        uint64_t *__restrict__ hash_early_out,
-                                                        uint32_t *__restrict__ early_off_out) {
+// First position p in (lo, hi] with reach[p] >= v, given reach[lo] < v <= reach[hi] (reach never decreases inside a run).
+__device__ __forceinline__ uint32_t first_reaching(const uint32_t *__restrict__ reach, uint32_t lo, uint32_t hi, uint32_t v) {
+  while (hi - lo > 1) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    if (reach[mid] >= v) hi = mid; else lo = mid;
+  }
+  return hi;
+}
+
+// Per token: the chosen candidate whose text it lies in (primary), and the next chosen candidate of the piece if
+// that one's text has begun at or before the token (the two overlap there); their keys go to the two streams.
+__global__ __launch_bounds__(256) void stream_keys_kernel(const uint64_t *__restrict__ hash,
+                                                          const uint32_t *__restrict__ run_off,
+                                                          const uint32_t *__restrict__ reach,
+                                                          const uint32_t *__restrict__ piece, uint32_t N, uint64_t base,
+                                                          uint64_t *__restrict__ hash_a_out, uint32_t *__restrict__ off_a_out,
+                                                          uint64_t *__restrict__ hash_b_out, uint32_t *__restrict__ off_b_out) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= N) return;
-  uint64_t key = CP_HASH_NONE;
-  uint32_t eo = 0xFFFFFFFFu;
+  uint64_t key[2] = {CP_HASH_NONE, CP_HASH_NONE};
+  uint32_t so[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
   const uint32_t ro = run_off[i];
-  if (hash[i] != CP_HASH_NONE && ro != 0xFFFFFFFFu && ro > 0 && reach[i] > i) {
-    uint32_t lo = i - ro, hi = i;  // reach[lo] = 0 (run start), reach[hi] > i
-    while (hi - lo > 1) {
-      const uint32_t mid = lo + (hi - lo) / 2;
-      if (reach[mid] > i) hi = mid; else lo = mid;
+  if (hash[i] != CP_HASH_NONE && ro != 0xFFFFFFFFu && ro > 0 && reach[i] > i && piece[i] != 0) {  // some candidate covers i
+    const uint32_t g = piece[i] - 1;
+    // ends of the chosen candidates' texts, one after the other, until one lies beyond i
+    uint32_t c = g, before = g, e = reach[g], k = 0;  // reach[g] = ext1[g]: nothing earlier reaches beyond g
+    while (e <= i) {  // token e is covered (the piece goes on to i), so a candidate before it reaches beyond it
+      before = e;
+      e = reach[e - 1];
+      ++k;
     }
-    const uint32_t a = hi;        // a candidate: reach[] rises only at candidates
-    if (reach[a - 1] <= a) {      // no earlier candidate's text reaches token a
-      key = substring_key(hash, base, a, i);
-      eo = i - a;
+    if (k) c = first_reaching(reach, c, before - 1, e);  // the chosen candidate that ends at e: after g, before `before`
+    key[k & 1] = substring_key(hash, base, c, i);
+    so[k & 1] = i - c;
+    const uint32_t further = reach[e - 1];  // e - 1 >= i is a token of the run
+    if (further > e) {
+      const uint32_t c2 = first_reaching(reach, c, e - 1, further);
+      if (c2 <= i) {
+        key[(k + 1) & 1] = substring_key(hash, base, c2, i);
+        so[(k + 1) & 1] = i - c2;
+      }
     }
   }
-  hash_early_out[i] = key;
-  if (early_off_out) early_off_out[i] = eo;
+  hash_a_out[i] = key[0];
+  if (off_a_out) off_a_out[i] = so[0];
+  if (hash_b_out) hash_b_out[i] = key[1];
+  if (off_b_out) off_b_out[i] = so[1];
 }
 
 // Keys under which a batch is stored when every text is kept once (Sec. 4.3.5 "Lifecycle management").
@@ -244,28 +268,29 @@ extern "C" int32_t cp_hash_probe(void *stream, const uint32_t *tok, const uint8_
 
 extern "C" int32_t cp_hash_floating(void *stream_, cp_table table, const uint8_t *slot_anchor, uint32_t n_pool_slots,
                                     const uint64_t *hash, const uint32_t *run_off, uint32_t N, uint64_t base,
-                                    uint32_t W, uint64_t *hash_early_out, uint32_t *early_off_out,
-                                    uint64_t *hash_late_out, uint32_t *late_off_out, void *scratch,
-                                    size_t scratch_bytes) {
+                                    uint32_t W, uint64_t *hash_a_out, uint32_t *off_a_out, uint64_t *hash_b_out,
+                                    uint32_t *off_b_out, void *scratch, size_t scratch_bytes) {
   using namespace cp;
   hipStream_t stream = (hipStream_t)stream_;
   if (N == 0) return CP_OK;
   if (N >= 0x80000000u) return CP_ERR_UNSUPPORTED;
   if (n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
-  if (W == 0 || !slot_anchor || !hash || !run_off || !hash_early_out || !scratch || !aligned(scratch, 256) ||
-      !aligned(hash, 8) || !aligned(hash_early_out, 8) || !aligned(hash_late_out, 8))
+  if (W == 0 || !slot_anchor || !hash || !run_off || !hash_a_out || !scratch || !aligned(scratch, 256) ||
+      !aligned(hash, 8) || !aligned(hash_a_out, 8) || !aligned(hash_b_out, 8))
     return CP_ERR_INVALID_ARG;
   if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
   Scratch sc(scratch, scratch_bytes);
   FloatOp::T *agg = sc.take<FloatOp::T>(div_up(N, kScanTile) + 1);
   uint32_t *ext1 = sc.take<uint32_t>(N);
   uint32_t *reach = sc.take<uint32_t>(N);
-  if (!agg || !ext1 || !reach) return CP_ERR_SCRATCH;
+  uint32_t *piece = sc.take<uint32_t>(N);
+  if (!agg || !ext1 || !reach || !piece) return CP_ERR_SCRATCH;
   if (int32_t rc = launch_anchor_extents(stream, table, slot_anchor, n_pool_slots, hash, run_off, N, W, base, ext1))
     return rc;
-  FloatOp op{hash, run_off, ext1, reach, hash_late_out, late_off_out, base, N};
+  FloatOp op{run_off, ext1, reach, piece, N};
   if (int32_t rc = run_scan<FloatOp>(stream, op, N, agg)) return rc;
-  early_key_kernel<<<div_up(N, 256), 256, 0, stream>>>(hash, run_off, reach, N, base, hash_early_out, early_off_out);
+  stream_keys_kernel<<<div_up(N, 256), 256, 0, stream>>>(hash, run_off, reach, piece, N, base, hash_a_out, off_a_out,
+                                                         hash_b_out, off_b_out);
   return check_launch();
 }
 

@@ -114,9 +114,9 @@ class GpuLookup:
     flags: int
     dst: torch.Tensor  # uint8 device tensor, layer-major [L][2][N][row_bytes]
     served: np.ndarray = None  # slots after the pool's policies (= slot without policies)
-    hash_float: np.ndarray = None  # pools with floating anchors only: keys of the earliest-candidate stream
+    hash_float: np.ndarray = None  # pools with floating anchors only: keys of candidate stream a
     run_off: np.ndarray = None
-    hash_late: np.ndarray = None  # ... and of the latest-candidate stream
+    hash_late: np.ndarray = None  # ... and of candidate stream b
 
 
 def lookup(st: GpuState, tok=None, mask=None, off=None, max_spans=None, gather=True) -> GpuLookup:

@@ -52,7 +52,7 @@ class LookupBuffers:
         self.max_spans = N if max_spans is None else max_spans
         i32, i64 = torch.int32, torch.int64
         self.hash = torch.empty(N, dtype=i64, device=device)
-        # floating anchors (if the pool uses them): keys of the earliest-candidate and the latest-candidate stream
+        # floating anchors (if the pool uses them): keys of the two candidate streams (hash_float: stream a, hash_late: stream b)
         self.hash_float = torch.empty(N, dtype=i64, device=device)
         self.hash_late = torch.empty(N, dtype=i64, device=device)
         self.run_off = torch.empty(N, dtype=i32, device=device)
@@ -60,7 +60,7 @@ class LookupBuffers:
         self.late_off = torch.empty(N, dtype=i32, device=device)
         self.cand = torch.empty(N, dtype=i32, device=device)  # unconfirmed slots (pools that verify)
         self.slot = torch.empty(N, dtype=i32, device=device)  # slot of every matched token
-        # what each key stream alone found / accepted (run-start keys, earliest candidate, latest candidate)
+        # what each key stream alone found / accepted (run-start keys, candidate stream a, candidate stream b)
         self.stream_slot = [torch.empty(N, dtype=i32, device=device) for _ in range(3)]
         # storing every text once: key, offset in its stored text and "the pool has it" per token
         self.ins_hash = torch.empty(N, dtype=i64, device=device)
@@ -187,8 +187,8 @@ class KVPool:
         keys = [(buf.hash, buf.run_off)]
         if self.slot_anchor is not None:
             B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off, self.anchor_window,
-                               buf.hash_float, buf.scratch, stream=stream, early_off_out=buf.float_off,
-                               hash_late_out=buf.hash_late, late_off_out=buf.late_off)
+                               buf.hash_float, buf.scratch, stream=stream, off_a_out=buf.float_off,
+                               hash_b_out=buf.hash_late, off_b_out=buf.late_off)
             keys += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
         if self.verify:
             for k, (key, seg_off) in enumerate(keys):

@@ -58,6 +58,27 @@ def test_overlapping_and_nested_candidates(G):
     compare_all(G, wl, anchor_window=2, verify=True)
 
 
+def test_a_staircase_of_overlapping_texts_is_served_whole(G):
+    """Seven stored texts, each 25 tokens of one 85-token sequence, ten tokens apart: up to three of them cover
+    a token of a request that quotes the sequence.  Every token from the first text's start on is served, the
+    chosen texts alternate between the two candidate streams, and verification confirms each on its own."""
+    rng = np.random.default_rng(78)
+    V = lambda n: rng.integers(0, 32000, n).astype(np.uint32)  # noqa: E731
+    seq = V(85)
+    donors = [seq[k:k + 25] for k in range(0, 61, 10)]
+    reqs = [np.concatenate([V(4), seq, V(3)]), np.concatenate([V(2), seq[10:70]]), np.concatenate([seq[5:80], V(6)])]
+    wl = gen.from_prompts("staircase", 0xC0FFEE22, gen.KVShape(2, 2, 64), donors, reqs, pool_slots=512)
+    for W, verify in ((1, False), (3, False), (8, True)):
+        ost, olk, gst, glk = compare_all(G, wl, anchor_window=W, verify=verify)
+        o = wl.off
+        assert (glk.slot[o[0] + 4:o[0] + 4 + 85] != NONE).all() and (glk.slot[o[0] + 89:o[0] + 92] == NONE).all()
+        assert (glk.slot[o[1] + 2:o[1] + 62] != NONE).all()
+        # the third request starts inside the first stored text: served from the second text's start (token 10) on
+        assert (glk.slot[o[2]:o[2] + 5] == NONE).all() and (glk.slot[o[2] + 5:o[2] + 75] != NONE).all()
+        both = (olk.hash_float != O.HASH_NONE) & (olk.hash_late != O.HASH_NONE)
+        assert both.sum() >= 3 * 15  # where consecutive chosen texts overlap, a token has a key in either stream
+
+
 def test_window_longer_than_every_run(G):
     wl = small_float(scale=0.125)
     ost, olk, gst, glk = compare_all(G, wl, anchor_window=100000)
