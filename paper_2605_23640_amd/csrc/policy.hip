@@ -86,19 +86,23 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Workgroup b takes tokens b, b + grid, ...: unmatched tokens come in long stretches (a request's own
 // text), striding spreads them over the grid.  All rows of an unmatched token are set to zero with
-// 16-byte non-temporal stores.
+// 16-byte non-temporal stores; the 256 lanes walk the token's (row, 16-byte column) space row-major, so
+// every lane stores at every step whatever the row length.
 __global__ __launch_bounds__(256) void fill_unmatched_kernel(const uint32_t *__restrict__ slot, uint32_t N,
                                                              uint8_t *__restrict__ dst, cp_kv_layout l) {
-  const uint32_t vec_per_row = l.n_kv_heads * l.head_dim * 2 / 16;
-  const uint32_t rows = l.n_layers * 2;
+  const uint32_t vpr = l.n_kv_heads * l.head_dim * 2 / 16;  // vectors per row
+  const uint32_t n_vec = l.n_layers * 2 * vpr;
+  const uint32_t r_step = 256 / vpr, c_step = 256 % vpr;
   const u32x4 zero = {0u, 0u, 0u, 0u};
   for (uint32_t t = blockIdx.x; t < N; t += gridDim.x) {
     if (slot[t] != kNone) continue;  // same for the whole workgroup
     uint8_t *tok = dst + (uint64_t)t * l.tok_stride;
-    for (uint32_t row = 0; row < rows; ++row) {
-      uint8_t *p = tok + (uint64_t)(row >> 1) * l.layer_stride + (uint64_t)(row & 1) * l.kv_stride;
-      for (uint32_t c = threadIdx.x; c < vec_per_row; c += blockDim.x)
-        __builtin_nontemporal_store(zero, (u32x4 *)(p + (uint64_t)c * 16));
+    uint32_t r = threadIdx.x / vpr, c = threadIdx.x % vpr;
+    for (uint32_t v = threadIdx.x; v < n_vec; v += 256) {
+      uint8_t *p = tok + (uint64_t)(r >> 1) * l.layer_stride + (uint64_t)(r & 1) * l.kv_stride + (uint64_t)c * 16;
+      __builtin_nontemporal_store(zero, (u32x4 *)p);
+      r += r_step, c += c_step;
+      if (c >= vpr) c -= vpr, r += 1;
     }
   }
 }
