@@ -355,8 +355,9 @@ __global__ __launch_bounds__(256) void gather_heads_kernel(const MoveItem *__res
 //   - the 256 mover lanes walk the (row, 16-byte column) space row-major; a round is U vectors per lane:
 //     all of a round's loads are issued before its first store, and a vector goes to all of its
 //     destinations before the next vector is touched.  Rows alternate K, V; with RoPE a lane rotates the
-//     vectors of its K rows (for the Llama shapes a wavefront holds only K or only V rows, so two SIMDs
-//     rotate while two copy).
+//     vectors of its K rows.  For the Llama shapes a step of the 256 lanes is exactly one K row and one V row,
+//     so a rotating gather swaps the two between the halves of the workgroup on every other step: each
+//     wavefront then rotates half of its vectors instead of two wavefronts rotating all of theirs.
 // Every wavefront executes exactly one barrier per unit and leaves when the scout reports that the
 // counter has passed the item count, which every workgroup's scout eventually sees.
 // Items that reach the mover name a destination inside `to`: cp_gather_kv's expansion and
