@@ -100,7 +100,8 @@ __device__ __forceinline__ uint64_t pow_u64(uint64_t b, uint32_t k) {  // b^k mo
 // live slot carries the anchor mark.)  Step 2's pre-check: how far does the stored text go on?  The key
 // of tokens a..t follows in O(1) from the run's chain hashes and a power of the base; stored runs are
 // closed under taking prefixes, so "key of a..t is stored" is true up to some last token and false
-// beyond it: that token is found by doubling steps and bisection, about 2 log2(length) lookups.
+// beyond it: that token is found by growing steps and then narrowing, 16 tokens looked up per round (one by each
+// lane of the group), about 2 log16(length) + 1 rounds.
 // ext1[a] = 1 + last token whose key from a is stored, 0 if a is no candidate.
 __global__ __launch_bounds__(kProbeThreads) void anchor_extent_kernel(cp_table table,
                                                                       const uint8_t *__restrict__ slot_anchor,
@@ -125,32 +126,39 @@ __global__ __launch_bounds__(kProbeThreads) void anchor_extent_kernel(cp_table t
   }
   const uint32_t s = group_lookup(table, wh);
   const bool cand = s < n_pool_slots && slot_anchor[s] != 0;
-  // lo = last token known to be stored from a, hi = first token known not to be (0 = none known yet)
-  uint32_t lo = end, hi = 0, step = 1;
+  // lo = last token known to be stored from a, hi = first token known not to be (0 = none known yet).  Every round
+  // the 16 lanes of the group look 16 tokens up at once, lane j the token lo + (j + 1) * stride by itself: as long
+  // as all are stored the stride grows sixteenfold, then the gap between lo and hi shrinks seventeenfold per round.
+  const uint32_t sub = threadIdx.x & (kBucket - 1);
+  uint32_t lo = end, hi = 0, stride = 1;
   bool searching = cand;
   while (__any(searching)) {  // wavefront-uniform loop; groups drop out one by one
     uint64_t key = CP_HASH_NONE;
-    uint32_t t = 0;
     if (searching) {
-      const uint64_t t64 = hi ? (uint64_t)lo + (hi - lo) / 2 : (uint64_t)lo + step;
-      // token t continues the run of the window iff its offset in the run says so
-      if (t64 < N && run_off[(uint32_t)t64] == ro_end + (uint32_t)(t64 - end)) {
-        t = (uint32_t)t64;
+      const uint64_t t64 = (uint64_t)lo + (uint64_t)(sub + 1) * stride;
+      // token t continues the run of the window iff its offset in the run says so; beyond the run, the batch, or a
+      // token already known not to be stored: not stored
+      if (t64 < N && (hi == 0 || t64 < hi) && run_off[(uint32_t)t64] == ro_end + (uint32_t)(t64 - end)) {
+        const uint32_t t = (uint32_t)t64;
         key = hash[t] - before * pow_u64(base, t - a + 1);
         if (key == CP_HASH_NONE) key = CP_HASH_NONE - 1;
-      } else {
-        t = (uint32_t)(t64 < N ? t64 : N);  // beyond the run (or the batch): not stored
       }
     }
-    const bool stored = group_lookup(table, key) != CP_SLOT_NONE;
+    const bool stored = lane_lookup(table, key) != CP_SLOT_NONE;
+    // stored runs are closed under taking prefixes: the lanes that found their key are the first k of the group
+    const uint32_t found = group_bits(__ballot(searching && stored));
+    const uint32_t k = (uint32_t)__ffs((int)~found) - 1;  // 16 if all found (bit 16 of ~found is set)
     if (searching) {
-      if (stored) {
-        lo = t;
-        if (!hi) step = step < 0x40000000u ? step * 2 : step;
+      const uint64_t first_missing = (uint64_t)lo + (uint64_t)(k + 1) * stride;
+      lo += k * stride;
+      if (k < kBucket && (hi == 0 || first_missing < hi)) hi = (uint32_t)(first_missing < 0xFFFFFFFFull ? first_missing : 0xFFFFFFFFull);
+      if (hi == 0) {
+        stride = stride < (1u << 26) ? stride * kBucket : stride;
+      } else if (hi - lo <= 1) {
+        searching = false;
       } else {
-        hi = t;
+        stride = (hi - lo + kBucket) / (kBucket + 1);
       }
-      if (hi && hi - lo <= 1) searching = false;
     }
   }
   if (a < N && (threadIdx.x & (kBucket - 1)) == 0) ext1[a] = cand ? lo + 1 : 0u;
