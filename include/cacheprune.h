@@ -8,7 +8,8 @@
  *
  * and, further down, the calls that widen it to the paper's retrieval and pool
  * life cycle: floating anchors (cp_hash_runs, cp_insert_anchors, cp_hash_floating,
- * cp_probe2, cp_probe3), exact confirmation of matches (cp_insert_kv_chain, cp_verify_chain),
+ * cp_probe2, cp_probe3), exact confirmation of matches (cp_insert_kv_chain, cp_verify_chain,
+ * cp_verify_streams),
  * one copy of stored text (cp_insert_keys, cp_insert_kv_dedup), pool policies
  * (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch, cp_lru_threshold, cp_evict,
  * cp_table_compact) and the KV annotator (cp_sat_build, cp_annotate).
@@ -252,6 +253,20 @@ int32_t cp_insert_kv_chain(void *stream, cp_table table, const uint64_t *hash, c
 int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand, uint32_t N,
                         const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots, int32_t merge,
                         uint32_t *slot_out, uint32_t *stream_out, void *scratch, size_t scratch_bytes);
+
+/* cp_verify_streams: the three key streams of a lookup with floating anchors confirmed in one call -
+ * what cp_probe + cp_verify_chain per stream and the merge in serving order give, in three launches
+ * instead of eight.  Stream 0: run-start keys, candidates cand_0 already looked up (cp_hash_probe),
+ * offsets seg_off_0 = run_off.  Streams a and b: keys and offsets of cp_hash_floating, looked up here.
+ * slot_out[i] = the slot of the first stream (0, a, b) that accepts token i, else CP_SLOT_NONE;
+ * stream_out_0 / _a / _b (each may be NULL): every stream's own result (for cp_touch and
+ * cp_insert_keys).  cand_0 must not alias an output. */
+int32_t cp_verify_streams(void *stream, cp_table table, const uint32_t *tok, uint32_t N, const uint32_t *seg_off_0,
+                          const uint32_t *cand_0, const uint64_t *key_a, const uint32_t *seg_off_a,
+                          const uint64_t *key_b, const uint32_t *seg_off_b, const uint32_t *slot_tok,
+                          const uint32_t *slot_parent, uint32_t n_pool_slots, uint32_t *slot_out,
+                          uint32_t *stream_out_0, uint32_t *stream_out_a, uint32_t *stream_out_b, void *scratch,
+                          size_t scratch_bytes);
 
 /* Run-length pass: turn per-token slots into copy descriptors (the "token
  * spans" of the retriever's metadata, Sec. 4.3.1).  A span is a maximal run of

@@ -32,7 +32,7 @@ EXPORTS = [
     "cp_hash_segments", "cp_probe", "cp_hash_probe", "cp_build_spans", "cp_gather_kv", "cp_gather_kv_static", "cp_insert_kv",
     "cp_event_create", "cp_event_elapsed_ms", "cp_event_destroy",
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2", "cp_probe3",
-    "cp_insert_kv_chain", "cp_verify_chain", "cp_insert_keys", "cp_insert_kv_dedup",
+    "cp_insert_kv_chain", "cp_verify_chain", "cp_verify_streams", "cp_insert_keys", "cp_insert_kv_dedup",
     "cp_filter_matches", "cp_mark_recompute", "cp_fill_unmatched", "cp_touch", "cp_lru_threshold", "cp_evict",
     "cp_table_compact", "cp_sat_scratch_bytes", "cp_sat_build", "cp_annotate",
 ]
@@ -137,6 +137,8 @@ def lib():
                                          u32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.cp_verify_chain.restype = i32
         L.cp_verify_chain.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, i32, vp, vp, vp, sz]
+        L.cp_verify_streams.restype = i32
+        L.cp_verify_streams.argtypes = [vp, TableStruct, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, vp, vp, vp, vp, sz]
         L.cp_filter_matches.restype = i32
         L.cp_filter_matches.argtypes = [vp, vp, vp, u32, u32, u32, vp, u32, vp, vp, sz]
         L.cp_mark_recompute.restype = i32
@@ -311,6 +313,21 @@ def cp_hash_floating(table: Table, slot_anchor, n_pool_slots, hashes, run_off, W
                                                       _ptr(hash_a_out), _ptr(off_a_out), _ptr(hash_b_out),
                                                       _ptr(off_b_out), _ptr(scratch), scratch.numel()))
     return hash_a_out
+
+
+def cp_verify_streams(table: Table, tok, seg_off_0, cand_0, key_a, seg_off_a, key_b, seg_off_b, slot_tok, slot_parent,
+                      n_pool_slots, slot_out, scratch, stream=None, stream_out=(None, None, None)):
+    _need_cuda(tok, seg_off_0, cand_0, key_a, seg_off_a, key_b, seg_off_b, slot_tok, slot_parent, slot_out, scratch,
+               *stream_out)
+    N = tok.numel()
+    for t in (seg_off_0, cand_0, key_a, seg_off_a, key_b, seg_off_b, slot_out):
+        assert t.numel() == N
+    assert slot_tok.numel() >= n_pool_slots and slot_parent.numel() >= n_pool_slots and len(stream_out) == 3
+    _check("cp_verify_streams", lib().cp_verify_streams(
+        _stream(stream), table.struct, _ptr(tok), N, _ptr(seg_off_0), _ptr(cand_0), _ptr(key_a), _ptr(seg_off_a),
+        _ptr(key_b), _ptr(seg_off_b), _ptr(slot_tok), _ptr(slot_parent), n_pool_slots, _ptr(slot_out),
+        _ptr(stream_out[0]), _ptr(stream_out[1]), _ptr(stream_out[2]), _ptr(scratch), scratch.numel()))
+    return slot_out
 
 
 def cp_verify_chain(tok, seg_off, cand, slot_tok, slot_parent, n_pool_slots, merge, slot_out, scratch, stream=None,

@@ -67,6 +67,10 @@ int32_t launch_scatter(hipStream_t stream, const void *src, const cp_kv_layout &
 int32_t launch_span_offsets(hipStream_t stream, const uint32_t *span_len, const uint32_t *n_spans, uint32_t max_spans,
                             uint32_t *span_off, uint32_t *agg);
 
+// out_a[i], out_b[i] = slot stored under hash_a[i], hash_b[i] (CP_SLOT_NONE if absent): two lookups per token, one launch.
+int32_t launch_probe_each(hipStream_t stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b,
+                          uint32_t N, uint32_t *out_a, uint32_t *out_b);
+
 // ext1[a] = 1 + the last token t such that the key of tokens a..t is stored, for every position a that is a
 // candidate (a W-token window starting at a, inside one run and after the run's first token, hashes to a
 // key of `table` whose slot carries an anchor mark); 0 for every other position.

@@ -83,6 +83,20 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(cp_table t, const 
   if (q < N && (threadIdx.x & (kBucket - 1)) == 0) slot_out[q] = result;
 }
 
+// Two key arrays looked up side by side, each into an output of its own (the candidates of two key streams).
+__global__ __launch_bounds__(kProbeThreads) void probe_each_kernel(cp_table t, const uint64_t *__restrict__ hash_a,
+                                                                   const uint64_t *__restrict__ hash_b, uint32_t N,
+                                                                   uint32_t *__restrict__ out_a,
+                                                                   uint32_t *__restrict__ out_b) {
+  const uint32_t q = (uint32_t)(((uint64_t)blockIdx.x * kProbeThreads + threadIdx.x) / kBucket);
+  const uint32_t ra = group_lookup(t, q < N ? hash_a[q] : CP_HASH_NONE);
+  const uint32_t rb = group_lookup(t, q < N ? hash_b[q] : CP_HASH_NONE);
+  if (q < N && (threadIdx.x & (kBucket - 1)) == 0) {
+    out_a[q] = ra;
+    out_b[q] = rb;
+  }
+}
+
 __device__ __forceinline__ uint64_t pow_u64(uint64_t b, uint32_t k) {  // b^k mod 2^64
   uint64_t r = 1;
   while (k) {
@@ -469,6 +483,14 @@ extern "C" int32_t cp_insert_anchors(void *stream, const uint32_t *run_off, cons
 }
 
 namespace cp {
+int32_t launch_probe_each(hipStream_t stream, cp_table table, const uint64_t *hash_a, const uint64_t *hash_b,
+                          uint32_t N, uint32_t *out_a, uint32_t *out_b) {
+  if (int32_t rc = table_ok(table)) return rc;
+  probe_each_kernel<<<div_up((uint64_t)N * kBucket, kProbeThreads), kProbeThreads, 0, stream>>>(table, hash_a, hash_b, N,
+                                                                                              out_a, out_b);
+  return check_launch();
+}
+
 int32_t launch_anchor_extents(hipStream_t stream, const cp_table &table, const uint8_t *slot_anchor,
                               uint32_t n_pool_slots, const uint64_t *hash, const uint32_t *run_off, uint32_t N,
                               uint32_t W, uint64_t base, uint32_t *ext1) {

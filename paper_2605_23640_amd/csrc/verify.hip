@@ -54,6 +54,54 @@ struct ChainOp {
   __device__ __forceinline__ void finish(T) const {}
 };
 
+// The three key streams of a lookup with floating anchors (run-start keys, candidate stream a, candidate stream
+// b) confirmed in one scan: two bits per stream, each stream's prefix AND independent of the others.  A token
+// is served from the first stream that accepts it.
+struct ChainOp3 {
+  using T = uint32_t;  // bits 2s, 2s+1: stream s's "failed since the segment start" and "holds a segment start"
+  const uint32_t *tok;
+  const uint32_t *seg_off[3];
+  const uint32_t *cand[3];
+  const uint32_t *slot_tok;
+  const uint32_t *slot_parent;
+  uint32_t *slot_out;
+  uint32_t *stream_out[3];  // nullable, each
+  uint32_t N, n_pool_slots;
+
+  static __device__ __forceinline__ T identity() { return 0u; }
+  static __device__ __forceinline__ T combine(T f, T g) {
+    const uint32_t starts = (g >> 1) & 0x15u;           // bit 2s set where g's stream s holds a segment start
+    return g | (f & ~(starts | (starts << 1)) & 0x3Fu);  // there g stands alone, elsewhere the failures add up
+  }
+  __device__ __forceinline__ uint32_t count() const { return N; }
+  __device__ __forceinline__ T one(uint32_t s, uint32_t i) const {
+    const uint32_t k = seg_off[s][i];
+    if (k == 0xFFFFFFFFu) return 3u;  // in no segment: fails, and nothing carries over it
+    const uint32_t c = cand[s][i];
+    bool ok = c < n_pool_slots;
+    uint32_t want_parent = CP_SLOT_NONE;
+    if (k != 0) {
+      ok = ok && i != 0 && seg_off[s][i - 1] == k - 1;  // offsets must count up along the segment
+      want_parent = ok ? cand[s][i - 1] : CP_SLOT_NONE;
+      ok = ok && want_parent < n_pool_slots;
+    }
+    ok = ok && slot_tok[c] == tok[i] && slot_parent[c] == want_parent;
+    return (ok ? 0u : 1u) | (k == 0 ? 2u : 0u);
+  }
+  __device__ __forceinline__ T load(uint32_t i) const { return one(0, i) | (one(1, i) << 2) | (one(2, i) << 4); }
+  __device__ __forceinline__ void store(uint32_t i, T, T incl) const {
+    uint32_t served = CP_SLOT_NONE;
+#pragma unroll
+    for (int s = 2; s >= 0; --s) {
+      const uint32_t r = ((incl >> (2 * s)) & 1u) ? CP_SLOT_NONE : cand[s][i];
+      if (stream_out[s]) stream_out[s][i] = r;
+      if (r != CP_SLOT_NONE) served = r;  // the earliest stream that accepts the token wins
+    }
+    slot_out[i] = served;
+  }
+  __device__ __forceinline__ void finish(T) const {}
+};
+
 }  // namespace
 
 int32_t launch_chain_verify(hipStream_t stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
@@ -82,4 +130,31 @@ extern "C" int32_t cp_verify_chain(void *stream, const uint32_t *tok, const uint
   if (!agg) return CP_ERR_SCRATCH;
   return launch_chain_verify((hipStream_t)stream, tok, seg_off, cand, N, slot_tok, slot_parent, n_pool_slots,
                              merge ? 1u : 0u, slot_out, stream_out, agg, nullptr);
+}
+
+extern "C" int32_t cp_verify_streams(void *stream_, cp_table table, const uint32_t *tok, uint32_t N,
+                                     const uint32_t *seg_off_0, const uint32_t *cand_0, const uint64_t *key_a,
+                                     const uint32_t *seg_off_a, const uint64_t *key_b, const uint32_t *seg_off_b,
+                                     const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots,
+                                     uint32_t *slot_out, uint32_t *stream_out_0, uint32_t *stream_out_a,
+                                     uint32_t *stream_out_b, void *scratch, size_t scratch_bytes) {
+  using namespace cp;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (N == 0) return CP_OK;
+  if (N >= 0x80000000u || n_pool_slots >= 0x80000000u) return CP_ERR_UNSUPPORTED;
+  if (!tok || !seg_off_0 || !cand_0 || !key_a || !seg_off_a || !key_b || !seg_off_b || !slot_tok || !slot_parent ||
+      !slot_out || !scratch || !aligned(scratch, 256) || !aligned(key_a, 8) || !aligned(key_b, 8))
+    return CP_ERR_INVALID_ARG;
+  if (cand_0 == slot_out || cand_0 == stream_out_0 || cand_0 == stream_out_a || cand_0 == stream_out_b)
+    return CP_ERR_INVALID_ARG;  // neighbours read cand while results are written
+  if (scratch_bytes < cp_scratch_bytes(N, 0, 0)) return CP_ERR_SCRATCH;
+  Scratch sc(scratch, scratch_bytes);
+  uint32_t *agg = sc.take<uint32_t>(div_up(N, kScanTile) + 1);
+  uint32_t *cand_a = sc.take<uint32_t>(N);
+  uint32_t *cand_b = sc.take<uint32_t>(N);
+  if (!agg || !cand_a || !cand_b) return CP_ERR_SCRATCH;
+  if (int32_t rc = launch_probe_each(stream, table, key_a, key_b, N, cand_a, cand_b)) return rc;
+  ChainOp3 op{tok, {seg_off_0, seg_off_a, seg_off_b}, {cand_0, cand_a, cand_b}, slot_tok, slot_parent, slot_out,
+              {stream_out_0, stream_out_a, stream_out_b}, N, n_pool_slots};
+  return run_scan<ChainOp3>(stream, op, N, agg);
 }

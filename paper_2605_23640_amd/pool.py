@@ -190,13 +190,14 @@ class KVPool:
                                buf.hash_float, buf.scratch, stream=stream, off_a_out=buf.float_off,
                                hash_b_out=buf.hash_late, off_b_out=buf.late_off)
             keys += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
-        if self.verify:
-            for k, (key, seg_off) in enumerate(keys):
-                if k > 0:
-                    B.cp_probe(self.table, key, buf.cand, stream=stream)
-                B.cp_verify_chain(tok, seg_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, k > 0,
-                                  buf.slot, buf.scratch, stream=stream,
-                                  stream_out=buf.stream_slot[k] if per_stream else None)
+        if self.verify and len(keys) == 3:  # the three streams confirmed in one pass
+            B.cp_verify_streams(self.table, tok, buf.run_off, buf.cand, buf.hash_float, buf.float_off, buf.hash_late,
+                                buf.late_off, self.slot_tok, self.slot_parent, self.n_slots, buf.slot, buf.scratch,
+                                stream=stream, stream_out=buf.stream_slot if per_stream else (None, None, None))
+        elif self.verify:
+            B.cp_verify_chain(tok, buf.run_off, buf.cand, self.slot_tok, self.slot_parent, self.n_slots, False,
+                              buf.slot, buf.scratch, stream=stream,
+                              stream_out=buf.stream_slot[0] if per_stream else None)
         else:
             B.cp_probe3(self.table, buf.hash, buf.hash_float, buf.hash_late, buf.slot, stream=stream)
             if per_stream:

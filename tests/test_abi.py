@@ -78,6 +78,12 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_insert_kv_chain(None, tab, P, Q, Q, Q, 4, 1, S, 4, P, lay, P, lay, 16, P, None, None, Q, S, S, S,
                                 big, None) == INV
     assert L.cp_verify_chain(None, P, P, Q, 4, P, P, 16, 0, Q, None, S, big) == INV  # cand and slot_out are one array
+    vs = lambda **kw: L.cp_verify_streams(*[kw.get(k, v) for k, v in dict(  # noqa: E731
+        stream=None, table=tab, tok=P, N=4, seg0=P, cand0=Q, key_a=P, seg_a=P, key_b=P, seg_b=P, slot_tok=P, slot_parent=P,
+        n_slots=16, slot_out=S, so0=None, soa=None, sob=None, scratch=S, bytes=big).items()])
+    assert vs(N=0) == B.OK
+    assert vs(key_b=None) == INV and vs(cand0=S) == INV  # a stream's keys missing; cand_0 and slot_out are one array
+    assert vs(table=B.TableStruct(P, Q, 1000)) == INV and vs(bytes=16) == SCR and vs(n_slots=1 << 31) == UNS
     assert L.cp_filter_matches(None, None, Q, 4, 1, 1, None, 0, P, S, big) == INV
     assert L.cp_mark_recompute(None, P, None, 4, 16, Q) == INV
     assert L.cp_fill_unmatched(None, None, 4, P, lay) == INV

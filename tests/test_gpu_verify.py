@@ -140,3 +140,42 @@ def test_verify_chain_edge_cases(G):
     with pytest.raises(B.CpError):
         B.cp_verify_chain(q, seg, cand, slot_tok, slot_parent, 16, False, cand, scratch)
     B.cp_verify_chain(q[:0], seg[:0], cand[:0], slot_tok, slot_parent, 16, False, out[:0], scratch)
+
+
+def test_three_streams_in_one_call_equal_the_calls_one_by_one(G):
+    """cp_verify_streams against cp_probe + cp_verify_chain per stream and the merge, on a workload where all
+    three streams find something and on random candidate slots (most of which must be rejected)."""
+    import torch
+    import paper_2605_23640_amd as cp
+    B = cp.binding
+    wl = gen.make("float", scale=0.125)  # documents stored alone, quoted behind other text
+    wl.shape = gen.KVShape(1, 2, 64)
+    st = G.prefill(wl, G.make_pool(wl, anchor_window=4, verify=True))
+    pool, N = st.pool, wl.n_tokens
+    tok, mask, off = G.dev_i32(wl.tok), torch.from_numpy(wl.mask.copy()).to(G.DEV), G.dev_i32(wl.off)
+    buf = cp.LookupBuffers(N, N, G.DEV, n_pool_slots=pool.n_slots)
+    B.cp_hash_probe(tok, mask, off, pool.table, buf.hash, buf.run_off, buf.cand, buf.scratch)
+    B.cp_hash_floating(pool.table, pool.slot_anchor, pool.n_slots, buf.hash, buf.run_off, 4, buf.hash_float, buf.scratch,
+                       off_a_out=buf.float_off, hash_b_out=buf.hash_late, off_b_out=buf.late_off)
+    rng = np.random.default_rng(4)
+    for junk in (False, True):
+        cand0 = buf.cand.clone()
+        if junk:  # a third of the run-start candidates replaced by arbitrary slots
+            r = torch.from_numpy(rng.integers(0, pool.n_slots, N).astype(np.int32)).to(G.DEV)
+            pick = torch.from_numpy(rng.random(N) < 0.33).to(G.DEV)
+            cand0 = torch.where(pick, r, cand0)
+        want_slot = torch.empty(N, dtype=torch.int32, device=G.DEV)
+        want_own = [torch.empty(N, dtype=torch.int32, device=G.DEV) for _ in range(3)]
+        tmp = torch.empty(N, dtype=torch.int32, device=G.DEV)
+        for k, (key, seg) in enumerate(((None, buf.run_off), (buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off))):
+            c = cand0 if k == 0 else B.cp_probe(pool.table, key, tmp)
+            B.cp_verify_chain(tok, seg, c, pool.slot_tok, pool.slot_parent, pool.n_slots, k > 0, want_slot, buf.scratch,
+                              stream_out=want_own[k])
+        got_slot = torch.empty(N, dtype=torch.int32, device=G.DEV)
+        got_own = [torch.empty(N, dtype=torch.int32, device=G.DEV) for _ in range(3)]
+        B.cp_verify_streams(pool.table, tok, buf.run_off, cand0, buf.hash_float, buf.float_off, buf.hash_late, buf.late_off,
+                            pool.slot_tok, pool.slot_parent, pool.n_slots, got_slot, buf.scratch, stream_out=got_own)
+        torch.cuda.synchronize()
+        assert torch.equal(got_slot, want_slot) and all(torch.equal(g, w) for g, w in zip(got_own, want_own))
+        served = [(G.host_u32(w) != NONE).sum() for w in want_own]
+        assert all(x > 0 for x in served[:2]), served  # (stream b serves where two stored texts overlap: not here)
