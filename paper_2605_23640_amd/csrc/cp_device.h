@@ -12,7 +12,7 @@ namespace cp {
 
 constexpr int kWave = 64;
 constexpr int kScanThreads = 256;
-constexpr int kScanItems = 4;
+constexpr int kScanItems = 1;
 constexpr int kScanTile = kScanThreads * kScanItems;  // elements per workgroup
 
 // Last HIP error seen by a launch helper on this host thread.
@@ -94,16 +94,19 @@ __device__ __forceinline__ typename Op::T block_exclusive_scan(typename Op::T v,
 // ---- ordered scan over n = op.count() elements -------------------------------
 // Op supplies:  T, identity(), combine(a, b), count(), load(i),
 //               store(i, exclusive, inclusive), finish(total)
-// Three forms, chosen by the number of tiles (kScanTile elements each):
-//   one tile            scan_single: one workgroup, one launch
-//   up to 512 tiles     scan_reduce (per-tile totals -> agg[tile]), then scan_apply_self: every tile
-//                       combines the totals of the tiles before it by itself (at most two loads per
-//                       thread) and scans its elements; the last tile calls op.finish.  Two launches.
-//   more                scan_reduce, scan_carry (one workgroup turns agg[] into exclusive tile
-//                       prefixes and calls op.finish), scan_apply.  Three launches.
+// Three forms, chosen by the number of elements.  A tile is kScanTile = 256 elements, one per thread: these
+// scans are bound by latency, not by bytes, so small tiles (many workgroups, short dependent chains) win.
+//   up to 1024 elements  scan_single: one workgroup walks the few tiles in order.  One launch.
+//   up to 1024 tiles     scan_reduce (per-tile totals -> agg[tile]), then scan_apply_self: every tile
+//                        combines the totals of the tiles before it by itself (at most four loads per
+//                        thread) and scans its elements; the last tile calls op.finish.  Two launches.
+//   more                 scan_reduce, scan_carry (one workgroup turns agg[] into exclusive tile
+//                        prefixes and calls op.finish), scan_apply.  Three launches.
 // No form waits for another workgroup.  Tiles past the end do nothing, so the grid may be sized for
 // an upper bound of n.
-constexpr uint32_t kSelfCarryTiles = 512;
+constexpr uint32_t kSelfCarryPerThread = 4;
+constexpr uint32_t kSelfCarryTiles = kSelfCarryPerThread * kScanThreads;  // 262,144 elements
+constexpr uint32_t kSingleItems = 1024;
 
 // Scan of one tile seeded with `prefix`; returns the tile's total combined onto the prefix.
 template <class Op>
@@ -132,8 +135,9 @@ __device__ __forceinline__ typename Op::T scan_tile(const Op &op, uint32_t n, ui
 
 template <class Op>
 __global__ __launch_bounds__(kScanThreads) void scan_single(Op op) {
-  const uint32_t n = op.count();  // at most kScanTile
-  typename Op::T total = scan_tile<Op>(op, n, 0, Op::identity());
+  const uint32_t n = op.count();  // at most kSingleItems: one workgroup walks the few tiles in order
+  typename Op::T total = Op::identity();
+  for (uint64_t base = 0; base == 0 || base < n; base += kScanTile) total = scan_tile<Op>(op, n, base, total);
   if (threadIdx.x == 0) op.finish(total);
 }
 
@@ -190,12 +194,11 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_self(Op op, const typ
     return;
   }
   if (base >= n) return;
-  // totals of the tiles before this one, in order: thread t takes entries 2t and 2t + 1
-  static_assert(kSelfCarryTiles <= 2 * kScanThreads, "two entries per thread must cover every earlier tile");
+  // totals of the tiles before this one, in order: thread t takes a few consecutive entries
   T mine = Op::identity();
 #pragma unroll
-  for (uint32_t k = 0; k < 2; ++k) {
-    const uint32_t t = 2 * threadIdx.x + k;
+  for (uint32_t k = 0; k < kSelfCarryPerThread; ++k) {
+    const uint32_t t = kSelfCarryPerThread * threadIdx.x + k;
     if (t < blockIdx.x) mine = Op::combine(mine, agg[t]);
   }
   T prefix;
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_apply_self(Op op, const typ
 template <class Op>
 int32_t run_scan(hipStream_t stream, const Op &op, uint32_t max_n, typename Op::T *agg) {
   uint32_t tiles = div_up(max_n, kScanTile);
-  if (tiles <= 1) {
+  if (max_n <= kSingleItems) {
     scan_single<Op><<<1, kScanThreads, 0, stream>>>(op);
   } else if (tiles <= kSelfCarryTiles) {
     scan_reduce<Op><<<tiles, kScanThreads, 0, stream>>>(op, agg);
