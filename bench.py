@@ -39,7 +39,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # (gather_rows_kernel_<workload>.txt; annotator_<n>.txt): measurements of an earlier run of the same
 # code, not of this run, and the bench line says so next to them.
 PROFILED_TRAFFIC = {"llama3-8b": 9024672260, "rope": 9669340862, "llama3-70b": 58261219980, "frag": 17206055558,
-                    "annotator-10000-full": 895904783, "annotator-10000": 347774253}
+                    "annotator-10000-full": 895897876, "annotator-10000": 347761408}
 PROFILED_FETCH = {"llama3-8b": 3093460030, "rope": 4436977590, "llama3-70b": 25345880056, "frag": 7416194775}
 # scatter_rows_kernel of the default step (scatter_rows_kernel_<workload>.txt and the gather files): (fetched, written)
 PROFILED_SCATTER = {"llama3-8b": (1687306858, 1683347987), "rope": (7662517344, 7642108268),
