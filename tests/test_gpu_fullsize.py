@@ -186,8 +186,9 @@ def test_full_size_float_anchors_verified_policies(G):
 
 
 def test_more_than_256_scan_tiles(G):
-    """About 600,000 tokens in one batch: the ordered scans run over some 600 tiles, so their single-workgroup carry
-    pass loops over several chunks of 256 tile totals (the configurations above stay below one chunk).
+    """About 600,000 tokens in one batch: the ordered scans run over some 2,300 tiles, more than the two-launch form
+    takes, so they use the three-launch form whose single-workgroup carry pass loops over several chunks of 256 tile
+    totals (the configurations above stay within the two-launch form).
     Tiny KV rows; floating anchors, verification, minimum length and marks on, so every scan takes part."""
     from test_gpu_parity import compare_all
 
