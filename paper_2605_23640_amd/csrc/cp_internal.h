@@ -81,7 +81,7 @@ int32_t launch_anchor_extents(hipStream_t stream, const cp_table &table, const u
 // Segmented prefix AND of the per-token chain checks (see verify.hip): slot_out[i] = cand[i] if every
 // token from the start of i's segment through i is consistent with slot_tok / slot_parent, else
 // CP_SLOT_NONE; with merge only entries that are CP_SLOT_NONE are written; stream_out (nullable) gets
-// the same values without regard to merge.  agg: div_up(N, 1024) + 1 words.
+// the same values without regard to merge.  agg: one word per scan tile of N elements, + 1.
 int32_t launch_chain_verify(hipStream_t stream, const uint32_t *tok, const uint32_t *seg_off, const uint32_t *cand,
                             uint32_t N, const uint32_t *slot_tok, const uint32_t *slot_parent, uint32_t n_pool_slots,
                             uint32_t merge, uint32_t *slot_out, uint32_t *stream_out, uint32_t *agg,

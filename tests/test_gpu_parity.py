@@ -365,7 +365,7 @@ def test_insert_and_evict_on_a_stream_that_is_not_the_current_one(G):
 
 def test_hash_and_probe_in_one_pass_equal_the_two_calls(G):
     """cp_hash_probe against cp_hash_segments / cp_hash_runs followed by cp_probe, on a table at load 0.85
-    (walks over several buckets) and on batches of one tile, several tiles and more than 512 tiles."""
+    (walks over several buckets) and on batches that take the scan's one-, two- and three-launch form."""
     import paper_2605_23640_amd as cp
 
     wl = gen.make_frag(scale=1 / 32, shape=gen.KVShape(2, 2, 64))
