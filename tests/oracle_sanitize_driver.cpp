@@ -20,13 +20,14 @@ constexpr uint32_t ROW = H * D * 2, TOKB = L * 2 * ROW;
 cpo_layout token_major() { return cpo_layout{L, H, D, TOKB, 2 * ROW, ROW}; }
 cpo_layout layer_major(uint32_t n) { return cpo_layout{L, H, D, ROW, 2ull * n * ROW, (uint64_t)n * ROW}; }
 
-void life_cycle(uint32_t seed, uint32_t vocab, uint32_t W, bool rope) {
+void life_cycle(uint32_t seed, uint32_t vocab, uint32_t W, bool rope, bool dedup, uint64_t capacity) {
   std::mt19937 rng(seed);
   const uint32_t S = 180 + seed % 50;
   std::vector<uint32_t> free_list(S);
   for (uint32_t s = 0; s < S; ++s) free_list[s] = s;
   std::shuffle(free_list.begin(), free_list.end(), rng);
   cpo_index *ix = cpo_index_new();
+  if (capacity) cpo_index_rebuild(ix, capacity);  // a table so small that some batches do not fit
   cpo_anchor_set *anchors = cpo_anchor_set_new();
   cpo_text *text = cpo_text_new(S);
   std::vector<uint8_t> pool((size_t)S * TOKB, 0x5A), marks(S, 0);
@@ -54,12 +55,13 @@ void life_cycle(uint32_t seed, uint32_t vocab, uint32_t W, bool rope) {
     std::vector<uint8_t> mask(N), rec(N);
     for (uint32_t i = 0; i < N; ++i) mask[i] = rng() % 12 == 0, rec[i] = rng() % 4 == 0;
     std::vector<uint64_t> h(N), hf(N), hl(N);
-    std::vector<uint32_t> ro(N), fo(N), lo(N), cand(N), got(N), own_b(N), own_c(N), served(N);
+    std::vector<uint32_t> ro(N), fo(N), lo(N), cand(N), got(N), own_a(N), own_b(N), own_c(N), served(N);
     cpo_hash_segments(tok.data(), mask.data(), off.data(), R, 0x100000001B3ull, h.data());
     cpo_run_offsets(mask.data(), off.data(), R, ro.data());
     // lookup: run-start keys and the two candidate streams, each confirmed, merged; policies; spans; gather; zero fill
     cpo_probe(ix, h.data(), N, cand.data());
     cpo_verify(text, tok.data(), ro.data(), cand.data(), N, 0, got.data());
+    own_a = got;
     cpo_hash_floating(anchors, ix, h.data(), ro.data(), N, 0x100000001B3ull, W, hf.data(), fo.data(), hl.data(), lo.data());
     cpo_probe(ix, hf.data(), N, cand.data());
     cpo_verify(text, tok.data(), fo.data(), cand.data(), N, 0, own_b.data());
@@ -97,16 +99,32 @@ void life_cycle(uint32_t seed, uint32_t vocab, uint32_t W, bool rope) {
     std::vector<uint8_t> src((size_t)N * TOKB + 1);
     for (auto &b : src) b = (uint8_t)rng();
     std::vector<uint32_t> slot_out(N);
-    const uint32_t n_new = cpo_insert_kv(ix, h.data(), off.data(), R, free_list.data(), (uint32_t)free_list.size(),
-                                         src.data(), layer_major(N), pool.data(), token_major(), slot_pos.data(),
-                                         slot_out.data(), &flags, tok.data(), slot_tok.data());
+    uint32_t n_new;
+    if (dedup) {  // every text once: the lookup above says what the pool has already
+      const uint32_t *seg[3] = {ro.data(), fo.data(), lo.data()}, *found_in[3] = {own_a.data(), own_b.data(), own_c.data()};
+      std::vector<uint64_t> ins_hash(N);
+      std::vector<uint32_t> ins_off(N), found(N);
+      cpo_insert_keys(h.data(), ro.data(), seg, found_in, 1 + 2 * (seed % 2), N, 0x100000001B3ull, ins_hash.data(),
+                      ins_off.data(), found.data());
+      n_new = cpo_insert_kv_dedup(ix, ins_hash.data(), found.data(), off.data(), R, free_list.data(),
+                                  (uint32_t)free_list.size(), src.data(), layer_major(N), pool.data(), token_major(),
+                                  slot_pos.data(), slot_out.data(), &flags, tok.data(), slot_tok.data());
+      cpo_text_record_dedup(text, tok.data(), ins_off.data(), found.data(), N, slot_out.data());
+      cpo_insert_anchors(anchors, ins_hash.data(), ins_off.data(), slot_out.data(), N, W);
+    } else {
+      n_new = cpo_insert_kv(ix, h.data(), off.data(), R, free_list.data(), (uint32_t)free_list.size(), src.data(),
+                            layer_major(N), pool.data(), token_major(), slot_pos.data(), slot_out.data(), &flags,
+                            tok.data(), slot_tok.data());
+      cpo_text_record(text, tok.data(), ro.data(), N, slot_out.data());
+      cpo_insert_anchors(anchors, h.data(), ro.data(), slot_out.data(), N, W);
+    }
     free_list.erase(free_list.begin(), free_list.begin() + n_new);
-    cpo_text_record(text, tok.data(), ro.data(), N, slot_out.data());
-    cpo_insert_anchors(anchors, h.data(), ro.data(), slot_out.data(), N, W);
+    if (capacity && (flags & CPO_FLAG_TABLE_FULL)) cpo_index_rebuild(ix, capacity);  // drop the keys without a slot
     cpo_mark_recompute(slot_out.data(), rec.data(), N, S, marks.data());
     cpo_touch(slot_out.data(), N, epoch, S, stamps.data());
   }
-  std::printf("life cycle %u: %llu keys, %llu prefix hashes\n", seed, (unsigned long long)cpo_index_size(ix),
+  std::printf("life cycle %u: %llu keys in %llu entries, %llu prefix hashes\n", seed,
+              (unsigned long long)cpo_index_size(ix), (unsigned long long)cpo_index_entries(ix),
               (unsigned long long)cpo_anchor_set_size(anchors));
   cpo_text_free(text);
   cpo_anchor_set_free(anchors);
@@ -150,7 +168,9 @@ void rotation() {
 }  // namespace
 
 int main() {
-  for (uint32_t seed = 0; seed < 24; ++seed) life_cycle(seed, seed % 3 == 0 ? 32000 : 2 + seed % 4, 1 + seed % 5, seed % 2);
+  for (uint32_t seed = 0; seed < 48; ++seed)
+    life_cycle(seed, seed % 3 == 0 ? 32000 : 2 + seed % 4, 1 + seed % 5, seed % 2, seed >= 24 && seed % 4 < 3,
+               seed >= 36 ? 96 + 16 * (seed % 5) : 0);
   for (uint32_t seed = 0; seed < 8; ++seed) annotator(seed, 1 + 13 * seed, seed % 3);
   rotation();
   std::puts("done");
