@@ -22,6 +22,7 @@ host on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
+import inspect
 import ctypes as C
 import json
 import os
@@ -225,6 +226,8 @@ def main():
     ap.add_argument("--dedup", action="store_true",
                     help="store every text once: what a lookup of a batch finds (also behind other text) is not stored again "
                          "(needs --anchor-window)")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="KV heads held by this GPU (0 = the workload's own): the share of a tensor-parallel rank")
     ap.add_argument("--free-list", default="random", choices=["random", "sequential"],
                     help="order in which pool slots are handed out (the configurations say random)")
     ap.add_argument("--pool-layout", default="token", choices=["token", "layer"],
@@ -266,7 +269,11 @@ def main():
                                  args.fanout, args.workgroups)
 
     t0 = time.time()
-    wl = gen.make(args.workload)
+    if args.kv_heads:  # one rank's share under tensor parallelism: the same tokens and slots, fewer heads per row
+        whole = inspect.signature(gen.WORKLOADS[args.workload]).parameters["shape"].default
+        wl = gen.make(args.workload, shape=gen.KVShape(whole.n_layers, args.kv_heads, whole.head_dim))
+    else:
+        wl = gen.make(args.workload)
     if args.free_list == "sequential":  # slots handed out in ascending order: matched runs become long spans
         wl.free_slots = np.arange(wl.pool_slots, dtype=np.uint32)
     sh = wl.shape
@@ -436,7 +443,7 @@ def main():
 
     # the stored counter readings belong to the gather of the default options
     same_gather = (args.anchor_window is None and args.min_len <= 1 and args.recompute == 0 and not args.dedup
-                   and args.pool_layout == "token" and args.free_list == "random")
+                   and args.pool_layout == "token" and args.free_list == "random" and not args.kv_heads)
     out = {
         "metric": "KV gather GB/s (% of HBM peak) + reused tokens/sec, Llama-3-8B KV shape",
         "value": step_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -90,6 +90,7 @@ constexpr uint32_t kMaxHalfDim = 256;    // head_dim <= 512 when rotating
 constexpr uint32_t kMaxFanout = 16;      // destinations served per pass over the source rows
 constexpr uint32_t kTrigDoubles = 1024;  // LDS doubles for cos (and as many for sin) per descriptor: fan-out * head_dim/2 <= this
 constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kTicketStride = 256;  // distance between the units of one ticket of the work counter
 constexpr uint32_t kShareReadsFrom = 4096;  // destination tokens from which a gather shares reads by default
 
 // cos/sin of (delta * inv_freq[j]) for any 32-bit delta come from five small
@@ -376,7 +377,7 @@ __device__ __forceinline__ void move_rows_body(
     const uint32_t *__restrict__ units /* nullable: every item is a unit of its own */,
     const uint32_t *__restrict__ unit_counts, uint32_t *counter, const uint8_t *__restrict__ from,
     const cp_kv_layout &fl, uint32_t n_from, uint8_t *__restrict__ to, const cp_kv_layout &tl, uint32_t fanout,
-    uint32_t *status_flags, const RA &rope) {
+    uint32_t take, uint32_t *status_flags, const RA &rope) {
   __shared__ UnitDesc s_unit[2];
   __shared__ double s_cos[2][ROPE ? kTrigDoubles : 1], s_sin[2][ROPE ? kTrigDoubles : 1];
 
@@ -411,9 +412,21 @@ __device__ __forceinline__ void move_rows_body(
   // while the other two only copy V rows.  Swapping K and V inside the pair on every other step of a round is
   // still a walk over every (row, column) once, and gives every wavefront half of the rotations.
   const uint32_t alternate = (ROPE && kMoveThreads % (2 * vpr) == 0) ? 1u : 0u;
+  // With rows shorter than a wavefront's 1 KiB the lanes of one wavefront would hold K rows and V rows side by
+  // side, and the wavefront would run the rotation with half of its lanes idle.  Where a step covers whole
+  // (K, V) pairs, the rows of a step are therefore dealt out so that the first half of the workgroup holds the
+  // step's K rows and the second half its V rows (a permutation inside the step's rows; nothing changes for
+  // rows of 1 KiB and more).  row_shift = the lane's row under this rule minus its row in row-major order.
+  uint32_t row_shift = 0;
+  if (alternate) {
+    const uint32_t pairs = r_step / 2;  // (K, V) pairs per step; r_init < r_step
+    row_shift = 2 * (r_init % pairs) + r_init / pairs - r_init;
+  }
 
   // ---- scout state (the same in all 64 lanes of the scout) ----
   uint32_t more_node = kNone, more_from = kNone;  // chain to continue in the next pass, and its source
+  uint32_t mine = 0, mine_k = take;               // first unit of this scout's ticket, and how many of its units are done
+  const uint32_t n_tickets = (n_units + take * kTicketStride - 1) / (take * kTicketStride) * kTicketStride;  // n_units < 2^31
 
   for (uint32_t turn = 0;; ++turn) {
     const uint32_t b = turn & 1u;
@@ -421,12 +434,20 @@ __device__ __forceinline__ void move_rows_body(
       // Describe the unit of turn `turn` into s_unit[b]; for turn 0 the movers wait at the barrier
       // below, afterwards they are moving the unit of turn - 1 out of s_unit[b ^ 1] meanwhile.
       uint32_t node = more_node, src = more_from;
+      MoveItem first{kNone, kNone, 0, kNone};  // a new unit's first item, read while it was looked at
+      bool have_first = false;
       if (node == kNone) {  // a new unit: the next one the counter hands out
         while (true) {
-          uint32_t i = 0;
-          if (lane == 0) i = atomicAdd(counter, 1u);
-          i = __shfl(i, 0, kWave);
-          if (i >= n_units) break;  // the counter only grows: every scout gets here
+          if (mine_k == take) {  // a new ticket: `take` units, kTicketStride apart (see launch_move)
+            uint32_t t = 0;
+            if (lane == 0) t = atomicAdd(counter, 1u);
+            t = __shfl(t, 0, kWave);
+            if (t >= n_tickets) break;  // the counter only grows: every scout gets here
+            mine = t / kTicketStride * (take * kTicketStride) + t % kTicketStride;
+            mine_k = 0;
+          }
+          const uint32_t i = mine + mine_k++ * kTicketStride;
+          if (i >= n_units) continue;  // the last group of tickets may reach past the end
           uint32_t w = i;
           if (units) w = units[i < n_chains ? i : max_items - 1 - (i - n_chains)];
           if (w >= n_items) continue;
@@ -438,6 +459,8 @@ __device__ __forceinline__ void move_rows_body(
           }
           node = w;
           src = it.from;
+          first = it;
+          have_first = true;
           break;
         }
       }
@@ -447,7 +470,7 @@ __device__ __forceinline__ void move_rows_body(
       for (uint32_t k = 0; k < kMaxFanout; ++k) {
         dl[k] = 0;
         if (k < fanout && node != kNone && node < n_items) {
-          const MoveItem it = items[node];
+          const MoveItem it = (k == 0 && have_first) ? first : items[node];
           dl[k] = it.delta;
           if (lane == 0) {
             s_unit[b].tobase[k] = (uint64_t)it.to * tl.tok_stride;
@@ -474,6 +497,7 @@ __device__ __forceinline__ void move_rows_body(
 #pragma unroll
               for (uint32_t level = 1; level < kTrigLevels; ++level) {
                 a >>= 7;
+                if (a == 0) break;  // all further digits are 0: their entries are (1, 0), which change nothing
                 t = rope.tables[(level * kTrigDigit + (a & (kTrigDigit - 1))) * half + j];
                 const double c2 = cs * t.x - sn * t.y;  // angles add: multiply the unit vectors
                 sn = sn * t.x + cs * t.y;
@@ -505,8 +529,9 @@ __device__ __forceinline__ void move_rows_body(
       bool ok[U], is_k[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        ok[u] = FULL || r < n_rows;  // r only grows, so the valid steps of a lane are a prefix
-        const uint32_t rr = r ^ (alternate & (uint32_t)u);  // (rounds start on even steps: U is even)
+        const uint32_t rp = r + row_shift;
+        ok[u] = FULL || rp < n_rows;  // rp only grows, so the valid steps of a lane are a prefix
+        const uint32_t rr = rp ^ (alternate & (uint32_t)u);  // (rounds start on even steps: U is even; n_rows is even)
         is_k[u] = (rr & 1u) == 0;
         const uint64_t l = rr >> 1, kv = rr & 1u;
         doff[u] = l * tl.layer_stride + kv * tl.kv_stride + (uint64_t)c * 16;
@@ -566,9 +591,9 @@ __global__ __launch_bounds__(kBlockThreads) void gather_rows_kernel(
     const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
     const uint32_t *__restrict__ units, const uint32_t *__restrict__ unit_counts, uint32_t *counter,
     const uint8_t *__restrict__ pool, cp_kv_layout pool_l, uint32_t n_pool_slots, uint8_t *__restrict__ dst,
-    cp_kv_layout dst_l, uint32_t fanout, uint32_t *status_flags, RA rope) {
+    cp_kv_layout dst_l, uint32_t fanout, uint32_t take, uint32_t *status_flags, RA rope) {
   move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, units, unit_counts, counter, pool, pool_l,
-                                        n_pool_slots, dst, dst_l, fanout, status_flags, rope);
+                                        n_pool_slots, dst, dst_l, fanout, take, status_flags, rope);
 }
 
 template <class RA, bool ROPE, bool NTL, bool NTS, int U>
@@ -576,9 +601,9 @@ __global__ __launch_bounds__(kBlockThreads) void scatter_rows_kernel(
     const MoveItem *__restrict__ items, const uint32_t *__restrict__ n_items_ptr, uint32_t max_items,
     const uint32_t *__restrict__ units, const uint32_t *__restrict__ unit_counts, uint32_t *counter,
     const uint8_t *__restrict__ src, cp_kv_layout src_l, uint32_t n_src_tokens, uint8_t *__restrict__ pool,
-    cp_kv_layout pool_l, uint32_t fanout, uint32_t *status_flags, RA rope) {
+    cp_kv_layout pool_l, uint32_t fanout, uint32_t take, uint32_t *status_flags, RA rope) {
   move_rows_body<RA, ROPE, NTL, NTS, U>(items, n_items_ptr, max_items, units, unit_counts, counter, src, src_l,
-                                        n_src_tokens, pool, pool_l, fanout, status_flags, rope);
+                                        n_src_tokens, pool, pool_l, fanout, take, status_flags, rope);
 }
 
 uint32_t cu_count() {
@@ -623,15 +648,23 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
     uint32_t cap = kTrigDoubles / (fl.head_dim / 2);
     if (fanout > cap) fanout = cap;
   }
+  // Units per ticket of the work counter.  Every workgroup of the chip adds to that one word, and such additions
+  // go through at about 80 per microsecond in all: enough for tokens of 64 KiB and more, a cap on the whole kernel
+  // for small ones (16 KiB tokens need 170 units per microsecond to keep HBM busy).  For small tokens a ticket
+  // is therefore worth several units, about 24 steps of the 256 lanes.  Ticket t of a group of kTicketStride
+  // tickets stands for units t, t + kTicketStride, t + 2 kTicketStride, .. of the group's stretch of the list: the workgroups
+  // that run at the same time are then still on neighbouring units (neighbouring destination rows), as with
+  // one unit per ticket, which consecutive units per ticket would give up (5 % slower on 40 KiB tokens).
+  const uint32_t take = steps >= 24 ? 1u : (uint32_t)(24 / steps) < 8u ? (uint32_t)(24 / steps) : 8u;
   const uint8_t *f = (const uint8_t *)from;
   uint8_t *t = (uint8_t *)to;
 #define CP_LAUNCH(NTL, NTS, UN)                                                                              \
   if constexpr (GATHER)                                                                                      \
     gather_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kBlockThreads, 0, stream>>>(                 \
-        items, n_items, max_items, units, unit_counts, counter, f, fl, n_from, t, tl, fanout, status_flags, rope); \
+        items, n_items, max_items, units, unit_counts, counter, f, fl, n_from, t, tl, fanout, take, status_flags, rope); \
   else                                                                                                       \
     scatter_rows_kernel<RA, ROPE, NTL, NTS, UN><<<(uint32_t)grid, kBlockThreads, 0, stream>>>(                \
-        items, n_items, max_items, units, unit_counts, counter, f, fl, n_from, t, tl, fanout, status_flags, rope)
+        items, n_items, max_items, units, unit_counts, counter, f, fl, n_from, t, tl, fanout, take, status_flags, rope)
   switch ((mo.nontemporal & 3u) | (lif >= 16 ? 8u : lif >= 8 ? 4u : 0u)) {
     case 0: CP_LAUNCH(false, false, 4); break;
     case 1: CP_LAUNCH(true, false, 4); break;

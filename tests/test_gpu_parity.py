@@ -146,6 +146,24 @@ def test_head_counts_that_are_not_powers_of_two(G, shape):
         assert (glk.span_delta != 0).mean() > 0.8
 
 
+@pytest.mark.parametrize("shape", [(32, 1, 128), (5, 2, 128), (3, 1, 128), (7, 4, 128)])
+def test_short_rows_of_a_tensor_parallel_share(G, shape):
+    """One or a few KV heads per GPU, as on a rank of a tensor-parallel model: rows of 256 B to 1 KiB and small
+    tokens.  The mover then takes several tokens per visit to its work counter (in strides, with a ragged last
+    group), and a rotating gather deals the K rows and the V rows of a step to different wavefronts, also where
+    the last step of a token holds fewer rows than a full one (5, 3 and 7 layers)."""
+    sh = gen.KVShape(*shape)
+    ost, olk, gst, glk = compare_all(G, gen.make_docs("tp-share", 0xC0FFEE70 + shape[0], sh, R=6, T=1500, prefix_len=200,
+                                                      n_docs=8, doc_len=(100, 300), docs_per_request=4, run_mean=8.0,
+                                                      cover=0.15, pool_slots=8192))
+    assert (glk.slot != NONE).sum() > 3000  # several groups of tickets
+    for style, layout in ((0, "token"), (1, "layer")):
+        wl = gen.make_rope(seed=0xC0FFEE60 + shape[0], scale=1 / 4, shape=sh)
+        wl.rope_style = style
+        ost, olk, gst, glk = compare_all(G, wl, pool_layout=layout)
+        assert (glk.span_delta != 0).sum() > 1500
+
+
 def test_contiguous_slots_give_long_spans(G):
     wl = gen.make_docs("contig", 7, gen.KVShape(4, 2, 64), R=4, T=1500, prefix_len=400, n_docs=5, doc_len=(200, 400),
                        docs_per_request=3, run_mean=8.0, cover=0.10, pool_slots=4096)
