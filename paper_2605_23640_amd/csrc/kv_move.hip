@@ -90,6 +90,7 @@ constexpr uint32_t kMaxHalfDim = 256;    // head_dim <= 512 when rotating
 constexpr uint32_t kMaxFanout = 16;      // destinations served per pass over the source rows
 constexpr uint32_t kTrigDoubles = 1024;  // LDS doubles for cos (and as many for sin) per descriptor: fan-out * head_dim/2 <= this
 constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kMaxTake = 8;         // units per ticket of the work counter, at most
 constexpr uint32_t kTicketStride = 256;  // distance between the units of one ticket of the work counter
 constexpr uint32_t kShareReadsFrom = 4096;  // destination tokens from which a gather shares reads by default
 
@@ -379,6 +380,8 @@ __device__ __forceinline__ void move_rows_body(
     const cp_kv_layout &fl, uint32_t n_from, uint8_t *__restrict__ to, const cp_kv_layout &tl, uint32_t fanout,
     uint32_t take, uint32_t *status_flags, const RA &rope) {
   __shared__ UnitDesc s_unit[2];
+  __shared__ MoveItem s_ahead[kMaxTake];  // the scout's own: first item of each unit of its ticket, and which item that is
+  __shared__ uint32_t s_ahead_w[kMaxTake];
   __shared__ double s_cos[2][ROPE ? kTrigDoubles : 1], s_sin[2][ROPE ? kTrigDoubles : 1];
 
   uint32_t n_items = *n_items_ptr;
@@ -445,13 +448,28 @@ __device__ __forceinline__ void move_rows_body(
             if (t >= n_tickets) break;  // the counter only grows: every scout gets here
             mine = t / kTicketStride * (take * kTicketStride) + t % kTicketStride;
             mine_k = 0;
+            // lane k fetches the first item of the ticket's k-th unit: the dependent loads (list entry, then item)
+            // are paid once per ticket, side by side, not once per unit
+            // (they wait in LDS, which only this wavefront touches: registers held across the movers' code
+            // would cost every wavefront of the kernel its occupancy)
+            if (lane < take) {
+              const uint32_t i = mine + lane * kTicketStride;  // (the last group of tickets may reach past the end)
+              uint32_t w = kNone;
+              u32x4 it{kNone, kNone, 0u, kNone};  // a MoveItem's four words
+              if (i < n_units) {
+                w = units ? units[i < n_chains ? i : max_items - 1 - (i - n_chains)] : i;
+                if (w < n_items) it = *reinterpret_cast<const u32x4 *>(&items[w]);
+                else w = kNone;
+              }
+              s_ahead_w[lane] = w;
+              *reinterpret_cast<u32x4 *>(&s_ahead[lane]) = it;
+            }
+            __builtin_amdgcn_wave_barrier();  // (LDS serves one wavefront's accesses in order)
           }
-          const uint32_t i = mine + mine_k++ * kTicketStride;
-          if (i >= n_units) continue;  // the last group of tickets may reach past the end
-          uint32_t w = i;
-          if (units) w = units[i < n_chains ? i : max_items - 1 - (i - n_chains)];
-          if (w >= n_items) continue;
-          const MoveItem it = items[w];
+          const uint32_t k = mine_k++;
+          const uint32_t w = s_ahead_w[k];
+          if (w == kNone) continue;
+          const MoveItem it = s_ahead[k];
           if (it.from == kNone) continue;  // an item that was taken out
           if (it.from >= n_from) {
             if (lane == 0) atomicOr(status_flags, CP_FLAG_BAD_INDEX);
@@ -655,7 +673,7 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   // tickets stands for units t, t + kTicketStride, t + 2 kTicketStride, .. of the group's stretch of the list: the workgroups
   // that run at the same time are then still on neighbouring units (neighbouring destination rows), as with
   // one unit per ticket, which consecutive units per ticket would give up (5 % slower on 40 KiB tokens).
-  const uint32_t take = steps >= 24 ? 1u : (uint32_t)(24 / steps) < 8u ? (uint32_t)(24 / steps) : 8u;
+  const uint32_t take = steps >= 24 ? 1u : (uint32_t)(24 / steps) < kMaxTake ? (uint32_t)(24 / steps) : kMaxTake;
   const uint8_t *f = (const uint8_t *)from;
   uint8_t *t = (uint8_t *)to;
 #define CP_LAUNCH(NTL, NTS, UN)                                                                              \
