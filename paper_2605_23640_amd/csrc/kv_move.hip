@@ -19,8 +19,9 @@
 //     the bytes written do not;
 //   - the chain heads are gathered into a dense work list (chains of several tokens first, single
 //     tokens after them), so no workgroup ever meets a token that has nothing to do; units of
-//     work are taken from the list through an atomic counter, so long chains and single tokens
-//     balance, and every workgroup leaves the loop as soon as the counter passes the unit count;
+//     work are taken from the list through an atomic counter (one unit per ticket, several for
+//     small tokens), so long chains and single tokens balance, and every workgroup leaves the
+//     loop as soon as the counter passes the ticket count;
 //   - a workgroup is four mover wavefronts plus one scout wavefront: the scout fetches and
 //     decodes the next unit (descriptor, chain links, rotation tables) into LDS while the movers
 //     copy the current one, so the movers never wait for a descriptor; one barrier per unit;
@@ -348,8 +349,8 @@ __global__ __launch_bounds__(256) void gather_heads_kernel(const MoveItem *__res
 
 // One work unit = one chain = all rows of one source token, written to every destination of the chain
 // (at most `fanout` of them per pass).  A workgroup is four mover wavefronts plus one scout wavefront:
-//   - the scout takes the next unit from the atomic counter while the movers are busy with the current
-//     one: it skips tokens that are not the head of a chain, walks the chain, and leaves the unit's
+//   - the scout takes the next unit (a ticket of the atomic counter names one or a few) while the movers
+//     are busy with the current one: it walks the unit's chain, and leaves the unit's
 //     source, destination offsets, deltas and (rotating gather) cos/sin values in the other half of a
 //     double-buffered descriptor in LDS.  Everything serial and latency-bound (dependent loads through
 //     items[] and head[], the trigonometric table products) is thus off the movers' path, and a unit
