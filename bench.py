@@ -39,12 +39,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # reads for a plain streaming kernel of known size.  They are copied from the summaries under profiles/
 # (gather_rows_kernel_<workload>.txt; annotator_<n>.txt): measurements of an earlier run of the same
 # code, not of this run, and the bench line says so next to them.
-PROFILED_TRAFFIC = {"llama3-8b": 9024672260, "rope": 9669340862, "llama3-70b": 58261219980, "frag": 17206055558,
+PROFILED_TRAFFIC = {"llama3-8b": 9025031415, "rope": 9670656782, "llama3-70b": 58250476725, "frag": 17205904545,
                     "annotator-10000-full": 895897876, "annotator-10000": 347761408}
-PROFILED_FETCH = {"llama3-8b": 3093460030, "rope": 4436977590, "llama3-70b": 25345880056, "frag": 7416194775}
+PROFILED_FETCH = {"llama3-8b": 3093452150, "rope": 4436997106, "llama3-70b": 25345694896, "frag": 7416200342}
 # scatter_rows_kernel of the default step (scatter_rows_kernel_<workload>.txt and the gather files): (fetched, written)
-PROFILED_SCATTER = {"llama3-8b": (1687306858, 1683347987), "rope": (7662517344, 7642108268),
-                    "llama3-70b": (6636764448, 6626772725)}
+PROFILED_SCATTER = {"llama3-8b": (1687336561, 1683374349), "rope": (7662560513, 7643897776),
+                    "llama3-70b": (6636806179, 6623393073)}
 
 
 def log(*a):

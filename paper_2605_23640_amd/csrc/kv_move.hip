@@ -646,7 +646,7 @@ int32_t launch_move(hipStream_t stream, const MoveItem *items, const uint32_t *n
   if (mo.start && hipEventRecord(mo.start, stream) != hipSuccess) return CP_ERR_HIP;
   // Defaults, measured on MI355X with the Llama row shapes.  Copy form: 16 loads in flight per lane and
   // one workgroup on seven of every eight compute units (224 of 256; one per unit is 1 % slower, two per
-  // unit with 8 loads 3-6 % slower).  Rotating form: 8 loads in flight (155 registers), two workgroups per
+  // unit with 8 loads 3-6 % slower).  Rotating form: 8 loads in flight (165 registers), two workgroups per
   // unit; with every wavefront taking half of the rotations (see `alternate` in the mover) that is 3 % faster
   // than 4 loads and within 2 % of the copy form on the same spans.  Small tokens get as many loads as they
   // have steps for.
