@@ -1,6 +1,7 @@
 """Parity at the full sizes of the benchmark configurations (Llama-3-8B shape,
 fragmentation stress, RoPE-shift reuse, Llama-3-70B shape), in the launch
-configuration bench.py times.
+configuration bench.py times, and of one tensor-parallel rank's share of two of
+them (one KV head per row).
 
 Hashes, slots, spans, deltas and inserted slots are compared in full against
 the CPU oracle (they do not depend on the KV shape, so the oracle runs them on
@@ -12,6 +13,7 @@ must hold exactly that (or the untouched fill pattern).  Re-rotated keys are
 compared on a seeded sample of tokens against the oracle's double-precision
 rotation, one by one."""
 import gc
+import inspect
 
 import numpy as np
 import pytest
@@ -49,9 +51,19 @@ def oracle_bookkeeping(wl):
     return st, lk
 
 
-@pytest.mark.parametrize("name", ["llama3-8b", "frag", "rope", "llama3-70b"])
+def make_workload(name):
+    """'llama3-70b' = the configuration; 'llama3-70b/1-head' = the same tokens, slots and spans with one KV head
+    per row: what one rank of an 8-way tensor-parallel model holds (rows of 256 B, small tokens)."""
+    base, _, share = name.partition("/")
+    if not share:
+        return gen.make(base)
+    whole = inspect.signature(gen.WORKLOADS[base]).parameters["shape"].default
+    return gen.make(base, shape=gen.KVShape(whole.n_layers, int(share.split("-")[0]), whole.head_dim))
+
+
+@pytest.mark.parametrize("name", ["llama3-8b", "frag", "rope", "llama3-70b", "llama3-70b/1-head", "rope/1-head"])
 def test_full_size(G, name):
-    wl = gen.make(name)
+    wl = make_workload(name)
     sh, N = wl.shape, wl.n_tokens
     print(f"\n[{name}] {wl.n_requests} requests x {N // wl.n_requests} tokens, pool "
           f"{wl.pool_slots * sh.tok_bytes / 2**30:.0f} GiB, request buffers {N * sh.tok_bytes / 2**30:.0f} GiB", flush=True)
