@@ -85,6 +85,28 @@ def test_random_batches_stored_once(G, seed, vocab, W, verify):
     assert ost.n_used < 0.8 * len(wl.donor_tok)
 
 
+@pytest.mark.parametrize("verify", [False, True])
+def test_one_request_per_call_keeps_one_copy_of_a_batchs_new_text(G, verify):
+    """Texts of one call do not see each other.  The same prompts in one call (four copies of their document, one
+    per lead) and one request per call (one copy), each against the oracle."""
+    rng = np.random.default_rng(13)
+    V = lambda n: rng.integers(0, 32000, int(n)).astype(np.uint32)  # noqa: E731
+    doc = V(700)
+    donors = [np.concatenate([doc, V(40)]), np.concatenate([V(90), doc, V(30)]), np.concatenate([V(35), doc]),
+              np.concatenate([V(150), doc, V(60)])]
+    outside = 40 + 90 + 30 + 35 + 150 + 60
+    reqs = [np.concatenate([V(12), doc, V(7)]), donors[3]]
+    used = []
+    for batch_tokens in (1 << 17, 800):  # everything in one call; one prompt per call
+        wl = gen.from_prompts("one-per-call", 0xC0FFEE34, gen.KVShape(2, 2, 64), donors, reqs, pool_slots=8192,
+                              donor_batch_tokens=batch_tokens)
+        assert len(wl.donor_batches) == (1 if batch_tokens > 800 else 4)
+        ost, gst, olk = both(G, wl, 8, verify)
+        used.append(ost.n_used)
+        assert (olk.slot[12:12 + 700] != NONE).all() and (olk.slot[wl.off[1]:] != NONE).all()
+    assert used == [sum(map(len, donors)), 700 + outside]
+
+
 def test_stored_once_with_a_full_pool_and_policies(G):
     """The free list runs out in the middle of a batch; LRU stamps, minimum length and zero fill are on."""
     rng = np.random.default_rng(9)

@@ -147,3 +147,39 @@ def test_insert_once_against_the_token_list_model(seed, vocab, W, verify):
     plain = sum(len(t) for t in corpus)
     assert used < 5 * 3 * 20  # far fewer tokens than were offered
     assert plain > 0
+
+
+@pytest.mark.parametrize("verify", [False, True])
+def test_a_batch_stored_request_by_request_keeps_one_copy_of_its_new_text(verify):
+    """Texts of one call do not see each other: a text that is new to the pool and comes several times in one
+    batch is stored once per lead.  Stored one request per call, the later requests find what the first stored.
+    Both call patterns against the token-list model."""
+    rng = np.random.default_rng(11)
+    W, S = 4, 2000
+    V = lambda n: rng.integers(0, 32000, int(n)).astype(np.uint32)  # noqa: E731
+    doc = V(90)
+    prompts = [np.concatenate([doc, V(6)]), np.concatenate([V(13), doc, V(4)]), np.concatenate([V(5), doc]),
+               np.concatenate([V(21), doc, V(8)])]
+    extra = [6, 13 + 4, 5, 21 + 8]  # tokens of each prompt outside the document
+
+    def store(calls):
+        free = rng.permutation(S).astype(np.uint32)
+        ix, anchors, tp = O.Index(), O.AnchorSet(), TextPool(free, W)
+        text = O.Text(S) if verify else None
+        pool, slot_pos = np.zeros((S, 1, 2, 8), np.uint16), np.zeros(S, np.int32)
+        used = 0
+        for ps in calls:
+            tok = np.concatenate(ps).astype(np.uint32)
+            mask = np.zeros(len(tok), np.uint8)
+            off = np.concatenate([[0], np.cumsum([len(p) for p in ps])]).astype(np.uint32)
+            so, used, _ = oracle_insert_once(ix, anchors, tok, mask, off, free, used, pool, slot_pos, W, text)
+            want = tp.insert_once(tok, mask, off)
+            assert list(so) == [NONE if s is None else s for s in want]
+            assert used == tp.n_used
+        for p in prompts:  # either way every prompt is found again whole
+            one = (p, np.zeros(len(p), np.uint8), np.array([0, len(p)], np.uint32))
+            assert (lookup(ix, anchors, *one, W, text) != NONE).all()
+        return used
+
+    assert store([prompts]) == sum(map(len, prompts))  # one call: four copies of the document
+    assert store([[p] for p in prompts]) == len(doc) + sum(extra)  # one request per call: one copy
