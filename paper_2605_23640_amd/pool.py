@@ -12,9 +12,15 @@ sequences of the two paths through libcacheprune.
 
 and, for a pool that confirms every match exactly (``verify=True``),
 
-    lookup :  cp_hash_runs -> cp_probe -> cp_verify_chain [-> cp_hash_floating -> 2 x (cp_probe -> cp_verify_chain)]
-              -> cp_build_spans -> cp_gather_kv
+    lookup :  cp_hash_probe (hashes, run offsets, candidates) -> cp_verify_chain -> cp_build_spans -> cp_gather_kv
+              with floating anchors: cp_hash_probe -> cp_hash_floating -> cp_verify_streams (the three key
+              streams probed and confirmed in one call) -> cp_build_spans -> cp_gather_kv
     insert :  cp_hash_runs -> cp_insert_kv_chain [-> cp_insert_anchors]
+
+and, for a pool that stores every text once (``dedup=True``),
+
+    insert :  the lookup's matching (every key stream's own finds) -> cp_insert_keys -> cp_insert_kv_dedup
+              -> cp_insert_anchors
 
 Policies hook in after the slots are known: cp_touch (LRU stamps), cp_filter_matches (minimum
 length, recompute marks) before cp_build_spans, cp_fill_unmatched after the gather;
