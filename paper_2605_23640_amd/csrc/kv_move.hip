@@ -394,6 +394,16 @@ __device__ __forceinline__ void move_rows_body(
     const uint32_t n_single = unit_counts[1] < max_items - n_chains ? unit_counts[1] : max_items - n_chains;
     n_units = n_chains + n_single;
   }
+  // Destinations that read so few distinct slots that there are fewer chains than workgroups would leave most
+  // of the chip idle while a few workgroups walk long chains.  Every token is then moved on its own, the
+  // links ignored; the repeated reads of those few slots come from cache.  (Counts are the same for every lane
+  // of every workgroup, so all decide alike.)
+  const bool solo = units != nullptr && n_units < gridDim.x && n_items / 2 >= n_units;
+  if (solo) {
+    units = nullptr;
+    n_chains = 0;
+    n_units = n_items;
+  }
   const uint32_t half = fl.head_dim / 2;
   const bool scout = threadIdx.x >= kMoveThreads;  // the fifth wavefront
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -495,7 +505,7 @@ __device__ __forceinline__ void move_rows_body(
             s_unit[b].tobase[k] = (uint64_t)it.to * tl.tok_stride;
             s_unit[b].delta[k] = it.delta;
           }
-          node = it.next;
+          node = solo ? kNone : it.next;
           K = k + 1;
         }
       }

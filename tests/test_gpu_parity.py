@@ -164,6 +164,29 @@ def test_short_rows_of_a_tensor_parallel_share(G, shape):
         assert (glk.span_delta != 0).sum() > 1500
 
 
+@pytest.mark.parametrize("shape", [(2, 2, 64), (4, 8, 128)])
+def test_thousands_of_destinations_read_a_few_slots(G, shape):
+    """Read sharing at its extremes.  Five thousand one-token requests for the same stored token: fewer chains
+    than workgroups, so the mover drops the links and moves every token on its own.  Then six hundred stored
+    tokens asked for ten times each: chains of ten, walked by the workgroup that takes them.  Copying and
+    rotating (the stored tokens sit behind a sensitive token, one position further on than in the requests)."""
+    sh = gen.KVShape(*shape)
+    rng = np.random.default_rng(3)
+    lead = lambda t: np.concatenate([[1], t]).astype(np.uint32)  # noqa: E731  (a sensitive token in front)
+    lead_mask = lambda t: np.concatenate([[1], np.zeros(len(t))]).astype(np.uint8)  # noqa: E731
+    one = [np.array([7, 9, 11], np.uint32)]
+    many = [np.array([t], np.uint32) for t in rng.permutation(32000)[:600]]
+    for donors, reqs in ((one, [np.array([7], np.uint32)] * 5000 + [np.array([7, 9], np.uint32)] * 50),
+                         (many, [many[i % 600] for i in range(6000)])):
+        wl = gen.from_prompts("few-slots", 5, sh, [lead(d) for d in donors], reqs, pool_slots=1024,
+                              donor_masks=[lead_mask(d) for d in donors])
+        ost, olk, gst, glk = compare_all(G, wl)
+        assert (glk.slot != NONE).all() and len(np.unique(glk.slot)) <= 600
+        wl.rope_theta, wl.rope_style = 500000.0, 0
+        ost, olk, gst, glk = compare_all(G, wl)
+        assert (glk.span_delta[:glk.n_spans] == -1).all()
+
+
 def test_contiguous_slots_give_long_spans(G):
     wl = gen.make_docs("contig", 7, gen.KVShape(4, 2, 64), R=4, T=1500, prefix_len=400, n_docs=5, doc_len=(200, 400),
                        docs_per_request=3, run_mean=8.0, cover=0.10, pool_slots=4096)
