@@ -12,7 +12,7 @@
  * cp_verify_streams),
  * one copy of stored text (cp_insert_keys, cp_insert_kv_dedup), pool policies
  * (cp_filter_matches, cp_mark_recompute, cp_fill_unmatched, cp_touch, cp_lru_threshold, cp_evict,
- * cp_table_compact) and the KV annotator (cp_sat_build, cp_annotate).
+ * cp_table_compact, cp_table_count) and the KV annotator (cp_sat_build, cp_annotate).
  *
  * Conventions for every call
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -442,6 +442,11 @@ int32_t cp_evict(void *stream, cp_table table, uint32_t *slot_stamp, uint32_t n_
                  uint32_t *freed_slots, uint32_t *n_freed, uint32_t *slot_parent, uint8_t *slot_recompute,
                  uint8_t *slot_anchor, void *scratch, size_t scratch_bytes);
 int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, uint32_t *status_flags);
+/* How full the index is (Sec. 4.3.5 "Lifecycle management": the pool's bookkeeping between evictions):
+ * counts_out (device, u32[2]) receives [0] the number of table entries that hold a key and [1] the number of
+ * those whose key has a slot.  [0] - [1] entries are held by keys without a slot (dropped when the pool was
+ * full, evicted, or claimed by a call that ended with CP_FLAG_TABLE_FULL): cp_table_compact gives them back.  Fails like cp_table_init on a malformed table. */
+int32_t cp_table_count(void *stream, cp_table table, uint32_t *counts_out);
 
 /* ---- KV annotator: which tokens of a finished request are worth storing ------------------------
  * Sec. 4.2.1 ("C1"), Steps 1-3.  attn (device, float[n][ld], ld >= n): attention weight from token

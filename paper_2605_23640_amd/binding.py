@@ -34,7 +34,7 @@ EXPORTS = [
     "cp_hash_runs", "cp_insert_anchors", "cp_hash_floating", "cp_probe2", "cp_probe3",
     "cp_insert_kv_chain", "cp_verify_chain", "cp_verify_streams", "cp_insert_keys", "cp_insert_kv_dedup",
     "cp_filter_matches", "cp_mark_recompute", "cp_fill_unmatched", "cp_touch", "cp_lru_threshold", "cp_evict",
-    "cp_table_compact", "cp_sat_scratch_bytes", "cp_sat_build", "cp_annotate",
+    "cp_table_compact", "cp_table_count", "cp_sat_scratch_bytes", "cp_sat_build", "cp_annotate",
 ]
 PARENT_POISON = 0xFFFFFFFE
 LRU_MAX_AGE = 4096
@@ -153,6 +153,8 @@ def lib():
         L.cp_evict.argtypes = [vp, TableStruct, vp, u32, vp, vp, vp, vp, vp, vp, vp, sz]
         L.cp_table_compact.restype = i32
         L.cp_table_compact.argtypes = [vp, TableStruct, TableStruct, vp]
+        L.cp_table_count.restype = i32
+        L.cp_table_count.argtypes = [vp, TableStruct, vp]
         L.cp_sat_scratch_bytes.restype = sz
         L.cp_sat_scratch_bytes.argtypes = [u32]
         L.cp_sat_build.restype = i32
@@ -433,6 +435,12 @@ def cp_evict(table: Table, slot_stamp, n_pool_slots, threshold, freed_slots, n_f
 def cp_table_compact(src: Table, dst: Table, status_flags, stream=None):
     _need_cuda(status_flags)
     _check("cp_table_compact", lib().cp_table_compact(_stream(stream), src.struct, dst.struct, _ptr(status_flags)))
+
+
+def cp_table_count(table: Table, counts_out, stream=None):
+    """counts_out: int32[2] on the device <- (entries holding a key, of which with a slot)."""
+    _need_cuda(counts_out)
+    _check("cp_table_count", lib().cp_table_count(_stream(stream), table.struct, _ptr(counts_out)))
 
 
 def new_sat_scratch(n, device="cuda"):

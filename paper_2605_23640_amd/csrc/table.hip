@@ -248,6 +248,28 @@ __global__ __launch_bounds__(kProbeThreads) void table_compact_kernel(cp_table s
   }
 }
 
+// How full the table is: entries that hold a key, and those of them whose key has a slot.  The difference is
+// what evictions and dropped tokens left behind, i.e. what cp_table_compact would give back.
+__global__ void table_count_zero_kernel(uint32_t *counts) { counts[0] = counts[1] = 0; }
+__global__ __launch_bounds__(kProbeThreads) void table_count_kernel(cp_table t, uint32_t *counts) {
+  uint32_t used = 0, live = 0;
+  for (uint64_t e = (uint64_t)blockIdx.x * kProbeThreads + threadIdx.x; e < t.capacity;
+       e += (uint64_t)gridDim.x * kProbeThreads) {
+    const bool has_key = t.keys[e] != CP_HASH_NONE;
+    used += has_key ? 1u : 0u;
+    live += (has_key && t.vals[e] < kPending) ? 1u : 0u;
+  }
+#pragma unroll
+  for (int m = 1; m < kWave; m <<= 1) {
+    used += __shfl_xor(used, m, kWave);
+    live += __shfl_xor(live, m, kWave);
+  }
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    if (used) atomicAdd(&counts[0], used);
+    if (live) atomicAdd(&counts[1], live);
+  }
+}
+
 // Insert, step 1: find or claim the table entry of every token's key and leave
 // in vals[] the smallest packed index that asked for a not-yet-stored key.
 __global__ __launch_bounds__(kProbeThreads) void insert_claim_kernel(cp_table t, const uint64_t *__restrict__ hash,
@@ -606,5 +628,15 @@ extern "C" int32_t cp_table_compact(void *stream, cp_table src, cp_table dst, ui
   if (!status_flags || src.keys == dst.keys || src.vals == dst.vals) return CP_ERR_INVALID_ARG;
   table_compact_kernel<<<div_up(src.capacity * kBucket, kProbeThreads), kProbeThreads, 0, (hipStream_t)stream>>>(
       src, dst, status_flags);
+  return check_launch();
+}
+
+extern "C" int32_t cp_table_count(void *stream, cp_table table, uint32_t *counts_out) {
+  using namespace cp;
+  if (int32_t rc = table_ok(table)) return rc;
+  if (!counts_out || !aligned(counts_out, 4)) return CP_ERR_INVALID_ARG;
+  table_count_zero_kernel<<<1, 1, 0, (hipStream_t)stream>>>(counts_out);
+  const uint32_t blocks = div_up(table.capacity, kProbeThreads);
+  table_count_kernel<<<blocks < 2048 ? blocks : 2048, kProbeThreads, 0, (hipStream_t)stream>>>(table, counts_out);
   return check_launch();
 }

@@ -92,6 +92,7 @@ def test_argument_errors_are_found_on_the_host():
     assert L.cp_lru_threshold(None, None, 16, 5, 1, P, S, big) == INV
     assert L.cp_evict(None, tab, None, 16, P, Q, S, None, None, None, S, big) == INV
     assert L.cp_table_compact(None, tab, tab, S) == INV  # source and destination share memory
+    assert L.cp_table_count(None, tab, None) == INV and L.cp_table_count(None, B.TableStruct(P, Q, 1000), S) == INV
     assert L.cp_sat_build(None, P, 100, 64, None, Q, S, big) == INV  # row stride shorter than a row
     assert L.cp_sat_build(None, P, (1 << 20) + 1, 1 << 21, None, Q, S, big) == UNS
     assert L.cp_sat_build(None, P, 100, 100, None, Q, S, 16) == SCR

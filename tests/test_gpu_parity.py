@@ -452,8 +452,16 @@ def test_table_overflow_stores_nothing_and_a_rebuilt_table_goes_on(G):
     o = wl.donor_off
     assert (ost.donor_slot[o[1]:o[1] + 40] != NONE).all() and (ost.donor_slot[o[1] + 40:] == NONE).all()
     assert G.verify_rows(gst.pool.pool, gst.pool.layout, ost.slot_uid, wl.seed) == 0
-    # rebuild into a larger table and store the two batches again
     pool = gst.pool
+    counts = torch.empty(2, dtype=torch.int32, device=G.DEV)
+
+    def table_counts():  # (entries holding a key, of which with a slot)
+        cp.cp_table_count(pool.table, counts)
+        return tuple(G.host_u32(counts).tolist())
+
+    used, live = table_counts()  # which keys of the failed batches took the last entries is not specified
+    assert live == len(ost.index) == 70 and ost.index.entries == 70 <= used <= 96
+    # rebuild into a larger table and store the two batches again
     fresh = cp.binding.Table(512, G.DEV)
     cp.cp_table_compact(pool.table, fresh, pool.flags)
     pool.table = fresh
@@ -475,6 +483,8 @@ def test_table_overflow_stores_nothing_and_a_rebuilt_table_goes_on(G):
         ost.n_used += n_new
         assert f2 == 0 and int(pool.flags.item()) == 0 and got_n == n_new == (90 if d == 1 else 30)
         assert np.array_equal(G.host_u32(sout), so)
+        assert table_counts() == (ost.index.entries, len(ost.index))
+    assert table_counts() == (190, 190)
     glk, olk = G.lookup(gst), OH.lookup(ost)
     assert np.array_equal(glk.slot, olk.slot) and (glk.slot != NONE).sum() == 70  # (the request has c behind other text)
 

@@ -173,6 +173,7 @@ class Lifecycle:
         if new_keys > len(self.free):
             T = O.lru_threshold(self.stamps, epoch, new_keys - len(self.free))
             freed = O.evict(self.ix, self.stamps, T, self.text, self.marks, self.anchors)
+            self.ix.rebuild(0)  # the pool's evict() also moves the keys that still have a slot to a fresh table
             self.free = np.concatenate([self.free, freed])
             g_freed = self.pool.evict(new_keys - self.pool.n_free(), buf.scratch)
             assert int(G.host_u32(self.pool.threshold)[0]) == T
@@ -212,6 +213,10 @@ class Lifecycle:
         if self.marks is not None:
             assert np.array_equal(self.pool.slot_recompute.cpu().numpy(), self.marks), epoch
         assert self.pool.n_free() == len(self.free) and int(self.pool.flags.item()) == self.flags
+        from paper_2605_23640_amd import binding as B
+        counts = torch.empty(2, dtype=torch.int32, device=G.DEV)
+        B.cp_table_count(self.pool.table, counts)  # entries holding a key, of which with a slot
+        assert tuple(G.host_u32(counts).tolist()) == (self.ix.entries, len(self.ix)), epoch
 
 
 @pytest.mark.parametrize("verify,min_len,marks,zero_fill", [(False, 1, False, False), (True, 1, False, False),
@@ -270,7 +275,7 @@ def test_table_compact_after_eviction(G):
     pool.slot_stamp.copy_(G.dev_i32(stamps))
     pool.epoch = 9
     scratch = B.new_scratch(wl.n_tokens, 0, G.DEV, pool.n_slots)
-    freed = G.host_u32(pool.evict(len(used) // 2, scratch))
+    freed = G.host_u32(pool.evict(len(used) // 2, scratch, compact=False))
     assert np.array_equal(freed, np.sort(used[::2]))
     hashes = torch.from_numpy(st.donor_hash.view(np.int64)).to(G.DEV)
     before = torch.empty(len(st.donor_hash), dtype=torch.int32, device=G.DEV)
@@ -278,8 +283,16 @@ def test_table_compact_after_eviction(G):
     b = G.host_u32(before)
     gone = np.isin(st.donor_slot, freed)
     assert (b[gone] == NONE).all() and np.array_equal(b[~gone], st.donor_slot[~gone])
+    # the table still holds the evicted slots' keys; a compacted copy holds only the keys that have a slot
+    counts = torch.empty(2, dtype=torch.int32, device=G.DEV)
+    n_keys = len(np.unique(st.donor_hash[st.donor_hash != O.HASH_NONE]))
+    n_live = len(np.unique(st.donor_slot[~gone & (st.donor_slot != NONE)]))
+    B.cp_table_count(pool.table, counts)
+    assert G.host_u32(counts).tolist() == [n_keys, n_live]
     fresh = B.Table(pool.table.capacity, G.DEV)
     B.cp_table_compact(pool.table, fresh, pool.flags)
+    B.cp_table_count(fresh, counts)
+    assert G.host_u32(counts).tolist() == [n_live, n_live] and n_live < n_keys
     after = torch.empty_like(before)
     B.cp_probe(fresh, hashes, after)
     assert np.array_equal(G.host_u32(after), b) and int(pool.flags.item()) == 0
