@@ -22,7 +22,6 @@ host on a bounded sample of the same workload.
 from __future__ import annotations
 
 import argparse
-import inspect
 import ctypes as C
 import json
 import os
@@ -270,7 +269,7 @@ def main():
 
     t0 = time.time()
     if args.kv_heads:  # one rank's share under tensor parallelism: the same tokens and slots, fewer heads per row
-        whole = inspect.signature(gen.WORKLOADS[args.workload]).parameters["shape"].default
+        whole = gen.default_shape(args.workload)
         wl = gen.make(args.workload, shape=gen.KVShape(whole.n_layers, args.kv_heads, whole.head_dim))
     else:
         wl = gen.make(args.workload)

@@ -16,6 +16,7 @@ keeping its structure.
 """
 from __future__ import annotations
 
+import inspect
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -480,3 +481,9 @@ WORKLOADS = {
 
 def make(name, **kw) -> Workload:
     return WORKLOADS[name](**kw)
+
+
+def default_shape(name) -> KVShape:
+    """The KV shape a workload is built with unless ``shape=`` says otherwise."""
+    f = make_tiny if name == "tiny" else WORKLOADS[name]
+    return inspect.signature(f).parameters["shape"].default

@@ -13,7 +13,6 @@ must hold exactly that (or the untouched fill pattern).  Re-rotated keys are
 compared on a seeded sample of tokens against the oracle's double-precision
 rotation, one by one."""
 import gc
-import inspect
 
 import numpy as np
 import pytest
@@ -57,7 +56,7 @@ def make_workload(name):
     base, _, share = name.partition("/")
     if not share:
         return gen.make(base)
-    whole = inspect.signature(gen.WORKLOADS[base]).parameters["shape"].default
+    whole = gen.default_shape(base)
     return gen.make(base, shape=gen.KVShape(whole.n_layers, int(share.split("-")[0]), whole.head_dim))
 
 
