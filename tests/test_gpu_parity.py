@@ -131,6 +131,31 @@ def test_rope_small_head_dim_64_and_large_shifts(G):
     assert np.abs(glk.span_delta).max() > 1000
 
 
+@pytest.mark.parametrize("shape", [(2, 1, 256), (1, 2, 512), (2, 3, 256), (1, 1, 512)])
+def test_rope_with_heads_of_256_and_512_elements(G, shape):
+    """The widest heads the rotating gather takes: a head's two halves then lie 16 or 32 lanes apart, and the
+    cos/sin values of one destination fill a quarter or half of the workgroup's table, so that a slot read by
+    many requests is served in passes of 8 or 4 destinations.  Both pairing styles, both pool layouts."""
+    sh = gen.KVShape(*shape)
+    for style, layout in ((0, "token"), (1, "layer")):
+        wl = gen.make_rope(seed=0xC0FFEE80 + shape[1] + shape[2], scale=1 / 16, shape=sh)
+        wl.rope_style = style
+        ost, olk, gst, glk = compare_all(G, wl, pool_layout=layout)
+        assert (glk.span_delta != 0).mean() > 0.8
+        # one stored text read by twelve requests, each of which has it at another position: chains of twelve
+        # destinations with twelve different rotations
+        rng = np.random.default_rng(shape[2])
+        doc = rng.integers(0, 32000, 640).astype(np.uint32)  # more slots than the mover has workgroups: chains stay chains
+        behind = lambda k: (np.concatenate([np.ones(k), doc]).astype(np.uint32),  # noqa: E731  (k sensitive tokens in front)
+                            np.concatenate([np.ones(k), np.zeros(len(doc))]).astype(np.uint8))
+        reqs = [behind(k) for k in (0, 2, 3, 5, 8, 13, 21, 34, 55, 89, 144, 233)]
+        wl = gen.from_prompts("wide-heads", 0xC0FFEE90 + shape[2], sh, [behind(1)[0]], [r[0] for r in reqs], pool_slots=1024,
+                              donor_masks=[behind(1)[1]], request_masks=[r[1] for r in reqs])
+        wl.rope_theta, wl.rope_style = 500000.0, style
+        ost, olk, gst, glk = compare_all(G, wl, pool_layout=layout)
+        assert (glk.slot != NONE).sum() == 12 * 640 and len(set(glk.span_delta[:glk.n_spans].tolist())) == 12
+
+
 @pytest.mark.parametrize("shape", [(2, 3, 64), (3, 5, 128), (1, 6, 16), (2, 7, 32), (1, 12, 64)])
 def test_head_counts_that_are_not_powers_of_two(G, shape):
     """Rows of 24, 80, 12, 28 and 96 sixteen-byte vectors: a step of the mover's 256 lanes then ends in the
