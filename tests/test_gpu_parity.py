@@ -131,6 +131,19 @@ def test_rope_small_head_dim_64_and_large_shifts(G):
     assert np.abs(glk.span_delta).max() > 1000
 
 
+@pytest.mark.parametrize("shape", [(1, 64, 128), (2, 40, 128), (1, 16, 512), (70, 1, 32)])
+def test_rows_longer_than_a_step_of_the_mover_and_many_layers(G, shape):
+    """Rows of 16 KiB, 10 KiB and 16 KiB: a step of the mover's 256 lanes covers a quarter of a row or less, so a
+    lane changes column from step to step and (second shape) row boundaries fall inside a step.  And 140 rows of
+    64 bytes.  Copying and rotating."""
+    sh = gen.KVShape(*shape)
+    compare_all(G, gen.make_docs("long-rows", 0xC0FFEEA0 + shape[1], sh, R=3, T=500, prefix_len=80, n_docs=5,
+                                 doc_len=(40, 120), docs_per_request=3, run_mean=8.0, cover=0.15, pool_slots=2048))
+    wl = gen.make_rope(seed=0xC0FFEEB0 + shape[1], scale=1 / 16, shape=sh)
+    ost, olk, gst, glk = compare_all(G, wl)
+    assert (glk.span_delta[:glk.n_spans] != 0).mean() > 0.5
+
+
 @pytest.mark.parametrize("shape", [(2, 1, 256), (1, 2, 512), (2, 3, 256), (1, 1, 512)])
 def test_rope_with_heads_of_256_and_512_elements(G, shape):
     """The widest heads the rotating gather takes: a head's two halves then lie 16 or 32 lanes apart, and the
