@@ -59,6 +59,8 @@ class Workload:
     rope_theta: float | None = None  # None: no key re-rotation in this workload
     rope_style: int = 0
     notes: dict = field(default_factory=dict)
+    # base of the chain hash for this workload (None: the library's default); Sec. 4.2.2 draws it at random
+    hash_base: int | None = None
     # one uniform number per donor token, equal wherever donors share text (it travels with the prefix and with
     # each document): "marked for recomputation at rate rho" = donor_u < rho.  None: not drawn for this workload.
     donor_u: np.ndarray | None = None

@@ -196,13 +196,13 @@ def hash_floating(anchors: AnchorSet, index: Index, hashes, run_off, W, base=BAS
 
 
 def match_streams(index: Index, tok, hashes, run_off, anchors: AnchorSet = None, W=None, text: "Text" = None,
-                  with_offsets=False):
+                  with_offsets=False, base=BASE):
     """What every key stream of a lookup finds, in the order in which they serve a token: the run-start
     keys, then (pools with floating anchors) the keys of candidate stream a and of candidate stream b.
     With ``text`` each stream's slots are confirmed against the stored text along its own segments."""
     streams = [(hashes, run_off)]
     if anchors is not None:
-        he, eo, hl, lo = hash_floating(anchors, index, hashes, run_off, W)
+        he, eo, hl, lo = hash_floating(anchors, index, hashes, run_off, W, base)
         streams += [(he, eo), (hl, lo)]
     out = []
     for keys, seg_off in streams:

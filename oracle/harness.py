@@ -71,7 +71,8 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
     )
     if bounded_table:  # the index as a table of the workload's capacity (in whole buckets of 16 entries)
         st.index.rebuild((int(wl.table_capacity) + 15) // 16 * 16)
-    st.donor_hash = O.hash_segments(wl.donor_tok, wl.donor_mask, wl.donor_off)
+    base = O.BASE if wl.hash_base is None else wl.hash_base
+    st.donor_hash = O.hash_segments(wl.donor_tok, wl.donor_mask, wl.donor_off, base)
     if anchor_window is not None:
         st.anchors, st.anchor_window = O.AnchorSet(), int(anchor_window)
     if verify:
@@ -90,8 +91,8 @@ def prefill(wl, src_provider=None, pool=None, flags_out=None, anchor_window=None
         b_roff = O.run_offsets(b_mask, off)
         if dedup:  # every text once: look the batch up first, leave out what the pool has (Sec. 4.3.5)
             streams = O.match_streams(st.index, b_tok, b_hash, b_roff, st.anchors, st.anchor_window, st.text,
-                                      with_offsets=True)
-            ins_hash, ins_off, found = O.insert_keys(b_hash, b_roff, streams)
+                                      with_offsets=True, base=base)
+            ins_hash, ins_off, found = O.insert_keys(b_hash, b_roff, streams, base)
             slot_out, n_new, fl = O.insert_kv_dedup(
                 st.index, ins_hash, found, off, wl.free_slots[st.n_used :], src, buf_layout(sh, n), st.pool,
                 pool_layout(sh), st.slot_pos, tok=b_tok, slot_tok=st.slot_tok)
@@ -156,7 +157,8 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
     re = sh.row_bytes // 2
     times = {}
     t = time.perf_counter()
-    h = O.hash_segments(tok, mask, off)
+    base = O.BASE if wl.hash_base is None else wl.hash_base
+    h = O.hash_segments(tok, mask, off, base)
     times["hash"] = time.perf_counter() - t
     hf = hl = roff = None
     t = time.perf_counter()
@@ -165,8 +167,8 @@ def lookup(st: OracleState, tok=None, mask=None, off=None, gather=True, max_span
     else:
         roff = O.run_offsets(mask, off)
         if st.anchors is not None:
-            hf, _, hl, _ = O.hash_floating(st.anchors, st.index, h, roff, st.anchor_window)
-        slot = O.merge_streams(O.match_streams(st.index, tok, h, roff, st.anchors, st.anchor_window, st.text))
+            hf, _, hl, _ = O.hash_floating(st.anchors, st.index, h, roff, st.anchor_window, base)
+        slot = O.merge_streams(O.match_streams(st.index, tok, h, roff, st.anchors, st.anchor_window, st.text, base=base))
     times["probe"] = time.perf_counter() - t
     use_rope = wl.rope_theta is not None
     served = slot

@@ -62,6 +62,7 @@ def make_pool(wl, free_slots=None, n_free=None, anchor_window=None, verify=False
         fs = fs[:n_free]
     # small test batches too go through the read-sharing form of the gather (its default starts at 4096 tokens)
     policies.setdefault("gather_opts", cp.binding.LaunchOpts(read_sharing=1))
+    policies.setdefault("hash_base", getattr(wl, "hash_base", None))
     pool = cp.KVPool(sh.n_layers, sh.n_kv_heads, sh.head_dim, wl.pool_slots, wl.table_capacity,
                      torch.from_numpy(fs.view(np.int32)), rope=rope, device=DEV,
                      pool_tensor=poison_tensor(wl.pool_slots * sh.tok_bytes), anchor_window=anchor_window,

@@ -90,8 +90,10 @@ class KVPool:
     def __init__(self, n_layers, n_kv_heads, head_dim, n_slots, table_capacity, free_slots, rope=None,
                  device="cuda", pool_tensor=None, anchor_window=None, verify=False,
                  min_len=1, recompute_marks=False, zero_fill=False, lru=False, pool_layout="token",
-                 gather_opts=None, insert_opts=None, dedup=False):
+                 gather_opts=None, insert_opts=None, dedup=False, hash_base=None):
         self.device = device
+        # base of the chain hash (Sec. 4.2.2 draws it at random); None: the library's default
+        self.hash_base = B.BASE if hash_base is None else int(hash_base)
         # launch options (binding.LaunchOpts or None = defaults) handed to every gather / insert of this pool
         self.gather_opts, self.insert_opts = gather_opts, insert_opts
         self.n_slots = int(n_slots)
@@ -175,7 +177,7 @@ class KVPool:
         return B.KVLayout.layer_major(L, H, D, n_tokens)
 
     def hash(self, tok, mask, off, out, scratch, stream=None):
-        return B.cp_hash_segments(tok, mask, off, out, scratch, stream=stream)
+        return B.cp_hash_segments(tok, mask, off, out, scratch, base=self.hash_base, stream=stream)
 
     def _match(self, tok, mask, off, buf: LookupBuffers, stream, per_stream, touch):
         """Hashes and slots of a batch: buf.slot = slot serving every token.  Returns the key streams as
@@ -184,16 +186,18 @@ class KVPool:
         the candidate streams found (the merged result is stamped by the caller)."""
         lru = touch and self.slot_stamp is not None
         if self.slot_anchor is None and not self.verify:
-            B.cp_hash_probe(tok, mask, off, self.table, buf.hash, None, buf.slot, buf.scratch, stream=stream)
+            B.cp_hash_probe(tok, mask, off, self.table, buf.hash, None, buf.slot, buf.scratch, base=self.hash_base,
+                            stream=stream)
             return [(None, buf.slot)]
         if self.verify:  # the run-start stream's candidates come with the hashes
-            B.cp_hash_probe(tok, mask, off, self.table, buf.hash, buf.run_off, buf.cand, buf.scratch, stream=stream)
+            B.cp_hash_probe(tok, mask, off, self.table, buf.hash, buf.run_off, buf.cand, buf.scratch,
+                            base=self.hash_base, stream=stream)
         else:
-            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, stream=stream)
+            B.cp_hash_runs(tok, mask, off, buf.hash, buf.run_off, buf.scratch, base=self.hash_base, stream=stream)
         keys = [(buf.hash, buf.run_off)]
         if self.slot_anchor is not None:
             B.cp_hash_floating(self.table, self.slot_anchor, self.n_slots, buf.hash, buf.run_off, self.anchor_window,
-                               buf.hash_float, buf.scratch, stream=stream, off_a_out=buf.float_off,
+                               buf.hash_float, buf.scratch, base=self.hash_base, stream=stream, off_a_out=buf.float_off,
                                hash_b_out=buf.hash_late, off_b_out=buf.late_off)
             keys += [(buf.hash_float, buf.float_off), (buf.hash_late, buf.late_off)]
         if self.verify and len(keys) == 3:  # the three streams confirmed in one pass
@@ -256,9 +260,9 @@ class KVPool:
         if self.slot_anchor is not None or self.verify:
             assert run_off_buf is not None, "a pool with floating anchors or verification needs run_off_buf"
             if not hashes_ready:
-                B.cp_hash_runs(tok, mask, off, hash_buf, run_off_buf, scratch, stream=stream)
+                B.cp_hash_runs(tok, mask, off, hash_buf, run_off_buf, scratch, base=self.hash_base, stream=stream)
         elif not hashes_ready:
-            B.cp_hash_segments(tok, mask, off, hash_buf, scratch, stream=stream)
+            B.cp_hash_segments(tok, mask, off, hash_buf, scratch, base=self.hash_base, stream=stream)
         n_free = self.free_slots.numel() - self.n_used
         iopts = self.insert_opts if insert_opts is None else insert_opts
         if self.verify:
@@ -291,7 +295,8 @@ class KVPool:
         assert buf is not None and buf.N == tok.numel(), "a pool with dedup needs the batch's LookupBuffers"
         N = tok.numel()
         streams = self._match(tok, mask, off, buf, stream, per_stream=True, touch=False)
-        B.cp_insert_keys(buf.hash, buf.run_off, streams, buf.ins_hash, buf.ins_off, buf.found, buf.scratch, stream=stream)
+        B.cp_insert_keys(buf.hash, buf.run_off, streams, buf.ins_hash, buf.ins_off, buf.found, buf.scratch,
+                         base=self.hash_base, stream=stream)
         n_free = self.free_slots.numel() - self.n_used
         B.cp_insert_kv_dedup(self.table, buf.ins_hash, buf.found, tok, buf.ins_off, off, self.free_slots[self.n_used:],
                              n_free, src, self.request_layout(N), self.pool, self.layout, self.n_slots, self.slot_pos,

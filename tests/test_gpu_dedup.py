@@ -63,8 +63,12 @@ def test_documents_behind_leads_are_stored_once(G, verify):
     assert ((plk.slot != NONE) <= (olk.slot != NONE)).all() and (olk.slot != NONE).sum() > 1600
 
 
-@pytest.mark.parametrize("seed,vocab,W,verify", [(1, 3, 2, False), (2, 4, 1, True), (3, 32000, 4, True), (4, 2, 3, False)])
-def test_random_batches_stored_once(G, seed, vocab, W, verify):
+@pytest.mark.parametrize("seed,vocab,W,verify,base", [(1, 3, 2, False, None), (2, 4, 1, True, None), (3, 32000, 4, True, None),
+                                                      (4, 2, 3, False, None), (5, 4, 2, True, 0x9E3779B97F4A7C15),
+                                                      (6, 32000, 3, False, 10)])
+def test_random_batches_stored_once(G, seed, vocab, W, verify, base):
+    """(The last two cases hash with another base than the default one: the keys texts are continued under are
+    substring keys, which take powers of the base.)"""
     rng = np.random.default_rng(seed)
     corpus = [rng.integers(0, vocab, int(n)).astype(np.uint32) for n in rng.integers(20, 90, 8)]
 
@@ -80,6 +84,7 @@ def test_random_batches_stored_once(G, seed, vocab, W, verify):
     masks = lambda ps: [(rng.random(len(p)) < 0.04).astype(np.uint8) for p in ps]  # noqa: E731
     wl = gen.from_prompts("stored-once-random", 0xC0FFEE32 + seed, gen.KVShape(2, 2, 64), donors, reqs, pool_slots=2048,
                           donor_masks=masks(donors), request_masks=masks(reqs), donor_batch_tokens=260)
+    wl.hash_base = base
     assert len(wl.donor_batches) >= 4
     ost, gst, olk = both(G, wl, W, verify)
     assert ost.n_used < 0.8 * len(wl.donor_tok)

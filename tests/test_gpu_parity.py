@@ -131,6 +131,21 @@ def test_rope_small_head_dim_64_and_large_shifts(G):
     assert np.abs(glk.span_delta).max() > 1000
 
 
+@pytest.mark.parametrize("base", [0x9E3779B97F4A7C15, 3, 10])
+def test_other_bases_of_the_chain_hash(G, base):
+    """The base is an argument of every hashing call (Sec. 4.2.2 draws it at random).  A 64-bit odd base, a tiny
+    one, and the even base of the paper's decimal example, whose powers vanish mod 2^64 after 64 tokens so that
+    long runs collide in crowds: keys, slots and served bytes still equal the oracle's, with and without
+    floating anchors and confirmation of matches (storing every text once: test_gpu_dedup.py)."""
+    wl = gen.make_float(scale=1 / 4, shape=gen.KVShape(2, 2, 64))
+    wl.hash_base = base
+    compare_all(G, wl)
+    compare_all(G, wl, anchor_window=8)
+    compare_all(G, wl, anchor_window=8, verify=True)
+    wl.rope_theta, wl.rope_style = 500000.0, 0
+    compare_all(G, wl, anchor_window=16, verify=True, min_len=4)
+
+
 @pytest.mark.parametrize("shape", [(1, 64, 128), (2, 40, 128), (1, 16, 512), (70, 1, 32)])
 def test_rows_longer_than_a_step_of_the_mover_and_many_layers(G, shape):
     """Rows of 16 KiB, 10 KiB and 16 KiB: a step of the mover's 256 lanes covers a quarter of a row or less, so a
