@@ -38,12 +38,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published peak HBM3E bandwidth
 # reads for a plain streaming kernel of known size.  They are copied from the summaries under profiles/
 # (gather_rows_kernel_<workload>.txt; annotator_<n>.txt): measurements of an earlier run of the same
 # code, not of this run, and the bench line says so next to them.
-PROFILED_TRAFFIC = {"llama3-8b": 9025653067, "rope": 9669718971, "llama3-70b": 58262449717, "frag": 17208347463,
-                    "annotator-10000-full": 895897876, "annotator-10000": 347761408}
-PROFILED_FETCH = {"llama3-8b": 3093438705, "rope": 4436789737, "llama3-70b": 25345878164, "frag": 7416087895}
+PROFILED_TRAFFIC = {"llama3-8b": 9036137124, "rope": 9681278928, "llama3-70b": 58311324550, "frag": 17228238218,
+                    "annotator-10000-full": 896676416, "annotator-10000": 347912128}
+PROFILED_FETCH = {"llama3-8b": 3093454910, "rope": 4436765597, "llama3-70b": 25345741631, "frag": 7416232637}
 # scatter_rows_kernel of the default step (scatter_rows_kernel_<workload>.txt and the gather files): (fetched, written)
-PROFILED_SCATTER = {"llama3-8b": (1687332893, 1683575710), "rope": (7662555616, 7643337883),
-                    "llama3-70b": (6636815676, 6627034465)}
+PROFILED_SCATTER = {"llama3-8b": (1687323882, 1686578150), "rope": (7662540819, 7659772570),
+                    "llama3-70b": (6636802933, 6635752960)}
 
 
 def log(*a):
